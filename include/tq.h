@@ -1,0 +1,117 @@
+/*
+ * tq - dictionary-coded int8 weight matrices kept compressed in HBM, with a fused
+ *      decode + dequantize + matrix-vector product for AMD MI355X (gfx950).
+ *
+ * Method (Tiny-QMoE): weights are quantized to 8 bits (paper section 3) and stored through a
+ * dictionary code (paper Background "Compression": LZW - longest dictionary string, emit its code,
+ * add string + next byte; section 4: 16-bit codewords, table lookup decompression that restores the
+ * quantized parameters exactly).  At inference the parameters stay compressed and are expanded
+ * layer by layer (Background "Inference"); here the expansion is fused into the matrix-vector
+ * product so the expanded matrix is never written to memory.
+ *
+ * Plain C ABI.  Every function returns TQ_OK (0) or a negative TQ_E_* code; after a failure
+ * tq_last_error_string() (thread-local) describes it.  No function throws.  "host" / "device" on a
+ * pointer says which memory it must point to.
+ */
+#ifndef TQ_H
+#define TQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TQ_OK 0
+#define TQ_E_INVALID_ARG (-1) /* null pointer, zero size, misaligned device pointer */
+#define TQ_E_BAD_BLOB (-2)    /* container fails validation */
+#define TQ_E_UNSUPPORTED (-3) /* e.g. batch > TQ_MAX_BATCH, dictionary too large for LDS */
+#define TQ_E_OOM (-4)
+#define TQ_E_HIP (-5)         /* a HIP runtime call or kernel launch failed */
+
+#define TQ_MAX_BATCH 16
+#define TQ_MAX_ENTRIES_DEVICE 32704 /* dictionary entries that fit the 160 KB LDS next to the decode tiles */
+#define TQ_DEFAULT_MAX_ENTRIES 32000
+#define TQ_DEFAULT_LMAX 3
+
+typedef struct tq_matrix *tq_handle;
+
+/* Encoder options; zero-initialise and set what you need (0 = default). */
+typedef struct tq_encode_opts {
+  uint32_t max_entries; /* dictionary size cap incl. the 256 single bytes; 256..TQ_MAX_ENTRIES_DEVICE */
+  uint32_t lmax;        /* longest run a dictionary entry may hold, 1..3 */
+  uint32_t n_threads;   /* host threads for the frozen-dictionary part of the parse; 0 = all cores (max 16) */
+  uint32_t reserved[5];
+} tq_encode_opts;
+
+typedef struct tq_info {
+  uint32_t rows, cols;         /* logical shape R x K, y = W x */
+  uint32_t rows_pad, cols_pad; /* shape the container stores (multiples of 16 and 256, zero filled) */
+  uint32_t n_entries, lmax;
+  uint64_t n_groups, n_codes; /* restart groups (16 x 256 weights each); 16-bit codes incl. padding codes */
+  uint64_t dict_bytes, offset_bytes, code_bytes, scale_bytes;
+  uint64_t compressed_bytes; /* sum of the four sections = bytes the kernels must read from HBM */
+} tq_info;
+
+/*
+ * Host-side encoder (off the hot path).  w: host, fp32 [rows][cols] row-major.
+ * Quantizes each row to int8 (symmetric, scale = absmax/127, round-half-to-even: the 8-bit setting
+ * of paper section 3 at per-row granularity), serializes the matrix in 16x8 micro-tiles, runs LZW
+ * with a frozen, size-capped dictionary over it (paper Background "Compression"), and lays out the
+ * container: header, dictionary, per-group code offsets, 16-bit code stream, per-row scales.
+ * *blob is allocated by the library; release it with tq_free_blob.  Deterministic for any n_threads.
+ */
+int tq_encode(const float *w, uint32_t rows, uint32_t cols, const tq_encode_opts *opts, void **blob, size_t *blob_bytes);
+
+/* Same, from already quantized weights.  q: host int8 [rows][cols]; scales: host fp32 [rows].
+ * Any byte value (including -128) is allowed. */
+int tq_encode_quantized(const int8_t *q, const float *scales, uint32_t rows, uint32_t cols, const tq_encode_opts *opts,
+                        void **blob, size_t *blob_bytes);
+
+void tq_free_blob(void *blob);
+
+/* Full host-side validation of a container (no GPU needed): header, section bounds, every dictionary
+ * entry, monotone 4-aligned group offsets, every code in range, padding codes only at group ends, and
+ * every group's runs summing to exactly 4096 bytes.  info may be NULL. */
+int tq_validate_blob(const void *blob, size_t blob_bytes, tq_info *info);
+
+/*
+ * blob: host.  Validates as tq_validate_blob does (so the kernels need no bounds checks on codes),
+ * copies dictionary, offsets, codes and scales into device memory owned by the handle, on the
+ * current HIP device.  Synchronous.  The caller may free blob on return.
+ * This is the "parameters stay compressed in memory" state of the paper's Background "Inference".
+ */
+int tq_create_from_encoded(const void *blob, size_t blob_bytes, tq_handle *out);
+
+/*
+ * Fused decode + dequantize + matrix-vector product (paper section 4 decompression feeding the
+ * layer's product, Background "Inference"), y[b][r] = scale[r] * sum_j Q[r][j] * x[b][j].
+ *   x: device, bf16 [batch][cols] row-major contiguous.
+ *   y: device, fp32 [batch][rows] row-major, fully overwritten.
+ *   stream: a hipStream_t (NULL = default stream).
+ * Asynchronous: returns after the launch; no host synchronisation, no allocation, no change to the
+ * handle, so it may be captured in a HIP graph and called concurrently on different streams.
+ * 1 <= batch <= TQ_MAX_BATCH, else TQ_E_UNSUPPORTED.  x and y must stay alive until the stream passes
+ * the kernel.  The result is deterministic (fixed summation order).
+ */
+int tq_matvec(tq_handle h, const void *x, void *y, int batch, void *stream);
+
+/*
+ * Un-fused form: expand the whole matrix (paper section 4, Listing "Decompressing Model Weights").
+ *   out: device, int8 [rows][cols] row-major, fully overwritten, bit-exact quantized weights.
+ * Same asynchrony rules as tq_matvec.
+ */
+int tq_decompress(tq_handle h, void *out, void *stream);
+
+int tq_get_info(tq_handle h, tq_info *out);
+
+/* Frees the device memory.  The caller guarantees no work using the handle is in flight.  NULL is a no-op. */
+int tq_destroy(tq_handle h);
+
+const char *tq_last_error_string(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TQ_H */

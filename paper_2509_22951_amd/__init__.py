@@ -1,0 +1,25 @@
+"""tq: dictionary-coded int8 weights kept compressed in HBM, fused decode + dequantize + GEMV on MI355X.
+
+Thin ctypes binding over libtq.so (C ABI in include/tq.h).  Argument marshalling only: every step of the
+hot path runs in the library's HIP kernels.  Importing this package never falls back to a CPU path; if the
+library has not been built, loading it raises.
+"""
+from .binding import (  # noqa: F401
+    TQ_MAX_BATCH,
+    TQ_MAX_ENTRIES_DEVICE,
+    TQ_DEFAULT_MAX_ENTRIES,
+    TqError,
+    TqInfo,
+    Matrix,
+    lib_path,
+    load,
+    tq_encode,
+    tq_encode_quantized,
+    tq_validate_blob,
+    tq_create_from_encoded,
+    tq_matvec,
+    tq_decompress,
+    tq_get_info,
+    tq_destroy,
+    tq_last_error_string,
+)

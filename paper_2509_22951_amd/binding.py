@@ -1,0 +1,181 @@
+"""ctypes binding for libtq.so.  Function names mirror include/tq.h; pointers are passed as integers
+(e.g. ``tensor.data_ptr()``, ``torch.cuda.current_stream().cuda_stream``) so no torch type crosses the ABI."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+TQ_MAX_BATCH = 16
+TQ_MAX_ENTRIES_DEVICE = 32704
+TQ_DEFAULT_MAX_ENTRIES = 32000
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB: Optional[ctypes.CDLL] = None
+
+EXPORTS = [
+    "tq_encode", "tq_encode_quantized", "tq_free_blob", "tq_validate_blob", "tq_create_from_encoded", "tq_matvec",
+    "tq_decompress", "tq_get_info", "tq_destroy", "tq_last_error_string",
+]
+
+
+class TqError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"tq error {code}: {msg}")
+        self.code = code
+
+
+class TqEncodeOpts(ctypes.Structure):
+    _fields_ = [("max_entries", ctypes.c_uint32), ("lmax", ctypes.c_uint32), ("n_threads", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32 * 5)]
+
+
+class TqInfo(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_uint32), ("cols", ctypes.c_uint32), ("rows_pad", ctypes.c_uint32),
+                ("cols_pad", ctypes.c_uint32), ("n_entries", ctypes.c_uint32), ("lmax", ctypes.c_uint32),
+                ("n_groups", ctypes.c_uint64), ("n_codes", ctypes.c_uint64), ("dict_bytes", ctypes.c_uint64),
+                ("offset_bytes", ctypes.c_uint64), ("code_bytes", ctypes.c_uint64), ("scale_bytes", ctypes.c_uint64),
+                ("compressed_bytes", ctypes.c_uint64)]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libtq.so")
+
+
+def load() -> ctypes.CDLL:
+    """Load libtq.so.  Raises if it has not been built (python -m paper_2509_22951_amd.build)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is missing: build it with `python paper_2509_22951_amd/build.py` "
+                                "(there is no CPU fallback)")
+    lib = ctypes.CDLL(path)
+    vp, sz, ci, u32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_uint32
+    lib.tq_encode.restype = ci
+    lib.tq_encode.argtypes = [vp, u32, u32, ctypes.POINTER(TqEncodeOpts), ctypes.POINTER(vp), ctypes.POINTER(sz)]
+    lib.tq_encode_quantized.restype = ci
+    lib.tq_encode_quantized.argtypes = [vp, vp, u32, u32, ctypes.POINTER(TqEncodeOpts), ctypes.POINTER(vp), ctypes.POINTER(sz)]
+    lib.tq_free_blob.restype = None
+    lib.tq_free_blob.argtypes = [vp]
+    lib.tq_validate_blob.restype = ci
+    lib.tq_validate_blob.argtypes = [vp, sz, ctypes.POINTER(TqInfo)]
+    lib.tq_create_from_encoded.restype = ci
+    lib.tq_create_from_encoded.argtypes = [vp, sz, ctypes.POINTER(vp)]
+    lib.tq_matvec.restype = ci
+    lib.tq_matvec.argtypes = [vp, vp, vp, ci, vp]
+    lib.tq_decompress.restype = ci
+    lib.tq_decompress.argtypes = [vp, vp, vp]
+    lib.tq_get_info.restype = ci
+    lib.tq_get_info.argtypes = [vp, ctypes.POINTER(TqInfo)]
+    lib.tq_destroy.restype = ci
+    lib.tq_destroy.argtypes = [vp]
+    lib.tq_last_error_string.restype = ctypes.c_char_p
+    lib.tq_last_error_string.argtypes = []
+    _LIB = lib
+    return lib
+
+
+def tq_last_error_string() -> str:
+    return load().tq_last_error_string().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise TqError(rc, tq_last_error_string())
+
+
+def _opts(max_entries: int, lmax: int, n_threads: int) -> TqEncodeOpts:
+    o = TqEncodeOpts()
+    o.max_entries, o.lmax, o.n_threads = max_entries, lmax, n_threads
+    return o
+
+
+def _take_blob(ptr: ctypes.c_void_p, n: ctypes.c_size_t) -> bytes:
+    try:
+        return ctypes.string_at(ptr.value, n.value)
+    finally:
+        load().tq_free_blob(ptr)
+
+
+def tq_encode(w: np.ndarray, max_entries: int = 0, lmax: int = 0, n_threads: int = 0) -> bytes:
+    """fp32 [rows, cols] host array -> container bytes."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    assert w.ndim == 2
+    ptr, n = ctypes.c_void_p(), ctypes.c_size_t()
+    o = _opts(max_entries, lmax, n_threads)
+    _check(load().tq_encode(w.ctypes.data, w.shape[0], w.shape[1], ctypes.byref(o), ctypes.byref(ptr), ctypes.byref(n)))
+    return _take_blob(ptr, n)
+
+
+def tq_encode_quantized(q: np.ndarray, scales: np.ndarray, max_entries: int = 0, lmax: int = 0, n_threads: int = 0) -> bytes:
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    assert q.ndim == 2 and scales.shape == (q.shape[0],)
+    ptr, n = ctypes.c_void_p(), ctypes.c_size_t()
+    o = _opts(max_entries, lmax, n_threads)
+    _check(load().tq_encode_quantized(q.ctypes.data, scales.ctypes.data, q.shape[0], q.shape[1], ctypes.byref(o),
+                                      ctypes.byref(ptr), ctypes.byref(n)))
+    return _take_blob(ptr, n)
+
+
+def tq_validate_blob(blob: bytes) -> dict:
+    info = TqInfo()
+    _check(load().tq_validate_blob(blob, len(blob), ctypes.byref(info)))
+    return info.as_dict()
+
+
+def tq_create_from_encoded(blob: bytes) -> int:
+    """Returns the opaque handle (an integer).  Needs a GPU."""
+    h = ctypes.c_void_p()
+    _check(load().tq_create_from_encoded(blob, len(blob), ctypes.byref(h)))
+    return h.value
+
+
+def tq_matvec(handle: int, x_ptr: int, y_ptr: int, batch: int, stream: int = 0) -> None:
+    _check(load().tq_matvec(handle, x_ptr, y_ptr, batch, stream))
+
+
+def tq_decompress(handle: int, out_ptr: int, stream: int = 0) -> None:
+    _check(load().tq_decompress(handle, out_ptr, stream))
+
+
+def tq_get_info(handle: int) -> dict:
+    info = TqInfo()
+    _check(load().tq_get_info(handle, ctypes.byref(info)))
+    return info.as_dict()
+
+
+def tq_destroy(handle: Optional[int]) -> None:
+    if handle:
+        _check(load().tq_destroy(handle))
+
+
+class Matrix:
+    """Owning convenience wrapper around a handle (marshalling only)."""
+
+    def __init__(self, blob: bytes):
+        self.handle = tq_create_from_encoded(blob)
+        self.info = tq_get_info(self.handle)
+
+    def matvec(self, x_ptr: int, y_ptr: int, batch: int, stream: int = 0) -> None:
+        tq_matvec(self.handle, x_ptr, y_ptr, batch, stream)
+
+    def decompress(self, out_ptr: int, stream: int = 0) -> None:
+        tq_decompress(self.handle, out_ptr, stream)
+
+    def close(self) -> None:
+        h, self.handle = self.handle, None
+        tq_destroy(h)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,201 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+Decoded weights must be bit-exact; outputs within 1e-3 of the float64 oracle, measured as
+max_r |y - y_ref| <= 1e-3 * max_r |y_ref| per (matrix, batch row)."""
+import numpy as np
+import pytest
+
+import paper_2509_22951_amd as tq
+from inputs import make_activations, make_weights, small_case
+from oracle import oracle as O
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (no CPU fallback exists)")
+    tq.load()
+    return torch.device("cuda:0")
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def gpu_decompress(m: tq.Matrix, dev):
+    out = torch.full((m.info["rows"], m.info["cols"]), 77, dtype=torch.int8, device=dev)
+    m.decompress(out.data_ptr(), _stream())
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def gpu_matvec(m: tq.Matrix, bits: np.ndarray, dev, misalign: bool = False):
+    batch = bits.shape[0]
+    flat = torch.from_numpy(bits.view(np.int16).reshape(-1).copy())
+    if misalign:   # same values at a 2-byte-aligned but not 16-byte-aligned address
+        buf = torch.zeros(flat.numel() + 8, dtype=torch.int16, device=dev)
+        buf[1:1 + flat.numel()] = flat.to(dev)
+        x = buf[1:1 + flat.numel()]
+    else:
+        x = flat.to(dev)
+    y = torch.full((batch, m.info["rows"]), float("nan"), dtype=torch.float32, device=dev)
+    m.matvec(x.data_ptr(), y.data_ptr(), batch, _stream())
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def check_outputs(y, ref, tol=1e-3):
+    assert y.shape == ref.shape and np.isfinite(y).all()
+    for b in range(ref.shape[0]):
+        scale = np.abs(ref[b]).max()
+        err = np.abs(y[b].astype(np.float64) - ref[b]).max()
+        assert err <= tol * max(scale, 1e-30), (b, err, scale)
+    return max(np.abs(y[b] - ref[b]).max() / max(np.abs(ref[b]).max(), 1e-30) for b in range(ref.shape[0]))
+
+
+CASES = [
+    # rows, cols, max_entries, lmax, dist
+    (64, 512, 32000, 3, "normal"),          # several groups, dictionary not full
+    (16, 8, 256, 3, "normal"),              # one micro-tile, singles only
+    (33, 300, 1000, 3, "normal"),           # ragged rows and columns
+    (17, 257, 300, 2, "student_t4"),        # ragged, tiny dictionary, lmax 2
+    (48, 256, 300, 1, "normal"),            # lmax 1: code == byte
+    (200, 1024, 4096, 3, "student_t4"),
+    (512, 2048, 32000, 3, "normal"),        # dictionary full and frozen; many bands per workgroup
+    (1040, 768, 32704, 3, "student_t4"),    # largest dictionary the device accepts; more bands than one pass
+    (2048, 2048, 32000, 3, "normal"),       # config 1
+]
+
+
+@pytest.mark.parametrize("rows,cols,max_entries,lmax,dist", CASES)
+def test_decompress_bit_exact_and_matvec(dev, rows, cols, max_entries, lmax, dist):
+    spec = small_case(rows, cols, seed=rows * 7 + cols, dist=dist)
+    W = make_weights(spec)
+    Qo, so = O.quantize_rows(W)
+    blob = tq.tq_encode(W, max_entries=max_entries, lmax=lmax)
+    m = tq.Matrix(blob)
+    try:
+        Q = gpu_decompress(m, dev)
+        assert np.array_equal(Q, Qo)
+        for batch in (1, 3, 8, 16):
+            bits, x = make_activations(spec, batch)
+            y = gpu_matvec(m, bits, dev)
+            ref = O.gemv_f64(Qo, so, x)
+            worst = check_outputs(y, ref)
+            assert worst < 1e-5      # fp32 accumulation of exact products: far inside the 1e-3 bar
+    finally:
+        m.close()
+
+
+def test_oracle_made_container_decodes_on_gpu(dev):
+    spec = small_case(96, 768, seed=5)
+    W = make_weights(spec)
+    enc = O.encode_matrix(W, max_entries=3000, lmax=3)
+    m = tq.Matrix(O.build_blob(enc))
+    try:
+        assert np.array_equal(gpu_decompress(m, dev), enc.Q)
+    finally:
+        m.close()
+
+
+def test_unit_vectors_probe_every_column_position(dev):
+    """x = e_j gives y[r] = s[r] * Q[r, j] exactly: checks the column each decoded run lands on."""
+    spec = small_case(32, 520, seed=11)
+    W = make_weights(spec)
+    Qo, so = O.quantize_rows(W)
+    m = tq.Matrix(tq.tq_encode(W, max_entries=2000))
+    try:
+        cols = [0, 1, 7, 8, 255, 256, 300, 511, 512, 519]
+        for c0 in range(0, len(cols), 16):
+            js = cols[c0:c0 + 16]
+            x = np.zeros((len(js), 520), np.float32)
+            for b, j in enumerate(js):
+                x[b, j] = 1.0
+            bits = (x.view(np.uint32) >> 16).astype(np.uint16)
+            y = gpu_matvec(m, bits, dev)
+            for b, j in enumerate(js):
+                want = (so.astype(np.float64) * Qo[:, j]).astype(np.float32)
+                assert np.array_equal(y[b], want), j
+    finally:
+        m.close()
+
+
+def test_ones_vector_gives_exact_row_sums(dev):
+    spec = small_case(64, 2048, seed=13)
+    W = make_weights(spec)
+    Qo, so = O.quantize_rows(W)
+    m = tq.Matrix(tq.tq_encode(W))
+    try:
+        bits = np.full((1, 2048), 0x3F80, np.uint16)      # bf16 1.0
+        y = gpu_matvec(m, bits, dev)
+        want = (so.astype(np.float64) * Qo.sum(axis=1, dtype=np.int64)).astype(np.float32)
+        np.testing.assert_allclose(y[0], want, rtol=2e-7, atol=0)
+    finally:
+        m.close()
+
+
+def test_unaligned_activation_pointer_and_odd_columns(dev):
+    for rows, cols in ((40, 300), (64, 512)):
+        spec = small_case(rows, cols, seed=17)
+        W = make_weights(spec)
+        Qo, so = O.quantize_rows(W)
+        m = tq.Matrix(tq.tq_encode(W, max_entries=1500))
+        try:
+            bits, x = make_activations(spec, 5)
+            y = gpu_matvec(m, bits, dev, misalign=True)
+            check_outputs(y, O.gemv_f64(Qo, so, x))
+        finally:
+            m.close()
+
+
+def test_byte_transparent_including_minus_128(dev):
+    rng = np.random.default_rng(2)
+    Q = rng.integers(-128, 128, (48, 512), dtype=np.int8)
+    Q[0, :] = -128
+    Q[1, :] = 0
+    Q[2, :] = 127
+    s = (rng.random(48) + 0.5).astype(np.float32)
+    m = tq.Matrix(tq.tq_encode_quantized(Q, s, max_entries=4000))
+    try:
+        assert np.array_equal(gpu_decompress(m, dev), Q)
+        spec = small_case(48, 512, seed=19)
+        bits, x = make_activations(spec, 2)
+        check_outputs(gpu_matvec(m, bits, dev), O.gemv_f64(Q, s, x))
+    finally:
+        m.close()
+
+
+def test_repeated_calls_are_deterministic_and_overwrite(dev):
+    spec = small_case(128, 1024, seed=23)
+    W = make_weights(spec)
+    m = tq.Matrix(tq.tq_encode(W))
+    try:
+        bits, _ = make_activations(spec, 4)
+        a = gpu_matvec(m, bits, dev)
+        b = gpu_matvec(m, bits, dev)
+        assert np.array_equal(a, b)
+    finally:
+        m.close()
+
+
+def test_argument_errors(dev):
+    spec = small_case(16, 256, seed=29)
+    m = tq.Matrix(tq.tq_encode(make_weights(spec)))
+    try:
+        y = torch.zeros((17, 16), dtype=torch.float32, device=dev)
+        x = torch.zeros((17, 256), dtype=torch.int16, device=dev)
+        for batch in (0, 17, -1):
+            with pytest.raises(tq.TqError) as ei:
+                m.matvec(x.data_ptr(), y.data_ptr(), batch, _stream())
+            assert ei.value.code == -3
+        with pytest.raises(tq.TqError) as ei:
+            m.matvec(0, y.data_ptr(), 1, _stream())
+        assert ei.value.code == -1
+    finally:
+        m.close()
+    with pytest.raises(tq.TqError) as ei:
+        tq.tq_create_from_encoded(b"\0" * 1024)
+    assert ei.value.code == -2
