@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Decode-step benchmark of the fused dictionary-decode + dequantize + GEMV path on one MI355X.
+
+A step = every matrix-vector product of one LLaMA-3.2-3B token step (28 layers x q,k,v,o,gate,up,down + lm_head,
+197 matrices, each with its own seeded activation), weights resident in HBM in compressed form.
+Prints one JSON line: compressed-weight HBM GB/s (value), tokens/s, roofline of the matvec kernel and the CPU
+oracle timed on a sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload: config 4 = LLaMA-3.2-3B decode-step sweep")
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--also-batch", type=int, default=8, help="second batch size reported under 'other_batches' (0 = none)")
+    ap.add_argument("--threads", type=int, default=min(16, os.cpu_count() or 1), help="host threads for setup")
+    ap.add_argument("--max-entries", type=int, default=0)
+    ap.add_argument("--lmax", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="debug: keep only the first N layers (+ lm_head)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path is a single-GPU kernel; DESIGN.md says how it "
+              "would shard). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2509_22951_amd as tq
+    from inputs import CONFIGS, config_matrices, make_activations, make_weights
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(2)
+    tq.load()
+    dev = torch.device("cuda:0")
+    specs = config_matrices(args.config)
+    if args.layers:
+        specs = [s for s in specs if s.name == "lm_head" or int(s.name[1:3]) < args.layers]
+    t_setup = time.time()
+
+    # ---- encode (host, off the hot path): generate -> quantize -> dictionary-code, a few matrices at a time
+    sample_names = {s.name for s in specs[:7]}          # the first layer doubles as the CPU-oracle sample
+    sample_blobs = {}
+    order = sorted(range(len(specs)), key=lambda i: -specs[i].rows * specs[i].cols)
+    workers = max(1, min(args.threads, 8))
+    inner = max(1, args.threads // workers)
+
+    def encode(i):
+        s = specs[i]
+        blob = tq.tq_encode(make_weights(s), max_entries=args.max_entries, lmax=args.lmax, n_threads=inner)
+        return i, blob
+
+    mats = [None] * len(specs)
+    with ThreadPoolExecutor(workers) as ex:
+        for i, blob in ex.map(encode, order):
+            mats[i] = tq.Matrix(blob)                   # validates, uploads, frees nothing on the hot path later
+            if specs[i].name in sample_names:
+                sample_blobs[i] = blob
+    infos = [m.info for m in mats]
+    comp_bytes = sum(i["compressed_bytes"] for i in infos)
+    n_weights = sum(s.rows * s.cols for s in specs)
+    n_codes = sum(i["n_codes"] for i in infos)
+
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def make_io(batch):
+        xs, ys = [], []
+        for s in specs:
+            bits, _ = make_activations(s, batch)
+            xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
+            ys.append(torch.empty((batch, s.rows), dtype=torch.float32, device=dev))
+        return xs, ys
+
+    def run(batch, steps, warmup):
+        xs, ys = make_io(batch)
+        ptrs = [(m, x.data_ptr(), y.data_ptr()) for m, x, y in zip(mats, xs, ys)]
+
+        def step():
+            for m, xp, yp in ptrs:
+                m.matvec(xp, yp, batch, stream)
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        ev_ms = e0.elapsed_time(e1) / steps
+        return wall_ms, ev_ms
+
+    setup_s = time.time() - t_setup
+    wall_ms, ev_ms = run(args.batch, args.steps, args.warmup)
+    others = {}
+    if args.also_batch and args.also_batch != args.batch:
+        w2, e2 = run(args.also_batch, max(3, args.steps // 2), args.warmup)
+        others[str(args.also_batch)] = {"ms_per_step": round(w2, 4), "GBps": round(comp_bytes / w2 / 1e6, 1),
+                                        "tokens_per_s": round(args.also_batch / (w2 * 1e-3), 1)}
+
+    gbps = comp_bytes / wall_ms / 1e6
+    ach = comp_bytes / ev_ms / 1e6
+    result = {
+        "metric": "compressed-weight HBM GB/s of the fused decode+dequant+GEMV decode-step sweep (% of 8 TB/s peak in "
+                  "roofline.frac; tokens/s alongside)",
+        "value": round(gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 activations x int8 weights, fp32 accumulate",
+        "data": "synthetic",
+        "tokens_per_s": round(args.batch / (wall_ms * 1e-3), 1),
+        "config": {
+            "workload": f"config {args.config}: {CONFIGS[args.config]['desc']}, batch {args.batch}",
+            "matrices": len(specs), "weights": n_weights, "compressed_bytes": comp_bytes,
+            "bytes_per_weight": round(comp_bytes / n_weights, 4), "weights_per_code": round(n_weights / n_codes, 4),
+            "max_entries": infos[0]["n_entries"], "lmax": infos[0]["lmax"], "launches_per_step": len(specs),
+        },
+        "roofline": {
+            "bound": "hbm", "kernel": "tq::k_matvec",
+            "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "note": "achieved = compressed bytes of the sweep / HIP-event time of one step on the launch stream "
+                    "(= mean bytes per launch / mean launch duration, launches back to back)",
+        },
+        "other_batches": others,
+        "setup_s": round(setup_s, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        t0 = time.perf_counter()
+        sb = 0
+        for i, blob in sorted(sample_blobs.items()):
+            _, x = make_activations(specs[i], args.batch)
+            O.matvec_from_blob(blob, x)                 # oracle: sequential decode, then float64 GEMV
+            sb += infos[i]["compressed_bytes"]
+        dt = time.perf_counter() - t0
+        sw = sum(specs[i].rows * specs[i].cols for i in sample_blobs)
+        result["cpu_baseline"] = {
+            "value": round(sb / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"first layer of the sweep ({len(sample_blobs)} matrices, {sw} weights, {dt:.2f} s): decode + "
+                      f"float64 GEMV, batch {args.batch}; whole sweep extrapolates to {dt * n_weights / sw:.1f} s/token",
+            "tokens_per_s_extrapolated": round(args.batch / (dt * n_weights / sw), 4),
+        }
+    print(json.dumps(result), flush=True)
+    for m in mats:
+        m.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -72,7 +72,7 @@ int tq_encode_quantized(const int8_t *q, const float *scales, uint32_t rows, uin
 void tq_free_blob(void *blob);
 
 /* Full host-side validation of a container (no GPU needed): header, section bounds, every dictionary
- * entry, monotone 4-aligned group offsets, every code in range, padding codes only at group ends, and
+ * entry, monotone 8-aligned group offsets, every code in range, padding codes only at group ends, and
  * every group's runs summing to exactly 4096 bytes.  info may be NULL. */
 int tq_validate_blob(const void *blob, size_t blob_bytes, tq_info *info);
 

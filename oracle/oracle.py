@@ -33,7 +33,7 @@ TILE_ROWS = 16      # rows per micro-tile
 MT_COLS = 8         # columns per micro-tile
 GROUP_COLS = 256    # columns per restart group (32 micro-tiles)
 GROUP_BYTES = TILE_ROWS * GROUP_COLS
-CODE_ALIGN = 4      # each group's code run is padded to a multiple of this many codes
+CODE_ALIGN = 8      # each group's code run is padded to a multiple of this many codes (one 16-byte lane load)
 LCAP = 16           # must equal TQO_LCAP in tq_oracle.c
 MAGIC = b"TQMOEv1\0"
 HEADER_BYTES = 256

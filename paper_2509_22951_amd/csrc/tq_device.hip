@@ -14,6 +14,7 @@
 // The expanded matrix never exists in HBM on the tq_matvec path.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <string>
@@ -26,7 +27,7 @@ namespace tq {
 
 constexpr int kWaves = 8;                      // wavefronts per workgroup (one workgroup per CU: LDS-bound occupancy)
 constexpr int kThreads = kWaves * 64;
-constexpr uint32_t kTileStride = kGroupBytes + 16;   // slack absorbs the over-writes of the last run and of pad codes
+constexpr uint32_t kTileStride = kGroupBytes + 16;   // slack absorbs the over-writes past the last run and of pad codes (length 0)
 constexpr uint32_t kLdsLimit = 160 * 1024;
 
 struct DevMat {
@@ -60,43 +61,178 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x) {
   return x;
 }
 
+// Copy the dictionary into LDS.  The loads of a batch of 8 x 8 KB are all issued before the first LDS write, so the
+// whole copy exposes two memory latencies instead of one per 8 KB.
 __device__ __forceinline__ void stage_dictionary(const DevMat& m, uint4* lds4, int tid) {
   const uint4* src = (const uint4*)m.dict;
-  for (uint32_t i = tid; i < m.dict_words_pad / 4; i += kThreads) lds4[i] = src[i];
+  const uint32_t n4 = m.dict_words_pad / 4;
+  constexpr int kBatch = 8;
+  for (uint32_t base = 0; base < n4; base += kBatch * kThreads) {
+    uint4 v[kBatch];
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      const uint32_t i = base + k * kThreads + tid;
+      v[k] = src[min(i, n4 - 1)];
+    }
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      const uint32_t i = base + k * kThreads + tid;
+      if (i < n4) lds4[i] = v[k];
+    }
+  }
   __syncthreads();
 }
 
-// Decode codes[begin, end) (a whole group; begin and end are multiples of 4) into tile[0, 4096).
+typedef __attribute__((address_space(3))) uint8_t lds_u8;
+typedef __attribute__((address_space(4))) const uint32_t const_u32;
+
+// Group offsets are wave-uniform and never written while a kernel runs: reading them through the constant address
+// space makes them scalar loads, which do not share a counter with the vector loads of the code stream.
+__device__ __forceinline__ uint32_t group_offset(const DevMat& m, uint32_t g) { return ((const_u32*)m.goff)[g]; }
+
+// Byte address inside LDS of a pointer into the workgroup's dynamic shared memory.
+__device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(size_t)(const lds_u8*)p; }
+
+typedef __attribute__((address_space(3))) const uint32_t lds_cu32;
+
+// LDS byte address of dictionary word `code`, for the code in the low / high half of a packed code pair:
+// one SDWA shift (selects the 16-bit half, zero-extends, multiplies by 4) instead of a mask and a shift.
+__device__ __forceinline__ uint32_t dict_address_lo(uint32_t pair, uint32_t two, uint32_t dict_base) {
+  uint32_t a;
+  asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0" : "=v"(a) : "v"(two), "v"(pair));
+  return a + dict_base;
+}
+__device__ __forceinline__ uint32_t dict_address_hi(uint32_t pair, uint32_t two, uint32_t dict_base) {
+  uint32_t a;
+  asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1" : "=v"(a) : "v"(two), "v"(pair));
+  return a + dict_base;
+}
+__device__ __forceinline__ uint32_t lds_read32(uint32_t addr) { return *(lds_cu32*)(size_t)addr; }
+
+// The byte scatter of eight looked-up codes.  a[i]: LDS byte address of run i's first byte; s[i]: dictionary words.
+// Explicit ds_write_b8 so that the order (byte 2 of every run, then byte 1, then byte 0) is exactly the one the
+// overwrite rule needs and no two byte stores are merged into an unaligned wider store.  The asm statements are
+// volatile (kept in order) but carry no memory clobber, so the dictionary reads of the next round may overlap them;
+// tile reads are fenced off explicitly with compiler_barrier().
 template <int kLmax>
-__device__ __forceinline__ void decode_group(const uint32_t* dict, const uint16_t* __restrict__ codes, uint32_t begin,
-                                             uint32_t end, uint32_t pad_word, volatile uint8_t* tile, int lane) {
-  uint32_t pos = 0;
-  for (uint32_t base = begin; base < end; base += 256) {
-    const uint32_t idx = base + 4 * lane;
-    uint2 cw = make_uint2(pad_word, pad_word);
-    if (idx < end) cw = *(const uint2*)(codes + idx);
-    const uint32_t s0 = dict[cw.x & 0xFFFFu], s1 = dict[cw.x >> 16], s2 = dict[cw.y & 0xFFFFu], s3 = dict[cw.y >> 16];
-    const uint32_t t1 = s0 >> 24, t2 = t1 + (s1 >> 24), t3 = t2 + (s2 >> 24), tot = t3 + (s3 >> 24);
-    const uint32_t incl = wave_inclusive_scan(tot);
-    const uint32_t p0 = pos + incl - tot, p1 = p0 + t1, p2 = p0 + t2, p3 = p0 + t3;
-    if (kLmax >= 3) {
-      tile[p0 + 2] = (uint8_t)(s0 >> 16);
-      tile[p1 + 2] = (uint8_t)(s1 >> 16);
-      tile[p2 + 2] = (uint8_t)(s2 >> 16);
-      tile[p3 + 2] = (uint8_t)(s3 >> 16);
-    }
-    if (kLmax >= 2) {
-      tile[p0 + 1] = (uint8_t)(s0 >> 8);
-      tile[p1 + 1] = (uint8_t)(s1 >> 8);
-      tile[p2 + 1] = (uint8_t)(s2 >> 8);
-      tile[p3 + 1] = (uint8_t)(s3 >> 8);
-    }
-    tile[p0] = (uint8_t)s0;
-    tile[p1] = (uint8_t)s1;
-    tile[p2] = (uint8_t)s2;
-    tile[p3] = (uint8_t)s3;
-    pos += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+__device__ __forceinline__ void scatter8(const uint32_t (&a)[8], const uint32_t (&s)[8]) {
+  if (kLmax >= 3)
+    asm volatile(
+        "ds_write_b8_d16_hi %0, %8 offset:2\n\tds_write_b8_d16_hi %1, %9 offset:2\n\t"
+        "ds_write_b8_d16_hi %2, %10 offset:2\n\tds_write_b8_d16_hi %3, %11 offset:2\n\t"
+        "ds_write_b8_d16_hi %4, %12 offset:2\n\tds_write_b8_d16_hi %5, %13 offset:2\n\t"
+        "ds_write_b8_d16_hi %6, %14 offset:2\n\tds_write_b8_d16_hi %7, %15 offset:2" ::"v"(a[0]),
+        "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(s[0]), "v"(s[1]), "v"(s[2]), "v"(s[3]),
+        "v"(s[4]), "v"(s[5]), "v"(s[6]), "v"(s[7]));
+  if (kLmax >= 2) {
+    uint32_t h[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) h[i] = s[i] >> 8;
+    asm volatile(
+        "ds_write_b8 %0, %8 offset:1\n\tds_write_b8 %1, %9 offset:1\n\t"
+        "ds_write_b8 %2, %10 offset:1\n\tds_write_b8 %3, %11 offset:1\n\t"
+        "ds_write_b8 %4, %12 offset:1\n\tds_write_b8 %5, %13 offset:1\n\t"
+        "ds_write_b8 %6, %14 offset:1\n\tds_write_b8 %7, %15 offset:1" ::"v"(a[0]),
+        "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(h[0]), "v"(h[1]), "v"(h[2]), "v"(h[3]),
+        "v"(h[4]), "v"(h[5]), "v"(h[6]), "v"(h[7]));
   }
+  asm volatile(
+      "ds_write_b8 %0, %8\n\tds_write_b8 %1, %9\n\tds_write_b8 %2, %10\n\tds_write_b8 %3, %11\n\t"
+      "ds_write_b8 %4, %12\n\tds_write_b8 %5, %13\n\tds_write_b8 %6, %14\n\tds_write_b8 %7, %15" ::"v"(a[0]),
+      "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(s[0]), "v"(s[1]), "v"(s[2]), "v"(s[3]),
+      "v"(s[4]), "v"(s[5]), "v"(s[6]), "v"(s[7]));
+}
+
+__device__ __forceinline__ void compiler_barrier() { asm volatile("" ::: "memory"); }
+
+constexpr int kRoundCodes = 512;   // 64 lanes x 8 consecutive codes (one 16-byte load per lane)
+constexpr int kDepth = 6;          // rounds of code loads kept in flight per wavefront (6 x 1 KB)
+
+// Decode the groups [g_lo, g_hi) one after the other into the wave's LDS tile and hand each decoded tile to
+// `consume(g)`.  The groups' codes are contiguous in memory, so the wavefront streams codes[goff[g_lo], goff[g_hi])
+// in rounds of 512 codes through a rolling window of kDepth outstanding loads, issued unconditionally from a
+// clamped index.  Per round: 8 dictionary lookups per lane, lane-local prefix of the run lengths, one DPP wave scan
+// of the lane totals, byte scatter.  A group ends somewhere inside a round (at a lane boundary, because every
+// group's run is padded to 8 codes): the lanes before the boundary scatter into the tile, the tile is consumed, and
+// the lanes after it scatter with positions rebased to the start of the next group.
+template <int kLmax, typename Consume>
+__device__ __forceinline__ void decode_chunk(const uint32_t* dict, const DevMat& m, uint32_t g_lo, uint32_t g_hi,
+                                             uint32_t tile_lds, int lane, Consume&& consume) {
+  if (g_lo >= g_hi) return;
+  const uint32_t cbeg = group_offset(m, g_lo), cend = group_offset(m, g_hi);
+  const uint32_t lane_off = 8 * lane;
+  const uint32_t dict_base = lds_address(dict);
+  const uint32_t two = 2;
+  auto load = [&](uint32_t round_start) -> uint4 { return *(const uint4*)(m.codes + min(round_start + lane_off, cend - 8)); };
+  uint4 cw[kDepth];
+#pragma unroll
+  for (int d = 0; d < kDepth; ++d) {
+    cw[d] = load(cbeg + kRoundCodes * d);
+    __builtin_amdgcn_sched_barrier(0);   // issue in consumption order: loads return in order, the loop waits per slot
+  }
+  uint32_t g = g_lo, gend = group_offset(m, g_lo + 1), pos = tile_lds;
+  for (uint32_t rs = cbeg; rs < cend; rs += kRoundCodes * kDepth) {
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+      const uint32_t r0 = rs + kRoundCodes * d;     // first code of this round (wave-uniform)
+      if (r0 < cend) {
+        uint4 c = cw[d];
+        if (r0 + kRoundCodes > cend && r0 + lane_off >= cend)   // last round of the chunk: lanes past the end decode nothing
+          c = make_uint4(m.pad_word, m.pad_word, m.pad_word, m.pad_word);
+        uint32_t s[8], a[8];
+        s[0] = lds_read32(dict_address_lo(c.x, two, dict_base));
+        s[1] = lds_read32(dict_address_hi(c.x, two, dict_base));
+        s[2] = lds_read32(dict_address_lo(c.y, two, dict_base));
+        s[3] = lds_read32(dict_address_hi(c.y, two, dict_base));
+        s[4] = lds_read32(dict_address_lo(c.z, two, dict_base));
+        s[5] = lds_read32(dict_address_hi(c.z, two, dict_base));
+        s[6] = lds_read32(dict_address_lo(c.w, two, dict_base));
+        s[7] = lds_read32(dict_address_hi(c.w, two, dict_base));
+        uint32_t t[8];   // t[i] = bytes before run i inside the lane
+        t[0] = 0;
+#pragma unroll
+        for (int i = 1; i < 8; ++i) t[i] = t[i - 1] + (s[i - 1] >> 24);
+        const uint32_t tot = t[7] + (s[7] >> 24);
+        const uint32_t incl = wave_inclusive_scan(tot);
+        const uint32_t excl = incl - tot;
+        const uint32_t round_bytes = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        if (r0 + kRoundCodes < gend) {               // the whole round lies inside group g
+#pragma unroll
+          for (int i = 0; i < 8; ++i) a[i] = pos + excl + t[i];
+          scatter8<kLmax>(a, s);
+          pos += round_bytes;
+        } else {                                    // group g ends at lane `cut` of this round (cut in 1..64)
+          const uint32_t cut = (gend - r0) >> 3;
+          if ((uint32_t)lane < cut) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) a[i] = pos + excl + t[i];
+            scatter8<kLmax>(a, s);
+          }
+          compiler_barrier();
+          consume(g);
+          compiler_barrier();
+          ++g;
+          const uint32_t before_cut = (uint32_t)__builtin_amdgcn_readlane((int)incl, (int)cut - 1);
+          pos = tile_lds + round_bytes - before_cut;
+          if (g < g_hi) {
+            gend = group_offset(m, g + 1);
+            if ((uint32_t)lane >= cut) {
+#pragma unroll
+              for (int i = 0; i < 8; ++i) a[i] = tile_lds + excl - before_cut + t[i];
+              scatter8<kLmax>(a, s);
+            }
+          }
+        }
+      }
+      cw[d] = load(r0 + kRoundCodes * kDepth);   // refill the slot only after its last use, so it stays in the same registers
+    }
+  }
+}
+
+// Whole-group decode without the cross-group pipeline (used by the general-alignment matvec path).
+template <int kLmax>
+__device__ __forceinline__ void decode_group(const uint32_t* dict, const DevMat& m, uint32_t g, uint32_t tile_lds, int lane) {
+  decode_chunk<kLmax>(dict, m, g, g + 1, tile_lds, lane, [](uint32_t) {});
 }
 
 // 8 int8 -> 8 bf16 (exact: |v| <= 128 needs 8 significant bits).  bf16 = upper half of the fp32 encoding.
@@ -115,43 +251,134 @@ __device__ __forceinline__ bf16x8 i8x8_to_bf16x8(uint2 w) {
   return __builtin_bit_cast(bf16x8, r);
 }
 
-// One workgroup per band of 16 rows at a time; its wavefronts take the band's column strips round-robin, keep a
-// 16 x 16 fp32 accumulator each (rows x batch), and the partial accumulators are summed through LDS in wave order.
-template <int kLmax>
+constexpr int kMaxBandsPerPass = 4;   // partial accumulators of one pass must fit the tile area: 4 x 8 waves x 1 KB
+constexpr int kMaxSlots = 4;          // groups per wavefront and pass whose activation fragments stay in registers
+
+// The 8 MFMA steps of one decoded tile: A = 16 rows x 32 k of int8 weights from the tile (converted to bf16),
+// B = the matching 32 k x 16 batch activation fragment held in registers.
+__device__ __forceinline__ f32x4 mfma_tile(const uint8_t* tile, int lane, const uint4 (&xf)[8], f32x4 acc) {
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const uint2 a8 = *(const uint2*)(tile + t * 512 + lane * 8);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(a8), __builtin_bit_cast(bf16x8, xf[t]), acc, 0, 0, 0);
+  }
+  return acc;
+}
+
+// Fused decode + dequantize + matrix-vector product, 16-byte aligned activations.
+// A workgroup takes `nb` consecutive bands (16 rows each) per pass.  The nb * n_strips groups of a pass are
+// contiguous in the code stream; wavefront w owns the kS consecutive group slots [kS*w, kS*w + kS) of every pass.
+// Slot -> column strip is the same in every pass, so the activation fragments of the wave's kS strips are loaded
+// once and stay in registers (kS * 32 VGPRs) and the decode loop issues no vector load but the code stream's.
+// A slot range touches at most two bands, so a wavefront carries two 16 x 16 fp32 accumulators (rows x batch).
+// After the pass the partial accumulators are summed through LDS in wave order (deterministic), scaled and stored.
+template <int kLmax, int kS>
 __global__ __launch_bounds__(kThreads, 1) void k_matvec(DevMat m, const uint16_t* __restrict__ x, float* __restrict__ y,
-                                                        int batch, int x_fast) {
+                                                        int batch, uint32_t nb) {
   extern __shared__ uint4 lds4[];
   uint32_t* dict = (uint32_t*)lds4;
   uint8_t* tiles = (uint8_t*)(dict + m.dict_words_pad);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j = lane & 15, kg = lane >> 4;
+  // activation fragments: lane (batch row j, k-group kg) holds x[j][strip*256 + 32 t + 8 kg .. + 8), zero past batch / cols
+  uint4 xf[kS][8];
+  {
+    const bool x_lane = j < batch;
+    const uint16_t* xlane = x + (size_t)(x_lane ? j : 0) * m.cols + kg * 8;
+#pragma unroll
+    for (int i = 0; i < kS; ++i) {
+      const uint32_t strip = (uint32_t)(kS * wave + i) % m.n_strips;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const uint32_t col = strip * kGroupCols + t * 32;
+        xf[i][t] = (x_lane && col + kg * 8 < m.cols) ? *(const uint4*)(xlane + col) : make_uint4(0, 0, 0, 0);
+      }
+    }
+  }
   stage_dictionary(m, lds4, tid);
   uint8_t* tile = tiles + wave * kTileStride;
+  const uint32_t tile_lds = lds_address(tile);
+  const uint32_t n_pass = (m.n_bands + nb - 1) / nb;
+  for (uint32_t pass = blockIdx.x; pass < n_pass; pass += gridDim.x) {
+    const uint32_t band0 = pass * nb, nbh = min(nb, m.n_bands - band0), ng = nbh * m.n_strips;
+    const uint32_t f_lo = min((uint32_t)(kS * wave), ng), f_hi = min((uint32_t)(kS * wave + kS), ng);
+    const uint32_t g_lo = band0 * m.n_strips + f_lo, g_hi = band0 * m.n_strips + f_hi;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc_first = {0.f, 0.f, 0.f, 0.f};
+    const uint32_t band_first = g_lo / m.n_strips;
+    uint32_t st = g_lo % m.n_strips;
+    decode_chunk<kLmax>(dict, m, g_lo, g_hi, tile_lds, lane, [&](uint32_t g) {
+      const uint32_t slot = g - g_lo;
+      if (kS == 1 || slot == 0) acc = mfma_tile(tile, lane, xf[0], acc);
+      else if (kS == 2 || slot == 1) acc = mfma_tile(tile, lane, xf[kS > 1 ? 1 : 0], acc);
+      else if (kS == 3 || slot == 2) acc = mfma_tile(tile, lane, xf[kS > 2 ? 2 : 0], acc);
+      else acc = mfma_tile(tile, lane, xf[kS > 3 ? 3 : 0], acc);
+      if (++st == m.n_strips) {
+        st = 0;
+        if (g + 1 < g_hi) {   // the slot range moves on to its second band
+          acc_first = acc;
+          acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+      }
+    });
+    // If the slot range stayed inside one band, everything is in `acc`: file it under the first band.
+    const bool two = (g_lo < g_hi) && ((g_hi - 1) / m.n_strips != band_first);
+    if (!two) {
+      acc_first = acc;
+      acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    // Partial sums: red[band_local][wave][256].  The tiles are free once every wave has finished its chunk.
+    __syncthreads();
+    float* red = (float*)tiles;
+    for (uint32_t bl = 0; bl < nbh; ++bl) {
+      const uint32_t bnd = band0 + bl;
+      const bool is_first = (g_lo < g_hi) && bnd == band_first, is_second = two && bnd == band_first + 1;
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        red[(bl * kWaves + wave) * 256 + v * 64 + lane] = is_first ? acc_first[v] : (is_second ? acc[v] : 0.f);
+    }
+    __syncthreads();
+    for (uint32_t o = tid; o < nbh * 256; o += kThreads) {
+      const uint32_t bl = o >> 8, e = o & 255;
+      float s = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) s += red[(bl * kWaves + w) * 256 + e];
+      const uint32_t v = e >> 6, l = e & 63;
+      const uint32_t row = (band0 + bl) * kTileRows + 4 * (l >> 4) + v;   // accumulator register v of lane l: row 4*(l/16)+v
+      const uint32_t b = l & 15;                                          // batch column l%16
+      if (b < (uint32_t)batch && row < m.rows) y[(size_t)b * m.rows + row] = s * m.scales[row];
+    }
+    __syncthreads();
+  }
+}
+
+// General-alignment fallback of the same product (activation pointer not 16-byte aligned or cols % 8 != 0):
+// one band per pass, strips round-robin over the wavefronts, element-wise bounds-checked activation loads.
+template <int kLmax>
+__global__ __launch_bounds__(kThreads, 1) void k_matvec_anyalign(DevMat m, const uint16_t* __restrict__ x,
+                                                                 float* __restrict__ y, int batch) {
+  extern __shared__ uint4 lds4[];
+  uint32_t* dict = (uint32_t*)lds4;
+  uint8_t* tiles = (uint8_t*)(dict + m.dict_words_pad);
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  stage_dictionary(m, lds4, tid);
+  uint8_t* tile = tiles + wave * kTileStride;
+  const uint32_t tile_lds = lds_address(tile);
   const int j = lane & 15, kg = lane >> 4;
   for (uint32_t band = blockIdx.x; band < m.n_bands; band += gridDim.x) {
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (uint32_t st = wave; st < m.n_strips; st += kWaves) {
-      const uint32_t g = band * m.n_strips + st;
-      decode_group<kLmax>(dict, m.codes, m.goff[g], m.goff[g + 1], m.pad_word, tile, lane);
+      decode_group<kLmax>(dict, m, band * m.n_strips + st, tile_lds, lane);
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         const uint2 a8 = *(const uint2*)(tile + t * 512 + lane * 8);
         const uint32_t col = st * kGroupCols + t * 32 + kg * 8;
-        uint4 xb = make_uint4(0, 0, 0, 0);
-        if (j < batch) {
-          const uint16_t* xr = x + (size_t)j * m.cols;
-          if (x_fast) {
-            if (col < m.cols) xb = *(const uint4*)(xr + col);
-          } else {
-            uint32_t e[8];
+        uint32_t e[8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) e[k] = (col + k < m.cols) ? xr[col + k] : 0u;
-            xb = make_uint4(e[0] | e[1] << 16, e[2] | e[3] << 16, e[4] | e[5] << 16, e[6] | e[7] << 16);
-          }
-        }
+        for (int k = 0; k < 8; ++k) e[k] = (j < batch && col + k < m.cols) ? x[(size_t)j * m.cols + col + k] : 0u;
+        const uint4 xb = make_uint4(e[0] | e[1] << 16, e[2] | e[3] << 16, e[4] | e[5] << 16, e[6] | e[7] << 16);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(a8), __builtin_bit_cast(bf16x8, xb), acc, 0, 0, 0);
       }
     }
-    // Cross-wave sum in fixed order.  The tiles are free once every wave has finished its strips.
     __syncthreads();
     float* red = (float*)tiles;
 #pragma unroll
@@ -162,26 +389,29 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(DevMat m, const uint16_t
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) s += red[w * 256 + tid];
       const int v = tid >> 6, l = tid & 63;
-      const uint32_t row = band * kTileRows + 4 * (l >> 4) + v;   // accumulator register v of lane l holds row 4*(l/16)+v
-      const int b = l & 15;                                       // and batch column l%16
+      const uint32_t row = band * kTileRows + 4 * (l >> 4) + v;
+      const int b = l & 15;
       if (b < batch && row < m.rows) y[(size_t)b * m.rows + row] = s * m.scales[row];
     }
     __syncthreads();
   }
 }
 
-// Every wavefront takes whole groups (grid-stride), decodes into its LDS tile and copies the 16 x 256 block out.
-template <int kLmax>
-__global__ __launch_bounds__(kThreads, 1) void k_decompress(DevMat m, int8_t* __restrict__ out, int out_fast) {
+// Expansion to the row-major int8 matrix.  The groups are split into one contiguous chunk per wavefront of the
+// grid; each decoded 16 x 256 tile is copied out with 16-byte stores (byte stores on the general-alignment path).
+template <int kLmax, bool kFastOut>
+__global__ __launch_bounds__(kThreads, 1) void k_decompress(DevMat m, int8_t* __restrict__ out) {
   extern __shared__ uint4 lds4[];
   uint32_t* dict = (uint32_t*)lds4;
   uint8_t* tiles = (uint8_t*)(dict + m.dict_words_pad);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   stage_dictionary(m, lds4, tid);
   uint8_t* tile = tiles + wave * kTileStride;
-  for (uint64_t g = (uint64_t)blockIdx.x * kWaves + wave; g < m.n_groups; g += (uint64_t)gridDim.x * kWaves) {
-    decode_group<kLmax>(dict, m.codes, m.goff[g], m.goff[g + 1], m.pad_word, tile, lane);
-    const uint32_t band = (uint32_t)(g / m.n_strips), st = (uint32_t)(g % m.n_strips);
+  const uint32_t tile_lds = lds_address(tile);
+  const uint64_t n_waves = (uint64_t)gridDim.x * kWaves, wid = (uint64_t)blockIdx.x * kWaves + wave;
+  const uint32_t g_lo = (uint32_t)(m.n_groups * wid / n_waves), g_hi = (uint32_t)(m.n_groups * (wid + 1) / n_waves);
+  uint32_t band = g_lo / m.n_strips, st = g_lo % m.n_strips;
+  decode_chunk<kLmax>(dict, m, g_lo, g_hi, tile_lds, lane, [&](uint32_t) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const int q = lane + 64 * t, i = q >> 4, pc = q & 15;   // row i of the band, 16-byte piece pc of its 256 columns
@@ -190,7 +420,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_decompress(DevMat m, int8_t* __
       const uint32_t row = band * kTileRows + i, col = st * kGroupCols + pc * 16;
       if (row >= m.rows || col >= m.cols) continue;
       int8_t* dst = out + (size_t)row * m.cols + col;
-      if (out_fast) {
+      if (kFastOut) {
         *(uint4*)dst = make_uint4(lo.x, lo.y, hi.x, hi.y);
       } else {
         const uint32_t w[4] = {lo.x, lo.y, hi.x, hi.y};
@@ -199,7 +429,11 @@ __global__ __launch_bounds__(kThreads, 1) void k_decompress(DevMat m, int8_t* __
           if (col + k < m.cols) dst[k] = (int8_t)(w[k >> 2] >> (8 * (k & 3)));
       }
     }
-  }
+    if (++st == m.n_strips) {
+      st = 0;
+      ++band;
+    }
+  });
 }
 
 }  // namespace tq
@@ -213,6 +447,7 @@ struct tq_matrix {
   int device;
   int n_cu;
   size_t lds_bytes;
+  uint32_t bands_per_pass, slots;   // launch shape of the aligned matvec kernel (0 bands: use the general kernel)
 };
 
 namespace {
@@ -222,13 +457,63 @@ int hip_fail(const char* what, hipError_t e) {
   return TQ_E_HIP;
 }
 
+typedef void (*matvec_fn)(DevMat, const uint16_t*, float*, int, uint32_t);
+typedef void (*matvec_any_fn)(DevMat, const uint16_t*, float*, int);
+typedef void (*decompress_fn)(DevMat, int8_t*);
+
 template <int kLmax>
-int allow_lds(size_t bytes) {
-  hipError_t e = hipFuncSetAttribute((const void*)k_matvec<kLmax>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(matvec)", e);
-  e = hipFuncSetAttribute((const void*)k_decompress<kLmax>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(decompress)", e);
+matvec_fn pick_matvec_slots(uint32_t slots) {
+  switch (slots) {
+    case 1: return k_matvec<kLmax, 1>;
+    case 2: return k_matvec<kLmax, 2>;
+    case 3: return k_matvec<kLmax, 3>;
+    default: return k_matvec<kLmax, 4>;
+  }
+}
+matvec_fn pick_matvec(uint32_t lmax, uint32_t slots) {
+  return lmax == 1 ? pick_matvec_slots<1>(slots) : lmax == 2 ? pick_matvec_slots<2>(slots) : pick_matvec_slots<3>(slots);
+}
+matvec_any_fn pick_matvec_any(uint32_t lmax) {
+  return lmax == 1 ? k_matvec_anyalign<1> : lmax == 2 ? k_matvec_anyalign<2> : k_matvec_anyalign<3>;
+}
+decompress_fn pick_decompress(uint32_t lmax, bool fast) {
+  switch (lmax) {
+    case 1: return fast ? k_decompress<1, true> : k_decompress<1, false>;
+    case 2: return fast ? k_decompress<2, true> : k_decompress<2, false>;
+    default: return fast ? k_decompress<3, true> : k_decompress<3, false>;
+  }
+}
+
+// Dynamic LDS above 64 KB has to be allowed per kernel function.
+int allow_lds(uint32_t lmax, size_t bytes) {
+  const void* fns[7] = {(const void*)pick_matvec(lmax, 1), (const void*)pick_matvec(lmax, 2), (const void*)pick_matvec(lmax, 3),
+                        (const void*)pick_matvec(lmax, 4), (const void*)pick_matvec_any(lmax),
+                        (const void*)pick_decompress(lmax, false), (const void*)pick_decompress(lmax, true)};
+  for (const void* f : fns) {
+    hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
+  }
   return TQ_OK;
+}
+
+// Bands per pass for the aligned matvec kernel: the value in {1, 2, 4} with the fewest sequential group decodes per
+// wavefront, ceil(passes / CUs) * slots with slots = ceil(nb * n_strips / 8).  Returns 0 when even one band needs
+// more than kMaxSlots slots (very wide matrices): those use the general kernel.
+uint32_t pick_bands_per_pass(uint32_t n_bands, uint32_t n_strips, uint32_t n_cu, uint32_t* slots_out) {
+  uint32_t best = 0;
+  uint64_t best_cost = UINT64_MAX;
+  for (uint32_t nb = 1; nb <= (uint32_t)kMaxBandsPerPass; nb *= 2) {
+    const uint64_t slots = ((uint64_t)nb * n_strips + kWaves - 1) / kWaves;
+    if (slots > (uint64_t)kMaxSlots) break;
+    const uint64_t passes = (n_bands + nb - 1) / nb;
+    const uint64_t cost = ((passes + n_cu - 1) / n_cu) * slots;
+    if (cost < best_cost) {
+      best_cost = cost;
+      best = nb;
+      *slots_out = (uint32_t)slots;
+    }
+  }
+  return best;
 }
 
 }  // namespace
@@ -281,9 +566,7 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
     (void)hipFree(base);
     return hip_fail("upload", e);
   }
-  int rc = allow_lds<1>(lds_bytes);
-  if (rc == TQ_OK) rc = allow_lds<2>(lds_bytes);
-  if (rc == TQ_OK) rc = allow_lds<3>(lds_bytes);
+  int rc = allow_lds(h.lmax, lds_bytes);
   if (rc != TQ_OK) {
     (void)hipFree(base);
     return rc;
@@ -299,6 +582,8 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   t->device = dev;
   t->n_cu = prop.multiProcessorCount;
   t->lds_bytes = lds_bytes;
+  t->slots = 0;
+  t->bands_per_pass = pick_bands_per_pass(h.rows_pad / kTileRows, h.cols_pad / kGroupCols, (uint32_t)prop.multiProcessorCount, &t->slots);
   t->m.dict = (const uint32_t*)(base + o_dict);
   t->m.goff = (const uint32_t*)(base + o_goff);
   t->m.codes = (const uint16_t*)(base + o_codes);
@@ -327,13 +612,16 @@ extern "C" int tq_matvec(tq_handle h, const void* x, void* y, int batch, void* s
     set_error("tq_matvec: x must be 2-byte and y 4-byte aligned");
     return TQ_E_INVALID_ARG;
   }
-  const int x_fast = (h->m.cols % 8 == 0) && ((uintptr_t)x % 16 == 0);
-  const unsigned grid = (unsigned)std::min<uint32_t>(h->m.n_bands, (uint32_t)h->n_cu);
-  hipStream_t s = (hipStream_t)stream;
-  switch (h->h.lmax) {
-    case 1: hipLaunchKernelGGL(k_matvec<1>, dim3(grid), dim3(kThreads), h->lds_bytes, s, h->m, (const uint16_t*)x, (float*)y, batch, x_fast); break;
-    case 2: hipLaunchKernelGGL(k_matvec<2>, dim3(grid), dim3(kThreads), h->lds_bytes, s, h->m, (const uint16_t*)x, (float*)y, batch, x_fast); break;
-    default: hipLaunchKernelGGL(k_matvec<3>, dim3(grid), dim3(kThreads), h->lds_bytes, s, h->m, (const uint16_t*)x, (float*)y, batch, x_fast); break;
+  const bool x_fast = (h->m.cols % 8 == 0) && ((uintptr_t)x % 16 == 0);
+  if (x_fast && h->bands_per_pass) {
+    const uint32_t nb = h->bands_per_pass, passes = (h->m.n_bands + nb - 1) / nb;
+    const unsigned grid = (unsigned)std::min<uint32_t>(passes, (uint32_t)h->n_cu);
+    hipLaunchKernelGGL(pick_matvec(h->h.lmax, h->slots), dim3(grid), dim3(kThreads), h->lds_bytes, (hipStream_t)stream,
+                       h->m, (const uint16_t*)x, (float*)y, batch, nb);
+  } else {
+    const unsigned grid = (unsigned)std::min<uint32_t>(h->m.n_bands, (uint32_t)h->n_cu);
+    hipLaunchKernelGGL(pick_matvec_any(h->h.lmax), dim3(grid), dim3(kThreads), h->lds_bytes, (hipStream_t)stream, h->m,
+                       (const uint16_t*)x, (float*)y, batch);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail("tq_matvec launch", e);
@@ -345,15 +633,11 @@ extern "C" int tq_decompress(tq_handle h, void* out, void* stream) {
     set_error("tq_decompress: null argument");
     return TQ_E_INVALID_ARG;
   }
-  const int out_fast = (h->m.cols % 16 == 0) && ((uintptr_t)out % 16 == 0);
+  const bool out_fast = (h->m.cols % 16 == 0) && ((uintptr_t)out % 16 == 0);
   const uint64_t wg_needed = (h->m.n_groups + kWaves - 1) / kWaves;
   const unsigned grid = (unsigned)std::min<uint64_t>(wg_needed, (uint64_t)h->n_cu);
-  hipStream_t s = (hipStream_t)stream;
-  switch (h->h.lmax) {
-    case 1: hipLaunchKernelGGL(k_decompress<1>, dim3(grid), dim3(kThreads), h->lds_bytes, s, h->m, (int8_t*)out, out_fast); break;
-    case 2: hipLaunchKernelGGL(k_decompress<2>, dim3(grid), dim3(kThreads), h->lds_bytes, s, h->m, (int8_t*)out, out_fast); break;
-    default: hipLaunchKernelGGL(k_decompress<3>, dim3(grid), dim3(kThreads), h->lds_bytes, s, h->m, (int8_t*)out, out_fast); break;
-  }
+  hipLaunchKernelGGL(pick_decompress(h->h.lmax, out_fast), dim3(grid), dim3(kThreads), h->lds_bytes, (hipStream_t)stream,
+                     h->m, (int8_t*)out);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail("tq_decompress launch", e);
   return TQ_OK;

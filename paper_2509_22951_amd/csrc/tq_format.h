@@ -13,7 +13,7 @@ constexpr uint32_t kTileRows = 16;      // rows of a micro-tile (= M of the 16x1
 constexpr uint32_t kMtCols = 8;         // columns of a micro-tile (= the 8 k-values one lane feeds the MFMA)
 constexpr uint32_t kGroupCols = 256;    // columns of a restart group: 32 micro-tiles, 8 MFMA steps
 constexpr uint32_t kGroupBytes = kTileRows * kGroupCols;
-constexpr uint32_t kCodeAlign = 4;      // codes per 8-byte lane load; each group's run is padded to this
+constexpr uint32_t kCodeAlign = 8;      // codes per 16-byte lane load; each group's run is padded to this
 constexpr uint32_t kSectionAlign = 256;
 constexpr uint32_t kHeaderBytes = 256;
 constexpr uint32_t kVersion = 1;
