@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--lmax", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="debug: keep only the first N layers (+ lm_head)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy, so a counter profile of this command holds a kernel of "
+                         "known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     return ap.parse_args()
 
 
@@ -118,6 +121,12 @@ def main():
         return wall_ms, ev_ms
 
     setup_s = time.time() - t_setup
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)       # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     wall_ms, ev_ms = run(args.batch, args.steps, args.warmup)
     others = {}
     if args.also_batch and args.also_batch != args.batch:

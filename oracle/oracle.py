@@ -238,11 +238,11 @@ def encode_matrix(W: np.ndarray, max_entries: int = 32000, lmax: int = 3) -> Enc
 
 
 def dict_slots(d: Dictionary) -> np.ndarray:
-    """Device dictionary words: bytes 0..2 = run (unused bytes zero), byte 3 = run length; one extra
-    all-zero word at index n_entries is the pad code's entry (length 0).  Needs lmax <= 3."""
+    """Device dictionary words: bytes 0..2 = run (unused bytes zero), byte 3 = run length in bits (8, 16
+    or 24); one extra all-zero word at index n_entries is the pad code's entry (length 0).  Needs lmax <= 3."""
     assert int(d.ent_len.max()) <= 3
     eb = d.ent_bytes.astype(np.uint32)
-    w = eb[:, 0] | (eb[:, 1] << 8) | (eb[:, 2] << 16) | (d.ent_len.astype(np.uint32) << 24)
+    w = eb[:, 0] | (eb[:, 1] << 8) | (eb[:, 2] << 16) | ((8 * d.ent_len.astype(np.uint32)) << 24)
     return np.concatenate([w, np.zeros(1, np.uint32)]).astype(np.uint32)
 
 
@@ -289,7 +289,8 @@ def parse_blob(blob: bytes) -> dict:
     stream = buf[o_c: o_c + b_c].view(np.uint16)
     scales = buf[o_s: o_s + b_s].view(np.float32)
     assert slots.size == n_entries + 1 and goff.size == n_groups + 1 and stream.size == n_codes and scales.size == rp
-    el = (slots[:n_entries] >> 24).astype(np.uint8)
+    assert np.all((slots[:n_entries] >> 24) % 8 == 0)
+    el = ((slots[:n_entries] >> 24) // 8).astype(np.uint8)
     eb = np.zeros((n_entries, LCAP), np.uint8)
     for k in range(3):
         eb[:, k] = (slots[:n_entries] >> (8 * k)) & 0xFF

@@ -59,10 +59,10 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, unsigned n_th
   // Dictionary: codes 0..255 are the single bytes; every entry has length 1..lmax and zero bytes past its length;
   // the pad entry is all zero (length 0).
   for (uint32_t e = 0; e < h.n_entries; ++e) {
-    uint32_t w = slot[e], len = w >> 24;
-    if (len < 1 || len > h.lmax) return bad("dictionary entry length");
+    uint32_t w = slot[e], bits = w >> 24, len = bits / 8;   // the top byte holds the run length in bits
+    if (bits % 8 || len < 1 || len > h.lmax) return bad("dictionary entry length");
     if (len < 3 && (w & 0xFFFFFFu) >> (8 * len)) return bad("dictionary entry has bytes past its length");
-    if (e < 256 && w != (e | 1u << 24)) return bad("codes 0..255 must be the single bytes");
+    if (e < 256 && w != (e | 8u << 24)) return bad("codes 0..255 must be the single bytes");
   }
   if (slot[h.n_entries] != 0) return bad("pad entry");
 
@@ -86,7 +86,7 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, unsigned n_th
         if (c > h.n_entries) { ok = false; break; }
         if (c == h.n_entries) { ++pads; continue; }
         if (pads) { ok = false; break; }   // a real code after a pad
-        sum += slot[c] >> 24;
+        sum += slot[c] >> 27;   // bits / 8
       }
       if (!ok || sum != kGroupBytes || pads >= kCodeAlign) {
         uint64_t cur = first_bad.load();

@@ -1,13 +1,13 @@
 // Device side of libtq for gfx950 (MI355X): handle management and the two hot-path kernels.
 //
 // Work decomposition.  The container stores the matrix as restart groups of 16 rows x 256 columns (4096 bytes,
-// 32 micro-tiles of 16x8 in MFMA operand order).  One wavefront decodes one group at a time:
-//   1. 64 lanes load 4 consecutive 16-bit codes each (one coalesced 512-byte read per round),
-//   2. look each code up in the LDS-resident dictionary (one 32-bit word: 3 run bytes + length),
-//   3. get every run's byte position from a lane-local prefix plus a DPP wave scan of the lane totals,
-//   4. scatter the run bytes into the wave's private 4 KB LDS tile.  Every code writes all three byte slots
-//      unconditionally, highest byte index first: a slot past a run's length lands on a position owned by a later
-//      run at a smaller byte index, so the owner's later write wins and no lane needs predication.
+// 32 micro-tiles of 16x8 in MFMA operand order).  One wavefront decodes one group at a time into a private 4 KB
+// LDS tile, streaming the 16-bit codes in rounds of 512:
+//   1. 64 lanes load 8 consecutive codes each (one coalesced 1 KB read per round, six rounds in flight),
+//   2. look each code up in the LDS-resident dictionary (one 32-bit word: 3 run bytes + length in bits),
+//   3. get the byte position of the lane's runs from a DPP wave scan of the lane totals,
+//   4. pack the lane's 8 runs into one byte string in registers (v_alignbit funnel) and OR it into the zeroed tile
+//      as a few aligned dwords (ds_or_b32), instead of one LDS byte store per decoded byte.
 // The tile then holds 8 MFMA A-operand blocks (16 rows x 32 k).  tq_matvec converts each lane's 8 int8 values to
 // bf16 (exact) and issues v_mfma_f32_16x16x32_bf16 against the activations (batch is the N dimension, up to 16);
 // tq_decompress copies the tile out to the row-major int8 matrix with 16-byte stores.
@@ -27,7 +27,7 @@ namespace tq {
 
 constexpr int kWaves = 8;                      // wavefronts per workgroup (one workgroup per CU: LDS-bound occupancy)
 constexpr int kThreads = kWaves * 64;
-constexpr uint32_t kTileStride = kGroupBytes + 16;   // slack absorbs the over-writes past the last run and of pad codes (length 0)
+constexpr uint32_t kTileStride = kGroupBytes + 16;
 constexpr uint32_t kLdsLimit = 160 * 1024;
 
 struct DevMat {
@@ -109,52 +109,61 @@ __device__ __forceinline__ uint32_t dict_address_hi(uint32_t pair, uint32_t two,
 }
 __device__ __forceinline__ uint32_t lds_read32(uint32_t addr) { return *(lds_cu32*)(size_t)addr; }
 
-// The byte scatter of eight looked-up codes.  a[i]: LDS byte address of run i's first byte; s[i]: dictionary words.
-// Explicit ds_write_b8 so that the order (byte 2 of every run, then byte 1, then byte 0) is exactly the one the
-// overwrite rule needs and no two byte stores are merged into an unaligned wider store.  The asm statements are
-// volatile (kept in order) but carry no memory clobber, so the dictionary reads of the next round may overlap them;
-// tile reads are fenced off explicitly with compiler_barrier().
-template <int kLmax>
-__device__ __forceinline__ void scatter8(const uint32_t (&a)[8], const uint32_t (&s)[8]) {
-  if (kLmax >= 3)
-    asm volatile(
-        "ds_write_b8_d16_hi %0, %8 offset:2\n\tds_write_b8_d16_hi %1, %9 offset:2\n\t"
-        "ds_write_b8_d16_hi %2, %10 offset:2\n\tds_write_b8_d16_hi %3, %11 offset:2\n\t"
-        "ds_write_b8_d16_hi %4, %12 offset:2\n\tds_write_b8_d16_hi %5, %13 offset:2\n\t"
-        "ds_write_b8_d16_hi %6, %14 offset:2\n\tds_write_b8_d16_hi %7, %15 offset:2" ::"v"(a[0]),
-        "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(s[0]), "v"(s[1]), "v"(s[2]), "v"(s[3]),
-        "v"(s[4]), "v"(s[5]), "v"(s[6]), "v"(s[7]));
-  if (kLmax >= 2) {
-    uint32_t h[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) h[i] = s[i] >> 8;
-    asm volatile(
-        "ds_write_b8 %0, %8 offset:1\n\tds_write_b8 %1, %9 offset:1\n\t"
-        "ds_write_b8 %2, %10 offset:1\n\tds_write_b8 %3, %11 offset:1\n\t"
-        "ds_write_b8 %4, %12 offset:1\n\tds_write_b8 %5, %13 offset:1\n\t"
-        "ds_write_b8 %6, %14 offset:1\n\tds_write_b8 %7, %15 offset:1" ::"v"(a[0]),
-        "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(h[0]), "v"(h[1]), "v"(h[2]), "v"(h[3]),
-        "v"(h[4]), "v"(h[5]), "v"(h[6]), "v"(h[7]));
-  }
-  asm volatile(
-      "ds_write_b8 %0, %8\n\tds_write_b8 %1, %9\n\tds_write_b8 %2, %10\n\tds_write_b8 %3, %11\n\t"
-      "ds_write_b8 %4, %12\n\tds_write_b8 %5, %13\n\tds_write_b8 %6, %14\n\tds_write_b8 %7, %15" ::"v"(a[0]),
-      "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(s[0]), "v"(s[1]), "v"(s[2]), "v"(s[3]),
-      "v"(s[4]), "v"(s[5]), "v"(s[6]), "v"(s[7]));
-}
-
 __device__ __forceinline__ void compiler_barrier() { asm volatile("" ::: "memory"); }
 
 constexpr int kRoundCodes = 512;   // 64 lanes x 8 consecutive codes (one 16-byte load per lane)
 constexpr int kDepth = 6;          // rounds of code loads kept in flight per wavefront (6 x 1 KB)
 
+// The 8 runs of a lane are consecutive in the output, so they are first packed into one contiguous byte string in
+// registers.  A dictionary word holds the run bytes in bits 0..23 and the run length in bits (8/16/24) in its top
+// byte; v_alignbit(word, acc, len) shifts the accumulator right by the run length and inserts exactly the run's
+// bytes at the top, whatever sits above them in the word.  After the 8 steps the string is top-justified in
+// A[0 .. 2*kLmax).  Only the dwords that can be non-zero after each step are touched.
+template <int kLmax>
+__device__ __forceinline__ void pack_runs(const uint32_t (&s)[8], uint32_t (&A)[2 * kLmax]) {
+  constexpr int ND = 2 * kLmax;
+#pragma unroll
+  for (int k = 0; k < ND; ++k) A[k] = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint32_t len = s[j] >> 24;
+    const int live = (kLmax * (j + 1) + 3) / 4 < ND ? (kLmax * (j + 1) + 3) / 4 : ND;   // dwords in use after this step
+#pragma unroll
+    for (int k = ND - live; k < ND - 1; ++k) A[k] = __builtin_amdgcn_alignbit(A[k + 1], A[k], len);
+    A[ND - 1] = __builtin_amdgcn_alignbit(s[j], A[ND - 1], len);
+  }
+}
+
+// OR the lane's packed string into the tile.  `end_bits` = bit position (from the tile start) one past the lane's
+// last byte.  The string is shifted so that its end falls on a dword boundary of the tile, which makes every store
+// an aligned dword; dwords shared with a neighbouring lane combine through the OR (the tile is zero before a group
+// is decoded).  Window dword k lies at `base + 4 k`; dwords that are zero in every lane are skipped.
+template <int kLmax>
+__device__ __forceinline__ void or_into_tile(const uint32_t (&A)[2 * kLmax], uint32_t end_bits, uint32_t tile_lds, int32_t rebase) {
+  constexpr int ND = 2 * kLmax;
+  const uint32_t r = (0u - end_bits) & 24u;                      // bits up to the next dword boundary (0, 8, 16, 24)
+  uint32_t B[ND + 1];
+  B[0] = __builtin_amdgcn_alignbit(A[0], 0u, r);
+#pragma unroll
+  for (int k = 1; k < ND; ++k) B[k] = __builtin_amdgcn_alignbit(A[k], A[k - 1], r);
+  B[ND] = A[ND - 1] >> r;
+  // address of window dword 0: (ceil(end / 4) - (ND + 1)) dwords from the tile start
+  const uint32_t base = tile_lds + (((end_bits + 24u) >> 5) << 2) - 4u * (ND + 1) + (uint32_t)rebase;
+#pragma unroll
+  for (int k = 0; k <= ND; ++k) {
+    // the upper half of the window is in use in nearly every round; the lower half only for long lanes
+    if (k >= (ND + 1) / 2 || __builtin_amdgcn_ballot_w64(B[k] != 0) != 0)
+      asm volatile("ds_or_b32 %0, %1 offset:%2" ::"v"(base), "v"(B[k]), "n"(4 * k));
+  }
+}
+
 // Decode the groups [g_lo, g_hi) one after the other into the wave's LDS tile and hand each decoded tile to
-// `consume(g)`.  The groups' codes are contiguous in memory, so the wavefront streams codes[goff[g_lo], goff[g_hi])
-// in rounds of 512 codes through a rolling window of kDepth outstanding loads, issued unconditionally from a
-// clamped index.  Per round: 8 dictionary lookups per lane, lane-local prefix of the run lengths, one DPP wave scan
-// of the lane totals, byte scatter.  A group ends somewhere inside a round (at a lane boundary, because every
-// group's run is padded to 8 codes): the lanes before the boundary scatter into the tile, the tile is consumed, and
-// the lanes after it scatter with positions rebased to the start of the next group.
+// `consume(g)`, which must leave the tile zero-filled again.  The groups' codes are contiguous in memory, so the
+// wavefront streams codes[goff[g_lo], goff[g_hi]) in rounds of 512 codes through a rolling window of kDepth
+// outstanding loads, issued unconditionally from a clamped index.  Per round: 8 dictionary lookups per lane, one DPP
+// wave scan of the lane totals, register packing, a handful of aligned ds_or_b32.  A group ends somewhere inside a
+// round, at a lane boundary because every group's run is padded to 8 codes: the lanes before the boundary store into
+// the tile, the tile is consumed, and the lanes after it store 4096 bytes lower, i.e. at the start of the next group.
 template <int kLmax, typename Consume>
 __device__ __forceinline__ void decode_chunk(const uint32_t* dict, const DevMat& m, uint32_t g_lo, uint32_t g_hi,
                                              uint32_t tile_lds, int lane, Consume&& consume) {
@@ -170,7 +179,8 @@ __device__ __forceinline__ void decode_chunk(const uint32_t* dict, const DevMat&
     cw[d] = load(cbeg + kRoundCodes * d);
     __builtin_amdgcn_sched_barrier(0);   // issue in consumption order: loads return in order, the loop waits per slot
   }
-  uint32_t g = g_lo, gend = group_offset(m, g_lo + 1), pos = tile_lds;
+  uint32_t g = g_lo, gend = group_offset(m, g_lo + 1);
+  uint32_t pos = 0;                                  // bits decoded so far in group g (wave-uniform)
   for (uint32_t rs = cbeg; rs < cend; rs += kRoundCodes * kDepth) {
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) {
@@ -179,7 +189,7 @@ __device__ __forceinline__ void decode_chunk(const uint32_t* dict, const DevMat&
         uint4 c = cw[d];
         if (r0 + kRoundCodes > cend && r0 + lane_off >= cend)   // last round of the chunk: lanes past the end decode nothing
           c = make_uint4(m.pad_word, m.pad_word, m.pad_word, m.pad_word);
-        uint32_t s[8], a[8];
+        uint32_t s[8];
         s[0] = lds_read32(dict_address_lo(c.x, two, dict_base));
         s[1] = lds_read32(dict_address_hi(c.x, two, dict_base));
         s[2] = lds_read32(dict_address_lo(c.y, two, dict_base));
@@ -188,45 +198,40 @@ __device__ __forceinline__ void decode_chunk(const uint32_t* dict, const DevMat&
         s[5] = lds_read32(dict_address_hi(c.z, two, dict_base));
         s[6] = lds_read32(dict_address_lo(c.w, two, dict_base));
         s[7] = lds_read32(dict_address_hi(c.w, two, dict_base));
-        uint32_t t[8];   // t[i] = bytes before run i inside the lane
-        t[0] = 0;
+        uint32_t tot = s[0] >> 24;
 #pragma unroll
-        for (int i = 1; i < 8; ++i) t[i] = t[i - 1] + (s[i - 1] >> 24);
-        const uint32_t tot = t[7] + (s[7] >> 24);
+        for (int i = 1; i < 8; ++i) tot += s[i] >> 24;
         const uint32_t incl = wave_inclusive_scan(tot);
-        const uint32_t excl = incl - tot;
-        const uint32_t round_bytes = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        const uint32_t round_bits = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        uint32_t A[2 * kLmax];
+        pack_runs<kLmax>(s, A);
+        const uint32_t end_bits = pos + incl;
         if (r0 + kRoundCodes < gend) {               // the whole round lies inside group g
-#pragma unroll
-          for (int i = 0; i < 8; ++i) a[i] = pos + excl + t[i];
-          scatter8<kLmax>(a, s);
-          pos += round_bytes;
+          or_into_tile<kLmax>(A, end_bits, tile_lds, 0);
+          pos += round_bits;
         } else {                                    // group g ends at lane `cut` of this round (cut in 1..64)
           const uint32_t cut = (gend - r0) >> 3;
-          if ((uint32_t)lane < cut) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) a[i] = pos + excl + t[i];
-            scatter8<kLmax>(a, s);
-          }
+          if ((uint32_t)lane < cut) or_into_tile<kLmax>(A, end_bits, tile_lds, 0);
           compiler_barrier();
           consume(g);
           compiler_barrier();
           ++g;
-          const uint32_t before_cut = (uint32_t)__builtin_amdgcn_readlane((int)incl, (int)cut - 1);
-          pos = tile_lds + round_bytes - before_cut;
+          pos = pos + round_bits - 8u * kGroupBytes;   // group g ended exactly at byte 4096
           if (g < g_hi) {
             gend = group_offset(m, g + 1);
-            if ((uint32_t)lane >= cut) {
-#pragma unroll
-              for (int i = 0; i < 8; ++i) a[i] = tile_lds + excl - before_cut + t[i];
-              scatter8<kLmax>(a, s);
-            }
+            if ((uint32_t)lane >= cut) or_into_tile<kLmax>(A, end_bits, tile_lds, -(int32_t)kGroupBytes);
           }
         }
       }
       cw[d] = load(r0 + kRoundCodes * kDepth);   // refill the slot only after its last use, so it stays in the same registers
     }
   }
+}
+
+// Zero a wave's 4 KB tile (64 lanes x 64 bytes).
+__device__ __forceinline__ void zero_tile(uint8_t* tile, int lane) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) *(uint4*)(tile + (k * 64 + lane) * 16) = make_uint4(0, 0, 0, 0);
 }
 
 // Whole-group decode without the cross-group pipeline (used by the general-alignment matvec path).
@@ -256,10 +261,12 @@ constexpr int kMaxSlots = 4;          // groups per wavefront and pass whose act
 
 // The 8 MFMA steps of one decoded tile: A = 16 rows x 32 k of int8 weights from the tile (converted to bf16),
 // B = the matching 32 k x 16 batch activation fragment held in registers.
-__device__ __forceinline__ f32x4 mfma_tile(const uint8_t* tile, int lane, const uint4 (&xf)[8], f32x4 acc) {
+__device__ __forceinline__ f32x4 mfma_tile(uint8_t* tile, int lane, const uint4 (&xf)[8], f32x4 acc) {
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
-    const uint2 a8 = *(const uint2*)(tile + t * 512 + lane * 8);
+    uint2* p = (uint2*)(tile + t * 512 + lane * 8);
+    const uint2 a8 = *p;
+    *p = make_uint2(0, 0);   // leave the tile zero-filled for the next group (the decoder ORs into it)
     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(a8), __builtin_bit_cast(bf16x8, xf[t]), acc, 0, 0, 0);
   }
   return acc;
@@ -295,9 +302,10 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(DevMat m, const uint16_t
       }
     }
   }
-  stage_dictionary(m, lds4, tid);
   uint8_t* tile = tiles + wave * kTileStride;
   const uint32_t tile_lds = lds_address(tile);
+  zero_tile(tile, lane);
+  stage_dictionary(m, lds4, tid);
   const uint32_t n_pass = (m.n_bands + nb - 1) / nb;
   for (uint32_t pass = blockIdx.x; pass < n_pass; pass += gridDim.x) {
     const uint32_t band0 = pass * nb, nbh = min(nb, m.n_bands - band0), ng = nbh * m.n_strips;
@@ -348,6 +356,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(DevMat m, const uint16_t
       if (b < (uint32_t)batch && row < m.rows) y[(size_t)b * m.rows + row] = s * m.scales[row];
     }
     __syncthreads();
+    zero_tile(tile, lane);   // the partial sums lay over the tiles; the decoder needs them zero
   }
 }
 
@@ -360,9 +369,10 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_anyalign(DevMat m, const
   uint32_t* dict = (uint32_t*)lds4;
   uint8_t* tiles = (uint8_t*)(dict + m.dict_words_pad);
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  stage_dictionary(m, lds4, tid);
   uint8_t* tile = tiles + wave * kTileStride;
   const uint32_t tile_lds = lds_address(tile);
+  zero_tile(tile, lane);
+  stage_dictionary(m, lds4, tid);
   const int j = lane & 15, kg = lane >> 4;
   for (uint32_t band = blockIdx.x; band < m.n_bands; band += gridDim.x) {
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -370,7 +380,9 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_anyalign(DevMat m, const
       decode_group<kLmax>(dict, m, band * m.n_strips + st, tile_lds, lane);
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
-        const uint2 a8 = *(const uint2*)(tile + t * 512 + lane * 8);
+        uint2* ap = (uint2*)(tile + t * 512 + lane * 8);
+        const uint2 a8 = *ap;
+        *ap = make_uint2(0, 0);
         const uint32_t col = st * kGroupCols + t * 32 + kg * 8;
         uint32_t e[8];
 #pragma unroll
@@ -394,6 +406,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_anyalign(DevMat m, const
       if (b < batch && row < m.rows) y[(size_t)b * m.rows + row] = s * m.scales[row];
     }
     __syncthreads();
+    zero_tile(tile, lane);
   }
 }
 
@@ -405,9 +418,10 @@ __global__ __launch_bounds__(kThreads, 1) void k_decompress(DevMat m, int8_t* __
   uint32_t* dict = (uint32_t*)lds4;
   uint8_t* tiles = (uint8_t*)(dict + m.dict_words_pad);
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  stage_dictionary(m, lds4, tid);
   uint8_t* tile = tiles + wave * kTileStride;
   const uint32_t tile_lds = lds_address(tile);
+  zero_tile(tile, lane);
+  stage_dictionary(m, lds4, tid);
   const uint64_t n_waves = (uint64_t)gridDim.x * kWaves, wid = (uint64_t)blockIdx.x * kWaves + wave;
   const uint32_t g_lo = (uint32_t)(m.n_groups * wid / n_waves), g_hi = (uint32_t)(m.n_groups * (wid + 1) / n_waves);
   uint32_t band = g_lo / m.n_strips, st = g_lo % m.n_strips;
@@ -415,8 +429,11 @@ __global__ __launch_bounds__(kThreads, 1) void k_decompress(DevMat m, int8_t* __
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const int q = lane + 64 * t, i = q >> 4, pc = q & 15;   // row i of the band, 16-byte piece pc of its 256 columns
-      const uint2 lo = *(const uint2*)(tile + (2 * pc) * 128 + i * 8);
-      const uint2 hi = *(const uint2*)(tile + (2 * pc + 1) * 128 + i * 8);
+      uint2* plo = (uint2*)(tile + (2 * pc) * 128 + i * 8);
+      uint2* phi = (uint2*)(tile + (2 * pc + 1) * 128 + i * 8);
+      const uint2 lo = *plo, hi = *phi;
+      *plo = make_uint2(0, 0);   // leave the tile zero-filled for the next group
+      *phi = make_uint2(0, 0);
       const uint32_t row = band * kTileRows + i, col = st * kGroupCols + pc * 16;
       if (row >= m.rows || col >= m.cols) continue;
       int8_t* dst = out + (size_t)row * m.cols + col;

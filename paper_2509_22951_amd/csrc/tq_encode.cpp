@@ -52,7 +52,7 @@ class Dict3 {
     tkey_.assign(cap, kNone);
     tval_.assign(cap, 0);
     slot_.reserve(max_entries + 1);
-    for (uint32_t b = 0; b < 256; ++b) slot_.push_back(b | (1u << 24));
+    for (uint32_t b = 0; b < 256; ++b) slot_.push_back(b | (8u << 24));   // top byte: run length in bits
   }
   uint32_t size() const { return (uint32_t)slot_.size(); }
   bool full() const { return size() >= max_; }
@@ -86,10 +86,10 @@ class Dict3 {
         uint32_t id = size();
         if (m == 1) {
           pair_[code << 8 | nb] = id;
-          slot_.push_back(code | nb << 8 | 2u << 24);
+          slot_.push_back(code | nb << 8 | 16u << 24);
         } else {
           insert3(code, nb, id);
-          slot_.push_back((slot_[code] & 0xFFFFu) | nb << 16 | 3u << 24);
+          slot_.push_back((slot_[code] & 0xFFFFu) | nb << 16 | 24u << 24);
         }
       }
       i += m;

@@ -28,7 +28,7 @@ struct Header {
   uint32_t tile_rows, mt_cols, group_cols, group_bytes;
   uint32_t n_entries, lmax, max_entries, pad_code;
   uint64_t n_groups, n_codes;
-  uint64_t off_dict, dict_bytes;      // uint32 slot[n_entries + 1]: run bytes in bits 0..23, length in bits 24..31
+  uint64_t off_dict, dict_bytes;      // uint32 slot[n_entries + 1]: run bytes in bits 0..23, run length in BITS (8/16/24) in bits 24..31
   uint64_t off_goff, goff_bytes;      // uint32 goff[n_groups + 1], in codes
   uint64_t off_codes, code_bytes;     // uint16 codes[n_codes]
   uint64_t off_scales, scale_bytes;   // float scale[rows_pad]

@@ -101,9 +101,10 @@ def test_validation_rejects_malformed_containers():
         "group length": _mutate(blob, o_c, "<H", 256 if p["stream"][0] < 256 else 0),
         "offset not monotone": _mutate(blob, o_g + 4, "<I", 0xFFFFFFF0),
         "offset misaligned": _mutate(blob, o_g + 4, "<I", int(p["goff"][1]) + 1),
-        "entry length": _mutate(blob, o_d + 4 * 300, "<I", (4 << 24) | 0x010203),
-        "single byte entry": _mutate(blob, o_d + 4 * 7, "<I", (1 << 24) | 8),
-        "pad entry": _mutate(blob, o_d + 4 * p["n_entries"], "<I", 1 << 24),
+        "entry length": _mutate(blob, o_d + 4 * 300, "<I", (32 << 24) | 0x010203),
+        "entry length not whole bytes": _mutate(blob, o_d + 4 * 300, "<I", (12 << 24) | 0x0102),
+        "single byte entry": _mutate(blob, o_d + 4 * 7, "<I", (8 << 24) | 8),
+        "pad entry": _mutate(blob, o_d + 4 * p["n_entries"], "<I", 8 << 24),
     }
     # a pad code in the middle of a group (before real codes)
     mid = bytearray(blob)

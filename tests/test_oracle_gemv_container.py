@@ -77,7 +77,7 @@ def test_container_round_trip(shape, max_entries):
     assert (p["rows"], p["cols"]) == shape and p["n_entries"] == enc.dictionary.n_entries
     assert p["n_codes"] == enc.stream.size and p["pad_code"] == enc.dictionary.n_entries
     assert p["slots"][-1] == 0                                    # the pad entry has length 0
-    assert np.array_equal(p["slots"][:256], np.arange(256, dtype=np.uint32) | (1 << 24))   # singles: code == byte
+    assert np.array_equal(p["slots"][:256], np.arange(256, dtype=np.uint32) | (8 << 24))   # singles: code == byte, 8 bits long
     Q, s = O.decode_blob(blob)
     assert np.array_equal(Q, enc.Q) and np.array_equal(s, enc.scales)
     Qq, sq = O.quantize_rows(W)
