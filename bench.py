@@ -22,6 +22,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM traffic of the matvec launches measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the default workload
+# (config 4, batch 1, default encoder options), scaled by a plain 1 GiB copy in the same run
+# (profiles/k_matvec_config4_batch1_hbm_traffic.txt): bytes read per algorithmic byte, bytes written per step.
+MEASURED_FETCH_PER_ALGORITHMIC_BYTE = 1.073
+MEASURED_WRITE_BYTES_PER_STEP = 3_609_600
 
 
 def parse_args():
@@ -160,9 +165,12 @@ def main():
         "roofline": {
             "bound": "hbm", "kernel": "tq::k_matvec",
             "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": (round((MEASURED_FETCH_PER_ALGORITHMIC_BYTE * comp_bytes + MEASURED_WRITE_BYTES_PER_STEP) / len(specs))
+                        if (args.config == 4 and args.batch == 1 and not args.max_entries and not args.lmax and not args.layers)
+                        else None),
             "note": "achieved = compressed bytes of the sweep / HIP-event time of one step on the launch stream "
-                    "(= mean bytes per launch / mean launch duration, launches back to back)",
+                    "(= mean bytes per launch / mean launch duration, launches back to back); traffic = HBM bytes per "
+                    "launch from the FETCH_SIZE/WRITE_SIZE counter runs under profiles/ (null off the profiled workload)",
         },
         "other_batches": others,
         "setup_s": round(setup_s, 1),
