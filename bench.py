@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--lmax", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="debug: keep only the first N layers (+ lm_head)")
+    ap.add_argument("--fuse", choices=["none", "independent"], default="independent",
+                    help="independent: products of a layer that do not depend on each other (q,k,v and gate,up) go out "
+                         "in one tq_matvec_multi launch; none: one tq_matvec launch per matrix")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, so a counter profile of this command holds a kernel of "
                          "known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -103,13 +106,36 @@ def main():
             ys.append(torch.empty((batch, s.rows), dtype=torch.float32, device=dev))
         return xs, ys
 
+    # launch plan: consecutive matrices that a transformer layer computes from the same input are independent
+    groups, cur = [], []
+    for i, s in enumerate(specs):
+        kind = s.name.split(".")[-1]
+        joins = args.fuse == "independent" and cur and (
+            (kind in ("k_proj", "v_proj") and specs[cur[-1]].name.split(".")[-1] in ("q_proj", "k_proj")) or
+            (kind == "up_proj" and specs[cur[-1]].name.split(".")[-1] == "gate_proj"))
+        if joins:
+            cur.append(i)
+        else:
+            if cur:
+                groups.append(cur)
+            cur = [i]
+    groups.append(cur)
+
     def run(batch, steps, warmup):
         xs, ys = make_io(batch)
-        ptrs = [(m, x.data_ptr(), y.data_ptr()) for m, x, y in zip(mats, xs, ys)]
+        calls = []
+        for g in groups:
+            if len(g) == 1:
+                m, xp, yp = mats[g[0]], xs[g[0]].data_ptr(), ys[g[0]].data_ptr()
+                calls.append(lambda m=m, xp=xp, yp=yp: m.matvec(xp, yp, batch, stream))
+            else:
+                mc = tq.MultiCall([mats[i].handle for i in g], [xs[i].data_ptr() for i in g],
+                                  [ys[i].data_ptr() for i in g], batch)
+                calls.append(lambda mc=mc: mc.launch(stream))
 
         def step():
-            for m, xp, yp in ptrs:
-                m.matvec(xp, yp, batch, stream)
+            for c in calls:
+                c()
 
         for _ in range(warmup):
             step()
@@ -160,12 +186,13 @@ def main():
             "workload": f"config {args.config}: {CONFIGS[args.config]['desc']}, batch {args.batch}",
             "matrices": len(specs), "weights": n_weights, "compressed_bytes": comp_bytes,
             "bytes_per_weight": round(comp_bytes / n_weights, 4), "weights_per_code": round(n_weights / n_codes, 4),
-            "max_entries": infos[0]["n_entries"], "lmax": infos[0]["lmax"], "launches_per_step": len(specs),
+            "max_entries": infos[0]["n_entries"], "lmax": infos[0]["lmax"], "launches_per_step": len(groups),
+            "fuse": args.fuse,
         },
         "roofline": {
             "bound": "hbm", "kernel": "tq::k_matvec",
             "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-            "traffic": (round((MEASURED_FETCH_PER_ALGORITHMIC_BYTE * comp_bytes + MEASURED_WRITE_BYTES_PER_STEP) / len(specs))
+            "traffic": (round((MEASURED_FETCH_PER_ALGORITHMIC_BYTE * comp_bytes + MEASURED_WRITE_BYTES_PER_STEP) / len(groups))
                         if (args.config == 4 and args.batch == 1 and not args.max_entries and not args.lmax and not args.layers)
                         else None),
             "note": "achieved = compressed bytes of the sweep / HIP-event time of one step on the launch stream "

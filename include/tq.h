@@ -33,14 +33,15 @@ extern "C" {
 #define TQ_MAX_BATCH 16
 #define TQ_MAX_ENTRIES_DEVICE 32704 /* dictionary entries that fit the 160 KB LDS next to the decode tiles */
 #define TQ_DEFAULT_MAX_ENTRIES 32000
-#define TQ_DEFAULT_LMAX 3
+#define TQ_DEFAULT_LMAX 0 /* auto */
 
 typedef struct tq_matrix *tq_handle;
 
 /* Encoder options; zero-initialise and set what you need (0 = default). */
 typedef struct tq_encode_opts {
   uint32_t max_entries; /* dictionary size cap incl. the 256 single bytes; 256..TQ_MAX_ENTRIES_DEVICE */
-  uint32_t lmax;        /* longest run a dictionary entry may hold, 1..3 */
+  uint32_t lmax;        /* longest run a dictionary entry may hold, 1..3; 0 = encode with 2 and with 3 and keep the
+                           smaller container (LZW spends dictionary slots on triples that near-uniform data never reuses) */
   uint32_t n_threads;   /* host threads for the frozen-dictionary part of the parse; 0 = all cores (max 16) */
   uint32_t reserved[5];
 } tq_encode_opts;
@@ -96,6 +97,17 @@ int tq_create_from_encoded(const void *blob, size_t blob_bytes, tq_handle *out);
  * the kernel.  The result is deterministic (fixed summation order).
  */
 int tq_matvec(tq_handle h, const void *x, void *y, int batch, void *stream);
+
+/*
+ * tq_matvec for n independent matrices in one launch (for instance the q, k and v projections of a layer, or gate
+ * and up: products that do not depend on each other; the paper's layer-by-layer expansion, Background "Inference",
+ * leaves their order free).  hs, xs, ys: host arrays of n handles / device x pointers / device y pointers, with the
+ * meaning they have in tq_matvec; all share `batch`.  The workgroups of all matrices are dispatched together, so
+ * small matrices fill the GPU side by side.  Results are identical to n tq_matvec calls.  If the matrices cannot be
+ * fused (more than 8, different run-length caps, an unaligned x) the call issues n single launches instead.
+ * Same asynchrony rules as tq_matvec.
+ */
+int tq_matvec_multi(int n, const tq_handle *hs, const void *const *xs, void *const *ys, int batch, void *stream);
 
 /*
  * Un-fused form: expand the whole matrix (paper section 4, Listing "Decompressing Model Weights").

@@ -18,6 +18,8 @@ from .binding import (  # noqa: F401
     tq_validate_blob,
     tq_create_from_encoded,
     tq_matvec,
+    tq_matvec_multi,
+    MultiCall,
     tq_decompress,
     tq_get_info,
     tq_destroy,

@@ -17,7 +17,7 @@ _LIB: Optional[ctypes.CDLL] = None
 
 EXPORTS = [
     "tq_encode", "tq_encode_quantized", "tq_free_blob", "tq_validate_blob", "tq_create_from_encoded", "tq_matvec",
-    "tq_decompress", "tq_get_info", "tq_destroy", "tq_last_error_string",
+    "tq_matvec_multi", "tq_decompress", "tq_get_info", "tq_destroy", "tq_last_error_string",
 ]
 
 
@@ -70,6 +70,8 @@ def load() -> ctypes.CDLL:
     lib.tq_create_from_encoded.argtypes = [vp, sz, ctypes.POINTER(vp)]
     lib.tq_matvec.restype = ci
     lib.tq_matvec.argtypes = [vp, vp, vp, ci, vp]
+    lib.tq_matvec_multi.restype = ci
+    lib.tq_matvec_multi.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
     lib.tq_decompress.restype = ci
     lib.tq_decompress.argtypes = [vp, vp, vp]
     lib.tq_get_info.restype = ci
@@ -140,6 +142,24 @@ def tq_create_from_encoded(blob: bytes) -> int:
 
 def tq_matvec(handle: int, x_ptr: int, y_ptr: int, batch: int, stream: int = 0) -> None:
     _check(load().tq_matvec(handle, x_ptr, y_ptr, batch, stream))
+
+
+class MultiCall:
+    """Pre-marshalled argument arrays for tq_matvec_multi (built once, launched many times)."""
+
+    def __init__(self, handles, x_ptrs, y_ptrs, batch: int):
+        n = len(handles)
+        assert n == len(x_ptrs) == len(y_ptrs) and n >= 1
+        arr = ctypes.c_void_p * n
+        self.n, self.batch = n, batch
+        self.hs, self.xs, self.ys = arr(*handles), arr(*x_ptrs), arr(*y_ptrs)
+
+    def launch(self, stream: int = 0) -> None:
+        _check(load().tq_matvec_multi(self.n, self.hs, self.xs, self.ys, self.batch, stream))
+
+
+def tq_matvec_multi(handles, x_ptrs, y_ptrs, batch: int, stream: int = 0) -> None:
+    MultiCall(handles, x_ptrs, y_ptrs, batch).launch(stream)
 
 
 def tq_decompress(handle: int, out_ptr: int, stream: int = 0) -> None:

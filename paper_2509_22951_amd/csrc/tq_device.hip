@@ -280,8 +280,8 @@ __device__ __forceinline__ f32x4 mfma_tile(uint8_t* tile, int lane, const uint4 
 // A slot range touches at most two bands, so a wavefront carries two 16 x 16 fp32 accumulators (rows x batch).
 // After the pass the partial accumulators are summed through LDS in wave order (deterministic), scaled and stored.
 template <int kLmax, int kS>
-__global__ __launch_bounds__(kThreads, 1) void k_matvec(DevMat m, const uint16_t* __restrict__ x, float* __restrict__ y,
-                                                        int batch, uint32_t nb) {
+__device__ __forceinline__ void matvec_body(const DevMat& m, const uint16_t* __restrict__ x, float* __restrict__ y, int batch,
+                                            uint32_t nb, uint32_t slots, uint32_t block, uint32_t n_blocks) {
   extern __shared__ uint4 lds4[];
   uint32_t* dict = (uint32_t*)lds4;
   uint8_t* tiles = (uint8_t*)(dict + m.dict_words_pad);
@@ -294,7 +294,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(DevMat m, const uint16_t
     const uint16_t* xlane = x + (size_t)(x_lane ? j : 0) * m.cols + kg * 8;
 #pragma unroll
     for (int i = 0; i < kS; ++i) {
-      const uint32_t strip = (uint32_t)(kS * wave + i) % m.n_strips;
+      const uint32_t strip = (slots * wave + i) % m.n_strips;
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         const uint32_t col = strip * kGroupCols + t * 32;
@@ -307,9 +307,9 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(DevMat m, const uint16_t
   zero_tile(tile, lane);
   stage_dictionary(m, lds4, tid);
   const uint32_t n_pass = (m.n_bands + nb - 1) / nb;
-  for (uint32_t pass = blockIdx.x; pass < n_pass; pass += gridDim.x) {
+  for (uint32_t pass = block; pass < n_pass; pass += n_blocks) {
     const uint32_t band0 = pass * nb, nbh = min(nb, m.n_bands - band0), ng = nbh * m.n_strips;
-    const uint32_t f_lo = min((uint32_t)(kS * wave), ng), f_hi = min((uint32_t)(kS * wave + kS), ng);
+    const uint32_t f_lo = min(slots * wave, ng), f_hi = min(slots * wave + slots, ng);
     const uint32_t g_lo = band0 * m.n_strips + f_lo, g_hi = band0 * m.n_strips + f_hi;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc_first = {0.f, 0.f, 0.f, 0.f};
     const uint32_t band_first = g_lo / m.n_strips;
@@ -358,6 +358,33 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(DevMat m, const uint16_t
     __syncthreads();
     zero_tile(tile, lane);   // the partial sums lay over the tiles; the decoder needs them zero
   }
+}
+
+template <int kLmax, int kS>
+__global__ __launch_bounds__(kThreads, 1) void k_matvec(DevMat m, const uint16_t* __restrict__ x, float* __restrict__ y,
+                                                        int batch, uint32_t nb) {
+  matvec_body<kLmax, kS>(m, x, y, batch, nb, kS, blockIdx.x, gridDim.x);
+}
+
+// Several independent matrices in one launch (e.g. the q, k, v projections of a layer): the grid is the
+// concatenation of each matrix's own grid, every workgroup serves exactly one matrix, so small matrices run side by
+// side instead of leaving most CUs idle one launch after the other.
+constexpr int kMaxMulti = 8;
+struct MultiArgs {
+  DevMat m[kMaxMulti];
+  const uint16_t* x[kMaxMulti];
+  float* y[kMaxMulti];
+  uint32_t nb[kMaxMulti], slots[kMaxMulti];
+  uint32_t first_block[kMaxMulti + 1];
+  int n, batch;
+};
+
+template <int kLmax, int kS>
+__global__ __launch_bounds__(kThreads, 1) void k_matvec_multi(MultiArgs a) {
+  int i = 0;
+  while (i + 1 < a.n && blockIdx.x >= a.first_block[i + 1]) ++i;
+  matvec_body<kLmax, kS>(a.m[i], a.x[i], a.y[i], a.batch, a.nb[i], a.slots[i], blockIdx.x - a.first_block[i],
+                         a.first_block[i + 1] - a.first_block[i]);
 }
 
 // General-alignment fallback of the same product (activation pointer not 16-byte aligned or cols % 8 != 0):
@@ -490,6 +517,19 @@ matvec_fn pick_matvec_slots(uint32_t slots) {
 matvec_fn pick_matvec(uint32_t lmax, uint32_t slots) {
   return lmax == 1 ? pick_matvec_slots<1>(slots) : lmax == 2 ? pick_matvec_slots<2>(slots) : pick_matvec_slots<3>(slots);
 }
+typedef void (*matvec_multi_fn)(MultiArgs);
+template <int kLmax>
+matvec_multi_fn pick_multi_slots(uint32_t slots) {
+  switch (slots) {
+    case 1: return k_matvec_multi<kLmax, 1>;
+    case 2: return k_matvec_multi<kLmax, 2>;
+    case 3: return k_matvec_multi<kLmax, 3>;
+    default: return k_matvec_multi<kLmax, 4>;
+  }
+}
+matvec_multi_fn pick_matvec_multi(uint32_t lmax, uint32_t slots) {
+  return lmax == 1 ? pick_multi_slots<1>(slots) : lmax == 2 ? pick_multi_slots<2>(slots) : pick_multi_slots<3>(slots);
+}
 matvec_any_fn pick_matvec_any(uint32_t lmax) {
   return lmax == 1 ? k_matvec_anyalign<1> : lmax == 2 ? k_matvec_anyalign<2> : k_matvec_anyalign<3>;
 }
@@ -503,9 +543,11 @@ decompress_fn pick_decompress(uint32_t lmax, bool fast) {
 
 // Dynamic LDS above 64 KB has to be allowed per kernel function.
 int allow_lds(uint32_t lmax, size_t bytes) {
-  const void* fns[7] = {(const void*)pick_matvec(lmax, 1), (const void*)pick_matvec(lmax, 2), (const void*)pick_matvec(lmax, 3),
-                        (const void*)pick_matvec(lmax, 4), (const void*)pick_matvec_any(lmax),
-                        (const void*)pick_decompress(lmax, false), (const void*)pick_decompress(lmax, true)};
+  const void* fns[11] = {(const void*)pick_matvec(lmax, 1), (const void*)pick_matvec(lmax, 2), (const void*)pick_matvec(lmax, 3),
+                         (const void*)pick_matvec(lmax, 4), (const void*)pick_matvec_multi(lmax, 1),
+                         (const void*)pick_matvec_multi(lmax, 2), (const void*)pick_matvec_multi(lmax, 3),
+                         (const void*)pick_matvec_multi(lmax, 4), (const void*)pick_matvec_any(lmax),
+                         (const void*)pick_decompress(lmax, false), (const void*)pick_decompress(lmax, true)};
   for (const void* f : fns) {
     hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
@@ -642,6 +684,62 @@ extern "C" int tq_matvec(tq_handle h, const void* x, void* y, int batch, void* s
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail("tq_matvec launch", e);
+  return TQ_OK;
+}
+
+extern "C" int tq_matvec_multi(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {
+  if (n < 1 || !hs || !xs || !ys) {
+    set_error("tq_matvec_multi: null argument or n < 1");
+    return TQ_E_INVALID_ARG;
+  }
+  if (batch < 1 || batch > TQ_MAX_BATCH) {
+    set_error("tq_matvec_multi: batch must be in [1, " + std::to_string(TQ_MAX_BATCH) + "]");
+    return TQ_E_UNSUPPORTED;
+  }
+  for (int i = 0; i < n; ++i) {
+    if (!hs[i] || !xs[i] || !ys[i]) {
+      set_error("tq_matvec_multi: null handle or pointer at index " + std::to_string(i));
+      return TQ_E_INVALID_ARG;
+    }
+    if ((uintptr_t)xs[i] % 2 || (uintptr_t)ys[i] % 4) {
+      set_error("tq_matvec_multi: x must be 2-byte and y 4-byte aligned");
+      return TQ_E_INVALID_ARG;
+    }
+  }
+  // One fused launch needs: at most kMaxMulti matrices, one dictionary run-length cap, one LDS size class, and the
+  // aligned kernel for every member.  Anything else is served by consecutive single launches (same results).
+  bool fuse = n >= 2 && n <= kMaxMulti;
+  for (int i = 0; i < n && fuse; ++i)
+    fuse = hs[i]->bands_per_pass != 0 && hs[i]->h.lmax == hs[0]->h.lmax && hs[i]->device == hs[0]->device &&
+           (hs[i]->m.cols % 8 == 0) && ((uintptr_t)xs[i] % 16 == 0);
+  if (!fuse) {
+    for (int i = 0; i < n; ++i)
+      if (int rc = tq_matvec(hs[i], xs[i], ys[i], batch, stream)) return rc;
+    return TQ_OK;
+  }
+  MultiArgs a;
+  std::memset(&a, 0, sizeof a);
+  a.n = n;
+  a.batch = batch;
+  uint32_t slots = 1, blocks = 0;
+  size_t lds = 0;
+  for (int i = 0; i < n; ++i) {
+    const tq_matrix* t = hs[i];
+    a.m[i] = t->m;
+    a.x[i] = (const uint16_t*)xs[i];
+    a.y[i] = (float*)ys[i];
+    a.nb[i] = t->bands_per_pass;
+    a.slots[i] = t->slots;
+    a.first_block[i] = blocks;
+    const uint32_t passes = (t->m.n_bands + t->bands_per_pass - 1) / t->bands_per_pass;
+    blocks += std::min<uint32_t>(passes, (uint32_t)t->n_cu);
+    slots = std::max(slots, t->slots);
+    lds = std::max(lds, t->lds_bytes);
+  }
+  a.first_block[n] = blocks;
+  hipLaunchKernelGGL(pick_matvec_multi(hs[0]->h.lmax, slots), dim3(blocks), dim3(kThreads), lds, (hipStream_t)stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail("tq_matvec_multi launch", e);
   return TQ_OK;
 }
 

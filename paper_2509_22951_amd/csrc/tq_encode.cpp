@@ -127,8 +127,8 @@ int check_opts(const tq_encode_opts* o, uint32_t* max_entries, uint32_t* lmax, u
     set_error("tq_encode: max_entries must be in [256, " + std::to_string(TQ_MAX_ENTRIES_DEVICE) + "]");
     return TQ_E_INVALID_ARG;
   }
-  if (*lmax < 1 || *lmax > 3) {
-    set_error("tq_encode: lmax must be 1, 2 or 3");
+  if (*lmax > 3) {
+    set_error("tq_encode: lmax must be 0 (auto), 1, 2 or 3");
     return TQ_E_INVALID_ARG;
   }
   return TQ_OK;
@@ -140,9 +140,35 @@ inline uint64_t ser_index(uint64_t r, uint64_t c, uint64_t cols_pad) {
          (c % kMtCols);
 }
 
+int encode_with_lmax(const std::vector<uint8_t>& S, const std::vector<float>& scales_pad, uint32_t rows, uint32_t cols,
+                     uint32_t rows_pad, uint32_t cols_pad, uint32_t max_entries, uint32_t lmax, unsigned n_threads,
+                     void** blob_out, size_t* bytes_out);
+
+// lmax == 0: encode with runs of at most 3 and of at most 2 bytes and keep the smaller container (3 on a tie).
 int encode_serialized(const std::vector<uint8_t>& S, const std::vector<float>& scales_pad, uint32_t rows, uint32_t cols,
                       uint32_t rows_pad, uint32_t cols_pad, uint32_t max_entries, uint32_t lmax, unsigned n_threads,
                       void** blob_out, size_t* bytes_out) {
+  if (lmax != 0)
+    return encode_with_lmax(S, scales_pad, rows, cols, rows_pad, cols_pad, max_entries, lmax, n_threads, blob_out, bytes_out);
+  void *b3 = nullptr, *b2 = nullptr;
+  size_t n3 = 0, n2 = 0;
+  int rc = encode_with_lmax(S, scales_pad, rows, cols, rows_pad, cols_pad, max_entries, 3, n_threads, &b3, &n3);
+  if (rc != TQ_OK) return rc;
+  rc = encode_with_lmax(S, scales_pad, rows, cols, rows_pad, cols_pad, max_entries, 2, n_threads, &b2, &n2);
+  if (rc != TQ_OK) {
+    std::free(b3);
+    return rc;
+  }
+  const bool take2 = n2 < n3;
+  std::free(take2 ? b3 : b2);
+  *blob_out = take2 ? b2 : b3;
+  *bytes_out = take2 ? n2 : n3;
+  return TQ_OK;
+}
+
+int encode_with_lmax(const std::vector<uint8_t>& S, const std::vector<float>& scales_pad, uint32_t rows, uint32_t cols,
+                     uint32_t rows_pad, uint32_t cols_pad, uint32_t max_entries, uint32_t lmax, unsigned n_threads,
+                     void** blob_out, size_t* bytes_out) {
   const uint64_t n_groups = (uint64_t)(rows_pad / kTileRows) * (cols_pad / kGroupCols);
   Dict3 dict(max_entries, lmax);
 

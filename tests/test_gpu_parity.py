@@ -181,6 +181,51 @@ def test_repeated_calls_are_deterministic_and_overwrite(dev):
         m.close()
 
 
+def test_multi_launch_matches_single_launches_and_oracle(dev):
+    """q/k/v-like trio of different heights in one launch: bit-identical to three tq_matvec calls."""
+    shapes = [(192, 768), (64, 768), (64, 768), (48, 768)]
+    for batch in (1, 8):
+        mats, xs, ys, refs, singles = [], [], [], [], []
+        for k, (r, c) in enumerate(shapes):
+            spec = small_case(r, c, seed=100 + k)
+            W = make_weights(spec)
+            Qo, so = O.quantize_rows(W)
+            m = tq.Matrix(tq.tq_encode(W, max_entries=3000, lmax=3))
+            bits, x = make_activations(spec, batch)
+            xd = torch.from_numpy(bits.view(np.int16).copy()).to(dev)
+            mats.append(m)
+            xs.append(xd)
+            ys.append(torch.full((batch, r), float("nan"), dtype=torch.float32, device=dev))
+            refs.append(O.gemv_f64(Qo, so, x))
+            singles.append(gpu_matvec(m, bits, dev))
+        tq.tq_matvec_multi([m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch, _stream())
+        torch.cuda.synchronize()
+        for y, ref, one in zip(ys, refs, singles):
+            got = y.cpu().numpy()
+            assert np.array_equal(got, one)
+            check_outputs(got, ref)
+        for m in mats:
+            m.close()
+
+
+def test_multi_launch_falls_back_when_members_differ(dev):
+    specs = [small_case(64, 512, seed=200), small_case(32, 300, seed=201)]     # second one: cols % 8 != 0
+    mats = [tq.Matrix(tq.tq_encode(make_weights(s), max_entries=2000, lmax=l)) for s, l in zip(specs, (3, 2))]
+    xs, ys, refs = [], [], []
+    for s, m in zip(specs, mats):
+        bits, x = make_activations(s, 2)
+        xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
+        ys.append(torch.zeros((2, s.rows), dtype=torch.float32, device=dev))
+        Qo, so = O.quantize_rows(make_weights(s))
+        refs.append(O.gemv_f64(Qo, so, x))
+    tq.tq_matvec_multi([m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], 2, _stream())
+    torch.cuda.synchronize()
+    for y, ref in zip(ys, refs):
+        check_outputs(y.cpu().numpy(), ref)
+    for m in mats:
+        m.close()
+
+
 def test_argument_errors(dev):
     spec = small_case(16, 256, seed=29)
     m = tq.Matrix(tq.tq_encode(make_weights(spec)))

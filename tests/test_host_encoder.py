@@ -48,6 +48,16 @@ def test_encoder_container_is_byte_identical_to_the_oracles(shape, max_entries, 
     assert np.array_equal(Q, Qo) and np.array_equal(s, so)
 
 
+@pytest.mark.parametrize("dist", ["normal", "student_t4"])
+def test_auto_lmax_keeps_the_smaller_container(dist):
+    W = make_weights(small_case(512, 2048, seed=21, dist=dist))
+    auto = tq.tq_encode(W)                       # lmax = 0: auto
+    cands = {l: O.build_blob(O.encode_matrix(W, max_entries=tq.TQ_DEFAULT_MAX_ENTRIES, lmax=l)) for l in (2, 3)}
+    want = cands[2] if len(cands[2]) < len(cands[3]) else cands[3]
+    assert auto == want
+    assert tq.tq_validate_blob(auto)["lmax"] == (2 if dist == "normal" else 3)
+
+
 def test_encoder_is_deterministic_across_thread_counts():
     W = make_weights(small_case(256, 2048, seed=9))
     a = tq.tq_encode(W, max_entries=2000, n_threads=1)
@@ -61,7 +71,7 @@ def test_encode_quantized_accepts_any_byte_and_matches_oracle():
     Q[3, :] = -128
     Q[5, :] = 0
     s = rng.random(40).astype(np.float32)
-    blob = tq.tq_encode_quantized(Q, s, max_entries=5000)
+    blob = tq.tq_encode_quantized(Q, s, max_entries=5000, lmax=3)
     assert blob == O.build_blob(O.encode_quantized(Q, s, max_entries=5000, lmax=3))
     Qd, sd = O.decode_blob(blob)
     assert np.array_equal(Qd, Q) and np.array_equal(sd, s)
