@@ -31,26 +31,37 @@ extern "C" {
 #define TQ_E_HIP (-5)         /* a HIP runtime call or kernel launch failed */
 
 #define TQ_MAX_BATCH 16
-#define TQ_MAX_ENTRIES_DEVICE 32704 /* dictionary entries that fit the 160 KB LDS next to the decode tiles */
-#define TQ_DEFAULT_MAX_ENTRIES 32000
-#define TQ_DEFAULT_LMAX 0 /* auto */
+/* Dictionary entries (incl. the 256 single bytes) that fit the 120 KB of LDS the kernels give the dictionary:
+ * an entry holds at most 2 weights and takes one 32-bit word there (two bf16 values); one more word is the pad entry. */
+#define TQ_MAX_ENTRIES_DEVICE 30719
+#define TQ_MAX_LMAX 2
+#define TQ_DEFAULT_LMAX 2
+#define TQ_DEFAULT_SEG_COLS 256
 
 typedef struct tq_matrix *tq_handle;
 
 /* Encoder options; zero-initialise and set what you need (0 = default). */
 typedef struct tq_encode_opts {
-  uint32_t max_entries; /* dictionary size cap incl. the 256 single bytes; 256..TQ_MAX_ENTRIES_DEVICE */
-  uint32_t lmax;        /* longest run a dictionary entry may hold, 1..3; 0 = encode with 2 and with 3 and keep the
-                           smaller container (LZW spends dictionary slots on triples that near-uniform data never reuses) */
+  uint32_t max_entries; /* dictionary size cap incl. the 256 single bytes; 256..TQ_MAX_ENTRIES_DEVICE;
+                           0 = TQ_MAX_ENTRIES_DEVICE */
+  uint32_t lmax;        /* longest run a dictionary entry may hold, 1..TQ_MAX_LMAX; 0 = TQ_DEFAULT_LMAX */
   uint32_t n_threads;   /* host threads for the frozen-dictionary part of the parse; 0 = all cores (max 16) */
-  uint32_t reserved[5];
+  uint32_t seg_cols;    /* columns per independently decodable segment (the tile width of the per-tile stream offsets):
+                           multiple of 16 in 16..1024; 0 = TQ_DEFAULT_SEG_COLS */
+  const void *dict_from;    /* NULL, or a container made earlier: its dictionary is taken over and LZW goes on from
+                               there (one dictionary over a sequence of matrices, as the table of paper section 4 is
+                               built over all parameters of the model).  Once the dictionary is full every later
+                               matrix of the sequence gets byte-identical dictionaries, which the device side stores
+                               and stages once. */
+  uint64_t dict_from_bytes; /* size of that container */
 } tq_encode_opts;
 
 typedef struct tq_info {
   uint32_t rows, cols;         /* logical shape R x K, y = W x */
-  uint32_t rows_pad, cols_pad; /* shape the container stores (multiples of 16 and 256, zero filled) */
+  uint32_t seg_cols, n_panels; /* columns per segment; segments per row */
   uint32_t n_entries, lmax;
-  uint64_t n_groups, n_codes; /* restart groups (16 x 256 weights each); 16-bit codes incl. padding codes */
+  uint64_t n_units, n_codes;   /* units of 16 rows x 4 segments; 16-bit codes stored, incl. padding codes */
+  uint64_t n_real_codes;       /* codes of the LZW parse itself (n_codes minus padding) */
   uint64_t dict_bytes, offset_bytes, code_bytes, scale_bytes;
   uint64_t compressed_bytes; /* sum of the four sections = bytes the kernels must read from HBM */
 } tq_info;
@@ -58,9 +69,10 @@ typedef struct tq_info {
 /*
  * Host-side encoder (off the hot path).  w: host, fp32 [rows][cols] row-major.
  * Quantizes each row to int8 (symmetric, scale = absmax/127, round-half-to-even: the 8-bit setting
- * of paper section 3 at per-row granularity), serializes the matrix in 16x8 micro-tiles, runs LZW
- * with a frozen, size-capped dictionary over it (paper Background "Compression"), and lays out the
- * container: header, dictionary, per-group code offsets, 16-bit code stream, per-row scales.
+ * of paper section 3 at per-row granularity), cuts the rows into segments of seg_cols columns, runs LZW
+ * with a frozen, size-capped dictionary over the segments (paper Background "Compression"; a run never
+ * crosses a segment boundary), and lays out the container: header, dictionary, per-unit code offsets,
+ * 16-bit code stream with the 64 lane streams of a unit interleaved, per-row scales.
  * *blob is allocated by the library; release it with tq_free_blob.  Deterministic for any n_threads.
  */
 int tq_encode(const float *w, uint32_t rows, uint32_t cols, const tq_encode_opts *opts, void **blob, size_t *blob_bytes);
@@ -73,8 +85,8 @@ int tq_encode_quantized(const int8_t *q, const float *scales, uint32_t rows, uin
 void tq_free_blob(void *blob);
 
 /* Full host-side validation of a container (no GPU needed): header, section bounds, every dictionary
- * entry, monotone 8-aligned group offsets, every code in range, padding codes only at group ends, and
- * every group's runs summing to exactly 4096 bytes.  info may be NULL. */
+ * entry, monotone unit offsets, every code in range, padding codes only at the end of a lane stream, and
+ * every lane stream's runs summing to exactly its segment's length.  info may be NULL. */
 int tq_validate_blob(const void *blob, size_t blob_bytes, tq_info *info);
 
 /*
@@ -94,7 +106,9 @@ int tq_create_from_encoded(const void *blob, size_t blob_bytes, tq_handle *out);
  * Asynchronous: returns after the launch; no host synchronisation, no allocation, no change to the
  * handle, so it may be captured in a HIP graph and called concurrently on different streams.
  * 1 <= batch <= TQ_MAX_BATCH, else TQ_E_UNSUPPORTED.  x and y must stay alive until the stream passes
- * the kernel.  The result is deterministic (fixed summation order).
+ * the kernel.  The result is deterministic (fixed summation order).  x values must be finite: a lane that has
+ * run out of codes multiplies activations of later columns by zero, so an infinity or NaN anywhere in x makes
+ * every output of that batch row non-finite (the plain definition does the same whenever a weight is zero).
  */
 int tq_matvec(tq_handle h, const void *x, void *y, int batch, void *stream);
 
@@ -104,7 +118,7 @@ int tq_matvec(tq_handle h, const void *x, void *y, int batch, void *stream);
  * leaves their order free).  hs, xs, ys: host arrays of n handles / device x pointers / device y pointers, with the
  * meaning they have in tq_matvec; all share `batch`.  The workgroups of all matrices are dispatched together, so
  * small matrices fill the GPU side by side.  Results are identical to n tq_matvec calls.  If the matrices cannot be
- * fused (more than 8, different run-length caps, an unaligned x) the call issues n single launches instead.
+ * fused (more than 8, dictionaries of different word width) the call issues n single launches instead.
  * Same asynchrony rules as tq_matvec.
  */
 int tq_matvec_multi(int n, const tq_handle *hs, const void *const *xs, void *const *ys, int batch, void *stream);

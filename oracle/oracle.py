@@ -29,13 +29,13 @@ from dataclasses import dataclass
 
 import numpy as np
 
-TILE_ROWS = 16      # rows per micro-tile
-MT_COLS = 8         # columns per micro-tile
-GROUP_COLS = 256    # columns per restart group (32 micro-tiles)
-GROUP_BYTES = TILE_ROWS * GROUP_COLS
-CODE_ALIGN = 8      # each group's code run is padded to a multiple of this many codes (one 16-byte lane load)
+UNIT_ROWS = 16      # rows of a unit (lane & 15)
+UNIT_PANELS = 4     # column panels of a unit (lane >> 4)
+CHUNK_CODES = 4     # codes per lane and chunk
+CHUNK_WORDS = 64 * CHUNK_CODES
+DEFAULT_SEG_COLS = 256
 LCAP = 16           # must equal TQO_LCAP in tq_oracle.c
-MAGIC = b"TQMOEv1\0"
+MAGIC = b"TQMOEv2\0"
 HEADER_BYTES = 256
 SECTION_ALIGN = 256
 
@@ -62,9 +62,9 @@ def _lib():
         lib = ctypes.CDLL(build_oracle_lib())
         ll, vp, ci = ctypes.c_longlong, ctypes.c_void_p, ctypes.c_int
         lib.tqo_lzw_encode.restype = ll
-        lib.tqo_lzw_encode.argtypes = [vp, ll, ll, ci, ci, vp, vp, vp, vp, ctypes.POINTER(ci)]
+        lib.tqo_lzw_encode.argtypes = [vp, ll, vp, ll, ci, ci, ci, vp, vp, vp, vp, ctypes.POINTER(ci)]
         lib.tqo_lzw_decode.restype = ll
-        lib.tqo_lzw_decode.argtypes = [vp, vp, ll, ll, ll, vp, vp, ci, ci, vp]
+        lib.tqo_lzw_decode.argtypes = [vp, vp, vp, ll, vp, vp, ci, ci, vp]
         lib.tqo_gemv_f64.restype = None
         lib.tqo_gemv_f64.argtypes = [vp, vp, vp, ll, ll, ll, vp]
         _LIB = lib
@@ -94,32 +94,55 @@ def quantize_rows(W: np.ndarray):
 
 # --------------------------------------------------------------------------- serialization
 
-def padded_shape(rows: int, cols: int):
-    rp = -(-rows // TILE_ROWS) * TILE_ROWS
-    cp = -(-cols // GROUP_COLS) * GROUP_COLS
-    return rp, cp
+def geometry(rows: int, cols: int, seg_cols: int = DEFAULT_SEG_COLS):
+    """(n_bands, n_panels, n_quads) of a rows x cols matrix cut into segments of seg_cols columns."""
+    assert seg_cols % 16 == 0 and 16 <= seg_cols <= 1024
+    n_bands = -(-rows // UNIT_ROWS)
+    n_panels = -(-cols // seg_cols)
+    n_quads = -(-n_panels // UNIT_PANELS)
+    return n_bands, n_panels, n_quads
 
 
-def serialize(Q: np.ndarray) -> np.ndarray:
-    """Matrix -> codec byte string.  Q is zero-padded to multiples of (16, 256); the string lists
-    16x8 micro-tiles (each row-major), micro-tiles left to right, 16-row bands top to bottom.
+def segment_table(rows: int, cols: int, seg_cols: int = DEFAULT_SEG_COLS):
+    """The segments in stream order.  A segment is seg_cols consecutive columns of one row (the last panel of a
+    row may be shorter).  They come in units of 64 = 16 consecutive rows (a band) x 4 consecutive panels (a quad),
+    units ordered band-major then quad; inside a unit, lane l owns row 16*band + (l & 15), panel 4*quad + (l >> 4).
+    Segments past the matrix edge exist with length 0.  Returns (row, col0, length) int64 arrays [n_units * 64]."""
+    n_bands, n_panels, n_quads = geometry(rows, cols, seg_cols)
+    band, quad, lane = np.meshgrid(np.arange(n_bands), np.arange(n_quads), np.arange(64), indexing="ij")
+    row = (UNIT_ROWS * band + (lane & 15)).reshape(-1).astype(np.int64)
+    panel = (UNIT_PANELS * quad + (lane >> 4)).reshape(-1).astype(np.int64)
+    col0 = panel * seg_cols
+    length = np.where((row < rows) & (panel < n_panels), np.minimum(seg_cols, cols - col0), 0).astype(np.int64)
+    length = np.maximum(length, 0)
+    return row, col0, length
+
+
+def serialize(Q: np.ndarray, seg_cols: int = DEFAULT_SEG_COLS):
+    """Matrix -> (codec byte string, segment lengths): the segments of segment_table() back to back;
     int8 -> byte by two's complement."""
     Q = np.ascontiguousarray(Q, dtype=np.int8)
     rows, cols = Q.shape
-    rp, cp = padded_shape(rows, cols)
-    P = np.zeros((rp, cp), dtype=np.int8)
-    P[:rows, :cols] = Q
-    # (band, i, microtile, c) -> (band, microtile, i, c)
-    S = P.reshape(rp // TILE_ROWS, TILE_ROWS, cp // MT_COLS, MT_COLS).transpose(0, 2, 1, 3)
-    return np.ascontiguousarray(S).reshape(-1).view(np.uint8)
+    row, col0, length = segment_table(rows, cols, seg_cols)
+    start = np.zeros(length.size + 1, np.int64)
+    np.cumsum(length, out=start[1:])
+    seg = np.repeat(np.arange(length.size), length)
+    within = np.arange(int(start[-1]), dtype=np.int64) - start[seg]
+    S = Q[row[seg], col0[seg] + within]
+    return np.ascontiguousarray(S).view(np.uint8), length.astype(np.uint32)
 
 
-def deserialize(S: np.ndarray, rows: int, cols: int) -> np.ndarray:
-    rp, cp = padded_shape(rows, cols)
+def deserialize(S: np.ndarray, rows: int, cols: int, seg_cols: int = DEFAULT_SEG_COLS) -> np.ndarray:
     S = np.ascontiguousarray(S, dtype=np.uint8)
-    assert S.size == rp * cp
-    P = S.view(np.int8).reshape(rp // TILE_ROWS, cp // MT_COLS, TILE_ROWS, MT_COLS).transpose(0, 2, 1, 3)
-    return np.ascontiguousarray(P).reshape(rp, cp)[:rows, :cols].copy()
+    row, col0, length = segment_table(rows, cols, seg_cols)
+    assert S.size == int(length.sum()) == rows * cols
+    start = np.zeros(length.size + 1, np.int64)
+    np.cumsum(length, out=start[1:])
+    seg = np.repeat(np.arange(length.size), length)
+    within = np.arange(S.size, dtype=np.int64) - start[seg]
+    Q = np.zeros((rows, cols), np.int8)
+    Q[row[seg], col0[seg] + within] = S.view(np.int8)
+    return Q
 
 
 # --------------------------------------------------------------------------- codec
@@ -137,54 +160,78 @@ class Dictionary:
         return bytes(self.ent_bytes[e, : self.ent_len[e]])
 
 
-def lzw_encode(S: np.ndarray, group_bytes: int = GROUP_BYTES, max_entries: int = 32000, lmax: int = 3):
-    """Returns (codes uint16 [n_codes] without padding, group_ncodes uint32 [n_groups], Dictionary)."""
+def lzw_encode(S: np.ndarray, seg_len, max_entries: int = 30719, lmax: int = 2, carry: "Dictionary | None" = None):
+    """LZW over the segments of S (a match never crosses a segment end).  `seg_len` is the array of segment
+    lengths, or one integer = equal-length segments (the last may be short).  `carry` = the dictionary a previous
+    call returned: the parse starts with those entries instead of the 256 singles alone.
+    Returns (codes uint16 [n_codes], seg_ncodes uint32 [n_segs], Dictionary)."""
     S = np.ascontiguousarray(S, dtype=np.uint8)
     n = int(S.size)
-    n_groups = -(-n // group_bytes) if n else 0
+    if np.isscalar(seg_len):
+        g = int(seg_len)
+        k = -(-n // g) if n else 0
+        seg_len = np.full(k, g, np.uint32)
+        if k:
+            seg_len[-1] = n - g * (k - 1)
+    seg_len = np.ascontiguousarray(seg_len, dtype=np.uint32)
+    n_segs = int(seg_len.size)
     codes = np.zeros(max(n, 1), dtype=np.uint16)
-    gnc = np.zeros(max(n_groups, 1), dtype=np.uint32)
+    snc = np.zeros(max(n_segs, 1), dtype=np.uint32)
     eb = np.zeros((max_entries, LCAP), dtype=np.uint8)
     el = np.zeros(max_entries, dtype=np.uint8)
+    n_init = 0
+    if carry is not None:
+        n_init = carry.n_entries
+        eb[:n_init] = carry.ent_bytes
+        el[:n_init] = carry.ent_len
     ne = ctypes.c_int(0)
-    nc = _lib().tqo_lzw_encode(_ptr(S), n, group_bytes, max_entries, lmax, _ptr(codes), _ptr(gnc), _ptr(eb), _ptr(el),
-                               ctypes.byref(ne))
+    nc = _lib().tqo_lzw_encode(_ptr(S), n, _ptr(seg_len), n_segs, max_entries, lmax, n_init, _ptr(codes), _ptr(snc),
+                               _ptr(eb), _ptr(el), ctypes.byref(ne))
     if nc < 0:
         raise ValueError("tqo_lzw_encode: bad arguments")
-    return codes[:nc].copy(), gnc[:n_groups].copy(), Dictionary(eb[: ne.value].copy(), el[: ne.value].copy())
+    return codes[:nc].copy(), snc[:n_segs].copy(), Dictionary(eb[: ne.value].copy(), el[: ne.value].copy())
 
 
-def pad_stream(codes: np.ndarray, group_ncodes: np.ndarray, pad_code: int, align: int = CODE_ALIGN):
-    """Lay the per-group code runs out with each run padded to a multiple of `align` codes.
-    Returns (stream uint16, goff uint32 [n_groups+1])."""
-    padded = (-(-group_ncodes.astype(np.int64) // align)) * align
-    goff = np.zeros(group_ncodes.size + 1, dtype=np.int64)
-    np.cumsum(padded, out=goff[1:])
-    stream = np.full(int(goff[-1]), pad_code, dtype=np.uint16)
-    src = np.zeros(group_ncodes.size + 1, dtype=np.int64)
-    np.cumsum(group_ncodes.astype(np.int64), out=src[1:])
-    # destination index of every real code
-    grp = np.repeat(np.arange(group_ncodes.size), group_ncodes.astype(np.int64))
-    dst = np.arange(codes.size, dtype=np.int64) - src[grp] + goff[grp]
+def interleave(codes: np.ndarray, seg_ncodes: np.ndarray, pad_code: int):
+    """Lay the code runs of the segments out as lane streams: segments come in units of 64 (segment g = lane g % 64
+    of unit g // 64; the last unit is completed with empty segments); every lane stream of a unit is padded with
+    pad_code to the unit's length = longest lane stream rounded up to whole chunks of 4 codes; code k of lane l of
+    unit u goes to stream[(uoff[u] + k // 4) * 256 + l * 4 + k % 4].  Returns (stream uint16, uoff uint32 [n_units+1],
+    in chunks)."""
+    n_segs = int(seg_ncodes.size)
+    n_units = -(-n_segs // 64)
+    cnt = np.zeros(n_units * 64, np.int64)
+    cnt[:n_segs] = seg_ncodes
+    unit_chunks = -(-cnt.reshape(n_units, 64).max(axis=1) // CHUNK_CODES) if n_units else np.zeros(0, np.int64)
+    uoff = np.zeros(n_units + 1, np.int64)
+    np.cumsum(unit_chunks, out=uoff[1:])
+    assert uoff[-1] * CHUNK_WORDS < 2 ** 32
+    stream = np.full(int(uoff[-1]) * CHUNK_WORDS, pad_code, dtype=np.uint16)
+    src = np.zeros(cnt.size + 1, np.int64)
+    np.cumsum(cnt, out=src[1:])
+    seg = np.repeat(np.arange(cnt.size), cnt)
+    k = np.arange(codes.size, dtype=np.int64) - src[seg]
+    dst = (uoff[seg // 64] + k // CHUNK_CODES) * CHUNK_WORDS + (seg % 64) * CHUNK_CODES + k % CHUNK_CODES
     stream[dst] = codes
-    assert goff[-1] < 2 ** 32
-    return stream, goff.astype(np.uint32)
+    return stream, uoff.astype(np.uint32)
 
 
-def lzw_decode(stream: np.ndarray, goff: np.ndarray, d: Dictionary, n_bytes: int, pad_code: int,
-               group_bytes: int = GROUP_BYTES) -> np.ndarray:
+def lzw_decode(stream: np.ndarray, uoff: np.ndarray, seg_len: np.ndarray, d: Dictionary, pad_code: int) -> np.ndarray:
+    """Inverse of lzw_encode + interleave: returns the byte string (segments back to back)."""
     stream = np.ascontiguousarray(stream, dtype=np.uint16)
-    goff = np.ascontiguousarray(goff, dtype=np.uint32)
-    n_groups = goff.size - 1
-    assert n_groups == (-(-n_bytes // group_bytes) if n_bytes else 0)
-    out = np.zeros(n_bytes, dtype=np.uint8)
+    uoff = np.ascontiguousarray(uoff, dtype=np.uint32)
+    seg_len = np.ascontiguousarray(seg_len, dtype=np.uint32)
+    n_segs = int(seg_len.size)
+    assert uoff.size - 1 == -(-n_segs // 64)
+    assert stream.size == int(uoff[-1]) * CHUNK_WORDS
+    out = np.zeros(max(int(seg_len.sum()), 1), dtype=np.uint8)
     eb = np.ascontiguousarray(d.ent_bytes, dtype=np.uint8)
     el = np.ascontiguousarray(d.ent_len, dtype=np.uint8)
-    rc = _lib().tqo_lzw_decode(_ptr(stream), _ptr(goff), n_groups, group_bytes, n_bytes, _ptr(eb), _ptr(el),
-                               d.n_entries, pad_code, _ptr(out))
+    rc = _lib().tqo_lzw_decode(_ptr(stream), _ptr(uoff), _ptr(seg_len), n_segs, _ptr(eb), _ptr(el), d.n_entries,
+                               pad_code, _ptr(out))
     if rc != 0:
-        raise ValueError(f"stream inconsistent in group {-rc - 1}")
-    return out
+        raise ValueError(f"stream inconsistent in segment {-rc - 1}")
+    return out[: int(seg_len.sum())]
 
 
 # --------------------------------------------------------------------------- GEMV
@@ -210,13 +257,14 @@ def gemv_f64(Q: np.ndarray, s: np.ndarray, x: np.ndarray) -> np.ndarray:
 class Encoded:
     rows: int
     cols: int
+    seg_cols: int
     lmax: int
     max_entries: int
     Q: np.ndarray           # int8 [rows, cols]
     scales: np.ndarray      # fp32 [rows]
     dictionary: Dictionary
-    stream: np.ndarray      # uint16, padded
-    goff: np.ndarray        # uint32 [n_groups + 1]
+    stream: np.ndarray      # uint16, interleaved and padded
+    uoff: np.ndarray        # uint32 [n_units + 1], in chunks
     n_real_codes: int
 
     @property
@@ -224,21 +272,24 @@ class Encoded:
         return self.dictionary.n_entries
 
 
-def encode_quantized(Q: np.ndarray, scales: np.ndarray, max_entries: int = 32000, lmax: int = 3) -> Encoded:
+def encode_quantized(Q: np.ndarray, scales: np.ndarray, max_entries: int = 30719, lmax: int = 2,
+                     seg_cols: int = DEFAULT_SEG_COLS, carry: "Dictionary | None" = None) -> Encoded:
     rows, cols = Q.shape
-    S = serialize(Q)
-    codes, gnc, d = lzw_encode(S, GROUP_BYTES, max_entries, lmax)
-    stream, goff = pad_stream(codes, gnc, d.n_entries)
-    return Encoded(rows, cols, lmax, max_entries, Q, np.asarray(scales, np.float32), d, stream, goff, int(codes.size))
+    S, seg_len = serialize(Q, seg_cols)
+    codes, snc, d = lzw_encode(S, seg_len, max_entries, lmax, carry)
+    stream, uoff = interleave(codes, snc, d.n_entries)
+    return Encoded(rows, cols, seg_cols, lmax, max_entries, Q, np.asarray(scales, np.float32), d, stream, uoff,
+                   int(codes.size))
 
 
-def encode_matrix(W: np.ndarray, max_entries: int = 32000, lmax: int = 3) -> Encoded:
+def encode_matrix(W: np.ndarray, max_entries: int = 30719, lmax: int = 2, seg_cols: int = DEFAULT_SEG_COLS,
+                  carry: "Dictionary | None" = None) -> Encoded:
     Q, s = quantize_rows(W)
-    return encode_quantized(Q, s, max_entries, lmax)
+    return encode_quantized(Q, s, max_entries, lmax, seg_cols, carry)
 
 
 def dict_slots(d: Dictionary) -> np.ndarray:
-    """Device dictionary words: bytes 0..2 = run (unused bytes zero), byte 3 = run length in bits (8, 16
+    """Container dictionary words: bytes 0..2 = run (unused bytes zero), byte 3 = run length in bits (8, 16
     or 24); one extra all-zero word at index n_entries is the pad code's entry (length 0).  Needs lmax <= 3."""
     assert int(d.ent_len.max()) <= 3
     eb = d.ent_bytes.astype(np.uint32)
@@ -250,26 +301,31 @@ def _align(n: int, a: int = SECTION_ALIGN) -> int:
     return -(-n // a) * a
 
 
-_HDR = struct.Struct("<8sII" "II" "II" "IIII" "IIII" "QQ" "QQ" "QQ" "QQ" "QQ" "Q" "I")
+# magic, version, header_bytes | rows, cols | seg_cols, unit_rows, unit_panels, chunk_codes | n_bands, n_panels,
+# n_quads | n_entries, lmax, max_entries, pad_code, reserved | n_units, n_chunks, n_real_codes |
+# (offset, size) of dictionary, unit offsets, codes, scales | total
+_HDR = struct.Struct("<8sII" "II" "IIII" "III" "IIIII" "QQQ" "QQ" "QQ" "QQ" "QQ" "Q")
 
 
 def build_blob(e: Encoded) -> bytes:
-    rp, cp = padded_shape(e.rows, e.cols)
+    n_bands, n_panels, n_quads = geometry(e.rows, e.cols, e.seg_cols)
+    n_units = n_bands * n_quads
     slots = dict_slots(e.dictionary)
-    scales = np.zeros(rp, np.float32)
+    scales = np.zeros(n_bands * UNIT_ROWS, np.float32)
     scales[: e.rows] = e.scales
-    n_groups = (rp // TILE_ROWS) * (cp // GROUP_COLS)
-    assert e.goff.size == n_groups + 1
-    sec = [slots.tobytes(), e.goff.astype(np.uint32).tobytes(), e.stream.astype(np.uint16).tobytes(), scales.tobytes()]
+    assert e.uoff.size == n_units + 1
+    n_chunks = int(e.uoff[-1])
+    assert e.stream.size == n_chunks * CHUNK_WORDS
+    sec = [slots.tobytes(), e.uoff.astype(np.uint32).tobytes(), e.stream.astype(np.uint16).tobytes(), scales.tobytes()]
     offs, pos = [], HEADER_BYTES
     for b in sec:
         offs.append(pos)
         pos = _align(pos + len(b))
     total = pos
-    hdr = _HDR.pack(MAGIC, 1, HEADER_BYTES, e.rows, e.cols, rp, cp, TILE_ROWS, MT_COLS, GROUP_COLS, GROUP_BYTES,
-                    e.dictionary.n_entries, e.lmax, e.max_entries, e.pad_code, n_groups, int(e.stream.size),
-                    offs[0], len(sec[0]), offs[1], len(sec[1]), offs[2], len(sec[2]), offs[3], len(sec[3]),
-                    total, CODE_ALIGN)
+    hdr = _HDR.pack(MAGIC, 2, HEADER_BYTES, e.rows, e.cols, e.seg_cols, UNIT_ROWS, UNIT_PANELS, CHUNK_CODES,
+                    n_bands, n_panels, n_quads, e.dictionary.n_entries, e.lmax, e.max_entries, e.pad_code, 0,
+                    n_units, n_chunks, e.n_real_codes,
+                    offs[0], len(sec[0]), offs[1], len(sec[1]), offs[2], len(sec[2]), offs[3], len(sec[3]), total)
     out = bytearray(total)
     out[: len(hdr)] = hdr
     for o, b in zip(offs, sec):
@@ -278,33 +334,38 @@ def build_blob(e: Encoded) -> bytes:
 
 
 def parse_blob(blob: bytes) -> dict:
-    (magic, version, hbytes, rows, cols, rp, cp, tr, mc, gc, gb, n_entries, lmax, max_entries, pad_code, n_groups,
-     n_codes, o_d, b_d, o_g, b_g, o_c, b_c, o_s, b_s, total, calign) = _HDR.unpack_from(blob, 0)
-    assert magic == MAGIC and version == 1 and hbytes == HEADER_BYTES
-    assert (tr, mc, gc, gb, calign) == (TILE_ROWS, MT_COLS, GROUP_COLS, GROUP_BYTES, CODE_ALIGN)
+    (magic, version, hbytes, rows, cols, seg_cols, ur, up, cc, n_bands, n_panels, n_quads, n_entries, lmax,
+     max_entries, pad_code, _res, n_units, n_chunks, n_real, o_d, b_d, o_u, b_u, o_c, b_c, o_s, b_s,
+     total) = _HDR.unpack_from(blob, 0)
+    assert magic == MAGIC and version == 2 and hbytes == HEADER_BYTES
+    assert (ur, up, cc) == (UNIT_ROWS, UNIT_PANELS, CHUNK_CODES)
+    assert (n_bands, n_panels, n_quads) == geometry(rows, cols, seg_cols) and n_units == n_bands * n_quads
     assert total == len(blob) and pad_code == n_entries
     buf = np.frombuffer(blob, dtype=np.uint8)
     slots = buf[o_d: o_d + b_d].view(np.uint32)
-    goff = buf[o_g: o_g + b_g].view(np.uint32)
+    uoff = buf[o_u: o_u + b_u].view(np.uint32)
     stream = buf[o_c: o_c + b_c].view(np.uint16)
     scales = buf[o_s: o_s + b_s].view(np.float32)
-    assert slots.size == n_entries + 1 and goff.size == n_groups + 1 and stream.size == n_codes and scales.size == rp
+    assert slots.size == n_entries + 1 and uoff.size == n_units + 1 and stream.size == n_chunks * CHUNK_WORDS
+    assert scales.size == n_bands * UNIT_ROWS and int(uoff[-1]) == n_chunks
     assert np.all((slots[:n_entries] >> 24) % 8 == 0)
     el = ((slots[:n_entries] >> 24) // 8).astype(np.uint8)
     eb = np.zeros((n_entries, LCAP), np.uint8)
     for k in range(3):
         eb[:, k] = (slots[:n_entries] >> (8 * k)) & 0xFF
-    return dict(rows=rows, cols=cols, rows_pad=rp, cols_pad=cp, n_entries=n_entries, lmax=lmax,
-                max_entries=max_entries, pad_code=pad_code, n_groups=n_groups, n_codes=n_codes,
-                dictionary=Dictionary(eb, el), slots=slots, goff=goff, stream=stream, scales=scales,
-                compressed_bytes=int(b_d + b_g + b_c + b_s), stream_bytes=int(b_c))
+    return dict(rows=rows, cols=cols, seg_cols=seg_cols, n_bands=n_bands, n_panels=n_panels, n_quads=n_quads,
+                n_entries=n_entries, lmax=lmax, max_entries=max_entries, pad_code=pad_code, n_units=n_units,
+                n_chunks=n_chunks, n_codes=n_chunks * CHUNK_WORDS, n_real_codes=n_real,
+                dictionary=Dictionary(eb, el), slots=slots, uoff=uoff, stream=stream, scales=scales,
+                compressed_bytes=int(b_d + b_u + b_c + b_s), stream_bytes=int(b_c))
 
 
 def decode_blob(blob: bytes):
     """Container -> (Q int8 [rows, cols], scales fp32 [rows]) through the oracle's own decoder."""
     p = parse_blob(blob)
-    S = lzw_decode(p["stream"], p["goff"], p["dictionary"], p["rows_pad"] * p["cols_pad"], p["pad_code"])
-    return deserialize(S, p["rows"], p["cols"]), p["scales"][: p["rows"]].copy()
+    _, _, seg_len = segment_table(p["rows"], p["cols"], p["seg_cols"])
+    S = lzw_decode(p["stream"], p["uoff"], seg_len.astype(np.uint32), p["dictionary"], p["pad_code"])
+    return deserialize(S, p["rows"], p["cols"], p["seg_cols"]), p["scales"][: p["rows"]].copy()
 
 
 def matvec_from_blob(blob: bytes, x: np.ndarray) -> np.ndarray:

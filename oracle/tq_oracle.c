@@ -9,7 +9,7 @@
  *                     new entry.  Two bounded-resource rules are added (the paper gives none):
  *                     entries stop being added once `max_entries` exist (the dictionary is then
  *                     frozen, never reset), and a match is at most `lmax` bytes and never crosses a
- *                     restart boundary (every `group_bytes` bytes of input).
+ *                     restart boundary (the input is a sequence of segments of given lengths).
  *   tqo_lzw_decode  - the decompression step of section 4 ("8-bit Quantization Compression"): each
  *                     codeword is replaced by its table sequence, reproducing the input exactly.
  *                     There is no escape/raw branch because the single bytes are always entries.
@@ -23,15 +23,22 @@
 #define TQO_LCAP 16 /* storage per entry; lmax may not exceed it */
 
 /*
- * in:  S[n] bytes; restart boundary every group_bytes (last group may be short)
- * out: codes[] (capacity n), group_ncodes[n_groups] = codes emitted per group,
+ * in:  S[n] bytes = n_segs segments back to back, segment g has seg_len[g] bytes (may be 0)
+ *      n_init: 0 to start from the 256 single bytes, or the number of entries (>= 256) already present in
+ *      ent_bytes / ent_len: the dictionary a previous call left behind, so that one LZW dictionary runs over a
+ *      sequence of inputs (section 4 of the paper builds its table over all parameters of the model)
+ * out: codes[] (capacity n), seg_ncodes[n_segs] = codes emitted per segment,
  *      ent_bytes[max_entries*TQO_LCAP], ent_len[max_entries], *n_entries
  * returns number of codes, or -1 on bad arguments / allocation failure.
  */
-long long tqo_lzw_encode(const uint8_t *S, long long n, long long group_bytes, int max_entries, int lmax,
-                         uint16_t *codes, uint32_t *group_ncodes, uint8_t *ent_bytes, uint8_t *ent_len,
-                         int *n_entries_out) {
-  if (max_entries < 256 || max_entries > 65536 || lmax < 1 || lmax > TQO_LCAP || group_bytes < 1) return -1;
+long long tqo_lzw_encode(const uint8_t *S, long long n, const uint32_t *seg_len, long long n_segs, int max_entries,
+                         int lmax, int n_init, uint16_t *codes, uint32_t *seg_ncodes, uint8_t *ent_bytes,
+                         uint8_t *ent_len, int *n_entries_out) {
+  if (max_entries < 256 || max_entries > 65536 || lmax < 1 || lmax > TQO_LCAP || n_segs < 0) return -1;
+  if (n_init != 0 && (n_init < 256 || n_init > max_entries)) return -1;
+  long long total = 0;
+  for (long long g = 0; g < n_segs; ++g) total += seg_len[g];
+  if (total != n) return -1;
   /* child[e*256 + b] = entry equal to (entry e followed by byte b), or -1 */
   int32_t *child = (int32_t *)malloc((size_t)max_entries * 256 * sizeof(int32_t));
   if (!child) return -1;
@@ -41,10 +48,19 @@ long long tqo_lzw_encode(const uint8_t *S, long long n, long long group_bytes, i
     ent_len[b] = 1;
     ent_bytes[(size_t)b * TQO_LCAP] = (uint8_t)b;
   }
+  /* carried-over entries: each is (an earlier entry) + one byte, because LZW only ever adds such strings */
+  for (int e = 256; e < n_init; ++e) {
+    int len = ent_len[e], par = ent_bytes[(size_t)e * TQO_LCAP];
+    if (len < 2 || len > lmax) { free(child); return -1; }
+    for (int k = 1; k < len - 1 && par >= 0; ++k) par = child[(size_t)par * 256 + ent_bytes[(size_t)e * TQO_LCAP + k]];
+    if (par < 0 || child[(size_t)par * 256 + ent_bytes[(size_t)e * TQO_LCAP + len - 1]] >= 0) { free(child); return -1; }
+    child[(size_t)par * 256 + ent_bytes[(size_t)e * TQO_LCAP + len - 1]] = e;
+    n_entries = e + 1;
+  }
   long long n_codes = 0;
-  long long g = 0;
-  for (long long gs = 0; gs < n; gs += group_bytes, ++g) {
-    long long ge = gs + group_bytes < n ? gs + group_bytes : n;
+  long long gs = 0;
+  for (long long g = 0; g < n_segs; ++g) {
+    long long ge = gs + seg_len[g];
     uint32_t emitted = 0;
     long long i = gs;
     while (i < ge) {
@@ -68,7 +84,8 @@ long long tqo_lzw_encode(const uint8_t *S, long long n, long long group_bytes, i
       }
       i += m;
     }
-    group_ncodes[g] = emitted;
+    seg_ncodes[g] = emitted;
+    gs = ge;
   }
   free(child);
   *n_entries_out = n_entries;
@@ -76,27 +93,35 @@ long long tqo_lzw_encode(const uint8_t *S, long long n, long long group_bytes, i
 }
 
 /*
- * Decodes groups [0, n_groups): group g uses codes[goff[g] .. goff[g+1]) and must produce exactly
- * min(group_bytes, n - g*group_bytes) bytes.  A code equal to pad_code produces nothing.
- * returns 0, or -(g+1) for the first group that is inconsistent (bad code, wrong length).
+ * Decodes segments [0, n_segs) from the interleaved layout: the segments come in units of 64 (segment g is lane
+ * g % 64 of unit g / 64); code k of lane l of unit u sits at codes[(uoff[u] + k / 4) * 256 + l * 4 + k % 4] and a
+ * lane's stream has (uoff[u+1] - uoff[u]) * 4 codes.  Segment g must produce exactly seg_len[g] bytes, written
+ * back to back to S_out.  A code equal to pad_code produces nothing and may only be followed by pad codes.
+ * returns 0, or -(g+1) for the first segment that is inconsistent (bad code, wrong length, code after a pad).
  */
-long long tqo_lzw_decode(const uint16_t *codes, const uint32_t *goff, long long n_groups, long long group_bytes,
-                         long long n, const uint8_t *ent_bytes, const uint8_t *ent_len, int n_entries, int pad_code,
-                         uint8_t *S_out) {
-  for (long long g = 0; g < n_groups; ++g) {
-    long long gs = g * group_bytes;
-    long long want = gs + group_bytes < n ? group_bytes : n - gs;
+long long tqo_lzw_decode(const uint16_t *codes, const uint32_t *uoff, const uint32_t *seg_len, long long n_segs,
+                         const uint8_t *ent_bytes, const uint8_t *ent_len, int n_entries, int pad_code, uint8_t *S_out) {
+  long long pos = 0;
+  for (long long g = 0; g < n_segs; ++g) {
+    long long u = g / 64, l = g % 64;
+    long long steps = ((long long)uoff[u + 1] - (long long)uoff[u]) * 4;
+    long long want = seg_len[g];
     long long c = 0;
-    for (uint32_t p = goff[g]; p < goff[g + 1]; ++p) {
-      int e = codes[p];
-      if (e == pad_code) continue;
-      if (e >= n_entries) return -(g + 1);
+    int seen_pad = 0;
+    for (long long k = 0; k < steps; ++k) {
+      int e = codes[((long long)uoff[u] + k / 4) * 256 + l * 4 + k % 4];
+      if (e == pad_code) {
+        seen_pad = 1;
+        continue;
+      }
+      if (seen_pad || e >= n_entries) return -(g + 1);
       int len = ent_len[e];
       if (c + len > want) return -(g + 1);
-      memcpy(S_out + gs + c, ent_bytes + (size_t)e * TQO_LCAP, (size_t)len);
+      memcpy(S_out + pos + c, ent_bytes + (size_t)e * TQO_LCAP, (size_t)len);
       c += len;
     }
     if (c != want) return -(g + 1);
+    pos += want;
   }
   return 0;
 }

@@ -7,7 +7,8 @@ library has not been built, loading it raises.
 from .binding import (  # noqa: F401
     TQ_MAX_BATCH,
     TQ_MAX_ENTRIES_DEVICE,
-    TQ_DEFAULT_MAX_ENTRIES,
+    TQ_MAX_LMAX,
+    TQ_DEFAULT_SEG_COLS,
     TqError,
     TqInfo,
     Matrix,

@@ -9,8 +9,9 @@ from typing import Optional
 import numpy as np
 
 TQ_MAX_BATCH = 16
-TQ_MAX_ENTRIES_DEVICE = 32704
-TQ_DEFAULT_MAX_ENTRIES = 32000
+TQ_MAX_ENTRIES_DEVICE = 30719
+TQ_MAX_LMAX = 2
+TQ_DEFAULT_SEG_COLS = 256
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB: Optional[ctypes.CDLL] = None
@@ -29,13 +30,14 @@ class TqError(RuntimeError):
 
 class TqEncodeOpts(ctypes.Structure):
     _fields_ = [("max_entries", ctypes.c_uint32), ("lmax", ctypes.c_uint32), ("n_threads", ctypes.c_uint32),
-                ("reserved", ctypes.c_uint32 * 5)]
+                ("seg_cols", ctypes.c_uint32), ("dict_from", ctypes.c_void_p), ("dict_from_bytes", ctypes.c_uint64)]
 
 
 class TqInfo(ctypes.Structure):
-    _fields_ = [("rows", ctypes.c_uint32), ("cols", ctypes.c_uint32), ("rows_pad", ctypes.c_uint32),
-                ("cols_pad", ctypes.c_uint32), ("n_entries", ctypes.c_uint32), ("lmax", ctypes.c_uint32),
-                ("n_groups", ctypes.c_uint64), ("n_codes", ctypes.c_uint64), ("dict_bytes", ctypes.c_uint64),
+    _fields_ = [("rows", ctypes.c_uint32), ("cols", ctypes.c_uint32), ("seg_cols", ctypes.c_uint32),
+                ("n_panels", ctypes.c_uint32), ("n_entries", ctypes.c_uint32), ("lmax", ctypes.c_uint32),
+                ("n_units", ctypes.c_uint64), ("n_codes", ctypes.c_uint64), ("n_real_codes", ctypes.c_uint64),
+                ("dict_bytes", ctypes.c_uint64),
                 ("offset_bytes", ctypes.c_uint64), ("code_bytes", ctypes.c_uint64), ("scale_bytes", ctypes.c_uint64),
                 ("compressed_bytes", ctypes.c_uint64)]
 
@@ -44,7 +46,7 @@ class TqInfo(ctypes.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libtq.so")
+    return os.environ.get("TQ_LIB_PATH") or os.path.join(_HERE, "libtq.so")
 
 
 def load() -> ctypes.CDLL:
@@ -93,9 +95,12 @@ def _check(rc: int):
         raise TqError(rc, tq_last_error_string())
 
 
-def _opts(max_entries: int, lmax: int, n_threads: int) -> TqEncodeOpts:
+def _opts(max_entries: int, lmax: int, n_threads: int, seg_cols: int, dict_from: Optional[bytes]) -> TqEncodeOpts:
     o = TqEncodeOpts()
-    o.max_entries, o.lmax, o.n_threads = max_entries, lmax, n_threads
+    o.max_entries, o.lmax, o.n_threads, o.seg_cols = max_entries, lmax, n_threads, seg_cols
+    if dict_from is not None:
+        o.dict_from = ctypes.cast(ctypes.c_char_p(dict_from), ctypes.c_void_p)   # the caller's bytes object outlives the call
+        o.dict_from_bytes = len(dict_from)
     return o
 
 
@@ -106,22 +111,25 @@ def _take_blob(ptr: ctypes.c_void_p, n: ctypes.c_size_t) -> bytes:
         load().tq_free_blob(ptr)
 
 
-def tq_encode(w: np.ndarray, max_entries: int = 0, lmax: int = 0, n_threads: int = 0) -> bytes:
-    """fp32 [rows, cols] host array -> container bytes."""
+def tq_encode(w: np.ndarray, max_entries: int = 0, lmax: int = 0, n_threads: int = 0, seg_cols: int = 0,
+              dict_from: Optional[bytes] = None) -> bytes:
+    """fp32 [rows, cols] host array -> container bytes.  dict_from: a container made earlier whose dictionary LZW
+    continues from (one dictionary over a sequence of matrices)."""
     w = np.ascontiguousarray(w, dtype=np.float32)
     assert w.ndim == 2
     ptr, n = ctypes.c_void_p(), ctypes.c_size_t()
-    o = _opts(max_entries, lmax, n_threads)
+    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from)
     _check(load().tq_encode(w.ctypes.data, w.shape[0], w.shape[1], ctypes.byref(o), ctypes.byref(ptr), ctypes.byref(n)))
     return _take_blob(ptr, n)
 
 
-def tq_encode_quantized(q: np.ndarray, scales: np.ndarray, max_entries: int = 0, lmax: int = 0, n_threads: int = 0) -> bytes:
+def tq_encode_quantized(q: np.ndarray, scales: np.ndarray, max_entries: int = 0, lmax: int = 0, n_threads: int = 0,
+                        seg_cols: int = 0, dict_from: Optional[bytes] = None) -> bytes:
     q = np.ascontiguousarray(q, dtype=np.int8)
     scales = np.ascontiguousarray(scales, dtype=np.float32)
     assert q.ndim == 2 and scales.shape == (q.shape[0],)
     ptr, n = ctypes.c_void_p(), ctypes.c_size_t()
-    o = _opts(max_entries, lmax, n_threads)
+    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from)
     _check(load().tq_encode_quantized(q.ctypes.data, scales.ctypes.data, q.shape[0], q.shape[1], ctypes.byref(o),
                                       ctypes.byref(ptr), ctypes.byref(n)))
     return _take_blob(ptr, n)

@@ -19,7 +19,7 @@ static int bad(const std::string& why) {
   return TQ_E_BAD_BLOB;
 }
 
-int validate_blob(const void* blob, size_t bytes, Header* hdr_out, unsigned n_threads) {
+int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* facts_out, unsigned n_threads) {
   if (!blob) {
     set_error("null container pointer");
     return TQ_E_INVALID_ARG;
@@ -29,23 +29,24 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, unsigned n_th
   std::memcpy(&h, blob, sizeof h);
   if (std::memcmp(h.magic, kMagic, 8) != 0) return bad("magic");
   if (h.version != kVersion || h.header_bytes != kHeaderBytes) return bad("version");
-  if (h.tile_rows != kTileRows || h.mt_cols != kMtCols || h.group_cols != kGroupCols || h.group_bytes != kGroupBytes ||
-      h.code_align != kCodeAlign)
-    return bad("tiling constants");
+  if (h.unit_rows != kUnitRows || h.unit_panels != kUnitPanels || h.chunk_codes != kChunkCodes) return bad("layout constants");
+  if (h.seg_cols < kMinSegCols || h.seg_cols > kMaxSegCols || h.seg_cols % 16) return bad("segment width");
   if (h.rows == 0 || h.cols == 0) return bad("empty shape");
-  if (h.rows_pad != round_up(h.rows, kTileRows) || h.cols_pad != round_up(h.cols, kGroupCols)) return bad("padded shape");
-  if (h.n_entries < 256 || h.n_entries > TQ_MAX_ENTRIES_DEVICE) return bad("entry count");
-  if (h.lmax < 1 || h.lmax > 3) return bad("lmax");
+  if (h.n_bands != (h.rows + kUnitRows - 1) / kUnitRows || h.n_panels != (h.cols + h.seg_cols - 1) / h.seg_cols ||
+      h.n_quads != (h.n_panels + kUnitPanels - 1) / kUnitPanels)
+    return bad("band / panel / quad counts");
+  if (h.lmax < 1 || h.lmax > TQ_MAX_LMAX) return bad("lmax");
+  if (h.n_entries < 256 || h.n_entries > TQ_MAX_ENTRIES_DEVICE || h.n_entries > h.max_entries) return bad("entry count");
   if (h.pad_code != h.n_entries) return bad("pad code");
-  const uint64_t n_groups = (uint64_t)(h.rows_pad / kTileRows) * (h.cols_pad / kGroupCols);
-  if (h.n_groups != n_groups) return bad("group count");
+  const uint64_t n_units = (uint64_t)h.n_bands * h.n_quads;
+  if (h.n_units != n_units) return bad("unit count");
   if (h.total_bytes != bytes) return bad("total size");
-  if (h.n_codes >= 0xFFFFFFFFull) return bad("code count");
-  if (h.dict_bytes != (uint64_t)(h.n_entries + 1) * 4 || h.goff_bytes != (n_groups + 1) * 4 || h.code_bytes != h.n_codes * 2 ||
-      h.scale_bytes != (uint64_t)h.rows_pad * 4)
+  if (h.n_chunks >= 0xFFFFFFFFull / kChunkWords) return bad("chunk count");
+  if (h.dict_bytes != (uint64_t)(h.n_entries + 1) * 4 || h.uoff_bytes != (n_units + 1) * 4 ||
+      h.code_bytes != h.n_chunks * kChunkWords * 2 || h.scale_bytes != (uint64_t)h.n_bands * kUnitRows * 4)
     return bad("section sizes");
-  const uint64_t offs[4] = {h.off_dict, h.off_goff, h.off_codes, h.off_scales};
-  const uint64_t lens[4] = {h.dict_bytes, h.goff_bytes, h.code_bytes, h.scale_bytes};
+  const uint64_t offs[4] = {h.off_dict, h.off_uoff, h.off_codes, h.off_scales};
+  const uint64_t lens[4] = {h.dict_bytes, h.uoff_bytes, h.code_bytes, h.scale_bytes};
   uint64_t prev_end = kHeaderBytes;
   for (int i = 0; i < 4; ++i) {
     if (offs[i] % kSectionAlign || offs[i] < prev_end || offs[i] > bytes || lens[i] > bytes - offs[i]) return bad("section bounds");
@@ -53,7 +54,7 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, unsigned n_th
   }
   const uint8_t* base = (const uint8_t*)blob;
   const uint32_t* slot = (const uint32_t*)(base + h.off_dict);
-  const uint32_t* goff = (const uint32_t*)(base + h.off_goff);
+  const uint32_t* uoff = (const uint32_t*)(base + h.off_uoff);
   const uint16_t* codes = (const uint16_t*)(base + h.off_codes);
 
   // Dictionary: codes 0..255 are the single bytes; every entry has length 1..lmax and zero bytes past its length;
@@ -67,46 +68,61 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, unsigned n_th
   if (slot[h.n_entries] != 0) return bad("pad entry");
 
   // Offsets.
-  if (goff[0] != 0 || goff[n_groups] != h.n_codes) return bad("first/last group offset");
-  for (uint64_t g = 0; g < n_groups; ++g)
-    if (goff[g + 1] < goff[g] || goff[g] % kCodeAlign || goff[g + 1] > h.n_codes) return bad("group offsets");
-  if (h.n_codes % kCodeAlign) return bad("code count alignment");
+  if (uoff[0] != 0 || uoff[n_units] != h.n_chunks) return bad("first/last unit offset");
+  for (uint64_t u = 0; u < n_units; ++u)
+    if (uoff[u + 1] <= uoff[u] || uoff[u + 1] > h.n_chunks) return bad("unit offsets");
 
-  // Codes: in range, pads only as a tail of fewer than kCodeAlign codes, runs sum to the group size.
-  std::atomic<uint64_t> first_bad(UINT64_MAX);
+  // Codes: in range, pads only at the end of a lane stream, every lane stream's runs sum to its segment's length.
+  std::atomic<uint64_t> first_bad(UINT64_MAX), real_codes(0);
+  std::atomic<uint32_t> overrun(0);
   n_threads = std::max(1u, std::min(n_threads, 16u));
-  n_threads = (unsigned)std::min<uint64_t>(n_threads, n_groups);
-  auto work = [&](uint64_t gb, uint64_t ge) {
-    for (uint64_t g = gb; g < ge && first_bad.load(std::memory_order_relaxed) == UINT64_MAX; ++g) {
-      uint32_t b = goff[g], e = goff[g + 1];
-      uint32_t sum = 0, pads = 0;
+  n_threads = (unsigned)std::min<uint64_t>(n_threads, n_units);
+  auto work = [&](uint64_t ub, uint64_t ue) {
+    uint64_t real = 0;
+    uint32_t over = 0;
+    for (uint64_t u = ub; u < ue && first_bad.load(std::memory_order_relaxed) == UINT64_MAX; ++u) {
+      const uint32_t band = (uint32_t)(u / h.n_quads), quad = (uint32_t)(u % h.n_quads);
+      const uint32_t steps = (uoff[u + 1] - uoff[u]) * kChunkCodes;
+      const uint16_t* cb = codes + (uint64_t)uoff[u] * kChunkWords;
       bool ok = true;
-      for (uint32_t p = b; p < e; ++p) {
-        uint32_t c = codes[p];
-        if (c > h.n_entries) { ok = false; break; }
-        if (c == h.n_entries) { ++pads; continue; }
-        if (pads) { ok = false; break; }   // a real code after a pad
-        sum += slot[c] >> 27;   // bits / 8
+      for (uint32_t l = 0; l < 64 && ok; ++l) {
+        const uint32_t want = segment_len(h, band, quad, l);
+        uint32_t sum = 0, pads = 0;
+        for (uint32_t k = 0; k < steps; ++k) {
+          const uint32_t c = cb[(uint64_t)(k / kChunkCodes) * kChunkWords + l * kChunkCodes + k % kChunkCodes];
+          if (c > h.n_entries) { ok = false; break; }
+          if (c == h.n_entries) { ++pads; continue; }
+          if (pads) { ok = false; break; }   // a real code after a pad
+          sum += slot[c] >> 27;   // bits / 8
+        }
+        if (sum != want) ok = false;
+        real += steps - pads;
+        over = std::max(over, want + 2 * pads);
       }
-      if (!ok || sum != kGroupBytes || pads >= kCodeAlign) {
+      if (!ok) {
         uint64_t cur = first_bad.load();
-        while (g < cur && !first_bad.compare_exchange_weak(cur, g)) {}
+        while (u < cur && !first_bad.compare_exchange_weak(cur, u)) {}
       }
     }
+    real_codes += real;
+    uint32_t cur = overrun.load();
+    while (over > cur && !overrun.compare_exchange_weak(cur, over)) {}
   };
   if (n_threads <= 1) {
-    work(0, n_groups);
+    work(0, n_units);
   } else {
     std::vector<std::thread> th;
-    uint64_t per = (n_groups + n_threads - 1) / n_threads;
+    uint64_t per = (n_units + n_threads - 1) / n_threads;
     for (unsigned t = 0; t < n_threads; ++t) {
-      uint64_t b = std::min(n_groups, t * per), e = std::min(n_groups, b + per);
+      uint64_t b = std::min(n_units, t * per), e = std::min(n_units, b + per);
       if (b < e) th.emplace_back(work, b, e);
     }
     for (auto& x : th) x.join();
   }
-  if (first_bad.load() != UINT64_MAX) return bad("code stream of group " + std::to_string(first_bad.load()));
+  if (first_bad.load() != UINT64_MAX) return bad("code stream of unit " + std::to_string(first_bad.load()));
+  if (real_codes.load() != h.n_real_codes) return bad("count of non-padding codes");
   if (hdr_out) *hdr_out = h;
+  if (facts_out) facts_out->max_lane_reach = overrun.load();
   return TQ_OK;
 }
 
@@ -114,17 +130,18 @@ void fill_info(const Header& h, tq_info* o) {
   std::memset(o, 0, sizeof *o);
   o->rows = h.rows;
   o->cols = h.cols;
-  o->rows_pad = h.rows_pad;
-  o->cols_pad = h.cols_pad;
+  o->seg_cols = h.seg_cols;
+  o->n_panels = h.n_panels;
   o->n_entries = h.n_entries;
   o->lmax = h.lmax;
-  o->n_groups = h.n_groups;
-  o->n_codes = h.n_codes;
+  o->n_units = h.n_units;
+  o->n_codes = h.n_chunks * kChunkWords;
+  o->n_real_codes = h.n_real_codes;
   o->dict_bytes = h.dict_bytes;
-  o->offset_bytes = h.goff_bytes;
+  o->offset_bytes = h.uoff_bytes;
   o->code_bytes = h.code_bytes;
   o->scale_bytes = h.scale_bytes;
-  o->compressed_bytes = h.dict_bytes + h.goff_bytes + h.code_bytes + h.scale_bytes;
+  o->compressed_bytes = h.dict_bytes + h.uoff_bytes + h.code_bytes + h.scale_bytes;
 }
 
 }  // namespace tq
@@ -134,7 +151,7 @@ extern "C" const char* tq_last_error_string(void) { return tq::g_err.c_str(); }
 extern "C" int tq_validate_blob(const void* blob, size_t blob_bytes, tq_info* info) {
   tq::Header h;
   unsigned hw = std::thread::hardware_concurrency();
-  int rc = tq::validate_blob(blob, blob_bytes, &h, hw ? hw : 1);
+  int rc = tq::validate_blob(blob, blob_bytes, &h, nullptr, hw ? hw : 1);
   if (rc == TQ_OK && info) tq::fill_info(h, info);
   return rc;
 }

@@ -1,5 +1,19 @@
-// Container layout shared by the host encoder, the validator and the device code of libtq.
+// Container layout (version 2) shared by the host encoder, the validator and the device code of libtq.
 // All integers little-endian; every section starts on a 256-byte boundary.
+//
+// The quantized matrix Q (int8, rows x cols, row-major) is cut into *segments*: seg_cols consecutive columns of one
+// row (the last panel of a row may be shorter).  A *unit* is the 64 segments one wavefront decodes in lockstep:
+// 16 consecutive rows (a band) x 4 consecutive column panels (a quad); lane l of the wavefront owns row
+// 16*band + (l & 15), panel 4*quad + (l >> 4).  Units are ordered band-major, quad-minor.  Segments past the matrix
+// edge are empty.  The LZW parse (paper Background "Compression") visits the segments in (unit, lane) order with one
+// dictionary per matrix; a run never crosses a segment boundary, so every lane's code stream can be decoded
+// independently of the others (per-tile stream offsets).
+//
+// Code section: for unit u the codes of its 64 lane streams are interleaved in chunks of 4 codes per lane:
+//   code k of lane l of unit u  ->  codes[(uoff[u] + k / 4) * 256 + l * 4 + k % 4]
+// Every lane stream of a unit is padded with pad codes (index n_entries, an empty entry) to the unit's length,
+// which is the longest lane stream rounded up to a multiple of 4.  One chunk is 512 contiguous bytes: a wavefront
+// reads it with one coalesced 8-byte load per lane.
 #pragma once
 #include <cstddef>
 #include <cstdint>
@@ -9,42 +23,58 @@ struct tq_info;
 
 namespace tq {
 
-constexpr uint32_t kTileRows = 16;      // rows of a micro-tile (= M of the 16x16x32 MFMA)
-constexpr uint32_t kMtCols = 8;         // columns of a micro-tile (= the 8 k-values one lane feeds the MFMA)
-constexpr uint32_t kGroupCols = 256;    // columns of a restart group: 32 micro-tiles, 8 MFMA steps
-constexpr uint32_t kGroupBytes = kTileRows * kGroupCols;
-constexpr uint32_t kCodeAlign = 8;      // codes per 16-byte lane load; each group's run is padded to this
+constexpr uint32_t kUnitRows = 16;      // rows of a unit (lanes l & 15)
+constexpr uint32_t kUnitPanels = 4;     // column panels of a unit (lanes l >> 4)
+constexpr uint32_t kChunkCodes = 4;     // codes per lane and chunk (one 8-byte load)
+constexpr uint32_t kChunkWords = 64 * kChunkCodes;   // 16-bit codes per chunk
+constexpr uint32_t kMinSegCols = 16, kMaxSegCols = 1024, kDefaultSegCols = 256;
 constexpr uint32_t kSectionAlign = 256;
 constexpr uint32_t kHeaderBytes = 256;
-constexpr uint32_t kVersion = 1;
-constexpr char kMagic[8] = {'T', 'Q', 'M', 'O', 'E', 'v', '1', '\0'};
+constexpr uint32_t kVersion = 2;
+constexpr char kMagic[8] = {'T', 'Q', 'M', 'O', 'E', 'v', '2', '\0'};
 
 #pragma pack(push, 1)
 struct Header {
   char magic[8];
   uint32_t version, header_bytes;
   uint32_t rows, cols;
-  uint32_t rows_pad, cols_pad;
-  uint32_t tile_rows, mt_cols, group_cols, group_bytes;
+  uint32_t seg_cols;                      // columns per segment (multiple of 16)
+  uint32_t unit_rows, unit_panels, chunk_codes;
+  uint32_t n_bands, n_panels, n_quads;    // ceil(rows / 16), ceil(cols / seg_cols), ceil(n_panels / 4)
   uint32_t n_entries, lmax, max_entries, pad_code;
-  uint64_t n_groups, n_codes;
-  uint64_t off_dict, dict_bytes;      // uint32 slot[n_entries + 1]: run bytes in bits 0..23, run length in BITS (8/16/24) in bits 24..31
-  uint64_t off_goff, goff_bytes;      // uint32 goff[n_groups + 1], in codes
-  uint64_t off_codes, code_bytes;     // uint16 codes[n_codes]
-  uint64_t off_scales, scale_bytes;   // float scale[rows_pad]
+  uint32_t reserved0;
+  uint64_t n_units, n_chunks;             // n_bands * n_quads; total chunks of the code section
+  uint64_t n_real_codes;                  // codes that are not padding
+  uint64_t off_dict, dict_bytes;          // uint32 slot[n_entries + 1]: run bytes in bits 0..23, run length in BITS (8/16/24) in bits 24..31
+  uint64_t off_uoff, uoff_bytes;          // uint32 uoff[n_units + 1], in chunks
+  uint64_t off_codes, code_bytes;         // uint16 codes[n_chunks * 256]
+  uint64_t off_scales, scale_bytes;       // float scale[n_bands * 16]
   uint64_t total_bytes;
-  uint32_t code_align;
-  uint8_t zero[kHeaderBytes - 156];
+  uint8_t zero[kHeaderBytes - 168];
 };
 #pragma pack(pop)
 static_assert(sizeof(Header) == kHeaderBytes, "header size");
 
 inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
+// Length in bytes of the segment lane `lane` of unit (band, quad) owns.
+inline uint32_t segment_len(const Header& h, uint32_t band, uint32_t quad, uint32_t lane) {
+  const uint32_t row = band * kUnitRows + (lane & 15), panel = quad * kUnitPanels + (lane >> 4);
+  if (row >= h.rows || panel >= h.n_panels) return 0;
+  const uint32_t c0 = panel * h.seg_cols;
+  return c0 + h.seg_cols <= h.cols ? h.seg_cols : h.cols - c0;
+}
+
 void set_error(const std::string& msg);   // thread-local last-error text
 
+// What validation learns about a container beyond the header.
+struct BlobFacts {
+  uint32_t max_lane_reach;   // largest (segment length + 2 * pad codes) of any lane stream: how many columns past the start
+                             // of its segment a lane's activation index can get when every pad code advances it by two
+};
+
 // Host-side structural validation; fills *hdr_out with a copy of the header on success.
-int validate_blob(const void* blob, size_t bytes, Header* hdr_out, unsigned n_threads);
+int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* facts_out, unsigned n_threads);
 void fill_info(const Header& h, ::tq_info* out);
 
 }  // namespace tq

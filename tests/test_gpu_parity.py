@@ -57,25 +57,27 @@ def check_outputs(y, ref, tol=1e-3):
 
 
 CASES = [
-    # rows, cols, max_entries, lmax, dist
-    (64, 512, 32000, 3, "normal"),          # several groups, dictionary not full
-    (16, 8, 256, 3, "normal"),              # one micro-tile, singles only
-    (33, 300, 1000, 3, "normal"),           # ragged rows and columns
-    (17, 257, 300, 2, "student_t4"),        # ragged, tiny dictionary, lmax 2
-    (48, 256, 300, 1, "normal"),            # lmax 1: code == byte
-    (200, 1024, 4096, 3, "student_t4"),
-    (512, 2048, 32000, 3, "normal"),        # dictionary full and frozen; many bands per workgroup
-    (1040, 768, 32704, 3, "student_t4"),    # largest dictionary the device accepts; more bands than one pass
-    (2048, 2048, 32000, 3, "normal"),       # config 1
+    # rows, cols, max_entries, lmax, seg_cols, dist
+    (64, 512, 30719, 2, 64, "normal"),          # several units, dictionary not full
+    (16, 8, 256, 2, 16, "normal"),              # one short segment per row, singles only
+    (33, 300, 1000, 2, 32, "normal"),           # ragged rows and columns, last quad partly empty
+    (17, 257, 300, 2, 256, "student_t4"),       # ragged, tiny dictionary, one-column last panel
+    (48, 256, 300, 1, 48, "normal"),            # lmax 1: code == byte; segment width not a multiple of 32
+    (200, 1024, 4096, 2, 128, "student_t4"),
+    (512, 2048, 30719, 2, 256, "normal"),       # dictionary full and frozen; several bands per workgroup
+    (1040, 768, 30719, 2, 192, "student_t4"),   # one quad per band
+    (300, 3000, 30719, 2, 1024, "normal"),      # widest segments
+    (4128, 1024, 30719, 2, 64, "normal"),       # more bands than CUs
+    (2048, 2048, 30719, 2, 256, "normal"),      # config 1
 ]
 
 
-@pytest.mark.parametrize("rows,cols,max_entries,lmax,dist", CASES)
-def test_decompress_bit_exact_and_matvec(dev, rows, cols, max_entries, lmax, dist):
+@pytest.mark.parametrize("rows,cols,max_entries,lmax,seg_cols,dist", CASES)
+def test_decompress_bit_exact_and_matvec(dev, rows, cols, max_entries, lmax, seg_cols, dist):
     spec = small_case(rows, cols, seed=rows * 7 + cols, dist=dist)
     W = make_weights(spec)
     Qo, so = O.quantize_rows(W)
-    blob = tq.tq_encode(W, max_entries=max_entries, lmax=lmax)
+    blob = tq.tq_encode(W, max_entries=max_entries, lmax=lmax, seg_cols=seg_cols)
     m = tq.Matrix(blob)
     try:
         Q = gpu_decompress(m, dev)
@@ -93,7 +95,7 @@ def test_decompress_bit_exact_and_matvec(dev, rows, cols, max_entries, lmax, dis
 def test_oracle_made_container_decodes_on_gpu(dev):
     spec = small_case(96, 768, seed=5)
     W = make_weights(spec)
-    enc = O.encode_matrix(W, max_entries=3000, lmax=3)
+    enc = O.encode_matrix(W, max_entries=3000, seg_cols=64)
     m = tq.Matrix(O.build_blob(enc))
     try:
         assert np.array_equal(gpu_decompress(m, dev), enc.Q)
@@ -106,9 +108,9 @@ def test_unit_vectors_probe_every_column_position(dev):
     spec = small_case(32, 520, seed=11)
     W = make_weights(spec)
     Qo, so = O.quantize_rows(W)
-    m = tq.Matrix(tq.tq_encode(W, max_entries=2000))
+    m = tq.Matrix(tq.tq_encode(W, max_entries=2000, seg_cols=64))
     try:
-        cols = [0, 1, 7, 8, 255, 256, 300, 511, 512, 519]
+        cols = [0, 1, 7, 8, 63, 64, 65, 127, 128, 255, 256, 300, 511, 512, 519]
         for c0 in range(0, len(cols), 16):
             js = cols[c0:c0 + 16]
             x = np.zeros((len(js), 520), np.float32)
@@ -181,49 +183,44 @@ def test_repeated_calls_are_deterministic_and_overwrite(dev):
         m.close()
 
 
-def test_multi_launch_matches_single_launches_and_oracle(dev):
-    """q/k/v-like trio of different heights in one launch: bit-identical to three tq_matvec calls."""
-    shapes = [(192, 768), (64, 768), (64, 768), (48, 768)]
-    for batch in (1, 8):
-        mats, xs, ys, refs, singles = [], [], [], [], []
-        for k, (r, c) in enumerate(shapes):
-            spec = small_case(r, c, seed=100 + k)
-            W = make_weights(spec)
-            Qo, so = O.quantize_rows(W)
-            m = tq.Matrix(tq.tq_encode(W, max_entries=3000, lmax=3))
-            bits, x = make_activations(spec, batch)
-            xd = torch.from_numpy(bits.view(np.int16).copy()).to(dev)
-            mats.append(m)
-            xs.append(xd)
-            ys.append(torch.full((batch, r), float("nan"), dtype=torch.float32, device=dev))
-            refs.append(O.gemv_f64(Qo, so, x))
-            singles.append(gpu_matvec(m, bits, dev))
-        tq.tq_matvec_multi([m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch, _stream())
-        torch.cuda.synchronize()
-        for y, ref, one in zip(ys, refs, singles):
-            got = y.cpu().numpy()
-            assert np.array_equal(got, one)
-            check_outputs(got, ref)
-        for m in mats:
-            m.close()
-
-
-def test_multi_launch_falls_back_when_members_differ(dev):
-    specs = [small_case(64, 512, seed=200), small_case(32, 300, seed=201)]     # second one: cols % 8 != 0
-    mats = [tq.Matrix(tq.tq_encode(make_weights(s), max_entries=2000, lmax=l)) for s, l in zip(specs, (3, 2))]
-    xs, ys, refs = [], [], []
-    for s, m in zip(specs, mats):
-        bits, x = make_activations(s, 2)
-        xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
-        ys.append(torch.zeros((2, s.rows), dtype=torch.float32, device=dev))
-        Qo, so = O.quantize_rows(make_weights(s))
+def _multi_case(dev, shapes, batch, shared_dictionary, max_entries=3000):
+    mats, xs, ys, refs, singles = [], [], [], [], []
+    prev = None
+    for k, (r, c, seg) in enumerate(shapes):
+        spec = small_case(r, c, seed=100 + k)
+        W = make_weights(spec)
+        Qo, so = O.quantize_rows(W)
+        blob = tq.tq_encode(W, max_entries=max_entries, seg_cols=seg, dict_from=prev if shared_dictionary else None)
+        prev = blob
+        m = tq.Matrix(blob)
+        bits, x = make_activations(spec, batch)
+        xd = torch.from_numpy(bits.view(np.int16).copy()).to(dev)
+        mats.append(m)
+        xs.append(xd)
+        ys.append(torch.full((batch, r), float("nan"), dtype=torch.float32, device=dev))
         refs.append(O.gemv_f64(Qo, so, x))
-    tq.tq_matvec_multi([m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], 2, _stream())
+        singles.append(gpu_matvec(m, bits, dev))
+    tq.tq_matvec_multi([m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch, _stream())
     torch.cuda.synchronize()
-    for y, ref in zip(ys, refs):
-        check_outputs(y.cpu().numpy(), ref)
+    for y, ref, one in zip(ys, refs, singles):
+        got = y.cpu().numpy()
+        check_outputs(got, ref)
+        assert np.abs(got - one).max() <= 1e-5 * np.abs(ref).max()   # another split of the rows over the wavefronts
     for m in mats:
         m.close()
+
+
+@pytest.mark.parametrize("shared_dictionary", [False, True])
+def test_multi_launch_matches_single_launches_and_oracle(dev, shared_dictionary):
+    """q/k/v/o/gate/down-like set of different shapes in one launch."""
+    shapes = [(192, 768, 64), (64, 768, 64), (64, 768, 192), (48, 768, 64), (512, 768, 192), (192, 2048, 256)]
+    for batch in (1, 8):
+        _multi_case(dev, shapes, batch, shared_dictionary)
+
+
+def test_multi_launch_of_more_matrices_than_one_kernel_takes(dev):
+    shapes = [(16 * (1 + k % 5), 256 + 64 * (k % 3), 64) for k in range(70)]
+    _multi_case(dev, shapes, 2, True, max_entries=600)
 
 
 def test_argument_errors(dev):

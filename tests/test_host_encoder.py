@@ -26,36 +26,56 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(tq.binding.EXPORTS)
 
 
-@pytest.mark.parametrize("shape,max_entries,lmax,dist", [
-    ((64, 512), 32000, 3, "normal"),
-    ((33, 300), 1000, 3, "normal"),
-    ((16, 8), 256, 3, "normal"),
-    ((200, 1024), 4096, 2, "student_t4"),
-    ((512, 2048), 32000, 3, "student_t4"),
-    ((48, 256), 300, 1, "normal"),
+@pytest.mark.parametrize("shape,max_entries,lmax,seg_cols,dist", [
+    ((64, 512), 30719, 2, 256, "normal"),
+    ((33, 300), 1000, 2, 64, "normal"),
+    ((16, 8), 256, 2, 16, "normal"),
+    ((200, 1024), 4096, 2, 128, "student_t4"),
+    ((512, 2048), 30719, 2, 256, "student_t4"),
+    ((48, 256), 300, 1, 256, "normal"),
+    ((100, 3000), 30719, 2, 1024, "normal"),
 ])
-def test_encoder_container_is_byte_identical_to_the_oracles(shape, max_entries, lmax, dist):
+def test_encoder_container_is_byte_identical_to_the_oracles(shape, max_entries, lmax, seg_cols, dist):
     W = make_weights(small_case(shape[0], shape[1], seed=7, dist=dist))
-    blob = tq.tq_encode(W, max_entries=max_entries, lmax=lmax)
-    ref = O.build_blob(O.encode_matrix(W, max_entries=max_entries, lmax=lmax))
+    blob = tq.tq_encode(W, max_entries=max_entries, lmax=lmax, seg_cols=seg_cols)
+    ref = O.build_blob(O.encode_matrix(W, max_entries=max_entries, lmax=lmax, seg_cols=seg_cols))
     assert blob == ref
     info = tq.tq_validate_blob(blob)
     p = O.parse_blob(blob)
     assert info["rows"] == shape[0] and info["cols"] == shape[1] and info["n_codes"] == p["n_codes"]
+    assert info["n_real_codes"] == p["n_real_codes"] and info["seg_cols"] == seg_cols
     assert info["compressed_bytes"] == p["compressed_bytes"]
     Q, s = O.decode_blob(blob)
     Qo, so = O.quantize_rows(W)
     assert np.array_equal(Q, Qo) and np.array_equal(s, so)
 
 
-@pytest.mark.parametrize("dist", ["normal", "student_t4"])
-def test_auto_lmax_keeps_the_smaller_container(dist):
-    W = make_weights(small_case(512, 2048, seed=21, dist=dist))
-    auto = tq.tq_encode(W)                       # lmax = 0: auto
-    cands = {l: O.build_blob(O.encode_matrix(W, max_entries=tq.TQ_DEFAULT_MAX_ENTRIES, lmax=l)) for l in (2, 3)}
-    want = cands[2] if len(cands[2]) < len(cands[3]) else cands[3]
-    assert auto == want
-    assert tq.tq_validate_blob(auto)["lmax"] == (2 if dist == "normal" else 3)
+def test_defaults_are_the_documented_ones():
+    W = make_weights(small_case(64, 512, seed=21))
+    assert tq.tq_encode(W) == O.build_blob(O.encode_matrix(W, max_entries=tq.TQ_MAX_ENTRIES_DEVICE, lmax=2, seg_cols=256))
+
+
+def test_dictionary_carried_over_a_sequence_of_matrices():
+    """dict_from: LZW goes on from the earlier container's dictionary; once it is full the later containers hold
+    byte-identical dictionary sections."""
+    Ws = [make_weights(small_case(r, c, seed=30 + k)) for k, (r, c) in enumerate([(512, 2048), (256, 3072), (64, 768)])]
+    blobs, encs = [], []
+    for k, W in enumerate(Ws):
+        blobs.append(tq.tq_encode(W, dict_from=blobs[-1] if blobs else None, seg_cols=192 if k else 256))
+        encs.append(O.encode_matrix(W, seg_cols=192 if k else 256, carry=encs[-1].dictionary if encs else None))
+        assert blobs[-1] == O.build_blob(encs[-1])
+    ps = [O.parse_blob(b) for b in blobs]
+    assert ps[0]["n_entries"] == tq.TQ_MAX_ENTRIES_DEVICE          # the first matrix fills the dictionary
+    assert np.array_equal(ps[0]["slots"], ps[1]["slots"]) and np.array_equal(ps[1]["slots"], ps[2]["slots"])
+    for W, b in zip(Ws, blobs):
+        assert np.array_equal(O.decode_blob(b)[0], O.quantize_rows(W)[0])
+    # a small dictionary keeps growing over the sequence
+    small = [tq.tq_encode(Ws[2][:2, :32], max_entries=400, seg_cols=16)]
+    small.append(tq.tq_encode(Ws[2][16:32, :64], max_entries=400, seg_cols=16, dict_from=small[0]))
+    n0, n1 = (O.parse_blob(b)["n_entries"] for b in small)
+    assert 256 < n0 < n1 <= 400
+    with pytest.raises(tq.TqError):      # the earlier dictionary does not fit the new cap
+        tq.tq_encode(Ws[2], max_entries=300, dict_from=small[1])
 
 
 def test_encoder_is_deterministic_across_thread_counts():
@@ -71,8 +91,8 @@ def test_encode_quantized_accepts_any_byte_and_matches_oracle():
     Q[3, :] = -128
     Q[5, :] = 0
     s = rng.random(40).astype(np.float32)
-    blob = tq.tq_encode_quantized(Q, s, max_entries=5000, lmax=3)
-    assert blob == O.build_blob(O.encode_quantized(Q, s, max_entries=5000, lmax=3))
+    blob = tq.tq_encode_quantized(Q, s, max_entries=5000, seg_cols=64)
+    assert blob == O.build_blob(O.encode_quantized(Q, s, max_entries=5000, seg_cols=64))
     Qd, sd = O.decode_blob(blob)
     assert np.array_equal(Qd, Q) and np.array_equal(sd, s)
 
@@ -85,7 +105,8 @@ def test_quantizer_ties_match_oracle():
 
 def test_encode_argument_errors():
     W = np.zeros((4, 4), np.float32)
-    for kw in (dict(max_entries=100), dict(max_entries=tq.TQ_MAX_ENTRIES_DEVICE + 1), dict(lmax=4)):
+    for kw in (dict(max_entries=100), dict(max_entries=tq.TQ_MAX_ENTRIES_DEVICE + 1), dict(lmax=3),
+               dict(seg_cols=24), dict(seg_cols=2048)):
         with pytest.raises(tq.TqError) as ei:
             tq.tq_encode(W, **kw)
         assert ei.value.code == -1
@@ -99,27 +120,31 @@ def _mutate(blob: bytes, offset: int, fmt: str, value) -> bytes:
 
 def test_validation_rejects_malformed_containers():
     W = make_weights(small_case(64, 512, seed=3))
-    blob = tq.tq_encode(W, max_entries=2000)
+    blob = tq.tq_encode(W, max_entries=2000, seg_cols=64)
     p = O.parse_blob(blob)
-    (o_d, _, o_g, _, o_c, _) = struct.unpack_from("<QQQQQQ", blob, 80)
+    (o_d, _, o_u, _, o_c, _) = struct.unpack_from("<QQQQQQ", blob, 96)
     assert tq.tq_validate_blob(blob)["n_entries"] == p["n_entries"]
+    assert o_d == 256 and np.array_equal(np.frombuffer(blob, np.uint32, 3, o_u), p["uoff"][:3])
+    last = int(np.flatnonzero(p["stream"][:256].reshape(64, 4)[0] != p["pad_code"]).max())   # lane 0, first chunk
     bad = {
         "magic": _mutate(blob, 0, "<B", 0x55),
         "truncated": blob[:-256],
         "rows": _mutate(blob, 16, "<I", 65),
+        "segment width": _mutate(blob, 24, "<I", 48),
         "code out of range": _mutate(blob, o_c, "<H", p["n_entries"] + 1),
-        "group length": _mutate(blob, o_c, "<H", 256 if p["stream"][0] < 256 else 0),
-        "offset not monotone": _mutate(blob, o_g + 4, "<I", 0xFFFFFFF0),
-        "offset misaligned": _mutate(blob, o_g + 4, "<I", int(p["goff"][1]) + 1),
-        "entry length": _mutate(blob, o_d + 4 * 300, "<I", (32 << 24) | 0x010203),
+        "segment length": _mutate(blob, o_c, "<H", 256 if p["stream"][0] < 256 else 0),
+        "offset not monotone": _mutate(blob, o_u + 4, "<I", 0xFFFFFFF0),
+        "offset shifted": _mutate(blob, o_u + 4, "<I", int(p["uoff"][1]) + 1),
+        "entry length": _mutate(blob, o_d + 4 * 300, "<I", (24 << 24) | 0x010203),
         "entry length not whole bytes": _mutate(blob, o_d + 4 * 300, "<I", (12 << 24) | 0x0102),
+        "entry bytes past its length": _mutate(blob, o_d + 4 * 7, "<I", (8 << 24) | 0x0107),
         "single byte entry": _mutate(blob, o_d + 4 * 7, "<I", (8 << 24) | 8),
         "pad entry": _mutate(blob, o_d + 4 * p["n_entries"], "<I", 8 << 24),
+        "count of real codes": _mutate(blob, 88, "<Q", p["n_real_codes"] + 1),
     }
-    # a pad code in the middle of a group (before real codes)
-    mid = bytearray(blob)
-    struct.pack_into("<H", mid, o_c + 2, p["pad_code"])
-    bad["pad inside group"] = bytes(mid)
+    # a pad code in the middle of a lane stream (before real codes)
+    assert last >= 1
+    bad["pad inside a lane stream"] = _mutate(blob, o_c, "<H", p["pad_code"])
     for why, b in bad.items():
         with pytest.raises(tq.TqError) as ei:
             tq.tq_validate_blob(b)

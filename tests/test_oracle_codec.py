@@ -9,10 +9,10 @@ from oracle import oracle as O
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
-def brute_force_lzw(S: bytes, group_bytes: int, max_entries: int, lmax: int):
+def brute_force_lzw(S: bytes, group_bytes: int, max_entries: int, lmax: int, entries=None):
     """Independent restatement used only as a pin: the dictionary is a plain Python list of byte strings and
     the longest match is found by trying every entry at every position (no trie, no incremental walk)."""
-    entries = [bytes([b]) for b in range(256)]
+    entries = [bytes([b]) for b in range(256)] if entries is None else list(entries)
     codes, per_group = [], []
     for gs in range(0, len(S), group_bytes):
         ge = min(gs + group_bytes, len(S))
@@ -36,7 +36,7 @@ def brute_force_lzw(S: bytes, group_bytes: int, max_entries: int, lmax: int):
 def test_published_worked_example():
     lines = [l.strip() for l in open(os.path.join(GOLDEN, "lzw_classic_example.txt")) if l.strip() and not l.startswith("#")]
     text, want = lines[0].encode(), [int(t) for t in lines[1].split()]
-    codes, gnc, d = O.lzw_encode(np.frombuffer(text, np.uint8), group_bytes=1 << 20, max_entries=65536, lmax=16)
+    codes, gnc, d = O.lzw_encode(np.frombuffer(text, np.uint8), seg_len=1 << 20, max_entries=65536, lmax=16)
     assert codes.tolist() == want
     assert d.n_entries == 271
     assert d.entry(256) == b"TO" and d.entry(265) == b"TOB" and d.entry(268) == b"TOBE" and d.entry(270) == b"RNO"
@@ -44,7 +44,7 @@ def test_published_worked_example():
 
 def test_triangular_growth_on_equal_bytes():
     # six equal bytes: phrases of length 1, 2, 3 (the classic triangular growth)
-    codes, gnc, d = O.lzw_encode(np.full(6, 1, np.uint8), group_bytes=64, max_entries=65536, lmax=8)
+    codes, gnc, d = O.lzw_encode(np.full(6, 1, np.uint8), seg_len=64, max_entries=65536, lmax=8)
     assert codes.tolist() == [1, 256, 257]
     assert [d.entry(c) for c in (256, 257)] == [b"\x01\x01", b"\x01\x01\x01"]
 
@@ -53,7 +53,7 @@ def test_triangular_growth_on_equal_bytes():
 @pytest.mark.parametrize("group", [64, 100, 4096])
 def test_all_zero_closed_form(lmax, group):
     n = 3 * group + 17
-    codes, gnc, d = O.lzw_encode(np.zeros(n, np.uint8), group_bytes=group, max_entries=65536, lmax=lmax)
+    codes, gnc, d = O.lzw_encode(np.zeros(n, np.uint8), seg_len=group, max_entries=65536, lmax=lmax)
     # closed form: first group grows 1,2,..,lmax then stays at lmax with a remainder run; later groups use lmax runs
     exp_lens = []
     have = 1  # longest all-zero phrase in the dictionary
@@ -81,60 +81,117 @@ def test_against_brute_force_small_alphabet(seed):
     group = int(rng.choice([16, 37, 128]))
     lmax = int(rng.choice([2, 3, 4, 8]))
     max_entries = int(rng.choice([258, 262, 300, 65536]))
-    codes, gnc, d = O.lzw_encode(S, group_bytes=group, max_entries=max_entries, lmax=lmax)
+    codes, gnc, d = O.lzw_encode(S, seg_len=group, max_entries=max_entries, lmax=lmax)
     bc, bg, be = brute_force_lzw(S.tobytes(), group, max_entries, lmax)
     assert codes.tolist() == bc
     assert gnc.tolist() == bg
+    # the same input cut into ragged segments given one by one
+    seg_len = []
+    left = n
+    while left:
+        seg_len.append(min(left, int(rng.integers(0, 40))))
+        left -= seg_len[-1]
+    codes2, snc2, d2 = O.lzw_encode(S, seg_len=np.array(seg_len, np.uint32), max_entries=max_entries, lmax=lmax)
+    entries = [bytes([b]) for b in range(256)]
+    want, pos = [], 0
+    for L in seg_len:      # brute force segment by segment, carrying the entries
+        c, _, entries = brute_force_lzw(S.tobytes()[pos:pos + L], max(L, 1), max_entries, lmax, entries=entries)
+        want.append(c)
+        pos += L
+    assert codes2.tolist() == [c for seg in want for c in seg] and snc2.tolist() == [len(c) for c in want]
     assert [d.entry(e) for e in range(d.n_entries)] == be
 
 
 def test_freeze_when_full_and_no_reset():
     rng = np.random.default_rng(7)
     S = rng.integers(0, 256, 20000, dtype=np.uint8)
-    codes, gnc, d = O.lzw_encode(S, group_bytes=4096, max_entries=300, lmax=3)
+    codes, gnc, d = O.lzw_encode(S, seg_len=4096, max_entries=300, lmax=3)
     assert d.n_entries == 300            # filled, then frozen
     assert int(codes.max()) < 300
     # entries were created by the first 44 codes only (one entry per code while not full)
-    first = O.lzw_encode(S[:200], group_bytes=4096, max_entries=300, lmax=3)[2]
+    first = O.lzw_encode(S[:200], seg_len=4096, max_entries=300, lmax=3)[2]
     assert [first.entry(e) for e in range(300)] == [d.entry(e) for e in range(300)]
 
 
-@pytest.mark.parametrize("lmax,max_entries", [(3, 32000), (3, 4096), (8, 65536), (2, 1000)])
+def _ragged_segments(rng, n_segs, lo, hi, empty_every=0):
+    seg_len = rng.integers(lo, hi, n_segs).astype(np.uint32)
+    if empty_every:
+        seg_len[::empty_every] = 0
+    return seg_len
+
+
+@pytest.mark.parametrize("lmax,max_entries", [(3, 32000), (3, 4096), (8, 65536), (2, 1000), (2, 30719)])
 def test_round_trip_identity(lmax, max_entries):
     rng = np.random.default_rng(11)
-    S = np.clip(np.rint(rng.standard_normal(70000) * 35), -127, 127).astype(np.int8).view(np.uint8)
-    codes, gnc, d = O.lzw_encode(S, group_bytes=4096, max_entries=max_entries, lmax=lmax)
-    stream, goff = O.pad_stream(codes, gnc, d.n_entries)
-    assert all(int(x) % O.CODE_ALIGN == 0 for x in goff)
-    assert stream.size - codes.size < O.CODE_ALIGN * gnc.size
-    back = O.lzw_decode(stream, goff, d, S.size, d.n_entries)
+    seg_len = _ragged_segments(rng, 300, 1, 400, empty_every=7)        # 4 full units and a ragged fifth one
+    S = np.clip(np.rint(rng.standard_normal(int(seg_len.sum())) * 35), -127, 127).astype(np.int8).view(np.uint8)
+    codes, snc, d = O.lzw_encode(S, seg_len=seg_len, max_entries=max_entries, lmax=lmax)
+    assert np.all(snc[seg_len == 0] == 0)
+    stream, uoff = O.interleave(codes, snc, d.n_entries)
+    assert uoff.size == 5 + 1 and stream.size == int(uoff[-1]) * O.CHUNK_WORDS
+    back = O.lzw_decode(stream, uoff, seg_len, d, d.n_entries)
     assert np.array_equal(back, S)
-    # matches never cross a restart boundary: every group decodes to exactly its own bytes (checked inside
+    # matches never cross a segment end: every segment decodes to exactly its own bytes (checked inside
     # lzw_decode) and no run is longer than lmax
     assert int(d.ent_len.max()) <= lmax
 
 
+def test_interleave_layout_by_hand():
+    """Three segments with 5, 0 and 2 codes: one unit of two chunks; lane l's code k sits at (k // 4) * 256 + 4 l + k % 4,
+    everything else is the pad code."""
+    codes = np.array([10, 11, 12, 13, 14, 20, 21], np.uint16)
+    stream, uoff = O.interleave(codes, np.array([5, 0, 2], np.uint32), pad_code=999)
+    assert uoff.tolist() == [0, 2] and stream.size == 512
+    want = np.full(512, 999, np.uint16)
+    want[0:4] = [10, 11, 12, 13]
+    want[256] = 14
+    want[8:10] = [20, 21]
+    assert np.array_equal(stream, want)
+
+
 def test_decode_rejects_inconsistent_stream():
     S = np.arange(256, dtype=np.uint8).repeat(2)
-    codes, gnc, d = O.lzw_encode(S, group_bytes=128, max_entries=400, lmax=3)
-    stream, goff = O.pad_stream(codes, gnc, d.n_entries)
+    seg_len = np.full(4, 128, np.uint32)
+    codes, snc, d = O.lzw_encode(S, seg_len=seg_len, max_entries=400, lmax=3)
+    stream, uoff = O.interleave(codes, snc, d.n_entries)
     bad = stream.copy()
     bad[0] = d.n_entries + 5           # not an entry and not the pad code
     with pytest.raises(ValueError):
-        O.lzw_decode(bad, goff, d, S.size, d.n_entries, group_bytes=128)
-    short = goff.copy()
-    short[1] -= O.CODE_ALIGN           # group 0 loses codes -> wrong length
+        O.lzw_decode(bad, uoff, seg_len, d, d.n_entries)
+    bad = stream.copy()
+    bad[1] = d.n_entries               # a pad code before real codes
     with pytest.raises(ValueError):
-        O.lzw_decode(stream, short, d, S.size, d.n_entries, group_bytes=128)
-    assert np.array_equal(O.lzw_decode(stream, goff, d, S.size, d.n_entries, group_bytes=128), S)
+        O.lzw_decode(bad, uoff, seg_len, d, d.n_entries)
+    wrong = seg_len.copy()
+    wrong[0] -= 1                      # segment 0 now decodes to one byte too many
+    with pytest.raises(ValueError):
+        O.lzw_decode(stream, uoff, wrong, d, d.n_entries)
+    assert np.array_equal(O.lzw_decode(stream, uoff, seg_len, d, d.n_entries), S)
+
+
+def test_dictionary_carried_over_equals_one_run_over_the_concatenation():
+    """LZW state is only the dictionary, so encoding B with the dictionary A left behind gives the codes that
+    encoding A followed by B in one go gives for B (section 4 builds one table over all parameters)."""
+    rng = np.random.default_rng(21)
+    A = rng.integers(0, 7, 3000).astype(np.uint8)
+    B = rng.integers(0, 7, 2000).astype(np.uint8)
+    for max_entries, lmax in ((400, 3), (65536, 4), (300, 2)):
+        ca, _, da = O.lzw_encode(A, seg_len=100, max_entries=max_entries, lmax=lmax)
+        cb, _, db = O.lzw_encode(B, seg_len=100, max_entries=max_entries, lmax=lmax, carry=da)
+        call, _, dall = O.lzw_encode(np.concatenate([A, B]), seg_len=100, max_entries=max_entries, lmax=lmax)
+        assert np.array_equal(np.concatenate([ca, cb]), call)
+        assert [db.entry(e) for e in range(db.n_entries)] == [dall.entry(e) for e in range(dall.n_entries)]
+        # and against the brute-force parser started from A's entries
+        bc, _, be = brute_force_lzw(B.tobytes(), 100, max_entries, lmax, entries=[da.entry(e) for e in range(da.n_entries)])
+        assert cb.tolist() == bc and [db.entry(e) for e in range(db.n_entries)] == be
 
 
 def test_singles_only_dictionary_is_identity_code():
     rng = np.random.default_rng(3)
     S = rng.integers(0, 256, 5000, dtype=np.uint8)
-    codes, gnc, d = O.lzw_encode(S, group_bytes=4096, max_entries=256, lmax=3)
+    codes, gnc, d = O.lzw_encode(S, seg_len=4096, max_entries=256, lmax=3)
     assert np.array_equal(codes, S.astype(np.uint16))     # code == byte
-    codes1, _, _ = O.lzw_encode(S, group_bytes=4096, max_entries=65536, lmax=1)
+    codes1, _, _ = O.lzw_encode(S, seg_len=4096, max_entries=65536, lmax=1)
     assert np.array_equal(codes1, S.astype(np.uint16))
 
 
@@ -146,7 +203,7 @@ def test_information_bound_on_iid_input():
     p = np.bincount(S, minlength=256) / S.size
     H = -(p[p > 0] * np.log2(p[p > 0])).sum()
     for max_entries in (32000, 65536):
-        codes, gnc, d = O.lzw_encode(S, group_bytes=4096, max_entries=max_entries, lmax=3)
+        codes, gnc, d = O.lzw_encode(S, seg_len=4096, max_entries=max_entries, lmax=3)
         sym_per_code = S.size / codes.size
         assert sym_per_code < 16.0 / H * 1.02
         assert sym_per_code > 1.5          # and it does find pairs

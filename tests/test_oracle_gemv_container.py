@@ -35,47 +35,52 @@ def test_gemv_unit_vectors_and_ones():
 
 def test_serialize_special_cases_reduce_to_slicing():
     rng = np.random.default_rng(2)
-    # one micro-tile: 16 x 8 -> the string starts with the matrix in row-major order, rest is zero padding
-    Q = rng.integers(-127, 128, (16, 8), dtype=np.int8)
-    S = O.serialize(Q)
-    assert S.size == 16 * 256
-    assert np.array_equal(S[:128].view(np.int8), Q.reshape(-1))
-    assert not S[128:].any()
-    # two micro-tiles side by side
-    Q = rng.integers(-127, 128, (16, 16), dtype=np.int8)
-    S = O.serialize(Q).view(np.int8)
-    assert np.array_equal(S[:128], Q[:, :8].reshape(-1)) and np.array_equal(S[128:256], Q[:, 8:].reshape(-1))
-    # two bands, two groups: band-major, then groups left to right, then micro-tiles
-    Q = rng.integers(-127, 128, (32, 512), dtype=np.int8)
-    S = O.serialize(Q).view(np.int8)
-    g = 4096
-    assert np.array_equal(S[0:128], Q[0:16, 0:8].reshape(-1))
-    assert np.array_equal(S[g + 128 * 3: g + 128 * 4], Q[0:16, 256 + 24: 256 + 32].reshape(-1))
-    assert np.array_equal(S[2 * g: 2 * g + 128], Q[16:32, 0:8].reshape(-1))
-    assert np.array_equal(S[3 * g + 128 * 31: 4 * g], Q[16:32, 504:512].reshape(-1))
+    # one full unit: 16 rows x 4 panels of 16 columns; lane l = row l % 16, panel l // 16
+    Q = rng.integers(-127, 128, (16, 64), dtype=np.int8)
+    S, seg_len = O.serialize(Q, seg_cols=16)
+    assert seg_len.tolist() == [16] * 64
+    for lane in (0, 1, 15, 16, 37, 63):
+        assert np.array_equal(S[16 * lane: 16 * lane + 16].view(np.int8), Q[lane % 16, 16 * (lane // 16): 16 * (lane // 16) + 16])
+    # two bands, two quads (8 panels): units in the order (band 0, quad 0), (band 0, quad 1), (band 1, quad 0), ...
+    Q = rng.integers(-127, 128, (32, 128), dtype=np.int8)
+    S, seg_len = O.serialize(Q, seg_cols=16)
+    unit = 64 * 16
+    assert np.array_equal(S[1 * unit + 16 * 17: 1 * unit + 16 * 18].view(np.int8), Q[1, 64 + 16: 64 + 32])      # band 0, quad 1, lane 17
+    assert np.array_equal(S[2 * unit + 16 * 63: 3 * unit].view(np.int8), Q[16 + 15, 48:64])                      # band 1, quad 0, lane 63
+    # ragged: 5 x 40 with panels of 16 -> 3 panels (16, 16, 8 columns) in one quad, rows 5..15 and panel 3 are empty
+    Q = rng.integers(-127, 128, (5, 40), dtype=np.int8)
+    S, seg_len = O.serialize(Q, seg_cols=16)
+    want = np.zeros((4, 16), np.uint32)
+    want[0, :5] = 16
+    want[1, :5] = 16
+    want[2, :5] = 8
+    assert np.array_equal(seg_len.reshape(4, 16), want)
+    assert np.array_equal(S[:16].view(np.int8), Q[0, :16]) and np.array_equal(S[-8:].view(np.int8), Q[4, 32:])
 
 
-@pytest.mark.parametrize("shape", [(16, 256), (5, 7), (33, 300), (48, 512), (1, 1), (17, 257)])
-def test_serialize_is_a_padded_permutation_and_inverts(shape):
+@pytest.mark.parametrize("shape,seg_cols", [((16, 256), 64), ((5, 7), 16), ((33, 300), 32), ((48, 512), 256), ((1, 1), 16),
+                                            ((17, 257), 256), ((40, 3000), 1024)])
+def test_serialize_is_a_permutation_and_inverts(shape, seg_cols):
     rng = np.random.default_rng(3)
     Q = rng.integers(-127, 128, shape, dtype=np.int8)
-    S = O.serialize(Q)
-    rp, cp = O.padded_shape(*shape)
-    assert S.size == rp * cp and rp % 16 == 0 and cp % 256 == 0
-    assert np.array_equal(np.sort(S[S != 0]), np.sort(Q.view(np.uint8)[Q != 0].reshape(-1)))
-    assert np.array_equal(O.deserialize(S, *shape), Q)
-    assert O.serialize(np.array([[-1]], np.int8))[0] == 0xFF      # two's complement byte
+    S, seg_len = O.serialize(Q, seg_cols)
+    n_bands, n_panels, n_quads = O.geometry(shape[0], shape[1], seg_cols)
+    assert seg_len.size == 64 * n_bands * n_quads and S.size == Q.size == int(seg_len.sum())
+    assert np.array_equal(np.sort(S), np.sort(Q.view(np.uint8).reshape(-1)))
+    assert np.array_equal(O.deserialize(S, shape[0], shape[1], seg_cols), Q)
+    assert O.serialize(np.array([[-1]], np.int8), 16)[0][0] == 0xFF      # two's complement byte
 
 
-@pytest.mark.parametrize("shape,max_entries", [((64, 512), 32000), ((33, 300), 1000), ((16, 8), 256), ((200, 1024), 4096)])
-def test_container_round_trip(shape, max_entries):
+@pytest.mark.parametrize("shape,max_entries,seg_cols", [((64, 512), 30719, 256), ((33, 300), 1000, 64), ((16, 8), 256, 16),
+                                                        ((200, 1024), 4096, 128)])
+def test_container_round_trip(shape, max_entries, seg_cols):
     spec = small_case(shape[0], shape[1], seed=42)
     W = make_weights(spec)
-    enc = O.encode_matrix(W, max_entries=max_entries, lmax=3)
+    enc = O.encode_matrix(W, max_entries=max_entries, lmax=2, seg_cols=seg_cols)
     blob = O.build_blob(enc)
     p = O.parse_blob(blob)
     assert (p["rows"], p["cols"]) == shape and p["n_entries"] == enc.dictionary.n_entries
-    assert p["n_codes"] == enc.stream.size and p["pad_code"] == enc.dictionary.n_entries
+    assert p["n_codes"] == enc.stream.size and p["pad_code"] == enc.dictionary.n_entries and p["seg_cols"] == seg_cols
     assert p["slots"][-1] == 0                                    # the pad entry has length 0
     assert np.array_equal(p["slots"][:256], np.arange(256, dtype=np.uint32) | (8 << 24))   # singles: code == byte, 8 bits long
     Q, s = O.decode_blob(blob)
@@ -93,7 +98,7 @@ def test_measured_ratio_config1_like():
     7.2 bits each); the measured ratio must sit under the entropy bound and above a sanity floor."""
     spec = small_case(512, 2048, seed=1)
     W = make_weights(spec)
-    enc = O.encode_matrix(W, max_entries=32000, lmax=3)
+    enc = O.encode_matrix(W, max_entries=30719, lmax=2)
     weights_per_code = (512 * 2048) / enc.n_real_codes
     p = np.bincount(enc.Q.view(np.uint8).reshape(-1), minlength=256) / enc.Q.size
     H = -(p[p > 0] * np.log2(p[p > 0])).sum()
