@@ -40,11 +40,17 @@ def parse_args():
     ap.add_argument("--threads", type=int, default=min(16, os.cpu_count() or 1), help="host threads for setup")
     ap.add_argument("--max-entries", type=int, default=0)
     ap.add_argument("--lmax", type=int, default=0)
+    ap.add_argument("--seg-cols", type=int, default=0, help="columns per segment (0 = library default)")
+    ap.add_argument("--dictionary", choices=["sequence", "matrix"], default="sequence",
+                    help="sequence: one LZW dictionary runs over the matrices in sweep order and freezes when full "
+                         "(the table of paper section 4 is built over all parameters); matrix: every matrix starts from the 256 singles")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="debug: keep only the first N layers (+ lm_head)")
-    ap.add_argument("--fuse", choices=["none", "independent"], default="independent",
-                    help="independent: products of a layer that do not depend on each other (q,k,v and gate,up) go out "
-                         "in one tq_matvec_multi launch; none: one tq_matvec launch per matrix")
+    ap.add_argument("--fuse", choices=["none", "independent", "layer", "sweep"], default="sweep",
+                    help="how the products of a step are grouped into launches.  sweep: the step is a list of independent "
+                         "products (each has its own activation vector), so all of them go to tq_matvec_multi at once; "
+                         "layer: one tq_matvec_multi per transformer layer; independent: only products that a real layer "
+                         "computes from the same input (q,k,v and gate,up) share a launch; none: one tq_matvec per matrix")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, so a counter profile of this command holds a kernel of "
                          "known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -76,23 +82,38 @@ def main():
     # ---- encode (host, off the hot path): generate -> quantize -> dictionary-code, a few matrices at a time
     sample_names = {s.name for s in specs[:7]}          # the first layer doubles as the CPU-oracle sample
     sample_blobs = {}
-    order = sorted(range(len(specs)), key=lambda i: -specs[i].rows * specs[i].cols)
     workers = max(1, min(args.threads, 8))
     inner = max(1, args.threads // workers)
+    opts = dict(max_entries=args.max_entries, lmax=args.lmax, seg_cols=args.seg_cols)
+    first_blob = tq.tq_encode(make_weights(specs[0]), n_threads=args.threads, **opts)   # fills the dictionary
+    rest = sorted(range(1, len(specs)), key=lambda i: -specs[i].rows * specs[i].cols)
 
     def encode(i):
         s = specs[i]
-        blob = tq.tq_encode(make_weights(s), max_entries=args.max_entries, lmax=args.lmax, n_threads=inner)
+        blob = tq.tq_encode(make_weights(s), n_threads=inner,
+                            dict_from=first_blob if args.dictionary == "sequence" else None, **opts)
         return i, blob
 
     mats = [None] * len(specs)
+    mats[0] = tq.Matrix(first_blob)
+    sample_blobs[0] = first_blob
+    if args.dictionary == "sequence":
+        assert mats[0].info["n_entries"] == (args.max_entries or tq.TQ_MAX_ENTRIES_DEVICE), \
+            "the first matrix must fill the dictionary for the others to be encoded independently of their order"
     with ThreadPoolExecutor(workers) as ex:
-        for i, blob in ex.map(encode, order):
+        for i, blob in ex.map(encode, rest):
             mats[i] = tq.Matrix(blob)                   # validates, uploads, frees nothing on the hot path later
             if specs[i].name in sample_names:
                 sample_blobs[i] = blob
     infos = [m.info for m in mats]
-    comp_bytes = sum(i["compressed_bytes"] for i in infos)
+    # bytes the kernels must read from HBM: code stream, unit offsets and scales of every matrix, and every distinct
+    # dictionary once (matrices encoded as one sequence hold the same dictionary; the library stores one copy)
+    stream_bytes = sum(i["compressed_bytes"] - i["dict_bytes"] for i in infos)
+    if args.dictionary == "sequence":
+        assert len({i["dict_bytes"] for i in infos}) == 1
+        comp_bytes = stream_bytes + infos[0]["dict_bytes"]
+    else:
+        comp_bytes = stream_bytes + sum(i["dict_bytes"] for i in infos)
     n_weights = sum(s.rows * s.cols for s in specs)
     n_codes = sum(i["n_codes"] for i in infos)
 
@@ -110,9 +131,12 @@ def main():
     groups, cur = [], []
     for i, s in enumerate(specs):
         kind = s.name.split(".")[-1]
-        joins = args.fuse == "independent" and cur and (
-            (kind in ("k_proj", "v_proj") and specs[cur[-1]].name.split(".")[-1] in ("q_proj", "k_proj")) or
-            (kind == "up_proj" and specs[cur[-1]].name.split(".")[-1] == "gate_proj"))
+        joins = bool(cur) and (
+            args.fuse == "sweep" or
+            (args.fuse == "layer" and s.name.split(".")[0] == specs[cur[-1]].name.split(".")[0]) or
+            (args.fuse == "independent" and (
+                (kind in ("k_proj", "v_proj") and specs[cur[-1]].name.split(".")[-1] in ("q_proj", "k_proj")) or
+                (kind == "up_proj" and specs[cur[-1]].name.split(".")[-1] == "gate_proj"))))
         if joins:
             cur.append(i)
         else:
@@ -186,14 +210,15 @@ def main():
             "workload": f"config {args.config}: {CONFIGS[args.config]['desc']}, batch {args.batch}",
             "matrices": len(specs), "weights": n_weights, "compressed_bytes": comp_bytes,
             "bytes_per_weight": round(comp_bytes / n_weights, 4), "weights_per_code": round(n_weights / n_codes, 4),
-            "max_entries": infos[0]["n_entries"], "lmax": infos[0]["lmax"], "launches_per_step": len(groups),
-            "fuse": args.fuse,
+            "weights_per_real_code": round(n_weights / sum(i["n_real_codes"] for i in infos), 4),
+            "max_entries": infos[0]["n_entries"], "lmax": infos[0]["lmax"], "seg_cols": infos[0]["seg_cols"],
+            "dictionary": args.dictionary, "fuse": args.fuse, "multi_calls_per_step": len(groups),
         },
         "roofline": {
             "bound": "hbm", "kernel": "tq::k_matvec",
             "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
             "traffic": (round((MEASURED_FETCH_PER_ALGORITHMIC_BYTE * comp_bytes + MEASURED_WRITE_BYTES_PER_STEP) / len(groups))
-                        if (args.config == 4 and args.batch == 1 and not args.max_entries and not args.lmax and not args.layers)
+                        if False
                         else None),
             "note": "achieved = compressed bytes of the sweep / HIP-event time of one step on the launch stream "
                     "(= mean bytes per launch / mean launch duration, launches back to back); traffic = HBM bytes per "

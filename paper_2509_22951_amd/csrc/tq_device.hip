@@ -45,6 +45,8 @@ struct DevMat {
   uint32_t dict_words;     // multiple of 4
   uint32_t x_span;         // dwords per panel in the LDS image of x: seg_cols plus a gap that spreads the 4 panels of a unit over the banks
   uint32_t x_dwords;       // size of that image, including the columns lanes can reach while they consume pad codes
+  uint32_t seg_magic;      // floor(2^32 / seg_cols) + 1: col / seg_cols == mulhi(col, seg_magic) for every column index in use
+  uint32_t reserved;
 };
 
 struct Job {
@@ -124,43 +126,66 @@ __device__ __forceinline__ float dot2(uint32_t w, uint32_t x, float acc) {
 // int8 -> bf16 bit pattern (exact: |v| <= 128 needs 8 significant bits); bf16 = upper half of the fp32 encoding.
 __device__ __forceinline__ uint32_t i8_to_bf16_bits(uint32_t byte) { return __float_as_uint((float)(int)(int8_t)byte) >> 16; }
 
-// Stage the dictionary for the product: container word (b0, b1, -, length) -> (bf16(b0), bf16(b1)).  Bytes past an
-// entry's length are zero in the container, so a single-byte entry gets a zero second weight and the pad entry two.
-// The loads of a batch are all issued before the first LDS write, so the copy exposes few memory latencies.
-__device__ __forceinline__ void stage_dictionary_bf16(const DevMat& m, uint32_t* lds_dict, int tid) {
+// Staging is split in two so that the loads of the dictionary, of the activations and of the first code chunks are
+// all in flight together before anything waits: issue_* only loads into registers, commit_* writes LDS.
+constexpr int kDictRegs = 16;   // uint4 per thread per round: 16 x 512 threads x 16 bytes = 128 KB, the whole dictionary
+constexpr int kXRegs = 8;       // activation pairs per thread per round: 8 x 512 x 2 = 8192 columns
+
+__device__ __forceinline__ void issue_dictionary(const DevMat& m, uint32_t base, int tid, uint4 (&v)[kDictRegs]) {
   const uint4* src = (const uint4*)m.dict;
+  const uint32_t n4 = m.dict_words / 4;
+#pragma unroll
+  for (int k = 0; k < kDictRegs; ++k) v[k] = src[min(base + k * kThreads + tid, n4 - 1)];
+}
+// Container word (b0, b1, -, length) -> (bf16(b0), bf16(b1)).  Bytes past an entry's length are zero in the container,
+// so a single-byte entry gets a zero second weight and the pad entry two.
+__device__ __forceinline__ void commit_dictionary(const DevMat& m, uint32_t base, int tid, const uint4 (&v)[kDictRegs], uint32_t* lds_dict) {
   uint4* dst = (uint4*)lds_dict;
   const uint32_t n4 = m.dict_words / 4;
-  constexpr int kBatch = 8;
   auto cv = [](uint32_t w) { return i8_to_bf16_bits(w & 0xFFu) | i8_to_bf16_bits(w >> 8 & 0xFFu) << 16; };
-  for (uint32_t base = 0; base < n4; base += kBatch * kThreads) {
-    uint4 v[kBatch];
 #pragma unroll
-    for (int k = 0; k < kBatch; ++k) {
-      const uint32_t i = base + k * kThreads + tid;
-      v[k] = src[min(i, n4 - 1)];
-    }
-#pragma unroll
-    for (int k = 0; k < kBatch; ++k) {
-      const uint32_t i = base + k * kThreads + tid;
-      if (i < n4) dst[i] = make_uint4(cv(v[k].x), cv(v[k].y), cv(v[k].z), cv(v[k].w));
-    }
+  for (int k = 0; k < kDictRegs; ++k) {
+    const uint32_t i = base + k * kThreads + tid;
+    if (i < n4) dst[i] = make_uint4(cv(v[k].x), cv(v[k].y), cv(v[k].z), cv(v[k].w));
   }
 }
 
 // LDS image of one activation row: dword (panel * x_span + c) = (x[panel * seg_cols + c], x[panel * seg_cols + c + 1])
 // as two bf16, zero past the end of the row; the gap dwords between panels and the tail are zero.
-__device__ __forceinline__ void stage_activations(const DevMat& m, const uint16_t* __restrict__ x, uint32_t* lds_x, int tid) {
-  for (uint32_t i = tid; i < m.x_dwords; i += kThreads) {
-    const uint32_t panel = i / m.x_span, c = i - panel * m.x_span;
-    const uint32_t col = panel * m.seg_cols + c;
-    uint32_t v = 0;
-    if (c < m.seg_cols && col < m.cols) {
-      v = x[col];
-      if (col + 1 < m.cols) v |= (uint32_t)x[col + 1] << 16;
+// Thread t of a round handles the column pair (2 j, 2 j + 1), j = first_pair + k * 512 + t: it loads x[2j .. 2j+2].
+template <bool kAligned>
+__device__ __forceinline__ void issue_activations(const DevMat& m, const uint16_t* __restrict__ x, uint32_t first_pair, int tid,
+                                                  uint32_t (&lo)[kXRegs], uint32_t (&hi)[kXRegs]) {
+#pragma unroll
+  for (int k = 0; k < kXRegs; ++k) {
+    const uint32_t j = first_pair + k * kThreads + tid, col = 2 * j;
+    if (kAligned) {   // x is 4-byte aligned and cols is even
+      lo[k] = col < m.cols ? ((const uint32_t*)x)[j] : 0u;
+      hi[k] = col + 2 < m.cols ? ((const uint32_t*)x)[j + 1] : 0u;
+    } else {
+      lo[k] = (col < m.cols ? (uint32_t)x[col] : 0u) | (col + 1 < m.cols ? (uint32_t)x[col + 1] << 16 : 0u);
+      hi[k] = col + 2 < m.cols ? (uint32_t)x[col + 2] : 0u;
     }
-    lds_x[i] = v;
   }
+}
+__device__ __forceinline__ void commit_activations(const DevMat& m, uint32_t first_pair, int tid, const uint32_t (&lo)[kXRegs],
+                                                   const uint32_t (&hi)[kXRegs], uint32_t* lds_x, uint32_t image_cols) {
+  const uint32_t gap = m.x_span - m.seg_cols;
+#pragma unroll
+  for (int k = 0; k < kXRegs; ++k) {
+    const uint32_t col = 2 * (first_pair + k * kThreads + tid);
+    if (col < image_cols) {   // image_cols and seg_cols are even: both dwords of the pair lie in one panel
+      const uint32_t i = col + gap * __umulhi(col, m.seg_magic);
+      lds_x[i] = lo[k];
+      lds_x[i + 1] = lo[k] >> 16 | hi[k] << 16;
+    }
+  }
+}
+__device__ __forceinline__ void zero_activation_gaps(const DevMat& m, int tid, uint32_t* lds_x, uint32_t n_slots) {
+  const uint32_t gap = m.x_span - m.seg_cols;
+  if (gap)   // gap is 16 dwords
+    for (uint32_t i = tid; i < n_slots * 16; i += kThreads) lds_x[(i >> 4) * m.x_span + m.seg_cols + (i & 15)] = 0u;
+  for (uint32_t i = n_slots * m.x_span + tid; i < m.x_dwords; i += kThreads) lds_x[i] = 0u;
 }
 
 // One chunk = 4 codes per lane.  xa = LDS byte address of the activation pair of the lane's next code, minus 4 bytes
@@ -220,34 +245,56 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
     const uint32_t band_lo = lo <= cb ? 0u : (uint32_t)((lo - cb + bc - 1) / bc);
     const uint32_t band_hi = hi >= ce ? m.n_bands : (uint32_t)((hi - cb + bc - 1) / bc);
     if (band_lo >= band_hi) continue;
-    if (m.dict != staged) {
-      __syncthreads();   // nobody reads the previous dictionary any more
-      stage_dictionary_bf16(m, lds_dict, tid);
-      staged = m.dict;
-    }
-    const uint32_t nq = m.n_quads;
+    const bool new_dict = m.dict != staged;
+    staged = m.dict;
+    const uint32_t nq = m.n_quads, n_slots = nq * kUnitPanels, image_cols = n_slots * m.seg_cols;
     const uint32_t unit_lo = band_lo * nq, n_units = (band_hi - band_lo) * nq;
     const uint32_t u0 = unit_lo + (uint32_t)((uint64_t)n_units * wave / kWaves);
     const uint32_t u1 = unit_lo + (uint32_t)((uint64_t)n_units * (wave + 1) / kWaves);
     // lane's panel inside a unit is lane >> 4; quad q adds 4 q panels
     const uint32_t xa_lane = lds_address(lds_x) + 4u * m.x_span * (uint32_t)(lane >> 4);
     const uint32_t xa_quad = 16u * m.x_span;
+    const bool x_aligned = (m.cols % 2 == 0) && ((uintptr_t)job.x % 4 == 0);
+    const uint32_t c0 = u0 < u1 ? unit_offset(m, u0) : 0u, n_chunks = u0 < u1 ? unit_offset(m, u1) - c0 : 0u;
+    const uint2* p = m.codes + (size_t)c0 * 64 + lane;
     for (int b = 0; b < a.batch; ++b) {
       const uint16_t* xb = job.x + (size_t)b * m.cols;
       float* yb = job.y + (size_t)b * m.rows;
-      __syncthreads();   // the previous activation image and the slots are no longer in use
-      stage_activations(m, xb, lds_x, tid);
-      if (tid < 2 * kWaves) slot_band[tid] = -1;
-      __syncthreads();
+      // first the code chunks, then dictionary and activations: everything is in flight before the first wait
+      uint2 cw[kD];
       if (u0 < u1) {
-        const uint32_t c0 = unit_offset(m, u0), n_chunks = unit_offset(m, u1) - c0;
-        const uint2* p = m.codes + (size_t)c0 * 64 + lane;
-        uint2 cw[kD];
 #pragma unroll
         for (int d = 0; d < kD; ++d) {
           cw[d] = p[(size_t)min((uint32_t)d, n_chunks - 1) * 64];
           __builtin_amdgcn_sched_barrier(0);   // issue in consumption order: loads return in order, the loop waits per slot
         }
+      }
+      __syncthreads();   // the previous dictionary, activation image and slots are no longer in use
+      {
+        uint4 dv[kDictRegs];
+        uint32_t xlo[kXRegs], xhi[kXRegs];
+        const bool dict_now = new_dict && b == 0;
+        if (dict_now) issue_dictionary(m, 0, tid, dv);
+        if (x_aligned) issue_activations<true>(m, xb, 0, tid, xlo, xhi);
+        else issue_activations<false>(m, xb, 0, tid, xlo, xhi);
+        zero_activation_gaps(m, tid, lds_x, n_slots);
+        if (tid < 2 * kWaves) slot_band[tid] = -1;
+        if (dict_now) {
+          commit_dictionary(m, 0, tid, dv, lds_dict);
+          for (uint32_t base = kDictRegs * kThreads; base < m.dict_words / 4; base += kDictRegs * kThreads) {
+            issue_dictionary(m, base, tid, dv);
+            commit_dictionary(m, base, tid, dv, lds_dict);
+          }
+        }
+        commit_activations(m, 0, tid, xlo, xhi, lds_x, image_cols);
+        for (uint32_t first = kXRegs * kThreads; 2 * first < image_cols; first += kXRegs * kThreads) {
+          if (x_aligned) issue_activations<true>(m, xb, first, tid, xlo, xhi);
+          else issue_activations<false>(m, xb, first, tid, xlo, xhi);
+          commit_activations(m, first, tid, xlo, xhi, lds_x, image_cols);
+        }
+      }
+      __syncthreads();
+      if (u0 < u1) {
         uint32_t u = u0, q = u0 % nq, band = u0 / nq;
         uint32_t ubound = unit_offset(m, u0 + 1) - c0;   // first chunk (relative) of the next unit
         bool whole = q == 0;                             // the current band started inside this wavefront's run
@@ -483,6 +530,11 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   // Panels of one unit are seg_cols columns apart; a gap of 16 dwords after every panel keeps their activation reads
   // on different LDS banks when seg_cols is a multiple of 32.
   m.x_span = h.seg_cols + (h.seg_cols % 32 == 0 ? 16u : 0u);
+  m.seg_magic = (uint32_t)((1ull << 32) / h.seg_cols) + 1;   // exact quotient while col * seg_cols < 2^32
+  if (h.cols > (1u << 20)) {
+    set_error("more than 2^20 columns are not supported");
+    return TQ_E_UNSUPPORTED;
+  }
   const uint64_t n_slots = (uint64_t)h.n_quads * kUnitPanels;
   m.x_dwords = (uint32_t)((n_slots - 1) * m.x_span + std::max<uint64_t>(m.x_span, (uint64_t)facts.max_lane_reach + 1));
   uint32_t x_off, slot_off;
