@@ -32,8 +32,9 @@ MEASURED_WRITE_BYTES_PER_STEP = 3_609_600
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100,
+                    help="untimed steps; a step takes under a millisecond and the GPU needs tens of milliseconds of load to reach its sustained clocks")
     ap.add_argument("--config", type=int, default=4, help="workload: config 4 = LLaMA-3.2-3B decode-step sweep")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--also-batch", type=int, default=8, help="second batch size reported under 'other_batches' (0 = none)")

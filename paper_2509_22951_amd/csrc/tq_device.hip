@@ -30,9 +30,10 @@ namespace tq {
 
 constexpr int kWaves = 8;            // wavefronts per workgroup of the product kernel (one workgroup per CU: LDS-bound)
 constexpr int kThreads = kWaves * 64;
-constexpr int kDepth = 8;            // chunks of code loads kept in flight per wavefront (8 x 512 bytes)
+constexpr int kDepth = 16;           // chunks of code loads kept in flight per wavefront (16 x 512 bytes; measured on the
+                                     // 3B sweep: 8 in flight 4.57 TB/s, 12 and 16 in flight 4.90 TB/s)
 constexpr uint32_t kLdsLimit = 160 * 1024;
-constexpr int kMaxMulti = 32;        // matrices one launch can serve (bounded by the kernel argument size)
+constexpr int kMaxMulti = 128;       // matrices one launch can serve (bounded by the 4 KB of kernel arguments)
 
 // What the kernels need to know about one matrix.
 struct DevMat {
@@ -50,20 +51,19 @@ struct DevMat {
 };
 
 struct Job {
-  DevMat m;
+  const DevMat* m;         // device copy of the matrix description
   const uint16_t* x;       // bf16 [batch][cols]
   float* y;                // fp32 [batch][rows]
-  uint64_t cost_begin;     // position of this matrix in the launch's cost line (sum of earlier matrices' n_bands * band_cost)
-  uint32_t band_cost;      // cost of one band (its number of weights / 16)
-  uint32_t reserved;
 };
 
+// The launch's cost line: matrix i covers [cost[i], cost[i + 1]), one band of it costs its number of columns.
 struct MatvecArgs {
   int n, batch;
-  uint64_t total_cost;
   uint32_t x_off, slot_off;   // byte offsets in LDS of the activation image and of the partial-sum slots
+  uint32_t cost[kMaxMulti + 1];
   Job j[kMaxMulti];
 };
+static_assert(sizeof(MatvecArgs) <= 4096, "kernel arguments");
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) const uint32_t lds_cu32;
@@ -83,6 +83,17 @@ __device__ __forceinline__ void static_for(F&& f) {
 // Unit offsets are wave-uniform and never written while a kernel runs: reading them through the constant address
 // space makes them scalar loads, which do not share a counter with the vector loads of the code stream.
 __device__ __forceinline__ uint32_t unit_offset(const DevMat& m, uint32_t u) { return ((const_u32*)m.uoff)[u]; }
+
+// A matrix description from device memory, through scalar loads.
+__device__ __forceinline__ DevMat load_description(const DevMat* p) {
+  static_assert(sizeof(DevMat) % 4 == 0, "whole dwords");
+  uint32_t w[sizeof(DevMat) / 4];
+#pragma unroll
+  for (size_t k = 0; k < sizeof(DevMat) / 4; ++k) w[k] = ((const_u32*)p)[k];
+  DevMat m;
+  __builtin_memcpy(&m, w, sizeof m);
+  return m;
+}
 
 // Byte address inside LDS of a pointer into the workgroup's dynamic shared memory.
 __device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(size_t)(const lds_u8*)p; }
@@ -191,23 +202,32 @@ __device__ __forceinline__ void zero_activation_gaps(const DevMat& m, int tid, u
 // One chunk = 4 codes per lane.  xa = LDS byte address of the activation pair of the lane's next code, minus 4 bytes
 // per code consumed since the last rebase; code k of the body therefore reads at xa + 4 k, and the constant part goes
 // into the instruction's offset field.  A single advances the lane by one column (already counted by the 4 k), a pair
-// by one more.
+// by one more.  The dictionary sits at LDS address 0, so a code's word offset is its address.
+// The chunk is split in two: issue_chunk starts the 8 LDS reads, finish_chunk does the 4 dot products one step later,
+// so that the reads of the next chunk are in flight while the products of this one execute.
+struct Operands {
+  uint32_t w0, w1, w2, w3, x0, x1, x2, x3;
+};
 template <int kCode0>
-__device__ __forceinline__ void chunk4(uint2 c, uint32_t dict_lds, uint32_t& xa, float& a0, float& a1) {
-  const uint32_t w0 = lds_read32(word_offset_lo(c.x) + dict_lds), w1 = lds_read32(word_offset_hi(c.x) + dict_lds);
-  const uint32_t w2 = lds_read32(word_offset_lo(c.y) + dict_lds), w3 = lds_read32(word_offset_hi(c.y) + dict_lds);
-  const uint32_t x0 = lds_read32_off<4 * kCode0>(xa);
+__device__ __forceinline__ void issue_chunk(uint2 c, uint32_t& xa, Operands& o) {
+  o.w0 = lds_read32(word_offset_lo(c.x));
+  o.w1 = lds_read32(word_offset_hi(c.x));
+  o.w2 = lds_read32(word_offset_lo(c.y));
+  o.w3 = lds_read32(word_offset_hi(c.y));
+  o.x0 = lds_read32_off<4 * kCode0>(xa);
   xa = (is_pair_lo(c.x) << 2) + xa;
-  const uint32_t x1 = lds_read32_off<4 * kCode0 + 4>(xa);
+  o.x1 = lds_read32_off<4 * kCode0 + 4>(xa);
   xa = (is_pair_hi(c.x) << 2) + xa;
-  const uint32_t x2 = lds_read32_off<4 * kCode0 + 8>(xa);
+  o.x2 = lds_read32_off<4 * kCode0 + 8>(xa);
   xa = (is_pair_lo(c.y) << 2) + xa;
-  const uint32_t x3 = lds_read32_off<4 * kCode0 + 12>(xa);
+  o.x3 = lds_read32_off<4 * kCode0 + 12>(xa);
   xa = (is_pair_hi(c.y) << 2) + xa;
-  a0 = dot2(w0, x0, a0);
-  a1 = dot2(w1, x1, a1);
-  a0 = dot2(w2, x2, a0);
-  a1 = dot2(w3, x3, a1);
+}
+__device__ __forceinline__ void finish_chunk(const Operands& o, float& a0, float& a1) {
+  a0 = dot2(o.w0, o.x0, a0);
+  a1 = dot2(o.w1, o.x1, a1);
+  a0 = dot2(o.w2, o.x2, a0);
+  a1 = dot2(o.w3, o.x3, a1);
 }
 
 // Sum of the four panel lanes of each row: afterwards every lane l holds the sum over lanes l % 16 + {0, 16, 32, 48}.
@@ -228,22 +248,26 @@ __device__ __forceinline__ float sum_over_panels(float v) {
 // so the result does not depend on timing.
 template <int kD>
 __global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
+  static_assert(kD % 2 == 0, "the operand sets alternate with the slot index");
   extern __shared__ uint4 lds4[];
   uint32_t* lds_dict = (uint32_t*)lds4;
   uint32_t* lds_x = (uint32_t*)((uint8_t*)lds4 + a.x_off);
   float* slot_val = (float*)((uint8_t*)lds4 + a.slot_off);           // [2 * kWaves][16]
   int* slot_band = (int*)(slot_val + 2 * kWaves * 16);               // [2 * kWaves]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const uint32_t dict_lds = lds_address(lds_dict);
-  const uint64_t lo = a.total_cost * blockIdx.x / gridDim.x, hi = a.total_cost * (blockIdx.x + 1) / gridDim.x;
+  if (lds_address(lds4) != 0) return;   // the code -> word lookup takes the dictionary to start at LDS address 0 (no static LDS here)
+  const uint64_t total = a.cost[a.n];
+  const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
   const uint32_t* staged = nullptr;
   for (int i = 0; i < a.n; ++i) {
-    const Job& job = a.j[i];
-    const DevMat& m = job.m;
-    const uint64_t cb = job.cost_begin, bc = job.band_cost, ce = cb + (uint64_t)m.n_bands * bc;
+    const uint32_t cb = a.cost[i], ce = a.cost[i + 1];
     if (hi <= cb || lo >= ce) continue;
-    const uint32_t band_lo = lo <= cb ? 0u : (uint32_t)((lo - cb + bc - 1) / bc);
-    const uint32_t band_hi = hi >= ce ? m.n_bands : (uint32_t)((hi - cb + bc - 1) / bc);
+    const Job job = a.j[i];
+    const DevMat m = load_description(job.m);
+    // a band goes to the share that holds its middle
+    const uint32_t bc = m.cols;
+    const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
+    const uint32_t band_hi = hi >= ce ? m.n_bands : min(m.n_bands, (hi - cb + bc / 2) / bc);
     if (band_lo >= band_hi) continue;
     const bool new_dict = m.dict != staged;
     staged = m.dict;
@@ -300,6 +324,8 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
         bool whole = q == 0;                             // the current band started inside this wavefront's run
         float a0 = 0.f, a1 = 0.f;
         uint32_t xa = xa_lane + q * xa_quad;
+        // two operand sets used alternately (kD is even): slot d loads into ops[d & 1] and finishes ops[(d - 1) & 1]
+        Operands ops[2] = {{0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u}};   // zero weights: finishing adds nothing
         auto finish_band = [&](bool complete) {
           const float v = sum_over_panels(a0 + a1);
           if (complete) {
@@ -318,6 +344,9 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
               if (r + d == ubound) {   // unit boundary: every lane restarts at the first column of its next segment
                 ++u;
                 if (++q == nq) {
+                  Operands& last = ops[(d + 1) & 1];
+                  finish_chunk(last, a0, a1);
+                  last.w0 = last.w1 = last.w2 = last.w3 = 0u;
                   finish_band(whole);
                   q = 0;
                   ++band;
@@ -328,12 +357,15 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
                 ubound = unit_offset(m, u + 1) - c0;
                 xa = xa_lane + q * xa_quad - 16u * d;
               }
-              chunk4<4 * d>(cw[d], dict_lds, xa, a0, a1);
+              issue_chunk<4 * d>(cw[d], xa, ops[d & 1]);
+              finish_chunk(ops[(d + 1) & 1], a0, a1);
             }
             cw[d] = p[(size_t)min(r + d + kD, n_chunks - 1) * 64];   // refill the slot only after its last use
           });
           xa += 16 * kD;
         }
+        if ((n_chunks - 1) & 1) finish_chunk(ops[1], a0, a1);   // the last chunk's operands are still waiting
+        else finish_chunk(ops[0], a0, a1);
         finish_band(whole && (u1 % nq == 0));
       }
       __syncthreads();
@@ -500,6 +532,7 @@ bool plan_matvec_lds(uint32_t dict_words_max, uint32_t x_dwords_max, uint32_t* x
 struct tq_matrix {
   Header h;
   DevMat m;
+  const DevMat* m_dev;   // the same description in device memory, for launches that serve many matrices
   DictCopy* dict;
   void* dev_base;
   int device;
@@ -574,7 +607,8 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
 
   const uint64_t sz_uoff = round_up(h.uoff_bytes, kSectionAlign), sz_codes = round_up(h.code_bytes, kSectionAlign),
                  sz_scales = round_up(h.scale_bytes, kSectionAlign);
-  const uint64_t o_uoff = 0, o_codes = o_uoff + sz_uoff, o_scales = o_codes + sz_codes, total = o_scales + sz_scales;
+  const uint64_t o_uoff = 0, o_codes = o_uoff + sz_uoff, o_scales = o_codes + sz_codes, o_desc = o_scales + sz_scales,
+                 total = o_desc + round_up(sizeof(DevMat), kSectionAlign);
   uint8_t* base = nullptr;
   e = hipMalloc((void**)&base, total);
   if (e != hipSuccess) {
@@ -585,6 +619,11 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   e = hipMemcpy(base + o_uoff, src + h.off_uoff, h.uoff_bytes, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(base + o_codes, src + h.off_codes, h.code_bytes, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(base + o_scales, src + h.off_scales, h.scale_bytes, hipMemcpyHostToDevice);
+  m.dict = dict->dev;
+  m.uoff = (const uint32_t*)(base + o_uoff);
+  m.codes = (const uint2*)(base + o_codes);
+  m.scales = (const float*)(base + o_scales);
+  if (e == hipSuccess) e = hipMemcpy(base + o_desc, &m, sizeof m, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   tq_matrix* t = e == hipSuccess ? new (std::nothrow) tq_matrix : nullptr;
   if (!t) {
@@ -594,12 +633,9 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
     set_error("out of host memory");
     return TQ_E_OOM;
   }
-  m.dict = dict->dev;
-  m.uoff = (const uint32_t*)(base + o_uoff);
-  m.codes = (const uint2*)(base + o_codes);
-  m.scales = (const float*)(base + o_scales);
   t->h = h;
   t->m = m;
+  t->m_dev = (const DevMat*)(base + o_desc);
   t->dict = dict;
   t->dev_base = base;
   t->device = dev;
@@ -612,29 +648,30 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
 
 namespace {
 
-// One launch of the product kernel for hs[0..n), n <= kMaxMulti, all on one device.
+// One launch of the product kernel for hs[0..n), n <= kMaxMulti, all on one device, total cost below 2^32.
 int launch_matvec(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream) {
   MatvecArgs a;
-  std::memset(&a, 0, sizeof a);
   a.n = n;
   a.batch = batch;
   uint32_t dict_words_max = 0, x_dwords_max = 0;
   uint64_t cost = 0, bands = 0, band_cost_max = 1;
   for (int i = 0; i < n; ++i) {
     const tq_matrix* t = hs[i];
-    Job& j = a.j[i];
-    j.m = t->m;
-    j.x = (const uint16_t*)xs[i];
-    j.y = (float*)ys[i];
-    j.cost_begin = cost;
-    j.band_cost = std::max<uint32_t>(1, t->m.cols);   // 16 rows x cols weights, in units of 16 weights
-    cost += (uint64_t)t->m.n_bands * j.band_cost;
+    a.j[i].m = t->m_dev;
+    a.j[i].x = (const uint16_t*)xs[i];
+    a.j[i].y = (float*)ys[i];
+    a.cost[i] = (uint32_t)cost;
+    cost += (uint64_t)t->m.n_bands * t->m.cols;   // a band costs its 16 x cols weights, counted in units of 16
     bands += t->m.n_bands;
-    band_cost_max = std::max<uint64_t>(band_cost_max, j.band_cost);
+    band_cost_max = std::max<uint64_t>(band_cost_max, t->m.cols);
     dict_words_max = std::max(dict_words_max, t->m.dict_words);
     x_dwords_max = std::max(x_dwords_max, t->m.x_dwords);
   }
-  a.total_cost = cost;
+  a.cost[n] = (uint32_t)cost;
+  if (cost > 0xFFFFFFFFull) {
+    set_error("more than 2^36 weights in one launch are not supported");
+    return TQ_E_UNSUPPORTED;
+  }
   size_t lds_total;
   if (!plan_matvec_lds(dict_words_max, x_dwords_max, &a.x_off, &a.slot_off, &lds_total)) {
     set_error("the matrices of this call together need " + std::to_string(lds_total) + " bytes of LDS (largest dictionary plus longest row)");
@@ -688,8 +725,23 @@ extern "C" int tq_matvec_multi(int n, const tq_handle* hs, const void* const* xs
     return TQ_E_INVALID_ARG;
   }
   if (int rc = check_call("tq_matvec_multi", n, hs, xs, ys, batch)) return rc;
-  for (int i = 0; i < n; i += kMaxMulti)
-    if (int rc = launch_matvec(std::min(kMaxMulti, n - i), hs + i, xs + i, ys + i, batch, (hipStream_t)stream)) return rc;
+  // as few launches as the kernel-argument size and the 32-bit cost line allow
+  for (int i = 0; i < n;) {
+    int k = 0;
+    uint64_t cost = 0;
+    while (i + k < n && k < kMaxMulti) {
+      const uint64_t c = (uint64_t)hs[i + k]->m.n_bands * hs[i + k]->m.cols;
+      if (k > 0 && cost + c > 0xFFFFFFFFull) break;
+      cost += c;
+      ++k;
+    }
+    if (cost > 0xFFFFFFFFull) {
+      set_error("tq_matvec_multi: a single matrix of more than 2^36 weights is not supported");
+      return TQ_E_UNSUPPORTED;
+    }
+    if (int rc = launch_matvec(k, hs + i, xs + i, ys + i, batch, (hipStream_t)stream)) return rc;
+    i += k;
+  }
   return TQ_OK;
 }
 
