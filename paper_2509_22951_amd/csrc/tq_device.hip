@@ -387,6 +387,249 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Product for batches of 2..16 activation rows: decode into an LDS tile, then bf16 MFMA with the batch as N.
+//
+// A lane's segment is (row l & 15, panel l >> 4) of its unit, which is exactly the A-operand layout of
+// v_mfma_f32_16x16x32_bf16: lane l supplies row l % 16 and the 8 k-values of group l / 16.  Taking those 8 values as
+// 8 consecutive columns of the lane's own segment makes every lane read back only what it wrote itself: the tile is a
+// per-lane strip of seg_cols (+8) bytes, a lane appends the bytes of its runs (both bytes of an entry are stored; the
+// second byte of a single-byte entry is overwritten by the next run), and after the unit's last chunk window w of
+// the unit is one MFMA: A = bytes [8 w, 8 w + 8) of every strip converted to bf16 (exact), B = the activations of the
+// 4 x 8 columns those bytes stand for, one batch row per lane % 16.  Strips of shorter or empty segments hold stale
+// (finite) values past their end; they meet activations that are zero there because B is loaded with bounds checks.
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) const u32x2 lds_cu64;
+
+// Byte offset of the 16-bit dictionary entry of the code in the low / high half of a packed code pair.
+__device__ __forceinline__ uint32_t half_offset_lo(uint32_t pair) {
+  uint32_t a;
+  const uint32_t one = 1;
+  asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0" : "=v"(a) : "v"(one), "v"(pair));
+  return a;
+}
+__device__ __forceinline__ uint32_t half_offset_hi(uint32_t pair) {
+  uint32_t a;
+  const uint32_t one = 1;
+  asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1" : "=v"(a) : "v"(one), "v"(pair));
+  return a;
+}
+__device__ __forceinline__ uint32_t lds_read16(uint32_t addr) { return *(lds_cu16*)(size_t)addr; }
+
+// 8 int8 -> 8 bf16 (exact: |v| <= 128 needs 8 significant bits).  bf16 = upper half of the fp32 encoding.
+__device__ __forceinline__ bf16x8 i8x8_to_bf16x8(uint2 w) {
+  uint4 r;
+  {
+    float f0 = (float)(int8_t)(w.x), f1 = (float)(int8_t)(w.x >> 8), f2 = (float)(int8_t)(w.x >> 16), f3 = (float)(int8_t)(w.x >> 24);
+    r.x = __builtin_amdgcn_perm(__float_as_uint(f1), __float_as_uint(f0), 0x07060302u);
+    r.y = __builtin_amdgcn_perm(__float_as_uint(f3), __float_as_uint(f2), 0x07060302u);
+  }
+  {
+    float f0 = (float)(int8_t)(w.y), f1 = (float)(int8_t)(w.y >> 8), f2 = (float)(int8_t)(w.y >> 16), f3 = (float)(int8_t)(w.y >> 24);
+    r.z = __builtin_amdgcn_perm(__float_as_uint(f1), __float_as_uint(f0), 0x07060302u);
+    r.w = __builtin_amdgcn_perm(__float_as_uint(f3), __float_as_uint(f2), 0x07060302u);
+  }
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// Append the runs of one chunk (4 codes) to the lane's strip.  ptr = LDS address of the lane's next byte; it stops at
+// `end` (the end of the segment), where the pad codes that fill up a shorter lane stream put their zero bytes: the
+// strips are 8 bytes apart, so those stay clear of the next strip.
+__device__ __forceinline__ void append_chunk(uint2 c, uint32_t& ptr, uint32_t end) {
+  const uint32_t e0 = lds_read16(half_offset_lo(c.x)), e1 = lds_read16(half_offset_hi(c.x));
+  const uint32_t e2 = lds_read16(half_offset_lo(c.y)), e3 = lds_read16(half_offset_hi(c.y));
+  const uint32_t l0 = is_pair_lo(c.x), l1 = is_pair_hi(c.x), l2 = is_pair_lo(c.y), l3 = is_pair_hi(c.y);
+  auto put = [&](uint32_t e, uint32_t pair) {
+    *(lds_u8*)(size_t)ptr = (uint8_t)e;
+    *(lds_u8*)(size_t)(ptr + 1) = (uint8_t)(e >> 8);
+    ptr = min(ptr + 1 + pair, end);
+  };
+  put(e0, l0);
+  put(e1, l1);
+  put(e2, l2);
+  put(e3, l3);
+}
+
+// Activation fragment of one MFMA step: 8 consecutive bf16 of batch row n starting at column col (zero outside).
+template <bool kFast>
+__device__ __forceinline__ uint4 load_x_fragment(const uint16_t* __restrict__ x, uint32_t cols, int batch, int n, uint32_t col) {
+  if (n >= batch || col >= cols) return make_uint4(0, 0, 0, 0);
+  const uint16_t* p = x + (size_t)n * cols + col;
+  if (kFast) return *(const uint4*)p;   // cols % 8 == 0 and x 16-byte aligned: the 8 columns exist and the load is aligned
+  uint32_t e[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) e[k] = col + k < cols ? (uint32_t)p[k] : 0u;
+  return make_uint4(e[0] | e[1] << 16, e[2] | e[3] << 16, e[4] | e[5] << 16, e[6] | e[7] << 16);
+}
+
+constexpr int kMfmaAhead = 4;   // activation fragments loaded ahead of their MFMA
+
+template <int kD, bool kXFast>
+__global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
+  extern __shared__ uint4 lds4[];
+  uint16_t* lds_dict = (uint16_t*)lds4;
+  uint8_t* tiles = (uint8_t*)lds4 + a.x_off;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n_threads = blockDim.x, n_waves = n_threads >> 6;
+  if (lds_address(lds4) != 0) return;   // the code -> entry lookup takes the dictionary to start at LDS address 0
+  const uint64_t total = a.cost[a.n];
+  const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
+  const uint32_t* staged = nullptr;
+  const int bn = lane & 15, kg = lane >> 4;   // B operand: batch row and k-group of this lane
+  for (int i = 0; i < a.n; ++i) {
+    const uint32_t cb = a.cost[i], ce = a.cost[i + 1];
+    if (hi <= cb || lo >= ce) continue;
+    const Job job = a.j[i];
+    const DevMat m = load_description(job.m);
+    const uint32_t bc = m.cols;
+    const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
+    const uint32_t band_hi = hi >= ce ? m.n_bands : min(m.n_bands, (hi - cb + bc / 2) / bc);
+    if (band_lo >= band_hi) continue;
+    const uint32_t nq = m.n_quads;
+    const uint32_t unit_lo = band_lo * nq, n_units = (band_hi - band_lo) * nq;
+    const uint32_t u0 = unit_lo + (uint32_t)((uint64_t)n_units * wave / n_waves);
+    const uint32_t u1 = unit_lo + (uint32_t)((uint64_t)n_units * (wave + 1) / n_waves);
+    const uint32_t c0 = u0 < u1 ? unit_offset(m, u0) : 0u, n_chunks = u0 < u1 ? unit_offset(m, u1) - c0 : 0u;
+    const uint2* p = m.codes + (size_t)c0 * 64 + lane;
+    uint2 cw[kD];
+    if (u0 < u1) {
+#pragma unroll
+      for (int d = 0; d < kD; ++d) {
+        cw[d] = p[(size_t)min((uint32_t)d, n_chunks - 1) * 64];
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    __syncthreads();   // the previous matrix's dictionary and partial sums are no longer in use
+    if (m.dict != staged) {
+      // 16-bit image of the dictionary: the run bytes of every entry (the length follows from the code)
+      const uint4* src = (const uint4*)m.dict;
+      uint2* dst = (uint2*)lds_dict;
+      const uint32_t n4 = m.dict_words / 4;
+      for (uint32_t base = 0; base < n4; base += kDictRegs * n_threads) {
+        uint4 v[kDictRegs];
+#pragma unroll
+        for (int k = 0; k < kDictRegs; ++k) v[k] = src[min(base + k * n_threads + tid, n4 - 1)];
+#pragma unroll
+        for (int k = 0; k < kDictRegs; ++k) {
+          const uint32_t idx = base + k * n_threads + tid;
+          if (idx < n4) dst[idx] = make_uint2((v[k].x & 0xFFFFu) | v[k].y << 16, (v[k].z & 0xFFFFu) | v[k].w << 16);
+        }
+      }
+      staged = m.dict;
+    }
+    __syncthreads();
+    const uint32_t strip = m.seg_cols + 8;   // bytes between the strips of two lanes
+    const uint32_t my_strip = lds_address(tiles) + (uint32_t)wave * 64u * strip + (uint32_t)lane * strip;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f}, head_acc = {0.f, 0.f, 0.f, 0.f}, tail_acc = {0.f, 0.f, 0.f, 0.f};
+    int head_band = -1, tail_band = -1;
+    if (u0 < u1) {
+      uint32_t u = u0, q = u0 % nq, band = u0 / nq;
+      uint32_t ubound = unit_offset(m, u0 + 1) - c0;
+      bool whole = q == 0;
+      const uint32_t n_panels = (m.cols + m.seg_cols - 1) / m.seg_cols;
+      auto segment_end = [&](uint32_t quad) {   // LDS address one past the lane's segment in the unit (band, quad)
+        const uint32_t row = band * kUnitRows + (lane & 15), panel = quad * kUnitPanels + (lane >> 4);
+        uint32_t len = 0;
+        if (row < m.rows && panel < n_panels) len = min(m.seg_cols, m.cols - panel * m.seg_cols);
+        return my_strip + len;
+      };
+      uint32_t ptr = my_strip, end = segment_end(q);
+      auto multiply_unit = [&]() {   // the unit (band, q) is complete in the tile
+        const uint32_t col0 = q * kUnitPanels * m.seg_cols;                       // first column of the unit
+        const uint32_t width = min(m.seg_cols, m.cols - col0), n_win = (width + 7) / 8;   // its widest segment is the first panel's
+        const uint32_t xcol = col0 + (uint32_t)kg * m.seg_cols;
+        uint4 xf[kMfmaAhead];
+#pragma unroll
+        for (int k = 0; k < kMfmaAhead; ++k) xf[k] = load_x_fragment<kXFast>(job.x, m.cols, a.batch, bn, xcol + 8 * k);
+        for (uint32_t w = 0; w < n_win; w += kMfmaAhead) {
+#pragma unroll
+          for (int k = 0; k < kMfmaAhead; ++k) {
+            if (w + k < n_win) {
+              const u32x2 a8v = *(lds_cu64*)(size_t)(my_strip + 8 * (w + k));
+              const uint2 a8 = make_uint2(a8v.x, a8v.y);
+              const uint4 xb = xf[k];
+              xf[k] = load_x_fragment<kXFast>(job.x, m.cols, a.batch, bn, xcol + 8 * (w + k + kMfmaAhead));
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(a8), __builtin_bit_cast(bf16x8, xb), acc, 0, 0, 0);
+            }
+          }
+        }
+      };
+      auto finish_band = [&](bool complete) {
+        if (complete) {
+          // accumulator register v of lane l: row 4 * (l / 16) + v of the band, batch row l % 16
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const uint32_t row = band * kUnitRows + 4 * kg + v;
+            if (bn < a.batch && row < m.rows) job.y[(size_t)bn * m.rows + row] = acc[v] * m.scales[row];
+          }
+        } else if (!whole) {   // band begun by an earlier wavefront
+          head_acc = acc;
+          head_band = (int)band;
+        } else {               // band left unfinished
+          tail_acc = acc;
+          tail_band = (int)band;
+        }
+        acc = f32x4{0.f, 0.f, 0.f, 0.f};
+      };
+      for (uint32_t r = 0; r < n_chunks; r += kD) {
+        static_for<kD>([&](auto dd) {
+          constexpr int d = decltype(dd)::value;
+          if (r + d < n_chunks) {
+            if (r + d == ubound) {   // the unit's last chunk has been appended
+              multiply_unit();
+              ++u;
+              if (++q == nq) {
+                finish_band(whole);
+                q = 0;
+                ++band;
+                whole = true;
+              }
+              ubound = unit_offset(m, u + 1) - c0;
+              ptr = my_strip;
+              end = segment_end(q);
+            }
+            append_chunk(cw[d], ptr, end);
+          }
+          cw[d] = p[(size_t)min(r + d + kD, n_chunks - 1) * 64];
+        });
+      }
+      multiply_unit();
+      finish_band(whole && (u1 % nq == 0));
+    }
+    __syncthreads();   // every wavefront is done with its tile: the partial sums go over the tile area
+    float* slot_val = (float*)tiles;                                 // [2 * n_waves][256]
+    int* slot_band = (int*)((uint8_t*)lds4 + a.slot_off);            // [2 * n_waves]
+    if (lane == 0) {
+      slot_band[2 * wave] = head_band;
+      slot_band[2 * wave + 1] = tail_band;
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      slot_val[(2 * wave) * 256 + v * 64 + lane] = head_acc[v];
+      slot_val[(2 * wave + 1) * 256 + v * 64 + lane] = tail_acc[v];
+    }
+    __syncthreads();
+    for (int o = tid; o < 2 * n_waves * 256; o += n_threads) {
+      const int s = o >> 8, e = o & 255;
+      const int bnd = slot_band[s];
+      bool first = bnd >= 0;
+      for (int t = 0; t < s; ++t) first = first && slot_band[t] != bnd;
+      if (first) {
+        float sum = slot_val[s * 256 + e];
+        for (int t = s + 1; t < 2 * n_waves; ++t)
+          if (slot_band[t] == bnd) sum += slot_val[t * 256 + e];
+        const int v = e >> 6, l = e & 63;
+        const uint32_t row = (uint32_t)bnd * kUnitRows + 4 * (l >> 4) + v;
+        const int b = l & 15;
+        if (b < a.batch && row < m.rows) job.y[(size_t)b * m.rows + row] = sum * m.scales[row];
+      }
+    }
+  }
+}
+
 // Expansion to the row-major int8 matrix.  The units are split into one contiguous run per wavefront of the grid.
 // A wavefront decodes a unit into its own LDS tile (lane l writes the run bytes of its segment one after the other:
 // both bytes of the dictionary entry are stored, and the second byte of a single-byte entry is overwritten by the
@@ -599,6 +842,8 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   // Dynamic LDS above 64 KB has to be allowed per kernel function.
   e = hipFuncSetAttribute((const void*)k_matvec<kDepth>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_decompress, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<kDepth, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<kDepth, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
 
   const uint8_t* src = (const uint8_t*)blob;
@@ -672,14 +917,38 @@ int launch_matvec(int n, const tq_handle* hs, const void* const* xs, void* const
     set_error("more than 2^36 weights in one launch are not supported");
     return TQ_E_UNSUPPORTED;
   }
+  // Every workgroup's share of the cost line is at least one band of the most expensive kind, and there is one
+  // workgroup per CU at most.
+  const uint64_t grid = std::max<uint64_t>(1, std::min<uint64_t>({(uint64_t)hs[0]->n_cu, bands, cost / band_cost_max}));
+  if (batch > 1) {
+    // MFMA path.  LDS: 16-bit dictionary image | one tile (64 strips) per wavefront, reused for the partial sums | slot ids.
+    uint32_t seg_max = 0;
+    bool fast = true;
+    for (int i = 0; i < n; ++i) {
+      seg_max = std::max(seg_max, hs[i]->m.seg_cols);
+      fast = fast && hs[i]->m.cols % 8 == 0 && (uintptr_t)xs[i] % 16 == 0;
+    }
+    const size_t dict16 = round_up((uint64_t)dict_words_max * 2, 16);
+    const size_t area = std::max<size_t>((size_t)64 * (seg_max + 8), 2048);   // per wavefront: its tile, later two slots of 1 KB
+    const size_t waves = std::min<size_t>(kWaves, (kLdsLimit - dict16 - 64) / area);
+    if (waves == 0) {
+      set_error("segments of " + std::to_string(seg_max) + " columns do not fit the LDS tile of the batched product");
+      return TQ_E_UNSUPPORTED;
+    }
+    a.x_off = (uint32_t)dict16;
+    a.slot_off = (uint32_t)(dict16 + waves * area);
+    const size_t lds = a.slot_off + 64;
+    if (fast) hipLaunchKernelGGL((k_matvec_mfma<kDepth, true>), dim3((unsigned)grid), dim3((unsigned)waves * 64), lds, stream, a);
+    else hipLaunchKernelGGL((k_matvec_mfma<kDepth, false>), dim3((unsigned)grid), dim3((unsigned)waves * 64), lds, stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("tq_matvec launch", e);
+    return TQ_OK;
+  }
   size_t lds_total;
   if (!plan_matvec_lds(dict_words_max, x_dwords_max, &a.x_off, &a.slot_off, &lds_total)) {
     set_error("the matrices of this call together need " + std::to_string(lds_total) + " bytes of LDS (largest dictionary plus longest row)");
     return TQ_E_UNSUPPORTED;
   }
-  // Every workgroup's share of the cost line is at least one band of the most expensive kind, and there is one
-  // workgroup per CU at most.
-  const uint64_t grid = std::max<uint64_t>(1, std::min<uint64_t>({(uint64_t)hs[0]->n_cu, bands, cost / band_cost_max}));
   hipLaunchKernelGGL(k_matvec<kDepth>, dim3((unsigned)grid), dim3(kThreads), lds_total, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail("tq_matvec launch", e);
