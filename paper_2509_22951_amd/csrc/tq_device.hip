@@ -453,19 +453,143 @@ __device__ __forceinline__ void append_chunk(uint2 c, uint32_t& ptr, uint32_t en
   put(e3, l3);
 }
 
-// Activation fragment of one MFMA step: 8 consecutive bf16 of batch row n starting at column col (zero outside).
-template <bool kFast>
-__device__ __forceinline__ uint4 load_x_fragment(const uint16_t* __restrict__ x, uint32_t cols, int batch, int n, uint32_t col) {
-  if (n >= batch || col >= cols) return make_uint4(0, 0, 0, 0);
-  const uint16_t* p = x + (size_t)n * cols + col;
-  if (kFast) return *(const uint4*)p;   // cols % 8 == 0 and x 16-byte aligned: the 8 columns exist and the load is aligned
-  uint32_t e[8];
+// Decode the units [u0, u1) of a matrix, one after the other, into the strips of this wavefront's tile and call
+// on_unit(band, quad) each time the tile holds a complete unit.  The code chunks of the run are contiguous in memory.
+// They are fetched in pieces of at most kPiece chunks that never straddle a unit (a unit is cut into equal pieces);
+// two register sets alternate, so the loads of the next piece are in flight while the current one is decoded.
+constexpr int kPiece = 16;
+
+template <typename OnUnit>
+__device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0, uint32_t u1, int lane, uint32_t my_strip, OnUnit&& on_unit) {
+  if (u0 >= u1) return;
+  const uint2* codes = m.codes + lane;
+  const uint32_t nq = m.n_quads, n_panels = (m.cols + m.seg_cols - 1) / m.seg_cols;
+  // walker over the pieces of the run: unit, pieces left in it, next chunk
+  uint32_t wu = u0, wc = unit_offset(m, u0), w_left = 0, w_base = 0, w_rem = 0;
+  auto next_piece = [&](uint32_t& start, uint32_t& n, bool& ends) {
+    if (w_left == 0) {
+      if (wu == u1) {
+        n = 0;
+        ends = false;
+        start = wc;
+        return;
+      }
+      const uint32_t len = unit_offset(m, wu + 1) - wc;
+      w_left = (len + kPiece - 1) / kPiece;
+      w_base = len / w_left;
+      w_rem = len - w_base * w_left;
+      ++wu;
+    }
+    n = w_base + (w_rem ? 1u : 0u);
+    if (w_rem) --w_rem;
+    start = wc;
+    wc += n;
+    ends = --w_left == 0;
+  };
+  auto load_piece = [&](uint2 (&cw)[kPiece], uint32_t start, uint32_t n) {
 #pragma unroll
-  for (int k = 0; k < 8; ++k) e[k] = col + k < cols ? (uint32_t)p[k] : 0u;
-  return make_uint4(e[0] | e[1] << 16, e[2] | e[3] << 16, e[4] | e[5] << 16, e[6] | e[7] << 16);
+    for (int k = 0; k < kPiece; ++k)
+      if ((uint32_t)k < n) cw[k] = codes[(size_t)(start + k) * 64];
+  };
+  // decoder state: the unit being filled
+  uint32_t band = u0 / nq, quad = u0 - band * nq;
+  auto segment_end = [&]() {   // LDS address one past the lane's segment in the unit (band, quad)
+    const uint32_t row = band * kUnitRows + (lane & 15), panel = quad * kUnitPanels + (lane >> 4);
+    uint32_t len = 0;
+    if (row < m.rows && panel < n_panels) len = min(m.seg_cols, m.cols - panel * m.seg_cols);
+    return my_strip + len;
+  };
+  uint32_t ptr = my_strip, end = segment_end();
+  auto decode_piece = [&](const uint2 (&cw)[kPiece], uint32_t n, bool ends) {
+#pragma unroll
+    for (int k = 0; k < kPiece; ++k)
+      if ((uint32_t)k < n) append_chunk(cw[k], ptr, end);
+    if (ends) {
+      on_unit(band, quad);
+      if (++quad == nq) {
+        quad = 0;
+        ++band;
+      }
+      ptr = my_strip;
+      end = segment_end();
+    }
+  };
+  uint2 cwa[kPiece], cwb[kPiece];
+  uint32_t sa, na, sb, nb;
+  bool ea, eb;
+  next_piece(sa, na, ea);
+  load_piece(cwa, sa, na);
+  while (na) {
+    next_piece(sb, nb, eb);
+    load_piece(cwb, sb, nb);
+    decode_piece(cwa, na, ea);
+    next_piece(sa, na, ea);
+    load_piece(cwa, sa, na);
+    decode_piece(cwb, nb, eb);
+  }
 }
 
-constexpr int kMfmaAhead = 4;   // activation fragments loaded ahead of their MFMA
+typedef __attribute__((address_space(1))) const uint16_t global_cu16;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) const u32x4 global_cu128;
+
+// Activation fragment of one MFMA step: 8 consecutive bf16 of one batch row starting at column col.  The load is
+// unconditional (columns past the end of the row are clamped into it) so that several of them can be in flight without
+// the compiler waiting for each; mask_x_fragment zeroes what lies past the row's end before use.
+template <bool kFast>
+__device__ __forceinline__ uint4 load_x_fragment(global_cu16* xrow, uint32_t cols, uint32_t col) {
+  if (kFast) {   // cols % 8 == 0 and x 16-byte aligned
+    const u32x4 v = *(global_cu128*)(xrow + min(col, cols - 8));
+    return make_uint4(v.x, v.y, v.z, v.w);
+  }
+  uint32_t e[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) e[k] = xrow[min(col + k, cols - 1)];
+  return make_uint4(e[0] | e[1] << 16, e[2] | e[3] << 16, e[4] | e[5] << 16, e[6] | e[7] << 16);
+}
+template <bool kFast>
+__device__ __forceinline__ uint4 mask_x_fragment(uint4 v, uint32_t cols, uint32_t col) {
+  if (kFast) return col < cols ? v : make_uint4(0, 0, 0, 0);
+  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    if (col + k >= cols) w[k >> 1] &= (k & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+constexpr int kMfmaGroup = 8;   // MFMA steps per group: the activation fragments of the next group load while this one runs
+
+// The MFMA steps of one decoded unit: step w multiplies bytes [8 w, 8 w + 8) of every lane's strip (16 rows x 4 panels
+// x 8 columns, converted to bf16) with the activations of those 32 columns.  n_win and ragged are wave-uniform.
+template <bool kFast, bool kRagged>
+__device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, global_cu16* xrow, uint32_t cols, uint32_t xcol, uint32_t n_win) {
+  uint4 xa[kMfmaGroup], xb[kMfmaGroup];
+#pragma unroll
+  for (int k = 0; k < kMfmaGroup; ++k) xa[k] = load_x_fragment<kFast>(xrow, cols, xcol + 8 * k);
+  for (uint32_t w = 0; w < n_win; w += 2 * kMfmaGroup) {
+#pragma unroll
+    for (int k = 0; k < kMfmaGroup; ++k) xb[k] = load_x_fragment<kFast>(xrow, cols, xcol + 8 * (w + kMfmaGroup + k));
+#pragma unroll
+    for (int k = 0; k < kMfmaGroup; ++k) {
+      if (w + k < n_win) {
+        const u32x2 a8 = *(lds_cu64*)(size_t)(my_strip + 8 * (w + k));
+        const uint4 x8 = kRagged ? mask_x_fragment<kFast>(xa[k], cols, xcol + 8 * (w + k)) : xa[k];
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8.x, a8.y)), __builtin_bit_cast(bf16x8, x8), acc, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < kMfmaGroup; ++k) xa[k] = load_x_fragment<kFast>(xrow, cols, xcol + 8 * (w + 2 * kMfmaGroup + k));
+#pragma unroll
+    for (int k = 0; k < kMfmaGroup; ++k) {
+      if (w + kMfmaGroup + k < n_win) {
+        const u32x2 a8 = *(lds_cu64*)(size_t)(my_strip + 8 * (w + kMfmaGroup + k));
+        const uint4 x8 = kRagged ? mask_x_fragment<kFast>(xb[k], cols, xcol + 8 * (w + kMfmaGroup + k)) : xb[k];
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8.x, a8.y)), __builtin_bit_cast(bf16x8, x8), acc, 0, 0, 0);
+      }
+    }
+  }
+  return acc;
+}
 
 template <int kD, bool kXFast>
 __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
@@ -492,16 +616,6 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
     const uint32_t unit_lo = band_lo * nq, n_units = (band_hi - band_lo) * nq;
     const uint32_t u0 = unit_lo + (uint32_t)((uint64_t)n_units * wave / n_waves);
     const uint32_t u1 = unit_lo + (uint32_t)((uint64_t)n_units * (wave + 1) / n_waves);
-    const uint32_t c0 = u0 < u1 ? unit_offset(m, u0) : 0u, n_chunks = u0 < u1 ? unit_offset(m, u1) - c0 : 0u;
-    const uint2* p = m.codes + (size_t)c0 * 64 + lane;
-    uint2 cw[kD];
-    if (u0 < u1) {
-#pragma unroll
-      for (int d = 0; d < kD; ++d) {
-        cw[d] = p[(size_t)min((uint32_t)d, n_chunks - 1) * 64];
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
     __syncthreads();   // the previous matrix's dictionary and partial sums are no longer in use
     if (m.dict != staged) {
       // 16-bit image of the dictionary: the run bytes of every entry (the length follows from the code)
@@ -525,80 +639,38 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
     const uint32_t my_strip = lds_address(tiles) + (uint32_t)wave * 64u * strip + (uint32_t)lane * strip;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f}, head_acc = {0.f, 0.f, 0.f, 0.f}, tail_acc = {0.f, 0.f, 0.f, 0.f};
     int head_band = -1, tail_band = -1;
-    if (u0 < u1) {
-      uint32_t u = u0, q = u0 % nq, band = u0 / nq;
-      uint32_t ubound = unit_offset(m, u0 + 1) - c0;
-      bool whole = q == 0;
-      const uint32_t n_panels = (m.cols + m.seg_cols - 1) / m.seg_cols;
-      auto segment_end = [&](uint32_t quad) {   // LDS address one past the lane's segment in the unit (band, quad)
-        const uint32_t row = band * kUnitRows + (lane & 15), panel = quad * kUnitPanels + (lane >> 4);
-        uint32_t len = 0;
-        if (row < m.rows && panel < n_panels) len = min(m.seg_cols, m.cols - panel * m.seg_cols);
-        return my_strip + len;
-      };
-      uint32_t ptr = my_strip, end = segment_end(q);
-      auto multiply_unit = [&]() {   // the unit (band, q) is complete in the tile
-        const uint32_t col0 = q * kUnitPanels * m.seg_cols;                       // first column of the unit
-        const uint32_t width = min(m.seg_cols, m.cols - col0), n_win = (width + 7) / 8;   // its widest segment is the first panel's
-        const uint32_t xcol = col0 + (uint32_t)kg * m.seg_cols;
-        uint4 xf[kMfmaAhead];
-#pragma unroll
-        for (int k = 0; k < kMfmaAhead; ++k) xf[k] = load_x_fragment<kXFast>(job.x, m.cols, a.batch, bn, xcol + 8 * k);
-        for (uint32_t w = 0; w < n_win; w += kMfmaAhead) {
-#pragma unroll
-          for (int k = 0; k < kMfmaAhead; ++k) {
-            if (w + k < n_win) {
-              const u32x2 a8v = *(lds_cu64*)(size_t)(my_strip + 8 * (w + k));
-              const uint2 a8 = make_uint2(a8v.x, a8v.y);
-              const uint4 xb = xf[k];
-              xf[k] = load_x_fragment<kXFast>(job.x, m.cols, a.batch, bn, xcol + 8 * (w + k + kMfmaAhead));
-              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(a8), __builtin_bit_cast(bf16x8, xb), acc, 0, 0, 0);
-            }
-          }
-        }
-      };
-      auto finish_band = [&](bool complete) {
-        if (complete) {
-          // accumulator register v of lane l: row 4 * (l / 16) + v of the band, batch row l % 16
+    // lanes past the batch repeat its last row: their output columns are never stored
+    global_cu16* xrow = (global_cu16*)job.x + (size_t)min(bn, a.batch - 1) * m.cols;
+    const uint32_t first_band = u0 / nq;
+    const bool first_whole = u0 % nq == 0;
+    decode_run_to_tile(m, u0, u1, lane, my_strip, [&](uint32_t band, uint32_t quad) {
+      const uint32_t col0 = quad * kUnitPanels * m.seg_cols;                            // first column of the unit
+      const uint32_t width = min(m.seg_cols, m.cols - col0);                            // its widest segment is the first panel's
+      const uint32_t n_win = (width + 7) / 8;
+      const uint32_t xcol = col0 + (uint32_t)kg * m.seg_cols;
+      if (!kXFast || col0 + kUnitPanels * m.seg_cols > m.cols)   // some fragment reaches past the row's end
+        acc = multiply_unit<kXFast, true>(acc, my_strip, xrow, m.cols, xcol, n_win);
+      else
+        acc = multiply_unit<kXFast, false>(acc, my_strip, xrow, m.cols, xcol, n_win);
+      const bool band_ends = quad + 1 == nq, run_ends = band * nq + quad + 1 == u1;
+      if (band_ends || run_ends) {
+        if (band_ends && (band != first_band || first_whole)) {
+          // the whole band lies in this wavefront's run.  Accumulator register v of lane l: row 4 * (l / 16) + v, batch row l % 16
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             const uint32_t row = band * kUnitRows + 4 * kg + v;
             if (bn < a.batch && row < m.rows) job.y[(size_t)bn * m.rows + row] = acc[v] * m.scales[row];
           }
-        } else if (!whole) {   // band begun by an earlier wavefront
+        } else if (band == first_band && !first_whole) {   // band begun by an earlier wavefront
           head_acc = acc;
           head_band = (int)band;
-        } else {               // band left unfinished
+        } else {                                           // band left unfinished
           tail_acc = acc;
           tail_band = (int)band;
         }
         acc = f32x4{0.f, 0.f, 0.f, 0.f};
-      };
-      for (uint32_t r = 0; r < n_chunks; r += kD) {
-        static_for<kD>([&](auto dd) {
-          constexpr int d = decltype(dd)::value;
-          if (r + d < n_chunks) {
-            if (r + d == ubound) {   // the unit's last chunk has been appended
-              multiply_unit();
-              ++u;
-              if (++q == nq) {
-                finish_band(whole);
-                q = 0;
-                ++band;
-                whole = true;
-              }
-              ubound = unit_offset(m, u + 1) - c0;
-              ptr = my_strip;
-              end = segment_end(q);
-            }
-            append_chunk(cw[d], ptr, end);
-          }
-          cw[d] = p[(size_t)min(r + d + kD, n_chunks - 1) * 64];
-        });
       }
-      multiply_unit();
-      finish_band(whole && (u1 % nq == 0));
-    }
+    });
     __syncthreads();   // every wavefront is done with its tile: the partial sums go over the tile area
     float* slot_val = (float*)tiles;                                 // [2 * n_waves][256]
     int* slot_band = (int*)((uint8_t*)lds4 + a.slot_off);            // [2 * n_waves]
