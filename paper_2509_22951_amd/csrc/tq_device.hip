@@ -84,6 +84,24 @@ __device__ __forceinline__ void static_for(F&& f) {
 // space makes them scalar loads, which do not share a counter with the vector loads of the code stream.
 __device__ __forceinline__ uint32_t unit_offset(const DevMat& m, uint32_t u) { return ((const_u32*)m.uoff)[u]; }
 
+// Loads and stores of device memory through the global address space.  Pointers that come out of a matrix description
+// read from memory are generic to the compiler; a generic access is a flat instruction, which counts on the LDS counter
+// as well as on the vector-memory one and so would make every LDS wait a wait for the code stream too.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint2 global_load(const uint2* p) {
+  const u32x2 v = *(__attribute__((address_space(1))) const u32x2*)p;
+  return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ uint4 global_load(const uint4* p) {
+  const u32x4 v = *(__attribute__((address_space(1))) const u32x4*)p;
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint32_t global_load(const uint32_t* p) { return *(__attribute__((address_space(1))) const uint32_t*)p; }
+__device__ __forceinline__ uint32_t global_load(const uint16_t* p) { return *(__attribute__((address_space(1))) const uint16_t*)p; }
+__device__ __forceinline__ float global_load(const float* p) { return *(__attribute__((address_space(1))) const float*)p; }
+__device__ __forceinline__ void global_store(float* p, float v) { *(__attribute__((address_space(1))) float*)p = v; }
+
 // A matrix description from device memory, through scalar loads.
 __device__ __forceinline__ DevMat load_description(const DevMat* p) {
   static_assert(sizeof(DevMat) % 4 == 0, "whole dwords");
@@ -146,7 +164,7 @@ __device__ __forceinline__ void issue_dictionary(const DevMat& m, uint32_t base,
   const uint4* src = (const uint4*)m.dict;
   const uint32_t n4 = m.dict_words / 4;
 #pragma unroll
-  for (int k = 0; k < kDictRegs; ++k) v[k] = src[min(base + k * kThreads + tid, n4 - 1)];
+  for (int k = 0; k < kDictRegs; ++k) v[k] = global_load(src + min(base + k * kThreads + tid, n4 - 1));
 }
 // Container word (b0, b1, -, length) -> (bf16(b0), bf16(b1)).  Bytes past an entry's length are zero in the container,
 // so a single-byte entry gets a zero second weight and the pad entry two.
@@ -171,11 +189,11 @@ __device__ __forceinline__ void issue_activations(const DevMat& m, const uint16_
   for (int k = 0; k < kXRegs; ++k) {
     const uint32_t j = first_pair + k * kThreads + tid, col = 2 * j;
     if (kAligned) {   // x is 4-byte aligned and cols is even
-      lo[k] = col < m.cols ? ((const uint32_t*)x)[j] : 0u;
-      hi[k] = col + 2 < m.cols ? ((const uint32_t*)x)[j + 1] : 0u;
+      lo[k] = col < m.cols ? global_load((const uint32_t*)x + j) : 0u;
+      hi[k] = col + 2 < m.cols ? global_load((const uint32_t*)x + j + 1) : 0u;
     } else {
-      lo[k] = (col < m.cols ? (uint32_t)x[col] : 0u) | (col + 1 < m.cols ? (uint32_t)x[col + 1] << 16 : 0u);
-      hi[k] = col + 2 < m.cols ? (uint32_t)x[col + 2] : 0u;
+      lo[k] = (col < m.cols ? global_load(x + col) : 0u) | (col + 1 < m.cols ? global_load(x + col + 1) << 16 : 0u);
+      hi[k] = col + 2 < m.cols ? global_load(x + col + 2) : 0u;
     }
   }
 }
@@ -289,7 +307,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
       if (u0 < u1) {
 #pragma unroll
         for (int d = 0; d < kD; ++d) {
-          cw[d] = p[(size_t)min((uint32_t)d, n_chunks - 1) * 64];
+          cw[d] = global_load(p + (size_t)min((uint32_t)d, n_chunks - 1) * 64);
           __builtin_amdgcn_sched_barrier(0);   // issue in consumption order: loads return in order, the loop waits per slot
         }
       }
@@ -330,7 +348,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
           const float v = sum_over_panels(a0 + a1);
           if (complete) {
             const uint32_t row = band * kUnitRows + lane;
-            if (lane < 16 && row < m.rows) yb[row] = v * m.scales[row];
+            if (lane < 16 && row < m.rows) global_store(yb + row, v * global_load(m.scales + row));
           } else {
             const int s = 2 * wave + (whole ? 1 : 0);   // slot 2w: band begun by an earlier wavefront; 2w + 1: band left unfinished
             if (lane < 16) slot_val[s * 16 + lane] = v;
@@ -360,7 +378,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
               issue_chunk<4 * d>(cw[d], xa, ops[d & 1]);
               finish_chunk(ops[(d + 1) & 1], a0, a1);
             }
-            cw[d] = p[(size_t)min(r + d + kD, n_chunks - 1) * 64];   // refill the slot only after its last use
+            cw[d] = global_load(p + (size_t)min(r + d + kD, n_chunks - 1) * 64);   // refill the slot only after its last use
           });
           xa += 16 * kD;
         }
@@ -380,7 +398,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
           for (int t = s + 1; t < 2 * kWaves; ++t)
             if (slot_band[t] == bnd) sum += slot_val[t * 16 + r16];
           const uint32_t row = (uint32_t)bnd * kUnitRows + r16;
-          if (row < m.rows) yb[row] = sum * m.scales[row];
+          if (row < m.rows) global_store(yb + row, sum * global_load(m.scales + row));
         }
       }
     }
@@ -401,7 +419,6 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) const u32x2 lds_cu64;
 
 // Byte offset of the 16-bit dictionary entry of the code in the low / high half of a packed code pair.
@@ -489,7 +506,7 @@ __device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0,
   auto load_piece = [&](uint2 (&cw)[kPiece], uint32_t start, uint32_t n) {
 #pragma unroll
     for (int k = 0; k < kPiece; ++k)
-      if ((uint32_t)k < n) cw[k] = codes[(size_t)(start + k) * 64];
+      if ((uint32_t)k < n) cw[k] = global_load(codes + (size_t)(start + k) * 64);
   };
   // decoder state: the unit being filled
   uint32_t band = u0 / nq, quad = u0 - band * nq;
@@ -530,7 +547,6 @@ __device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0,
 }
 
 typedef __attribute__((address_space(1))) const uint16_t global_cu16;
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) const u32x4 global_cu128;
 
 // Activation fragment of one MFMA step: 8 consecutive bf16 of one batch row starting at column col.  The load is
@@ -625,7 +641,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
       for (uint32_t base = 0; base < n4; base += kDictRegs * n_threads) {
         uint4 v[kDictRegs];
 #pragma unroll
-        for (int k = 0; k < kDictRegs; ++k) v[k] = src[min(base + k * n_threads + tid, n4 - 1)];
+        for (int k = 0; k < kDictRegs; ++k) v[k] = global_load(src + min(base + k * n_threads + tid, n4 - 1));
 #pragma unroll
         for (int k = 0; k < kDictRegs; ++k) {
           const uint32_t idx = base + k * n_threads + tid;
@@ -659,7 +675,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             const uint32_t row = band * kUnitRows + 4 * kg + v;
-            if (bn < a.batch && row < m.rows) job.y[(size_t)bn * m.rows + row] = acc[v] * m.scales[row];
+            if (bn < a.batch && row < m.rows) global_store(job.y + (size_t)bn * m.rows + row, acc[v] * global_load(m.scales + row));
           }
         } else if (band == first_band && !first_whole) {   // band begun by an earlier wavefront
           head_acc = acc;
@@ -696,7 +712,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
         const int v = e >> 6, l = e & 63;
         const uint32_t row = (uint32_t)bnd * kUnitRows + 4 * (l >> 4) + v;
         const int b = l & 15;
-        if (b < a.batch && row < m.rows) job.y[(size_t)b * m.rows + row] = sum * m.scales[row];
+        if (b < a.batch && row < m.rows) global_store(job.y + (size_t)b * m.rows + row, sum * global_load(m.scales + row));
       }
     }
   }
