@@ -23,10 +23,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # HBM traffic of the matvec launches measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the default workload
-# (config 4, batch 1, default encoder options), scaled by a plain 1 GiB copy in the same run
-# (profiles/k_matvec_config4_batch1_hbm_traffic.txt): bytes read per algorithmic byte, bytes written per step.
-MEASURED_FETCH_PER_ALGORITHMIC_BYTE = 1.073
-MEASURED_WRITE_BYTES_PER_STEP = 3_609_600
+# (config 4, batch 1, default encoder options, whole sweep in one tq_matvec_multi call), scaled by a plain 1 GiB copy in
+# the same run (profiles/k_matvec_config4_batch1_hbm_traffic.txt): bytes read per algorithmic byte, bytes written per step.
+MEASURED_FETCH_PER_ALGORITHMIC_BYTE = 1.0077
+MEASURED_WRITE_BYTES_PER_STEP = 22_256_000
 
 
 def parse_args():
@@ -46,6 +46,9 @@ def parse_args():
                     help="sequence: one LZW dictionary runs over the matrices in sweep order and freezes when full "
                          "(the table of paper section 4 is built over all parameters); matrix: every matrix starts from the 256 singles")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-layers", type=int, default=8,
+                    help="layers of the sweep the CPU oracle is timed on (8 layers = 56 matrices take about 10 s on one core)")
+    ap.add_argument("--no-decompress", action="store_true", help="skip the tq_decompress pass over all matrices")
     ap.add_argument("--layers", type=int, default=0, help="debug: keep only the first N layers (+ lm_head)")
     ap.add_argument("--fuse", choices=["none", "independent", "layer", "sweep"], default="sweep",
                     help="how the products of a step are grouped into launches.  sweep: the step is a list of independent "
@@ -81,7 +84,7 @@ def main():
     t_setup = time.time()
 
     # ---- encode (host, off the hot path): generate -> quantize -> dictionary-code, a few matrices at a time
-    sample_names = {s.name for s in specs[:7]}          # the first layer doubles as the CPU-oracle sample
+    sample_names = {s.name for s in specs[:7 * args.cpu_sample_layers]}   # the first layers double as the CPU-oracle sample
     sample_blobs = {}
     workers = max(1, min(args.threads, 8))
     inner = max(1, args.threads // workers)
@@ -190,6 +193,32 @@ def main():
         others[str(args.also_batch)] = {"ms_per_step": round(w2, 4), "GBps": round(comp_bytes / w2 / 1e6, 1),
                                         "tokens_per_s": round(args.also_batch / (w2 * 1e-3), 1)}
 
+    decompress = None
+    if not args.no_decompress:
+        out = torch.empty(n_weights, dtype=torch.int8, device=dev)          # the whole model expanded, matrix after matrix
+        offs = np.cumsum([0] + [s.rows * s.cols for s in specs])
+        handles, ptrs = [m.handle for m in mats], [out.data_ptr() + int(o) for o in offs[:-1]]
+        def expand():
+            tq.tq_decompress_multi(handles, ptrs, stream)
+        for _ in range(5):
+            expand()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        e0.record()
+        for _ in range(reps):
+            expand()
+        e1.record()
+        torch.cuda.synchronize()
+        d_ms = e0.elapsed_time(e1) / reps
+        decompress = {"ms_per_model": round(d_ms, 3), "kernel_launches": -(-len(mats) // 128),
+                      "GBps_read_plus_write": round((comp_bytes + n_weights) / d_ms / 1e6, 1),
+                      "GBps_written": round(n_weights / d_ms / 1e6, 1)}
+        del out
+
+    n_launches = sum(-(-len(g) // 128) for g in groups)     # tq_matvec_multi serves up to 128 matrices per kernel launch
+    profiled = (args.config == 4 and args.batch == 1 and args.fuse == "sweep" and args.dictionary == "sequence"
+                and not (args.max_entries or args.lmax or args.seg_cols or args.layers))
     gbps = comp_bytes / wall_ms / 1e6
     ach = comp_bytes / ev_ms / 1e6
     result = {
@@ -213,19 +242,21 @@ def main():
             "bytes_per_weight": round(comp_bytes / n_weights, 4), "weights_per_code": round(n_weights / n_codes, 4),
             "weights_per_real_code": round(n_weights / sum(i["n_real_codes"] for i in infos), 4),
             "max_entries": infos[0]["n_entries"], "lmax": infos[0]["lmax"], "seg_cols": infos[0]["seg_cols"],
-            "dictionary": args.dictionary, "fuse": args.fuse, "multi_calls_per_step": len(groups),
+            "dictionary": args.dictionary, "fuse": args.fuse, "kernel_launches_per_step": n_launches,
         },
         "roofline": {
             "bound": "hbm", "kernel": "tq::k_matvec",
             "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-            "traffic": (round((MEASURED_FETCH_PER_ALGORITHMIC_BYTE * comp_bytes + MEASURED_WRITE_BYTES_PER_STEP) / len(groups))
-                        if False
-                        else None),
-            "note": "achieved = compressed bytes of the sweep / HIP-event time of one step on the launch stream "
-                    "(= mean bytes per launch / mean launch duration, launches back to back); traffic = HBM bytes per "
-                    "launch from the FETCH_SIZE/WRITE_SIZE counter runs under profiles/ (null off the profiled workload)",
+            "traffic": (round((MEASURED_FETCH_PER_ALGORITHMIC_BYTE * comp_bytes + MEASURED_WRITE_BYTES_PER_STEP) / n_launches)
+                        if profiled else None),
+            "algorithmic_bytes_per_launch": round(comp_bytes / n_launches),
+            "launch_us": round(ev_ms * 1e3 / n_launches, 1),
+            "note": "achieved = algorithmic (compressed) bytes per launch / mean launch duration, from HIP events on the "
+                    "launch stream around the timed steps (launches back to back); traffic = HBM bytes per launch from "
+                    "the FETCH_SIZE/WRITE_SIZE counter runs under profiles/ (null off the profiled workload)",
         },
         "other_batches": others,
+        "decompress": decompress,
         "setup_s": round(setup_s, 1),
     }
 
@@ -241,7 +272,7 @@ def main():
         sw = sum(specs[i].rows * specs[i].cols for i in sample_blobs)
         result["cpu_baseline"] = {
             "value": round(sb / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"first layer of the sweep ({len(sample_blobs)} matrices, {sw} weights, {dt:.2f} s): decode + "
+            "sample": f"first {args.cpu_sample_layers} layers of the sweep ({len(sample_blobs)} matrices, {sw} weights, {dt:.2f} s): decode + "
                       f"float64 GEMV, batch {args.batch}; whole sweep extrapolates to {dt * n_weights / sw:.1f} s/token",
             "tokens_per_s_extrapolated": round(args.batch / (dt * n_weights / sw), 4),
         }

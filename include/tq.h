@@ -107,19 +107,24 @@ int tq_create_from_encoded(const void *blob, size_t blob_bytes, tq_handle *out);
  * handle, so it may be captured in a HIP graph and called concurrently on different streams.
  * 1 <= batch <= TQ_MAX_BATCH, else TQ_E_UNSUPPORTED.  x and y must stay alive until the stream passes
  * the kernel.  The result is deterministic (fixed summation order).  x values must be finite: a lane that has
- * run out of codes multiplies activations of later columns by zero, so an infinity or NaN anywhere in x makes
- * every output of that batch row non-finite (the plain definition does the same whenever a weight is zero).
+ * run out of codes multiplies activations of later columns by zero, so an infinity or NaN anywhere in x can make
+ * any output of that batch row non-finite (the plain definition does the same wherever a weight is zero).
+ * batch 1 runs the dot-product kernel (activations gathered from an LDS image of x), batch 2..16 the MFMA kernel
+ * (decoded weights pass through an LDS tile; the batch is the N dimension).
  */
 int tq_matvec(tq_handle h, const void *x, void *y, int batch, void *stream);
 
 /*
- * tq_matvec for n independent matrices in one launch (for instance the q, k and v projections of a layer, or gate
- * and up: products that do not depend on each other; the paper's layer-by-layer expansion, Background "Inference",
- * leaves their order free).  hs, xs, ys: host arrays of n handles / device x pointers / device y pointers, with the
- * meaning they have in tq_matvec; all share `batch`.  The workgroups of all matrices are dispatched together, so
- * small matrices fill the GPU side by side.  Results are identical to n tq_matvec calls.  If the matrices cannot be
- * fused (more than 8, dictionaries of different word width) the call issues n single launches instead.
- * Same asynchrony rules as tq_matvec.
+ * tq_matvec for n independent matrices in as few launches as possible (for instance the q, k and v projections of a
+ * layer, or gate and up, or every product of a step when their inputs are all known: products that do not depend on
+ * each other; the paper's layer-by-layer expansion, Background "Inference", leaves their order free).
+ * hs, xs, ys: host arrays of n handles / device x pointers / device y pointers, with the meaning they have in
+ * tq_matvec; all share `batch`.  One kernel launch serves up to 128 matrices: the rows of all of them are cut into
+ * equal shares of work, one per compute unit, so small matrices fill the GPU side by side, and a workgroup stages a
+ * dictionary again only when the next matrix holds a different one (matrices encoded with dict_from share theirs).
+ * Each output is a deterministic function of its matrix, x and the set of matrices in the call (the split of the rows
+ * over workgroups, hence the summation order across a row's segments, depends on that set); it equals what tq_matvec
+ * returns up to that reordering of fp32 additions.  Same asynchrony rules as tq_matvec.
  */
 int tq_matvec_multi(int n, const tq_handle *hs, const void *const *xs, void *const *ys, int batch, void *stream);
 
@@ -129,6 +134,10 @@ int tq_matvec_multi(int n, const tq_handle *hs, const void *const *xs, void *con
  * Same asynchrony rules as tq_matvec.
  */
 int tq_decompress(tq_handle h, void *out, void *stream);
+
+/* tq_decompress for n matrices in as few launches as possible (up to 128 matrices per launch; the work is shared out
+ * as in tq_matvec_multi).  outs: host array of n device pointers, outs[i] as `out` of tq_decompress for hs[i]. */
+int tq_decompress_multi(int n, const tq_handle *hs, void *const *outs, void *stream);
 
 int tq_get_info(tq_handle h, tq_info *out);
 

@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     tq_matvec_multi,
     MultiCall,
     tq_decompress,
+    tq_decompress_multi,
     tq_get_info,
     tq_destroy,
     tq_last_error_string,

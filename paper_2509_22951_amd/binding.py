@@ -18,7 +18,7 @@ _LIB: Optional[ctypes.CDLL] = None
 
 EXPORTS = [
     "tq_encode", "tq_encode_quantized", "tq_free_blob", "tq_validate_blob", "tq_create_from_encoded", "tq_matvec",
-    "tq_matvec_multi", "tq_decompress", "tq_get_info", "tq_destroy", "tq_last_error_string",
+    "tq_matvec_multi", "tq_decompress", "tq_decompress_multi", "tq_get_info", "tq_destroy", "tq_last_error_string",
 ]
 
 
@@ -76,6 +76,8 @@ def load() -> ctypes.CDLL:
     lib.tq_matvec_multi.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
     lib.tq_decompress.restype = ci
     lib.tq_decompress.argtypes = [vp, vp, vp]
+    lib.tq_decompress_multi.restype = ci
+    lib.tq_decompress_multi.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), vp]
     lib.tq_get_info.restype = ci
     lib.tq_get_info.argtypes = [vp, ctypes.POINTER(TqInfo)]
     lib.tq_destroy.restype = ci
@@ -172,6 +174,13 @@ def tq_matvec_multi(handles, x_ptrs, y_ptrs, batch: int, stream: int = 0) -> Non
 
 def tq_decompress(handle: int, out_ptr: int, stream: int = 0) -> None:
     _check(load().tq_decompress(handle, out_ptr, stream))
+
+
+def tq_decompress_multi(handles, out_ptrs, stream: int = 0) -> None:
+    n = len(handles)
+    assert n == len(out_ptrs) and n >= 1
+    arr = ctypes.c_void_p * n
+    _check(load().tq_decompress_multi(n, arr(*handles), arr(*out_ptrs), stream))
 
 
 def tq_get_info(handle: int) -> dict:

@@ -10,7 +10,8 @@
 //   3. tq_matvec gathers the activation pair (x[col], x[col+1]) from an LDS image of x and issues one
 //      v_dot2_f32_bf16 per code; the per-lane sums of the 4 panels of a row are added at the end of a band of 16
 //      rows, multiplied by the row scale and stored,
-//   4. tq_decompress writes the run bytes into a per-wave LDS tile and copies finished tiles out row-major.
+//   4. for batches of 2..16 rows and for tq_decompress the lanes append their run bytes to per-lane strips of an LDS
+//      tile instead; a finished unit is multiplied by bf16 MFMA (batch = N) or copied out row-major.
 // The expanded matrix never exists in HBM on the tq_matvec path.
 #include <hip/hip_runtime.h>
 
@@ -59,7 +60,9 @@ struct Job {
 // The launch's cost line: matrix i covers [cost[i], cost[i + 1]), one band of it costs its number of columns.
 struct MatvecArgs {
   int n, batch;
-  uint32_t x_off, slot_off;   // byte offsets in LDS of the activation image and of the partial-sum slots
+  uint32_t x_off, slot_off;   // byte offsets in LDS of the activation image (or of the tiles) and of the partial-sum slots
+  uint32_t tile_area;         // bytes of LDS per wavefront in the tile kernels (the same for every matrix of the launch)
+  uint32_t reserved;
   uint32_t cost[kMaxMulti + 1];
   Job j[kMaxMulti];
 };
@@ -652,7 +655,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
     }
     __syncthreads();
     const uint32_t strip = m.seg_cols + 8;   // bytes between the strips of two lanes
-    const uint32_t my_strip = lds_address(tiles) + (uint32_t)wave * 64u * strip + (uint32_t)lane * strip;
+    const uint32_t my_strip = lds_address(tiles) + (uint32_t)wave * a.tile_area + (uint32_t)lane * strip;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f}, head_acc = {0.f, 0.f, 0.f, 0.f}, tail_acc = {0.f, 0.f, 0.f, 0.f};
     int head_band = -1, tail_band = -1;
     // lanes past the batch repeat its last row: their output columns are never stored
@@ -718,71 +721,75 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
   }
 }
 
-// Expansion to the row-major int8 matrix.  The units are split into one contiguous run per wavefront of the grid.
-// A wavefront decodes a unit into its own LDS tile (lane l writes the run bytes of its segment one after the other:
-// both bytes of the dictionary entry are stored, and the second byte of a single-byte entry is overwritten by the
-// next run) and then copies the tile out with 16-byte pieces, 64 consecutive pieces per store.
-// Tile layout: [16 rows][4 panels][seg_cols + 4 bytes]; the 4 spare bytes take the stores past a segment's end.
-__global__ __launch_bounds__(kThreads, 1) void k_decompress(DevMat m, int8_t* __restrict__ out, uint32_t pad_code, int out_aligned) {
+// Expansion to the row-major int8 matrices (the paper's own online step: every codeword is replaced by its table
+// sequence).  Same work split and same tile decode as the batched product; a finished unit is copied out in 16-byte
+// pieces, consecutive lanes taking consecutive pieces of a row (4 panels x seg_cols contiguous bytes per row).
+// The y pointer of a job is the int8 output matrix here; the activation pointer is not used.
+__global__ __launch_bounds__(kThreads, 1) void k_decompress(MatvecArgs a) {
   extern __shared__ uint4 lds4[];
   uint16_t* lds_dict = (uint16_t*)lds4;
+  uint8_t* tiles = (uint8_t*)lds4 + a.x_off;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int n_waves = blockDim.x >> 6;
-  for (uint32_t i = tid; i < m.dict_words; i += blockDim.x) lds_dict[i] = (uint16_t)m.dict[i];
-  __syncthreads();
-  const uint32_t seg_stride = m.seg_cols + 4, tile_bytes = 64 * seg_stride;
-  uint8_t* tile = (uint8_t*)lds4 + (((size_t)m.dict_words * 2 + 15) & ~(size_t)15) + (size_t)wave * tile_bytes;
-  const uint32_t dict_lds = lds_address(lds_dict);
-  const uint32_t my_seg = lds_address(tile) + (uint32_t)((lane & 15) * 4 + (lane >> 4)) * seg_stride;
-  const uint64_t n_units = (uint64_t)m.n_bands * m.n_quads;
-  const uint64_t gw = (uint64_t)gridDim.x * n_waves, wid = (uint64_t)blockIdx.x * n_waves + wave;
-  const uint32_t u0 = (uint32_t)(n_units * wid / gw), u1 = (uint32_t)(n_units * (wid + 1) / gw);
-  const uint32_t n_panels = (m.cols + m.seg_cols - 1) / m.seg_cols;
-  for (uint32_t u = u0; u < u1; ++u) {
-    const uint32_t band = u / m.n_quads, quad = u - band * m.n_quads;
-    const uint32_t row = band * kUnitRows + (lane & 15), panel = quad * kUnitPanels + (lane >> 4);
-    uint32_t seg_len = 0;
-    if (row < m.rows && panel < n_panels) seg_len = min(m.seg_cols, m.cols - panel * m.seg_cols);
-    const uint32_t c0 = unit_offset(m, u), c1 = unit_offset(m, u + 1);
-    const uint2* p = m.codes + (size_t)c0 * 64 + lane;
-    uint32_t pos = 0;
-    uint2 nxt = p[0];
-    for (uint32_t c = c0; c < c1; ++c) {
-      const uint2 cur = nxt;
-      p += 64;
-      if (c + 1 < c1) nxt = p[0];
-      const uint32_t code[4] = {cur.x & 0xFFFFu, cur.x >> 16, cur.y & 0xFFFFu, cur.y >> 16};
+  const int n_threads = blockDim.x, n_waves = n_threads >> 6;
+  if (lds_address(lds4) != 0) return;   // the code -> entry lookup takes the dictionary to start at LDS address 0
+  const uint64_t total = a.cost[a.n];
+  const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
+  const uint32_t* staged = nullptr;
+  for (int i = 0; i < a.n; ++i) {
+    const uint32_t cb = a.cost[i], ce = a.cost[i + 1];
+    if (hi <= cb || lo >= ce) continue;
+    const Job job = a.j[i];
+    const DevMat m = load_description(job.m);
+    const uint32_t bc = m.cols;
+    const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
+    const uint32_t band_hi = hi >= ce ? m.n_bands : min(m.n_bands, (hi - cb + bc / 2) / bc);
+    if (band_lo >= band_hi) continue;
+    const uint32_t nq = m.n_quads;
+    const uint32_t unit_lo = band_lo * nq, n_units = (band_hi - band_lo) * nq;
+    const uint32_t u0 = unit_lo + (uint32_t)((uint64_t)n_units * wave / n_waves);
+    const uint32_t u1 = unit_lo + (uint32_t)((uint64_t)n_units * (wave + 1) / n_waves);
+    if (m.dict != staged) {
+      __syncthreads();   // nobody reads the previous dictionary any more
+      const uint4* src = (const uint4*)m.dict;
+      uint2* dst = (uint2*)lds_dict;
+      const uint32_t n4 = m.dict_words / 4;
+      for (uint32_t base = 0; base < n4; base += kDictRegs * n_threads) {
+        uint4 v[kDictRegs];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const uint32_t e = *(lds_cu16*)(size_t)(dict_lds + 2 * code[k]);
-        *(lds_u8*)(size_t)(my_seg + pos) = (uint8_t)e;
-        *(lds_u8*)(size_t)(my_seg + pos + 1) = (uint8_t)(e >> 8);
-        // a pad code leaves the position where it is: it only occurs once the segment is complete
-        pos = min(pos + 1 + (code[k] >= 256u ? 1u : 0u), seg_len);
-      }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    // copy out: piece i of the tile = 16 bytes at column 16 * (i % ppp) of segment slot i / ppp
-    const uint32_t ppp = m.seg_cols / 16;
-    for (uint32_t i = lane; i < 64 * ppp; i += 64) {
-      const uint32_t slot = i / ppp, pc = i - slot * ppp;
-      const uint32_t r = band * kUnitRows + (slot >> 2), col = (quad * kUnitPanels + (slot & 3)) * m.seg_cols + pc * 16;
-      if (r >= m.rows || col >= m.cols) continue;
-      const uint32_t src = lds_address(tile) + slot * seg_stride + pc * 16;
-      const uint32_t w0 = lds_read32(src), w1 = lds_read32(src + 4), w2 = lds_read32(src + 8), w3 = lds_read32(src + 12);
-      int8_t* dst = out + (size_t)r * m.cols + col;
-      if (out_aligned && col + 16 <= m.cols) {
-        *(uint4*)dst = make_uint4(w0, w1, w2, w3);
-      } else {
-        const uint32_t w[4] = {w0, w1, w2, w3};
+        for (int k = 0; k < kDictRegs; ++k) v[k] = global_load(src + min(base + k * n_threads + tid, n4 - 1));
 #pragma unroll
-        for (int k = 0; k < 16; ++k)
-          if (col + k < m.cols) dst[k] = (int8_t)(w[k >> 2] >> (8 * (k & 3)));
+        for (int k = 0; k < kDictRegs; ++k) {
+          const uint32_t idx = base + k * n_threads + tid;
+          if (idx < n4) dst[idx] = make_uint2((v[k].x & 0xFFFFu) | v[k].y << 16, (v[k].z & 0xFFFFu) | v[k].w << 16);
+        }
       }
+      staged = m.dict;
+      __syncthreads();
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    const uint32_t strip = m.seg_cols + 8;
+    const uint32_t tile_lds = lds_address(tiles) + (uint32_t)wave * a.tile_area;   // matrices of different segment width may be in work at once
+    int8_t* out = (int8_t*)job.y;
+    const bool aligned = (m.cols % 16 == 0) && ((uintptr_t)out % 16 == 0);
+    const uint32_t ppp = m.seg_cols / 16;   // 16-byte pieces per segment
+    decode_run_to_tile(m, u0, u1, lane, tile_lds + (uint32_t)lane * strip, [&](uint32_t band, uint32_t quad) {
+      for (uint32_t pc = lane; pc < 64 * ppp; pc += 64) {
+        const uint32_t seg = pc / ppp, part = pc - seg * ppp;            // segment (row seg / 4, panel seg % 4) of the unit
+        const uint32_t row = band * kUnitRows + (seg >> 2), col = (quad * kUnitPanels + (seg & 3)) * m.seg_cols + part * 16;
+        if (row >= m.rows || col >= m.cols) continue;
+        const uint32_t src = tile_lds + ((seg >> 2) + 16 * (seg & 3)) * strip + part * 16;   // strip of lane (row, panel)
+        const u32x2 lo8 = *(lds_cu64*)(size_t)src, hi8 = *(lds_cu64*)(size_t)(src + 8);
+        int8_t* dst = out + (size_t)row * m.cols + col;
+        if (aligned && col + 16 <= m.cols) {
+          u32x4 v = {lo8.x, lo8.y, hi8.x, hi8.y};
+          *(__attribute__((address_space(1))) u32x4*)dst = v;
+        } else {
+          const uint32_t w[4] = {lo8.x, lo8.y, hi8.x, hi8.y};
+#pragma unroll
+          for (int k = 0; k < 16; ++k)
+            if (col + k < m.cols) *(__attribute__((address_space(1))) int8_t*)(dst + k) = (int8_t)(w[k >> 2] >> (8 * (k & 3)));
+        }
+      }
+    });
   }
 }
 
@@ -868,8 +875,6 @@ struct tq_matrix {
   void* dev_base;
   int device;
   int n_cu;
-  uint32_t decompress_waves;
-  size_t decompress_lds;
 };
 
 extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_handle* out) {
@@ -909,13 +914,11 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
               " bytes of LDS; the device has " + std::to_string(kLdsLimit));
     return TQ_E_UNSUPPORTED;
   }
-  // tq_decompress: 16-bit dictionary image plus one tile of 64 segments per wavefront.
-  const size_t dict16 = round_up((uint64_t)m.dict_words * 2, 16), tile = (size_t)64 * (h.seg_cols + 4);
-  if (dict16 + tile > kLdsLimit) {
-    set_error("segments of " + std::to_string(h.seg_cols) + " columns do not fit the LDS tile of tq_decompress");
+  // tq_decompress and the batched product: 16-bit dictionary image plus one tile of 64 strips per wavefront.
+  if (round_up((uint64_t)m.dict_words * 2, 16) + (size_t)64 * (h.seg_cols + 8) + 64 > kLdsLimit) {
+    set_error("segments of " + std::to_string(h.seg_cols) + " columns do not fit the LDS tile");
     return TQ_E_UNSUPPORTED;
   }
-  const uint32_t dwaves = (uint32_t)std::min<size_t>(kWaves, (kLdsLimit - dict16) / tile);
 
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -973,25 +976,28 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   t->dev_base = base;
   t->device = dev;
   t->n_cu = prop.multiProcessorCount;
-  t->decompress_waves = dwaves;
-  t->decompress_lds = dict16 + (size_t)dwaves * tile;
   *out = t;
   return TQ_OK;
 }
 
 namespace {
 
-// One launch of the product kernel for hs[0..n), n <= kMaxMulti, all on one device, total cost below 2^32.
-int launch_matvec(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream) {
+enum class Op { kMatvec, kDecompress };
+
+// One kernel launch for hs[0..n), n <= kMaxMulti, all on one device, total cost below 2^32.
+// kMatvec: xs/ys are the activations and outputs; kDecompress: ys are the int8 output matrices, xs is not used.
+int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream) {
   MatvecArgs a;
   a.n = n;
   a.batch = batch;
-  uint32_t dict_words_max = 0, x_dwords_max = 0;
+  a.tile_area = a.reserved = 0;
+  uint32_t dict_words_max = 0, x_dwords_max = 0, seg_max = 0;
   uint64_t cost = 0, bands = 0, band_cost_max = 1;
+  bool x_fast = true;
   for (int i = 0; i < n; ++i) {
     const tq_matrix* t = hs[i];
     a.j[i].m = t->m_dev;
-    a.j[i].x = (const uint16_t*)xs[i];
+    a.j[i].x = xs ? (const uint16_t*)xs[i] : nullptr;
     a.j[i].y = (float*)ys[i];
     a.cost[i] = (uint32_t)cost;
     cost += (uint64_t)t->m.n_bands * t->m.cols;   // a band costs its 16 x cols weights, counted in units of 16
@@ -999,6 +1005,8 @@ int launch_matvec(int n, const tq_handle* hs, const void* const* xs, void* const
     band_cost_max = std::max<uint64_t>(band_cost_max, t->m.cols);
     dict_words_max = std::max(dict_words_max, t->m.dict_words);
     x_dwords_max = std::max(x_dwords_max, t->m.x_dwords);
+    seg_max = std::max(seg_max, t->m.seg_cols);
+    x_fast = x_fast && t->m.cols % 8 == 0 && xs && (uintptr_t)xs[i] % 16 == 0;
   }
   a.cost[n] = (uint32_t)cost;
   if (cost > 0xFFFFFFFFull) {
@@ -1008,38 +1016,51 @@ int launch_matvec(int n, const tq_handle* hs, const void* const* xs, void* const
   // Every workgroup's share of the cost line is at least one band of the most expensive kind, and there is one
   // workgroup per CU at most.
   const uint64_t grid = std::max<uint64_t>(1, std::min<uint64_t>({(uint64_t)hs[0]->n_cu, bands, cost / band_cost_max}));
-  if (batch > 1) {
-    // MFMA path.  LDS: 16-bit dictionary image | one tile (64 strips) per wavefront, reused for the partial sums | slot ids.
-    uint32_t seg_max = 0;
-    bool fast = true;
-    for (int i = 0; i < n; ++i) {
-      seg_max = std::max(seg_max, hs[i]->m.seg_cols);
-      fast = fast && hs[i]->m.cols % 8 == 0 && (uintptr_t)xs[i] % 16 == 0;
+  if (op == Op::kMatvec && batch == 1) {
+    size_t lds_total;
+    if (!plan_matvec_lds(dict_words_max, x_dwords_max, &a.x_off, &a.slot_off, &lds_total)) {
+      set_error("the matrices of this call together need " + std::to_string(lds_total) + " bytes of LDS (largest dictionary plus longest row)");
+      return TQ_E_UNSUPPORTED;
     }
+    hipLaunchKernelGGL(k_matvec<kDepth>, dim3((unsigned)grid), dim3(kThreads), lds_total, stream, a);
+  } else {
+    // Tile decode.  LDS: 16-bit dictionary image | one tile (64 strips) per wavefront, which the batched product reuses
+    // for its partial sums (two slots of 1 KB per wavefront) | slot ids.
     const size_t dict16 = round_up((uint64_t)dict_words_max * 2, 16);
-    const size_t area = std::max<size_t>((size_t)64 * (seg_max + 8), 2048);   // per wavefront: its tile, later two slots of 1 KB
+    const size_t area = std::max<size_t>((size_t)64 * (seg_max + 8), 2048);
     const size_t waves = std::min<size_t>(kWaves, (kLdsLimit - dict16 - 64) / area);
     if (waves == 0) {
-      set_error("segments of " + std::to_string(seg_max) + " columns do not fit the LDS tile of the batched product");
+      set_error("segments of " + std::to_string(seg_max) + " columns do not fit the LDS tile");
       return TQ_E_UNSUPPORTED;
     }
     a.x_off = (uint32_t)dict16;
+    a.tile_area = (uint32_t)area;
     a.slot_off = (uint32_t)(dict16 + waves * area);
     const size_t lds = a.slot_off + 64;
-    if (fast) hipLaunchKernelGGL((k_matvec_mfma<kDepth, true>), dim3((unsigned)grid), dim3((unsigned)waves * 64), lds, stream, a);
-    else hipLaunchKernelGGL((k_matvec_mfma<kDepth, false>), dim3((unsigned)grid), dim3((unsigned)waves * 64), lds, stream, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail("tq_matvec launch", e);
-    return TQ_OK;
+    const dim3 block((unsigned)waves * 64);
+    if (op == Op::kDecompress) hipLaunchKernelGGL(k_decompress, dim3((unsigned)grid), block, lds, stream, a);
+    else if (x_fast) hipLaunchKernelGGL((k_matvec_mfma<kDepth, true>), dim3((unsigned)grid), block, lds, stream, a);
+    else hipLaunchKernelGGL((k_matvec_mfma<kDepth, false>), dim3((unsigned)grid), block, lds, stream, a);
   }
-  size_t lds_total;
-  if (!plan_matvec_lds(dict_words_max, x_dwords_max, &a.x_off, &a.slot_off, &lds_total)) {
-    set_error("the matrices of this call together need " + std::to_string(lds_total) + " bytes of LDS (largest dictionary plus longest row)");
-    return TQ_E_UNSUPPORTED;
-  }
-  hipLaunchKernelGGL(k_matvec<kDepth>, dim3((unsigned)grid), dim3(kThreads), lds_total, stream, a);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return hip_fail("tq_matvec launch", e);
+  if (e != hipSuccess) return hip_fail(op == Op::kDecompress ? "tq_decompress launch" : "tq_matvec launch", e);
+  return TQ_OK;
+}
+
+// As few launches as the kernel-argument size and the 32-bit cost line allow.
+int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream) {
+  for (int i = 0; i < n;) {
+    int k = 0;
+    uint64_t cost = 0;
+    while (i + k < n && k < kMaxMulti) {
+      const uint64_t c = (uint64_t)hs[i + k]->m.n_bands * hs[i + k]->m.cols;
+      if (k > 0 && cost + c > 0xFFFFFFFFull) break;
+      cost += c;
+      ++k;
+    }
+    if (int rc = launch(op, k, hs + i, xs ? xs + i : nullptr, ys + i, batch, stream)) return rc;
+    i += k;
+  }
   return TQ_OK;
 }
 
@@ -1073,7 +1094,7 @@ extern "C" int tq_matvec(tq_handle h, const void* x, void* y, int batch, void* s
     return TQ_E_INVALID_ARG;
   }
   if (int rc = check_call("tq_matvec", 1, &h, &x, &y, batch)) return rc;
-  return launch_matvec(1, &h, &x, &y, batch, (hipStream_t)stream);
+  return launch(Op::kMatvec, 1, &h, &x, &y, batch, (hipStream_t)stream);
 }
 
 extern "C" int tq_matvec_multi(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {
@@ -1082,24 +1103,7 @@ extern "C" int tq_matvec_multi(int n, const tq_handle* hs, const void* const* xs
     return TQ_E_INVALID_ARG;
   }
   if (int rc = check_call("tq_matvec_multi", n, hs, xs, ys, batch)) return rc;
-  // as few launches as the kernel-argument size and the 32-bit cost line allow
-  for (int i = 0; i < n;) {
-    int k = 0;
-    uint64_t cost = 0;
-    while (i + k < n && k < kMaxMulti) {
-      const uint64_t c = (uint64_t)hs[i + k]->m.n_bands * hs[i + k]->m.cols;
-      if (k > 0 && cost + c > 0xFFFFFFFFull) break;
-      cost += c;
-      ++k;
-    }
-    if (cost > 0xFFFFFFFFull) {
-      set_error("tq_matvec_multi: a single matrix of more than 2^36 weights is not supported");
-      return TQ_E_UNSUPPORTED;
-    }
-    if (int rc = launch_matvec(k, hs + i, xs + i, ys + i, batch, (hipStream_t)stream)) return rc;
-    i += k;
-  }
-  return TQ_OK;
+  return launch_all(Op::kMatvec, n, hs, xs, ys, batch, (hipStream_t)stream);
 }
 
 extern "C" int tq_decompress(tq_handle h, void* out, void* stream) {
@@ -1107,14 +1111,25 @@ extern "C" int tq_decompress(tq_handle h, void* out, void* stream) {
     set_error("tq_decompress: null argument");
     return TQ_E_INVALID_ARG;
   }
-  const int out_aligned = (h->m.cols % 16 == 0) && ((uintptr_t)out % 16 == 0);
-  const uint64_t wg_needed = (h->h.n_units + h->decompress_waves - 1) / h->decompress_waves;
-  const unsigned grid = (unsigned)std::min<uint64_t>(wg_needed, (uint64_t)h->n_cu);
-  hipLaunchKernelGGL(k_decompress, dim3(grid), dim3(h->decompress_waves * 64), h->decompress_lds, (hipStream_t)stream, h->m,
-                     (int8_t*)out, h->h.pad_code, out_aligned);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return hip_fail("tq_decompress launch", e);
-  return TQ_OK;
+  return launch(Op::kDecompress, 1, &h, nullptr, &out, 1, (hipStream_t)stream);
+}
+
+extern "C" int tq_decompress_multi(int n, const tq_handle* hs, void* const* outs, void* stream) {
+  if (n < 1 || !hs || !outs) {
+    set_error("tq_decompress_multi: null argument or n < 1");
+    return TQ_E_INVALID_ARG;
+  }
+  for (int i = 0; i < n; ++i) {
+    if (!hs[i] || !outs[i]) {
+      set_error("tq_decompress_multi: null handle or pointer at index " + std::to_string(i));
+      return TQ_E_INVALID_ARG;
+    }
+    if (hs[i]->device != hs[0]->device) {
+      set_error("tq_decompress_multi: all matrices of a call must live on one device");
+      return TQ_E_INVALID_ARG;
+    }
+  }
+  return launch_all(Op::kDecompress, n, hs, nullptr, outs, 1, (hipStream_t)stream);
 }
 
 extern "C" int tq_get_info(tq_handle h, tq_info* out) {

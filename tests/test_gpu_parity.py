@@ -223,6 +223,24 @@ def test_multi_launch_of_more_matrices_than_one_kernel_takes(dev):
     _multi_case(dev, shapes, 2, True, max_entries=600)
 
 
+def test_decompress_multi_is_bit_exact(dev):
+    shapes = [(192, 768, 64), (40, 300, 32), (64, 768, 192), (48, 2048, 256), (512, 768, 192), (17, 257, 256)] * 25   # 150 > 128
+    mats, outs, want = [], [], []
+    prev = None
+    for k, (r, c, seg) in enumerate(shapes):
+        W = make_weights(small_case(r, c, seed=300 + k))
+        prev = tq.tq_encode(W, max_entries=900, seg_cols=seg, dict_from=prev if k % 7 else None)
+        mats.append(tq.Matrix(prev))
+        outs.append(torch.full((r, c), 77, dtype=torch.int8, device=dev))
+        want.append(O.quantize_rows(W)[0])
+    tq.tq_decompress_multi([m.handle for m in mats], [o.data_ptr() for o in outs], _stream())
+    torch.cuda.synchronize()
+    for o, w in zip(outs, want):
+        assert np.array_equal(o.cpu().numpy(), w)
+    for m in mats:
+        m.close()
+
+
 def test_argument_errors(dev):
     spec = small_case(16, 256, seed=29)
     m = tq.Matrix(tq.tq_encode(make_weights(spec)))
