@@ -55,6 +55,8 @@ def parse_args():
                          "products (each has its own activation vector), so all of them go to tq_matvec_multi at once; "
                          "layer: one tq_matvec_multi per transformer layer; independent: only products that a real layer "
                          "computes from the same input (q,k,v and gate,up) share a launch; none: one tq_matvec per matrix")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and replay it (takes the host's launch cost out of plans with many launches)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, so a counter profile of this command holds a kernel of "
                          "known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -89,21 +91,34 @@ def main():
     workers = max(1, min(args.threads, 8))
     inner = max(1, args.threads // workers)
     opts = dict(max_entries=args.max_entries, lmax=args.lmax, seg_cols=args.seg_cols)
-    first_blob = tq.tq_encode(make_weights(specs[0]), n_threads=args.threads, **opts)   # fills the dictionary
-    rest = sorted(range(1, len(specs)), key=lambda i: -specs[i].rows * specs[i].cols)
+    # One LZW dictionary over the sequence: the matrices are encoded one after the other, each starting from the
+    # dictionary the previous one ended with, until the dictionary is full (Gaussian weights fill it inside the first
+    # matrix) or the first layer is through; from then on it is frozen at the size it has reached, so the remaining
+    # matrices no longer depend on each other and are encoded in parallel.
+    mats = [None] * len(specs)
+    cap = args.max_entries or tq.TQ_MAX_ENTRIES_DEVICE
+    prev, n_chain = None, 0
+    while n_chain < min(7, len(specs)):
+        i = n_chain
+        blob = tq.tq_encode(make_weights(specs[i]), n_threads=args.threads,
+                            dict_from=prev if args.dictionary == "sequence" else None, **opts)
+        mats[i] = tq.Matrix(blob)
+        if specs[i].name in sample_names:
+            sample_blobs[i] = blob
+        prev = blob
+        n_chain += 1
+        if args.dictionary != "sequence" or mats[i].info["n_entries"] == cap:
+            break
+    if args.dictionary == "sequence":
+        opts["max_entries"] = mats[n_chain - 1].info["n_entries"]
+    rest = sorted(range(n_chain, len(specs)), key=lambda i: -specs[i].rows * specs[i].cols)
 
     def encode(i):
         s = specs[i]
         blob = tq.tq_encode(make_weights(s), n_threads=inner,
-                            dict_from=first_blob if args.dictionary == "sequence" else None, **opts)
+                            dict_from=prev if args.dictionary == "sequence" else None, **opts)
         return i, blob
 
-    mats = [None] * len(specs)
-    mats[0] = tq.Matrix(first_blob)
-    sample_blobs[0] = first_blob
-    if args.dictionary == "sequence":
-        assert mats[0].info["n_entries"] == (args.max_entries or tq.TQ_MAX_ENTRIES_DEVICE), \
-            "the first matrix must fill the dictionary for the others to be encoded independently of their order"
     with ThreadPoolExecutor(workers) as ex:
         for i, blob in ex.map(encode, rest):
             mats[i] = tq.Matrix(blob)                   # validates, uploads, frees nothing on the hot path later
@@ -113,9 +128,8 @@ def main():
     # bytes the kernels must read from HBM: code stream, unit offsets and scales of every matrix, and every distinct
     # dictionary once (matrices encoded as one sequence hold the same dictionary; the library stores one copy)
     stream_bytes = sum(i["compressed_bytes"] - i["dict_bytes"] for i in infos)
-    if args.dictionary == "sequence":
-        assert len({i["dict_bytes"] for i in infos}) == 1
-        comp_bytes = stream_bytes + infos[0]["dict_bytes"]
+    if args.dictionary == "sequence":   # the matrices of the chain hold growing dictionaries, all later ones the last of them
+        comp_bytes = stream_bytes + sum(i["dict_bytes"] for i in infos[:n_chain])
     else:
         comp_bytes = stream_bytes + sum(i["dict_bytes"] for i in infos)
     n_weights = sum(s.rows * s.cols for s in specs)
@@ -161,9 +175,22 @@ def main():
                                   [ys[i].data_ptr() for i in g], batch)
                 calls.append(lambda mc=mc: mc.launch(stream))
 
-        def step():
+        def eager_step():
             for c in calls:
                 c()
+
+        step = eager_step
+        if args.graph:
+            eager_step()
+            torch.cuda.synchronize()
+            side = torch.cuda.Stream()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                cap = torch.cuda.current_stream().cuda_stream
+                for g in groups:     # the same calls, issued on the capturing stream
+                    tq.tq_matvec_multi([mats[i].handle for i in g], [xs[i].data_ptr() for i in g],
+                                       [ys[i].data_ptr() for i in g], batch, cap)
+            step = graph.replay
 
         for _ in range(warmup):
             step()
@@ -241,8 +268,9 @@ def main():
             "matrices": len(specs), "weights": n_weights, "compressed_bytes": comp_bytes,
             "bytes_per_weight": round(comp_bytes / n_weights, 4), "weights_per_code": round(n_weights / n_codes, 4),
             "weights_per_real_code": round(n_weights / sum(i["n_real_codes"] for i in infos), 4),
-            "max_entries": infos[0]["n_entries"], "lmax": infos[0]["lmax"], "seg_cols": infos[0]["seg_cols"],
+            "dictionary_entries": infos[-1]["n_entries"], "lmax": infos[0]["lmax"], "seg_cols": infos[0]["seg_cols"],
             "dictionary": args.dictionary, "fuse": args.fuse, "kernel_launches_per_step": n_launches,
+            "hip_graph": bool(args.graph),
         },
         "roofline": {
             "bound": "hbm", "kernel": "tq::k_matvec",

@@ -241,6 +241,52 @@ def test_decompress_multi_is_bit_exact(dev):
         m.close()
 
 
+def test_launches_can_be_captured_in_a_hip_graph_and_replayed(dev):
+    """The launch calls allocate nothing and do not synchronise: a captured step replays to the eager results, every
+    time, with eager work of the same kernels in between."""
+    shapes = [(192, 768, 64), (64, 768, 192), (48, 2048, 256)]
+    for batch in (1, 4):
+        mats, xs, ys = [], [], []
+        prev = None
+        for k, (r, c, seg) in enumerate(shapes):
+            spec = small_case(r, c, seed=400 + k)
+            prev = tq.tq_encode(make_weights(spec), max_entries=2000, seg_cols=seg, dict_from=prev)
+            mats.append(tq.Matrix(prev))
+            bits, _ = make_activations(spec, batch)
+            xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
+            ys.append(torch.zeros((batch, r), dtype=torch.float32, device=dev))
+        hs, xp, yp = [m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys]
+        out = torch.zeros((48, 2048), dtype=torch.int8, device=dev)
+        tq.tq_matvec_multi(hs, xp, yp, batch, _stream())
+        mats[2].decompress(out.data_ptr(), _stream())
+        torch.cuda.synchronize()
+        want_y, want_q = [y.clone() for y in ys], out.clone()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            cap = torch.cuda.current_stream().cuda_stream
+            tq.tq_matvec_multi(hs, xp, yp, batch, cap)
+            tq.tq_matvec(hs[0], xp[0], yp[0], batch, cap)
+            tq.tq_decompress(hs[2], out.data_ptr(), cap)
+        for _ in range(3):
+            for y in ys:
+                y.fill_(-1.0)          # fill kernels, not memsets
+            out.fill_(9)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for y, w in zip(ys[1:], want_y[1:]):
+                assert torch.equal(y, w)
+            assert torch.equal(out, want_q)
+            check = torch.zeros_like(ys[0])
+            tq.tq_matvec(hs[0], xp[0], check.data_ptr(), batch, _stream())    # eager work between the replays
+            torch.cuda.synchronize()
+            assert torch.equal(ys[0], check)
+        del graph
+        for m in mats:
+            m.close()
+
+
 def test_argument_errors(dev):
     spec = small_case(16, 256, seed=29)
     m = tq.Matrix(tq.tq_encode(make_weights(spec)))
