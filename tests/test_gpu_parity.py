@@ -241,6 +241,58 @@ def test_decompress_multi_is_bit_exact(dev):
         m.close()
 
 
+def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows(dev):
+    """Config-4 shapes at full size (one 3B layer plus lm_head 128256 x 3072), encoded as bench.py encodes them (one
+    dictionary over the sequence, default options) and launched as bench.py launches them (all matrices in one
+    tq_matvec_multi / tq_decompress_multi call), batch 1 and 8.  The oracle computes sampled rows one by one:
+    quantization is per row, so the sampled rows of Q and their float64 products need only those rows of W."""
+    from inputs import config_matrices
+    specs = [s for s in config_matrices(4) if s.name.startswith("L00.") or s.name == "lm_head"]
+    assert len(specs) == 8 and specs[-1].rows == 128256
+    rng = np.random.default_rng(77)
+    mats, picks, q_ref, s_ref = [], [], [], []
+    prev = None
+    for spec in specs:
+        W = make_weights(spec)
+        prev = tq.tq_encode(W, dict_from=prev)
+        mats.append(tq.Matrix(prev))
+        rows = np.unique(np.concatenate([[0, 15, 16, spec.rows - 17, spec.rows - 1], rng.integers(0, spec.rows, 59)]))
+        Qs, ss = O.quantize_rows(W[rows])
+        picks.append(rows)
+        q_ref.append(Qs)
+        s_ref.append(ss)
+        del W
+    assert mats[0].info["n_entries"] == tq.TQ_MAX_ENTRIES_DEVICE and mats[-1].info["seg_cols"] == 256
+    handles = [m.handle for m in mats]
+    try:
+        outs = [torch.full((sp.rows, sp.cols), 77, dtype=torch.int8, device=dev) for sp in specs]
+        tq.tq_decompress_multi(handles, [o.data_ptr() for o in outs], _stream())
+        torch.cuda.synchronize()
+        for o, rows, Qs in zip(outs, picks, q_ref):
+            assert np.array_equal(o[torch.from_numpy(rows).to(dev)].cpu().numpy(), Qs)
+        assert int((outs[-1] == 77).sum()) < outs[-1].numel() // 100      # nothing left unwritten (77 is an ordinary value too)
+        del outs
+        for batch in (1, 8):
+            xs, ys, xf = [], [], []
+            for sp in specs:
+                bits, x = make_activations(sp, batch)
+                xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
+                ys.append(torch.full((batch, sp.rows), float("nan"), dtype=torch.float32, device=dev))
+                xf.append(x)
+            tq.tq_matvec_multi(handles, [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch, _stream())
+            torch.cuda.synchronize()
+            for y, rows, Qs, ss, x in zip(ys, picks, q_ref, s_ref, xf):
+                got = y.cpu().numpy()
+                assert np.isfinite(got).all()
+                ref = O.gemv_f64(Qs, ss, x)                           # [batch, sampled rows]
+                scale = np.abs(ref).max(axis=1, keepdims=True)
+                assert (np.abs(got[:, rows] - ref) <= 1e-3 * scale).all()
+                assert (np.abs(got[:, rows] - ref) <= 1e-5 * scale).all()   # what fp32 accumulation of exact products gives
+    finally:
+        for m in mats:
+            m.close()
+
+
 def test_launches_can_be_captured_in_a_hip_graph_and_replayed(dev):
     """The launch calls allocate nothing and do not synchronise: a captured step replays to the eager results, every
     time, with eager work of the same kernels in between."""
