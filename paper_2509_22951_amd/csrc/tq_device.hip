@@ -29,8 +29,10 @@
 
 namespace tq {
 
-constexpr int kWaves = 8;            // wavefronts per workgroup of the product kernel (one workgroup per CU: LDS-bound)
+constexpr int kWaves = 8;            // most wavefronts per workgroup of the tile kernels (one workgroup per CU: LDS-bound)
 constexpr int kThreads = kWaves * 64;
+constexpr int kDotWaves = 8;         // wavefronts per workgroup of the batch-1 kernel (measured on the 3B sweep, TB/s:
+                                     // 6 waves 4.61, 8 waves 5.12, 10 waves 4.64, 12 waves 4.90, 16 waves 4.28)
 constexpr int kDepth = 16;           // chunks of code loads kept in flight per wavefront (16 x 512 bytes; measured on the
                                      // 3B sweep: 8 in flight 4.57 TB/s, 12 and 16 in flight 4.90 TB/s)
 constexpr uint32_t kLdsLimit = 160 * 1024;
@@ -160,9 +162,9 @@ __device__ __forceinline__ uint32_t i8_to_bf16_bits(uint32_t byte) { return __fl
 
 // Staging is split in two so that the loads of the dictionary, of the activations and of the first code chunks are
 // all in flight together before anything waits: issue_* only loads into registers, commit_* writes LDS.
-constexpr int kDictRegs = 16;   // uint4 per thread per round: 16 x 512 threads x 16 bytes = 128 KB, the whole dictionary
-constexpr int kXRegs = 8;       // activation pairs per thread per round: 8 x 512 x 2 = 8192 columns
+constexpr int kDictRegs = 16;   // uint4 per thread per round of the tile kernels' dictionary staging
 
+template <int kThreads, int kDictRegs>   // kDictRegs x kThreads x 16 bytes per round (128 KB: the whole dictionary in one)
 __device__ __forceinline__ void issue_dictionary(const DevMat& m, uint32_t base, int tid, uint4 (&v)[kDictRegs]) {
   const uint4* src = (const uint4*)m.dict;
   const uint32_t n4 = m.dict_words / 4;
@@ -171,6 +173,7 @@ __device__ __forceinline__ void issue_dictionary(const DevMat& m, uint32_t base,
 }
 // Container word (b0, b1, -, length) -> (bf16(b0), bf16(b1)).  Bytes past an entry's length are zero in the container,
 // so a single-byte entry gets a zero second weight and the pad entry two.
+template <int kThreads, int kDictRegs>
 __device__ __forceinline__ void commit_dictionary(const DevMat& m, uint32_t base, int tid, const uint4 (&v)[kDictRegs], uint32_t* lds_dict) {
   uint4* dst = (uint4*)lds_dict;
   const uint32_t n4 = m.dict_words / 4;
@@ -185,7 +188,7 @@ __device__ __forceinline__ void commit_dictionary(const DevMat& m, uint32_t base
 // LDS image of one activation row: dword (panel * x_span + c) = (x[panel * seg_cols + c], x[panel * seg_cols + c + 1])
 // as two bf16, zero past the end of the row; the gap dwords between panels and the tail are zero.
 // Thread t of a round handles the column pair (2 j, 2 j + 1), j = first_pair + k * 512 + t: it loads x[2j .. 2j+2].
-template <bool kAligned>
+template <bool kAligned, int kThreads, int kXRegs>   // kXRegs x kThreads x 2 columns per round (8192)
 __device__ __forceinline__ void issue_activations(const DevMat& m, const uint16_t* __restrict__ x, uint32_t first_pair, int tid,
                                                   uint32_t (&lo)[kXRegs], uint32_t (&hi)[kXRegs]) {
 #pragma unroll
@@ -200,6 +203,7 @@ __device__ __forceinline__ void issue_activations(const DevMat& m, const uint16_
     }
   }
 }
+template <int kThreads, int kXRegs>
 __device__ __forceinline__ void commit_activations(const DevMat& m, uint32_t first_pair, int tid, const uint32_t (&lo)[kXRegs],
                                                    const uint32_t (&hi)[kXRegs], uint32_t* lds_x, uint32_t image_cols) {
   const uint32_t gap = m.x_span - m.seg_cols;
@@ -213,6 +217,7 @@ __device__ __forceinline__ void commit_activations(const DevMat& m, uint32_t fir
     }
   }
 }
+template <int kThreads>
 __device__ __forceinline__ void zero_activation_gaps(const DevMat& m, int tid, uint32_t* lds_x, uint32_t n_slots) {
   const uint32_t gap = m.x_span - m.seg_cols;
   if (gap)   // gap is 16 dwords
@@ -267,9 +272,10 @@ __device__ __forceinline__ float sum_over_panels(float v) {
 // lies entirely inside its run (it scales and stores those rows itself); a band it shares with its neighbours goes to
 // one of two partial-sum slots in LDS, and after a workgroup barrier the slots of a band are added in wavefront order,
 // so the result does not depend on timing.
-template <int kD>
-__global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
+template <int kD, int kWaves>
+__global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
   static_assert(kD % 2 == 0, "the operand sets alternate with the slot index");
+  constexpr int kThreads = kWaves * 64, kDictRegs = 128 / kWaves, kXRegs = 64 / kWaves;
   extern __shared__ uint4 lds4[];
   uint32_t* lds_dict = (uint32_t*)lds4;
   uint32_t* lds_x = (uint32_t*)((uint8_t*)lds4 + a.x_off);
@@ -319,23 +325,23 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec(MatvecArgs a) {
         uint4 dv[kDictRegs];
         uint32_t xlo[kXRegs], xhi[kXRegs];
         const bool dict_now = new_dict && b == 0;
-        if (dict_now) issue_dictionary(m, 0, tid, dv);
-        if (x_aligned) issue_activations<true>(m, xb, 0, tid, xlo, xhi);
-        else issue_activations<false>(m, xb, 0, tid, xlo, xhi);
-        zero_activation_gaps(m, tid, lds_x, n_slots);
+        if (dict_now) issue_dictionary<kThreads, kDictRegs>(m, 0, tid, dv);
+        if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
+        else issue_activations<false, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
+        zero_activation_gaps<kThreads>(m, tid, lds_x, n_slots);
         if (tid < 2 * kWaves) slot_band[tid] = -1;
         if (dict_now) {
-          commit_dictionary(m, 0, tid, dv, lds_dict);
+          commit_dictionary<kThreads, kDictRegs>(m, 0, tid, dv, lds_dict);
           for (uint32_t base = kDictRegs * kThreads; base < m.dict_words / 4; base += kDictRegs * kThreads) {
-            issue_dictionary(m, base, tid, dv);
-            commit_dictionary(m, base, tid, dv, lds_dict);
+            issue_dictionary<kThreads, kDictRegs>(m, base, tid, dv);
+            commit_dictionary<kThreads, kDictRegs>(m, base, tid, dv, lds_dict);
           }
         }
-        commit_activations(m, 0, tid, xlo, xhi, lds_x, image_cols);
+        commit_activations<kThreads, kXRegs>(m, 0, tid, xlo, xhi, lds_x, image_cols);
         for (uint32_t first = kXRegs * kThreads; 2 * first < image_cols; first += kXRegs * kThreads) {
-          if (x_aligned) issue_activations<true>(m, xb, first, tid, xlo, xhi);
-          else issue_activations<false>(m, xb, first, tid, xlo, xhi);
-          commit_activations(m, first, tid, xlo, xhi, lds_x, image_cols);
+          if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
+          else issue_activations<false, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
+          commit_activations<kThreads, kXRegs>(m, first, tid, xlo, xhi, lds_x, image_cols);
         }
       }
       __syncthreads();
@@ -855,7 +861,7 @@ hipError_t release_dictionary(DictCopy* d) {
   return e;
 }
 
-constexpr uint32_t kSlotBytes = 2 * kWaves * 16 * 4 + 2 * kWaves * 4;
+constexpr uint32_t kSlotBytes = 2 * kDotWaves * 16 * 4 + 2 * kDotWaves * 4;
 
 // LDS plan of the product kernel for a set of matrices: dictionary | activation image | partial-sum slots.
 bool plan_matvec_lds(uint32_t dict_words_max, uint32_t x_dwords_max, uint32_t* x_off, uint32_t* slot_off, size_t* total) {
@@ -931,7 +937,7 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
     return TQ_E_UNSUPPORTED;
   }
   // Dynamic LDS above 64 KB has to be allowed per kernel function.
-  e = hipFuncSetAttribute((const void*)k_matvec<kDepth>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  e = hipFuncSetAttribute((const void*)k_matvec<kDepth, kDotWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_decompress, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<kDepth, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<kDepth, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
@@ -1022,7 +1028,7 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
       set_error("the matrices of this call together need " + std::to_string(lds_total) + " bytes of LDS (largest dictionary plus longest row)");
       return TQ_E_UNSUPPORTED;
     }
-    hipLaunchKernelGGL(k_matvec<kDepth>, dim3((unsigned)grid), dim3(kThreads), lds_total, stream, a);
+    hipLaunchKernelGGL((k_matvec<kDepth, kDotWaves>), dim3((unsigned)grid), dim3(kDotWaves * 64), lds_total, stream, a);
   } else {
     // Tile decode.  LDS: 16-bit dictionary image | one tile (64 strips) per wavefront, which the batched product reuses
     // for its partial sums (two slots of 1 KB per wavefront) | slot ids.
