@@ -461,32 +461,47 @@ __device__ __forceinline__ bf16x8 i8x8_to_bf16x8(uint2 w) {
   return __builtin_bit_cast(bf16x8, r);
 }
 
-// Append the runs of one chunk (4 codes) to the lane's strip.  ptr = LDS address of the lane's next byte; it stops at
-// `end` (the end of the segment), where the pad codes that fill up a shorter lane stream put their zero bytes: the
-// strips are 8 bytes apart, so those stay clear of the next strip.
-__device__ __forceinline__ void append_chunk(uint2 c, uint32_t& ptr, uint32_t end) {
+// Append the runs of one chunk (4 codes) to the lane's strip.  The 4 entries (1 or 2 bytes each; the length follows
+// from the code) are packed into one string of up to 8 bytes in registers, joined to the bytes the lane has not
+// written yet (`carry`: the pos % 8 bytes after its last complete 8-byte piece), and one aligned 8-byte piece goes to
+// LDS when it is complete: one store per chunk instead of one per byte.  pos = bytes of the segment appended so far.
+// Pad codes (entry 0, counted as 2 bytes by the code test) only follow a complete segment: the clamp against the
+// bytes still missing drops them.
+typedef __attribute__((address_space(3))) uint64_t lds_u64;
+__device__ __forceinline__ void append_chunk(uint2 c, uint32_t strip, uint32_t seg_len, uint32_t& pos, uint64_t& carry) {
   const uint32_t e0 = lds_read16(half_offset_lo(c.x)), e1 = lds_read16(half_offset_hi(c.x));
   const uint32_t e2 = lds_read16(half_offset_lo(c.y)), e3 = lds_read16(half_offset_hi(c.y));
-  const uint32_t l0 = is_pair_lo(c.x), l1 = is_pair_hi(c.x), l2 = is_pair_lo(c.y), l3 = is_pair_hi(c.y);
-  auto put = [&](uint32_t e, uint32_t pair) {
-    *(lds_u8*)(size_t)ptr = (uint8_t)e;
-    *(lds_u8*)(size_t)(ptr + 1) = (uint8_t)(e >> 8);
-    ptr = min(ptr + 1 + pair, end);
-  };
-  put(e0, l0);
-  put(e1, l1);
-  put(e2, l2);
-  put(e3, l3);
+  const uint32_t p0 = is_pair_lo(c.x), p1 = is_pair_hi(c.x), p2 = is_pair_lo(c.y), p3 = is_pair_hi(c.y);
+  const uint32_t a01 = e1 << ((p0 << 3) + 8) | e0, n01 = p0 + p1 + 2;   // codes 0, 1: n01 = 2..4 bytes
+  const uint32_t a23 = e3 << ((p2 << 3) + 8) | e2, n23 = p2 + p3 + 2;   // codes 2, 3
+  const uint32_t t = (n01 << 3) - 8;                                    // 8, 16, 24: a23 starts 8 + t bits into the string
+  const uint32_t s0 = (a23 << t) << 8 | a01, s1 = a23 >> (24 - t);
+  const uint64_t str = (uint64_t)s1 << 32 | s0;
+  const uint32_t n = min(n01 + n23, seg_len - pos);
+  const uint32_t f = pos & 7u, sh = f << 3;
+  const uint64_t lo = carry | str << sh, hi = (str >> 1) >> (63 - sh);  // the 16 bytes carry + string; hi is 0 for f == 0
+  const bool full = f + n >= 8;
+  if (full) *(lds_u64*)(size_t)(strip + (pos & ~7u)) = lo;
+  carry = full ? hi : lo;
+  pos += n;
+}
+// The bytes after the last complete 8-byte piece (a segment whose length is not a multiple of 8).
+__device__ __forceinline__ void flush_carry(uint32_t strip, uint32_t pos, uint64_t carry) {
+  if (pos & 7u) *(lds_u64*)(size_t)(strip + (pos & ~7u)) = carry;
 }
 
 // Decode the units [u0, u1) of a matrix, one after the other, into the strips of this wavefront's tile and call
-// on_unit(band, quad) each time the tile holds a complete unit.  The code chunks of the run are contiguous in memory.
+// on_unit(band, quad) each time the tile holds a complete unit; before_last_piece(band, quad) is called ahead of the
+// unit's last piece of chunks, a few thousand clocks earlier (the place to request what on_unit will need).  The code chunks of the run are contiguous in memory.
 // They are fetched in pieces of at most kPiece chunks that never straddle a unit (a unit is cut into equal pieces);
 // two register sets alternate, so the loads of the next piece are in flight while the current one is decoded.
-constexpr int kPiece = 16;
+// Every piece issues exactly kPiece loads (those past its end repeat its last chunk): a fixed number of loads in flight
+// is what lets the compiler wait for the current piece only and not for the one just requested.
+constexpr int kPiece = 12;   // units of 256-column segments are 33..36 chunks long: three pieces with little repetition
 
-template <typename OnUnit>
-__device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0, uint32_t u1, int lane, uint32_t my_strip, OnUnit&& on_unit) {
+template <typename BeforeLast, typename OnUnit>
+__device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0, uint32_t u1, int lane, uint32_t my_strip,
+                                                   BeforeLast&& before_last_piece, OnUnit&& on_unit) {
   if (u0 >= u1) return;
   const uint2* codes = m.codes + lane;
   const uint32_t nq = m.n_quads, n_panels = (m.cols + m.seg_cols - 1) / m.seg_cols;
@@ -512,32 +527,37 @@ __device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0,
     wc += n;
     ends = --w_left == 0;
   };
+  const uint32_t run_last = unit_offset(m, u1) - 1;   // last chunk of the run
   auto load_piece = [&](uint2 (&cw)[kPiece], uint32_t start, uint32_t n) {
+    const uint32_t last = min(start + max(n, 1u) - 1, run_last);
 #pragma unroll
-    for (int k = 0; k < kPiece; ++k)
-      if ((uint32_t)k < n) cw[k] = global_load(codes + (size_t)(start + k) * 64);
+    for (int k = 0; k < kPiece; ++k) cw[k] = global_load(codes + (size_t)min(start + k, last) * 64);
   };
   // decoder state: the unit being filled
   uint32_t band = u0 / nq, quad = u0 - band * nq;
-  auto segment_end = [&]() {   // LDS address one past the lane's segment in the unit (band, quad)
+  auto segment_length = [&]() {   // of the lane's segment in the unit (band, quad)
     const uint32_t row = band * kUnitRows + (lane & 15), panel = quad * kUnitPanels + (lane >> 4);
     uint32_t len = 0;
     if (row < m.rows && panel < n_panels) len = min(m.seg_cols, m.cols - panel * m.seg_cols);
-    return my_strip + len;
+    return len;
   };
-  uint32_t ptr = my_strip, end = segment_end();
+  uint32_t pos = 0, seg_len = segment_length();
+  uint64_t carry = 0;
   auto decode_piece = [&](const uint2 (&cw)[kPiece], uint32_t n, bool ends) {
+    if (ends) before_last_piece(band, quad);
 #pragma unroll
     for (int k = 0; k < kPiece; ++k)
-      if ((uint32_t)k < n) append_chunk(cw[k], ptr, end);
+      if ((uint32_t)k < n) append_chunk(cw[k], my_strip, seg_len, pos, carry);
     if (ends) {
+      flush_carry(my_strip, pos, carry);
       on_unit(band, quad);
       if (++quad == nq) {
         quad = 0;
         ++band;
       }
-      ptr = my_strip;
-      end = segment_end();
+      pos = 0;
+      carry = 0;
+      seg_len = segment_length();
     }
   };
   uint2 cwa[kPiece], cwb[kPiece];
@@ -586,34 +606,51 @@ constexpr int kMfmaGroup = 8;   // MFMA steps per group: the activation fragment
 
 // The MFMA steps of one decoded unit: step w multiplies bytes [8 w, 8 w + 8) of every lane's strip (16 rows x 4 panels
 // x 8 columns, converted to bf16) with the activations of those 32 columns.  n_win and ragged are wave-uniform.
+// The MFMA steps of one decoded unit: step w multiplies bytes [8 w, 8 w + 8) of every lane's strip (16 rows x 4 panels
+// x 8 columns, converted to bf16) with the activations of those 32 columns.  n_win is wave-uniform.
+// Four accumulators so that consecutive MFMAs do not wait for each other; groups of kMfmaGroup steps whose weight
+// reads are all issued before the first conversion and whose activation fragments were requested a group earlier
+// (the first group by the caller, into xa).
 template <bool kFast, bool kRagged>
-__device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, global_cu16* xrow, uint32_t cols, uint32_t xcol, uint32_t n_win) {
-  uint4 xa[kMfmaGroup], xb[kMfmaGroup];
+__device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, global_cu16* xrow, uint32_t cols, uint32_t xcol, uint32_t n_win,
+                                               uint4 (&xa)[kMfmaGroup]) {
+  f32x4 part[4] = {acc, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  uint4 xb[kMfmaGroup];
+  auto request = [&](uint4 (&xf)[kMfmaGroup], uint32_t w0) {
 #pragma unroll
-  for (int k = 0; k < kMfmaGroup; ++k) xa[k] = load_x_fragment<kFast>(xrow, cols, xcol + 8 * k);
+    for (int k = 0; k < kMfmaGroup; ++k) xf[k] = load_x_fragment<kFast>(xrow, cols, xcol + 8 * (w0 + k));
+  };
+  auto run_group = [&](const uint4 (&xf)[kMfmaGroup], uint32_t w0) {
+    if (w0 + kMfmaGroup <= n_win) {   // whole group
+      u32x2 a8[kMfmaGroup];
+#pragma unroll
+      for (int k = 0; k < kMfmaGroup; ++k) a8[k] = *(lds_cu64*)(size_t)(my_strip + 8 * (w0 + k));
+#pragma unroll
+      for (int k = 0; k < kMfmaGroup; ++k) {
+        const uint4 x8 = kRagged ? mask_x_fragment<kFast>(xf[k], cols, xcol + 8 * (w0 + k)) : xf[k];
+        part[k & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8[k].x, a8[k].y)), __builtin_bit_cast(bf16x8, x8),
+                                                              part[k & 3], 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < kMfmaGroup; ++k) {
+        if (w0 + k < n_win) {
+          const u32x2 a8 = *(lds_cu64*)(size_t)(my_strip + 8 * (w0 + k));
+          const uint4 x8 = kRagged ? mask_x_fragment<kFast>(xf[k], cols, xcol + 8 * (w0 + k)) : xf[k];
+          part[k & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8.x, a8.y)), __builtin_bit_cast(bf16x8, x8),
+                                                                part[k & 3], 0, 0, 0);
+        }
+      }
+    }
+  };
+  // xa holds the first group already: it was requested before the unit's last piece of chunks was decoded
   for (uint32_t w = 0; w < n_win; w += 2 * kMfmaGroup) {
-#pragma unroll
-    for (int k = 0; k < kMfmaGroup; ++k) xb[k] = load_x_fragment<kFast>(xrow, cols, xcol + 8 * (w + kMfmaGroup + k));
-#pragma unroll
-    for (int k = 0; k < kMfmaGroup; ++k) {
-      if (w + k < n_win) {
-        const u32x2 a8 = *(lds_cu64*)(size_t)(my_strip + 8 * (w + k));
-        const uint4 x8 = kRagged ? mask_x_fragment<kFast>(xa[k], cols, xcol + 8 * (w + k)) : xa[k];
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8.x, a8.y)), __builtin_bit_cast(bf16x8, x8), acc, 0, 0, 0);
-      }
-    }
-#pragma unroll
-    for (int k = 0; k < kMfmaGroup; ++k) xa[k] = load_x_fragment<kFast>(xrow, cols, xcol + 8 * (w + 2 * kMfmaGroup + k));
-#pragma unroll
-    for (int k = 0; k < kMfmaGroup; ++k) {
-      if (w + kMfmaGroup + k < n_win) {
-        const u32x2 a8 = *(lds_cu64*)(size_t)(my_strip + 8 * (w + kMfmaGroup + k));
-        const uint4 x8 = kRagged ? mask_x_fragment<kFast>(xb[k], cols, xcol + 8 * (w + kMfmaGroup + k)) : xb[k];
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8.x, a8.y)), __builtin_bit_cast(bf16x8, x8), acc, 0, 0, 0);
-      }
-    }
+    request(xb, w + kMfmaGroup);
+    run_group(xa, w);
+    request(xa, w + 2 * kMfmaGroup);
+    run_group(xb, w + kMfmaGroup);
   }
-  return acc;
+  return (part[0] + part[1]) + (part[2] + part[3]);
 }
 
 template <int kD, bool kXFast>
@@ -668,15 +705,20 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
     global_cu16* xrow = (global_cu16*)job.x + (size_t)min(bn, a.batch - 1) * m.cols;
     const uint32_t first_band = u0 / nq;
     const bool first_whole = u0 % nq == 0;
-    decode_run_to_tile(m, u0, u1, lane, my_strip, [&](uint32_t band, uint32_t quad) {
+    uint4 xa[kMfmaGroup];   // activation fragments of the first MFMA group of the unit being decoded
+    decode_run_to_tile(m, u0, u1, lane, my_strip, [&](uint32_t, uint32_t quad) {
+#pragma unroll
+      for (int k = 0; k < kMfmaGroup; ++k)
+        xa[k] = load_x_fragment<kXFast>(xrow, m.cols, (quad * kUnitPanels + (uint32_t)kg) * m.seg_cols + 8 * k);
+    }, [&](uint32_t band, uint32_t quad) {
       const uint32_t col0 = quad * kUnitPanels * m.seg_cols;                            // first column of the unit
       const uint32_t width = min(m.seg_cols, m.cols - col0);                            // its widest segment is the first panel's
       const uint32_t n_win = (width + 7) / 8;
       const uint32_t xcol = col0 + (uint32_t)kg * m.seg_cols;
       if (!kXFast || col0 + kUnitPanels * m.seg_cols > m.cols)   // some fragment reaches past the row's end
-        acc = multiply_unit<kXFast, true>(acc, my_strip, xrow, m.cols, xcol, n_win);
+        acc = multiply_unit<kXFast, true>(acc, my_strip, xrow, m.cols, xcol, n_win, xa);
       else
-        acc = multiply_unit<kXFast, false>(acc, my_strip, xrow, m.cols, xcol, n_win);
+        acc = multiply_unit<kXFast, false>(acc, my_strip, xrow, m.cols, xcol, n_win, xa);
       const bool band_ends = quad + 1 == nq, run_ends = band * nq + quad + 1 == u1;
       if (band_ends || run_ends) {
         if (band_ends && (band != first_band || first_whole)) {
@@ -698,7 +740,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
     });
     __syncthreads();   // every wavefront is done with its tile: the partial sums go over the tile area
     float* slot_val = (float*)tiles;                                 // [2 * n_waves][256]
-    int* slot_band = (int*)((uint8_t*)lds4 + a.slot_off);            // [2 * n_waves]
+    int* slot_band = (int*)(slot_val + 2 * n_waves * 256);           // [2 * n_waves], also inside the tile area
     if (lane == 0) {
       slot_band[2 * wave] = head_band;
       slot_band[2 * wave + 1] = tail_band;
@@ -777,7 +819,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_decompress(MatvecArgs a) {
     int8_t* out = (int8_t*)job.y;
     const bool aligned = (m.cols % 16 == 0) && ((uintptr_t)out % 16 == 0);
     const uint32_t ppp = m.seg_cols / 16;   // 16-byte pieces per segment
-    decode_run_to_tile(m, u0, u1, lane, tile_lds + (uint32_t)lane * strip, [&](uint32_t band, uint32_t quad) {
+    decode_run_to_tile(m, u0, u1, lane, tile_lds + (uint32_t)lane * strip, [](uint32_t, uint32_t) {}, [&](uint32_t band, uint32_t quad) {
       for (uint32_t pc = lane; pc < 64 * ppp; pc += 64) {
         const uint32_t seg = pc / ppp, part = pc - seg * ppp;            // segment (row seg / 4, panel seg % 4) of the unit
         const uint32_t row = band * kUnitRows + (seg >> 2), col = (quad * kUnitPanels + (seg & 3)) * m.seg_cols + part * 16;
@@ -921,7 +963,7 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
     return TQ_E_UNSUPPORTED;
   }
   // tq_decompress and the batched product: 16-bit dictionary image plus one tile of 64 strips per wavefront.
-  if (round_up((uint64_t)m.dict_words * 2, 16) + (size_t)64 * (h.seg_cols + 8) + 64 > kLdsLimit) {
+  if (round_up((uint64_t)m.dict_words * 2, 16) + (size_t)64 * (h.seg_cols + 8) > kLdsLimit) {
     set_error("segments of " + std::to_string(h.seg_cols) + " columns do not fit the LDS tile");
     return TQ_E_UNSUPPORTED;
   }
@@ -1031,18 +1073,18 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     hipLaunchKernelGGL((k_matvec<kDepth, kDotWaves>), dim3((unsigned)grid), dim3(kDotWaves * 64), lds_total, stream, a);
   } else {
     // Tile decode.  LDS: 16-bit dictionary image | one tile (64 strips) per wavefront, which the batched product reuses
-    // for its partial sums (two slots of 1 KB per wavefront) | slot ids.
+    // for its partial sums (per wavefront two slots of 1 KB and their two band numbers).
     const size_t dict16 = round_up((uint64_t)dict_words_max * 2, 16);
-    const size_t area = std::max<size_t>((size_t)64 * (seg_max + 8), 2048);
-    const size_t waves = std::min<size_t>(kWaves, (kLdsLimit - dict16 - 64) / area);
+    const size_t area = std::max<size_t>((size_t)64 * (seg_max + 8), 2048 + 8);
+    const size_t waves = std::min<size_t>(kWaves, (kLdsLimit - dict16) / area);
     if (waves == 0) {
       set_error("segments of " + std::to_string(seg_max) + " columns do not fit the LDS tile");
       return TQ_E_UNSUPPORTED;
     }
     a.x_off = (uint32_t)dict16;
     a.tile_area = (uint32_t)area;
-    a.slot_off = (uint32_t)(dict16 + waves * area);
-    const size_t lds = a.slot_off + 64;
+    a.slot_off = 0;
+    const size_t lds = dict16 + waves * area;
     const dim3 block((unsigned)waves * 64);
     if (op == Op::kDecompress) hipLaunchKernelGGL(k_decompress, dim3((unsigned)grid), block, lds, stream, a);
     else if (x_fast) hipLaunchKernelGGL((k_matvec_mfma<kDepth, true>), dim3((unsigned)grid), block, lds, stream, a);
