@@ -37,10 +37,13 @@ constexpr int kDepth = 16;           // chunks of code loads kept in flight per 
                                      // 3B sweep: 8 in flight 4.57 TB/s, 12 and 16 in flight 4.90 TB/s)
 constexpr uint32_t kLdsLimit = 160 * 1024;
 constexpr int kMaxMulti = 128;       // matrices one launch can serve (bounded by the 4 KB of kernel arguments)
+constexpr int kInlineDescriptions = 4;
 
 // What the kernels need to know about one matrix.
 struct DevMat {
   const uint32_t* dict;    // container dictionary words (run bytes + length), dict_words of them, zero filled past the pad entry
+  const uint32_t* dict_bf16;   // the same entries as two bf16 weights each (second one zero for a single byte): the form the
+                               // batch-1 kernel keeps in LDS, made once when the dictionary is uploaded
   const uint32_t* uoff;    // n_units + 1 unit offsets, in chunks
   const uint2* codes;      // chunk c, lane l -> codes[c * 64 + l] (4 codes)
   const float* scales;     // n_bands * 16 row scales
@@ -67,6 +70,8 @@ struct MatvecArgs {
   uint32_t reserved;
   uint32_t cost[kMaxMulti + 1];
   Job j[kMaxMulti];
+  DevMat first[kInlineDescriptions];   // descriptions of the first matrices by value: a launch of one matrix (or of a
+                                       // few) does not wait for a read of device memory before it can start loading
 };
 static_assert(sizeof(MatvecArgs) <= 4096, "kernel arguments");
 
@@ -157,31 +162,25 @@ __device__ __forceinline__ float dot2(uint32_t w, uint32_t x, float acc) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, x), acc, false);
 }
 
-// int8 -> bf16 bit pattern (exact: |v| <= 128 needs 8 significant bits); bf16 = upper half of the fp32 encoding.
-__device__ __forceinline__ uint32_t i8_to_bf16_bits(uint32_t byte) { return __float_as_uint((float)(int)(int8_t)byte) >> 16; }
-
 // Staging is split in two so that the loads of the dictionary, of the activations and of the first code chunks are
 // all in flight together before anything waits: issue_* only loads into registers, commit_* writes LDS.
 constexpr int kDictRegs = 16;   // uint4 per thread per round of the tile kernels' dictionary staging
 
 template <int kThreads, int kDictRegs>   // kDictRegs x kThreads x 16 bytes per round (128 KB: the whole dictionary in one)
 __device__ __forceinline__ void issue_dictionary(const DevMat& m, uint32_t base, int tid, uint4 (&v)[kDictRegs]) {
-  const uint4* src = (const uint4*)m.dict;
+  const uint4* src = (const uint4*)m.dict_bf16;
   const uint32_t n4 = m.dict_words / 4;
 #pragma unroll
   for (int k = 0; k < kDictRegs; ++k) v[k] = global_load(src + min(base + k * kThreads + tid, n4 - 1));
 }
-// Container word (b0, b1, -, length) -> (bf16(b0), bf16(b1)).  Bytes past an entry's length are zero in the container,
-// so a single-byte entry gets a zero second weight and the pad entry two.
 template <int kThreads, int kDictRegs>
 __device__ __forceinline__ void commit_dictionary(const DevMat& m, uint32_t base, int tid, const uint4 (&v)[kDictRegs], uint32_t* lds_dict) {
   uint4* dst = (uint4*)lds_dict;
   const uint32_t n4 = m.dict_words / 4;
-  auto cv = [](uint32_t w) { return i8_to_bf16_bits(w & 0xFFu) | i8_to_bf16_bits(w >> 8 & 0xFFu) << 16; };
 #pragma unroll
   for (int k = 0; k < kDictRegs; ++k) {
     const uint32_t i = base + k * kThreads + tid;
-    if (i < n4) dst[i] = make_uint4(cv(v[k].x), cv(v[k].y), cv(v[k].z), cv(v[k].w));
+    if (i < n4) dst[i] = v[k];
   }
 }
 
@@ -290,14 +289,14 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
     const uint32_t cb = a.cost[i], ce = a.cost[i + 1];
     if (hi <= cb || lo >= ce) continue;
     const Job job = a.j[i];
-    const DevMat m = load_description(job.m);
+    const DevMat m = i < kInlineDescriptions ? a.first[i] : load_description(job.m);
     // a band goes to the share that holds its middle
     const uint32_t bc = m.cols;
     const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
     const uint32_t band_hi = hi >= ce ? m.n_bands : min(m.n_bands, (hi - cb + bc / 2) / bc);
     if (band_lo >= band_hi) continue;
-    const bool new_dict = m.dict != staged;
-    staged = m.dict;
+    const bool new_dict = m.dict_bf16 != staged;
+    staged = m.dict_bf16;
     const uint32_t nq = m.n_quads, n_slots = nq * kUnitPanels, image_cols = n_slots * m.seg_cols;
     const uint32_t unit_lo = band_lo * nq, n_units = (band_hi - band_lo) * nq;
     const uint32_t u0 = unit_lo + (uint32_t)((uint64_t)n_units * wave / kWaves);
@@ -353,11 +352,13 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
         uint32_t xa = xa_lane + q * xa_quad;
         // two operand sets used alternately (kD is even): slot d loads into ops[d & 1] and finishes ops[(d - 1) & 1]
         Operands ops[2] = {{0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u}};   // zero weights: finishing adds nothing
+        // the scales of the band in work are requested when the band starts (the array is padded to whole bands)
+        float scale = global_load(m.scales + band * kUnitRows + (lane & 15));
         auto finish_band = [&](bool complete) {
           const float v = sum_over_panels(a0 + a1);
           if (complete) {
             const uint32_t row = band * kUnitRows + lane;
-            if (lane < 16 && row < m.rows) global_store(yb + row, v * global_load(m.scales + row));
+            if (lane < 16 && row < m.rows) global_store(yb + row, v * scale);
           } else {
             const int s = 2 * wave + (whole ? 1 : 0);   // slot 2w: band begun by an earlier wavefront; 2w + 1: band left unfinished
             if (lane < 16) slot_val[s * 16 + lane] = v;
@@ -377,6 +378,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
                   finish_band(whole);
                   q = 0;
                   ++band;
+                  scale = global_load(m.scales + band * kUnitRows + (lane & 15));   // a next unit exists, so does this band
                   whole = true;
                   a0 = 0.f;
                   a1 = 0.f;
@@ -669,7 +671,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
     const uint32_t cb = a.cost[i], ce = a.cost[i + 1];
     if (hi <= cb || lo >= ce) continue;
     const Job job = a.j[i];
-    const DevMat m = load_description(job.m);
+    const DevMat m = i < kInlineDescriptions ? a.first[i] : load_description(job.m);
     const uint32_t bc = m.cols;
     const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
     const uint32_t band_hi = hi >= ce ? m.n_bands : min(m.n_bands, (hi - cb + bc / 2) / bc);
@@ -787,7 +789,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_decompress(MatvecArgs a) {
     const uint32_t cb = a.cost[i], ce = a.cost[i + 1];
     if (hi <= cb || lo >= ce) continue;
     const Job job = a.j[i];
-    const DevMat m = load_description(job.m);
+    const DevMat m = i < kInlineDescriptions ? a.first[i] : load_description(job.m);
     const uint32_t bc = m.cols;
     const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
     const uint32_t band_hi = hi >= ce ? m.n_bands : min(m.n_bands, (hi - cb + bc / 2) / bc);
@@ -858,9 +860,18 @@ int hip_fail(const char* what, hipError_t e) {
 struct DictCopy {
   int device;
   std::vector<uint32_t> words;   // host copy for the comparison
-  uint32_t* dev;
+  uint32_t* dev;        // container words
+  uint32_t* dev_bf16;   // (bf16(b0), bf16(b1)) per entry; a single-byte entry has a zero second weight, the pad entry two
   int refs;
 };
+
+// int8 -> bf16 bit pattern (exact: |v| <= 128 needs 8 significant bits); bf16 = upper half of the fp32 encoding.
+uint32_t i8_to_bf16_bits(uint32_t byte) {
+  const float f = (float)(int8_t)byte;
+  uint32_t u;
+  std::memcpy(&u, &f, 4);
+  return u >> 16;
+}
 std::mutex g_dict_mutex;
 std::vector<DictCopy*> g_dicts;
 
@@ -880,12 +891,18 @@ int acquire_dictionary(int device, const uint32_t* words, uint32_t n_words, uint
   d->device = device;
   d->words.assign(words, words + n_words);
   d->refs = 1;
-  d->dev = nullptr;
+  d->dev = d->dev_bf16 = nullptr;
+  // bytes past an entry's length are zero in the container, so the conversion needs no length test
+  std::vector<uint32_t> pairs(n_words_pad, 0u);
+  for (uint32_t i = 0; i < n_words; ++i) pairs[i] = i8_to_bf16_bits(words[i] & 0xFFu) | i8_to_bf16_bits(words[i] >> 8 & 0xFFu) << 16;
   hipError_t e = hipMalloc((void**)&d->dev, (size_t)n_words_pad * 4);
+  if (e == hipSuccess) e = hipMalloc((void**)&d->dev_bf16, (size_t)n_words_pad * 4);
   if (e == hipSuccess) e = hipMemset(d->dev, 0, (size_t)n_words_pad * 4);
   if (e == hipSuccess) e = hipMemcpy(d->dev, words, (size_t)n_words * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(d->dev_bf16, pairs.data(), (size_t)n_words_pad * 4, hipMemcpyHostToDevice);
   if (e != hipSuccess) {
     if (d->dev) (void)hipFree(d->dev);
+    if (d->dev_bf16) (void)hipFree(d->dev_bf16);
     delete d;
     return hip_fail("dictionary upload", e);
   }
@@ -899,8 +916,9 @@ hipError_t release_dictionary(DictCopy* d) {
   if (--d->refs > 0) return hipSuccess;
   g_dicts.erase(std::find(g_dicts.begin(), g_dicts.end(), d));
   hipError_t e = hipFree(d->dev);
+  hipError_t e2 = hipFree(d->dev_bf16);
   delete d;
-  return e;
+  return e != hipSuccess ? e : e2;
 }
 
 constexpr uint32_t kSlotBytes = 2 * kDotWaves * 16 * 4 + 2 * kDotWaves * 4;
@@ -1004,6 +1022,7 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   if (e == hipSuccess) e = hipMemcpy(base + o_codes, src + h.off_codes, h.code_bytes, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(base + o_scales, src + h.off_scales, h.scale_bytes, hipMemcpyHostToDevice);
   m.dict = dict->dev;
+  m.dict_bf16 = dict->dev_bf16;
   m.uoff = (const uint32_t*)(base + o_uoff);
   m.codes = (const uint2*)(base + o_codes);
   m.scales = (const float*)(base + o_scales);
@@ -1045,6 +1064,7 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
   for (int i = 0; i < n; ++i) {
     const tq_matrix* t = hs[i];
     a.j[i].m = t->m_dev;
+    if (i < kInlineDescriptions) a.first[i] = t->m;
     a.j[i].x = xs ? (const uint16_t*)xs[i] : nullptr;
     a.j[i].y = (float*)ys[i];
     a.cost[i] = (uint32_t)cost;
