@@ -36,6 +36,8 @@ constexpr int kDotWaves = 8;         // wavefronts per workgroup of the batch-1 
 constexpr int kDepth = 16;           // chunks of code loads kept in flight per wavefront (16 x 512 bytes; measured on the
                                      // 3B sweep: 8 in flight 4.57 TB/s, 12 and 16 in flight 4.90 TB/s)
 constexpr uint32_t kLdsLimit = 160 * 1024;
+constexpr int kPiece = 12;           // code chunks fetched together by a wavefront (units of 256-column segments are
+                                     // 33..36 chunks long: three pieces with little repetition)
 constexpr int kMaxMulti = 128;       // matrices one launch can serve (bounded by the 4 KB of kernel arguments)
 constexpr int kInlineDescriptions = 4;
 
@@ -248,11 +250,20 @@ __device__ __forceinline__ void issue_chunk(uint2 c, uint32_t& xa, Operands& o) 
   o.x3 = lds_read32_off<4 * kCode0 + 12>(xa);
   xa = (is_pair_hi(c.y) << 2) + xa;
 }
+template <int kCode0>
+__device__ __forceinline__ void chunk4(uint2 c, uint32_t& xa, float& a0, float& a1);
 __device__ __forceinline__ void finish_chunk(const Operands& o, float& a0, float& a1) {
   a0 = dot2(o.w0, o.x0, a0);
   a1 = dot2(o.w1, o.x1, a1);
   a0 = dot2(o.w2, o.x2, a0);
   a1 = dot2(o.w3, o.x3, a1);
+}
+
+template <int kCode0>
+__device__ __forceinline__ void chunk4(uint2 c, uint32_t& xa, float& a0, float& a1) {
+  Operands o;
+  issue_chunk<kCode0>(c, xa, o);
+  finish_chunk(o, a0, a1);
 }
 
 // Sum of the four panel lanes of each row: afterwards every lane l holds the sum over lanes l % 16 + {0, 16, 32, 48}.
@@ -310,15 +321,6 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
     for (int b = 0; b < a.batch; ++b) {
       const uint16_t* xb = job.x + (size_t)b * m.cols;
       float* yb = job.y + (size_t)b * m.rows;
-      // first the code chunks, then dictionary and activations: everything is in flight before the first wait
-      uint2 cw[kD];
-      if (u0 < u1) {
-#pragma unroll
-        for (int d = 0; d < kD; ++d) {
-          cw[d] = global_load(p + (size_t)min((uint32_t)d, n_chunks - 1) * 64);
-          __builtin_amdgcn_sched_barrier(0);   // issue in consumption order: loads return in order, the loop waits per slot
-        }
-      }
       __syncthreads();   // the previous dictionary, activation image and slots are no longer in use
       {
         uint4 dv[kDictRegs];
@@ -345,13 +347,10 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
       }
       __syncthreads();
       if (u0 < u1) {
-        uint32_t u = u0, q = u0 % nq, band = u0 / nq;
-        uint32_t ubound = unit_offset(m, u0 + 1) - c0;   // first chunk (relative) of the next unit
+        uint32_t q = u0 % nq, band = u0 / nq;
         bool whole = q == 0;                             // the current band started inside this wavefront's run
         float a0 = 0.f, a1 = 0.f;
         uint32_t xa = xa_lane + q * xa_quad;
-        // two operand sets used alternately (kD is even): slot d loads into ops[d & 1] and finishes ops[(d - 1) & 1]
-        Operands ops[2] = {{0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u}};   // zero weights: finishing adds nothing
         // the scales of the band in work are requested when the band starts (the array is padded to whole bands)
         float scale = global_load(m.scales + band * kUnitRows + (lane & 15));
         auto finish_band = [&](bool complete) {
@@ -365,37 +364,79 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
             if (lane == 0) slot_band[s] = (int)band;
           }
         };
-        for (uint32_t r = 0; r < n_chunks; r += kD) {
-          static_for<kD>([&](auto dd) {
-            constexpr int d = decltype(dd)::value;
-            if (r + d < n_chunks) {
-              if (r + d == ubound) {   // unit boundary: every lane restarts at the first column of its next segment
-                ++u;
-                if (++q == nq) {
-                  Operands& last = ops[(d + 1) & 1];
-                  finish_chunk(last, a0, a1);
-                  last.w0 = last.w1 = last.w2 = last.w3 = 0u;
-                  finish_band(whole);
-                  q = 0;
-                  ++band;
-                  scale = global_load(m.scales + band * kUnitRows + (lane & 15));   // a next unit exists, so does this band
-                  whole = true;
-                  a0 = 0.f;
-                  a1 = 0.f;
-                }
-                ubound = unit_offset(m, u + 1) - c0;
-                xa = xa_lane + q * xa_quad - 16u * d;
-              }
-              issue_chunk<4 * d>(cw[d], xa, ops[d & 1]);
-              finish_chunk(ops[(d + 1) & 1], a0, a1);
+        // The chunks of the run come in pieces of at most kPiece that never straddle a unit (a unit is cut into equal
+        // pieces); two register sets alternate and every piece issues exactly kPiece loads (those past its end repeat
+        // its last chunk), so the loads of the next piece are in flight while this one is worked on.  A piece of kPiece
+        // or kPiece - 1 chunks (all pieces of a unit of 256-column segments) runs as straight-line code: the LDS reads
+        // of later chunks overlap the dot products of earlier ones.
+        uint32_t wu = u0, wc = c0, w_left = 0, w_base = 0, w_rem = 0;
+        auto next_piece = [&](uint32_t& start, uint32_t& n, bool& ends) {
+          if (w_left == 0) {
+            if (wu == u1) {
+              n = 0;
+              ends = false;
+              start = wc;
+              return;
             }
-            cw[d] = global_load(p + (size_t)min(r + d + kD, n_chunks - 1) * 64);   // refill the slot only after its last use
-          });
-          xa += 16 * kD;
+            const uint32_t len = unit_offset(m, wu + 1) - wc;
+            w_left = (len + kPiece - 1) / kPiece;
+            w_base = len / w_left;
+            w_rem = len - w_base * w_left;
+            ++wu;
+          }
+          n = w_base + (w_rem ? 1u : 0u);
+          if (w_rem) --w_rem;
+          start = wc;
+          wc += n;
+          ends = --w_left == 0;
+        };
+        const uint32_t run_last = c0 + n_chunks - 1;
+        const uint2* codes = m.codes + lane;
+        auto load_piece = [&](uint2 (&cw)[kPiece], uint32_t start, uint32_t n) {
+          const uint32_t last = min(start + max(n, 1u) - 1, run_last);
+#pragma unroll
+          for (int k = 0; k < kPiece; ++k) cw[k] = global_load(codes + (size_t)min(start + k, last) * 64);
+        };
+        auto run_piece = [&](const uint2 (&cw)[kPiece], uint32_t n, bool ends) {
+          if (n == kPiece) {
+            static_for<kPiece>([&](auto kk) { chunk4<4 * decltype(kk)::value>(cw[decltype(kk)::value], xa, a0, a1); });
+          } else if (n == kPiece - 1) {
+            static_for<kPiece - 1>([&](auto kk) { chunk4<4 * decltype(kk)::value>(cw[decltype(kk)::value], xa, a0, a1); });
+          } else {
+            static_for<kPiece>([&](auto kk) {
+              constexpr int k = decltype(kk)::value;
+              if ((uint32_t)k < n) chunk4<4 * k>(cw[k], xa, a0, a1);
+            });
+          }
+          xa += 16 * n;
+          if (ends) {   // every lane restarts at the first column of its next segment
+            if (++q == nq) {
+              const bool more = band * nq + nq < u1;
+              finish_band(whole);
+              q = 0;
+              ++band;
+              if (more) scale = global_load(m.scales + band * kUnitRows + (lane & 15));
+              whole = true;
+              a0 = 0.f;
+              a1 = 0.f;
+            }
+            xa = xa_lane + q * xa_quad;
+          }
+        };
+        uint2 cwa[kPiece], cwb[kPiece];
+        uint32_t sa, na, sb, nb;
+        bool ea, eb;
+        next_piece(sa, na, ea);
+        load_piece(cwa, sa, na);
+        while (na) {
+          next_piece(sb, nb, eb);
+          load_piece(cwb, sb, nb);
+          run_piece(cwa, na, ea);
+          next_piece(sa, na, ea);
+          load_piece(cwa, sa, na);
+          run_piece(cwb, nb, eb);
         }
-        if ((n_chunks - 1) & 1) finish_chunk(ops[1], a0, a1);   // the last chunk's operands are still waiting
-        else finish_chunk(ops[0], a0, a1);
-        finish_band(whole && (u1 % nq == 0));
+        if (u1 % nq) finish_band(false);   // the run ends inside a band (a band that ends with the run was finished above)
       }
       __syncthreads();
       // Combine the shared bands: the first slot of a band adds the later slots of the same band in slot order.
@@ -499,7 +540,6 @@ __device__ __forceinline__ void flush_carry(uint32_t strip, uint32_t pos, uint64
 // two register sets alternate, so the loads of the next piece are in flight while the current one is decoded.
 // Every piece issues exactly kPiece loads (those past its end repeat its last chunk): a fixed number of loads in flight
 // is what lets the compiler wait for the current piece only and not for the one just requested.
-constexpr int kPiece = 12;   // units of 256-column segments are 33..36 chunks long: three pieces with little repetition
 
 template <typename BeforeLast, typename OnUnit>
 __device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0, uint32_t u1, int lane, uint32_t my_strip,
