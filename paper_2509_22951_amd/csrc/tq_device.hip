@@ -33,8 +33,8 @@ constexpr int kWaves = 8;            // most wavefronts per workgroup of the til
 constexpr int kThreads = kWaves * 64;
 constexpr int kDotWaves = 8;         // wavefronts per workgroup of the batch-1 kernel (measured on the 3B sweep, TB/s:
                                      // 6 waves 4.61, 8 waves 5.12, 10 waves 4.64, 12 waves 4.90, 16 waves 4.28)
-constexpr int kDepth = 16;           // chunks of code loads kept in flight per wavefront (16 x 512 bytes; measured on the
-                                     // 3B sweep: 8 in flight 4.57 TB/s, 12 and 16 in flight 4.90 TB/s)
+constexpr int kDotPiece = 8;         // chunks per piece in the batch-1 kernel: two pieces (16 x 512 bytes) are in flight per
+                                     // wavefront (measured on the 3B sweep, TB/s: 4 chunks 5.30, 6 5.48, 8 5.47, 12 5.41, 18 5.24)
 constexpr uint32_t kLdsLimit = 160 * 1024;
 constexpr int kPiece = 12;           // code chunks fetched together by a wavefront (units of 256-column segments are
                                      // 33..36 chunks long: three pieces with little repetition)
@@ -227,43 +227,26 @@ __device__ __forceinline__ void zero_activation_gaps(const DevMat& m, int tid, u
 }
 
 // One chunk = 4 codes per lane.  xa = LDS byte address of the activation pair of the lane's next code, minus 4 bytes
-// per code consumed since the last rebase; code k of the body therefore reads at xa + 4 k, and the constant part goes
-// into the instruction's offset field.  A single advances the lane by one column (already counted by the 4 k), a pair
-// by one more.  The dictionary sits at LDS address 0, so a code's word offset is its address.
-// The chunk is split in two: issue_chunk starts the 8 LDS reads, finish_chunk does the 4 dot products one step later,
-// so that the reads of the next chunk are in flight while the products of this one execute.
-struct Operands {
-  uint32_t w0, w1, w2, w3, x0, x1, x2, x3;
-};
-template <int kCode0>
-__device__ __forceinline__ void issue_chunk(uint2 c, uint32_t& xa, Operands& o) {
-  o.w0 = lds_read32(word_offset_lo(c.x));
-  o.w1 = lds_read32(word_offset_hi(c.x));
-  o.w2 = lds_read32(word_offset_lo(c.y));
-  o.w3 = lds_read32(word_offset_hi(c.y));
-  o.x0 = lds_read32_off<4 * kCode0>(xa);
-  xa = (is_pair_lo(c.x) << 2) + xa;
-  o.x1 = lds_read32_off<4 * kCode0 + 4>(xa);
-  xa = (is_pair_hi(c.x) << 2) + xa;
-  o.x2 = lds_read32_off<4 * kCode0 + 8>(xa);
-  xa = (is_pair_lo(c.y) << 2) + xa;
-  o.x3 = lds_read32_off<4 * kCode0 + 12>(xa);
-  xa = (is_pair_hi(c.y) << 2) + xa;
-}
-template <int kCode0>
-__device__ __forceinline__ void chunk4(uint2 c, uint32_t& xa, float& a0, float& a1);
-__device__ __forceinline__ void finish_chunk(const Operands& o, float& a0, float& a1) {
-  a0 = dot2(o.w0, o.x0, a0);
-  a1 = dot2(o.w1, o.x1, a1);
-  a0 = dot2(o.w2, o.x2, a0);
-  a1 = dot2(o.w3, o.x3, a1);
-}
-
+// per code consumed since the start of the piece; code k of the piece therefore reads at xa + 4 k, and the constant
+// part goes into the instruction's offset field.  A single advances the lane by one column (already counted by the
+// 4 k), a pair by one more.  The dictionary sits at LDS address 0, so a code's word offset is its address.
+// Per chunk and lane: 4 dictionary words, 4 activation pairs, 4 v_dot2_f32_bf16 into two accumulators.
 template <int kCode0>
 __device__ __forceinline__ void chunk4(uint2 c, uint32_t& xa, float& a0, float& a1) {
-  Operands o;
-  issue_chunk<kCode0>(c, xa, o);
-  finish_chunk(o, a0, a1);
+  const uint32_t w0 = lds_read32(word_offset_lo(c.x)), w1 = lds_read32(word_offset_hi(c.x));
+  const uint32_t w2 = lds_read32(word_offset_lo(c.y)), w3 = lds_read32(word_offset_hi(c.y));
+  const uint32_t x0 = lds_read32_off<4 * kCode0>(xa);
+  xa = (is_pair_lo(c.x) << 2) + xa;
+  const uint32_t x1 = lds_read32_off<4 * kCode0 + 4>(xa);
+  xa = (is_pair_hi(c.x) << 2) + xa;
+  const uint32_t x2 = lds_read32_off<4 * kCode0 + 8>(xa);
+  xa = (is_pair_lo(c.y) << 2) + xa;
+  const uint32_t x3 = lds_read32_off<4 * kCode0 + 12>(xa);
+  xa = (is_pair_hi(c.y) << 2) + xa;
+  a0 = dot2(w0, x0, a0);
+  a1 = dot2(w1, x1, a1);
+  a0 = dot2(w2, x2, a0);
+  a1 = dot2(w3, x3, a1);
 }
 
 // Sum of the four panel lanes of each row: afterwards every lane l holds the sum over lanes l % 16 + {0, 16, 32, 48}.
@@ -273,18 +256,17 @@ __device__ __forceinline__ float sum_over_panels(float v) {
   return v;
 }
 
-// Fused decode + dequantize + matrix-vector product for up to kMaxMulti matrices.
+// Fused decode + dequantize + matrix-vector product for one activation row and up to kMaxMulti matrices.
 //
 // The launch's work is the line of all bands (16 rows each) of all matrices, each band weighted by its number of
-// weights; workgroup g takes the bands that start inside the g-th equal share of that line, so a workgroup serves a
+// weights; workgroup g takes the bands whose middle lies in the g-th equal share of that line, so a workgroup serves a
 // contiguous range of whole bands of one matrix after the other.  Inside a matrix the units of those bands are
 // contiguous in the code stream and are cut into one contiguous run per wavefront.  A wavefront owns every band that
 // lies entirely inside its run (it scales and stores those rows itself); a band it shares with its neighbours goes to
 // one of two partial-sum slots in LDS, and after a workgroup barrier the slots of a band are added in wavefront order,
 // so the result does not depend on timing.
-template <int kD, int kWaves>
+template <int kPiece, int kWaves>
 __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
-  static_assert(kD % 2 == 0, "the operand sets alternate with the slot index");
   constexpr int kThreads = kWaves * 64, kDictRegs = 128 / kWaves, kXRegs = 64 / kWaves;
   extern __shared__ uint4 lds4[];
   uint32_t* lds_dict = (uint32_t*)lds4;
@@ -317,15 +299,14 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
     const uint32_t xa_quad = 16u * m.x_span;
     const bool x_aligned = (m.cols % 2 == 0) && ((uintptr_t)job.x % 4 == 0);
     const uint32_t c0 = u0 < u1 ? unit_offset(m, u0) : 0u, n_chunks = u0 < u1 ? unit_offset(m, u1) - c0 : 0u;
-    const uint2* p = m.codes + (size_t)c0 * 64 + lane;
-    for (int b = 0; b < a.batch; ++b) {
-      const uint16_t* xb = job.x + (size_t)b * m.cols;
-      float* yb = job.y + (size_t)b * m.rows;
+    {   // one activation row: larger batches run the MFMA kernel
+      const uint16_t* xb = job.x;
+      float* yb = job.y;
       __syncthreads();   // the previous dictionary, activation image and slots are no longer in use
       {
         uint4 dv[kDictRegs];
         uint32_t xlo[kXRegs], xhi[kXRegs];
-        const bool dict_now = new_dict && b == 0;
+        const bool dict_now = new_dict;
         if (dict_now) issue_dictionary<kThreads, kDictRegs>(m, 0, tid, dv);
         if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
         else issue_activations<false, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
@@ -402,6 +383,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
             static_for<kPiece>([&](auto kk) { chunk4<4 * decltype(kk)::value>(cw[decltype(kk)::value], xa, a0, a1); });
           } else if (n == kPiece - 1) {
             static_for<kPiece - 1>([&](auto kk) { chunk4<4 * decltype(kk)::value>(cw[decltype(kk)::value], xa, a0, a1); });
+          } else if (n == kPiece - 2) {
+            static_for<kPiece - 2>([&](auto kk) { chunk4<4 * decltype(kk)::value>(cw[decltype(kk)::value], xa, a0, a1); });
           } else {
             static_for<kPiece>([&](auto kk) {
               constexpr int k = decltype(kk)::value;
@@ -695,7 +678,7 @@ __device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, glo
   return (part[0] + part[1]) + (part[2] + part[3]);
 }
 
-template <int kD, bool kXFast>
+template <bool kXFast>
 __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
   extern __shared__ uint4 lds4[];
   uint16_t* lds_dict = (uint16_t*)lds4;
@@ -1037,10 +1020,10 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
     return TQ_E_UNSUPPORTED;
   }
   // Dynamic LDS above 64 KB has to be allowed per kernel function.
-  e = hipFuncSetAttribute((const void*)k_matvec<kDepth, kDotWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_decompress, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<kDepth, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<kDepth, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
 
   const uint8_t* src = (const uint8_t*)blob;
@@ -1130,7 +1113,7 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
       set_error("the matrices of this call together need " + std::to_string(lds_total) + " bytes of LDS (largest dictionary plus longest row)");
       return TQ_E_UNSUPPORTED;
     }
-    hipLaunchKernelGGL((k_matvec<kDepth, kDotWaves>), dim3((unsigned)grid), dim3(kDotWaves * 64), lds_total, stream, a);
+    hipLaunchKernelGGL((k_matvec<kDotPiece, kDotWaves>), dim3((unsigned)grid), dim3(kDotWaves * 64), lds_total, stream, a);
   } else {
     // Tile decode.  LDS: 16-bit dictionary image | one tile (64 strips) per wavefront, which the batched product reuses
     // for its partial sums (per wavefront two slots of 1 KB and their two band numbers).
@@ -1147,8 +1130,8 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     const size_t lds = dict16 + waves * area;
     const dim3 block((unsigned)waves * 64);
     if (op == Op::kDecompress) hipLaunchKernelGGL(k_decompress, dim3((unsigned)grid), block, lds, stream, a);
-    else if (x_fast) hipLaunchKernelGGL((k_matvec_mfma<kDepth, true>), dim3((unsigned)grid), block, lds, stream, a);
-    else hipLaunchKernelGGL((k_matvec_mfma<kDepth, false>), dim3((unsigned)grid), block, lds, stream, a);
+    else if (x_fast) hipLaunchKernelGGL((k_matvec_mfma<true>), dim3((unsigned)grid), block, lds, stream, a);
+    else hipLaunchKernelGGL((k_matvec_mfma<false>), dim3((unsigned)grid), block, lds, stream, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(op == Op::kDecompress ? "tq_decompress launch" : "tq_matvec launch", e);
