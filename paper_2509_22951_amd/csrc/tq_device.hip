@@ -570,9 +570,17 @@ __device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0,
   uint64_t carry = 0;
   auto decode_piece = [&](const uint2 (&cw)[kPiece], uint32_t n, bool ends) {
     if (ends) before_last_piece(band, quad);
+    if (n == kPiece) {   // whole pieces as straight-line code: the dictionary reads of later chunks overlap the packing of earlier ones
 #pragma unroll
-    for (int k = 0; k < kPiece; ++k)
-      if ((uint32_t)k < n) append_chunk(cw[k], my_strip, seg_len, pos, carry);
+      for (int k = 0; k < kPiece; ++k) append_chunk(cw[k], my_strip, seg_len, pos, carry);
+    } else if (n == kPiece - 1) {
+#pragma unroll
+      for (int k = 0; k < kPiece - 1; ++k) append_chunk(cw[k], my_strip, seg_len, pos, carry);
+    } else {
+#pragma unroll
+      for (int k = 0; k < kPiece; ++k)
+        if ((uint32_t)k < n) append_chunk(cw[k], my_strip, seg_len, pos, carry);
+    }
     if (ends) {
       flush_carry(my_strip, pos, carry);
       on_unit(band, quad);
