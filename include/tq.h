@@ -64,6 +64,10 @@ typedef struct tq_info {
   uint64_t n_real_codes;       /* codes of the LZW parse itself (n_codes minus padding) */
   uint64_t dict_bytes, offset_bytes, code_bytes, scale_bytes;
   uint64_t compressed_bytes; /* sum of the four sections = bytes the kernels must read from HBM */
+  uint32_t lane_spread;      /* the 64 segments of a unit are decoded in step, 4 codes of each at a time: the largest
+                                difference, in columns, between two of them that are both still incomplete.  The batched
+                                product keeps only a window of every segment in LDS when this stays small (see tq_matvec). */
+  uint32_t reserved;
 } tq_info;
 
 /*

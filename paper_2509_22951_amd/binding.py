@@ -39,7 +39,7 @@ class TqInfo(ctypes.Structure):
                 ("n_units", ctypes.c_uint64), ("n_codes", ctypes.c_uint64), ("n_real_codes", ctypes.c_uint64),
                 ("dict_bytes", ctypes.c_uint64),
                 ("offset_bytes", ctypes.c_uint64), ("code_bytes", ctypes.c_uint64), ("scale_bytes", ctypes.c_uint64),
-                ("compressed_bytes", ctypes.c_uint64)]
+                ("compressed_bytes", ctypes.c_uint64), ("lane_spread", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}

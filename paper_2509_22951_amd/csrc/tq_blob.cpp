@@ -74,17 +74,20 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* fa
 
   // Codes: in range, pads only at the end of a lane stream, every lane stream's runs sum to its segment's length.
   std::atomic<uint64_t> first_bad(UINT64_MAX), real_codes(0);
-  std::atomic<uint32_t> overrun(0);
+  std::atomic<uint32_t> overrun(0), spread(0);
   n_threads = std::max(1u, std::min(n_threads, 16u));
   n_threads = (unsigned)std::min<uint64_t>(n_threads, n_units);
   auto work = [&](uint64_t ub, uint64_t ue) {
     uint64_t real = 0;
-    uint32_t over = 0;
+    uint32_t over = 0, wide = 0;
+    std::vector<uint32_t> reach_lo, reach_hi;   // per chunk count: least / greatest column reached by an unfinished lane
     for (uint64_t u = ub; u < ue && first_bad.load(std::memory_order_relaxed) == UINT64_MAX; ++u) {
       const uint32_t band = (uint32_t)(u / h.n_quads), quad = (uint32_t)(u % h.n_quads);
       const uint32_t steps = (uoff[u + 1] - uoff[u]) * kChunkCodes;
       const uint16_t* cb = codes + (uint64_t)uoff[u] * kChunkWords;
       bool ok = true;
+      reach_lo.assign(steps / kChunkCodes, UINT32_MAX);
+      reach_hi.assign(steps / kChunkCodes, 0);
       for (uint32_t l = 0; l < 64 && ok; ++l) {
         const uint32_t want = segment_len(h, band, quad, l);
         uint32_t sum = 0, pads = 0;
@@ -94,11 +97,17 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* fa
           if (c == h.n_entries) { ++pads; continue; }
           if (pads) { ok = false; break; }   // a real code after a pad
           sum += slot[c] >> 27;   // bits / 8
+          if (k % kChunkCodes == kChunkCodes - 1 && sum < want) {   // a whole chunk taken, segment not complete
+            reach_lo[k / kChunkCodes] = std::min(reach_lo[k / kChunkCodes], sum);
+            reach_hi[k / kChunkCodes] = std::max(reach_hi[k / kChunkCodes], sum);
+          }
         }
         if (sum != want) ok = false;
         real += steps - pads;
         over = std::max(over, want + 2 * pads);
       }
+      for (size_t k = 0; ok && k < reach_lo.size(); ++k)
+        if (reach_hi[k] > reach_lo[k] && reach_lo[k] != UINT32_MAX) wide = std::max(wide, reach_hi[k] - reach_lo[k]);
       if (!ok) {
         uint64_t cur = first_bad.load();
         while (u < cur && !first_bad.compare_exchange_weak(cur, u)) {}
@@ -107,6 +116,8 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* fa
     real_codes += real;
     uint32_t cur = overrun.load();
     while (over > cur && !overrun.compare_exchange_weak(cur, over)) {}
+    cur = spread.load();
+    while (wide > cur && !spread.compare_exchange_weak(cur, wide)) {}
   };
   if (n_threads <= 1) {
     work(0, n_units);
@@ -122,11 +133,14 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* fa
   if (first_bad.load() != UINT64_MAX) return bad("code stream of unit " + std::to_string(first_bad.load()));
   if (real_codes.load() != h.n_real_codes) return bad("count of non-padding codes");
   if (hdr_out) *hdr_out = h;
-  if (facts_out) facts_out->max_lane_reach = overrun.load();
+  if (facts_out) {
+    facts_out->max_lane_reach = overrun.load();
+    facts_out->max_lane_spread = spread.load();
+  }
   return TQ_OK;
 }
 
-void fill_info(const Header& h, tq_info* o) {
+void fill_info(const Header& h, const BlobFacts& facts, tq_info* o) {
   std::memset(o, 0, sizeof *o);
   o->rows = h.rows;
   o->cols = h.cols;
@@ -142,6 +156,7 @@ void fill_info(const Header& h, tq_info* o) {
   o->code_bytes = h.code_bytes;
   o->scale_bytes = h.scale_bytes;
   o->compressed_bytes = h.dict_bytes + h.uoff_bytes + h.code_bytes + h.scale_bytes;
+  o->lane_spread = facts.max_lane_spread;
 }
 
 }  // namespace tq
@@ -150,8 +165,9 @@ extern "C" const char* tq_last_error_string(void) { return tq::g_err.c_str(); }
 
 extern "C" int tq_validate_blob(const void* blob, size_t blob_bytes, tq_info* info) {
   tq::Header h;
+  tq::BlobFacts facts;
   unsigned hw = std::thread::hardware_concurrency();
-  int rc = tq::validate_blob(blob, blob_bytes, &h, nullptr, hw ? hw : 1);
-  if (rc == TQ_OK && info) tq::fill_info(h, info);
+  int rc = tq::validate_blob(blob, blob_bytes, &h, &facts, hw ? hw : 1);
+  if (rc == TQ_OK && info) tq::fill_info(h, facts, info);
   return rc;
 }

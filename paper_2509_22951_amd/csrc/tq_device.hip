@@ -686,8 +686,174 @@ __device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, glo
   return (part[0] + part[1]) + (part[2] + part[3]);
 }
 
-template <bool kXFast>
-__global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
+// ---------------------------------------------------------------------------------------------------------------
+// The same product with a ring of kRingBytes per lane in place of the whole strip.  The 16 rows of a band take their
+// codes in step but reach different columns, so some per-lane storage has to bring them back into line before an MFMA
+// can take 8 columns of all of them; what it has to hold is only the distance between the slowest and the fastest lane,
+// not the segment.  Every kRingStep chunks the wavefront asks whether every unfinished lane has passed the next
+// kRingGroup windows (one compare and a look at the condition mask) and, if so, multiplies them; a lane advances by at
+// most 8 columns per chunk, so one group per look keeps up.  Bytes of the ring are reused kRingBytes columns later: a
+// lane writes 8-byte piece q only when q + 8 - kRingBytes <= done, which holds whenever no two unfinished lanes are
+// ever more than kRingSpread columns apart; the host checks that for every unit when the container is loaded and sends
+// a matrix that does not keep it to the whole-strip kernel.  With 8 KB per wavefront instead of 17 KB (segments of
+// 256 columns) 12 wavefronts share a CU, 3 per SIMD, instead of 6.
+// Piece p (8 bytes) of lane l lives at p ^ (l & 15) within the lane's ring: when the 64 lanes read the same window, the
+// 16 lanes served together hit different banks.
+// Needs rows of a whole number of units (a multiple of 4 * seg_cols columns) and 16-byte aligned activations.
+constexpr int kRingBytes = 128;
+constexpr int kRingWaves = 12;
+constexpr int kRingThreads = kRingWaves * 64;
+constexpr int kRingPiece = 12;    // chunks per piece of the code stream (two register sets)
+constexpr int kRingStep = 4;      // chunks between two looks at the lanes' progress
+constexpr int kRingGroup = 4;     // MFMA steps per group
+constexpr uint32_t kRingSpread = kRingBytes - 8 * kRingStep - 8 * kRingGroup + 1;
+static_assert(kRingPiece % kRingStep == 0 && kRingGroup == 4 && kRingStep <= kRingGroup, "ring schedule");
+
+// append_chunk for the ring: the complete 8-byte piece goes to its swizzled place; sw8 = 8 * (lane & 15).
+__device__ __forceinline__ void append_chunk_ring(uint2 c, uint32_t ring, uint32_t sw8, uint32_t seg_len, uint32_t& pos, uint64_t& carry) {
+  const uint32_t e0 = lds_read16(half_offset_lo(c.x)), e1 = lds_read16(half_offset_hi(c.x));
+  const uint32_t e2 = lds_read16(half_offset_lo(c.y)), e3 = lds_read16(half_offset_hi(c.y));
+  const uint32_t p0 = is_pair_lo(c.x), p1 = is_pair_hi(c.x), p2 = is_pair_lo(c.y), p3 = is_pair_hi(c.y);
+  const uint32_t a01 = e1 << ((p0 << 3) + 8) | e0, n01 = p0 + p1 + 2;
+  const uint32_t a23 = e3 << ((p2 << 3) + 8) | e2, n23 = p2 + p3 + 2;
+  const uint32_t t = (n01 << 3) - 8;
+  const uint32_t s0 = (a23 << t) << 8 | a01, s1 = a23 >> (24 - t);
+  const uint64_t str = (uint64_t)s1 << 32 | s0;
+  const uint32_t n = min(n01 + n23, seg_len - pos);
+  const uint32_t f = pos & 7u, sh = f << 3;
+  const uint64_t lo = carry | str << sh, hi = (str >> 1) >> (63 - sh);
+  const bool full = f + n >= 8;
+  if (full) *(lds_u64*)(size_t)(ring | ((pos ^ sw8) & 0x78u)) = lo;
+  carry = full ? hi : lo;
+  pos += n;
+}
+
+// Decode the units [u0, u1) and multiply them as they come.  part[4] are the running sums of the band in work (MFMA
+// step k of a group adds to part[k]); on_unit(band, quad) is called after the last MFMA of every unit.
+template <typename OnUnit>
+__device__ __forceinline__ void decode_run_ring(const DevMat& m, uint32_t u0, uint32_t u1, int lane, uint32_t ring, global_cu16* xrow,
+                                                f32x4 (&part)[4], OnUnit&& on_unit) {
+  if (u0 >= u1) return;
+  constexpr int kP = kRingPiece, kG = kRingGroup;
+  const uint32_t nq = m.n_quads;
+  const uint32_t sw8 = (uint32_t)(lane & 15) << 3, kg = (uint32_t)lane >> 4;
+  uint32_t wu = u0, wc = unit_offset(m, u0), w_left = 0, w_base = 0, w_rem = 0;
+  auto next_piece = [&](uint32_t& start, uint32_t& n, bool& ends) {
+    if (w_left == 0) {
+      if (wu == u1) {
+        n = 0;
+        ends = false;
+        start = wc;
+        return;
+      }
+      const uint32_t len = unit_offset(m, wu + 1) - wc;
+      w_left = (len + kP - 1) / kP;
+      w_base = len / w_left;
+      w_rem = len - w_base * w_left;
+      ++wu;
+    }
+    n = w_base + (w_rem ? 1u : 0u);
+    if (w_rem) --w_rem;
+    start = wc;
+    wc += n;
+    ends = --w_left == 0;
+  };
+  const uint32_t run_last = unit_offset(m, u1) - 1;
+  auto load_piece = [&](uint2 (&cw)[kP], uint32_t start, uint32_t n) {
+    const uint32_t last = min(start + max(n, 1u) - 1, run_last);
+#pragma unroll
+    for (int k = 0; k < kP; ++k) cw[k] = global_load(m.codes + (size_t)min(start + k, last) * 64 + lane);
+  };
+  // the unit in work
+  uint32_t band = u0 / nq, quad = u0 - band * nq;
+  uint32_t pos = 0, seg_len = 0, done = 0, xcol = 0;
+  const uint32_t n_win8 = m.seg_cols;   // every unit has 4 whole panels
+  uint64_t carry = 0;
+  uint4 xb[kG];   // activation fragments of the next group of MFMA steps: 4 consecutive 16-byte pieces of the row
+  auto request = [&](uint32_t w8) {   // a group that starts past the unit's end is only requested, never used: it is moved back into the row
+    const global_cu128* p = (const global_cu128*)(xrow + min(xcol + w8, m.cols - 8 * kG));
+#pragma unroll
+    for (int k = 0; k < kG; ++k) {
+      const u32x4 v = p[k];
+      xb[k] = make_uint4(v.x, v.y, v.z, v.w);
+    }
+  };
+  auto start_unit = [&]() {
+    const uint32_t row = band * kUnitRows + (lane & 15);
+    seg_len = row < m.rows ? m.seg_cols : 0u;
+    xcol = (quad * kUnitPanels + kg) * m.seg_cols;
+    pos = 0;
+    carry = 0;
+    done = 0;
+    request(0);
+  };
+  auto mfma_step = [&](u32x2 a8, uint4 x8, int acc) {
+    part[acc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8.x, a8.y)), __builtin_bit_cast(bf16x8, x8), part[acc], 0, 0, 0);
+  };
+  // One group of MFMA steps if every lane that is still decoding has written the columns [done, done + 8 kG).
+  auto multiply_ready = [&]() {
+    const uint32_t next = done + 8 * kG;
+    if (next > n_win8) return;
+    if (__builtin_amdgcn_ballot_w64(pos < min(seg_len, next)) != 0) return;
+    const uint32_t base = done ^ sw8;
+    u32x2 a8[kG];
+#pragma unroll
+    for (int k = 0; k < kG; ++k) a8[k] = *(lds_cu64*)(size_t)(ring | ((base ^ (8u * k)) & 0x78u));
+#pragma unroll
+    for (int k = 0; k < kG; ++k) mfma_step(a8[k], xb[k], k);
+    done = next;
+    request(done);
+  };
+  auto decode_piece = [&](const uint2 (&cw)[kP], uint32_t n, bool ends) {
+    if (n == 0) return;
+    if (n >= kP - 1) {
+#pragma unroll
+      for (int k = 0; k < kP - 1; ++k) {
+        append_chunk_ring(cw[k], ring, sw8, seg_len, pos, carry);
+        if (k % kRingStep == kRingStep - 1) multiply_ready();
+      }
+      if (n == kP) append_chunk_ring(cw[kP - 1], ring, sw8, seg_len, pos, carry);
+    } else {
+#pragma unroll
+      for (int k = 0; k < kP - 2; ++k) {
+        if ((uint32_t)k < n) append_chunk_ring(cw[k], ring, sw8, seg_len, pos, carry);
+        if (k % kRingStep == kRingStep - 1 && (uint32_t)k + 1 < n) multiply_ready();
+      }
+    }
+    multiply_ready();
+    if (ends) {
+      // every lane is complete; at most one whole group was left, and fewer than kG windows when the segment width
+      // is not a multiple of 32 columns
+      for (; done < n_win8; done += 8) {
+        const u32x2 a8 = *(lds_cu64*)(size_t)(ring | ((done ^ sw8) & 0x78u));
+        mfma_step(a8, load_x_fragment<true>(xrow, m.cols, xcol + done), 0);
+      }
+      on_unit(band, quad);
+      if (++quad == nq) {
+        quad = 0;
+        ++band;
+      }
+      start_unit();
+    }
+  };
+  start_unit();
+  uint2 cwa[kP], cwb[kP];
+  uint32_t sa, na, sb, nb;
+  bool ea, eb;
+  next_piece(sa, na, ea);
+  load_piece(cwa, sa, na);
+  while (na) {
+    next_piece(sb, nb, eb);
+    load_piece(cwb, sb, nb);
+    decode_piece(cwa, na, ea);
+    next_piece(sa, na, ea);
+    load_piece(cwa, sa, na);
+    decode_piece(cwb, nb, eb);
+  }
+}
+
+template <bool kXFast, bool kRing>
+__global__ __launch_bounds__(kRing ? kRingThreads : kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
   extern __shared__ uint4 lds4[];
   uint16_t* lds_dict = (uint16_t*)lds4;
   uint8_t* tiles = (uint8_t*)lds4 + a.x_off;
@@ -730,28 +896,14 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
       staged = m.dict;
     }
     __syncthreads();
-    const uint32_t strip = m.seg_cols + 8;   // bytes between the strips of two lanes
-    const uint32_t my_strip = lds_address(tiles) + (uint32_t)wave * a.tile_area + (uint32_t)lane * strip;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f}, head_acc = {0.f, 0.f, 0.f, 0.f}, tail_acc = {0.f, 0.f, 0.f, 0.f};
     int head_band = -1, tail_band = -1;
     // lanes past the batch repeat its last row: their output columns are never stored
     global_cu16* xrow = (global_cu16*)job.x + (size_t)min(bn, a.batch - 1) * m.cols;
     const uint32_t first_band = u0 / nq;
     const bool first_whole = u0 % nq == 0;
-    uint4 xa[kMfmaGroup];   // activation fragments of the first MFMA group of the unit being decoded
-    decode_run_to_tile(m, u0, u1, lane, my_strip, [&](uint32_t, uint32_t quad) {
-#pragma unroll
-      for (int k = 0; k < kMfmaGroup; ++k)
-        xa[k] = load_x_fragment<kXFast>(xrow, m.cols, (quad * kUnitPanels + (uint32_t)kg) * m.seg_cols + 8 * k);
-    }, [&](uint32_t band, uint32_t quad) {
-      const uint32_t col0 = quad * kUnitPanels * m.seg_cols;                            // first column of the unit
-      const uint32_t width = min(m.seg_cols, m.cols - col0);                            // its widest segment is the first panel's
-      const uint32_t n_win = (width + 7) / 8;
-      const uint32_t xcol = col0 + (uint32_t)kg * m.seg_cols;
-      if (!kXFast || col0 + kUnitPanels * m.seg_cols > m.cols)   // some fragment reaches past the row's end
-        acc = multiply_unit<kXFast, true>(acc, my_strip, xrow, m.cols, xcol, n_win, xa);
-      else
-        acc = multiply_unit<kXFast, false>(acc, my_strip, xrow, m.cols, xcol, n_win, xa);
+    // acc holds the sums of the band in work when its last unit (or the run's) has been multiplied
+    auto finish_unit = [&](uint32_t band, uint32_t quad) {
       const bool band_ends = quad + 1 == nq, run_ends = band * nq + quad + 1 == u1;
       if (band_ends || run_ends) {
         if (band_ends && (band != first_band || first_whole)) {
@@ -770,7 +922,38 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
         }
         acc = f32x4{0.f, 0.f, 0.f, 0.f};
       }
-    });
+    };
+    if constexpr (kRing) {
+      const uint32_t ring = lds_address(tiles) + (uint32_t)wave * a.tile_area + (uint32_t)lane * kRingBytes;
+      f32x4 part[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+      decode_run_ring(m, u0, u1, lane, ring, xrow, part, [&](uint32_t band, uint32_t quad) {
+        if (quad + 1 == nq || band * nq + quad + 1 == u1) {
+          acc = (part[0] + part[1]) + (part[2] + part[3]);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) part[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        finish_unit(band, quad);
+      });
+    } else {
+      const uint32_t strip = m.seg_cols + 8;   // bytes between the strips of two lanes
+      const uint32_t my_strip = lds_address(tiles) + (uint32_t)wave * a.tile_area + (uint32_t)lane * strip;
+      uint4 xa[kMfmaGroup];   // activation fragments of the first MFMA group of the unit being decoded
+      decode_run_to_tile(m, u0, u1, lane, my_strip, [&](uint32_t, uint32_t quad) {
+#pragma unroll
+        for (int k = 0; k < kMfmaGroup; ++k)
+          xa[k] = load_x_fragment<kXFast>(xrow, m.cols, (quad * kUnitPanels + (uint32_t)kg) * m.seg_cols + 8 * k);
+      }, [&](uint32_t band, uint32_t quad) {
+        const uint32_t col0 = quad * kUnitPanels * m.seg_cols;                            // first column of the unit
+        const uint32_t width = min(m.seg_cols, m.cols - col0);                            // its widest segment is the first panel's
+        const uint32_t n_win = (width + 7) / 8;
+        const uint32_t xcol = col0 + (uint32_t)kg * m.seg_cols;
+        if (!kXFast || col0 + kUnitPanels * m.seg_cols > m.cols)   // some fragment reaches past the row's end
+          acc = multiply_unit<kXFast, true>(acc, my_strip, xrow, m.cols, xcol, n_win, xa);
+        else
+          acc = multiply_unit<kXFast, false>(acc, my_strip, xrow, m.cols, xcol, n_win, xa);
+        finish_unit(band, quad);
+      });
+    }
     __syncthreads();   // every wavefront is done with its tile: the partial sums go over the tile area
     float* slot_val = (float*)tiles;                                 // [2 * n_waves][256]
     int* slot_band = (int*)(slot_val + 2 * n_waves * 256);           // [2 * n_waves], also inside the tile area
@@ -966,6 +1149,7 @@ bool plan_matvec_lds(uint32_t dict_words_max, uint32_t x_dwords_max, uint32_t* x
 
 struct tq_matrix {
   Header h;
+  BlobFacts facts;
   DevMat m;
   const DevMat* m_dev;   // the same description in device memory, for launches that serve many matrices
   DictCopy* dict;
@@ -1030,8 +1214,9 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   // Dynamic LDS above 64 KB has to be allowed per kernel function.
   e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_decompress, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
 
   const uint8_t* src = (const uint8_t*)blob;
@@ -1068,6 +1253,7 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
     return TQ_E_OOM;
   }
   t->h = h;
+  t->facts = facts;
   t->m = m;
   t->m_dev = (const DevMat*)(base + o_desc);
   t->dict = dict;
@@ -1084,7 +1270,8 @@ enum class Op { kMatvec, kDecompress };
 
 // One kernel launch for hs[0..n), n <= kMaxMulti, all on one device, total cost below 2^32.
 // kMatvec: xs/ys are the activations and outputs; kDecompress: ys are the int8 output matrices, xs is not used.
-int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream) {
+// ring: the batched product with a ring per lane (every matrix of the call has passed ring_eligible).
+int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream, bool ring = false) {
   MatvecArgs a;
   a.n = n;
   a.batch = batch;
@@ -1122,6 +1309,19 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
       return TQ_E_UNSUPPORTED;
     }
     hipLaunchKernelGGL((k_matvec<kDotPiece, kDotWaves>), dim3((unsigned)grid), dim3(kDotWaves * 64), lds_total, stream, a);
+  } else if (ring) {
+    // LDS: 16-bit dictionary image | one ring per lane (aligned to its size: the kernel ORs piece offsets into its
+    // address), reused for the partial sums like the tiles below.
+    const size_t dict16 = round_up((uint64_t)dict_words_max * 2, kRingBytes);
+    a.x_off = (uint32_t)dict16;
+    a.tile_area = 64 * kRingBytes;
+    a.slot_off = 0;
+    const size_t lds = dict16 + (size_t)kRingWaves * a.tile_area;
+    if (lds > kLdsLimit || !x_fast) {
+      set_error("internal: ring launch with a dictionary or activations that do not fit it");
+      return TQ_E_UNSUPPORTED;
+    }
+    hipLaunchKernelGGL((k_matvec_mfma<true, true>), dim3((unsigned)grid), dim3(kRingThreads), lds, stream, a);
   } else {
     // Tile decode.  LDS: 16-bit dictionary image | one tile (64 strips) per wavefront, which the batched product reuses
     // for its partial sums (per wavefront two slots of 1 KB and their two band numbers).
@@ -1138,16 +1338,56 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     const size_t lds = dict16 + waves * area;
     const dim3 block((unsigned)waves * 64);
     if (op == Op::kDecompress) hipLaunchKernelGGL(k_decompress, dim3((unsigned)grid), block, lds, stream, a);
-    else if (x_fast) hipLaunchKernelGGL((k_matvec_mfma<true>), dim3((unsigned)grid), block, lds, stream, a);
-    else hipLaunchKernelGGL((k_matvec_mfma<false>), dim3((unsigned)grid), block, lds, stream, a);
+    else if (x_fast) hipLaunchKernelGGL((k_matvec_mfma<true, false>), dim3((unsigned)grid), block, lds, stream, a);
+    else hipLaunchKernelGGL((k_matvec_mfma<false, false>), dim3((unsigned)grid), block, lds, stream, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(op == Op::kDecompress ? "tq_decompress launch" : "tq_matvec launch", e);
   return TQ_OK;
 }
 
+// Whether the batched product of this matrix can keep a ring per lane instead of the whole strip.
+bool ring_eligible(const tq_matrix* t, const void* x) {
+  return t->facts.max_lane_spread <= kRingSpread && t->m.cols % (kUnitPanels * t->m.seg_cols) == 0 && t->m.seg_cols >= 8 * kRingGroup &&
+         (uintptr_t)x % 16 == 0 &&
+         round_up((uint64_t)t->m.dict_words * 2, kRingBytes) + (size_t)kRingWaves * 64 * kRingBytes <= kLdsLimit;
+}
+
 // As few launches as the kernel-argument size and the 32-bit cost line allow.
-int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream) {
+int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream, bool ring = false) {
+  if (op == Op::kMatvec && batch > 1 && !ring) {
+    // The matrices that can take the ring kernel go there, the others to the whole-strip kernel; the products are
+    // independent, so regrouping them changes nothing but the launches.
+    int n_ring = 0;
+    for (int i = 0; i < n; ++i) n_ring += ring_eligible(hs[i], xs[i]);
+    if (n_ring == n) return launch_all(op, n, hs, xs, ys, batch, stream, true);
+    if (n_ring > 0) {
+      std::vector<tq_handle> h2[2];
+      std::vector<const void*> x2[2];
+      std::vector<void*> y2[2];
+      for (int i = 0; i < n; ++i) {
+        const int g = ring_eligible(hs[i], xs[i]) ? 1 : 0;
+        h2[g].push_back(hs[i]);
+        x2[g].push_back(xs[i]);
+        y2[g].push_back(ys[i]);
+      }
+      if (int rc = launch_all(op, (int)h2[1].size(), h2[1].data(), x2[1].data(), y2[1].data(), batch, stream, true)) return rc;
+      n = (int)h2[0].size();
+      for (int i = 0; i < n;) {   // the rest, below, with the vectors alive
+        int k = 0;
+        uint64_t cost = 0;
+        while (i + k < n && k < kMaxMulti) {
+          const uint64_t c = (uint64_t)h2[0][i + k]->m.n_bands * h2[0][i + k]->m.cols;
+          if (k > 0 && cost + c > 0xFFFFFFFFull) break;
+          cost += c;
+          ++k;
+        }
+        if (int rc = launch(op, k, h2[0].data() + i, x2[0].data() + i, y2[0].data() + i, batch, stream, false)) return rc;
+        i += k;
+      }
+      return TQ_OK;
+    }
+  }
   for (int i = 0; i < n;) {
     int k = 0;
     uint64_t cost = 0;
@@ -1157,7 +1397,7 @@ int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* c
       cost += c;
       ++k;
     }
-    if (int rc = launch(op, k, hs + i, xs ? xs + i : nullptr, ys + i, batch, stream)) return rc;
+    if (int rc = launch(op, k, hs + i, xs ? xs + i : nullptr, ys + i, batch, stream, ring)) return rc;
     i += k;
   }
   return TQ_OK;
@@ -1193,7 +1433,7 @@ extern "C" int tq_matvec(tq_handle h, const void* x, void* y, int batch, void* s
     return TQ_E_INVALID_ARG;
   }
   if (int rc = check_call("tq_matvec", 1, &h, &x, &y, batch)) return rc;
-  return launch(Op::kMatvec, 1, &h, &x, &y, batch, (hipStream_t)stream);
+  return launch(Op::kMatvec, 1, &h, &x, &y, batch, (hipStream_t)stream, batch > 1 && ring_eligible(h, x));
 }
 
 extern "C" int tq_matvec_multi(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {
@@ -1236,7 +1476,7 @@ extern "C" int tq_get_info(tq_handle h, tq_info* out) {
     set_error("tq_get_info: null argument");
     return TQ_E_INVALID_ARG;
   }
-  fill_info(h->h, out);
+  fill_info(h->h, h->facts, out);
   return TQ_OK;
 }
 

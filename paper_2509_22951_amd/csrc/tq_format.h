@@ -71,10 +71,13 @@ void set_error(const std::string& msg);   // thread-local last-error text
 struct BlobFacts {
   uint32_t max_lane_reach;   // largest (segment length + 2 * pad codes) of any lane stream: how many columns past the start
                              // of its segment a lane's activation index can get when every pad code advances it by two
+  uint32_t max_lane_spread;  // the 64 lanes of a unit take their chunks in step; after any number of chunks, the lanes whose
+                             // segment is not yet complete have reached different columns of it: the largest difference
+                             // between two of them, over all units and all chunk counts
 };
 
 // Host-side structural validation; fills *hdr_out with a copy of the header on success.
 int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* facts_out, unsigned n_threads);
-void fill_info(const Header& h, ::tq_info* out);
+void fill_info(const Header& h, const BlobFacts& facts, ::tq_info* out);
 
 }  // namespace tq
