@@ -687,70 +687,98 @@ __device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, glo
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// The same product with a ring of kRingBytes per lane in place of the whole strip.  The 16 rows of a band take their
-// codes in step but reach different columns, so some per-lane storage has to bring them back into line before an MFMA
-// can take 8 columns of all of them; what it has to hold is only the distance between the slowest and the fastest lane,
-// not the segment.  Every kRingStep chunks the wavefront asks whether every unfinished lane has passed the next
-// kRingGroup windows (one compare and a look at the condition mask) and, if so, multiplies them; a lane advances by at
-// most 8 columns per chunk, so one group per look keeps up.  Bytes of the ring are reused kRingBytes columns later: a
-// lane writes 8-byte piece q only when q + 8 - kRingBytes <= done, which holds whenever no two unfinished lanes are
-// ever more than kRingSpread columns apart; the host checks that for every unit when the container is loaded and sends
-// a matrix that does not keep it to the whole-strip kernel.  With 8 KB per wavefront instead of 17 KB (segments of
-// 256 columns) 12 wavefronts share a CU, 3 per SIMD, instead of 6.
+// The batched product with a ring of kRingBytes per lane in place of the whole strip, and the activations in LDS.
+//
+// The 16 rows of a band take their codes in step but reach different columns, so some per-lane storage has to bring
+// them back into line before an MFMA can take 8 columns of all of them; what it has to hold is only the distance
+// between the slowest and the fastest lane, not the segment.  Every kRingStep chunks the wavefront asks whether every
+// unfinished lane has passed the next kRingGroup windows (one compare and a look at the condition mask) and, if so,
+// multiplies them; a lane advances by at most 8 columns per chunk, so one group per look keeps up.  Bytes of the ring
+// are reused kRingBytes columns later: a lane writes 8-byte piece q only when q + 8 - kRingBytes <= done, which holds
+// whenever no two unfinished lanes are ever more than kRingSpread columns apart; the host checks that for every unit
+// when the container is loaded and sends a matrix that does not keep it to the whole-strip kernel.
 // Piece p (8 bytes) of lane l lives at p ^ (l & 15) within the lane's ring: when the 64 lanes read the same window, the
 // 16 lanes served together hit different banks.
-// Needs rows of a whole number of units (a multiple of 4 * seg_cols columns) and 16-byte aligned activations.
+//
+// With 8 KB of ring per wavefront, 8 wavefronts leave room for the activations of one quad (4 panels) in LDS, laid out
+// as the B operands the MFMA steps take: [panel][window][batch row 0..15][8 columns], 16 bytes per lane and step, read
+// with one ds_read_b128.  (Taken from global memory, every step's fragment load touches 4 panels x batch rows
+// different cache lines; that, not the decode, then bounds the kernel.)  All wavefronts of a workgroup therefore work
+// on the same quad at a time: the workgroup walks the quads of its bands in the outer loop, wavefront w takes the
+// bands w, w + 8, ... whole, and a band's sums go to y once per quad: a plain store for the first quad, an atomic add
+// (no return value, so nothing waits for it) for the others.  One wavefront issues all of them for a given y element,
+// in quad order, so the result does not depend on timing.
+// Needs rows of a whole number of units (a multiple of 4 * seg_cols columns), segments of 32..256 columns in
+// multiples of 32, and 16-byte aligned activations.
 constexpr int kRingBytes = 128;
-constexpr int kRingWaves = 12;
+constexpr int kRingWaves = 8;
 constexpr int kRingThreads = kRingWaves * 64;
 constexpr int kRingPiece = 12;    // chunks per piece of the code stream (two register sets)
 constexpr int kRingStep = 4;      // chunks between two looks at the lanes' progress
 constexpr int kRingGroup = 4;     // MFMA steps per group
 constexpr uint32_t kRingSpread = kRingBytes - 8 * kRingStep - 8 * kRingGroup + 1;
+constexpr uint32_t kRingMaxSeg = 256;
+constexpr uint32_t kRingXTile = kUnitPanels * kRingMaxSeg * 16 * 2;   // bytes: 4 panels x 256 columns x 16 batch rows of bf16
 static_assert(kRingPiece % kRingStep == 0 && kRingGroup == 4 && kRingStep <= kRingGroup, "ring schedule");
 
+// Chunk `chunk` of the code stream, lane's 4 codes: a wave-uniform base in scalar registers plus the lane's offset, so
+// that no vector arithmetic goes into the address.
+__device__ __forceinline__ uint2 load_chunk(const uint2* codes, uint32_t chunk, int lane) {
+  const uint64_t base = (uint64_t)codes + (uint64_t)chunk * (64 * sizeof(uint2));
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)base), hi = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32));
+  const u32x2 v = ((__attribute__((address_space(1))) const u32x2*)((uint64_t)hi << 32 | lo))[(uint32_t)lane];
+  return make_uint2(v.x, v.y);
+}
+
 // append_chunk for the ring: the complete 8-byte piece goes to its swizzled place; sw8 = 8 * (lane & 15).
+// pos never passes seg_len (pad codes fall off the end), and a piece is complete when pos crosses a multiple of 8.
 __device__ __forceinline__ void append_chunk_ring(uint2 c, uint32_t ring, uint32_t sw8, uint32_t seg_len, uint32_t& pos, uint64_t& carry) {
   const uint32_t e0 = lds_read16(half_offset_lo(c.x)), e1 = lds_read16(half_offset_hi(c.x));
   const uint32_t e2 = lds_read16(half_offset_lo(c.y)), e3 = lds_read16(half_offset_hi(c.y));
   const uint32_t p0 = is_pair_lo(c.x), p1 = is_pair_hi(c.x), p2 = is_pair_lo(c.y), p3 = is_pair_hi(c.y);
-  const uint32_t a01 = e1 << ((p0 << 3) + 8) | e0, n01 = p0 + p1 + 2;
-  const uint32_t a23 = e3 << ((p2 << 3) + 8) | e2, n23 = p2 + p3 + 2;
-  const uint32_t t = (n01 << 3) - 8;
-  const uint32_t s0 = (a23 << t) << 8 | a01, s1 = a23 >> (24 - t);
-  const uint64_t str = (uint64_t)s1 << 32 | s0;
-  const uint32_t n = min(n01 + n23, seg_len - pos);
-  const uint32_t f = pos & 7u, sh = f << 3;
-  const uint64_t lo = carry | str << sh, hi = (str >> 1) >> (63 - sh);
-  const bool full = f + n >= 8;
+  const uint32_t a01 = e1 << ((p0 << 3) + 8) | e0, n01 = p0 + p1 + 2;   // codes 0, 1: n01 = 2..4 bytes
+  const uint32_t a23 = e3 << ((p2 << 3) + 8) | e2, n23 = p2 + p3 + 2;   // codes 2, 3
+  const uint64_t str = (uint64_t)a23 << (n01 << 3) | a01;               // the 4..8 bytes of the chunk
+  const uint32_t after = min(pos + n01 + n23, seg_len);
+  const uint32_t sh = (pos & 7u) << 3;
+  const uint64_t lo = carry | str << sh, hi = (str >> 1) >> (63 - sh);  // the 16 bytes carry + string; hi is 0 when pos % 8 == 0
+  const bool full = (after ^ pos) >= 8;
   if (full) *(lds_u64*)(size_t)(ring | ((pos ^ sw8) & 0x78u)) = lo;
   carry = full ? hi : lo;
-  pos += n;
+  pos = after;
 }
 
-// Decode the units [u0, u1) and multiply them as they come.  part[4] are the running sums of the band in work (MFMA
-// step k of a group adds to part[k]); on_unit(band, quad) is called after the last MFMA of every unit.
+typedef __attribute__((address_space(3))) const u32x4 lds_cu128;
+
+// Decode and multiply the units first, first + stride, ... (n_units of them; every unit has 4 whole panels of seg_cols
+// columns).  ring: LDS address of the lane's ring; xfrag: LDS address of the lane's 16 bytes of window 0 in the
+// activation tile (window w is 256 w bytes further); row: the lane's row in the first unit, row_stride further in each
+// following one.  on_unit(k, sums) is called with the k-th unit's 16 x 16 sums after its last MFMA step.
 template <typename OnUnit>
-__device__ __forceinline__ void decode_run_ring(const DevMat& m, uint32_t u0, uint32_t u1, int lane, uint32_t ring, global_cu16* xrow,
-                                                f32x4 (&part)[4], OnUnit&& on_unit) {
-  if (u0 >= u1) return;
+__device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t first, uint32_t stride, uint32_t n_units, int lane, uint32_t ring,
+                                                  uint32_t xfrag, uint32_t row, uint32_t row_stride, OnUnit&& on_unit) {
+  if (n_units == 0) return;
+  uint32_t seg_len = row < m.rows ? m.seg_cols : 0u;   // a row past the end of the matrix has no segment: its lane decodes nothing
   constexpr int kP = kRingPiece, kG = kRingGroup;
-  const uint32_t nq = m.n_quads;
-  const uint32_t sw8 = (uint32_t)(lane & 15) << 3, kg = (uint32_t)lane >> 4;
-  uint32_t wu = u0, wc = unit_offset(m, u0), w_left = 0, w_base = 0, w_rem = 0;
+  const uint32_t sw8 = (uint32_t)(lane & 15) << 3;
+  const uint32_t n_win8 = m.seg_cols;
+  // walker over the pieces: unit index, pieces left in the unit, next chunk
+  uint32_t wk = 0, wc = 0, w_left = 0, w_base = 0, w_rem = 0;
   auto next_piece = [&](uint32_t& start, uint32_t& n, bool& ends) {
     if (w_left == 0) {
-      if (wu == u1) {
+      if (wk == n_units) {
         n = 0;
         ends = false;
         start = wc;
         return;
       }
-      const uint32_t len = unit_offset(m, wu + 1) - wc;
+      const uint32_t u = first + wk * stride;
+      wc = unit_offset(m, u);
+      const uint32_t len = unit_offset(m, u + 1) - wc;
       w_left = (len + kP - 1) / kP;
       w_base = len / w_left;
       w_rem = len - w_base * w_left;
-      ++wu;
+      ++wk;
     }
     n = w_base + (w_rem ? 1u : 0u);
     if (w_rem) --w_rem;
@@ -758,102 +786,169 @@ __device__ __forceinline__ void decode_run_ring(const DevMat& m, uint32_t u0, ui
     wc += n;
     ends = --w_left == 0;
   };
-  const uint32_t run_last = unit_offset(m, u1) - 1;
-  auto load_piece = [&](uint2 (&cw)[kP], uint32_t start, uint32_t n) {
-    const uint32_t last = min(start + max(n, 1u) - 1, run_last);
+  // Every piece issues exactly kP loads (those past its end repeat its last chunk), kRingStep of them at a time.
+  auto load_part = [&](uint2 (&cw)[kP], uint32_t start, uint32_t n, int part) {
+    const uint32_t last = n ? start + n - 1 : start - 1;   // n == 0 (past the last unit, start >= 1): the chunk before, never used
 #pragma unroll
-    for (int k = 0; k < kP; ++k) cw[k] = global_load(m.codes + (size_t)min(start + k, last) * 64 + lane);
+    for (int k = part * kRingStep; k < (part + 1) * kRingStep; ++k) cw[k] = load_chunk(m.codes, min(start + k, last), lane);
   };
-  // the unit in work
-  uint32_t band = u0 / nq, quad = u0 - band * nq;
-  uint32_t pos = 0, seg_len = 0, done = 0, xcol = 0;
-  const uint32_t n_win8 = m.seg_cols;   // every unit has 4 whole panels
+  uint32_t pos = 0, done = 0, unit_k = 0;
   uint64_t carry = 0;
-  uint4 xb[kG];   // activation fragments of the next group of MFMA steps: 4 consecutive 16-byte pieces of the row
-  auto request = [&](uint32_t w8) {   // a group that starts past the unit's end is only requested, never used: it is moved back into the row
-    const global_cu128* p = (const global_cu128*)(xrow + min(xcol + w8, m.cols - 8 * kG));
-#pragma unroll
-    for (int k = 0; k < kG; ++k) {
-      const u32x4 v = p[k];
-      xb[k] = make_uint4(v.x, v.y, v.z, v.w);
-    }
-  };
-  auto start_unit = [&]() {
-    const uint32_t row = band * kUnitRows + (lane & 15);
-    seg_len = row < m.rows ? m.seg_cols : 0u;
-    xcol = (quad * kUnitPanels + kg) * m.seg_cols;
-    pos = 0;
-    carry = 0;
-    done = 0;
-    request(0);
-  };
-  auto mfma_step = [&](u32x2 a8, uint4 x8, int acc) {
-    part[acc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8.x, a8.y)), __builtin_bit_cast(bf16x8, x8), part[acc], 0, 0, 0);
-  };
+  f32x4 part[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
   // One group of MFMA steps if every lane that is still decoding has written the columns [done, done + 8 kG).
   auto multiply_ready = [&]() {
     const uint32_t next = done + 8 * kG;
     if (next > n_win8) return;
     if (__builtin_amdgcn_ballot_w64(pos < min(seg_len, next)) != 0) return;
     const uint32_t base = done ^ sw8;
+    const uint32_t xa = xfrag + done * 32;   // 256 bytes per window
     u32x2 a8[kG];
+    u32x4 x8[kG];
 #pragma unroll
-    for (int k = 0; k < kG; ++k) a8[k] = *(lds_cu64*)(size_t)(ring | ((base ^ (8u * k)) & 0x78u));
+    for (int k = 0; k < kG; ++k) {
+      a8[k] = *(lds_cu64*)(size_t)(ring | ((base ^ (8u * k)) & 0x78u));
+      x8[k] = *(lds_cu128*)(size_t)(xa + 256 * k);
+    }
 #pragma unroll
-    for (int k = 0; k < kG; ++k) mfma_step(a8[k], xb[k], k);
+    for (int k = 0; k < kG; ++k)
+      part[k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8[k].x, a8[k].y)), __builtin_bit_cast(bf16x8, x8[k]), part[k], 0, 0, 0);
     done = next;
-    request(done);
   };
-  auto decode_piece = [&](const uint2 (&cw)[kP], uint32_t n, bool ends) {
+  auto decode_piece = [&](const uint2 (&cw)[kP], uint32_t n, bool ends, uint2 (&cw_next)[kP], uint32_t next_start, uint32_t next_n) {
     if (n == 0) return;
     if (n >= kP - 1) {
 #pragma unroll
       for (int k = 0; k < kP - 1; ++k) {
         append_chunk_ring(cw[k], ring, sw8, seg_len, pos, carry);
-        if (k % kRingStep == kRingStep - 1) multiply_ready();
+        if (k % kRingStep == kRingStep - 1) {
+          multiply_ready();
+          load_part(cw_next, next_start, next_n, k / kRingStep);
+        }
       }
       if (n == kP) append_chunk_ring(cw[kP - 1], ring, sw8, seg_len, pos, carry);
     } else {
 #pragma unroll
       for (int k = 0; k < kP - 2; ++k) {
         if ((uint32_t)k < n) append_chunk_ring(cw[k], ring, sw8, seg_len, pos, carry);
-        if (k % kRingStep == kRingStep - 1 && (uint32_t)k + 1 < n) multiply_ready();
+        if (k % kRingStep == kRingStep - 1) {
+          if ((uint32_t)k + 1 < n) multiply_ready();
+          load_part(cw_next, next_start, next_n, k / kRingStep);
+        }
       }
     }
     multiply_ready();
-    if (ends) {
-      // every lane is complete; at most one whole group was left, and fewer than kG windows when the segment width
-      // is not a multiple of 32 columns
-      for (; done < n_win8; done += 8) {
-        const u32x2 a8 = *(lds_cu64*)(size_t)(ring | ((done ^ sw8) & 0x78u));
-        mfma_step(a8, load_x_fragment<true>(xrow, m.cols, xcol + done), 0);
-      }
-      on_unit(band, quad);
-      if (++quad == nq) {
-        quad = 0;
-        ++band;
-      }
-      start_unit();
+    load_part(cw_next, next_start, next_n, kP / kRingStep - 1);
+    if (ends) {   // every lane is complete and at most one whole group was left: the unit has been multiplied
+      on_unit(unit_k, (part[0] + part[1]) + (part[2] + part[3]));
+#pragma unroll
+      for (int k = 0; k < 4; ++k) part[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+      ++unit_k;
+      row += row_stride;
+      seg_len = row < m.rows ? m.seg_cols : 0u;
+      pos = 0;
+      carry = 0;
+      done = 0;
     }
   };
-  start_unit();
   uint2 cwa[kP], cwb[kP];
   uint32_t sa, na, sb, nb;
   bool ea, eb;
   next_piece(sa, na, ea);
-  load_piece(cwa, sa, na);
-  while (na) {
+#pragma unroll
+  for (int j = 0; j < kP / kRingStep; ++j) load_part(cwa, sa, na, j);
+  while (na) {   // two register sets: one is decoded while the other is filled
     next_piece(sb, nb, eb);
-    load_piece(cwb, sb, nb);
-    decode_piece(cwa, na, ea);
+    decode_piece(cwa, na, ea, cwb, sb, nb);
     next_piece(sa, na, ea);
-    load_piece(cwa, sa, na);
-    decode_piece(cwb, nb, eb);
+    decode_piece(cwb, nb, eb, cwa, sa, na);
   }
 }
 
-template <bool kXFast, bool kRing>
-__global__ __launch_bounds__(kRing ? kRingThreads : kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
+__global__ __launch_bounds__(kRingThreads, 1) void k_matvec_ring(MatvecArgs a) {
+  extern __shared__ uint4 lds4[];
+  uint16_t* lds_dict = (uint16_t*)lds4;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if (lds_address(lds4) != 0) return;   // the code -> entry lookup takes the dictionary to start at LDS address 0
+  const uint32_t rings = a.x_off, xtile = a.slot_off;   // LDS addresses (the LDS segment starts at 0)
+  const uint64_t total = a.cost[a.n];
+  const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
+  const uint32_t* staged = nullptr;
+  const int bn = lane & 15, kg = lane >> 4;   // B operand: batch row and k-group (panel) of this lane
+  const uint32_t ring = rings + (uint32_t)wave * (64 * kRingBytes) + (uint32_t)lane * kRingBytes;
+  for (int i = 0; i < a.n; ++i) {
+    const uint32_t cb = a.cost[i], ce = a.cost[i + 1];
+    if (hi <= cb || lo >= ce) continue;
+    const Job job = a.j[i];
+    const DevMat m = i < kInlineDescriptions ? a.first[i] : load_description(job.m);
+    const uint32_t bc = m.cols;
+    const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
+    const uint32_t band_hi = hi >= ce ? m.n_bands : min(m.n_bands, (hi - cb + bc / 2) / bc);
+    if (band_lo >= band_hi) continue;
+    const uint32_t nq = m.n_quads, n_win = m.seg_cols / 8;
+    __syncthreads();   // the previous matrix's dictionary and activation tile are no longer in use
+    if (m.dict != staged) {
+      // 16-bit image of the dictionary: the run bytes of every entry (the length follows from the code)
+      const uint4* src = (const uint4*)m.dict;
+      uint2* dst = (uint2*)lds_dict;
+      const uint32_t n4 = m.dict_words / 4;
+      for (uint32_t base = 0; base < n4; base += kDictRegs * kRingThreads) {
+        uint4 v[kDictRegs];
+#pragma unroll
+        for (int k = 0; k < kDictRegs; ++k) v[k] = global_load(src + min(base + k * kRingThreads + tid, n4 - 1));
+#pragma unroll
+        for (int k = 0; k < kDictRegs; ++k) {
+          const uint32_t idx = base + k * kRingThreads + tid;
+          if (idx < n4) dst[idx] = make_uint2((v[k].x & 0xFFFFu) | v[k].y << 16, (v[k].z & 0xFFFFu) | v[k].w << 16);
+        }
+      }
+      staged = m.dict;
+    }
+    // this wavefront's bands: band_lo + wave, + kRingWaves, ...
+    const uint32_t n_bands = band_hi - band_lo;
+    const uint32_t my_bands = n_bands > (uint32_t)wave ? (n_bands - wave + kRingWaves - 1) / kRingWaves : 0u;
+    const uint32_t my_row = (band_lo + wave) * kUnitRows + (lane & 15);   // the lane's row in the wavefront's first band
+    const uint32_t xfrag = xtile + ((uint32_t)kg * n_win * 16 + bn) * 16;
+    for (uint32_t q = 0; q < nq; ++q) {
+      if (q) __syncthreads();   // everybody has finished the previous quad: its activation tile can go
+      // Activation tile of quad q: piece ((panel * n_win + w) * 16 + batch row) holds 8 columns; rows past the batch are zero.
+      const uint32_t col0 = q * kUnitPanels * m.seg_cols, pieces = kUnitPanels * n_win * 16;
+      for (uint32_t o = tid; o < pieces; o += kRingThreads) {
+        const uint32_t r = o / (kUnitPanels * n_win), c = o - r * (kUnitPanels * n_win);   // batch row, 8-column piece of the quad
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (r < (uint32_t)a.batch) v = *(global_cu128*)((global_cu16*)job.x + (size_t)r * m.cols + col0 + 8 * c);
+        *(__attribute__((address_space(3))) u32x4*)(size_t)(xtile + (c * 16 + r) * 16) = v;   // c = panel * n_win + w
+      }
+      __syncthreads();
+      // Sums of lane l: rows 4 * (l / 16) + v of the band, batch row l % 16.  The scales of the next band are requested
+      // when this one's have been used, a unit ahead of their use: waiting for them is then not a wait for the code
+      // chunks requested in between.
+      const uint32_t band0 = band_lo + wave;
+      float scale[4];
+      auto request_scales = [&](uint32_t band) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) scale[v] = global_load(m.scales + min(band, m.n_bands - 1) * kUnitRows + 4 * kg + v);
+      };
+      request_scales(band0);
+      decode_units_ring(m, band0 * nq + q, kRingWaves * nq, my_bands, lane, ring, xfrag, my_row, kRingWaves * kUnitRows,
+                        [&](uint32_t k, f32x4 sums) {
+        const uint32_t band = band0 + k * kRingWaves;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const uint32_t row = band * kUnitRows + 4 * kg + v;
+          if (bn < a.batch && row < m.rows) {
+            float* y = job.y + (size_t)bn * m.rows + row;
+            if (q == 0) global_store(y, sums[v] * scale[v]);
+            else (void)__builtin_amdgcn_global_atomic_fadd_f32((__attribute__((address_space(1))) float*)y, sums[v] * scale[v]);
+          }
+        }
+        request_scales(band + kRingWaves);
+      });
+    }
+  }
+}
+
+template <bool kXFast>
+__global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
   extern __shared__ uint4 lds4[];
   uint16_t* lds_dict = (uint16_t*)lds4;
   uint8_t* tiles = (uint8_t*)lds4 + a.x_off;
@@ -923,18 +1018,7 @@ __global__ __launch_bounds__(kRing ? kRingThreads : kThreads, 1) void k_matvec_m
         acc = f32x4{0.f, 0.f, 0.f, 0.f};
       }
     };
-    if constexpr (kRing) {
-      const uint32_t ring = lds_address(tiles) + (uint32_t)wave * a.tile_area + (uint32_t)lane * kRingBytes;
-      f32x4 part[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-      decode_run_ring(m, u0, u1, lane, ring, xrow, part, [&](uint32_t band, uint32_t quad) {
-        if (quad + 1 == nq || band * nq + quad + 1 == u1) {
-          acc = (part[0] + part[1]) + (part[2] + part[3]);
-#pragma unroll
-          for (int k = 0; k < 4; ++k) part[k] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-        finish_unit(band, quad);
-      });
-    } else {
+    {
       const uint32_t strip = m.seg_cols + 8;   // bytes between the strips of two lanes
       const uint32_t my_strip = lds_address(tiles) + (uint32_t)wave * a.tile_area + (uint32_t)lane * strip;
       uint4 xa[kMfmaGroup];   // activation fragments of the first MFMA group of the unit being decoded
@@ -1214,9 +1298,9 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   // Dynamic LDS above 64 KB has to be allowed per kernel function.
   e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_decompress, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
 
   const uint8_t* src = (const uint8_t*)blob;
@@ -1311,17 +1395,17 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     hipLaunchKernelGGL((k_matvec<kDotPiece, kDotWaves>), dim3((unsigned)grid), dim3(kDotWaves * 64), lds_total, stream, a);
   } else if (ring) {
     // LDS: 16-bit dictionary image | one ring per lane (aligned to its size: the kernel ORs piece offsets into its
-    // address), reused for the partial sums like the tiles below.
+    // address) | the activation tile of one quad.
     const size_t dict16 = round_up((uint64_t)dict_words_max * 2, kRingBytes);
     a.x_off = (uint32_t)dict16;
     a.tile_area = 64 * kRingBytes;
-    a.slot_off = 0;
-    const size_t lds = dict16 + (size_t)kRingWaves * a.tile_area;
+    a.slot_off = (uint32_t)(dict16 + (size_t)kRingWaves * a.tile_area);
+    const size_t lds = a.slot_off + kRingXTile;
     if (lds > kLdsLimit || !x_fast) {
       set_error("internal: ring launch with a dictionary or activations that do not fit it");
       return TQ_E_UNSUPPORTED;
     }
-    hipLaunchKernelGGL((k_matvec_mfma<true, true>), dim3((unsigned)grid), dim3(kRingThreads), lds, stream, a);
+    hipLaunchKernelGGL(k_matvec_ring, dim3((unsigned)grid), dim3(kRingThreads), lds, stream, a);
   } else {
     // Tile decode.  LDS: 16-bit dictionary image | one tile (64 strips) per wavefront, which the batched product reuses
     // for its partial sums (per wavefront two slots of 1 KB and their two band numbers).
@@ -1338,8 +1422,8 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     const size_t lds = dict16 + waves * area;
     const dim3 block((unsigned)waves * 64);
     if (op == Op::kDecompress) hipLaunchKernelGGL(k_decompress, dim3((unsigned)grid), block, lds, stream, a);
-    else if (x_fast) hipLaunchKernelGGL((k_matvec_mfma<true, false>), dim3((unsigned)grid), block, lds, stream, a);
-    else hipLaunchKernelGGL((k_matvec_mfma<false, false>), dim3((unsigned)grid), block, lds, stream, a);
+    else if (x_fast) hipLaunchKernelGGL((k_matvec_mfma<true>), dim3((unsigned)grid), block, lds, stream, a);
+    else hipLaunchKernelGGL((k_matvec_mfma<false>), dim3((unsigned)grid), block, lds, stream, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(op == Op::kDecompress ? "tq_decompress launch" : "tq_matvec launch", e);
@@ -1348,9 +1432,10 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
 
 // Whether the batched product of this matrix can keep a ring per lane instead of the whole strip.
 bool ring_eligible(const tq_matrix* t, const void* x) {
-  return t->facts.max_lane_spread <= kRingSpread && t->m.cols % (kUnitPanels * t->m.seg_cols) == 0 && t->m.seg_cols >= 8 * kRingGroup &&
-         (uintptr_t)x % 16 == 0 &&
-         round_up((uint64_t)t->m.dict_words * 2, kRingBytes) + (size_t)kRingWaves * 64 * kRingBytes <= kLdsLimit;
+  const DevMat& m = t->m;
+  return t->facts.max_lane_spread <= kRingSpread && m.cols % (kUnitPanels * m.seg_cols) == 0 && m.seg_cols % (8 * kRingGroup) == 0 &&
+         m.seg_cols <= kRingMaxSeg && (uintptr_t)x % 16 == 0 &&
+         round_up((uint64_t)m.dict_words * 2, kRingBytes) + (size_t)kRingWaves * 64 * kRingBytes + kRingXTile <= kLdsLimit;
 }
 
 // As few launches as the kernel-argument size and the 32-bit cost line allow.
