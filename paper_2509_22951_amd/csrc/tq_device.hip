@@ -101,6 +101,15 @@ __device__ __forceinline__ uint32_t unit_offset(const DevMat& m, uint32_t u) { r
 // as well as on the vector-memory one and so would make every LDS wait a wait for the code stream too.
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// Chunk `chunk` of the code stream, lane's 4 codes: a wave-uniform base in scalar registers plus the lane's offset, so
+// that no vector arithmetic goes into the address.
+__device__ __forceinline__ uint2 load_chunk(const uint2* codes, uint32_t chunk, int lane) {
+  const uint64_t base = (uint64_t)codes + (uint64_t)chunk * (64 * sizeof(uint2));
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)base), hi = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32));
+  const u32x2 v = ((__attribute__((address_space(1))) const u32x2*)((uint64_t)hi << 32 | lo))[(uint32_t)lane];
+  return make_uint2(v.x, v.y);
+}
+
 __device__ __forceinline__ uint2 global_load(const uint2* p) {
   const u32x2 v = *(__attribute__((address_space(1))) const u32x2*)p;
   return make_uint2(v.x, v.y);
@@ -231,18 +240,27 @@ __device__ __forceinline__ void zero_activation_gaps(const DevMat& m, int tid, u
 // part goes into the instruction's offset field.  A single advances the lane by one column (already counted by the
 // 4 k), a pair by one more.  The dictionary sits at LDS address 0, so a code's word offset is its address.
 // Per chunk and lane: 4 dictionary words, 4 activation pairs, 4 v_dot2_f32_bf16 into two accumulators.
+// xa + 4 * pair as one instruction.  Written out because the compiler otherwise keeps a running count of the pairs and
+// forms every address from it with a second instruction: a shorter dependency chain, but a quarter more vector
+// instructions per code.
+__device__ __forceinline__ uint32_t advance_by_pair(uint32_t pair, uint32_t xa) {
+  uint32_t r;
+  asm("v_lshl_add_u32 %0, %1, 2, %2" : "=v"(r) : "v"(pair), "v"(xa));
+  return r;
+}
+
 template <int kCode0>
 __device__ __forceinline__ void chunk4(uint2 c, uint32_t& xa, float& a0, float& a1) {
   const uint32_t w0 = lds_read32(word_offset_lo(c.x)), w1 = lds_read32(word_offset_hi(c.x));
   const uint32_t w2 = lds_read32(word_offset_lo(c.y)), w3 = lds_read32(word_offset_hi(c.y));
   const uint32_t x0 = lds_read32_off<4 * kCode0>(xa);
-  xa = (is_pair_lo(c.x) << 2) + xa;
+  xa = advance_by_pair(is_pair_lo(c.x), xa);
   const uint32_t x1 = lds_read32_off<4 * kCode0 + 4>(xa);
-  xa = (is_pair_hi(c.x) << 2) + xa;
+  xa = advance_by_pair(is_pair_hi(c.x), xa);
   const uint32_t x2 = lds_read32_off<4 * kCode0 + 8>(xa);
-  xa = (is_pair_lo(c.y) << 2) + xa;
+  xa = advance_by_pair(is_pair_lo(c.y), xa);
   const uint32_t x3 = lds_read32_off<4 * kCode0 + 12>(xa);
-  xa = (is_pair_hi(c.y) << 2) + xa;
+  xa = advance_by_pair(is_pair_hi(c.y), xa);
   a0 = dot2(w0, x0, a0);
   a1 = dot2(w1, x1, a1);
   a0 = dot2(w2, x2, a0);
@@ -372,11 +390,10 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
           ends = --w_left == 0;
         };
         const uint32_t run_last = c0 + n_chunks - 1;
-        const uint2* codes = m.codes + lane;
         auto load_piece = [&](uint2 (&cw)[kPiece], uint32_t start, uint32_t n) {
           const uint32_t last = min(start + max(n, 1u) - 1, run_last);
 #pragma unroll
-          for (int k = 0; k < kPiece; ++k) cw[k] = global_load(codes + (size_t)min(start + k, last) * 64);
+          for (int k = 0; k < kPiece; ++k) cw[k] = load_chunk(m.codes, min(start + k, last), lane);
         };
         auto run_piece = [&](const uint2 (&cw)[kPiece], uint32_t n, bool ends) {
           if (n == kPiece) {
@@ -528,7 +545,6 @@ template <typename BeforeLast, typename OnUnit>
 __device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0, uint32_t u1, int lane, uint32_t my_strip,
                                                    BeforeLast&& before_last_piece, OnUnit&& on_unit) {
   if (u0 >= u1) return;
-  const uint2* codes = m.codes + lane;
   const uint32_t nq = m.n_quads, n_panels = (m.cols + m.seg_cols - 1) / m.seg_cols;
   // walker over the pieces of the run: unit, pieces left in it, next chunk
   uint32_t wu = u0, wc = unit_offset(m, u0), w_left = 0, w_base = 0, w_rem = 0;
@@ -556,7 +572,7 @@ __device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0,
   auto load_piece = [&](uint2 (&cw)[kPiece], uint32_t start, uint32_t n) {
     const uint32_t last = min(start + max(n, 1u) - 1, run_last);
 #pragma unroll
-    for (int k = 0; k < kPiece; ++k) cw[k] = global_load(codes + (size_t)min(start + k, last) * 64);
+    for (int k = 0; k < kPiece; ++k) cw[k] = load_chunk(m.codes, min(start + k, last), lane);
   };
   // decoder state: the unit being filled
   uint32_t band = u0 / nq, quad = u0 - band * nq;
@@ -720,15 +736,6 @@ constexpr uint32_t kRingSpread = kRingBytes - 8 * kRingStep - 8 * kRingGroup + 1
 constexpr uint32_t kRingMaxSeg = 256;
 constexpr uint32_t kRingXTile = kUnitPanels * kRingMaxSeg * 16 * 2;   // bytes: 4 panels x 256 columns x 16 batch rows of bf16
 static_assert(kRingPiece % kRingStep == 0 && kRingGroup == 4 && kRingStep <= kRingGroup, "ring schedule");
-
-// Chunk `chunk` of the code stream, lane's 4 codes: a wave-uniform base in scalar registers plus the lane's offset, so
-// that no vector arithmetic goes into the address.
-__device__ __forceinline__ uint2 load_chunk(const uint2* codes, uint32_t chunk, int lane) {
-  const uint64_t base = (uint64_t)codes + (uint64_t)chunk * (64 * sizeof(uint2));
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)base), hi = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32));
-  const u32x2 v = ((__attribute__((address_space(1))) const u32x2*)((uint64_t)hi << 32 | lo))[(uint32_t)lane];
-  return make_uint2(v.x, v.y);
-}
 
 // append_chunk for the ring: the complete 8-byte piece goes to its swizzled place; sw8 = 8 * (lane & 15).
 // pos never passes seg_len (pad codes fall off the end), and a piece is complete when pos crosses a multiple of 8.

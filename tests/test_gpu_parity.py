@@ -293,6 +293,60 @@ def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows
             m.close()
 
 
+RING_SPREAD_LIMIT = 65   # lane_spread up to which the batched product keeps a 128-byte ring per lane instead of the whole segment
+
+
+def test_batched_product_ring_and_whole_strip_kernels_agree(dev):
+    """A matrix encoded with an inherited, full dictionary keeps its 64 lanes close together (lane_spread small): with
+    16-byte aligned activations its batched product runs on the ring kernel, with misaligned ones on the whole-strip
+    kernel.  Both must match the oracle, for every batch size that takes these kernels, over several bands, several
+    quads, rows past the last band's end, and 1, 2 and 8 windows per segment."""
+    first = tq.tq_encode(make_weights(small_case(256, 1024, seed=900)), max_entries=3000, seg_cols=64)
+    for rows, cols, seg in [(200, 2048, 256), (1000, 512, 64), (96, 1024, 128), (40, 256, 32)]:
+        spec = small_case(rows, cols, seed=901 + rows)
+        W = make_weights(spec)
+        blob = tq.tq_encode(W, max_entries=3000, seg_cols=seg, dict_from=first)
+        info = tq.tq_validate_blob(blob)
+        assert info["lane_spread"] <= RING_SPREAD_LIMIT and cols % (4 * seg) == 0, info
+        Qo, so = O.quantize_rows(W)
+        m = tq.Matrix(blob)
+        try:
+            for batch in (2, 5, 8, 16):
+                bits, x = make_activations(spec, batch)
+                ref = O.gemv_f64(Qo, so, x)
+                ring = gpu_matvec(m, bits, dev)
+                strip = gpu_matvec(m, bits, dev, misalign=True)
+                check_outputs(ring, ref)
+                check_outputs(strip, ref)
+                assert np.abs(ring - strip).max() <= 1e-5 * np.abs(ref).max()
+                assert np.array_equal(ring, gpu_matvec(m, bits, dev))   # the atomic adds come in a fixed order
+        finally:
+            m.close()
+
+
+def test_lanes_far_apart_fall_back_to_the_whole_strip_kernel(dev):
+    """All-zero rows (every code a pair once the dictionary knows the pair of zeros) next to rows of values the small
+    frozen dictionary has no pairs for (every code a single): the lanes of a unit drift far apart, lane_spread exceeds
+    what a ring can absorb, and the batched product must still be exact through the whole-strip kernel."""
+    rng = np.random.default_rng(5)
+    rows, cols = 64, 2048
+    Q = rng.integers(-127, 128, size=(rows, cols), dtype=np.int8)
+    Q[::2] = 0
+    scales = rng.uniform(0.5, 2.0, rows).astype(np.float32)
+    blob = tq.tq_encode_quantized(Q, scales, max_entries=300, seg_cols=256)
+    info = tq.tq_validate_blob(blob)
+    assert info["lane_spread"] > RING_SPREAD_LIMIT, info
+    spec = small_case(rows, cols, seed=77)
+    m = tq.Matrix(blob)
+    try:
+        assert np.array_equal(gpu_decompress(m, dev), Q)
+        for batch in (1, 8):
+            bits, x = make_activations(spec, batch)
+            check_outputs(gpu_matvec(m, bits, dev), O.gemv_f64(Q, scales, x))
+    finally:
+        m.close()
+
+
 def test_launches_can_be_captured_in_a_hip_graph_and_replayed(dev):
     """The launch calls allocate nothing and do not synchronise: a captured step replays to the eager results, every
     time, with eager work of the same kernels in between."""

@@ -149,3 +149,38 @@ def test_validation_rejects_malformed_containers():
         with pytest.raises(tq.TqError) as ei:
             tq.tq_validate_blob(b)
         assert ei.value.code == -2, why
+
+
+def _lane_spread_from_the_stream(blob: bytes) -> int:
+    """Largest difference between the columns two still incomplete lanes of one unit have reached after the same
+    number of chunks, counted directly from the parsed container."""
+    p = O.parse_blob(blob)
+    _, _, seg_len = O.segment_table(p["rows"], p["cols"], p["seg_cols"])
+    lens = np.concatenate([p["dictionary"].ent_len.astype(np.int64), [0]])   # the pad code adds nothing
+    worst = 0
+    for u in range(p["n_units"]):
+        lo, hi = int(p["uoff"][u]), int(p["uoff"][u + 1])
+        codes = p["stream"][lo * 256: hi * 256].reshape(hi - lo, 64, 4)
+        reached = np.cumsum(lens[codes].sum(axis=2), axis=0)                     # [chunk, lane]
+        want = np.zeros(64, np.int64)
+        segs = seg_len[u * 64: (u + 1) * 64]
+        want[: segs.size] = segs
+        for r in reached:
+            busy = r < want
+            if busy.sum() >= 2:
+                worst = max(worst, int(r[busy].max() - r[busy].min()))
+    return worst
+
+
+@pytest.mark.parametrize("rows,cols,seg_cols,max_entries", [(64, 512, 64, 1000), (40, 300, 32, 300), (48, 1024, 256, 30719),
+                                                            (17, 257, 256, 400)])
+def test_validation_reports_the_lane_spread(rows, cols, seg_cols, max_entries):
+    first = tq.tq_encode(make_weights(small_case(rows, cols, seed=31)), max_entries=max_entries, seg_cols=seg_cols)
+    second = tq.tq_encode(make_weights(small_case(rows, cols, seed=32)), max_entries=max_entries, seg_cols=seg_cols, dict_from=first)
+    for blob in (first, second):
+        assert tq.tq_validate_blob(blob)["lane_spread"] == _lane_spread_from_the_stream(blob)
+    Q = np.zeros((32, 512), np.int8)
+    Q[1::2] = np.random.default_rng(3).integers(-127, 128, size=(16, 512), dtype=np.int8)
+    blob = tq.tq_encode_quantized(Q, np.ones(32, np.float32), max_entries=300, seg_cols=256)
+    spread = tq.tq_validate_blob(blob)["lane_spread"]
+    assert spread == _lane_spread_from_the_stream(blob) and spread > 65
