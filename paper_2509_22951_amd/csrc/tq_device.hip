@@ -55,7 +55,7 @@ struct DevMat {
   uint32_t x_span;         // dwords per panel in the LDS image of x: seg_cols plus a gap that spreads the 4 panels of a unit over the banks
   uint32_t x_dwords;       // size of that image, including the columns lanes can reach while they consume pad codes
   uint32_t seg_magic;      // floor(2^32 / seg_cols) + 1: col / seg_cols == mulhi(col, seg_magic) for every column index in use
-  uint32_t reserved;
+  uint32_t reserved;       // how the ring kernel may decode the matrix: 0 not at all, 1 in groups of windows, 2 window by window
 };
 
 struct Job {
@@ -712,7 +712,10 @@ __device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, glo
 // multiplies them; a lane advances by at most 8 columns per chunk, so one group per look keeps up.  Bytes of the ring
 // are reused kRingBytes columns later: a lane writes 8-byte piece q only when q + 8 - kRingBytes <= done, which holds
 // whenever no two unfinished lanes are ever more than kRingSpread columns apart; the host checks that for every unit
-// when the container is loaded and sends a matrix that does not keep it to the whole-strip kernel.
+// when the container is loaded.  A matrix that does not keep it is decoded in a careful mode - a look after every chunk
+// and one MFMA step at a time, which absorbs a distance of kRingSpreadCareful columns (the first units of a matrix that
+// starts a dictionary, where early segments are still all single bytes, need that) - or, beyond that, goes to the
+// whole-strip kernel.
 // Piece p (8 bytes) of lane l lives at p ^ (l & 15) within the lane's ring: when the 64 lanes read the same window, the
 // 16 lanes served together hit different banks.
 //
@@ -733,6 +736,7 @@ constexpr int kRingPiece = 12;    // chunks per piece of the code stream (two re
 constexpr int kRingStep = 4;      // chunks between two looks at the lanes' progress
 constexpr int kRingGroup = 4;     // MFMA steps per group
 constexpr uint32_t kRingSpread = kRingBytes - 8 * kRingStep - 8 * kRingGroup + 1;
+constexpr uint32_t kRingSpreadCareful = kRingBytes - 8 - 8 + 1;   // looking after every chunk, one MFMA step at a time
 constexpr uint32_t kRingMaxSeg = 256;
 constexpr uint32_t kRingXTile = kUnitPanels * kRingMaxSeg * 16 * 2;   // bytes: 4 panels x 256 columns x 16 batch rows of bf16
 static_assert(kRingPiece % kRingStep == 0 && kRingGroup == 4 && kRingStep <= kRingGroup, "ring schedule");
@@ -761,12 +765,12 @@ typedef __attribute__((address_space(3))) const u32x4 lds_cu128;
 // columns).  ring: LDS address of the lane's ring; xfrag: LDS address of the lane's 16 bytes of window 0 in the
 // activation tile (window w is 256 w bytes further); row: the lane's row in the first unit, row_stride further in each
 // following one.  on_unit(k, sums) is called with the k-th unit's 16 x 16 sums after its last MFMA step.
-template <typename OnUnit>
+template <bool kCareful, typename OnUnit>
 __device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t first, uint32_t stride, uint32_t n_units, int lane, uint32_t ring,
                                                   uint32_t xfrag, uint32_t row, uint32_t row_stride, OnUnit&& on_unit) {
   if (n_units == 0) return;
   uint32_t seg_len = row < m.rows ? m.seg_cols : 0u;   // a row past the end of the matrix has no segment: its lane decodes nothing
-  constexpr int kP = kRingPiece, kG = kRingGroup;
+  constexpr int kP = kRingPiece, kG = kCareful ? 1 : kRingGroup, kLook = kCareful ? 1 : kRingStep;
   const uint32_t sw8 = (uint32_t)(lane & 15) << 3;
   const uint32_t n_win8 = m.seg_cols;
   // walker over the pieces: unit index, pieces left in the unit, next chunk
@@ -827,20 +831,16 @@ __device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t firs
 #pragma unroll
       for (int k = 0; k < kP - 1; ++k) {
         append_chunk_ring(cw[k], ring, sw8, seg_len, pos, carry);
-        if (k % kRingStep == kRingStep - 1) {
-          multiply_ready();
-          load_part(cw_next, next_start, next_n, k / kRingStep);
-        }
+        if (k % kLook == kLook - 1) multiply_ready();
+        if (k % kRingStep == kRingStep - 1) load_part(cw_next, next_start, next_n, k / kRingStep);
       }
       if (n == kP) append_chunk_ring(cw[kP - 1], ring, sw8, seg_len, pos, carry);
     } else {
 #pragma unroll
       for (int k = 0; k < kP - 2; ++k) {
         if ((uint32_t)k < n) append_chunk_ring(cw[k], ring, sw8, seg_len, pos, carry);
-        if (k % kRingStep == kRingStep - 1) {
-          if ((uint32_t)k + 1 < n) multiply_ready();
-          load_part(cw_next, next_start, next_n, k / kRingStep);
-        }
+        if (k % kLook == kLook - 1 && (uint32_t)k + 1 < n) multiply_ready();
+        if (k % kRingStep == kRingStep - 1) load_part(cw_next, next_start, next_n, k / kRingStep);
       }
     }
     multiply_ready();
@@ -915,16 +915,36 @@ __global__ __launch_bounds__(kRingThreads, 1) void k_matvec_ring(MatvecArgs a) {
     const uint32_t my_bands = n_bands > (uint32_t)wave ? (n_bands - wave + kRingWaves - 1) / kRingWaves : 0u;
     const uint32_t my_row = (band_lo + wave) * kUnitRows + (lane & 15);   // the lane's row in the wavefront's first band
     const uint32_t xfrag = xtile + ((uint32_t)kg * n_win * 16 + bn) * 16;
+    // Activation tile of a quad: piece ((panel * n_win + w) * 16 + batch row) holds 8 columns; rows past the batch are
+    // zero.  The pieces of the next quad's tile are requested into registers before this quad is decoded and written
+    // to LDS when everybody has finished it, so that nobody waits for device memory between two quads.
+    constexpr int kTileRegs = kRingXTile / 16 / kRingThreads;
+    const uint32_t pieces = kUnitPanels * n_win * 16, per_row = kUnitPanels * n_win;
+    u32x4 tile[kTileRegs];
+    auto request_tile = [&](uint32_t q) {
+      const uint32_t col0 = q * kUnitPanels * m.seg_cols;
+#pragma unroll
+      for (int k = 0; k < kTileRegs; ++k) {
+        const uint32_t o = min((uint32_t)tid + k * kRingThreads, pieces - 1);
+        const uint32_t r = o / per_row, c = o - r * per_row;   // batch row, 8-column piece of the quad
+        tile[k] = *(global_cu128*)((global_cu16*)job.x + (size_t)min(r, (uint32_t)a.batch - 1) * m.cols + col0 + 8 * c);
+      }
+    };
+    auto commit_tile = [&]() {
+#pragma unroll
+      for (int k = 0; k < kTileRegs; ++k) {
+        const uint32_t o = (uint32_t)tid + k * kRingThreads;
+        const uint32_t r = o / per_row, c = o - r * per_row;
+        u32x4 v = tile[k];
+        if (r >= (uint32_t)a.batch) v = u32x4{0u, 0u, 0u, 0u};
+        if (o < pieces) *(__attribute__((address_space(3))) u32x4*)(size_t)(xtile + (c * 16 + r) * 16) = v;   // c = panel * n_win + w
+      }
+    };
+    request_tile(0);
     for (uint32_t q = 0; q < nq; ++q) {
       if (q) __syncthreads();   // everybody has finished the previous quad: its activation tile can go
-      // Activation tile of quad q: piece ((panel * n_win + w) * 16 + batch row) holds 8 columns; rows past the batch are zero.
-      const uint32_t col0 = q * kUnitPanels * m.seg_cols, pieces = kUnitPanels * n_win * 16;
-      for (uint32_t o = tid; o < pieces; o += kRingThreads) {
-        const uint32_t r = o / (kUnitPanels * n_win), c = o - r * (kUnitPanels * n_win);   // batch row, 8-column piece of the quad
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (r < (uint32_t)a.batch) v = *(global_cu128*)((global_cu16*)job.x + (size_t)r * m.cols + col0 + 8 * c);
-        *(__attribute__((address_space(3))) u32x4*)(size_t)(xtile + (c * 16 + r) * 16) = v;   // c = panel * n_win + w
-      }
+      commit_tile();
+      if (q + 1 < nq) request_tile(q + 1);
       __syncthreads();
       // Sums of lane l: rows 4 * (l / 16) + v of the band, batch row l % 16.  The scales of the next band are requested
       // when this one's have been used, a unit ahead of their use: waiting for them is then not a wait for the code
@@ -936,8 +956,7 @@ __global__ __launch_bounds__(kRingThreads, 1) void k_matvec_ring(MatvecArgs a) {
         for (int v = 0; v < 4; ++v) scale[v] = global_load(m.scales + min(band, m.n_bands - 1) * kUnitRows + 4 * kg + v);
       };
       request_scales(band0);
-      decode_units_ring(m, band0 * nq + q, kRingWaves * nq, my_bands, lane, ring, xfrag, my_row, kRingWaves * kUnitRows,
-                        [&](uint32_t k, f32x4 sums) {
+      auto finish_unit = [&](uint32_t k, f32x4 sums) {
         const uint32_t band = band0 + k * kRingWaves;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -949,7 +968,11 @@ __global__ __launch_bounds__(kRingThreads, 1) void k_matvec_ring(MatvecArgs a) {
           }
         }
         request_scales(band + kRingWaves);
-      });
+      };
+      if (m.reserved == 2)
+        decode_units_ring<true>(m, band0 * nq + q, kRingWaves * nq, my_bands, lane, ring, xfrag, my_row, kRingWaves * kUnitRows, finish_unit);
+      else
+        decode_units_ring<false>(m, band0 * nq + q, kRingWaves * nq, my_bands, lane, ring, xfrag, my_row, kRingWaves * kUnitRows, finish_unit);
     }
   }
 }
@@ -1272,6 +1295,7 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   // on different LDS banks when seg_cols is a multiple of 32.
   m.x_span = h.seg_cols + (h.seg_cols % 32 == 0 ? 16u : 0u);
   m.seg_magic = (uint32_t)((1ull << 32) / h.seg_cols) + 1;   // exact quotient while col * seg_cols < 2^32
+  m.reserved = facts.max_lane_spread <= kRingSpread ? 1u : facts.max_lane_spread <= kRingSpreadCareful ? 2u : 0u;
   if (h.cols > (1u << 20)) {
     set_error("more than 2^20 columns are not supported");
     return TQ_E_UNSUPPORTED;
@@ -1440,7 +1464,7 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
 // Whether the batched product of this matrix can keep a ring per lane instead of the whole strip.
 bool ring_eligible(const tq_matrix* t, const void* x) {
   const DevMat& m = t->m;
-  return t->facts.max_lane_spread <= kRingSpread && m.cols % (kUnitPanels * m.seg_cols) == 0 && m.seg_cols % (8 * kRingGroup) == 0 &&
+  return m.reserved != 0 && m.cols % (kUnitPanels * m.seg_cols) == 0 && m.seg_cols % (8 * kRingGroup) == 0 &&
          m.seg_cols <= kRingMaxSeg && (uintptr_t)x % 16 == 0 &&
          round_up((uint64_t)m.dict_words * 2, kRingBytes) + (size_t)kRingWaves * 64 * kRingBytes + kRingXTile <= kLdsLimit;
 }
