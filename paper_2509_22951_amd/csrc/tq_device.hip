@@ -807,19 +807,22 @@ __device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t firs
   uint64_t carry = 0;
   f32x4 part[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
   // One group of MFMA steps if every lane that is still decoding has written the columns [done, done + 8 kG).
+  // The operands are read before it is known whether the group is ready (volatile: the reads stay ahead of the test),
+  // so that their latency overlaps the test; an unready group just reads them again at the next look.
   auto multiply_ready = [&]() {
-    const uint32_t next = done + 8 * kG;
-    if (next > n_win8) return;
-    if (__builtin_amdgcn_ballot_w64(pos < min(seg_len, next)) != 0) return;
-    const uint32_t base = done ^ sw8;
-    const uint32_t xa = xfrag + done * 32;   // 256 bytes per window
+    const uint32_t at = min(done, n_win8 - 8 * kG);   // at the unit's end: any place inside the ring and the tile
+    const uint32_t base = at ^ sw8;
+    const uint32_t xa = xfrag + at * 32;   // 256 bytes per window
     u32x2 a8[kG];
     u32x4 x8[kG];
 #pragma unroll
     for (int k = 0; k < kG; ++k) {
-      a8[k] = *(lds_cu64*)(size_t)(ring | ((base ^ (8u * k)) & 0x78u));
-      x8[k] = *(lds_cu128*)(size_t)(xa + 256 * k);
+      a8[k] = *(volatile lds_cu64*)(size_t)(ring | ((base ^ (8u * k)) & 0x78u));
+      x8[k] = *(volatile lds_cu128*)(size_t)(xa + 256 * k);
     }
+    const uint32_t next = done + 8 * kG;
+    if (next > n_win8) return;
+    if (__builtin_amdgcn_ballot_w64(pos < min(seg_len, next)) != 0) return;
 #pragma unroll
     for (int k = 0; k < kG; ++k)
       part[k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8[k].x, a8[k].y)), __builtin_bit_cast(bf16x8, x8[k]), part[k], 0, 0, 0);
