@@ -724,9 +724,9 @@ __device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, glo
 // with one ds_read_b128.  (Taken from global memory, every step's fragment load touches 4 panels x batch rows
 // different cache lines; that, not the decode, then bounds the kernel.)  All wavefronts of a workgroup therefore work
 // on the same quad at a time: the workgroup walks the quads of its bands in the outer loop, wavefront w takes the
-// bands w, w + 8, ... whole, and a band's sums go to y once per quad: a plain store for the first quad, an atomic add
-// (no return value, so nothing waits for it) for the others.  One wavefront issues all of them for a given y element,
-// in quad order, so the result does not depend on timing.
+// whole bands, and a band's sums go to y once per quad: a plain store for the first quad, an atomic add (no return
+// value, so nothing waits for it) for the others.  The stores and adds to a given y element are issued in quad order,
+// one workgroup barrier apart from each other, so the result does not depend on timing.
 // Needs rows of a whole number of units (a multiple of 4 * seg_cols columns), segments of 32..256 columns in
 // multiples of 32, and 16-byte aligned activations.
 constexpr int kRingBytes = 128;
@@ -761,35 +761,47 @@ __device__ __forceinline__ void append_chunk_ring(uint2 c, uint32_t ring, uint32
 
 typedef __attribute__((address_space(3))) const u32x4 lds_cu128;
 
-// Decode and multiply the units first, first + stride, ... (n_units of them; every unit has 4 whole panels of seg_cols
-// columns).  ring: LDS address of the lane's ring; xfrag: LDS address of the lane's 16 bytes of window 0 in the
-// activation tile (window w is 256 w bytes further); row: the lane's row in the first unit, row_stride further in each
-// following one.  on_unit(k, sums) is called with the k-th unit's 16 x 16 sums after its last MFMA step.
-template <bool kCareful, typename OnUnit>
-__device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t first, uint32_t stride, uint32_t n_units, int lane, uint32_t ring,
-                                                  uint32_t xfrag, uint32_t row, uint32_t row_stride, OnUnit&& on_unit) {
-  if (n_units == 0) return;
-  uint32_t seg_len = row < m.rows ? m.seg_cols : 0u;   // a row past the end of the matrix has no segment: its lane decodes nothing
+// Decode and multiply units of quad `quad`, one band after the other (every unit has 4 whole panels of seg_cols
+// columns): first the one of band first_band, then those of the bands claim() hands out, until it returns kNoBand.
+// ring: LDS address of the lane's ring; xfrag: LDS address of the lane's 16 bytes of window 0 in the activation tile
+// (window w is 256 w bytes further).  on_unit(band, next_band, sums) is called with a unit's 16 x 16 sums after its
+// last MFMA step; next_band is the band that follows (claimed a piece of chunks ahead), or kNoBand.
+constexpr uint32_t kNoBand = 0xFFFFFFFFu;
+template <bool kCareful, typename Claim, typename OnUnit>
+__device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t quad, uint32_t first_band, Claim&& claim, int lane, uint32_t ring,
+                                                  uint32_t xfrag, OnUnit&& on_unit) {
+  if (first_band == kNoBand) return;
   constexpr int kP = kRingPiece, kG = kCareful ? 1 : kRingGroup, kLook = kCareful ? 1 : kRingStep;
   const uint32_t sw8 = (uint32_t)(lane & 15) << 3;
   const uint32_t n_win8 = m.seg_cols;
-  // walker over the pieces: unit index, pieces left in the unit, next chunk
-  uint32_t wk = 0, wc = 0, w_left = 0, w_base = 0, w_rem = 0;
+  // a row past the end of the matrix has no segment: its lane decodes nothing
+  auto segment_length = [&](uint32_t band) { return band != kNoBand && band * kUnitRows + (lane & 15) < m.rows ? m.seg_cols : 0u; };
+  uint32_t cur_band = first_band, seg_len = segment_length(first_band);
+  // walker over the pieces: the band it is in (the decoder is at most one band behind), pieces left in it, next chunk
+  uint32_t w_band = kNoBand, wc = 0, w_left = 0, w_base = 0, w_rem = 0;
+  bool w_started = false;
   auto next_piece = [&](uint32_t& start, uint32_t& n, bool& ends) {
     if (w_left == 0) {
-      if (wk == n_units) {
+      if (w_started && w_band == kNoBand) {   // nothing left to claim
         n = 0;
         ends = false;
         start = wc;
         return;
       }
-      const uint32_t u = first + wk * stride;
+      w_band = w_started ? claim() : first_band;
+      w_started = true;
+      if (w_band == kNoBand) {
+        n = 0;
+        ends = false;
+        start = wc;
+        return;
+      }
+      const uint32_t u = w_band * m.n_quads + quad;
       wc = unit_offset(m, u);
       const uint32_t len = unit_offset(m, u + 1) - wc;
       w_left = (len + kP - 1) / kP;
       w_base = len / w_left;
       w_rem = len - w_base * w_left;
-      ++wk;
     }
     n = w_base + (w_rem ? 1u : 0u);
     if (w_rem) --w_rem;
@@ -803,7 +815,7 @@ __device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t firs
 #pragma unroll
     for (int k = part * kRingStep; k < (part + 1) * kRingStep; ++k) cw[k] = load_chunk(m.codes, min(start + k, last), lane);
   };
-  uint32_t pos = 0, done = 0, unit_k = 0;
+  uint32_t pos = 0, done = 0;
   uint64_t carry = 0;
   f32x4 part[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
   // One group of MFMA steps if every lane that is still decoding has written the columns [done, done + 8 kG).
@@ -849,12 +861,13 @@ __device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t firs
     multiply_ready();
     load_part(cw_next, next_start, next_n, kP / kRingStep - 1);
     if (ends) {   // every lane is complete and at most one whole group was left: the unit has been multiplied
-      on_unit(unit_k, (part[0] + part[1]) + (part[2] + part[3]));
+      // the walker is one piece ahead: w_band is the band of the unit that follows, if there is one
+      const uint32_t next_band = w_band == cur_band ? kNoBand : w_band;
+      on_unit(cur_band, next_band, (part[0] + part[1]) + (part[2] + part[3]));
 #pragma unroll
       for (int k = 0; k < 4; ++k) part[k] = f32x4{0.f, 0.f, 0.f, 0.f};
-      ++unit_k;
-      row += row_stride;
-      seg_len = row < m.rows ? m.seg_cols : 0u;
+      cur_band = next_band;
+      seg_len = segment_length(cur_band);
       pos = 0;
       carry = 0;
       done = 0;
@@ -913,10 +926,19 @@ __global__ __launch_bounds__(kRingThreads, 1) void k_matvec_ring(MatvecArgs a) {
       }
       staged = m.dict;
     }
-    // this wavefront's bands: band_lo + wave, + kRingWaves, ...
+    // Bands are handed out one at a time, per quad, through a counter in LDS: wavefront w starts with band w of the
+    // workgroup's range and claims the next free one while it decodes the last piece of chunks of the one in work.
+    // (An even split up front leaves wavefronts waiting at the end of every quad: for the slowest, and for the one more
+    // band that some of them have.)
     const uint32_t n_bands = band_hi - band_lo;
-    const uint32_t my_bands = n_bands > (uint32_t)wave ? (n_bands - wave + kRingWaves - 1) / kRingWaves : 0u;
-    const uint32_t my_row = (band_lo + wave) * kUnitRows + (lane & 15);   // the lane's row in the wavefront's first band
+    typedef __attribute__((address_space(3))) uint32_t lds_u32;
+    lds_u32* next_band_counter = (lds_u32*)(size_t)(xtile + kRingXTile);
+    auto claim = [&]() {
+      uint32_t b = 0;
+      if (lane == 0) b = __hip_atomic_fetch_add(next_band_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      b = __builtin_amdgcn_readfirstlane(b);
+      return b < n_bands ? band_lo + b : kNoBand;
+    };
     const uint32_t xfrag = xtile + ((uint32_t)kg * n_win * 16 + bn) * 16;
     // Activation tile of a quad: piece ((panel * n_win + w) * 16 + batch row) holds 8 columns; rows past the batch are
     // zero.  The pieces of the next quad's tile are requested into registers before this quad is decoded and written
@@ -946,21 +968,21 @@ __global__ __launch_bounds__(kRingThreads, 1) void k_matvec_ring(MatvecArgs a) {
     request_tile(0);
     for (uint32_t q = 0; q < nq; ++q) {
       if (q) __syncthreads();   // everybody has finished the previous quad: its activation tile can go
+      if (tid == 0) *next_band_counter = kRingWaves;   // bands 0 .. kRingWaves - 1 are the wavefronts' first ones
       commit_tile();
       if (q + 1 < nq) request_tile(q + 1);
       __syncthreads();
       // Sums of lane l: rows 4 * (l / 16) + v of the band, batch row l % 16.  The scales of the next band are requested
       // when this one's have been used, a unit ahead of their use: waiting for them is then not a wait for the code
       // chunks requested in between.
-      const uint32_t band0 = band_lo + wave;
+      const uint32_t band0 = (uint32_t)wave < n_bands ? band_lo + wave : kNoBand;
       float scale[4];
       auto request_scales = [&](uint32_t band) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) scale[v] = global_load(m.scales + min(band, m.n_bands - 1) * kUnitRows + 4 * kg + v);
       };
       request_scales(band0);
-      auto finish_unit = [&](uint32_t k, f32x4 sums) {
-        const uint32_t band = band0 + k * kRingWaves;
+      auto finish_unit = [&](uint32_t band, uint32_t next_band, f32x4 sums) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const uint32_t row = band * kUnitRows + 4 * kg + v;
@@ -970,12 +992,10 @@ __global__ __launch_bounds__(kRingThreads, 1) void k_matvec_ring(MatvecArgs a) {
             else (void)__builtin_amdgcn_global_atomic_fadd_f32((__attribute__((address_space(1))) float*)y, sums[v] * scale[v]);
           }
         }
-        request_scales(band + kRingWaves);
+        request_scales(next_band);
       };
-      if (m.reserved == 2)
-        decode_units_ring<true>(m, band0 * nq + q, kRingWaves * nq, my_bands, lane, ring, xfrag, my_row, kRingWaves * kUnitRows, finish_unit);
-      else
-        decode_units_ring<false>(m, band0 * nq + q, kRingWaves * nq, my_bands, lane, ring, xfrag, my_row, kRingWaves * kUnitRows, finish_unit);
+      if (m.reserved == 2) decode_units_ring<true>(m, q, band0, claim, lane, ring, xfrag, finish_unit);
+      else decode_units_ring<false>(m, q, band0, claim, lane, ring, xfrag, finish_unit);
     }
   }
 }
@@ -1434,7 +1454,7 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     a.x_off = (uint32_t)dict16;
     a.tile_area = 64 * kRingBytes;
     a.slot_off = (uint32_t)(dict16 + (size_t)kRingWaves * a.tile_area);
-    const size_t lds = a.slot_off + kRingXTile;
+    const size_t lds = a.slot_off + kRingXTile + 128;   // + the band counter
     if (lds > kLdsLimit || !x_fast) {
       set_error("internal: ring launch with a dictionary or activations that do not fit it");
       return TQ_E_UNSUPPORTED;
@@ -1469,7 +1489,7 @@ bool ring_eligible(const tq_matrix* t, const void* x) {
   const DevMat& m = t->m;
   return m.reserved != 0 && m.cols % (kUnitPanels * m.seg_cols) == 0 && m.seg_cols % (8 * kRingGroup) == 0 &&
          m.seg_cols <= kRingMaxSeg && (uintptr_t)x % 16 == 0 &&
-         round_up((uint64_t)m.dict_words * 2, kRingBytes) + (size_t)kRingWaves * 64 * kRingBytes + kRingXTile <= kLdsLimit;
+         round_up((uint64_t)m.dict_words * 2, kRingBytes) + (size_t)kRingWaves * 64 * kRingBytes + kRingXTile + 128 <= kLdsLimit;
 }
 
 // As few launches as the kernel-argument size and the 32-bit cost line allow.
