@@ -730,15 +730,15 @@ __device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, glo
 // Needs rows of a whole number of units (a multiple of 4 * seg_cols columns), segments of 32..256 columns in
 // multiples of 32, and 16-byte aligned activations.
 constexpr int kRingBytes = 128;
-constexpr int kRingWaves = 8;
-constexpr int kRingThreads = kRingWaves * 64;
+constexpr int kRingWaves = 8;       // with an activation tile of 16 batch rows
+constexpr int kRingWavesHalf = 10;  // with one of 8 batch rows (batches up to 8): more wavefronts fit next to the smaller tile
 constexpr int kRingPiece = 12;    // chunks per piece of the code stream (two register sets)
 constexpr int kRingStep = 4;      // chunks between two looks at the lanes' progress
 constexpr int kRingGroup = 4;     // MFMA steps per group
 constexpr uint32_t kRingSpread = kRingBytes - 8 * kRingStep - 8 * kRingGroup + 1;
 constexpr uint32_t kRingSpreadCareful = kRingBytes - 8 - 8 + 1;   // looking after every chunk, one MFMA step at a time
 constexpr uint32_t kRingMaxSeg = 256;
-constexpr uint32_t kRingXTile = kUnitPanels * kRingMaxSeg * 16 * 2;   // bytes: 4 panels x 256 columns x 16 batch rows of bf16
+constexpr uint32_t ring_x_tile(int rows) { return kUnitPanels * kRingMaxSeg * rows * 2; }   // bytes: 4 panels x 256 columns x batch rows of bf16
 static_assert(kRingPiece % kRingStep == 0 && kRingGroup == 4 && kRingStep <= kRingGroup, "ring schedule");
 
 // append_chunk for the ring: the complete 8-byte piece goes to its swizzled place; sw8 = 8 * (lane & 15).
@@ -764,10 +764,10 @@ typedef __attribute__((address_space(3))) const u32x4 lds_cu128;
 // Decode and multiply units of quad `quad`, one band after the other (every unit has 4 whole panels of seg_cols
 // columns): first the one of band first_band, then those of the bands claim() hands out, until it returns kNoBand.
 // ring: LDS address of the lane's ring; xfrag: LDS address of the lane's 16 bytes of window 0 in the activation tile
-// (window w is 256 w bytes further).  on_unit(band, next_band, sums) is called with a unit's 16 x 16 sums after its
+// (window w is 16 kRows w bytes further).  on_unit(band, next_band, sums) is called with a unit's 16 x 16 sums after its
 // last MFMA step; next_band is the band that follows (claimed a piece of chunks ahead), or kNoBand.
 constexpr uint32_t kNoBand = 0xFFFFFFFFu;
-template <bool kCareful, typename Claim, typename OnUnit>
+template <bool kCareful, int kRows, typename Claim, typename OnUnit>
 __device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t quad, uint32_t first_band, Claim&& claim, int lane, uint32_t ring,
                                                   uint32_t xfrag, OnUnit&& on_unit) {
   if (first_band == kNoBand) return;
@@ -824,13 +824,13 @@ __device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t quad
   auto multiply_ready = [&]() {
     const uint32_t at = min(done, n_win8 - 8 * kG);   // at the unit's end: any place inside the ring and the tile
     const uint32_t base = at ^ sw8;
-    const uint32_t xa = xfrag + at * 32;   // 256 bytes per window
+    const uint32_t xa = xfrag + at * (2 * kRows);   // 16 kRows bytes per window
     u32x2 a8[kG];
     u32x4 x8[kG];
 #pragma unroll
     for (int k = 0; k < kG; ++k) {
       a8[k] = *(volatile lds_cu64*)(size_t)(ring | ((base ^ (8u * k)) & 0x78u));
-      x8[k] = *(volatile lds_cu128*)(size_t)(xa + 256 * k);
+      x8[k] = *(volatile lds_cu128*)(size_t)(xa + 16 * kRows * k);
     }
     const uint32_t next = done + 8 * kG;
     if (next > n_win8) return;
@@ -887,7 +887,10 @@ __device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t quad
   }
 }
 
-__global__ __launch_bounds__(kRingThreads, 1) void k_matvec_ring(MatvecArgs a) {
+template <int kWaves, int kRows>
+__global__ __launch_bounds__(kWaves * 64, 1) void k_matvec_ring(MatvecArgs a) {
+  constexpr int kRingThreads = kWaves * 64;
+  constexpr uint32_t kRingXTile = ring_x_tile(kRows);
   extern __shared__ uint4 lds4[];
   uint16_t* lds_dict = (uint16_t*)lds4;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -939,12 +942,12 @@ __global__ __launch_bounds__(kRingThreads, 1) void k_matvec_ring(MatvecArgs a) {
       b = __builtin_amdgcn_readfirstlane(b);
       return b < n_bands ? band_lo + b : kNoBand;
     };
-    const uint32_t xfrag = xtile + ((uint32_t)kg * n_win * 16 + bn) * 16;
-    // Activation tile of a quad: piece ((panel * n_win + w) * 16 + batch row) holds 8 columns; rows past the batch are
+    const uint32_t xfrag = xtile + ((uint32_t)kg * n_win * kRows + (bn & (kRows - 1))) * 16;   // lanes past kRows repeat a row: their sums are not stored
+    // Activation tile of a quad: piece ((panel * n_win + w) * kRows + batch row) holds 8 columns; rows past the batch are
     // zero.  The pieces of the next quad's tile are requested into registers before this quad is decoded and written
     // to LDS when everybody has finished it, so that nobody waits for device memory between two quads.
-    constexpr int kTileRegs = kRingXTile / 16 / kRingThreads;
-    const uint32_t pieces = kUnitPanels * n_win * 16, per_row = kUnitPanels * n_win;
+    constexpr int kTileRegs = (kRingXTile / 16 + kRingThreads - 1) / kRingThreads;
+    const uint32_t pieces = kUnitPanels * n_win * kRows, per_row = kUnitPanels * n_win;
     u32x4 tile[kTileRegs];
     auto request_tile = [&](uint32_t q) {
       const uint32_t col0 = q * kUnitPanels * m.seg_cols;
@@ -962,13 +965,13 @@ __global__ __launch_bounds__(kRingThreads, 1) void k_matvec_ring(MatvecArgs a) {
         const uint32_t r = o / per_row, c = o - r * per_row;
         u32x4 v = tile[k];
         if (r >= (uint32_t)a.batch) v = u32x4{0u, 0u, 0u, 0u};
-        if (o < pieces) *(__attribute__((address_space(3))) u32x4*)(size_t)(xtile + (c * 16 + r) * 16) = v;   // c = panel * n_win + w
+        if (o < pieces) *(__attribute__((address_space(3))) u32x4*)(size_t)(xtile + (c * kRows + r) * 16) = v;   // c = panel * n_win + w
       }
     };
     request_tile(0);
     for (uint32_t q = 0; q < nq; ++q) {
       if (q) __syncthreads();   // everybody has finished the previous quad: its activation tile can go
-      if (tid == 0) *next_band_counter = kRingWaves;   // bands 0 .. kRingWaves - 1 are the wavefronts' first ones
+      if (tid == 0) *next_band_counter = kWaves;   // bands 0 .. kWaves - 1 are the wavefronts' first ones
       commit_tile();
       if (q + 1 < nq) request_tile(q + 1);
       __syncthreads();
@@ -994,8 +997,8 @@ __global__ __launch_bounds__(kRingThreads, 1) void k_matvec_ring(MatvecArgs a) {
         }
         request_scales(next_band);
       };
-      if (m.reserved == 2) decode_units_ring<true>(m, q, band0, claim, lane, ring, xfrag, finish_unit);
-      else decode_units_ring<false>(m, q, band0, claim, lane, ring, xfrag, finish_unit);
+      if (m.reserved == 2) decode_units_ring<true, kRows>(m, q, band0, claim, lane, ring, xfrag, finish_unit);
+      else decode_units_ring<false, kRows>(m, q, band0, claim, lane, ring, xfrag, finish_unit);
     }
   }
 }
@@ -1354,7 +1357,8 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_decompress, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWaves, 16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesHalf, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
 
   const uint8_t* src = (const uint8_t*)blob;
@@ -1453,13 +1457,16 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     const size_t dict16 = round_up((uint64_t)dict_words_max * 2, kRingBytes);
     a.x_off = (uint32_t)dict16;
     a.tile_area = 64 * kRingBytes;
-    a.slot_off = (uint32_t)(dict16 + (size_t)kRingWaves * a.tile_area);
-    const size_t lds = a.slot_off + kRingXTile + 128;   // + the band counter
+    const bool half = batch <= 8;   // 8 batch rows in the tile: room for two more wavefronts
+    const int waves = half ? kRingWavesHalf : kRingWaves;
+    a.slot_off = (uint32_t)(dict16 + (size_t)waves * a.tile_area);
+    const size_t lds = a.slot_off + ring_x_tile(half ? 8 : 16) + 128;   // + the band counter
     if (lds > kLdsLimit || !x_fast) {
       set_error("internal: ring launch with a dictionary or activations that do not fit it");
       return TQ_E_UNSUPPORTED;
     }
-    hipLaunchKernelGGL(k_matvec_ring, dim3((unsigned)grid), dim3(kRingThreads), lds, stream, a);
+    if (half) hipLaunchKernelGGL((k_matvec_ring<kRingWavesHalf, 8>), dim3((unsigned)grid), dim3(kRingWavesHalf * 64), lds, stream, a);
+    else hipLaunchKernelGGL((k_matvec_ring<kRingWaves, 16>), dim3((unsigned)grid), dim3(kRingWaves * 64), lds, stream, a);
   } else {
     // Tile decode.  LDS: 16-bit dictionary image | one tile (64 strips) per wavefront, which the batched product reuses
     // for its partial sums (per wavefront two slots of 1 KB and their two band numbers).
@@ -1489,7 +1496,7 @@ bool ring_eligible(const tq_matrix* t, const void* x) {
   const DevMat& m = t->m;
   return m.reserved != 0 && m.cols % (kUnitPanels * m.seg_cols) == 0 && m.seg_cols % (8 * kRingGroup) == 0 &&
          m.seg_cols <= kRingMaxSeg && (uintptr_t)x % 16 == 0 &&
-         round_up((uint64_t)m.dict_words * 2, kRingBytes) + (size_t)kRingWaves * 64 * kRingBytes + kRingXTile + 128 <= kLdsLimit;
+         round_up((uint64_t)m.dict_words * 2, kRingBytes) + (size_t)kRingWaves * 64 * kRingBytes + ring_x_tile(16) + 128 <= kLdsLimit;
 }
 
 // As few launches as the kernel-argument size and the 32-bit cost line allow.
