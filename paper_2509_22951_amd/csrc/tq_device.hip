@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -738,6 +739,7 @@ constexpr int kRingGroup = 4;     // MFMA steps per group
 constexpr uint32_t kRingSpread = kRingBytes - 8 * kRingStep - 8 * kRingGroup + 1;
 constexpr uint32_t kRingSpreadCareful = kRingBytes - 8 - 8 + 1;   // looking after every chunk, one MFMA step at a time
 constexpr uint32_t kRingMaxSeg = 256;
+constexpr int kRingMinBandsPerCu = 24;   // below that many bands per CU in a launch the whole-strip kernel is used
 constexpr uint32_t ring_x_tile(int rows) { return kUnitPanels * kRingMaxSeg * rows * 2; }   // bytes: 4 panels x 256 columns x batch rows of bf16
 static_assert(kRingPiece % kRingStep == 0 && kRingGroup == 4 && kRingStep <= kRingGroup, "ring schedule");
 
@@ -1492,6 +1494,13 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
 }
 
 // Whether the batched product of this matrix can keep a ring per lane instead of the whole strip.
+// Bands per CU a launch needs for the ring kernel; TQ_RING_MIN_BANDS_PER_CU overrides it (tests use 0 to put small
+// matrices through that kernel).
+uint64_t ring_min_bands_per_cu() {
+  if (const char* e = std::getenv("TQ_RING_MIN_BANDS_PER_CU")) return std::strtoull(e, nullptr, 10);
+  return kRingMinBandsPerCu;
+}
+
 bool ring_eligible(const tq_matrix* t, const void* x) {
   const DevMat& m = t->m;
   return m.reserved != 0 && m.cols % (kUnitPanels * m.seg_cols) == 0 && m.seg_cols % (8 * kRingGroup) == 0 &&
@@ -1504,15 +1513,23 @@ int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* c
   if (op == Op::kMatvec && batch > 1 && !ring) {
     // The matrices that can take the ring kernel go there, the others to the whole-strip kernel; the products are
     // independent, so regrouping them changes nothing but the launches.
+    // The ring kernel gives whole bands to wavefronts, a quad at a time: it needs many bands per workgroup to keep its
+    // wavefronts busy (the whole-strip kernel splits single units between them).
     int n_ring = 0;
-    for (int i = 0; i < n; ++i) n_ring += ring_eligible(hs[i], xs[i]);
+    uint64_t ring_bands = 0;
+    for (int i = 0; i < n; ++i)
+      if (ring_eligible(hs[i], xs[i])) {
+        ++n_ring;
+        ring_bands += hs[i]->m.n_bands;
+      }
+    if (ring_bands < ring_min_bands_per_cu() * hs[0]->n_cu) n_ring = 0;
     if (n_ring == n) return launch_all(op, n, hs, xs, ys, batch, stream, true);
     if (n_ring > 0) {
       std::vector<tq_handle> h2[2];
       std::vector<const void*> x2[2];
       std::vector<void*> y2[2];
       for (int i = 0; i < n; ++i) {
-        const int g = ring_eligible(hs[i], xs[i]) ? 1 : 0;
+        const int g = ring_eligible(hs[i], xs[i]) ? 1 : 0;   // n_ring > 0: the eligible ones have enough bands together
         h2[g].push_back(hs[i]);
         x2[g].push_back(xs[i]);
         y2[g].push_back(ys[i]);
@@ -1579,7 +1596,8 @@ extern "C" int tq_matvec(tq_handle h, const void* x, void* y, int batch, void* s
     return TQ_E_INVALID_ARG;
   }
   if (int rc = check_call("tq_matvec", 1, &h, &x, &y, batch)) return rc;
-  return launch(Op::kMatvec, 1, &h, &x, &y, batch, (hipStream_t)stream, batch > 1 && ring_eligible(h, x));
+  return launch(Op::kMatvec, 1, &h, &x, &y, batch, (hipStream_t)stream,
+                batch > 1 && ring_eligible(h, x) && h->m.n_bands >= ring_min_bands_per_cu() * h->n_cu);
 }
 
 extern "C" int tq_matvec_multi(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {

@@ -21,6 +21,12 @@ def dev():
     return torch.device("cuda:0")
 
 
+@pytest.fixture
+def ring_for_small_launches(monkeypatch):
+    """The library keeps the ring kernel for launches with many bands per CU; this lets a small matrix through."""
+    monkeypatch.setenv("TQ_RING_MIN_BANDS_PER_CU", "0")
+
+
 def _stream():
     return torch.cuda.current_stream().cuda_stream
 
@@ -218,6 +224,14 @@ def test_multi_launch_matches_single_launches_and_oracle(dev, shared_dictionary)
         _multi_case(dev, shapes, batch, shared_dictionary)
 
 
+def test_multi_launch_splits_into_ring_and_whole_strip_launches(dev, ring_for_small_launches):
+    """One call whose matrices go partly to the ring kernel (inherited dictionary, whole units, aligned activations) and
+    partly to the whole-strip kernel (300 columns: no whole units)."""
+    shapes = [(192, 768, 64), (64, 768, 64), (64, 768, 192), (40, 300, 32), (512, 768, 192), (192, 2048, 256), (100, 1024, 128)]
+    for batch in (3, 8, 16):
+        _multi_case(dev, shapes, batch, True)
+
+
 def test_multi_launch_of_more_matrices_than_one_kernel_takes(dev):
     shapes = [(16 * (1 + k % 5), 256 + 64 * (k % 3), 64) for k in range(70)]
     _multi_case(dev, shapes, 2, True, max_entries=600)
@@ -296,7 +310,7 @@ def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows
 RING_SPREAD_LIMIT = 65   # lane_spread up to which the batched product keeps a 128-byte ring per lane instead of the whole segment
 
 
-def test_batched_product_ring_and_whole_strip_kernels_agree(dev):
+def test_batched_product_ring_and_whole_strip_kernels_agree(dev, ring_for_small_launches):
     """A matrix encoded with an inherited, full dictionary keeps its 64 lanes close together (lane_spread small): with
     16-byte aligned activations its batched product runs on the ring kernel, with misaligned ones on the whole-strip
     kernel.  Both must match the oracle, for every batch size that takes these kernels, over several bands, several
@@ -324,7 +338,7 @@ def test_batched_product_ring_and_whole_strip_kernels_agree(dev):
             m.close()
 
 
-def test_matrix_that_starts_a_dictionary_takes_the_careful_ring_mode(dev):
+def test_matrix_that_starts_a_dictionary_takes_the_careful_ring_mode(dev, ring_for_small_launches):
     """The first segments of a matrix that starts from the 256 single bytes are nearly all singles, later ones nearly all
     pairs: the lanes of the first units are further apart than the ring absorbs in groups of 4 windows, but not further
     than it absorbs window by window."""
