@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of the matvec launches measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the default workload
 # (config 4, batch 1, default encoder options, whole sweep in one tq_matvec_multi call), scaled by a plain 1 GiB copy in
 # the same run (profiles/k_matvec_config4_batch1_hbm_traffic.txt): bytes read per algorithmic byte, bytes written per step.
-MEASURED_FETCH_PER_ALGORITHMIC_BYTE = 1.0041
-MEASURED_WRITE_BYTES_PER_STEP = 3_628_700
+MEASURED_FETCH_PER_ALGORITHMIC_BYTE = 1.0040
+MEASURED_WRITE_BYTES_PER_STEP = 3_628_000
 
 
 def parse_args():
