@@ -113,8 +113,15 @@ int tq_create_from_encoded(const void *blob, size_t blob_bytes, tq_handle *out);
  * the kernel.  The result is deterministic (fixed summation order).  x values must be finite: a lane that has
  * run out of codes multiplies activations of later columns by zero, so an infinity or NaN anywhere in x can make
  * any output of that batch row non-finite (the plain definition does the same wherever a weight is zero).
- * batch 1 runs the dot-product kernel (activations gathered from an LDS image of x), batch 2..16 the MFMA kernel
- * (decoded weights pass through an LDS tile; the batch is the N dimension).
+ * batch 1 runs the dot-product kernel (activations gathered from an LDS image of x), batch 2..16 an MFMA kernel
+ * (the batch is the N dimension).  Of those there are two.  The ring kernel keeps 128 bytes of every segment in LDS
+ * and multiplies while it decodes; it takes matrices whose lane_spread (tq_info) is at most 113 columns, whose rows
+ * are a whole number of units (cols a multiple of 4 * seg_cols), with seg_cols a multiple of 32 up to 256 and x
+ * 16-byte aligned, in calls that bring at least 24 bands of 16 rows per compute unit (the environment variable
+ * TQ_RING_MIN_BANDS_PER_CU overrides that number; it is read at every call).  Everything else goes through the
+ * whole-strip kernel, which decodes a unit into an LDS tile before it multiplies it.  The ring kernel adds the partial
+ * sums of a row's later quads (groups of 4 segments) to y with atomic adds, always in the same order; y must not be
+ * read or written by anything else on the device while the call runs (true of any output buffer).
  */
 int tq_matvec(tq_handle h, const void *x, void *y, int batch, void *stream);
 
