@@ -157,6 +157,59 @@ int tq_destroy(tq_handle h);
 
 const char *tq_last_error_string(void);
 
+/*
+ * The stream format of the paper's section 4 listings, taken literally (the container above is this library's own
+ * reading of the method; this is the format the paper prints).
+ *
+ * Table (Listing "Finding Frequent Sequences"): every window of TQ_LISTING_SEQ = 4 consecutive byte values of every
+ * parameter, at every offset, never across two parameters, is counted; the top_k most frequent windows, most frequent
+ * first and among equally frequent ones in order of first appearance, get the codewords 1, 2, ...
+ * Stream (Listing "Compressing Model Weights"), per parameter, 16-bit words: the values are cut into groups of 4 from
+ * the start; a group in the table becomes its codeword, any other group the marker 0xFFFF followed by its 4 values,
+ * one word each; fewer than 4 values left at the end follow a marker likewise.
+ * top_k is at most TQ_LISTING_MAX_TOP_K = 65534: with the 65535 the listing prints as default, the last codeword
+ * would have the marker's value.  Codeword 0 is never assigned.
+ */
+#define TQ_LISTING_SEQ 4
+#define TQ_LISTING_MAX_TOP_K 65534u
+
+typedef struct tq_listing_s *tq_listing;
+
+typedef struct tq_listing_info {
+  uint64_t n_values;  /* byte values the stream stands for */
+  uint64_t n_words;   /* 16-bit words of the stream */
+  uint64_t n_tokens;  /* codewords + markers */
+  uint64_t n_escapes; /* markers */
+  uint32_t n_table;   /* table entries */
+  uint32_t reserved;
+} tq_listing_info;
+
+/* Host.  params[i]: lens[i] byte values.  *table: n_table x 4 values, entry i = codeword i + 1; allocated by the
+ * library, release with tq_free_blob.  Fewer than top_k entries when there are fewer distinct windows. */
+int tq_listing_build_table(const uint8_t *const *params, const uint64_t *lens, uint32_t n_params, uint32_t top_k,
+                           uint8_t **table, uint32_t *n_table);
+
+/* Host.  One parameter -> its words (allocated by the library, release with tq_free_blob).  Table entries must be
+ * distinct. */
+int tq_listing_compress(const uint8_t *values, uint64_t n_values, const uint8_t *table, uint32_t n_table,
+                        uint16_t **words, uint64_t *n_words);
+
+/* words, table: host.  Validates the stream (every codeword in the table, raw values at most 255, a marker followed by
+ * 4 values except at the very end, where 1..3 are allowed), copies stream and table into device memory the handle
+ * owns, on the current HIP device, and keeps the number of tokens ahead of every block of words, which is what lets
+ * the device expand the stream in parallel.  Synchronous; the caller may free words and table on return. */
+int tq_listing_create(const uint16_t *words, uint64_t n_words, const uint8_t *table, uint32_t n_table, tq_listing *out);
+
+/* Listing "Decompressing Model Weights" on the device.  out: device, n_values bytes (tq_listing_get_info), fully
+ * overwritten with exactly the values that were compressed.  Asynchronous on `stream` (a hipStream_t, NULL = default
+ * stream); no allocation, no change to the handle. */
+int tq_listing_decompress(tq_listing h, void *out, void *stream);
+
+int tq_listing_get_info(tq_listing h, tq_listing_info *out);
+
+/* Frees the device memory; no work of the handle may be in flight.  NULL is a no-op. */
+int tq_listing_destroy(tq_listing h);
+
 #ifdef __cplusplus
 }
 #endif

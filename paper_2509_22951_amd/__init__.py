@@ -26,4 +26,8 @@ from .binding import (  # noqa: F401
     tq_get_info,
     tq_destroy,
     tq_last_error_string,
+    TqListingInfo,
+    Listing,
+    tq_listing_build_table,
+    tq_listing_compress,
 )

@@ -19,6 +19,8 @@ _LIB: Optional[ctypes.CDLL] = None
 EXPORTS = [
     "tq_encode", "tq_encode_quantized", "tq_free_blob", "tq_validate_blob", "tq_create_from_encoded", "tq_matvec",
     "tq_matvec_multi", "tq_decompress", "tq_decompress_multi", "tq_get_info", "tq_destroy", "tq_last_error_string",
+    "tq_listing_build_table", "tq_listing_compress", "tq_listing_create", "tq_listing_decompress", "tq_listing_get_info",
+    "tq_listing_destroy",
 ]
 
 
@@ -43,6 +45,14 @@ class TqInfo(ctypes.Structure):
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+class TqListingInfo(ctypes.Structure):
+    _fields_ = [("n_values", ctypes.c_uint64), ("n_words", ctypes.c_uint64), ("n_tokens", ctypes.c_uint64),
+                ("n_escapes", ctypes.c_uint64), ("n_table", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_ if n != "reserved"}
 
 
 def lib_path() -> str:
@@ -84,6 +94,19 @@ def load() -> ctypes.CDLL:
     lib.tq_destroy.argtypes = [vp]
     lib.tq_last_error_string.restype = ctypes.c_char_p
     lib.tq_last_error_string.argtypes = []
+    u64 = ctypes.c_uint64
+    lib.tq_listing_build_table.restype = ci
+    lib.tq_listing_build_table.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(u64), u32, u32, ctypes.POINTER(vp), ctypes.POINTER(u32)]
+    lib.tq_listing_compress.restype = ci
+    lib.tq_listing_compress.argtypes = [vp, u64, vp, u32, ctypes.POINTER(vp), ctypes.POINTER(u64)]
+    lib.tq_listing_create.restype = ci
+    lib.tq_listing_create.argtypes = [vp, u64, vp, u32, ctypes.POINTER(vp)]
+    lib.tq_listing_decompress.restype = ci
+    lib.tq_listing_decompress.argtypes = [vp, vp, vp]
+    lib.tq_listing_get_info.restype = ci
+    lib.tq_listing_get_info.argtypes = [vp, ctypes.POINTER(TqListingInfo)]
+    lib.tq_listing_destroy.restype = ci
+    lib.tq_listing_destroy.argtypes = [vp]
     _LIB = lib
     return lib
 
@@ -210,6 +233,64 @@ class Matrix:
     def close(self) -> None:
         h, self.handle = self.handle, None
         tq_destroy(h)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ---- the stream format of the paper's section 4 listings (marshalling only) ----
+
+def tq_listing_build_table(params, top_k: int = 65534) -> np.ndarray:
+    """params: sequence of uint8 arrays (one per parameter).  Returns uint8 [n, 4]; row i is codeword i + 1."""
+    arrs = [np.ascontiguousarray(p, dtype=np.uint8).reshape(-1) for p in params]
+    n = len(arrs)
+    ptrs = (ctypes.c_void_p * max(n, 1))(*[a.ctypes.data for a in arrs])
+    lens = (ctypes.c_uint64 * max(n, 1))(*[a.size for a in arrs])
+    table, n_table = ctypes.c_void_p(), ctypes.c_uint32()
+    _check(load().tq_listing_build_table(ptrs, lens, n, top_k, ctypes.byref(table), ctypes.byref(n_table)))
+    try:
+        raw = ctypes.string_at(table.value, n_table.value * 4) if n_table.value else b""
+    finally:
+        load().tq_free_blob(table)
+    return np.frombuffer(raw, dtype=np.uint8).reshape(-1, 4).copy()
+
+
+def tq_listing_compress(values: np.ndarray, table: np.ndarray) -> np.ndarray:
+    """One parameter's byte values -> its uint16 words."""
+    v = np.ascontiguousarray(values, dtype=np.uint8).reshape(-1)
+    t = np.ascontiguousarray(table, dtype=np.uint8).reshape(-1, 4)
+    words, n_words = ctypes.c_void_p(), ctypes.c_uint64()
+    _check(load().tq_listing_compress(v.ctypes.data, v.size, t.ctypes.data, t.shape[0], ctypes.byref(words), ctypes.byref(n_words)))
+    try:
+        raw = ctypes.string_at(words.value, n_words.value * 2) if n_words.value else b""
+    finally:
+        load().tq_free_blob(words)
+    return np.frombuffer(raw, dtype=np.uint16).copy()
+
+
+class Listing:
+    """Owning wrapper around a tq_listing handle (a compressed parameter and its table in device memory)."""
+
+    def __init__(self, words: np.ndarray, table: np.ndarray):
+        w = np.ascontiguousarray(words, dtype=np.uint16).reshape(-1)
+        t = np.ascontiguousarray(table, dtype=np.uint8).reshape(-1, 4)
+        h = ctypes.c_void_p()
+        _check(load().tq_listing_create(w.ctypes.data, w.size, t.ctypes.data, t.shape[0], ctypes.byref(h)))
+        self.handle = h.value
+        info = TqListingInfo()
+        _check(load().tq_listing_get_info(self.handle, ctypes.byref(info)))
+        self.info = info.as_dict()
+
+    def decompress(self, out_ptr: int, stream: int = 0) -> None:
+        _check(load().tq_listing_decompress(self.handle, out_ptr, stream))
+
+    def close(self) -> None:
+        h, self.handle = self.handle, None
+        if h:
+            _check(load().tq_listing_destroy(h))
 
     def __del__(self):
         try:

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtq.so")
-SOURCES = ["tq_encode.cpp", "tq_blob.cpp", "tq_device.hip"]
+SOURCES = ["tq_encode.cpp", "tq_blob.cpp", "tq_device.hip", "tq_listing.hip"]
 HEADERS = ["tq_format.h", os.path.join("..", "..", "include", "tq.h")]
 
 
