@@ -49,6 +49,8 @@ def parse_args():
     ap.add_argument("--cpu-sample-layers", type=int, default=8,
                     help="layers of the sweep the CPU oracle is timed on (8 layers = 56 matrices take about 10 s on one core)")
     ap.add_argument("--no-decompress", action="store_true", help="skip the tq_decompress pass over all matrices")
+    ap.add_argument("--no-listing", action="store_true",
+                    help="skip the leg that expands one matrix stored in the paper's own section 4 stream format")
     ap.add_argument("--layers", type=int, default=0, help="debug: keep only the first N layers (+ lm_head)")
     ap.add_argument("--fuse", choices=["none", "independent", "layer", "sweep"], default="sweep",
                     help="how the products of a step are grouped into launches.  sweep: the step is a list of independent "
@@ -61,6 +63,44 @@ def parse_args():
                     help="also run one plain 1 GiB device copy, so a counter profile of this command holds a kernel of "
                          "known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     return ap.parse_args()
+
+
+def listing_leg(specs, dev, stream):
+    """The paper's section 4 stream format, literally: table of the most frequent windows of 4 values over the first
+    matrix of the workload, the largest of its first matrices compressed with it, expanded on the device."""
+    import torch
+
+    import paper_2509_22951_amd as tq
+    from inputs import make_weights
+    from oracle import oracle as O                        # its quantizer makes the input bytes; nothing of it is timed
+    first = specs[0]
+    big = max(specs[:8], key=lambda s: s.rows * s.cols)
+    q_first = O.quantize_rows(make_weights(first))[0].view(np.uint8).reshape(-1)
+    table = tq.tq_listing_build_table([q_first])
+    values = O.quantize_rows(make_weights(big))[0].view(np.uint8).reshape(-1)
+    words = tq.tq_listing_compress(values, table)
+    h = tq.Listing(words, table)
+    out = torch.empty(values.size, dtype=torch.uint8, device=dev)
+    for _ in range(20):
+        h.decompress(out.data_ptr(), stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 100
+    e0.record()
+    for _ in range(reps):
+        h.decompress(out.data_ptr(), stream)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    ok = bool(torch.equal(out.cpu(), torch.from_numpy(values)))
+    info = h.info
+    h.close()
+    moved = 2 * info["n_words"] + info["n_values"]
+    return {"workload": f"{big.name} ({big.rows}x{big.cols}) in the paper's section 4 format, table from {first.name}",
+            "values": info["n_values"], "words": info["n_words"], "table_entries": info["n_table"],
+            "groups_in_table": round(1 - info["n_escapes"] / max(info["n_tokens"], 1), 4),
+            "bytes_per_value": round(2 * info["n_words"] / max(info["n_values"], 1), 3),
+            "us": round(us, 1), "GBps_read_plus_write": round(moved / us / 1e3, 1), "exact": ok}
 
 
 def main():
@@ -243,6 +283,10 @@ def main():
                       "GBps_written": round(n_weights / d_ms / 1e6, 1)}
         del out
 
+    listing = None
+    if not args.no_listing:
+        listing = listing_leg(specs, dev, stream)
+
     n_launches = sum(-(-len(g) // 128) for g in groups)     # tq_matvec_multi serves up to 128 matrices per kernel launch
     profiled = (args.config == 4 and args.batch == 1 and args.fuse == "sweep" and args.dictionary == "sequence"
                 and not (args.max_entries or args.lmax or args.seg_cols or args.layers))
@@ -285,6 +329,7 @@ def main():
         },
         "other_batches": others,
         "decompress": decompress,
+        "listing_format": listing,
         "setup_s": round(setup_s, 1),
     }
 

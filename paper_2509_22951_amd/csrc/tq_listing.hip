@@ -10,7 +10,7 @@
 // exactly 4 values (the last one of a stream possibly fewer), so token t writes values [4 t, 4 t + 4): all that is
 // missing is the number of tokens before a word.  That count is a property of the stream, not of a call: the host
 // takes it once per block of kBlockWords words while it validates the stream, and the kernel adds a prefix count
-// within the block (wave ballots + one pass over the wave totals in LDS).
+// within the block (one ballot per word position of a thread + one pass over the wave totals in LDS).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -29,7 +29,9 @@ namespace {
 
 constexpr uint32_t kSeq = TQ_LISTING_SEQ;
 constexpr uint32_t kMarker = 0xFFFFu;
-constexpr int kBlockWords = 1024;   // words per workgroup = threads per workgroup
+constexpr int kThreadWords = 8;     // words per thread: one 16-byte load
+constexpr int kListingThreads = 256;
+constexpr int kBlockWords = kListingThreads * kThreadWords;   // words per workgroup
 
 int hip_fail(const char* what, hipError_t e) {
   set_error(std::string(what) + ": " + hipGetErrorString(e));
@@ -38,45 +40,82 @@ int hip_fail(const char* what, hipError_t e) {
 
 inline uint32_t pack4(const uint8_t* v) { return v[0] | (uint32_t)v[1] << 8 | (uint32_t)v[2] << 16 | (uint32_t)v[3] << 24; }
 
-// One thread per word.  words: n_words 16-bit words; table[c - 1]: the 4 values of codeword c, first value in the low
-// byte; block_base[b]: tokens that start before word b * kBlockWords; out: n_values bytes.
-__global__ __launch_bounds__(kBlockWords) void k_listing_decompress(const uint16_t* __restrict__ words, uint64_t n_words,
-                                                                    const uint32_t* __restrict__ table,
-                                                                    const uint32_t* __restrict__ block_base, uint8_t* __restrict__ out,
-                                                                    uint64_t n_values) {
-  __shared__ uint16_t w[kBlockWords + 2 * kSeq];   // the block's words with 4 words on either side
-  __shared__ uint32_t wave_tokens[kBlockWords / 64];
+// Thread t of a workgroup takes the 8 words [8 t, 8 t + 8) of the workgroup's kBlockWords words, plus the 4 words before
+// them (to know which of its words are raw values) and the 4 after them (the raw values of a marker near its end).
+// words: n_words 16-bit words, 16-byte aligned; table[c - 1]: the 4 values of codeword c, first value in the low byte;
+// block_base[b]: tokens that start before word b * kBlockWords; out: n_values bytes.
+__global__ __launch_bounds__(kListingThreads) void k_listing_decompress(const uint16_t* __restrict__ words, uint64_t n_words,
+                                                                        const uint32_t* __restrict__ table,
+                                                                        const uint32_t* __restrict__ block_base, uint8_t* __restrict__ out) {
+  __shared__ uint32_t wave_tokens[kListingThreads / 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const uint64_t first = (uint64_t)blockIdx.x * kBlockWords;
-  for (int k = tid; k < kBlockWords + 2 * (int)kSeq; k += kBlockWords) {
-    const int64_t i = (int64_t)first + k - (int)kSeq;
-    w[k] = i >= 0 && (uint64_t)i < n_words ? words[i] : (uint16_t)0;   // 0 is neither a marker nor a codeword
+  const uint64_t i0 = ((uint64_t)blockIdx.x * kListingThreads + tid) * kThreadWords;   // this thread's first word
+  // w[4 + j] = word i0 + j for j = -4 .. 11; words outside the stream read as 0, which is neither marker nor codeword
+  uint32_t w[kThreadWords + 2 * kSeq];
+  {
+    uint2 before = make_uint2(0u, 0u), after = make_uint2(0u, 0u);
+    uint4 mine = make_uint4(0u, 0u, 0u, 0u);
+    if (i0 >= kSeq && i0 <= n_words) before = *(const uint2*)(words + i0 - kSeq);
+    if (i0 + kThreadWords <= n_words) {
+      mine = *(const uint4*)(words + i0);
+    } else {
+      uint32_t h[kThreadWords];
+      for (int j = 0; j < kThreadWords; ++j) h[j] = i0 + j < n_words ? words[i0 + j] : 0u;
+      mine = make_uint4(h[0] | h[1] << 16, h[2] | h[3] << 16, h[4] | h[5] << 16, h[6] | h[7] << 16);
+    }
+    if (i0 + kThreadWords + kSeq <= n_words) {
+      after = *(const uint2*)(words + i0 + kThreadWords);
+    } else {
+      uint32_t h[kSeq];
+      for (int j = 0; j < (int)kSeq; ++j) h[j] = i0 + kThreadWords + j < n_words ? words[i0 + kThreadWords + j] : 0u;
+      after = make_uint2(h[0] | h[1] << 16, h[2] | h[3] << 16);
+    }
+    const uint32_t packed[8] = {before.x, before.y, mine.x, mine.y, mine.z, mine.w, after.x, after.y};
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      w[2 * k] = packed[k] & 0xFFFFu;
+      w[2 * k + 1] = packed[k] >> 16;
+    }
   }
-  __syncthreads();
-  const uint64_t i = first + tid;
-  const int k = tid + kSeq;
-  const bool covered = w[k - 1] == kMarker || w[k - 2] == kMarker || w[k - 3] == kMarker || w[k - 4] == kMarker;
-  const bool starts = i < n_words && !covered;
-  const uint64_t ballot = __builtin_amdgcn_ballot_w64(starts);
-  if (lane == 0) wave_tokens[wave] = (uint32_t)__builtin_popcountll(ballot);
-  __syncthreads();
-  uint32_t before = (uint32_t)__builtin_popcountll(ballot & ((1ull << lane) - 1));
-  for (int v = 0; v < wave; ++v) before += wave_tokens[v];
-  if (!starts) return;
-  const uint64_t o = ((uint64_t)block_base[blockIdx.x] + before) * kSeq;   // first value of this token
-  uint32_t v4;
-  uint32_t n = kSeq;
-  if (w[k] == kMarker) {
-    v4 = (uint32_t)(w[k + 1] & 0xFF) | (uint32_t)(w[k + 2] & 0xFF) << 8 | (uint32_t)(w[k + 3] & 0xFF) << 16 | (uint32_t)(w[k + 4] & 0xFF) << 24;
-    const uint64_t left = n_words - 1 - i;                                // the last marker of a stream may have fewer values
-    if (left < kSeq) n = (uint32_t)left;
-  } else {
-    v4 = table[w[k] - 1];
+  // which of the thread's words start a token
+  uint32_t starts = 0;
+#pragma unroll
+  for (int j = 0; j < kThreadWords; ++j) {
+    const bool covered = w[kSeq + j - 1] == kMarker || w[kSeq + j - 2] == kMarker || w[kSeq + j - 3] == kMarker || w[kSeq + j - 4] == kMarker;
+    if (i0 + j < n_words && !covered) starts |= 1u << j;
   }
-  if (n == kSeq && ((uintptr_t)out & 3) == 0) {
-    *(uint32_t*)(out + o) = v4;
-  } else {
-    for (uint32_t b = 0; b < n; ++b) out[o + b] = (uint8_t)(v4 >> (8 * b));
+  // tokens that start in the workgroup before this thread's words: threads of lower lanes, then lower wavefronts
+  uint32_t lower = 0, in_wave = 0;
+#pragma unroll
+  for (int j = 0; j < kThreadWords; ++j) {
+    const uint64_t ballot = __builtin_amdgcn_ballot_w64((starts >> j) & 1u);
+    lower += (uint32_t)__builtin_popcountll(ballot & ((1ull << lane) - 1));
+    in_wave += (uint32_t)__builtin_popcountll(ballot);
+  }
+  if (lane == 0) wave_tokens[wave] = in_wave;
+  __syncthreads();
+  for (int v = 0; v < wave; ++v) lower += wave_tokens[v];
+  uint64_t token = (uint64_t)block_base[blockIdx.x] + lower;
+  const bool aligned = ((uintptr_t)out & 3) == 0;
+#pragma unroll
+  for (int j = 0; j < kThreadWords; ++j) {
+    if (!((starts >> j) & 1u)) continue;
+    const uint32_t c = w[kSeq + j];
+    uint32_t v4, n = kSeq;
+    if (c == kMarker) {
+      v4 = (w[kSeq + j + 1] & 0xFF) | (w[kSeq + j + 2] & 0xFF) << 8 | (w[kSeq + j + 3] & 0xFF) << 16 | (w[kSeq + j + 4] & 0xFF) << 24;
+      const uint64_t left = n_words - 1 - (i0 + j);   // the last marker of a stream may have fewer values
+      if (left < kSeq) n = (uint32_t)left;
+    } else {
+      v4 = table[c - 1];
+    }
+    const uint64_t o = token * kSeq;   // first value of this token
+    if (n == kSeq && aligned) {
+      *(uint32_t*)(out + o) = v4;
+    } else {
+      for (uint32_t b = 0; b < n; ++b) out[o + b] = (uint8_t)(v4 >> (8 * b));
+    }
+    ++token;
   }
 }
 
@@ -309,8 +348,8 @@ extern "C" int tq_listing_decompress(tq_listing h, void* out, void* stream) {
     return TQ_E_INVALID_ARG;
   }
   if (h->n_blocks == 0) return TQ_OK;
-  hipLaunchKernelGGL(k_listing_decompress, dim3((unsigned)h->n_blocks), dim3(kBlockWords), 0, (hipStream_t)stream, h->words, h->info.n_words,
-                     h->table, h->block_base, (uint8_t*)out, h->info.n_values);
+  hipLaunchKernelGGL(k_listing_decompress, dim3((unsigned)h->n_blocks), dim3(kListingThreads), 0, (hipStream_t)stream, h->words,
+                     h->info.n_words, h->table, h->block_base, (uint8_t*)out);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail("tq_listing_decompress launch", e);
   return TQ_OK;
