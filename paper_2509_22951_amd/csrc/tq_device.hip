@@ -10,8 +10,10 @@
 //   3. tq_matvec gathers the activation pair (x[col], x[col+1]) from an LDS image of x and issues one
 //      v_dot2_f32_bf16 per code; the per-lane sums of the 4 panels of a row are added at the end of a band of 16
 //      rows, multiplied by the row scale and stored,
-//   4. for batches of 2..16 rows and for tq_decompress the lanes append their run bytes to per-lane strips of an LDS
-//      tile instead; a finished unit is multiplied by bf16 MFMA (batch = N) or copied out row-major.
+//   4. for batches of 2..16 rows and for tq_decompress the lanes append their run bytes to per-lane storage in LDS
+//      instead - a ring of 128 bytes (k_matvec_ring: multiplied by bf16 MFMA, batch = N, while the decode goes on) or
+//      a strip holding the whole segment (k_matvec_mfma: multiplied when the unit is complete; k_decompress: copied
+//      out row-major).
 // The expanded matrix never exists in HBM on the tq_matvec path.
 #include <hip/hip_runtime.h>
 
@@ -459,13 +461,14 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// Product for batches of 2..16 activation rows: decode into an LDS tile, then bf16 MFMA with the batch as N.
+// Product for batches of 2..16 activation rows, whole-strip form: decode a unit into an LDS tile, then bf16 MFMA with
+// the batch as N.  (Large launches of well-behaved matrices take the ring form further down instead.)
 //
 // A lane's segment is (row l & 15, panel l >> 4) of its unit, which is exactly the A-operand layout of
 // v_mfma_f32_16x16x32_bf16: lane l supplies row l % 16 and the 8 k-values of group l / 16.  Taking those 8 values as
 // 8 consecutive columns of the lane's own segment makes every lane read back only what it wrote itself: the tile is a
-// per-lane strip of seg_cols (+8) bytes, a lane appends the bytes of its runs (both bytes of an entry are stored; the
-// second byte of a single-byte entry is overwritten by the next run), and after the unit's last chunk window w of
+// per-lane strip of seg_cols (+8) bytes, a lane appends the bytes of its runs (packed in registers, one aligned 8-byte
+// store per chunk), and after the unit's last chunk window w of
 // the unit is one MFMA: A = bytes [8 w, 8 w + 8) of every strip converted to bf16 (exact), B = the activations of the
 // 4 x 8 columns those bytes stand for, one batch row per lane % 16.  Strips of shorter or empty segments hold stale
 // (finite) values past their end; they meet activations that are zero there because B is loaded with bounds checks.
@@ -654,8 +657,6 @@ __device__ __forceinline__ uint4 mask_x_fragment(uint4 v, uint32_t cols, uint32_
 
 constexpr int kMfmaGroup = 8;   // MFMA steps per group: the activation fragments of the next group load while this one runs
 
-// The MFMA steps of one decoded unit: step w multiplies bytes [8 w, 8 w + 8) of every lane's strip (16 rows x 4 panels
-// x 8 columns, converted to bf16) with the activations of those 32 columns.  n_win and ragged are wave-uniform.
 // The MFMA steps of one decoded unit: step w multiplies bytes [8 w, 8 w + 8) of every lane's strip (16 rows x 4 panels
 // x 8 columns, converted to bf16) with the activations of those 32 columns.  n_win is wave-uniform.
 // Four accumulators so that consecutive MFMAs do not wait for each other; groups of kMfmaGroup steps whose weight
