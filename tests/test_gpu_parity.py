@@ -258,7 +258,8 @@ def test_decompress_multi_is_bit_exact(dev):
 def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows(dev):
     """Config-4 shapes at full size (one 3B layer plus lm_head 128256 x 3072), encoded as bench.py encodes them (one
     dictionary over the sequence, default options) and launched as bench.py launches them (all matrices in one
-    tq_matvec_multi / tq_decompress_multi call), batch 1 and 8.  The oracle computes sampled rows one by one:
+    tq_matvec_multi / tq_decompress_multi call), batch 1, 8 and 16 (dot-product kernel, ring kernel with 10 and with 8
+    wavefronts: the call brings 9,744 bands, enough for the ring kernel).  The oracle computes sampled rows one by one:
     quantization is per row, so the sampled rows of Q and their float64 products need only those rows of W."""
     from inputs import config_matrices
     specs = [s for s in config_matrices(4) if s.name.startswith("L00.") or s.name == "lm_head"]
@@ -286,7 +287,8 @@ def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows
             assert np.array_equal(o[torch.from_numpy(rows).to(dev)].cpu().numpy(), Qs)
         assert int((outs[-1] == 77).sum()) < outs[-1].numel() // 100      # nothing left unwritten (77 is an ordinary value too)
         del outs
-        for batch in (1, 8):
+        assert all(m.info["lane_spread"] <= 113 for m in mats)   # none of them needs the whole-strip kernel
+        for batch in (1, 8, 16):
             xs, ys, xf = [], [], []
             for sp in specs:
                 bits, x = make_activations(sp, batch)
