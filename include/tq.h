@@ -40,6 +40,9 @@ extern "C" {
 
 typedef struct tq_matrix *tq_handle;
 
+#define TQ_DICT_LZW 0
+#define TQ_DICT_FREQUENCY 1
+
 /* Encoder options; zero-initialise and set what you need (0 = default). */
 typedef struct tq_encode_opts {
   uint32_t max_entries; /* dictionary size cap incl. the 256 single bytes; 256..TQ_MAX_ENTRIES_DEVICE;
@@ -54,6 +57,14 @@ typedef struct tq_encode_opts {
                                matrix of the sequence gets byte-identical dictionaries, which the device side stores
                                and stages once. */
   uint64_t dict_from_bytes; /* size of that container */
+  uint32_t dictionary;      /* TQ_DICT_LZW (0, default): LZW growth with freeze, the paper's Background "Compression".
+                               TQ_DICT_FREQUENCY: the dictionary is fixed before the parse - dict_from's if given, else
+                               the 256 single bytes plus the most frequent pairs of neighbouring bytes of this matrix
+                               (counted at every offset inside a segment; most frequent first, equally frequent ones in
+                               order of first appearance: how the paper's section 4 picks its table), as many as
+                               max_entries leaves room for - and the parse is the same greedy longest match.  Same
+                               container, same kernels. */
+  uint32_t reserved;
 } tq_encode_opts;
 
 typedef struct tq_info {

@@ -9,6 +9,7 @@ Everything here is the plain definition (or the paper's algorithm step by step) 
                       granularity is the benchmark configuration's, not the listing's per-tensor min/max).
 * ``serialize``       the fixed byte order in which a matrix is handed to the codec (format rule, no maths).
 * ``lzw_encode``      LZW as described in the paper's Background, "Compression" (C, see tq_oracle.c).
+* ``frequency_dictionary``  entries picked by frequency, as section 4 picks its table (runs of 2; numpy).
 * ``lzw_decode``      table lookup decompression, section 4: reproduces the quantized bytes exactly.
 * ``gemv_f64``        y = diag(s) Q x in float64, the definition the fused kernel must reach.
 * ``build_blob`` / ``parse_blob``  writer and reader of the container format, written from the format
@@ -17,7 +18,7 @@ Everything here is the plain definition (or the paper's algorithm step by step) 
 Pins (tests/test_oracle_*.py): quantizer closed forms and invariances; serialization special cases that
 reduce to numpy slicing; LZW against a published worked example, closed-form all-equal inputs, a
 brute-force longest-match parser on tiny alphabets, round-trip identity and the zeroth-order entropy
-bound; GEMV against numpy float64 matmul and unit-vector probes.  No function here is unpinned.
+bound; the frequency dictionary against hand-counted inputs and against a plain counting loop; GEMV against numpy float64 matmul and unit-vector probes.  No function here is unpinned.
 """
 from __future__ import annotations
 
@@ -272,20 +273,57 @@ class Encoded:
         return self.dictionary.n_entries
 
 
+def frequency_dictionary(S: np.ndarray, seg_len: np.ndarray, max_entries: int = 30719, lmax: int = 2) -> Dictionary:
+    """Dictionary chosen by frequency, the way the paper's section 4 picks its table entries (most frequent sequences
+    first; equally frequent ones in order of first appearance), for runs of 2: the 256 single bytes, then the most
+    frequent pairs of neighbouring bytes, counted at every offset inside a segment and never across two segments, as
+    many as max_entries leaves room for.  lmax 1: the singles alone."""
+    assert lmax in (1, 2)
+    S = np.ascontiguousarray(S, dtype=np.uint8)
+    eb = np.zeros((256, LCAP), np.uint8)
+    eb[:, 0] = np.arange(256)
+    el = np.ones(256, np.uint8)
+    room = max_entries - 256
+    if lmax < 2 or room <= 0 or S.size < 2:
+        return Dictionary(eb, el)
+    inside = np.ones(S.size - 1, bool)                       # pair (i, i + 1) lies inside one segment
+    ends = np.cumsum(np.asarray(seg_len, dtype=np.int64))
+    cut = ends[(ends > 0) & (ends < S.size)]
+    inside[cut - 1] = False
+    keys = (S[:-1].astype(np.uint32) << 8 | S[1:])[inside]
+    if keys.size == 0:
+        return Dictionary(eb, el)
+    uniq, first, count = np.unique(keys, return_index=True, return_counts=True)
+    order = np.lexsort((first, -count.astype(np.int64)))[:room]
+    pairs = np.zeros((order.size, LCAP), np.uint8)
+    pairs[:, 0] = uniq[order] >> 8
+    pairs[:, 1] = uniq[order] & 0xFF
+    return Dictionary(np.concatenate([eb, pairs]), np.concatenate([el, np.full(order.size, 2, np.uint8)]))
+
+
 def encode_quantized(Q: np.ndarray, scales: np.ndarray, max_entries: int = 30719, lmax: int = 2,
-                     seg_cols: int = DEFAULT_SEG_COLS, carry: "Dictionary | None" = None) -> Encoded:
+                     seg_cols: int = DEFAULT_SEG_COLS, carry: "Dictionary | None" = None, dictionary: str = "lzw") -> Encoded:
+    """dictionary "lzw": LZW growth with freeze (the paper's Background).  "frequency": the dictionary is fixed before
+    the parse - the carried one if given, else frequency_dictionary of this matrix - and the parse is the same greedy
+    longest match."""
     rows, cols = Q.shape
     S, seg_len = serialize(Q, seg_cols)
-    codes, snc, d = lzw_encode(S, seg_len, max_entries, lmax, carry)
+    if dictionary == "frequency":
+        fixed = carry if carry is not None else frequency_dictionary(S, seg_len, max_entries, lmax)
+        codes, snc, d = lzw_encode(S, seg_len, fixed.n_entries, lmax, fixed)     # full from the start: nothing is added
+        assert d.n_entries == fixed.n_entries
+    else:
+        assert dictionary == "lzw"
+        codes, snc, d = lzw_encode(S, seg_len, max_entries, lmax, carry)
     stream, uoff = interleave(codes, snc, d.n_entries)
     return Encoded(rows, cols, seg_cols, lmax, max_entries, Q, np.asarray(scales, np.float32), d, stream, uoff,
                    int(codes.size))
 
 
 def encode_matrix(W: np.ndarray, max_entries: int = 30719, lmax: int = 2, seg_cols: int = DEFAULT_SEG_COLS,
-                  carry: "Dictionary | None" = None) -> Encoded:
+                  carry: "Dictionary | None" = None, dictionary: str = "lzw") -> Encoded:
     Q, s = quantize_rows(W)
-    return encode_quantized(Q, s, max_entries, lmax, seg_cols, carry)
+    return encode_quantized(Q, s, max_entries, lmax, seg_cols, carry, dictionary)
 
 
 def dict_slots(d: Dictionary) -> np.ndarray:

@@ -32,7 +32,8 @@ class TqError(RuntimeError):
 
 class TqEncodeOpts(ctypes.Structure):
     _fields_ = [("max_entries", ctypes.c_uint32), ("lmax", ctypes.c_uint32), ("n_threads", ctypes.c_uint32),
-                ("seg_cols", ctypes.c_uint32), ("dict_from", ctypes.c_void_p), ("dict_from_bytes", ctypes.c_uint64)]
+                ("seg_cols", ctypes.c_uint32), ("dict_from", ctypes.c_void_p), ("dict_from_bytes", ctypes.c_uint64),
+                ("dictionary", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 class TqInfo(ctypes.Structure):
@@ -120,9 +121,14 @@ def _check(rc: int):
         raise TqError(rc, tq_last_error_string())
 
 
-def _opts(max_entries: int, lmax: int, n_threads: int, seg_cols: int, dict_from: Optional[bytes]) -> TqEncodeOpts:
+DICTIONARY_KINDS = {"lzw": 0, "frequency": 1}
+
+
+def _opts(max_entries: int, lmax: int, n_threads: int, seg_cols: int, dict_from: Optional[bytes],
+          dictionary: str = "lzw") -> TqEncodeOpts:
     o = TqEncodeOpts()
     o.max_entries, o.lmax, o.n_threads, o.seg_cols = max_entries, lmax, n_threads, seg_cols
+    o.dictionary = DICTIONARY_KINDS[dictionary]
     if dict_from is not None:
         o.dict_from = ctypes.cast(ctypes.c_char_p(dict_from), ctypes.c_void_p)   # the caller's bytes object outlives the call
         o.dict_from_bytes = len(dict_from)
@@ -137,24 +143,24 @@ def _take_blob(ptr: ctypes.c_void_p, n: ctypes.c_size_t) -> bytes:
 
 
 def tq_encode(w: np.ndarray, max_entries: int = 0, lmax: int = 0, n_threads: int = 0, seg_cols: int = 0,
-              dict_from: Optional[bytes] = None) -> bytes:
+              dict_from: Optional[bytes] = None, dictionary: str = "lzw") -> bytes:
     """fp32 [rows, cols] host array -> container bytes.  dict_from: a container made earlier whose dictionary LZW
     continues from (one dictionary over a sequence of matrices)."""
     w = np.ascontiguousarray(w, dtype=np.float32)
     assert w.ndim == 2
     ptr, n = ctypes.c_void_p(), ctypes.c_size_t()
-    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from)
+    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from, dictionary)
     _check(load().tq_encode(w.ctypes.data, w.shape[0], w.shape[1], ctypes.byref(o), ctypes.byref(ptr), ctypes.byref(n)))
     return _take_blob(ptr, n)
 
 
 def tq_encode_quantized(q: np.ndarray, scales: np.ndarray, max_entries: int = 0, lmax: int = 0, n_threads: int = 0,
-                        seg_cols: int = 0, dict_from: Optional[bytes] = None) -> bytes:
+                        seg_cols: int = 0, dict_from: Optional[bytes] = None, dictionary: str = "lzw") -> bytes:
     q = np.ascontiguousarray(q, dtype=np.int8)
     scales = np.ascontiguousarray(scales, dtype=np.float32)
     assert q.ndim == 2 and scales.shape == (q.shape[0],)
     ptr, n = ctypes.c_void_p(), ctypes.c_size_t()
-    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from)
+    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from, dictionary)
     _check(load().tq_encode_quantized(q.ctypes.data, scales.ctypes.data, q.shape[0], q.shape[1], ctypes.byref(o),
                                       ctypes.byref(ptr), ctypes.byref(n)))
     return _take_blob(ptr, n)

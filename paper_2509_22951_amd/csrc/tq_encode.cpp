@@ -62,6 +62,14 @@ class PairDict {
     }
     return true;
   }
+  // A two-byte run chosen from outside (frequency dictionary); false when it exists already or nothing fits.
+  bool add_pair(uint32_t b0, uint32_t b1) {
+    uint32_t& p = pair_[b0 << 8 | b1];
+    if (p != kNone || full() || lmax_ < 2) return false;
+    p = size();
+    slot_.push_back(b0 | b1 << 8 | 16u << 24);
+    return true;
+  }
   uint32_t size() const { return (uint32_t)slot_.size(); }
   bool full() const { return size() >= max_; }
   const std::vector<uint32_t>& slots() const { return slot_; }
@@ -116,6 +124,10 @@ int check_opts(const tq_encode_opts* o, uint32_t* max_entries, uint32_t* lmax, u
   }
   if (o && (o->dict_from != nullptr) != (o->dict_from_bytes != 0)) {
     set_error("tq_encode: dict_from and dict_from_bytes must be given together");
+    return TQ_E_INVALID_ARG;
+  }
+  if (o && o->dictionary != TQ_DICT_LZW && o->dictionary != TQ_DICT_FREQUENCY) {
+    set_error("tq_encode: dictionary must be TQ_DICT_LZW or TQ_DICT_FREQUENCY");
     return TQ_E_INVALID_ARG;
   }
   return TQ_OK;
@@ -177,10 +189,37 @@ int encode_quantized_matrix(const std::vector<uint8_t>& Q, const std::vector<flo
     }
   };
 
+  const bool by_frequency = opts && opts->dictionary == TQ_DICT_FREQUENCY;
+  if (by_frequency && !(opts && opts->dict_from) && lmax >= 2 && max_entries > 256) {
+    // The most frequent pairs of neighbouring bytes, counted at every offset inside a segment, segments in the order
+    // they are parsed in; ties go to the pair seen first.
+    std::vector<uint64_t> count(65536, 0), first(65536, 0);
+    uint64_t seen = 0;
+    for (uint64_t uu = 0; uu < n_units; ++uu) {
+      const uint32_t band = (uint32_t)(uu / h.n_quads), quad = (uint32_t)(uu % h.n_quads);
+      for (uint32_t lane = 0; lane < 64; ++lane) {
+        const uint32_t len = segment_len(h, band, quad, lane);
+        if (len < 2) continue;
+        const uint8_t* seg = Q.data() + (uint64_t)(band * kUnitRows + (lane & 15)) * cols + (uint64_t)(quad * kUnitPanels + (lane >> 4)) * seg_cols;
+        for (uint32_t i = 0; i + 1 < len; ++i) {
+          const uint32_t key = (uint32_t)seg[i] << 8 | seg[i + 1];
+          if (count[key]++ == 0) first[key] = seen;
+          ++seen;
+        }
+      }
+    }
+    std::vector<uint32_t> keys;
+    for (uint32_t k = 0; k < 65536; ++k)
+      if (count[k]) keys.push_back(k);
+    std::sort(keys.begin(), keys.end(), [&](uint32_t a, uint32_t b) { return count[a] != count[b] ? count[a] > count[b] : first[a] < first[b]; });
+    for (uint32_t k : keys)
+      if (!dict.add_pair(k >> 8, k & 0xFF)) break;
+  }
+
   // Phase 1 (sequential): units in order while the dictionary can still grow.
   std::vector<UnitRange> ranges(1 + n_threads);
   uint64_t u = 0;
-  for (; u < n_units && !dict.full(); ++u) parse_unit(u, true, ranges[0]);
+  for (; !by_frequency && u < n_units && !dict.full(); ++u) parse_unit(u, true, ranges[0]);
   ranges[0].u_end = u;
   const uint64_t u_frozen = u;
   const uint32_t n_entries = dict.size();

@@ -362,6 +362,29 @@ def test_matrix_that_starts_a_dictionary_takes_the_careful_ring_mode(dev, ring_f
         m.close()
 
 
+def test_frequency_dictionary_containers_on_the_device(dev, ring_for_small_launches):
+    """Same container, same kernels: a dictionary picked by frequency decodes bit-exactly and multiplies within
+    tolerance (dot-product kernel, ring kernel - such a matrix has no start-up phase of single bytes, its lanes stay
+    close - and whole-strip kernel through misaligned activations)."""
+    spec = small_case(256, 2048, seed=61)
+    W = make_weights(spec)
+    blob = tq.tq_encode(W, dictionary="frequency")
+    lzw = tq.tq_validate_blob(tq.tq_encode(W))
+    info = tq.tq_validate_blob(blob)
+    assert info["lane_spread"] <= RING_SPREAD_LIMIT < lzw["lane_spread"] and info["n_real_codes"] < lzw["n_real_codes"]
+    Qo, so = O.quantize_rows(W)
+    m = tq.Matrix(blob)
+    try:
+        assert np.array_equal(gpu_decompress(m, dev), Qo)
+        for batch in (1, 8, 16):
+            bits, x = make_activations(spec, batch)
+            ref = O.gemv_f64(Qo, so, x)
+            check_outputs(gpu_matvec(m, bits, dev), ref)
+            check_outputs(gpu_matvec(m, bits, dev, misalign=True), ref)
+    finally:
+        m.close()
+
+
 def test_lanes_far_apart_fall_back_to_the_whole_strip_kernel(dev):
     """All-zero rows (every code a pair once the dictionary knows the pair of zeros) next to rows of values the small
     frozen dictionary has no pairs for (every code a single): the lanes of a unit drift far apart, lane_spread exceeds

@@ -184,3 +184,25 @@ def test_validation_reports_the_lane_spread(rows, cols, seg_cols, max_entries):
     blob = tq.tq_encode_quantized(Q, np.ones(32, np.float32), max_entries=300, seg_cols=256)
     spread = tq.tq_validate_blob(blob)["lane_spread"]
     assert spread == _lane_spread_from_the_stream(blob) and spread > 65
+
+
+@pytest.mark.parametrize("shape,max_entries,lmax,seg_cols,dist", [
+    ((64, 512), 30719, 2, 256, "normal"),
+    ((33, 300), 1000, 2, 64, "normal"),
+    ((16, 8), 256, 2, 16, "normal"),
+    ((200, 1024), 4096, 2, 128, "student_t4"),
+    ((48, 256), 300, 1, 256, "normal"),
+])
+def test_frequency_dictionary_container_is_byte_identical_to_the_oracles(shape, max_entries, lmax, seg_cols, dist):
+    W = make_weights(small_case(shape[0], shape[1], seed=8, dist=dist))
+    blob = tq.tq_encode(W, max_entries=max_entries, lmax=lmax, seg_cols=seg_cols, dictionary="frequency")
+    enc = O.encode_matrix(W, max_entries=max_entries, lmax=lmax, seg_cols=seg_cols, dictionary="frequency")
+    assert blob == O.build_blob(enc)
+    tq.tq_validate_blob(blob)
+    assert np.array_equal(O.decode_blob(blob)[0], O.quantize_rows(W)[0])
+    # carried over to the next matrix the dictionary stays as it is, in both kinds of encoder run
+    W2 = make_weights(small_case(shape[0], shape[1], seed=9, dist=dist))
+    blob2 = tq.tq_encode(W2, max_entries=max_entries, lmax=lmax, seg_cols=seg_cols, dictionary="frequency", dict_from=blob)
+    enc2 = O.encode_matrix(W2, max_entries=max_entries, lmax=lmax, seg_cols=seg_cols, dictionary="frequency", carry=enc.dictionary)
+    assert blob2 == O.build_blob(enc2)
+    assert np.array_equal(O.parse_blob(blob2)["slots"], O.parse_blob(blob)["slots"])

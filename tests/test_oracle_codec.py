@@ -4,6 +4,7 @@ import os
 import numpy as np
 import pytest
 
+from inputs import make_weights, small_case
 from oracle import oracle as O
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -207,3 +208,65 @@ def test_information_bound_on_iid_input():
         sym_per_code = S.size / codes.size
         assert sym_per_code < 16.0 / H * 1.02
         assert sym_per_code > 1.5          # and it does find pairs
+
+
+# ---- dictionary picked by frequency (how the paper's section 4 picks its table), runs of 2 ----
+
+def _pairs_of(d):
+    return [tuple(int(x) for x in d.ent_bytes[e, :2]) for e in range(256, d.n_entries)]
+
+
+def test_frequency_dictionary_on_hand_counted_input():
+    # one segment 1 2 1 2 1 2 3 1 2: (1,2) x4, (2,1) x2, (2,3) x1, (3,1) x1
+    S = np.array([1, 2, 1, 2, 1, 2, 3, 1, 2], np.uint8)
+    d = O.frequency_dictionary(S, np.array([9], np.uint32), max_entries=300)
+    assert d.n_entries == 260 and np.all(d.ent_len[:256] == 1) and np.all(d.ent_len[256:] == 2)
+    assert [d.entry(e) for e in (0, 65, 255)] == [b"\x00", b"A", b"\xff"]
+    assert _pairs_of(d) == [(1, 2), (2, 1), (2, 3), (3, 1)]
+    assert _pairs_of(O.frequency_dictionary(S, np.array([9], np.uint32), max_entries=258)) == [(1, 2), (2, 1)]
+    assert O.frequency_dictionary(S, np.array([9], np.uint32), max_entries=256).n_entries == 256
+    assert O.frequency_dictionary(S, np.array([9], np.uint32), max_entries=300, lmax=1).n_entries == 256
+    # with the two best pairs the greedy parse is 12 12 12 3 12 (hand-derived)
+    e = O.encode_quantized(S.view(np.int8).reshape(1, 9), np.ones(1, np.float32), max_entries=258, seg_cols=16, dictionary="frequency")
+    codes = e.stream.reshape(-1, 64, 4)[:, 0, :].reshape(-1)          # lane 0 holds the only segment
+    assert codes[: e.n_real_codes].tolist() == [256, 256, 256, 3, 256]
+
+
+def test_frequency_dictionary_never_counts_across_segments_and_breaks_ties_by_first_appearance():
+    # segments 1 2 1 | 2 1 2: inside them (1,2) (2,1) | (2,1) (1,2); the pair (1,2) across the cut is not counted
+    S = np.array([1, 2, 1, 2, 1, 2], np.uint8)
+    assert _pairs_of(O.frequency_dictionary(S, np.array([3, 3], np.uint32), 300)) == [(1, 2), (2, 1)]
+    # as one segment the same bytes give (1,2) x3, (2,1) x2
+    assert _pairs_of(O.frequency_dictionary(S, np.array([6], np.uint32), 300)) == [(1, 2), (2, 1)]
+    S = np.array([7, 7, 9, 9, 7, 7], np.uint8)
+    assert _pairs_of(O.frequency_dictionary(S, np.array([2, 2, 2], np.uint32), 300)) == [(7, 7), (9, 9)]
+    assert _pairs_of(O.frequency_dictionary(S, np.array([0, 6, 0], np.uint32), 300)) == [(7, 7), (7, 9), (9, 9), (9, 7)]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_frequency_dictionary_against_a_counting_loop(seed):
+    rng = np.random.default_rng(seed)
+    seg_len = rng.integers(0, 9, size=40).astype(np.uint32)
+    S = rng.integers(0, 4, size=int(seg_len.sum()), dtype=np.uint8)
+    count, first, pos, t = {}, {}, 0, 0
+    for n in seg_len:
+        seg = S[pos: pos + n]
+        for a, b in zip(seg[:-1], seg[1:]):
+            k = (int(a), int(b))
+            count[k] = count.get(k, 0) + 1
+            first.setdefault(k, t)
+            t += 1
+        pos += int(n)
+    want = sorted(count, key=lambda k: (-count[k], first[k]))
+    for room in (0, 3, 100):
+        assert _pairs_of(O.frequency_dictionary(S, seg_len, 256 + room)) == want[:room]
+
+
+def test_frequency_dictionary_round_trip_and_gain_over_lzw():
+    W = make_weights(small_case(256, 2048, seed=12))
+    Q, s = O.quantize_rows(W)
+    f = O.encode_quantized(Q, s, dictionary="frequency")
+    l = O.encode_quantized(Q, s, dictionary="lzw")
+    S, seg_len = O.serialize(Q)
+    assert np.array_equal(O.lzw_decode(f.stream, f.uoff, seg_len, f.dictionary, f.pad_code), S)
+    assert f.dictionary.n_entries == 30719 and f.n_real_codes < l.n_real_codes       # the better-chosen pairs cover more
