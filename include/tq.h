@@ -151,6 +151,21 @@ int tq_matvec(tq_handle h, const void *x, void *y, int batch, void *stream);
 int tq_matvec_multi(int n, const tq_handle *hs, const void *const *xs, void *const *ys, int batch, void *stream);
 
 /*
+ * The gated pair of a feed-forward block in one pass (the products of the gate and the up projection read the same x;
+ * their elementwise combination is fused into the kernel that produces them instead of costing two more passes over
+ * their outputs): a container made by tq_encode_gate_up holds the two R x K matrices row-interleaved (row 2r = gate
+ * row r, row 2r + 1 = up row r; each row keeps its own scale), and
+ *   y[b][r] = silu(g) * u,  g = scale[2r] * sum_j Q[2r][j] x[b][j],  u = scale[2r+1] * sum_j Q[2r+1][j] x[b][j],
+ *   silu(g) = g / (1 + exp(-g)) in fp32.
+ * y: device, fp32 [batch][rows / 2].  Works on any handle with an even number of rows; otherwise as tq_matvec /
+ * tq_matvec_multi (batch 1: dot-product kernel; batch 2..16: the whole-strip MFMA kernel).
+ */
+int tq_encode_gate_up(const float *w_gate, const float *w_up, uint32_t rows, uint32_t cols, const tq_encode_opts *opts,
+                      void **blob, size_t *blob_bytes);
+int tq_matvec_gate_up(tq_handle h, const void *x, void *y, int batch, void *stream);
+int tq_matvec_gate_up_multi(int n, const tq_handle *hs, const void *const *xs, void *const *ys, int batch, void *stream);
+
+/*
  * Un-fused form: expand the whole matrix (paper section 4, Listing "Decompressing Model Weights").
  *   out: device, int8 [rows][cols] row-major, fully overwritten, bit-exact quantized weights.
  * Same asynchrony rules as tq_matvec.

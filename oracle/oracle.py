@@ -252,6 +252,23 @@ def gemv_f64(Q: np.ndarray, s: np.ndarray, x: np.ndarray) -> np.ndarray:
     return y
 
 
+def gate_up_f64(Qg: np.ndarray, sg: np.ndarray, Qu: np.ndarray, su: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """The gated pair of a feed-forward block by its definition, in float64: silu(g) * u with g, u the two
+    matrix-vector products and silu(g) = g / (1 + exp(-g))."""
+    g = gemv_f64(Qg, sg, x)
+    u = gemv_f64(Qu, su, x)
+    return g / (1.0 + np.exp(-g)) * u
+
+
+def interleave_rows(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """Rows a[0], b[0], a[1], b[1], ... (the row order of a gate/up container)."""
+    assert a.shape == b.shape
+    out = np.empty((2 * a.shape[0],) + a.shape[1:], dtype=a.dtype)
+    out[0::2] = a
+    out[1::2] = b
+    return out
+
+
 # --------------------------------------------------------------------------- whole-matrix encode + container
 
 @dataclass

@@ -30,4 +30,7 @@ from .binding import (  # noqa: F401
     Listing,
     tq_listing_build_table,
     tq_listing_compress,
+    tq_encode_gate_up,
+    tq_matvec_gate_up,
+    tq_matvec_gate_up_multi,
 )

@@ -19,6 +19,7 @@ _LIB: Optional[ctypes.CDLL] = None
 EXPORTS = [
     "tq_encode", "tq_encode_quantized", "tq_free_blob", "tq_validate_blob", "tq_create_from_encoded", "tq_matvec",
     "tq_matvec_multi", "tq_decompress", "tq_decompress_multi", "tq_get_info", "tq_destroy", "tq_last_error_string",
+    "tq_encode_gate_up", "tq_matvec_gate_up", "tq_matvec_gate_up_multi",
     "tq_listing_build_table", "tq_listing_compress", "tq_listing_create", "tq_listing_decompress", "tq_listing_get_info",
     "tq_listing_destroy",
 ]
@@ -83,6 +84,12 @@ def load() -> ctypes.CDLL:
     lib.tq_create_from_encoded.argtypes = [vp, sz, ctypes.POINTER(vp)]
     lib.tq_matvec.restype = ci
     lib.tq_matvec.argtypes = [vp, vp, vp, ci, vp]
+    lib.tq_encode_gate_up.restype = ci
+    lib.tq_encode_gate_up.argtypes = [vp, vp, u32, u32, ctypes.POINTER(TqEncodeOpts), ctypes.POINTER(vp), ctypes.POINTER(sz)]
+    lib.tq_matvec_gate_up.restype = ci
+    lib.tq_matvec_gate_up.argtypes = [vp, vp, vp, ci, vp]
+    lib.tq_matvec_gate_up_multi.restype = ci
+    lib.tq_matvec_gate_up_multi.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
     lib.tq_matvec_multi.restype = ci
     lib.tq_matvec_multi.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
     lib.tq_decompress.restype = ci
@@ -166,6 +173,19 @@ def tq_encode_quantized(q: np.ndarray, scales: np.ndarray, max_entries: int = 0,
     return _take_blob(ptr, n)
 
 
+def tq_encode_gate_up(w_gate: np.ndarray, w_up: np.ndarray, max_entries: int = 0, lmax: int = 0, n_threads: int = 0,
+                      seg_cols: int = 0, dict_from: Optional[bytes] = None, dictionary: str = "lzw") -> bytes:
+    """Two fp32 [rows, cols] host arrays -> one container of 2 * rows rows, gate and up rows interleaved."""
+    g = np.ascontiguousarray(w_gate, dtype=np.float32)
+    u = np.ascontiguousarray(w_up, dtype=np.float32)
+    assert g.ndim == 2 and g.shape == u.shape
+    ptr, n = ctypes.c_void_p(), ctypes.c_size_t()
+    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from, dictionary)
+    _check(load().tq_encode_gate_up(g.ctypes.data, u.ctypes.data, g.shape[0], g.shape[1], ctypes.byref(o), ctypes.byref(ptr),
+                                    ctypes.byref(n)))
+    return _take_blob(ptr, n)
+
+
 def tq_validate_blob(blob: bytes) -> dict:
     info = TqInfo()
     _check(load().tq_validate_blob(blob, len(blob), ctypes.byref(info)))
@@ -181,6 +201,17 @@ def tq_create_from_encoded(blob: bytes) -> int:
 
 def tq_matvec(handle: int, x_ptr: int, y_ptr: int, batch: int, stream: int = 0) -> None:
     _check(load().tq_matvec(handle, x_ptr, y_ptr, batch, stream))
+
+
+def tq_matvec_gate_up(handle: int, x_ptr: int, y_ptr: int, batch: int, stream: int = 0) -> None:
+    _check(load().tq_matvec_gate_up(handle, x_ptr, y_ptr, batch, stream))
+
+
+def tq_matvec_gate_up_multi(handles, x_ptrs, y_ptrs, batch: int, stream: int = 0) -> None:
+    n = len(handles)
+    assert n == len(x_ptrs) == len(y_ptrs) and n >= 1
+    arr = ctypes.c_void_p * n
+    _check(load().tq_matvec_gate_up_multi(n, arr(*handles), arr(*x_ptrs), arr(*y_ptrs), batch, stream))
 
 
 class MultiCall:

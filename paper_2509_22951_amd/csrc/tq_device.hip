@@ -72,7 +72,7 @@ struct MatvecArgs {
   int n, batch;
   uint32_t x_off, slot_off;   // byte offsets in LDS of the activation image (or of the tiles) and of the partial-sum slots
   uint32_t tile_area;         // bytes of LDS per wavefront in the tile kernels (the same for every matrix of the launch)
-  uint32_t reserved;
+  uint32_t gate_up;           // 1: rows 2r and 2r + 1 are a gate and an up projection; y[b][r] = silu(row 2r) * (row 2r + 1)
   uint32_t cost[kMaxMulti + 1];
   Job j[kMaxMulti];
   DevMat first[kInlineDescriptions];   // descriptions of the first matrices by value: a launch of one matrix (or of a
@@ -277,6 +277,9 @@ __device__ __forceinline__ float sum_over_panels(float v) {
   return v;
 }
 
+// The gated product of a feed-forward block: silu(gate) * up, silu(g) = g / (1 + exp(-g)).
+__device__ __forceinline__ float silu_times(float gate, float up) { return gate / (1.f + __expf(-gate)) * up; }
+
 // Fused decode + dequantize + matrix-vector product for one activation row and up to kMaxMulti matrices.
 //
 // The launch's work is the line of all bands (16 rows each) of all matrices, each band weighted by its number of
@@ -359,7 +362,12 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
           const float v = sum_over_panels(a0 + a1);
           if (complete) {
             const uint32_t row = band * kUnitRows + lane;
-            if (lane < 16 && row < m.rows) global_store(yb + row, v * scale);
+            if (a.gate_up) {   // lanes 2r, 2r + 1 hold the gate and the up row of output r
+              const float t = v * scale, other = __shfl_xor(t, 1);
+              if (lane < 16 && !(lane & 1) && row + 1 < m.rows) global_store(yb + row / 2, silu_times(t, other));
+            } else if (lane < 16 && row < m.rows) {
+              global_store(yb + row, v * scale);
+            }
           } else {
             const int s = 2 * wave + (whole ? 1 : 0);   // slot 2w: band begun by an earlier wavefront; 2w + 1: band left unfinished
             if (lane < 16) slot_val[s * 16 + lane] = v;
@@ -453,7 +461,12 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
           for (int t = s + 1; t < 2 * kWaves; ++t)
             if (slot_band[t] == bnd) sum += slot_val[t * 16 + r16];
           const uint32_t row = (uint32_t)bnd * kUnitRows + r16;
-          if (row < m.rows) global_store(yb + row, sum * global_load(m.scales + row));
+          if (a.gate_up) {   // the two threads of a pair of rows are neighbours and take this branch together
+            const float t = sum * global_load(m.scales + min(row, m.rows - 1)), other = __shfl_xor(t, 1);
+            if (!(r16 & 1) && row + 1 < m.rows) global_store(yb + row / 2, silu_times(t, other));
+          } else if (row < m.rows) {
+            global_store(yb + row, sum * global_load(m.scales + row));
+          }
         }
       }
     }
@@ -1062,10 +1075,20 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
       if (band_ends || run_ends) {
         if (band_ends && (band != first_band || first_whole)) {
           // the whole band lies in this wavefront's run.  Accumulator register v of lane l: row 4 * (l / 16) + v, batch row l % 16
+          if (a.gate_up) {   // registers 0, 1 and 2, 3 of a lane are gate and up row of two outputs
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const uint32_t row = band * kUnitRows + 4 * kg + v;
-            if (bn < a.batch && row < m.rows) global_store(job.y + (size_t)bn * m.rows + row, acc[v] * global_load(m.scales + row));
+            for (int v = 0; v < 4; v += 2) {
+              const uint32_t row = band * kUnitRows + 4 * kg + v;
+              if (bn < a.batch && row + 1 < m.rows)
+                global_store(job.y + (size_t)bn * (m.rows / 2) + row / 2,
+                             silu_times(acc[v] * global_load(m.scales + row), acc[v + 1] * global_load(m.scales + row + 1)));
+            }
+          } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              const uint32_t row = band * kUnitRows + 4 * kg + v;
+              if (bn < a.batch && row < m.rows) global_store(job.y + (size_t)bn * m.rows + row, acc[v] * global_load(m.scales + row));
+            }
           }
         } else if (band == first_band && !first_whole) {   // band begun by an earlier wavefront
           head_acc = acc;
@@ -1116,13 +1139,22 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
       bool first = bnd >= 0;
       for (int t = 0; t < s; ++t) first = first && slot_band[t] != bnd;
       if (first) {
-        float sum = slot_val[s * 256 + e];
-        for (int t = s + 1; t < 2 * n_waves; ++t)
-          if (slot_band[t] == bnd) sum += slot_val[t * 256 + e];
+        auto slot_sum = [&](int el) {
+          float sum = slot_val[s * 256 + el];
+          for (int t = s + 1; t < 2 * n_waves; ++t)
+            if (slot_band[t] == bnd) sum += slot_val[t * 256 + el];
+          return sum;
+        };
         const int v = e >> 6, l = e & 63;
         const uint32_t row = (uint32_t)bnd * kUnitRows + 4 * (l >> 4) + v;
         const int b = l & 15;
-        if (b < a.batch && row < m.rows) global_store(job.y + (size_t)b * m.rows + row, sum * global_load(m.scales + row));
+        if (a.gate_up) {   // element e + 64 is the up row that belongs to this gate row
+          if (!(v & 1) && b < a.batch && row + 1 < m.rows)
+            global_store(job.y + (size_t)b * (m.rows / 2) + row / 2,
+                         silu_times(slot_sum(e) * global_load(m.scales + row), slot_sum(e + 64) * global_load(m.scales + row + 1)));
+        } else if (b < a.batch && row < m.rows) {
+          global_store(job.y + (size_t)b * m.rows + row, slot_sum(e) * global_load(m.scales + row));
+        }
       }
     }
   }
@@ -1416,11 +1448,13 @@ enum class Op { kMatvec, kDecompress };
 // One kernel launch for hs[0..n), n <= kMaxMulti, all on one device, total cost below 2^32.
 // kMatvec: xs/ys are the activations and outputs; kDecompress: ys are the int8 output matrices, xs is not used.
 // ring: the batched product with a ring per lane (every matrix of the call has passed ring_eligible).
-int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream, bool ring = false) {
+int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream, bool ring = false,
+           bool gate_up = false) {
   MatvecArgs a;
   a.n = n;
   a.batch = batch;
-  a.tile_area = a.reserved = 0;
+  a.tile_area = 0;
+  a.gate_up = gate_up ? 1u : 0u;
   uint32_t dict_words_max = 0, x_dwords_max = 0, seg_max = 0;
   uint64_t cost = 0, bands = 0, band_cost_max = 1;
   bool x_fast = true;
@@ -1510,8 +1544,9 @@ bool ring_eligible(const tq_matrix* t, const void* x) {
 }
 
 // As few launches as the kernel-argument size and the 32-bit cost line allow.
-int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream, bool ring = false) {
-  if (op == Op::kMatvec && batch > 1 && !ring) {
+int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream, bool ring = false,
+               bool gate_up = false) {
+  if (op == Op::kMatvec && batch > 1 && !ring && !gate_up) {   // (the ring kernel adds partial sums to y: no place for silu)
     // The matrices that can take the ring kernel go there, the others to the whole-strip kernel; the products are
     // independent, so regrouping them changes nothing but the launches.
     // The ring kernel gives whole bands to wavefronts, a quad at a time: it needs many bands per workgroup to keep its
@@ -1561,7 +1596,7 @@ int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* c
       cost += c;
       ++k;
     }
-    if (int rc = launch(op, k, hs + i, xs ? xs + i : nullptr, ys + i, batch, stream, ring)) return rc;
+    if (int rc = launch(op, k, hs + i, xs ? xs + i : nullptr, ys + i, batch, stream, ring, gate_up)) return rc;
     i += k;
   }
   return TQ_OK;
@@ -1608,6 +1643,28 @@ extern "C" int tq_matvec_multi(int n, const tq_handle* hs, const void* const* xs
   }
   if (int rc = check_call("tq_matvec_multi", n, hs, xs, ys, batch)) return rc;
   return launch_all(Op::kMatvec, n, hs, xs, ys, batch, (hipStream_t)stream);
+}
+
+extern "C" int tq_matvec_gate_up_multi(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {
+  if (n < 1 || !hs || !xs || !ys) {
+    set_error("tq_matvec_gate_up_multi: null argument or n < 1");
+    return TQ_E_INVALID_ARG;
+  }
+  if (int rc = check_call("tq_matvec_gate_up_multi", n, hs, xs, ys, batch)) return rc;
+  for (int i = 0; i < n; ++i)
+    if (hs[i]->m.rows % 2) {
+      set_error("tq_matvec_gate_up_multi: the matrix at index " + std::to_string(i) + " has an odd number of rows");
+      return TQ_E_INVALID_ARG;
+    }
+  return launch_all(Op::kMatvec, n, hs, xs, ys, batch, (hipStream_t)stream, false, true);
+}
+
+extern "C" int tq_matvec_gate_up(tq_handle h, const void* x, void* y, int batch, void* stream) {
+  if (!h || !x || !y) {
+    set_error("tq_matvec_gate_up: null argument");
+    return TQ_E_INVALID_ARG;
+  }
+  return tq_matvec_gate_up_multi(1, &h, &x, &y, batch, stream);
 }
 
 extern "C" int tq_decompress(tq_handle h, void* out, void* stream) {

@@ -369,4 +369,23 @@ extern "C" int tq_encode_quantized(const int8_t* q, const float* scales_in, uint
   }
 }
 
+extern "C" int tq_encode_gate_up(const float* w_gate, const float* w_up, uint32_t rows, uint32_t cols, const tq_encode_opts* opts,
+                                 void** blob, size_t* blob_bytes) {
+  if (!w_gate || !w_up || !blob || !blob_bytes || rows == 0 || cols == 0 || rows > 0x7FFFFFFFu) {
+    set_error("tq_encode_gate_up: null pointer or empty shape");
+    return TQ_E_INVALID_ARG;
+  }
+  try {
+    std::vector<float> w((size_t)2 * rows * cols);   // row 2r = gate row r, row 2r + 1 = up row r
+    for (uint32_t r = 0; r < rows; ++r) {
+      std::memcpy(w.data() + (size_t)(2 * r) * cols, w_gate + (size_t)r * cols, (size_t)cols * 4);
+      std::memcpy(w.data() + (size_t)(2 * r + 1) * cols, w_up + (size_t)r * cols, (size_t)cols * 4);
+    }
+    return tq_encode(w.data(), 2 * rows, cols, opts, blob, blob_bytes);
+  } catch (const std::bad_alloc&) {
+    set_error("tq_encode_gate_up: out of host memory");
+    return TQ_E_OOM;
+  }
+}
+
 extern "C" void tq_free_blob(void* blob) { std::free(blob); }

@@ -362,6 +362,60 @@ def test_matrix_that_starts_a_dictionary_takes_the_careful_ring_mode(dev, ring_f
         m.close()
 
 
+def _gpu_gate_up(m, bits, dev, rows):
+    batch = bits.shape[0]
+    x = torch.from_numpy(bits.view(np.int16).reshape(-1).copy()).to(dev)
+    y = torch.full((batch, rows), float("nan"), dtype=torch.float32, device=dev)
+    tq.tq_matvec_gate_up(m.handle, x.data_ptr(), y.data_ptr(), batch, _stream())
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+@pytest.mark.parametrize("rows,cols,seg_cols", [(8, 64, 16), (100, 768, 64), (1027, 2048, 256), (520, 1000, 128)])
+def test_gate_up_product_with_fused_silu(dev, rows, cols, seg_cols):
+    """silu(W_gate x) * (W_up x) from one container of interleaved rows, against the float64 definition: batch 1
+    (dot-product kernel) and batched (whole-strip MFMA kernel), bands that end in the middle of a pair's band included."""
+    sg, su = small_case(rows, cols, seed=70), small_case(rows, cols, seed=71)
+    Wg, Wu = make_weights(sg), make_weights(su)
+    Qg, scg = O.quantize_rows(Wg)
+    Qu, scu = O.quantize_rows(Wu)
+    m = tq.Matrix(tq.tq_encode_gate_up(Wg, Wu, seg_cols=seg_cols))
+    try:
+        assert m.info["rows"] == 2 * rows
+        assert np.array_equal(gpu_decompress(m, dev), O.interleave_rows(Qg, Qu))
+        for batch in (1, 3, 16):
+            bits, x = make_activations(sg, batch)
+            got = _gpu_gate_up(m, bits, dev, rows)
+            check_outputs(got, O.gate_up_f64(Qg, scg, Qu, scu, x))
+            assert np.array_equal(got, _gpu_gate_up(m, bits, dev, rows))
+    finally:
+        m.close()
+
+
+def test_gate_up_multi_and_argument_errors(dev):
+    pairs = [(64, 512, 64), (200, 768, 192), (48, 2048, 256)]
+    mats, refs, xs, ys = [], [], [], []
+    batch = 4
+    for k, (r, c, seg) in enumerate(pairs):
+        sg, su = small_case(r, c, seed=80 + 2 * k), small_case(r, c, seed=81 + 2 * k)
+        Wg, Wu = make_weights(sg), make_weights(su)
+        mats.append(tq.Matrix(tq.tq_encode_gate_up(Wg, Wu, seg_cols=seg, max_entries=2000)))
+        bits, x = make_activations(sg, batch)
+        xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
+        ys.append(torch.full((batch, r), float("nan"), dtype=torch.float32, device=dev))
+        refs.append(O.gate_up_f64(*O.quantize_rows(Wg), *O.quantize_rows(Wu), x))
+    tq.tq_matvec_gate_up_multi([m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch, _stream())
+    torch.cuda.synchronize()
+    for y, ref in zip(ys, refs):
+        check_outputs(y.cpu().numpy(), ref)
+    odd = tq.Matrix(tq.tq_encode(make_weights(small_case(17, 64, seed=90)), seg_cols=16))
+    with pytest.raises(tq.TqError) as e:
+        tq.tq_matvec_gate_up(odd.handle, xs[0].data_ptr(), ys[0].data_ptr(), 1, _stream())
+    assert e.value.code == -1
+    for m in mats + [odd]:
+        m.close()
+
+
 def test_frequency_dictionary_containers_on_the_device(dev, ring_for_small_launches):
     """Same container, same kernels: a dictionary picked by frequency decodes bit-exactly and multiplies within
     tolerance (dot-product kernel, ring kernel - such a matrix has no start-up phase of single bytes, its lanes stay

@@ -206,3 +206,11 @@ def test_frequency_dictionary_container_is_byte_identical_to_the_oracles(shape, 
     enc2 = O.encode_matrix(W2, max_entries=max_entries, lmax=lmax, seg_cols=seg_cols, dictionary="frequency", carry=enc.dictionary)
     assert blob2 == O.build_blob(enc2)
     assert np.array_equal(O.parse_blob(blob2)["slots"], O.parse_blob(blob)["slots"])
+
+
+def test_gate_up_container_is_the_row_interleaved_matrix():
+    Wg = make_weights(small_case(24, 300, seed=41))
+    Wu = make_weights(small_case(24, 300, seed=42))
+    blob = tq.tq_encode_gate_up(Wg, Wu, max_entries=1000, seg_cols=64)
+    assert blob == O.build_blob(O.encode_matrix(O.interleave_rows(Wg, Wu), max_entries=1000, seg_cols=64))
+    assert tq.tq_validate_blob(blob)["rows"] == 48

@@ -103,3 +103,21 @@ def test_measured_ratio_config1_like():
     p = np.bincount(enc.Q.view(np.uint8).reshape(-1), minlength=256) / enc.Q.size
     H = -(p[p > 0] * np.log2(p[p > 0])).sum()
     assert 1.5 < weights_per_code < 16.0 / H * 1.02
+
+
+def test_gate_up_definition_on_textbook_values():
+    """silu(1) = 0.7310585786300049, silu(2) = 1.7615941559557649, silu(-2) = -0.2384058440442351, silu(0) = 0."""
+    Qg = np.array([[1, 0], [2, 0], [-2, 0], [0, 5]], np.int8)
+    Qu = np.array([[3, 0], [3, 0], [3, 0], [3, 0]], np.int8)
+    ones = np.ones(4, np.float32)
+    x = np.array([[1.0, 0.0]], np.float32)
+    y = O.gate_up_f64(Qg, ones, Qu, ones, x)
+    assert np.allclose(y[0], [3 * 0.7310585786300049, 3 * 1.7615941559557649, 3 * -0.2384058440442351, 0.0], rtol=0, atol=1e-15)
+    # scales enter each product separately: halving the gate scale halves g, not y
+    y2 = O.gate_up_f64(Qg, np.float32(0.5) * ones, Qu, np.float32(2) * ones, x)
+    assert np.allclose(y2[0, :2], [6 * 0.5 / (1 + np.exp(-0.5)), 6 * 0.7310585786300049], rtol=0, atol=1e-15)
+    # large gate: silu(g) -> g; large negative gate: -> 0
+    big = O.gate_up_f64(np.array([[127], [-127]], np.int8), np.ones(2, np.float32), np.array([[1], [1]], np.int8), np.ones(2, np.float32),
+                        np.array([[1.0]], np.float32))
+    assert abs(big[0, 0] - 127.0) < 1e-12 and abs(big[0, 1]) < 1e-12
+    assert O.interleave_rows(np.array([[1], [2]]), np.array([[7], [8]])).ravel().tolist() == [1, 7, 2, 8]
