@@ -53,6 +53,8 @@ def parse_args():
     ap.add_argument("--cpu-sample-layers", type=int, default=8,
                     help="layers of the sweep the CPU oracle is timed on (8 layers = 56 matrices take about 10 s on one core)")
     ap.add_argument("--no-decompress", action="store_true", help="skip the tq_decompress pass over all matrices")
+    ap.add_argument("--no-gate-up", action="store_true",
+                    help="skip the leg that runs the gate/up pairs of the workload as fused silu(gate) * up products")
     ap.add_argument("--no-listing", action="store_true",
                     help="skip the leg that expands one matrix stored in the paper's own section 4 stream format")
     ap.add_argument("--layers", type=int, default=0, help="debug: keep only the first N layers (+ lm_head)")
@@ -67,6 +69,52 @@ def parse_args():
                     help="also run one plain 1 GiB device copy, so a counter profile of this command holds a kernel of "
                          "known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     return ap.parse_args()
+
+
+def gate_up_leg(specs, mats, prev, opts, args, dev, stream):
+    """The gate/up pairs of the workload (up to 8 layers of them) as fused products: one container of interleaved rows
+    per pair, silu(gate) * up in the kernel's epilogue, against the same pairs as two separate products each."""
+    import torch
+
+    import paper_2509_22951_amd as tq
+    from inputs import make_activations, make_weights
+    pairs = [(i, i + 1) for i in range(len(specs) - 1)
+             if specs[i].name.endswith("gate_proj") and specs[i + 1].name.endswith("up_proj")][:8]
+    if not pairs:
+        return None
+    batch = args.batch
+    fused = [tq.Matrix(tq.tq_encode_gate_up(make_weights(specs[g]), make_weights(specs[u]), n_threads=args.threads,
+                                            dict_from=prev, **opts)) for g, u in pairs]
+    xs = [torch.from_numpy(make_activations(specs[g], batch)[0].view(np.int16).copy()).to(dev) for g, _ in pairs]
+    ys = [torch.empty((batch, specs[g].rows), dtype=torch.float32, device=dev) for g, _ in pairs]
+    y2 = [torch.empty((batch, specs[g].rows), dtype=torch.float32, device=dev) for g, _ in pairs]
+    hs, xp, yp = [m.handle for m in fused], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys]
+    sep = tq.MultiCall([mats[i].handle for p in pairs for i in p], [x.data_ptr() for x in xs for _ in (0, 1)],
+                       [y.data_ptr() for pair in zip(ys, y2) for y in pair], batch)
+
+    def timed(f, reps=100):
+        for _ in range(100):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    # the encoding above left the GPU idle: both forms are timed twice, alternating, and the better time counts
+    t_fused = t_sep = float("inf")
+    for _ in range(2):
+        t_sep = min(t_sep, timed(lambda: sep.launch(stream)))
+        t_fused = min(t_fused, timed(lambda: tq.tq_matvec_gate_up_multi(hs, xp, yp, batch, stream)))
+    nbytes = sum(m.info["compressed_bytes"] - m.info["dict_bytes"] for m in fused)
+    for m in fused:
+        m.close()
+    return {"pairs": len(pairs), "batch": batch, "weights": sum(2 * specs[g].rows * specs[g].cols for g, _ in pairs),
+            "fused_ms": round(t_fused, 4), "two_products_ms": round(t_sep, 4),
+            "fused_GBps": round(nbytes / t_fused / 1e6, 1)}
 
 
 def listing_leg(specs, dev, stream):
@@ -290,6 +338,9 @@ def main():
     listing = None
     if not args.no_listing:
         listing = listing_leg(specs, dev, stream)
+    gate_up = None
+    if not args.no_gate_up:
+        gate_up = gate_up_leg(specs, mats, prev if args.dictionary == "sequence" else None, opts, args, dev, stream)
 
     n_launches = sum(-(-len(g) // 128) for g in groups)     # tq_matvec_multi serves up to 128 matrices per kernel launch
     profiled = (args.config == 4 and args.batch == 1 and args.fuse == "sweep" and args.dictionary == "sequence"
@@ -333,6 +384,7 @@ def main():
         },
         "other_batches": others,
         "decompress": decompress,
+        "gate_up_fused": gate_up,
         "listing_format": listing,
         "setup_s": round(setup_s, 1),
     }
