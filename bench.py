@@ -49,6 +49,8 @@ def parse_args():
                     help="lzw: LZW growth with freeze (the paper's Background, the headline configuration); frequency: the "
                          "first matrix of a sequence (every matrix with --dictionary matrix) fixes the dictionary as its "
                          "most frequent byte pairs, the way the paper's section 4 picks table entries")
+    ap.add_argument("--bits", type=int, default=8, choices=range(2, 9),
+                    help="quantization width (paper section 3 tried 8, 6, 4, 2 and ternary); the headline is 8")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-layers", type=int, default=8,
                     help="layers of the sweep the CPU oracle is timed on (8 layers = 56 matrices take about 10 s on one core)")
@@ -182,7 +184,8 @@ def main():
     sample_blobs = {}
     workers = max(1, min(args.threads, 8))
     inner = max(1, args.threads // workers)
-    opts = dict(max_entries=args.max_entries, lmax=args.lmax, seg_cols=args.seg_cols, dictionary=args.dictionary_kind)
+    opts = dict(max_entries=args.max_entries, lmax=args.lmax, seg_cols=args.seg_cols, dictionary=args.dictionary_kind,
+                bits=0 if args.bits == 8 else args.bits)
     # One LZW dictionary over the sequence: the matrices are encoded one after the other, each starting from the
     # dictionary the previous one ended with, until the dictionary is full (Gaussian weights fill it inside the first
     # matrix) or the first layer is through; from then on it is frozen at the size it has reached, so the remaining
@@ -344,7 +347,8 @@ def main():
 
     n_launches = sum(-(-len(g) // 128) for g in groups)     # tq_matvec_multi serves up to 128 matrices per kernel launch
     profiled = (args.config == 4 and args.batch == 1 and args.fuse == "sweep" and args.dictionary == "sequence"
-                and args.dictionary_kind == "lzw" and not (args.max_entries or args.lmax or args.seg_cols or args.layers))
+                and args.dictionary_kind == "lzw" and args.bits == 8
+                and not (args.max_entries or args.lmax or args.seg_cols or args.layers))
     gbps = comp_bytes / wall_ms / 1e6
     ach = comp_bytes / ev_ms / 1e6
     result = {
@@ -368,7 +372,7 @@ def main():
             "bytes_per_weight": round(comp_bytes / n_weights, 4), "weights_per_code": round(n_weights / n_codes, 4),
             "weights_per_real_code": round(n_weights / sum(i["n_real_codes"] for i in infos), 4),
             "dictionary_entries": infos[-1]["n_entries"], "lmax": infos[0]["lmax"], "seg_cols": infos[0]["seg_cols"],
-            "dictionary": args.dictionary, "dictionary_kind": args.dictionary_kind, "fuse": args.fuse, "kernel_launches_per_step": n_launches,
+            "dictionary": args.dictionary, "dictionary_kind": args.dictionary_kind, "bits": args.bits, "fuse": args.fuse, "kernel_launches_per_step": n_launches,
             "hip_graph": bool(args.graph),
         },
         "roofline": {

@@ -42,6 +42,8 @@ typedef struct tq_matrix *tq_handle;
 
 #define TQ_DICT_LZW 0
 #define TQ_DICT_FREQUENCY 1
+#define TQ_PACK_NONE 0u
+#define TQ_PACK_NIBBLES 1u
 
 /* Encoder options; zero-initialise and set what you need (0 = default). */
 typedef struct tq_encode_opts {
@@ -50,7 +52,7 @@ typedef struct tq_encode_opts {
   uint32_t lmax;        /* longest run a dictionary entry may hold, 1..TQ_MAX_LMAX; 0 = TQ_DEFAULT_LMAX */
   uint32_t n_threads;   /* host threads for the frozen-dictionary part of the parse; 0 = all cores (max 16) */
   uint32_t seg_cols;    /* columns per independently decodable segment (the tile width of the per-tile stream offsets):
-                           multiple of 16 in 16..1024; 0 = TQ_DEFAULT_SEG_COLS */
+                           multiple of 16 in 16..1024; 0 = TQ_DEFAULT_SEG_COLS (half of it with TQ_PACK_NIBBLES) */
   const void *dict_from;    /* NULL, or a container made earlier: its dictionary is taken over and LZW goes on from
                                there (one dictionary over a sequence of matrices, as the table of paper section 4 is
                                built over all parameters of the model).  Once the dictionary is full every later
@@ -64,12 +66,22 @@ typedef struct tq_encode_opts {
                                order of first appearance: how the paper's section 4 picks its table), as many as
                                max_entries leaves room for - and the parse is the same greedy longest match.  Same
                                container, same kernels. */
+  uint32_t bits;            /* tq_encode only: quantization width b, 2..8; 0 = 8.  Levels -qmax..qmax with
+                               qmax = 2^(b-1) - 1 (8: 127, 6: 31, 4: 7, 2: 1, the ternary case): the widths the paper's
+                               section 3 tried.  The values stay one per byte, so container and kernels are the same;
+                               with fewer distinct bytes more of the pairs get a dictionary entry. */
+  uint32_t packing;         /* TQ_PACK_NONE (0, default): one value per byte.  TQ_PACK_NIBBLES (widths of at most 4 bits;
+                               tq_encode: bits 2..4, tq_encode_quantized: values in [-8, 7]; an even number of columns):
+                               two values share a byte - column 2j in bits 0..3, column 2j + 1 in bits 4..7, 4-bit two's
+                               complement - and that byte matrix, half as wide, is what the dictionary codes; seg_cols
+                               then counts bytes.  A code stands for up to four weights.  The kernels expand the
+                               nibbles where they dequantize; x, y and the output of tq_decompress keep their shapes. */
   uint32_t reserved;
 } tq_encode_opts;
 
 typedef struct tq_info {
   uint32_t rows, cols;         /* logical shape R x K, y = W x */
-  uint32_t seg_cols, n_panels; /* columns per segment; segments per row */
+  uint32_t seg_cols, n_panels; /* stored bytes per segment (= columns, or two columns each with TQ_PACK_NIBBLES); segments per row */
   uint32_t n_entries, lmax;
   uint64_t n_units, n_codes;   /* units of 16 rows x 4 segments; 16-bit codes stored, incl. padding codes */
   uint64_t n_real_codes;       /* codes of the LZW parse itself (n_codes minus padding) */
@@ -78,7 +90,7 @@ typedef struct tq_info {
   uint32_t lane_spread;      /* the 64 segments of a unit are decoded in step, 4 codes of each at a time: the largest
                                 difference, in columns, between two of them that are both still incomplete.  The batched
                                 product keeps only a window of every segment in LDS when this stays small (see tq_matvec). */
-  uint32_t reserved;
+  uint32_t packing;          /* TQ_PACK_NONE or TQ_PACK_NIBBLES (see tq_encode_opts) */
 } tq_info;
 
 /*

@@ -78,17 +78,22 @@ def _ptr(a: np.ndarray):
 
 # --------------------------------------------------------------------------- quantizer
 
-def quantize_rows(W: np.ndarray):
-    """Per-row symmetric absmax int8.  All arithmetic in IEEE fp32, in this order:
-    amax = max_j |W[r,j]|;  s[r] = amax / 127;  Q[r,j] = clamp(rne(W[r,j] / s[r]), -127, 127).
-    A row of zeros gets s = 0 and Q = 0.  Dequantized weight = s[r] * Q[r,j].
+def quantize_rows(W: np.ndarray, bits: int = 8):
+    """Per-row symmetric absmax quantization to `bits` bits (paper section 3: a fixed range of discrete levels set by
+    the number of bits; 2..8).  qmax = 2^(bits-1) - 1 (127 at 8 bits, 1 at 2 bits: ternary).  All arithmetic in IEEE
+    fp32, in this order:
+    amax = max_j |W[r,j]|;  s[r] = amax / qmax;  Q[r,j] = clamp(rne(W[r,j] / s[r]), -qmax, qmax).
+    A row of zeros gets s = 0 and Q = 0.  Dequantized weight = s[r] * Q[r,j].  Q is kept one value per int8.
     """
+    if not 2 <= bits <= 8:
+        raise ValueError("bits must be in [2, 8]")
+    qmax = np.float32((1 << (bits - 1)) - 1)
     W = np.ascontiguousarray(W, dtype=np.float32)
     amax = np.max(np.abs(W), axis=1).astype(np.float32)
-    s = (amax / np.float32(127.0)).astype(np.float32)
+    s = (amax / qmax).astype(np.float32)
     safe = np.where(s > 0, s, np.float32(1.0)).astype(np.float32)
     t = (W / safe[:, None]).astype(np.float32)
-    q = np.clip(np.rint(t), -127.0, 127.0)
+    q = np.clip(np.rint(t), -qmax, qmax)
     q = np.where(s[:, None] > 0, q, 0.0)
     return q.astype(np.int8), s
 
@@ -284,6 +289,7 @@ class Encoded:
     stream: np.ndarray      # uint16, interleaved and padded
     uoff: np.ndarray        # uint32 [n_units + 1], in chunks
     n_real_codes: int
+    packing: int = 0        # 1: Q holds two 4-bit values per byte (pack_nibbles), the weight matrix is rows x 2 cols
 
     @property
     def pad_code(self) -> int:
@@ -318,6 +324,26 @@ def frequency_dictionary(S: np.ndarray, seg_len: np.ndarray, max_entries: int = 
     return Dictionary(np.concatenate([eb, pairs]), np.concatenate([el, np.full(order.size, 2, np.uint8)]))
 
 
+def pack_nibbles(Q: np.ndarray) -> np.ndarray:
+    """Two 4-bit values per byte: byte j of a row = (Q[r, 2j] mod 16) + 16 * (Q[r, 2j+1] mod 16), the values in 4-bit two's
+    complement (-8..7).  Returned as int8 [rows, cols / 2]: the byte matrix that is then coded like any other."""
+    Q = np.asarray(Q, dtype=np.int64)
+    if Q.shape[1] % 2 or Q.min(initial=0) < -8 or Q.max(initial=0) > 7:
+        raise ValueError("pack_nibbles: an even number of columns of values in [-8, 7]")
+    lo, hi = Q[:, 0::2] % 16, Q[:, 1::2] % 16
+    return (lo + 16 * hi).astype(np.uint8).view(np.int8)
+
+
+def unpack_nibbles(P: np.ndarray) -> np.ndarray:
+    """Inverse of pack_nibbles: int8 [rows, 2 * cols] from the byte matrix."""
+    b = np.asarray(P).view(np.uint8).astype(np.int64)
+    lo, hi = b % 16, b // 16
+    Q = np.empty((b.shape[0], 2 * b.shape[1]), np.int64)
+    Q[:, 0::2] = np.where(lo >= 8, lo - 16, lo)
+    Q[:, 1::2] = np.where(hi >= 8, hi - 16, hi)
+    return Q.astype(np.int8)
+
+
 def encode_quantized(Q: np.ndarray, scales: np.ndarray, max_entries: int = 30719, lmax: int = 2,
                      seg_cols: int = DEFAULT_SEG_COLS, carry: "Dictionary | None" = None, dictionary: str = "lzw") -> Encoded:
     """dictionary "lzw": LZW growth with freeze (the paper's Background).  "frequency": the dictionary is fixed before
@@ -337,10 +363,20 @@ def encode_quantized(Q: np.ndarray, scales: np.ndarray, max_entries: int = 30719
                    int(codes.size))
 
 
-def encode_matrix(W: np.ndarray, max_entries: int = 30719, lmax: int = 2, seg_cols: int = DEFAULT_SEG_COLS,
-                  carry: "Dictionary | None" = None, dictionary: str = "lzw") -> Encoded:
-    Q, s = quantize_rows(W)
-    return encode_quantized(Q, s, max_entries, lmax, seg_cols, carry, dictionary)
+def encode_matrix(W: np.ndarray, max_entries: int = 30719, lmax: int = 2, seg_cols: "int | None" = None,
+                  carry: "Dictionary | None" = None, dictionary: str = "lzw", bits: int = 8, pack: bool = False) -> Encoded:
+    """pack (widths of at most 4 bits): two values share a byte (pack_nibbles) and the byte matrix, half as wide, is what
+    gets coded; seg_cols then counts bytes.  seg_cols None: 256, or 128 bytes (256 weights again) when packing."""
+    if seg_cols is None:
+        seg_cols = DEFAULT_SEG_COLS // 2 if pack else DEFAULT_SEG_COLS
+    Q, s = quantize_rows(W, bits)
+    if not pack:
+        return encode_quantized(Q, s, max_entries, lmax, seg_cols, carry, dictionary)
+    if bits > 4:
+        raise ValueError("packing takes widths of at most 4 bits")
+    e = encode_quantized(pack_nibbles(Q), s, max_entries, lmax, seg_cols, carry, dictionary)
+    e.packing = 1
+    return e
 
 
 def dict_slots(d: Dictionary) -> np.ndarray:
@@ -357,7 +393,7 @@ def _align(n: int, a: int = SECTION_ALIGN) -> int:
 
 
 # magic, version, header_bytes | rows, cols | seg_cols, unit_rows, unit_panels, chunk_codes | n_bands, n_panels,
-# n_quads | n_entries, lmax, max_entries, pad_code, reserved | n_units, n_chunks, n_real_codes |
+# n_quads | n_entries, lmax, max_entries, pad_code, packing | n_units, n_chunks, n_real_codes |
 # (offset, size) of dictionary, unit offsets, codes, scales | total
 _HDR = struct.Struct("<8sII" "II" "IIII" "III" "IIIII" "QQQ" "QQ" "QQ" "QQ" "QQ" "Q")
 
@@ -378,7 +414,7 @@ def build_blob(e: Encoded) -> bytes:
         pos = _align(pos + len(b))
     total = pos
     hdr = _HDR.pack(MAGIC, 2, HEADER_BYTES, e.rows, e.cols, e.seg_cols, UNIT_ROWS, UNIT_PANELS, CHUNK_CODES,
-                    n_bands, n_panels, n_quads, e.dictionary.n_entries, e.lmax, e.max_entries, e.pad_code, 0,
+                    n_bands, n_panels, n_quads, e.dictionary.n_entries, e.lmax, e.max_entries, e.pad_code, e.packing,
                     n_units, n_chunks, e.n_real_codes,
                     offs[0], len(sec[0]), offs[1], len(sec[1]), offs[2], len(sec[2]), offs[3], len(sec[3]), total)
     out = bytearray(total)
@@ -390,12 +426,12 @@ def build_blob(e: Encoded) -> bytes:
 
 def parse_blob(blob: bytes) -> dict:
     (magic, version, hbytes, rows, cols, seg_cols, ur, up, cc, n_bands, n_panels, n_quads, n_entries, lmax,
-     max_entries, pad_code, _res, n_units, n_chunks, n_real, o_d, b_d, o_u, b_u, o_c, b_c, o_s, b_s,
+     max_entries, pad_code, packing, n_units, n_chunks, n_real, o_d, b_d, o_u, b_u, o_c, b_c, o_s, b_s,
      total) = _HDR.unpack_from(blob, 0)
     assert magic == MAGIC and version == 2 and hbytes == HEADER_BYTES
     assert (ur, up, cc) == (UNIT_ROWS, UNIT_PANELS, CHUNK_CODES)
     assert (n_bands, n_panels, n_quads) == geometry(rows, cols, seg_cols) and n_units == n_bands * n_quads
-    assert total == len(blob) and pad_code == n_entries
+    assert total == len(blob) and pad_code == n_entries and packing in (0, 1)
     buf = np.frombuffer(blob, dtype=np.uint8)
     slots = buf[o_d: o_d + b_d].view(np.uint32)
     uoff = buf[o_u: o_u + b_u].view(np.uint32)
@@ -409,18 +445,20 @@ def parse_blob(blob: bytes) -> dict:
     for k in range(3):
         eb[:, k] = (slots[:n_entries] >> (8 * k)) & 0xFF
     return dict(rows=rows, cols=cols, seg_cols=seg_cols, n_bands=n_bands, n_panels=n_panels, n_quads=n_quads,
-                n_entries=n_entries, lmax=lmax, max_entries=max_entries, pad_code=pad_code, n_units=n_units,
+                n_entries=n_entries, lmax=lmax, max_entries=max_entries, pad_code=pad_code, packing=packing, n_units=n_units,
                 n_chunks=n_chunks, n_codes=n_chunks * CHUNK_WORDS, n_real_codes=n_real,
                 dictionary=Dictionary(eb, el), slots=slots, uoff=uoff, stream=stream, scales=scales,
                 compressed_bytes=int(b_d + b_u + b_c + b_s), stream_bytes=int(b_c))
 
 
 def decode_blob(blob: bytes):
-    """Container -> (Q int8 [rows, cols], scales fp32 [rows]) through the oracle's own decoder."""
+    """Container -> (Q int8 [rows, K], scales fp32 [rows]) through the oracle's own decoder; K is the header's cols, twice
+    that for a container of packed 4-bit values."""
     p = parse_blob(blob)
     _, _, seg_len = segment_table(p["rows"], p["cols"], p["seg_cols"])
     S = lzw_decode(p["stream"], p["uoff"], seg_len.astype(np.uint32), p["dictionary"], p["pad_code"])
-    return deserialize(S, p["rows"], p["cols"], p["seg_cols"]), p["scales"][: p["rows"]].copy()
+    Q = deserialize(S, p["rows"], p["cols"], p["seg_cols"])
+    return (unpack_nibbles(Q) if p["packing"] else Q), p["scales"][: p["rows"]].copy()
 
 
 def matvec_from_blob(blob: bytes, x: np.ndarray) -> np.ndarray:

@@ -34,7 +34,8 @@ class TqError(RuntimeError):
 class TqEncodeOpts(ctypes.Structure):
     _fields_ = [("max_entries", ctypes.c_uint32), ("lmax", ctypes.c_uint32), ("n_threads", ctypes.c_uint32),
                 ("seg_cols", ctypes.c_uint32), ("dict_from", ctypes.c_void_p), ("dict_from_bytes", ctypes.c_uint64),
-                ("dictionary", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("dictionary", ctypes.c_uint32), ("bits", ctypes.c_uint32), ("packing", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32)]
 
 
 class TqInfo(ctypes.Structure):
@@ -43,7 +44,7 @@ class TqInfo(ctypes.Structure):
                 ("n_units", ctypes.c_uint64), ("n_codes", ctypes.c_uint64), ("n_real_codes", ctypes.c_uint64),
                 ("dict_bytes", ctypes.c_uint64),
                 ("offset_bytes", ctypes.c_uint64), ("code_bytes", ctypes.c_uint64), ("scale_bytes", ctypes.c_uint64),
-                ("compressed_bytes", ctypes.c_uint64), ("lane_spread", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("compressed_bytes", ctypes.c_uint64), ("lane_spread", ctypes.c_uint32), ("packing", ctypes.c_uint32)]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -132,9 +133,11 @@ DICTIONARY_KINDS = {"lzw": 0, "frequency": 1}
 
 
 def _opts(max_entries: int, lmax: int, n_threads: int, seg_cols: int, dict_from: Optional[bytes],
-          dictionary: str = "lzw") -> TqEncodeOpts:
+          dictionary: str = "lzw", bits: int = 0, pack: bool = False) -> TqEncodeOpts:
     o = TqEncodeOpts()
     o.max_entries, o.lmax, o.n_threads, o.seg_cols = max_entries, lmax, n_threads, seg_cols
+    o.bits = bits
+    o.packing = 1 if pack else 0
     o.dictionary = DICTIONARY_KINDS[dictionary]
     if dict_from is not None:
         o.dict_from = ctypes.cast(ctypes.c_char_p(dict_from), ctypes.c_void_p)   # the caller's bytes object outlives the call
@@ -150,37 +153,39 @@ def _take_blob(ptr: ctypes.c_void_p, n: ctypes.c_size_t) -> bytes:
 
 
 def tq_encode(w: np.ndarray, max_entries: int = 0, lmax: int = 0, n_threads: int = 0, seg_cols: int = 0,
-              dict_from: Optional[bytes] = None, dictionary: str = "lzw") -> bytes:
+              dict_from: Optional[bytes] = None, dictionary: str = "lzw", bits: int = 0, pack: bool = False) -> bytes:
     """fp32 [rows, cols] host array -> container bytes.  dict_from: a container made earlier whose dictionary LZW
-    continues from (one dictionary over a sequence of matrices)."""
+    continues from (one dictionary over a sequence of matrices).  bits: quantization width, 2..8 (0 = 8).
+    pack (bits 2..4): two values per stored byte (TQ_PACK_NIBBLES)."""
     w = np.ascontiguousarray(w, dtype=np.float32)
     assert w.ndim == 2
     ptr, n = ctypes.c_void_p(), ctypes.c_size_t()
-    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from, dictionary)
+    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from, dictionary, bits, pack)
     _check(load().tq_encode(w.ctypes.data, w.shape[0], w.shape[1], ctypes.byref(o), ctypes.byref(ptr), ctypes.byref(n)))
     return _take_blob(ptr, n)
 
 
 def tq_encode_quantized(q: np.ndarray, scales: np.ndarray, max_entries: int = 0, lmax: int = 0, n_threads: int = 0,
-                        seg_cols: int = 0, dict_from: Optional[bytes] = None, dictionary: str = "lzw") -> bytes:
+                        seg_cols: int = 0, dict_from: Optional[bytes] = None, dictionary: str = "lzw", pack: bool = False) -> bytes:
     q = np.ascontiguousarray(q, dtype=np.int8)
     scales = np.ascontiguousarray(scales, dtype=np.float32)
     assert q.ndim == 2 and scales.shape == (q.shape[0],)
     ptr, n = ctypes.c_void_p(), ctypes.c_size_t()
-    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from, dictionary)
+    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from, dictionary, 0, pack)
     _check(load().tq_encode_quantized(q.ctypes.data, scales.ctypes.data, q.shape[0], q.shape[1], ctypes.byref(o),
                                       ctypes.byref(ptr), ctypes.byref(n)))
     return _take_blob(ptr, n)
 
 
 def tq_encode_gate_up(w_gate: np.ndarray, w_up: np.ndarray, max_entries: int = 0, lmax: int = 0, n_threads: int = 0,
-                      seg_cols: int = 0, dict_from: Optional[bytes] = None, dictionary: str = "lzw") -> bytes:
+                      seg_cols: int = 0, dict_from: Optional[bytes] = None, dictionary: str = "lzw", bits: int = 0,
+                      pack: bool = False) -> bytes:
     """Two fp32 [rows, cols] host arrays -> one container of 2 * rows rows, gate and up rows interleaved."""
     g = np.ascontiguousarray(w_gate, dtype=np.float32)
     u = np.ascontiguousarray(w_up, dtype=np.float32)
     assert g.ndim == 2 and g.shape == u.shape
     ptr, n = ctypes.c_void_p(), ctypes.c_size_t()
-    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from, dictionary)
+    o = _opts(max_entries, lmax, n_threads, seg_cols, dict_from, dictionary, bits, pack)
     _check(load().tq_encode_gate_up(g.ctypes.data, u.ctypes.data, g.shape[0], g.shape[1], ctypes.byref(o), ctypes.byref(ptr),
                                     ctypes.byref(n)))
     return _take_blob(ptr, n)

@@ -36,6 +36,8 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* fa
       h.n_quads != (h.n_panels + kUnitPanels - 1) / kUnitPanels)
     return bad("band / panel / quad counts");
   if (h.lmax < 1 || h.lmax > TQ_MAX_LMAX) return bad("lmax");
+  if (h.packing > TQ_PACK_NIBBLES) return bad("packing");
+  if (h.packing && h.cols > 0x7FFFFFFFu) return bad("packed width");
   if (h.n_entries < 256 || h.n_entries > TQ_MAX_ENTRIES_DEVICE || h.n_entries > h.max_entries) return bad("entry count");
   if (h.pad_code != h.n_entries) return bad("pad code");
   const uint64_t n_units = (uint64_t)h.n_bands * h.n_quads;
@@ -143,7 +145,8 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* fa
 void fill_info(const Header& h, const BlobFacts& facts, tq_info* o) {
   std::memset(o, 0, sizeof *o);
   o->rows = h.rows;
-  o->cols = h.cols;
+  o->cols = h.packing ? 2 * h.cols : h.cols;
+  o->packing = h.packing;
   o->seg_cols = h.seg_cols;
   o->n_panels = h.n_panels;
   o->n_entries = h.n_entries;

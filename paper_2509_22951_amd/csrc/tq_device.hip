@@ -59,6 +59,8 @@ struct DevMat {
   uint32_t x_dwords;       // size of that image, including the columns lanes can reach while they consume pad codes
   uint32_t seg_magic;      // floor(2^32 / seg_cols) + 1: col / seg_cols == mulhi(col, seg_magic) for every column index in use
   uint32_t reserved;       // how the ring kernel may decode the matrix: 0 not at all, 1 in groups of windows, 2 window by window
+  uint32_t packing;        // 1: every byte holds two 4-bit weights (columns 2j and 2j + 1 of a matrix of 2 * cols columns); rows,
+                           // cols and seg_cols describe the byte matrix, and dict_bf16 holds four fp8 (e4m3) weights per entry
 };
 
 struct Job {
@@ -270,6 +272,58 @@ __device__ __forceinline__ void chunk4(uint2 c, uint32_t& xa, float& a0, float& 
   a1 = dot2(w3, x3, a1);
 }
 
+// The same for a matrix of packed 4-bit weights.  A dictionary word holds the entry's four weights as fp8 (e4m3 holds
+// -8..7 exactly; two zeros after a single byte), one activation dword holds the two columns of a byte: code k reads the
+// dwords at xa + 4 k and the next one, and two conversions give the bf16 pairs for two dot products.
+__device__ __forceinline__ float dot2_fp8(uint32_t w, bool high, uint32_t x, float acc) {
+  const bf16x2 wb = high ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
+  return __builtin_amdgcn_fdot2_f32_bf16(wb, __builtin_bit_cast(bf16x2, x), acc, false);
+}
+template <int kCode0>
+__device__ __forceinline__ void chunk4_packed(uint2 c, uint32_t& xa, float& a0, float& a1) {
+  const uint32_t w0 = lds_read32(word_offset_lo(c.x)), w1 = lds_read32(word_offset_hi(c.x));
+  const uint32_t w2 = lds_read32(word_offset_lo(c.y)), w3 = lds_read32(word_offset_hi(c.y));
+  const uint32_t x0 = lds_read32_off<4 * kCode0>(xa), x0b = lds_read32_off<4 * kCode0 + 4>(xa);
+  xa = advance_by_pair(is_pair_lo(c.x), xa);
+  const uint32_t x1 = lds_read32_off<4 * kCode0 + 4>(xa), x1b = lds_read32_off<4 * kCode0 + 8>(xa);
+  xa = advance_by_pair(is_pair_hi(c.x), xa);
+  const uint32_t x2 = lds_read32_off<4 * kCode0 + 8>(xa), x2b = lds_read32_off<4 * kCode0 + 12>(xa);
+  xa = advance_by_pair(is_pair_lo(c.y), xa);
+  const uint32_t x3 = lds_read32_off<4 * kCode0 + 12>(xa), x3b = lds_read32_off<4 * kCode0 + 16>(xa);
+  xa = advance_by_pair(is_pair_hi(c.y), xa);
+  a0 = dot2_fp8(w0, false, x0, a0);
+  a1 = dot2_fp8(w0, true, x0b, a1);
+  a0 = dot2_fp8(w1, false, x1, a0);
+  a1 = dot2_fp8(w1, true, x1b, a1);
+  a0 = dot2_fp8(w2, false, x2, a0);
+  a1 = dot2_fp8(w2, true, x2b, a1);
+  a0 = dot2_fp8(w3, false, x3, a0);
+  a1 = dot2_fp8(w3, true, x3b, a1);
+}
+
+// LDS image of one activation row for packed weights: dword (panel * x_span + c) = the two activations of byte column
+// panel * seg_cols + c, zero past the end of the row.  Thread t of a round handles dword first + k * kThreads + t.
+template <bool kAligned, int kThreads, int kXRegs>
+__device__ __forceinline__ void issue_activations_packed(const DevMat& m, const uint16_t* __restrict__ x, uint32_t first, int tid,
+                                                         uint32_t (&v)[kXRegs]) {
+#pragma unroll
+  for (int k = 0; k < kXRegs; ++k) {
+    const uint32_t j = first + k * kThreads + tid;
+    if (kAligned) v[k] = j < m.cols ? global_load((const uint32_t*)x + j) : 0u;   // x is 4-byte aligned
+    else v[k] = j < m.cols ? global_load(x + 2 * j) | global_load(x + 2 * j + 1) << 16 : 0u;
+  }
+}
+template <int kThreads, int kXRegs>
+__device__ __forceinline__ void commit_activations_packed(const DevMat& m, uint32_t first, int tid, const uint32_t (&v)[kXRegs], uint32_t* lds_x,
+                                                          uint32_t image_cols) {
+  const uint32_t gap = m.x_span - m.seg_cols;
+#pragma unroll
+  for (int k = 0; k < kXRegs; ++k) {
+    const uint32_t j = first + k * kThreads + tid;
+    if (j < image_cols) lds_x[j + gap * __umulhi(j, m.seg_magic)] = v[k];
+  }
+}
+
 // Sum of the four panel lanes of each row: afterwards every lane l holds the sum over lanes l % 16 + {0, 16, 32, 48}.
 __device__ __forceinline__ float sum_over_panels(float v) {
   v += __shfl_xor(v, 16);
@@ -289,7 +343,7 @@ __device__ __forceinline__ float silu_times(float gate, float up) { return gate 
 // lies entirely inside its run (it scales and stores those rows itself); a band it shares with its neighbours goes to
 // one of two partial-sum slots in LDS, and after a workgroup barrier the slots of a band are added in wavefront order,
 // so the result does not depend on timing.
-template <int kPiece, int kWaves>
+template <int kPiece, int kWaves, bool kPacked>
 __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
   constexpr int kThreads = kWaves * 64, kDictRegs = 128 / kWaves, kXRegs = 64 / kWaves;
   extern __shared__ uint4 lds4[];
@@ -321,7 +375,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
     // lane's panel inside a unit is lane >> 4; quad q adds 4 q panels
     const uint32_t xa_lane = lds_address(lds_x) + 4u * m.x_span * (uint32_t)(lane >> 4);
     const uint32_t xa_quad = 16u * m.x_span;
-    const bool x_aligned = (m.cols % 2 == 0) && ((uintptr_t)job.x % 4 == 0);
+    const bool x_aligned = (kPacked || m.cols % 2 == 0) && ((uintptr_t)job.x % 4 == 0);
     const uint32_t c0 = u0 < u1 ? unit_offset(m, u0) : 0u, n_chunks = u0 < u1 ? unit_offset(m, u1) - c0 : 0u;
     {   // one activation row: larger batches run the MFMA kernel
       const uint16_t* xb = job.x;
@@ -332,8 +386,13 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
         uint32_t xlo[kXRegs], xhi[kXRegs];
         const bool dict_now = new_dict;
         if (dict_now) issue_dictionary<kThreads, kDictRegs>(m, 0, tid, dv);
-        if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
-        else issue_activations<false, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
+        if constexpr (kPacked) {
+          if (x_aligned) issue_activations_packed<true, kThreads, kXRegs>(m, xb, 0, tid, xlo);
+          else issue_activations_packed<false, kThreads, kXRegs>(m, xb, 0, tid, xlo);
+        } else {
+          if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
+          else issue_activations<false, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
+        }
         zero_activation_gaps<kThreads>(m, tid, lds_x, n_slots);
         if (tid < 2 * kWaves) slot_band[tid] = -1;
         if (dict_now) {
@@ -343,11 +402,20 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
             commit_dictionary<kThreads, kDictRegs>(m, base, tid, dv, lds_dict);
           }
         }
-        commit_activations<kThreads, kXRegs>(m, 0, tid, xlo, xhi, lds_x, image_cols);
-        for (uint32_t first = kXRegs * kThreads; 2 * first < image_cols; first += kXRegs * kThreads) {
-          if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
-          else issue_activations<false, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
-          commit_activations<kThreads, kXRegs>(m, first, tid, xlo, xhi, lds_x, image_cols);
+        if constexpr (kPacked) {
+          commit_activations_packed<kThreads, kXRegs>(m, 0, tid, xlo, lds_x, image_cols);
+          for (uint32_t first = kXRegs * kThreads; first < image_cols; first += kXRegs * kThreads) {
+            if (x_aligned) issue_activations_packed<true, kThreads, kXRegs>(m, xb, first, tid, xlo);
+            else issue_activations_packed<false, kThreads, kXRegs>(m, xb, first, tid, xlo);
+            commit_activations_packed<kThreads, kXRegs>(m, first, tid, xlo, lds_x, image_cols);
+          }
+        } else {
+          commit_activations<kThreads, kXRegs>(m, 0, tid, xlo, xhi, lds_x, image_cols);
+          for (uint32_t first = kXRegs * kThreads; 2 * first < image_cols; first += kXRegs * kThreads) {
+            if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
+            else issue_activations<false, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
+            commit_activations<kThreads, kXRegs>(m, first, tid, xlo, xhi, lds_x, image_cols);
+          }
         }
       }
       __syncthreads();
@@ -407,16 +475,20 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
           for (int k = 0; k < kPiece; ++k) cw[k] = load_chunk(m.codes, min(start + k, last), lane);
         };
         auto run_piece = [&](const uint2 (&cw)[kPiece], uint32_t n, bool ends) {
+          auto chunk = [&](auto kk) {
+            constexpr int k = decltype(kk)::value;
+            if constexpr (kPacked) chunk4_packed<4 * k>(cw[k], xa, a0, a1);
+            else chunk4<4 * k>(cw[k], xa, a0, a1);
+          };
           if (n == kPiece) {
-            static_for<kPiece>([&](auto kk) { chunk4<4 * decltype(kk)::value>(cw[decltype(kk)::value], xa, a0, a1); });
+            static_for<kPiece>(chunk);
           } else if (n == kPiece - 1) {
-            static_for<kPiece - 1>([&](auto kk) { chunk4<4 * decltype(kk)::value>(cw[decltype(kk)::value], xa, a0, a1); });
+            static_for<kPiece - 1>(chunk);
           } else if (n == kPiece - 2) {
-            static_for<kPiece - 2>([&](auto kk) { chunk4<4 * decltype(kk)::value>(cw[decltype(kk)::value], xa, a0, a1); });
+            static_for<kPiece - 2>(chunk);
           } else {
             static_for<kPiece>([&](auto kk) {
-              constexpr int k = decltype(kk)::value;
-              if ((uint32_t)k < n) chunk4<4 * k>(cw[k], xa, a0, a1);
+              if ((uint32_t)decltype(kk)::value < n) chunk(kk);
             });
           }
           xa += 16 * n;
@@ -519,6 +591,19 @@ __device__ __forceinline__ bf16x8 i8x8_to_bf16x8(uint2 w) {
     r.w = __builtin_amdgcn_perm(__float_as_uint(f3), __float_as_uint(f2), 0x07060302u);
   }
   return __builtin_bit_cast(bf16x8, r);
+}
+
+// 8 packed 4-bit weights (a dword: byte j holds columns 2j in bits 0..3 and 2j + 1 in bits 4..7, two's complement)
+// -> 8 bf16 in column order (exact).
+__device__ __forceinline__ bf16x8 nib8_to_bf16x8(uint32_t d) {
+  uint32_t r[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    // (the builtin's result type is unsigned: without the casts -1 would convert as 2^32 - 1)
+    const float lo = (float)(int)__builtin_amdgcn_sbfe(d, 8 * j, 4), hi = (float)(int)__builtin_amdgcn_sbfe(d, 8 * j + 4, 4);
+    r[j] = __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+  }
+  return __builtin_bit_cast(bf16x8, make_uint4(r[0], r[1], r[2], r[3]));
 }
 
 // Append the runs of one chunk (4 codes) to the lane's strip.  The 4 entries (1 or 2 bytes each; the length follows
@@ -675,7 +760,9 @@ constexpr int kMfmaGroup = 8;   // MFMA steps per group: the activation fragment
 // Four accumulators so that consecutive MFMAs do not wait for each other; groups of kMfmaGroup steps whose weight
 // reads are all issued before the first conversion and whose activation fragments were requested a group earlier
 // (the first group by the caller, into xa).
-template <bool kFast, bool kRagged>
+// kPacked: the strips hold packed 4-bit weights; a step then takes 4 bytes of every strip (8 columns again), n_win counts
+// those steps, and cols and xcol are columns of the weight matrix (twice the byte columns).
+template <bool kFast, bool kRagged, bool kPacked>
 __device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, global_cu16* xrow, uint32_t cols, uint32_t xcol, uint32_t n_win,
                                                uint4 (&xa)[kMfmaGroup]) {
   f32x4 part[4] = {acc, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
@@ -684,25 +771,38 @@ __device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, glo
 #pragma unroll
     for (int k = 0; k < kMfmaGroup; ++k) xf[k] = load_x_fragment<kFast>(xrow, cols, xcol + 8 * (w0 + k));
   };
+  auto weights = [&](uint32_t w) {   // the 8 weights of step w as bf16
+    if constexpr (kPacked) {
+      return nib8_to_bf16x8(*(lds_cu32*)(size_t)(my_strip + 4 * w));
+    } else {
+      const u32x2 a8 = *(lds_cu64*)(size_t)(my_strip + 8 * w);
+      return i8x8_to_bf16x8(make_uint2(a8.x, a8.y));
+    }
+  };
   auto run_group = [&](const uint4 (&xf)[kMfmaGroup], uint32_t w0) {
     if (w0 + kMfmaGroup <= n_win) {   // whole group
-      u32x2 a8[kMfmaGroup];
+      bf16x8 a8[kMfmaGroup];
+      if constexpr (kPacked) {
 #pragma unroll
-      for (int k = 0; k < kMfmaGroup; ++k) a8[k] = *(lds_cu64*)(size_t)(my_strip + 8 * (w0 + k));
+        for (int k = 0; k < kMfmaGroup; ++k) a8[k] = weights(w0 + k);
+      } else {
+        u32x2 raw[kMfmaGroup];
+#pragma unroll
+        for (int k = 0; k < kMfmaGroup; ++k) raw[k] = *(lds_cu64*)(size_t)(my_strip + 8 * (w0 + k));
+#pragma unroll
+        for (int k = 0; k < kMfmaGroup; ++k) a8[k] = i8x8_to_bf16x8(make_uint2(raw[k].x, raw[k].y));
+      }
 #pragma unroll
       for (int k = 0; k < kMfmaGroup; ++k) {
         const uint4 x8 = kRagged ? mask_x_fragment<kFast>(xf[k], cols, xcol + 8 * (w0 + k)) : xf[k];
-        part[k & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8[k].x, a8[k].y)), __builtin_bit_cast(bf16x8, x8),
-                                                              part[k & 3], 0, 0, 0);
+        part[k & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8[k], __builtin_bit_cast(bf16x8, x8), part[k & 3], 0, 0, 0);
       }
     } else {
 #pragma unroll
       for (int k = 0; k < kMfmaGroup; ++k) {
         if (w0 + k < n_win) {
-          const u32x2 a8 = *(lds_cu64*)(size_t)(my_strip + 8 * (w0 + k));
           const uint4 x8 = kRagged ? mask_x_fragment<kFast>(xf[k], cols, xcol + 8 * (w0 + k)) : xf[k];
-          part[k & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8.x, a8.y)), __builtin_bit_cast(bf16x8, x8),
-                                                                part[k & 3], 0, 0, 0);
+          part[k & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(weights(w0 + k), __builtin_bit_cast(bf16x8, x8), part[k & 3], 0, 0, 0);
         }
       }
     }
@@ -1019,7 +1119,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec_ring(MatvecArgs a) {
   }
 }
 
-template <bool kXFast>
+template <bool kXFast, bool kPacked>
 __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
   extern __shared__ uint4 lds4[];
   uint16_t* lds_dict = (uint16_t*)lds4;
@@ -1066,7 +1166,9 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
     f32x4 acc = {0.f, 0.f, 0.f, 0.f}, head_acc = {0.f, 0.f, 0.f, 0.f}, tail_acc = {0.f, 0.f, 0.f, 0.f};
     int head_band = -1, tail_band = -1;
     // lanes past the batch repeat its last row: their output columns are never stored
-    global_cu16* xrow = (global_cu16*)job.x + (size_t)min(bn, a.batch - 1) * m.cols;
+    constexpr uint32_t pk = kPacked ? 2u : 1u;   // columns of the weight matrix per stored byte
+    const uint32_t x_cols = pk * m.cols;
+    global_cu16* xrow = (global_cu16*)job.x + (size_t)min(bn, a.batch - 1) * x_cols;
     const uint32_t first_band = u0 / nq;
     const bool first_whole = u0 % nq == 0;
     // acc holds the sums of the band in work when its last unit (or the run's) has been multiplied
@@ -1107,16 +1209,15 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
       decode_run_to_tile(m, u0, u1, lane, my_strip, [&](uint32_t, uint32_t quad) {
 #pragma unroll
         for (int k = 0; k < kMfmaGroup; ++k)
-          xa[k] = load_x_fragment<kXFast>(xrow, m.cols, (quad * kUnitPanels + (uint32_t)kg) * m.seg_cols + 8 * k);
+          xa[k] = load_x_fragment<kXFast>(xrow, x_cols, pk * (quad * kUnitPanels + (uint32_t)kg) * m.seg_cols + 8 * k);
       }, [&](uint32_t band, uint32_t quad) {
-        const uint32_t col0 = quad * kUnitPanels * m.seg_cols;                            // first column of the unit
+        const uint32_t col0 = quad * kUnitPanels * m.seg_cols;                            // first (byte) column of the unit
         const uint32_t width = min(m.seg_cols, m.cols - col0);                            // its widest segment is the first panel's
-        const uint32_t n_win = (width + 7) / 8;
-        const uint32_t xcol = col0 + (uint32_t)kg * m.seg_cols;
-        if (!kXFast || col0 + kUnitPanels * m.seg_cols > m.cols)   // some fragment reaches past the row's end
-          acc = multiply_unit<kXFast, true>(acc, my_strip, xrow, m.cols, xcol, n_win, xa);
-        else
-          acc = multiply_unit<kXFast, false>(acc, my_strip, xrow, m.cols, xcol, n_win, xa);
+        const uint32_t n_win = (pk * width + 7) / 8;
+        const uint32_t xcol = pk * (col0 + (uint32_t)kg * m.seg_cols);
+        const bool ragged = !kXFast || col0 + kUnitPanels * m.seg_cols > m.cols;          // some fragment reaches past the row's end
+        if (ragged) acc = multiply_unit<kXFast, true, kPacked>(acc, my_strip, xrow, x_cols, xcol, n_win, xa);
+        else acc = multiply_unit<kXFast, false, kPacked>(acc, my_strip, xrow, x_cols, xcol, n_win, xa);
         finish_unit(band, quad);
       });
     }
@@ -1208,7 +1309,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_decompress(MatvecArgs a) {
     const uint32_t strip = m.seg_cols + 8;
     const uint32_t tile_lds = lds_address(tiles) + (uint32_t)wave * a.tile_area;   // matrices of different segment width may be in work at once
     int8_t* out = (int8_t*)job.y;
-    const bool aligned = (m.cols % 16 == 0) && ((uintptr_t)out % 16 == 0);
+    const bool aligned = ((m.packing ? 2 * m.cols : m.cols) % 16 == 0) && ((uintptr_t)out % 16 == 0);
     const uint32_t ppp = m.seg_cols / 16;   // 16-byte pieces per segment
     decode_run_to_tile(m, u0, u1, lane, tile_lds + (uint32_t)lane * strip, [](uint32_t, uint32_t) {}, [&](uint32_t band, uint32_t quad) {
       for (uint32_t pc = lane; pc < 64 * ppp; pc += 64) {
@@ -1217,6 +1318,28 @@ __global__ __launch_bounds__(kThreads, 1) void k_decompress(MatvecArgs a) {
         if (row >= m.rows || col >= m.cols) continue;
         const uint32_t src = tile_lds + ((seg >> 2) + 16 * (seg & 3)) * strip + part * 16;   // strip of lane (row, panel)
         const u32x2 lo8 = *(lds_cu64*)(size_t)src, hi8 = *(lds_cu64*)(size_t)(src + 8);
+        if (m.packing) {   // 16 bytes -> 32 int8: columns 2 col .. 2 col + 31 of a row of 2 cols values
+          int8_t* dst2 = out + ((size_t)row * m.cols + col) * 2;
+          const uint32_t w[4] = {lo8.x, lo8.y, hi8.x, hi8.y};
+          uint32_t e[8];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {   // nibbles to bytes with their sign (8 -> 0xF8 inside its own byte), then in column order
+            uint32_t even = w[k] & 0x0F0F0F0Fu, odd = (w[k] >> 4) & 0x0F0F0F0Fu;
+            even |= (even & 0x08080808u) * 0x1Eu;
+            odd |= (odd & 0x08080808u) * 0x1Eu;
+            e[2 * k] = __builtin_amdgcn_perm(odd, even, 0x05010400u);
+            e[2 * k + 1] = __builtin_amdgcn_perm(odd, even, 0x07030602u);
+          }
+          if (aligned && col + 16 <= m.cols) {
+            *(__attribute__((address_space(1))) u32x4*)dst2 = u32x4{e[0], e[1], e[2], e[3]};
+            *(__attribute__((address_space(1))) u32x4*)(dst2 + 16) = u32x4{e[4], e[5], e[6], e[7]};
+          } else {
+#pragma unroll
+            for (int k = 0; k < 32; ++k)
+              if (col + k / 2 < m.cols) *(__attribute__((address_space(1))) int8_t*)(dst2 + k) = (int8_t)(e[k >> 2] >> (8 * (k & 3)));
+          }
+          continue;
+        }
         int8_t* dst = out + (size_t)row * m.cols + col;
         if (aligned && col + 16 <= m.cols) {
           u32x4 v = {lo8.x, lo8.y, hi8.x, hi8.y};
@@ -1250,7 +1373,9 @@ struct DictCopy {
   int device;
   std::vector<uint32_t> words;   // host copy for the comparison
   uint32_t* dev;        // container words
-  uint32_t* dev_bf16;   // (bf16(b0), bf16(b1)) per entry; a single-byte entry has a zero second weight, the pad entry two
+  uint32_t* dev_bf16;   // (bf16(b0), bf16(b1)) per entry; a single-byte entry has a zero second weight, the pad entry two.
+                        // Packed 4-bit weights: the four nibbles of (b0, b1) as fp8 e4m3, in column order.
+  uint32_t packing;
   int refs;
 };
 
@@ -1261,13 +1386,23 @@ uint32_t i8_to_bf16_bits(uint32_t byte) {
   std::memcpy(&u, &f, 4);
   return u >> 16;
 }
+// 4-bit two's complement -> fp8 e4m3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits): -8..7 are all exact.
+uint32_t nibble_to_fp8_bits(uint32_t nibble) {
+  const int v = (int)(nibble & 7u) - (int)(nibble & 8u);
+  const uint32_t mag = (uint32_t)(v < 0 ? -v : v), sign = v < 0 ? 0x80u : 0u;
+  if (mag == 0) return 0;
+  uint32_t e = 0;
+  while ((mag >> (e + 1)) != 0) ++e;                       // mag = 2^e * (1 + mantissa / 8)
+  const uint32_t mant = ((mag << 3) >> e) & 7u;
+  return sign | (e + 7) << 3 | mant;
+}
 std::mutex g_dict_mutex;
 std::vector<DictCopy*> g_dicts;
 
-int acquire_dictionary(int device, const uint32_t* words, uint32_t n_words, uint32_t n_words_pad, DictCopy** out) {
+int acquire_dictionary(int device, const uint32_t* words, uint32_t n_words, uint32_t n_words_pad, uint32_t packing, DictCopy** out) {
   std::lock_guard<std::mutex> lock(g_dict_mutex);
   for (DictCopy* d : g_dicts)
-    if (d->device == device && d->words.size() == n_words && std::memcmp(d->words.data(), words, (size_t)n_words * 4) == 0) {
+    if (d->device == device && d->packing == packing && d->words.size() == n_words && std::memcmp(d->words.data(), words, (size_t)n_words * 4) == 0) {
       ++d->refs;
       *out = d;
       return TQ_OK;
@@ -1280,10 +1415,17 @@ int acquire_dictionary(int device, const uint32_t* words, uint32_t n_words, uint
   d->device = device;
   d->words.assign(words, words + n_words);
   d->refs = 1;
+  d->packing = packing;
   d->dev = d->dev_bf16 = nullptr;
   // bytes past an entry's length are zero in the container, so the conversion needs no length test
   std::vector<uint32_t> pairs(n_words_pad, 0u);
-  for (uint32_t i = 0; i < n_words; ++i) pairs[i] = i8_to_bf16_bits(words[i] & 0xFFu) | i8_to_bf16_bits(words[i] >> 8 & 0xFFu) << 16;
+  for (uint32_t i = 0; i < n_words; ++i) {
+    if (packing) {
+      for (uint32_t k = 0; k < 4; ++k) pairs[i] |= nibble_to_fp8_bits(words[i] >> (4 * k) & 15u) << (8 * k);
+    } else {
+      pairs[i] = i8_to_bf16_bits(words[i] & 0xFFu) | i8_to_bf16_bits(words[i] >> 8 & 0xFFu) << 16;
+    }
+  }
   hipError_t e = hipMalloc((void**)&d->dev, (size_t)n_words_pad * 4);
   if (e == hipSuccess) e = hipMalloc((void**)&d->dev_bf16, (size_t)n_words_pad * 4);
   if (e == hipSuccess) e = hipMemset(d->dev, 0, (size_t)n_words_pad * 4);
@@ -1357,6 +1499,8 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   m.x_span = h.seg_cols + (h.seg_cols % 32 == 0 ? 16u : 0u);
   m.seg_magic = (uint32_t)((1ull << 32) / h.seg_cols) + 1;   // exact quotient while col * seg_cols < 2^32
   m.reserved = facts.max_lane_spread <= kRingSpread ? 1u : facts.max_lane_spread <= kRingSpreadCareful ? 2u : 0u;
+  m.packing = h.packing;
+  if (h.packing) m.reserved = 0;   // the ring kernel takes one weight per byte
   if (h.cols > (1u << 20)) {
     set_error("more than 2^20 columns are not supported");
     return TQ_E_UNSUPPORTED;
@@ -1388,17 +1532,20 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
     return TQ_E_UNSUPPORTED;
   }
   // Dynamic LDS above 64 KB has to be allowed per kernel function.
-  e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_decompress, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWaves, 16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesHalf, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
 
   const uint8_t* src = (const uint8_t*)blob;
   DictCopy* dict = nullptr;
-  if (int rc = acquire_dictionary(dev, (const uint32_t*)(src + h.off_dict), h.n_entries + 1, m.dict_words, &dict)) return rc;
+  if (int rc = acquire_dictionary(dev, (const uint32_t*)(src + h.off_dict), h.n_entries + 1, m.dict_words, h.packing, &dict)) return rc;
 
   const uint64_t sz_uoff = round_up(h.uoff_bytes, kSectionAlign), sz_codes = round_up(h.code_bytes, kSectionAlign),
                  sz_scales = round_up(h.scale_bytes, kSectionAlign);
@@ -1471,7 +1618,7 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     dict_words_max = std::max(dict_words_max, t->m.dict_words);
     x_dwords_max = std::max(x_dwords_max, t->m.x_dwords);
     seg_max = std::max(seg_max, t->m.seg_cols);
-    x_fast = x_fast && t->m.cols % 8 == 0 && xs && (uintptr_t)xs[i] % 16 == 0;
+    x_fast = x_fast && (t->m.packing ? 2 : 1) * t->m.cols % 8 == 0 && xs && (uintptr_t)xs[i] % 16 == 0;
   }
   a.cost[n] = (uint32_t)cost;
   if (cost > 0xFFFFFFFFull) {
@@ -1487,7 +1634,9 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
       set_error("the matrices of this call together need " + std::to_string(lds_total) + " bytes of LDS (largest dictionary plus longest row)");
       return TQ_E_UNSUPPORTED;
     }
-    hipLaunchKernelGGL((k_matvec<kDotPiece, kDotWaves>), dim3((unsigned)grid), dim3(kDotWaves * 64), lds_total, stream, a);
+    // (all matrices of a product launch hold their weights the same way: launch_all sees to that)
+    if (hs[0]->m.packing) hipLaunchKernelGGL((k_matvec<kDotPiece, kDotWaves, true>), dim3((unsigned)grid), dim3(kDotWaves * 64), lds_total, stream, a);
+    else hipLaunchKernelGGL((k_matvec<kDotPiece, kDotWaves, false>), dim3((unsigned)grid), dim3(kDotWaves * 64), lds_total, stream, a);
   } else if (ring) {
     // LDS: 16-bit dictionary image | one ring per lane (aligned to its size: the kernel ORs piece offsets into its
     // address) | the activation tile of one quad.
@@ -1520,8 +1669,10 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     const size_t lds = dict16 + waves * area;
     const dim3 block((unsigned)waves * 64);
     if (op == Op::kDecompress) hipLaunchKernelGGL(k_decompress, dim3((unsigned)grid), block, lds, stream, a);
-    else if (x_fast) hipLaunchKernelGGL((k_matvec_mfma<true>), dim3((unsigned)grid), block, lds, stream, a);
-    else hipLaunchKernelGGL((k_matvec_mfma<false>), dim3((unsigned)grid), block, lds, stream, a);
+    else if (hs[0]->m.packing && x_fast) hipLaunchKernelGGL((k_matvec_mfma<true, true>), dim3((unsigned)grid), block, lds, stream, a);
+    else if (hs[0]->m.packing) hipLaunchKernelGGL((k_matvec_mfma<false, true>), dim3((unsigned)grid), block, lds, stream, a);
+    else if (x_fast) hipLaunchKernelGGL((k_matvec_mfma<true, false>), dim3((unsigned)grid), block, lds, stream, a);
+    else hipLaunchKernelGGL((k_matvec_mfma<false, false>), dim3((unsigned)grid), block, lds, stream, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(op == Op::kDecompress ? "tq_decompress launch" : "tq_matvec launch", e);
@@ -1546,6 +1697,27 @@ bool ring_eligible(const tq_matrix* t, const void* x) {
 // As few launches as the kernel-argument size and the 32-bit cost line allow.
 int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream, bool ring = false,
                bool gate_up = false) {
+  if (op == Op::kMatvec) {
+    // The product kernels are built once per weight format: matrices of packed 4-bit weights and the others take
+    // separate launches.
+    int n_packed = 0;
+    for (int i = 0; i < n; ++i) n_packed += hs[i]->m.packing ? 1 : 0;
+    if (n_packed != 0 && n_packed != n) {
+      for (uint32_t want = 0; want < 2; ++want) {
+        std::vector<tq_handle> h2;
+        std::vector<const void*> x2;
+        std::vector<void*> y2;
+        for (int i = 0; i < n; ++i)
+          if ((hs[i]->m.packing ? 1u : 0u) == want) {
+            h2.push_back(hs[i]);
+            x2.push_back(xs[i]);
+            y2.push_back(ys[i]);
+          }
+        if (int rc = launch_all(op, (int)h2.size(), h2.data(), x2.data(), y2.data(), batch, stream, ring, gate_up)) return rc;
+      }
+      return TQ_OK;
+    }
+  }
   if (op == Op::kMatvec && batch > 1 && !ring && !gate_up) {   // (the ring kernel adds partial sums to y: no place for silu)
     // The matrices that can take the ring kernel go there, the others to the whole-strip kernel; the products are
     // independent, so regrouping them changes nothing but the launches.

@@ -108,7 +108,8 @@ class PairDict {
 int check_opts(const tq_encode_opts* o, uint32_t* max_entries, uint32_t* lmax, uint32_t* seg_cols, unsigned* n_threads) {
   *max_entries = (o && o->max_entries) ? o->max_entries : TQ_MAX_ENTRIES_DEVICE;
   *lmax = (o && o->lmax) ? o->lmax : TQ_DEFAULT_LMAX;
-  *seg_cols = (o && o->seg_cols) ? o->seg_cols : TQ_DEFAULT_SEG_COLS;
+  // (packed values: the same number of weights per segment by default)
+  *seg_cols = (o && o->seg_cols) ? o->seg_cols : (o && o->packing == TQ_PACK_NIBBLES) ? TQ_DEFAULT_SEG_COLS / 2 : TQ_DEFAULT_SEG_COLS;
   *n_threads = pick_threads(o ? o->n_threads : 0);
   if (*lmax < 1 || *lmax > TQ_MAX_LMAX) {
     set_error("tq_encode: lmax must be 0 (default), 1 or 2");
@@ -130,6 +131,14 @@ int check_opts(const tq_encode_opts* o, uint32_t* max_entries, uint32_t* lmax, u
     set_error("tq_encode: dictionary must be TQ_DICT_LZW or TQ_DICT_FREQUENCY");
     return TQ_E_INVALID_ARG;
   }
+  if (o && o->bits != 0 && (o->bits < 2 || o->bits > 8)) {
+    set_error("tq_encode: bits must be 0 (= 8) or in [2, 8]");
+    return TQ_E_INVALID_ARG;
+  }
+  if (o && o->packing > TQ_PACK_NIBBLES) {
+    set_error("tq_encode: packing must be TQ_PACK_NONE or TQ_PACK_NIBBLES");
+    return TQ_E_INVALID_ARG;
+  }
   return TQ_OK;
 }
 
@@ -140,6 +149,25 @@ struct UnitRange {
   std::vector<uint16_t> cnt;
 };
 
+// Two 4-bit values per byte (low nibble: the even column).  false if a value does not fit or the column count is odd.
+bool pack_nibbles(const std::vector<uint8_t>& Q, uint32_t rows, uint32_t cols, std::vector<uint8_t>* out) {
+  if (cols % 2) {
+    set_error("tq_encode: packing needs an even number of columns");
+    return false;
+  }
+  out->assign((size_t)rows * (cols / 2), 0);
+  for (size_t i = 0; i < out->size(); ++i) {
+    const int a = (int8_t)Q[2 * i], b = (int8_t)Q[2 * i + 1];
+    if (a < -8 || a > 7 || b < -8 || b > 7) {
+      set_error("tq_encode: packing takes values in [-8, 7]");
+      return false;
+    }
+    (*out)[i] = (uint8_t)((a & 15) | (b & 15) << 4);
+  }
+  return true;
+}
+
+// Q: the byte matrix rows x cols that is coded (for packing 1 the packed one).
 int encode_quantized_matrix(const std::vector<uint8_t>& Q, const std::vector<float>& scales_pad, uint32_t rows, uint32_t cols,
                             const tq_encode_opts* opts, void** blob_out, size_t* bytes_out) {
   uint32_t max_entries, lmax, seg_cols;
@@ -162,6 +190,7 @@ int encode_quantized_matrix(const std::vector<uint8_t>& Q, const std::vector<flo
   h.n_units = (uint64_t)h.n_bands * h.n_quads;
   h.lmax = lmax;
   h.max_entries = max_entries;
+  h.packing = opts ? opts->packing : 0;
   const uint64_t n_units = h.n_units;
 
   PairDict dict(max_entries, lmax);
@@ -328,22 +357,38 @@ extern "C" int tq_encode(const float* w, uint32_t rows, uint32_t cols, const tq_
     const uint32_t rows_pad = (uint32_t)round_up(rows, kUnitRows);
     std::vector<uint8_t> Q((size_t)rows * cols, 0);
     std::vector<float> scales(rows_pad, 0.f);
-    // Per row, in IEEE fp32 and in this order: amax = max|w|, s = amax / 127, q = clamp(rne(w / s), -127, 127).
+    // Per row, in IEEE fp32 and in this order: amax = max|w|, s = amax / qmax, q = clamp(rne(w / s), -qmax, qmax),
+    // qmax = 2^(bits - 1) - 1 (paper section 3: a fixed range of levels set by the number of bits; 127 at 8 bits).
+    if (opts && opts->bits != 0 && (opts->bits < 2 || opts->bits > 8)) {
+      set_error("tq_encode: bits must be 0 (= 8) or in [2, 8]");
+      return TQ_E_INVALID_ARG;
+    }
+    const bool packed = opts && opts->packing == TQ_PACK_NIBBLES;
+    if (packed && (opts->bits < 2 || opts->bits > 4)) {
+      set_error("tq_encode: TQ_PACK_NIBBLES takes bits 2..4");
+      return TQ_E_INVALID_ARG;
+    }
+    const float qmax = (float)((1u << ((opts && opts->bits ? opts->bits : 8u) - 1)) - 1u);
     parallel_for(rows, nt, [&](uint64_t rb, uint64_t re, unsigned) {
       for (uint64_t r = rb; r < re; ++r) {
         const float* row = w + r * cols;
         float amax = 0.f;
         for (uint32_t c = 0; c < cols; ++c) amax = std::max(amax, std::fabs(row[c]));
-        const float s = amax / 127.0f;
+        const float s = amax / qmax;
         scales[r] = s;
         if (!(s > 0.f)) continue;  // all-zero row: bytes stay 0
         for (uint32_t c = 0; c < cols; ++c) {
           float t = std::nearbyintf(row[c] / s);  // default rounding mode: to nearest, ties to even
-          t = std::min(127.0f, std::max(-127.0f, t));
+          t = std::min(qmax, std::max(-qmax, t));
           Q[r * cols + c] = (uint8_t)(int8_t)(int)t;
         }
       }
     });
+    if (packed) {
+      std::vector<uint8_t> P;
+      if (!pack_nibbles(Q, rows, cols, &P)) return TQ_E_INVALID_ARG;
+      return encode_quantized_matrix(P, scales, rows, cols / 2, opts, blob, blob_bytes);
+    }
     return encode_quantized_matrix(Q, scales, rows, cols, opts, blob, blob_bytes);
   } catch (const std::bad_alloc&) {
     set_error("tq_encode: out of host memory");
@@ -362,6 +407,11 @@ extern "C" int tq_encode_quantized(const int8_t* q, const float* scales_in, uint
     std::vector<uint8_t> Q((const uint8_t*)q, (const uint8_t*)q + (size_t)rows * cols);
     std::vector<float> scales(rows_pad, 0.f);
     std::copy(scales_in, scales_in + rows, scales.begin());
+    if (opts && opts->packing == TQ_PACK_NIBBLES) {
+      std::vector<uint8_t> P;
+      if (!pack_nibbles(Q, rows, cols, &P)) return TQ_E_INVALID_ARG;
+      return encode_quantized_matrix(P, scales, rows, cols / 2, opts, blob, blob_bytes);
+    }
     return encode_quantized_matrix(Q, scales, rows, cols, opts, blob, blob_bytes);
   } catch (const std::bad_alloc&) {
     set_error("tq_encode_quantized: out of host memory");

@@ -9,6 +9,10 @@
 // dictionary per matrix; a run never crosses a segment boundary, so every lane's code stream can be decoded
 // independently of the others (per-tile stream offsets).
 //
+// packing 1 (values of at most 4 bits): byte j of a row holds the values of columns 2j (bits 0..3) and 2j + 1 (bits 4..7)
+// in 4-bit two's complement; rows, cols, seg_cols and everything below describe that byte matrix, half as wide as the
+// weight matrix.
+//
 // Code section: for unit u the codes of its 64 lane streams are interleaved in chunks of 4 codes per lane:
 //   code k of lane l of unit u  ->  codes[(uoff[u] + k / 4) * 256 + l * 4 + k % 4]
 // Every lane stream of a unit is padded with pad codes (index n_entries, an empty entry) to the unit's length,
@@ -42,7 +46,7 @@ struct Header {
   uint32_t unit_rows, unit_panels, chunk_codes;
   uint32_t n_bands, n_panels, n_quads;    // ceil(rows / 16), ceil(cols / seg_cols), ceil(n_panels / 4)
   uint32_t n_entries, lmax, max_entries, pad_code;
-  uint32_t reserved0;
+  uint32_t packing;                       // 0: one value per byte; 1: two 4-bit values per byte (the matrix has 2 * cols columns)
   uint64_t n_units, n_chunks;             // n_bands * n_quads; total chunks of the code section
   uint64_t n_real_codes;                  // codes that are not padding
   uint64_t off_dict, dict_bytes;          // uint32 slot[n_entries + 1]: run bytes in bits 0..23, run length in BITS (8/16/24) in bits 24..31

@@ -362,6 +362,120 @@ def test_matrix_that_starts_a_dictionary_takes_the_careful_ring_mode(dev, ring_f
         m.close()
 
 
+@pytest.mark.parametrize("width", [6, 4, 2])
+def test_lower_quantization_widths_through_the_same_path(dev, ring_for_small_launches, width):
+    """Paper section 3: 6-, 4- and 2-bit (ternary) levels.  One value per byte, same container and kernels: the expansion
+    is the oracle's quantized matrix bit for bit, the products match its float64 definition."""
+    spec = small_case(272, 2048, seed=960 + width)
+    W = make_weights(spec)
+    Qo, so = O.quantize_rows(W, bits=width)
+    m = tq.Matrix(tq.tq_encode(W, bits=width))
+    try:
+        assert np.array_equal(gpu_decompress(m, dev), Qo)
+        for batch in (1, 3, 16):
+            bits, x = make_activations(spec, batch)
+            check_outputs(gpu_matvec(m, bits, dev), O.gemv_f64(Qo, so, x))
+    finally:
+        m.close()
+
+
+PACKED_CASES = [
+    # rows, cols, bits, seg_cols (bytes), dictionary
+    (64, 1024, 4, 64, "lzw"),            # whole units
+    (16, 32, 4, 16, "lzw"),              # one segment per row
+    (33, 600, 4, 32, "lzw"),             # ragged rows, last quad partly empty, cols / 2 not a multiple of 8
+    (17, 514, 3, 256, "lzw"),            # one-byte last panel
+    (272, 2048, 4, 128, "frequency"),    # the default segment width, several bands per wavefront
+    (100, 4096, 2, 128, "lzw"),          # ternary
+    (1027, 1536, 4, 128, "lzw"),         # more bands than wavefronts
+]
+
+
+@pytest.mark.parametrize("rows,cols,width,seg_cols,dictionary", PACKED_CASES)
+def test_packed_four_bit_weights(dev, rows, cols, width, seg_cols, dictionary):
+    """Two 4-bit values per stored byte: the expansion gives the oracle's quantized matrix bit for bit (one int8 per weight),
+    the products match its float64 definition, at batch 1 (fp8 dictionary image, two dot products per code) and at
+    batches on the MFMA kernel, with aligned and misaligned activations."""
+    spec = small_case(rows, cols, seed=970 + rows)
+    W = make_weights(spec)
+    Qo, so = O.quantize_rows(W, bits=width)
+    m = tq.Matrix(tq.tq_encode(W, bits=width, seg_cols=seg_cols, dictionary=dictionary, pack=True))
+    try:
+        assert m.info["packing"] == 1 and (m.info["rows"], m.info["cols"]) == (rows, cols)
+        assert np.array_equal(gpu_decompress(m, dev), Qo)
+        for batch in (1, 2, 5, 16):
+            bits, x = make_activations(spec, batch)
+            ref = O.gemv_f64(Qo, so, x)
+            check_outputs(gpu_matvec(m, bits, dev), ref)
+            check_outputs(gpu_matvec(m, bits, dev, misalign=True), ref)
+    finally:
+        m.close()
+
+
+def test_packed_weights_take_every_nibble_value(dev):
+    """All 16 nibble values, -8 included (the quantizer never makes it, a container may hold it): the batch-1 kernel's fp8
+    image and the MFMA kernel's conversion are exact for each."""
+    rng = np.random.default_rng(12)
+    Q = rng.integers(-8, 8, (48, 512), dtype=np.int8)
+    Q[0, :16] = np.arange(-8, 8)
+    s = (rng.random(48) + 0.5).astype(np.float32)
+    m = tq.Matrix(tq.tq_encode_quantized(Q, s, seg_cols=64, pack=True))
+    try:
+        assert np.array_equal(gpu_decompress(m, dev), Q)
+        spec = small_case(48, 512, seed=971)
+        for batch in (1, 4):
+            bits, x = make_activations(spec, batch)
+            check_outputs(gpu_matvec(m, bits, dev), O.gemv_f64(Q, s, x), tol=1e-5)
+        e = np.zeros((1, 512), np.float32)          # unit vectors: every column lands where it belongs
+        for j in (0, 1, 2, 15, 127, 128, 129, 511):
+            e[:] = 0
+            e[0, j] = 1.0
+            bits = (e.view(np.uint32) >> 16).astype(np.uint16)
+            y = gpu_matvec(m, bits, dev)
+            assert np.array_equal(y[0], s * Q[:, j].astype(np.float32)), j      # one fp32 product per row: exact
+    finally:
+        m.close()
+
+
+def test_one_call_with_packed_and_plain_matrices(dev):
+    shapes = [(192, 768, 4, True), (64, 768, 8, False), (64, 1024, 4, True), (48, 768, 6, False), (512, 768, 2, True)]
+    for batch in (1, 8):
+        mats, xs, ys, refs = [], [], [], []
+        for k, (r, c, width, pack) in enumerate(shapes):
+            spec = small_case(r, c, seed=980 + k)
+            W = make_weights(spec)
+            Qo, so = O.quantize_rows(W, bits=width)
+            mats.append(tq.Matrix(tq.tq_encode(W, bits=width, seg_cols=64, pack=pack)))
+            bits, x = make_activations(spec, batch)
+            refs.append(O.gemv_f64(Qo, so, x))
+            xs.append(torch.from_numpy(bits.view(np.int16).reshape(-1).copy()).to(dev))
+            ys.append(torch.full((batch, r), float("nan"), dtype=torch.float32, device=dev))
+        tq.tq_matvec_multi([m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch, _stream())
+        torch.cuda.synchronize()
+        for y, ref in zip(ys, refs):
+            check_outputs(y.cpu().numpy(), ref)
+        outs = [torch.full((r, c), 77, dtype=torch.int8, device=dev) for (r, c, _, _) in shapes]
+        tq.tq_decompress_multi([m.handle for m in mats], [o.data_ptr() for o in outs], _stream())
+        torch.cuda.synchronize()
+        for k, (r, c, width, _) in enumerate(shapes):
+            assert np.array_equal(outs[k].cpu().numpy(), O.quantize_rows(make_weights(small_case(r, c, seed=980 + k)), bits=width)[0])
+        for m in mats:
+            m.close()
+
+
+def test_packed_gate_up(dev):
+    sg, su = small_case(200, 768, seed=990), small_case(200, 768, seed=991)
+    Wg, Wu = make_weights(sg), make_weights(su)
+    m = tq.Matrix(tq.tq_encode_gate_up(Wg, Wu, bits=4, pack=True))
+    try:
+        for batch in (1, 6):
+            bits, x = make_activations(sg, batch)
+            ref = O.gate_up_f64(*O.quantize_rows(Wg, bits=4), *O.quantize_rows(Wu, bits=4), x)
+            check_outputs(_gpu_gate_up(m, bits, dev, 200), ref)
+    finally:
+        m.close()
+
+
 def _gpu_gate_up(m, bits, dev, rows):
     batch = bits.shape[0]
     x = torch.from_numpy(bits.view(np.int16).reshape(-1).copy()).to(dev)

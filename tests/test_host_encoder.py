@@ -103,10 +103,70 @@ def test_quantizer_ties_match_oracle():
     assert Q.tolist() == [[-127, 0, 62, 64, 127, 0, 2, 2]] and s.tolist() == [1.0]
 
 
+def test_lower_widths_give_the_oracles_container():
+    W = make_weights(small_case(48, 640, seed=17))
+    for bits, dictionary in ((6, "lzw"), (4, "lzw"), (2, "lzw"), (4, "frequency")):
+        blob = tq.tq_encode(W, seg_cols=64, bits=bits, dictionary=dictionary)
+        assert blob == O.build_blob(O.encode_matrix(W, seg_cols=64, bits=bits, dictionary=dictionary)), (bits, dictionary)
+        Q, s = O.decode_blob(blob)
+        Qo, so = O.quantize_rows(W, bits=bits)
+        assert np.array_equal(Q, Qo) and np.array_equal(s, so)
+    W4 = np.array([[-7.0, 0.0, 2.5, 3.5, 7.0, -6.5, 0.49, 6.51]], np.float32)
+    Q, s = O.decode_blob(tq.tq_encode(W4, bits=4))
+    assert Q.tolist() == [[-7, 0, 2, 4, 7, -6, 0, 7]] and s.tolist() == [1.0]
+    assert tq.tq_encode(W, seg_cols=64, bits=8) == tq.tq_encode(W, seg_cols=64) == tq.tq_encode(W, seg_cols=64, bits=0)
+
+
+def test_packed_containers_match_the_oracle():
+    W = make_weights(small_case(48, 640, seed=19))
+    for bits, dictionary, seg in ((4, "lzw", 64), (3, "lzw", 32), (2, "lzw", 16), (4, "frequency", 64)):
+        blob = tq.tq_encode(W, seg_cols=seg, bits=bits, dictionary=dictionary, pack=True)
+        assert blob == O.build_blob(O.encode_matrix(W, seg_cols=seg, bits=bits, dictionary=dictionary, pack=True)), (bits, dictionary)
+        info = tq.tq_validate_blob(blob)
+        assert info["packing"] == 1 and info["cols"] == 640 and info["rows"] == 48
+        Q, s = O.decode_blob(blob)
+        Qo, so = O.quantize_rows(W, bits=bits)
+        assert np.array_equal(Q, Qo) and np.array_equal(s, so)
+    # already quantized values, any nibble
+    rng = np.random.default_rng(5)
+    Q = rng.integers(-8, 8, (20, 96), dtype=np.int8)
+    s = (rng.random(20) + 0.5).astype(np.float32)
+    blob = tq.tq_encode_quantized(Q, s, seg_cols=16, pack=True)
+    assert blob == O.build_blob(_packed_encoded(Q, s, 16))
+    assert np.array_equal(O.decode_blob(blob)[0], Q)
+    assert tq.tq_validate_blob(tq.tq_encode(W, seg_cols=64))["packing"] == 0
+
+
+def _packed_encoded(Q, s, seg_cols):
+    e = O.encode_quantized(O.pack_nibbles(Q), s, seg_cols=seg_cols)
+    e.packing = 1
+    return e
+
+
+def test_packing_argument_errors():
+    W = np.zeros((4, 8), np.float32)
+    for kw in (dict(pack=True), dict(pack=True, bits=6), dict(pack=True, bits=8)):
+        with pytest.raises(tq.TqError) as ei:
+            tq.tq_encode(W, **kw)
+        assert ei.value.code == -1
+    with pytest.raises(tq.TqError):
+        tq.tq_encode(np.zeros((4, 7), np.float32), bits=4, pack=True)          # odd number of columns
+    with pytest.raises(tq.TqError):
+        tq.tq_encode_quantized(np.full((2, 4), 8, np.int8), np.ones(2, np.float32), pack=True)   # 8 does not fit 4 bits
+
+
+def test_four_bit_values_all_pair_up():
+    # 15 levels: every pair of neighbouring values gets a dictionary entry early on, so nearly every code stands for two weights
+    W = make_weights(small_case(256, 1024, seed=18))
+    info = tq.tq_validate_blob(tq.tq_encode(W, bits=4))
+    assert info["n_entries"] <= 256 + 15 * 15
+    assert 256 * 1024 / info["n_real_codes"] > 1.99
+
+
 def test_encode_argument_errors():
     W = np.zeros((4, 4), np.float32)
     for kw in (dict(max_entries=100), dict(max_entries=tq.TQ_MAX_ENTRIES_DEVICE + 1), dict(lmax=3),
-               dict(seg_cols=24), dict(seg_cols=2048)):
+               dict(seg_cols=24), dict(seg_cols=2048), dict(bits=1), dict(bits=9)):
         with pytest.raises(tq.TqError) as ei:
             tq.tq_encode(W, **kw)
         assert ei.value.code == -1

@@ -121,3 +121,51 @@ def test_gate_up_definition_on_textbook_values():
                         np.array([[1.0]], np.float32))
     assert abs(big[0, 0] - 127.0) < 1e-12 and abs(big[0, 1]) < 1e-12
     assert O.interleave_rows(np.array([[1], [2]]), np.array([[7], [8]])).ravel().tolist() == [1, 7, 2, 8]
+
+
+# ----- two 4-bit values per byte
+
+def test_nibble_packing_by_hand():
+    # column 2j in bits 0..3, column 2j + 1 in bits 4..7, 4-bit two's complement: -1 = 0xF, -8 = 0x8
+    Q = np.array([[1, 2, -1, 0, 7, -8, -7, 3]], np.int8)
+    P = O.pack_nibbles(Q)
+    assert P.dtype == np.int8 and P.shape == (1, 4)
+    assert P.view(np.uint8).tolist() == [[0x21, 0x0F, 0x87, 0x39]]
+    assert np.array_equal(O.unpack_nibbles(P), Q)
+
+
+def test_nibble_packing_round_trips_every_byte_and_rejects_what_does_not_fit():
+    P = np.arange(256, dtype=np.uint8).reshape(2, 128).view(np.int8)
+    Q = O.unpack_nibbles(P)
+    assert Q.shape == (2, 256) and Q.min() == -8 and Q.max() == 7
+    assert np.array_equal(O.pack_nibbles(Q), P)
+    for v in range(256):                                 # arithmetic definition of the two fields
+        lo, hi = int(Q.reshape(-1)[2 * v]), int(Q.reshape(-1)[2 * v + 1])
+        assert (lo % 16) + 16 * (hi % 16) == v
+    with pytest.raises(ValueError):
+        O.pack_nibbles(np.array([[8, 0]], np.int8))
+    with pytest.raises(ValueError):
+        O.pack_nibbles(np.array([[0, -9]], np.int8))
+    with pytest.raises(ValueError):
+        O.pack_nibbles(np.zeros((2, 3), np.int8))
+
+
+def test_packed_container_decodes_to_the_quantized_matrix_and_is_half_as_wide():
+    W = make_weights(small_case(40, 1000, seed=23))
+    for bits in (4, 3, 2):
+        e = O.encode_matrix(W, seg_cols=64, bits=bits, pack=True)
+        assert e.packing == 1 and e.cols == 500
+        blob = O.build_blob(e)
+        p = O.parse_blob(blob)
+        assert p["packing"] == 1 and p["cols"] == 500
+        Q, s = O.decode_blob(blob)
+        Qo, so = O.quantize_rows(W, bits=bits)
+        assert Q.shape == (40, 1000) and np.array_equal(Q, Qo) and np.array_equal(s, so)
+        _, x = make_activations(small_case(40, 1000, seed=23), 2)
+        assert np.array_equal(O.matvec_from_blob(blob, x), O.gemv_f64(Qo, so, x))
+    with pytest.raises(ValueError):
+        O.encode_matrix(W, bits=6, pack=True)
+    # more weights per code than one value per byte can reach (2)
+    packed, plain = O.parse_blob(O.build_blob(O.encode_matrix(W, bits=4, pack=True))), O.parse_blob(O.build_blob(O.encode_matrix(W, bits=4)))
+    assert W.size / packed["n_real_codes"] > 2.5 > 2.0 >= W.size / plain["n_real_codes"]
+    assert packed["n_real_codes"] < 0.8 * plain["n_real_codes"]
