@@ -51,6 +51,8 @@ def parse_args():
                          "most frequent byte pairs, the way the paper's section 4 picks table entries")
     ap.add_argument("--bits", type=int, default=8, choices=range(2, 9),
                     help="quantization width (paper section 3 tried 8, 6, 4, 2 and ternary); the headline is 8")
+    ap.add_argument("--pack", action="store_true",
+                    help="with --bits 2..4: two values per stored byte (a code then stands for up to four weights)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-layers", type=int, default=8,
                     help="layers of the sweep the CPU oracle is timed on (8 layers = 56 matrices take about 10 s on one core)")
@@ -159,6 +161,8 @@ def listing_leg(specs, dev, stream):
 
 def main():
     args = parse_args()
+    if args.pack and args.bits > 4:
+        sys.exit("--pack takes --bits 2..4")
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path is a single-GPU kernel; DESIGN.md says how it "
               "would shard). Run with --gpus 1.", file=sys.stderr)
@@ -185,7 +189,7 @@ def main():
     workers = max(1, min(args.threads, 8))
     inner = max(1, args.threads // workers)
     opts = dict(max_entries=args.max_entries, lmax=args.lmax, seg_cols=args.seg_cols, dictionary=args.dictionary_kind,
-                bits=0 if args.bits == 8 else args.bits)
+                bits=0 if args.bits == 8 else args.bits, pack=args.pack)
     # One LZW dictionary over the sequence: the matrices are encoded one after the other, each starting from the
     # dictionary the previous one ended with, until the dictionary is full (Gaussian weights fill it inside the first
     # matrix) or the first layer is through; from then on it is frozen at the size it has reached, so the remaining
@@ -363,7 +367,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16 activations x int8 weights, fp32 accumulate",
+        "dtype": f"bf16 activations x {'int8' if args.bits == 8 else str(args.bits) + '-bit'} weights, fp32 accumulate",
         "data": "synthetic",
         "tokens_per_s": round(args.batch / (wall_ms * 1e-3), 1),
         "config": {
@@ -372,7 +376,7 @@ def main():
             "bytes_per_weight": round(comp_bytes / n_weights, 4), "weights_per_code": round(n_weights / n_codes, 4),
             "weights_per_real_code": round(n_weights / sum(i["n_real_codes"] for i in infos), 4),
             "dictionary_entries": infos[-1]["n_entries"], "lmax": infos[0]["lmax"], "seg_cols": infos[0]["seg_cols"],
-            "dictionary": args.dictionary, "dictionary_kind": args.dictionary_kind, "bits": args.bits, "fuse": args.fuse, "kernel_launches_per_step": n_launches,
+            "dictionary": args.dictionary, "dictionary_kind": args.dictionary_kind, "bits": args.bits, "packing": "nibbles" if args.pack else "none", "fuse": args.fuse, "kernel_launches_per_step": n_launches,
             "hip_graph": bool(args.graph),
         },
         "roofline": {
