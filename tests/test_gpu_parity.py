@@ -255,12 +255,14 @@ def test_decompress_multi_is_bit_exact(dev):
         m.close()
 
 
-def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows(dev):
+@pytest.mark.parametrize("width,pack", [(8, False), (4, True)])
+def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows(dev, width, pack):
     """Config-4 shapes at full size (one 3B layer plus lm_head 128256 x 3072), encoded as bench.py encodes them (one
     dictionary over the sequence, default options) and launched as bench.py launches them (all matrices in one
     tq_matvec_multi / tq_decompress_multi call), batch 1, 8 and 16 (dot-product kernel, ring kernel with 10 and with 8
     wavefronts: the call brings 9,744 bands, enough for the ring kernel).  The oracle computes sampled rows one by one:
-    quantization is per row, so the sampled rows of Q and their float64 products need only those rows of W."""
+    quantization is per row, so the sampled rows of Q and their float64 products need only those rows of W.
+    Second case: the same shapes as packed 4-bit weights (bench.py --bits 4 --pack)."""
     from inputs import config_matrices
     specs = [s for s in config_matrices(4) if s.name.startswith("L00.") or s.name == "lm_head"]
     assert len(specs) == 8 and specs[-1].rows == 128256
@@ -269,15 +271,18 @@ def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows
     prev = None
     for spec in specs:
         W = make_weights(spec)
-        prev = tq.tq_encode(W, dict_from=prev)
+        prev = tq.tq_encode(W, dict_from=prev, bits=0 if width == 8 else width, pack=pack)
         mats.append(tq.Matrix(prev))
         rows = np.unique(np.concatenate([[0, 15, 16, spec.rows - 17, spec.rows - 1], rng.integers(0, spec.rows, 59)]))
-        Qs, ss = O.quantize_rows(W[rows])
+        Qs, ss = O.quantize_rows(W[rows], bits=width)
         picks.append(rows)
         q_ref.append(Qs)
         s_ref.append(ss)
         del W
-    assert mats[0].info["n_entries"] == tq.TQ_MAX_ENTRIES_DEVICE and mats[-1].info["seg_cols"] == 256
+    if pack:
+        assert all(m.info["packing"] == 1 and m.info["seg_cols"] == 128 for m in mats)
+    else:
+        assert mats[0].info["n_entries"] == tq.TQ_MAX_ENTRIES_DEVICE and mats[-1].info["seg_cols"] == 256
     handles = [m.handle for m in mats]
     try:
         outs = [torch.full((sp.rows, sp.cols), 77, dtype=torch.int8, device=dev) for sp in specs]
@@ -287,7 +292,7 @@ def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows
             assert np.array_equal(o[torch.from_numpy(rows).to(dev)].cpu().numpy(), Qs)
         assert int((outs[-1] == 77).sum()) < outs[-1].numel() // 100      # nothing left unwritten (77 is an ordinary value too)
         del outs
-        assert all(m.info["lane_spread"] <= 113 for m in mats)   # none of them needs the whole-strip kernel
+        assert pack or all(m.info["lane_spread"] <= 113 for m in mats)   # none of them needs the whole-strip kernel
         for batch in (1, 8, 16):
             xs, ys, xf = [], [], []
             for sp in specs:
