@@ -145,6 +145,9 @@ int tq_create_from_encoded(const void *blob, size_t blob_bytes, tq_handle *out);
  * whole-strip kernel, which decodes a unit into an LDS tile before it multiplies it.  The ring kernel adds the partial
  * sums of a row's later quads (groups of 4 segments) to y with atomic adds, always in the same order; y must not be
  * read or written by anything else on the device while the call runs (true of any output buffer).
+ * Containers of packed 4-bit weights (TQ_PACK_NIBBLES): cols is the number of weights per row, twice the stored bytes;
+ * batch 1 runs the dot-product kernel with four weights per dictionary entry, batch 2..16 the same two MFMA kernels
+ * (the ring kernel then takes segments of at most 128 bytes).
  */
 int tq_matvec(tq_handle h, const void *x, void *y, int batch, void *stream);
 

@@ -15,6 +15,9 @@
 //      a strip holding the whole segment (k_matvec_mfma: multiplied when the unit is complete; k_decompress: copied
 //      out row-major).
 // The expanded matrix never exists in HBM on the tq_matvec path.
+// Containers of packed 4-bit weights (two per stored byte) take the same decode; what changes is the dequantization:
+// four fp8 weights per dictionary word and two dot products per code at batch 1, nibbles expanded to bf16 ahead of the
+// MFMA in the batched kernels, nibbles expanded to int8 in the copy-out of tq_decompress.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -846,7 +849,7 @@ __device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, glo
 // value, so nothing waits for it) for the others.  The stores and adds to a given y element are issued in quad order,
 // one workgroup barrier apart from each other, so the result does not depend on timing.
 // Needs rows of a whole number of units (a multiple of 4 * seg_cols columns), segments of 32..256 columns in
-// multiples of 32, and 16-byte aligned activations.
+// multiples of 32 (packed 4-bit weights: 32..128 bytes), and 16-byte aligned activations.
 constexpr int kRingBytes = 128;
 constexpr int kRingWaves = 8;       // with an activation tile of 16 batch rows
 constexpr int kRingWavesHalf = 10;  // with one of 8 batch rows (batches up to 8): more wavefronts fit next to the smaller tile
@@ -886,7 +889,9 @@ typedef __attribute__((address_space(3))) const u32x4 lds_cu128;
 // (window w is 16 kRows w bytes further).  on_unit(band, next_band, sums) is called with a unit's 16 x 16 sums after its
 // last MFMA step; next_band is the band that follows (claimed a piece of chunks ahead), or kNoBand.
 constexpr uint32_t kNoBand = 0xFFFFFFFFu;
-template <bool kCareful, int kRows, typename Claim, typename OnUnit>
+// kPacked: the ring holds packed 4-bit weights; an 8-byte piece is then two MFMA steps (16 columns), and the activation
+// tile has two windows per piece.
+template <bool kCareful, int kRows, bool kPacked, typename Claim, typename OnUnit>
 __device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t quad, uint32_t first_band, Claim&& claim, int lane, uint32_t ring,
                                                   uint32_t xfrag, OnUnit&& on_unit) {
   if (first_band == kNoBand) return;
@@ -943,20 +948,28 @@ __device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t quad
   auto multiply_ready = [&]() {
     const uint32_t at = min(done, n_win8 - 8 * kG);   // at the unit's end: any place inside the ring and the tile
     const uint32_t base = at ^ sw8;
-    const uint32_t xa = xfrag + at * (2 * kRows);   // 16 kRows bytes per window
+    constexpr int kX = kPacked ? 2 : 1;             // activation windows per 8-byte piece of the ring
+    const uint32_t xa = xfrag + at * (2 * kRows * kX);   // 16 kRows bytes per window
     u32x2 a8[kG];
-    u32x4 x8[kG];
+    u32x4 x8[kG * kX];
 #pragma unroll
     for (int k = 0; k < kG; ++k) {
       a8[k] = *(volatile lds_cu64*)(size_t)(ring | ((base ^ (8u * k)) & 0x78u));
-      x8[k] = *(volatile lds_cu128*)(size_t)(xa + 16 * kRows * k);
+#pragma unroll
+      for (int h = 0; h < kX; ++h) x8[k * kX + h] = *(volatile lds_cu128*)(size_t)(xa + 16 * kRows * (k * kX + h));
     }
     const uint32_t next = done + 8 * kG;
     if (next > n_win8) return;
     if (__builtin_amdgcn_ballot_w64(pos < min(seg_len, next)) != 0) return;
 #pragma unroll
-    for (int k = 0; k < kG; ++k)
-      part[k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8[k].x, a8[k].y)), __builtin_bit_cast(bf16x8, x8[k]), part[k], 0, 0, 0);
+    for (int k = 0; k < kG; ++k) {
+      if constexpr (kPacked) {
+        part[k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(nib8_to_bf16x8(a8[k].x), __builtin_bit_cast(bf16x8, x8[2 * k]), part[k], 0, 0, 0);
+        part[k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(nib8_to_bf16x8(a8[k].y), __builtin_bit_cast(bf16x8, x8[2 * k + 1]), part[k], 0, 0, 0);
+      } else {
+        part[k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i8x8_to_bf16x8(make_uint2(a8[k].x, a8[k].y)), __builtin_bit_cast(bf16x8, x8[k]), part[k], 0, 0, 0);
+      }
+    }
     done = next;
   };
   auto decode_piece = [&](const uint2 (&cw)[kP], uint32_t n, bool ends, uint2 (&cw_next)[kP], uint32_t next_start, uint32_t next_n) {
@@ -1006,7 +1019,7 @@ __device__ __forceinline__ void decode_units_ring(const DevMat& m, uint32_t quad
   }
 }
 
-template <int kWaves, int kRows>
+template <int kWaves, int kRows, bool kPacked>
 __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec_ring(MatvecArgs a) {
   constexpr int kRingThreads = kWaves * 64;
   constexpr uint32_t kRingXTile = ring_x_tile(kRows);
@@ -1029,7 +1042,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec_ring(MatvecArgs a) {
     const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
     const uint32_t band_hi = hi >= ce ? m.n_bands : min(m.n_bands, (hi - cb + bc / 2) / bc);
     if (band_lo >= band_hi) continue;
-    const uint32_t nq = m.n_quads, n_win = m.seg_cols / 8;
+    constexpr uint32_t pk = kPacked ? 2u : 1u;             // columns of the weight matrix per stored byte
+    const uint32_t nq = m.n_quads, n_win = pk * m.seg_cols / 8;   // activation windows (8 columns) per segment
     __syncthreads();   // the previous matrix's dictionary and activation tile are no longer in use
     if (m.dict != staged) {
       // 16-bit image of the dictionary: the run bytes of every entry (the length follows from the code)
@@ -1069,12 +1083,12 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec_ring(MatvecArgs a) {
     const uint32_t pieces = kUnitPanels * n_win * kRows, per_row = kUnitPanels * n_win;
     u32x4 tile[kTileRegs];
     auto request_tile = [&](uint32_t q) {
-      const uint32_t col0 = q * kUnitPanels * m.seg_cols;
+      const uint32_t col0 = q * kUnitPanels * pk * m.seg_cols;
 #pragma unroll
       for (int k = 0; k < kTileRegs; ++k) {
         const uint32_t o = min((uint32_t)tid + k * kRingThreads, pieces - 1);
         const uint32_t r = o / per_row, c = o - r * per_row;   // batch row, 8-column piece of the quad
-        tile[k] = *(global_cu128*)((global_cu16*)job.x + (size_t)min(r, (uint32_t)a.batch - 1) * m.cols + col0 + 8 * c);
+        tile[k] = *(global_cu128*)((global_cu16*)job.x + (size_t)min(r, (uint32_t)a.batch - 1) * (pk * m.cols) + col0 + 8 * c);
       }
     };
     auto commit_tile = [&]() {
@@ -1116,8 +1130,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec_ring(MatvecArgs a) {
         }
         request_scales(next_band);
       };
-      if (m.reserved == 2) decode_units_ring<true, kRows>(m, q, band0, claim, lane, ring, xfrag, finish_unit);
-      else decode_units_ring<false, kRows>(m, q, band0, claim, lane, ring, xfrag, finish_unit);
+      if (m.reserved == 2) decode_units_ring<true, kRows, kPacked>(m, q, band0, claim, lane, ring, xfrag, finish_unit);
+      else decode_units_ring<false, kRows, kPacked>(m, q, band0, claim, lane, ring, xfrag, finish_unit);
     }
   }
 }
@@ -1503,7 +1517,6 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   m.seg_magic = (uint32_t)((1ull << 32) / h.seg_cols) + 1;   // exact quotient while col * seg_cols < 2^32
   m.reserved = facts.max_lane_spread <= kRingSpread ? 1u : facts.max_lane_spread <= kRingSpreadCareful ? 2u : 0u;
   m.packing = h.packing;
-  if (h.packing) m.reserved = 0;   // the ring kernel takes one weight per byte
   if (h.cols > (1u << 20)) {
     set_error("more than 2^20 columns are not supported");
     return TQ_E_UNSUPPORTED;
@@ -1542,8 +1555,10 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWaves, 16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesHalf, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWaves, 16, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesHalf, 8, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWaves, 16, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesHalf, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
 
   const uint8_t* src = (const uint8_t*)blob;
@@ -1654,8 +1669,11 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
       set_error("internal: ring launch with a dictionary or activations that do not fit it");
       return TQ_E_UNSUPPORTED;
     }
-    if (half) hipLaunchKernelGGL((k_matvec_ring<kRingWavesHalf, 8>), dim3((unsigned)grid), dim3(kRingWavesHalf * 64), lds, stream, a);
-    else hipLaunchKernelGGL((k_matvec_ring<kRingWaves, 16>), dim3((unsigned)grid), dim3(kRingWaves * 64), lds, stream, a);
+    const bool packed = hs[0]->m.packing != 0;
+    if (half && packed) hipLaunchKernelGGL((k_matvec_ring<kRingWavesHalf, 8, true>), dim3((unsigned)grid), dim3(kRingWavesHalf * 64), lds, stream, a);
+    else if (half) hipLaunchKernelGGL((k_matvec_ring<kRingWavesHalf, 8, false>), dim3((unsigned)grid), dim3(kRingWavesHalf * 64), lds, stream, a);
+    else if (packed) hipLaunchKernelGGL((k_matvec_ring<kRingWaves, 16, true>), dim3((unsigned)grid), dim3(kRingWaves * 64), lds, stream, a);
+    else hipLaunchKernelGGL((k_matvec_ring<kRingWaves, 16, false>), dim3((unsigned)grid), dim3(kRingWaves * 64), lds, stream, a);
   } else {
     // Tile decode.  LDS: 16-bit dictionary image | one tile (64 strips) per wavefront, which the batched product reuses
     // for its partial sums (per wavefront two slots of 1 KB and their two band numbers).
@@ -1692,8 +1710,9 @@ uint64_t ring_min_bands_per_cu() {
 
 bool ring_eligible(const tq_matrix* t, const void* x) {
   const DevMat& m = t->m;
+  const uint32_t seg_weights = (m.packing ? 2u : 1u) * m.seg_cols;   // what the activation tile of a quad is sized by
   return m.reserved != 0 && m.cols % (kUnitPanels * m.seg_cols) == 0 && m.seg_cols % (8 * kRingGroup) == 0 &&
-         m.seg_cols <= kRingMaxSeg && (uintptr_t)x % 16 == 0 &&
+         seg_weights <= kRingMaxSeg && (uintptr_t)x % 16 == 0 &&
          round_up((uint64_t)m.dict_words * 2, kRingBytes) + (size_t)kRingWaves * 64 * kRingBytes + ring_x_tile(16) + 128 <= kLdsLimit;
 }
 

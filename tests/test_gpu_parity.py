@@ -417,6 +417,38 @@ def test_packed_four_bit_weights(dev, rows, cols, width, seg_cols, dictionary):
         m.close()
 
 
+def test_packed_weights_on_the_ring_kernel(dev, ring_for_small_launches):
+    """Whole units of packed bytes with the lanes close together: aligned activations take the ring kernel (two MFMA steps
+    per 8-byte piece), misaligned ones the whole-strip kernel; both match the oracle.  The first matrix starts its
+    dictionary (lanes further apart: careful mode or whole strips), the others inherit a full one."""
+    first_spec = small_case(256, 1024, seed=995)
+    first = tq.tq_encode(make_weights(first_spec), bits=4, seg_cols=64, pack=True)
+    cases = [(first_spec, first)]
+    for rows, cols, seg in [(200, 2048, 128), (1000, 512, 64), (96, 1024, 128), (40, 256, 32)]:
+        spec = small_case(rows, cols, seed=996 + rows)
+        cases.append((spec, tq.tq_encode(make_weights(spec), bits=4, seg_cols=seg, pack=True, dict_from=first)))
+    spreads = []
+    for spec, blob in cases:
+        info = tq.tq_validate_blob(blob)
+        spreads.append(info["lane_spread"])
+        assert (spec.cols // 2) % (4 * info["seg_cols"]) == 0
+        Qo, so = O.quantize_rows(make_weights(spec), bits=4)
+        m = tq.Matrix(blob)
+        try:
+            for batch in (2, 5, 8, 16):
+                bits, x = make_activations(spec, batch)
+                ref = O.gemv_f64(Qo, so, x)
+                ring = gpu_matvec(m, bits, dev)
+                strip = gpu_matvec(m, bits, dev, misalign=True)
+                check_outputs(ring, ref)
+                check_outputs(strip, ref)
+                assert np.abs(ring - strip).max() <= 1e-5 * np.abs(ref).max()
+                assert np.array_equal(ring, gpu_matvec(m, bits, dev))
+        finally:
+            m.close()
+    assert min(spreads[1:]) <= RING_SPREAD_LIMIT, spreads       # at least these run in groups of four pieces
+
+
 def test_packed_weights_take_every_nibble_value(dev):
     """All 16 nibble values, -8 included (the quantizer never makes it, a container may hold it): the batch-1 kernel's fp8
     image and the MFMA kernel's conversion are exact for each."""
