@@ -255,17 +255,20 @@ def test_decompress_multi_is_bit_exact(dev):
         m.close()
 
 
-@pytest.mark.parametrize("width,pack", [(8, False), (4, True)])
-def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows(dev, width, pack):
+@pytest.mark.parametrize("config,width,pack,batches", [(4, 8, False, (1, 8, 16)), (4, 4, True, (1, 8, 16)),
+                                                       (5, 8, False, (16,)), (3, 8, False, (1,)), (2, 8, False, (1,))])
+def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows(dev, config, width, pack, batches):
     """Config-4 shapes at full size (one 3B layer plus lm_head 128256 x 3072), encoded as bench.py encodes them (one
     dictionary over the sequence, default options) and launched as bench.py launches them (all matrices in one
     tq_matvec_multi / tq_decompress_multi call), batch 1, 8 and 16 (dot-product kernel, ring kernel with 10 and with 8
     wavefronts: the call brings 9,744 bands, enough for the ring kernel).  The oracle computes sampled rows one by one:
     quantization is per row, so the sampled rows of Q and their float64 products need only those rows of W.
-    Second case: the same shapes as packed 4-bit weights (bench.py --bits 4 --pack)."""
+    Second case: the same shapes as packed 4-bit weights (bench.py --bits 4 --pack).  Then config 5 (the same shapes with
+    Student-t weights, batch 16, and the expansion of every matrix), config 3 (one LLaMA-3.2-1B layer plus its lm_head
+    128256 x 2048) and config 2 (the 1B layer alone: a launch too small for the ring kernel)."""
     from inputs import config_matrices
-    specs = [s for s in config_matrices(4) if s.name.startswith("L00.") or s.name == "lm_head"]
-    assert len(specs) == 8 and specs[-1].rows == 128256
+    specs = [s for s in config_matrices(config) if config == 2 or s.name.startswith("L00.") or s.name == "lm_head"]
+    assert len(specs) == (7 if config == 2 else 8) and (config == 2 or specs[-1].rows == 128256)
     rng = np.random.default_rng(77)
     mats, picks, q_ref, s_ref = [], [], [], []
     prev = None
@@ -282,7 +285,7 @@ def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows
     if pack:
         assert all(m.info["packing"] == 1 and m.info["seg_cols"] == 128 for m in mats)
     else:
-        assert mats[0].info["n_entries"] == tq.TQ_MAX_ENTRIES_DEVICE and mats[-1].info["seg_cols"] == 256
+        assert mats[-1].info["n_entries"] == tq.TQ_MAX_ENTRIES_DEVICE and mats[-1].info["seg_cols"] == 256
     handles = [m.handle for m in mats]
     try:
         outs = [torch.full((sp.rows, sp.cols), 77, dtype=torch.int8, device=dev) for sp in specs]
@@ -292,8 +295,9 @@ def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows
             assert np.array_equal(o[torch.from_numpy(rows).to(dev)].cpu().numpy(), Qs)
         assert int((outs[-1] == 77).sum()) < outs[-1].numel() // 100      # nothing left unwritten (77 is an ordinary value too)
         del outs
-        assert pack or all(m.info["lane_spread"] <= 113 for m in mats)   # none of them needs the whole-strip kernel
-        for batch in (1, 8, 16):
+        if config == 4 and not pack:
+            assert all(m.info["lane_spread"] <= 113 for m in mats)   # none of them needs the whole-strip kernel
+        for batch in batches:
             xs, ys, xf = [], [], []
             for sp in specs:
                 bits, x = make_activations(sp, batch)
