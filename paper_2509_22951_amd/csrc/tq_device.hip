@@ -853,6 +853,7 @@ __device__ __forceinline__ f32x4 multiply_unit(f32x4 acc, uint32_t my_strip, glo
 constexpr int kRingBytes = 128;
 constexpr int kRingWaves = 8;       // with an activation tile of 16 batch rows
 constexpr int kRingWavesHalf = 10;  // with one of 8 batch rows (batches up to 8): more wavefronts fit next to the smaller tile
+constexpr int kRingWavesMore = 12;  // the same beside a dictionary of at most 24,512 entries
 constexpr int kRingPiece = 12;    // chunks per piece of the code stream (two register sets)
 constexpr int kRingStep = 4;      // chunks between two looks at the lanes' progress
 constexpr int kRingGroup = 4;     // MFMA steps per group
@@ -1559,6 +1560,8 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesHalf, 8, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWaves, 16, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesHalf, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesMore, 8, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesMore, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
 
   const uint8_t* src = (const uint8_t*)blob;
@@ -1662,7 +1665,8 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     a.x_off = (uint32_t)dict16;
     a.tile_area = 64 * kRingBytes;
     const bool half = batch <= 8;   // 8 batch rows in the tile: room for two more wavefronts
-    const int waves = half ? kRingWavesHalf : kRingWaves;
+    const bool more = half && dict16 + (size_t)kRingWavesMore * a.tile_area + ring_x_tile(8) + 128 <= kLdsLimit;   // a smaller dictionary leaves room
+    const int waves = more ? kRingWavesMore : half ? kRingWavesHalf : kRingWaves;
     a.slot_off = (uint32_t)(dict16 + (size_t)waves * a.tile_area);
     const size_t lds = a.slot_off + ring_x_tile(half ? 8 : 16) + 128;   // + the band counter
     if (lds > kLdsLimit || !x_fast) {
@@ -1670,7 +1674,9 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
       return TQ_E_UNSUPPORTED;
     }
     const bool packed = hs[0]->m.packing != 0;
-    if (half && packed) hipLaunchKernelGGL((k_matvec_ring<kRingWavesHalf, 8, true>), dim3((unsigned)grid), dim3(kRingWavesHalf * 64), lds, stream, a);
+    if (more && packed) hipLaunchKernelGGL((k_matvec_ring<kRingWavesMore, 8, true>), dim3((unsigned)grid), dim3(kRingWavesMore * 64), lds, stream, a);
+    else if (more) hipLaunchKernelGGL((k_matvec_ring<kRingWavesMore, 8, false>), dim3((unsigned)grid), dim3(kRingWavesMore * 64), lds, stream, a);
+    else if (half && packed) hipLaunchKernelGGL((k_matvec_ring<kRingWavesHalf, 8, true>), dim3((unsigned)grid), dim3(kRingWavesHalf * 64), lds, stream, a);
     else if (half) hipLaunchKernelGGL((k_matvec_ring<kRingWavesHalf, 8, false>), dim3((unsigned)grid), dim3(kRingWavesHalf * 64), lds, stream, a);
     else if (packed) hipLaunchKernelGGL((k_matvec_ring<kRingWaves, 16, true>), dim3((unsigned)grid), dim3(kRingWaves * 64), lds, stream, a);
     else hipLaunchKernelGGL((k_matvec_ring<kRingWaves, 16, false>), dim3((unsigned)grid), dim3(kRingWaves * 64), lds, stream, a);
