@@ -40,6 +40,7 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kDotWavesPacked = 12;  // the same kernel for packed 4-bit weights: more work per byte read, more wavefronts to
                                      // hide it (config 4, ms per step: 8 wavefronts 0.379, 12 0.370, 16 0.379)
 constexpr int kDotWavesMax = 12;
+constexpr int kDotPiecePacked = 6;   // its units are half as long (segments of 128 bytes: 17 chunks, three pieces of 5 or 6)
 constexpr int kDotWaves = 8;         // wavefronts per workgroup of the batch-1 kernel (measured on the 3B sweep, TB/s:
                                      // 6 waves 4.61, 8 waves 5.12, 10 waves 4.64, 12 waves 4.90, 16 waves 4.28)
 constexpr int kDotPiece = 8;         // chunks per piece in the batch-1 kernel: two pieces (16 x 512 bytes) are in flight per
@@ -1550,7 +1551,7 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   }
   // Dynamic LDS above 64 KB has to be allowed per kernel function.
   e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWavesPacked, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_decompress, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
@@ -1656,7 +1657,7 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
       return TQ_E_UNSUPPORTED;
     }
     // (all matrices of a product launch hold their weights the same way: launch_all sees to that)
-    if (hs[0]->m.packing) hipLaunchKernelGGL((k_matvec<kDotPiece, kDotWavesPacked, true>), dim3((unsigned)grid), dim3(kDotWavesPacked * 64), lds_total, stream, a);
+    if (hs[0]->m.packing) hipLaunchKernelGGL((k_matvec<kDotPiecePacked, kDotWavesPacked, true>), dim3((unsigned)grid), dim3(kDotWavesPacked * 64), lds_total, stream, a);
     else hipLaunchKernelGGL((k_matvec<kDotPiece, kDotWaves, false>), dim3((unsigned)grid), dim3(kDotWaves * 64), lds_total, stream, a);
   } else if (ring) {
     // LDS: 16-bit dictionary image | one ring per lane (aligned to its size: the kernel ORs piece offsets into its
