@@ -23,10 +23,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # HBM traffic of the matvec launches measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the default workload
-# (config 4, batch 1, default encoder options, whole sweep in one tq_matvec_multi call), scaled by a plain 1 GiB copy in
+# (config 4, batch 1, default encoder options, whole sweep as one prepared step = one kernel launch), scaled by a plain 1 GiB copy in
 # the same run (profiles/k_matvec_config4_batch1_hbm_traffic.txt): bytes read per algorithmic byte, bytes written per step.
-MEASURED_FETCH_PER_ALGORITHMIC_BYTE = 1.0040
-MEASURED_WRITE_BYTES_PER_STEP = 3_628_000
+MEASURED_FETCH_PER_ALGORITHMIC_BYTE = 1.0030
+MEASURED_WRITE_BYTES_PER_STEP = 3_618_000
 
 
 def parse_args():
@@ -67,6 +67,8 @@ def parse_args():
                          "products (each has its own activation vector), so all of them go to tq_matvec_multi at once; "
                          "layer: one tq_matvec_multi per transformer layer; independent: only products that a real layer "
                          "computes from the same input (q,k,v and gate,up) share a launch; none: one tq_matvec per matrix")
+    ap.add_argument("--no-prepared-step", action="store_true",
+                    help="launch through tq_matvec_multi (at most 128 matrices per kernel launch) instead of a prepared tq_step")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and replay it (takes the host's launch cost out of plans with many launches)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -262,17 +264,24 @@ def main():
             cur = [i]
     groups.append(cur)
 
+    launches = [0]   # kernel launches per step relative to tq_matvec_multi's, for the batch run last
+
     def run(batch, steps, warmup):
         xs, ys = make_io(batch)
         calls = []
+        launches[0] = 0
         for g in groups:
             if len(g) == 1:
                 m, xp, yp = mats[g[0]], xs[g[0]].data_ptr(), ys[g[0]].data_ptr()
                 calls.append(lambda m=m, xp=xp, yp=yp: m.matvec(xp, yp, batch, stream))
-            else:
+            elif args.no_prepared_step:
                 mc = tq.MultiCall([mats[i].handle for i in g], [xs[i].data_ptr() for i in g],
                                   [ys[i].data_ptr() for i in g], batch)
                 calls.append(lambda mc=mc: mc.launch(stream))
+            else:   # the same products as a prepared step: buffers fixed, jobs in device memory, up to 896 matrices per launch
+                st = tq.Step([mats[i].handle for i in g], [xs[i].data_ptr() for i in g], [ys[i].data_ptr() for i in g], batch)
+                launches[0] += st.info["n_launches"] - (-(-len(g) // 128))
+                calls.append(lambda st=st: st.launch(stream))
 
         def eager_step():
             for c in calls:
@@ -289,6 +298,7 @@ def main():
                 for g in groups:     # the same calls, issued on the capturing stream
                     tq.tq_matvec_multi([mats[i].handle for i in g], [xs[i].data_ptr() for i in g],
                                        [ys[i].data_ptr() for i in g], batch, cap)
+                launches[0] = 0
             step = graph.replay
 
         for _ in range(warmup):
@@ -313,6 +323,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     wall_ms, ev_ms = run(args.batch, args.steps, args.warmup)
+    launch_delta = launches[0]
     others = {}
     if args.also_batch and args.also_batch != args.batch:
         w2, e2 = run(args.also_batch, max(3, args.steps // 2), args.warmup)
@@ -349,9 +360,11 @@ def main():
     if not args.no_gate_up:
         gate_up = gate_up_leg(specs, mats, prev if args.dictionary == "sequence" else None, opts, args, dev, stream)
 
-    n_launches = sum(-(-len(g) // 128) for g in groups)     # tq_matvec_multi serves up to 128 matrices per kernel launch
+    # tq_matvec_multi serves up to 128 matrices per kernel launch; a prepared step may need fewer launches (or more,
+    # where the matrices of a group go to different kernels)
+    n_launches = sum(-(-len(g) // 128) for g in groups) + launch_delta
     profiled = (args.config == 4 and args.batch == 1 and args.fuse == "sweep" and args.dictionary == "sequence"
-                and args.dictionary_kind == "lzw" and args.bits == 8
+                and args.dictionary_kind == "lzw" and args.bits == 8 and not args.no_prepared_step and not args.graph
                 and not (args.max_entries or args.lmax or args.seg_cols or args.layers))
     gbps = comp_bytes / wall_ms / 1e6
     ach = comp_bytes / ev_ms / 1e6
@@ -376,7 +389,8 @@ def main():
             "bytes_per_weight": round(comp_bytes / n_weights, 4), "weights_per_code": round(n_weights / n_codes, 4),
             "weights_per_real_code": round(n_weights / sum(i["n_real_codes"] for i in infos), 4),
             "dictionary_entries": infos[-1]["n_entries"], "lmax": infos[0]["lmax"], "seg_cols": infos[0]["seg_cols"],
-            "dictionary": args.dictionary, "dictionary_kind": args.dictionary_kind, "bits": args.bits, "packing": "nibbles" if args.pack else "none", "fuse": args.fuse, "kernel_launches_per_step": n_launches,
+            "dictionary": args.dictionary, "dictionary_kind": args.dictionary_kind, "bits": args.bits, "packing": "nibbles" if args.pack else "none", "fuse": args.fuse, "prepared_step": not args.no_prepared_step and not args.graph,
+            "kernel_launches_per_step": n_launches,
             "hip_graph": bool(args.graph),
         },
         "roofline": {

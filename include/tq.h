@@ -181,6 +181,33 @@ int tq_matvec_gate_up(tq_handle h, const void *x, void *y, int batch, void *stre
 int tq_matvec_gate_up_multi(int n, const tq_handle *hs, const void *const *xs, void *const *ys, int batch, void *stream);
 
 /*
+ * A prepared step: tq_matvec_multi (flags 0) or tq_matvec_gate_up_multi (TQ_STEP_GATE_UP) for a fixed set of matrices and
+ * buffers, with everything but the stream decided once - for a decode loop that runs the same products on the same
+ * buffers token after token (the layer-by-layer use of the compressed parameters in the paper's Background "Inference").
+ * tq_step_create does what those calls do before they launch (argument checks, which kernel takes which matrix, the
+ * split of the work) and copies the list of (matrix description, x, y) to device memory, which it allocates
+ * (n * 104 bytes; synchronous, not for the hot path).  A launch that reads its matrices from that table serves up to
+ * 896 of them where the kernel arguments hold 128: a whole decode step of a model becomes one kernel launch.
+ * tq_step_launch only launches: no allocation, no synchronisation, nothing of the step is changed, so it may be
+ * captured in a HIP graph and the same step may run on several streams (they write the same y).  Results are those of
+ * the calls it stands for, up to the order of fp32 additions where the work is split differently.
+ * The matrices, x and y must outlive the step and keep their addresses; x and y are read and written at every launch.
+ * Errors as for tq_matvec_multi; tq_step_destroy(NULL) is a no-op; no launch of the step may be in flight when it is
+ * destroyed.
+ */
+#define TQ_STEP_GATE_UP 1u
+typedef struct tq_step *tq_step_handle;
+typedef struct tq_step_info {
+  uint32_t n_matrices, n_launches; /* kernel launches one tq_step_launch makes */
+  uint64_t table_bytes;            /* device memory the step holds */
+} tq_step_info;
+int tq_step_create(int n, const tq_handle *hs, const void *const *xs, void *const *ys, int batch, uint32_t flags,
+                   tq_step_handle *out);
+int tq_step_launch(tq_step_handle s, void *stream);
+int tq_step_get_info(tq_step_handle s, tq_step_info *out);
+int tq_step_destroy(tq_step_handle s);
+
+/*
  * Un-fused form: expand the whole matrix (paper section 4, Listing "Decompressing Model Weights").
  *   out: device, int8 [rows][cols] row-major, fully overwritten, bit-exact quantized weights.
  * Same asynchrony rules as tq_matvec.

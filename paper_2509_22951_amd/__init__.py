@@ -33,4 +33,10 @@ from .binding import (  # noqa: F401
     tq_encode_gate_up,
     tq_matvec_gate_up,
     tq_matvec_gate_up_multi,
+    TQ_STEP_GATE_UP,
+    Step,
+    tq_step_create,
+    tq_step_launch,
+    tq_step_get_info,
+    tq_step_destroy,
 )

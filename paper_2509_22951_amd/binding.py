@@ -20,6 +20,7 @@ EXPORTS = [
     "tq_encode", "tq_encode_quantized", "tq_free_blob", "tq_validate_blob", "tq_create_from_encoded", "tq_matvec",
     "tq_matvec_multi", "tq_decompress", "tq_decompress_multi", "tq_get_info", "tq_destroy", "tq_last_error_string",
     "tq_encode_gate_up", "tq_matvec_gate_up", "tq_matvec_gate_up_multi",
+    "tq_step_create", "tq_step_launch", "tq_step_get_info", "tq_step_destroy",
     "tq_listing_build_table", "tq_listing_compress", "tq_listing_create", "tq_listing_decompress", "tq_listing_get_info",
     "tq_listing_destroy",
 ]
@@ -36,6 +37,10 @@ class TqEncodeOpts(ctypes.Structure):
                 ("seg_cols", ctypes.c_uint32), ("dict_from", ctypes.c_void_p), ("dict_from_bytes", ctypes.c_uint64),
                 ("dictionary", ctypes.c_uint32), ("bits", ctypes.c_uint32), ("packing", ctypes.c_uint32),
                 ("reserved", ctypes.c_uint32)]
+
+
+class TqStepInfo(ctypes.Structure):
+    _fields_ = [("n_matrices", ctypes.c_uint32), ("n_launches", ctypes.c_uint32), ("table_bytes", ctypes.c_uint64)]
 
 
 class TqInfo(ctypes.Structure):
@@ -93,6 +98,14 @@ def load() -> ctypes.CDLL:
     lib.tq_matvec_gate_up_multi.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
     lib.tq_matvec_multi.restype = ci
     lib.tq_matvec_multi.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
+    lib.tq_step_create.restype = ci
+    lib.tq_step_create.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, u32, ctypes.POINTER(vp)]
+    lib.tq_step_launch.restype = ci
+    lib.tq_step_launch.argtypes = [vp, vp]
+    lib.tq_step_get_info.restype = ci
+    lib.tq_step_get_info.argtypes = [vp, ctypes.POINTER(TqStepInfo)]
+    lib.tq_step_destroy.restype = ci
+    lib.tq_step_destroy.argtypes = [vp]
     lib.tq_decompress.restype = ci
     lib.tq_decompress.argtypes = [vp, vp, vp]
     lib.tq_decompress_multi.restype = ci
@@ -235,6 +248,53 @@ class MultiCall:
 
 def tq_matvec_multi(handles, x_ptrs, y_ptrs, batch: int, stream: int = 0) -> None:
     MultiCall(handles, x_ptrs, y_ptrs, batch).launch(stream)
+
+
+TQ_STEP_GATE_UP = 1
+
+
+def tq_step_create(handles, x_ptrs, y_ptrs, batch: int, flags: int = 0) -> int:
+    n = len(handles)
+    assert n == len(x_ptrs) == len(y_ptrs) and n >= 1
+    arr = ctypes.c_void_p * n
+    out = ctypes.c_void_p()
+    _check(load().tq_step_create(n, arr(*handles), arr(*x_ptrs), arr(*y_ptrs), batch, flags, ctypes.byref(out)))
+    return out.value
+
+
+def tq_step_launch(step: int, stream: int = 0) -> None:
+    _check(load().tq_step_launch(step, stream))
+
+
+def tq_step_get_info(step: int) -> dict:
+    info = TqStepInfo()
+    _check(load().tq_step_get_info(step, ctypes.byref(info)))
+    return {n: int(getattr(info, n)) for n, _ in info._fields_}
+
+
+def tq_step_destroy(step) -> None:
+    _check(load().tq_step_destroy(step))
+
+
+class Step:
+    """Owning wrapper around a prepared step (marshalling only): tq_matvec_multi for fixed matrices and buffers."""
+
+    def __init__(self, handles, x_ptrs, y_ptrs, batch: int, gate_up: bool = False):
+        self.handle = tq_step_create(handles, x_ptrs, y_ptrs, batch, TQ_STEP_GATE_UP if gate_up else 0)
+        self.info = tq_step_get_info(self.handle)
+
+    def launch(self, stream: int = 0) -> None:
+        tq_step_launch(self.handle, stream)
+
+    def close(self) -> None:
+        h, self.handle = self.handle, None
+        tq_step_destroy(h)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def tq_decompress(handle: int, out_ptr: int, stream: int = 0) -> None:

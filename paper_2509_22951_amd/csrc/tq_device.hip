@@ -76,16 +76,32 @@ struct Job {
   float* y;                // fp32 [batch][rows]
 };
 
+// A job together with its matrix description, as a prepared step keeps them in device memory.
+struct StepEntry {
+  DevMat m;
+  const uint16_t* x;
+  float* y;
+};
+constexpr int kMaxStep = 896;        // matrices one launch can serve when the jobs come from a device table
+
 // The launch's cost line: matrix i covers [cost[i], cost[i + 1]), one band of it costs its number of columns.
+// The jobs travel in the kernel arguments (up to kMaxMulti of them) or, for a prepared step, sit in a table in device
+// memory (up to kMaxStep); the cost line is in the arguments either way, at the same place.
 struct MatvecArgs {
   int n, batch;
   uint32_t x_off, slot_off;   // byte offsets in LDS of the activation image (or of the tiles) and of the partial-sum slots
   uint32_t tile_area;         // bytes of LDS per wavefront in the tile kernels (the same for every matrix of the launch)
   uint32_t gate_up;           // 1: rows 2r and 2r + 1 are a gate and an up projection; y[b][r] = silu(row 2r) * (row 2r + 1)
-  uint32_t cost[kMaxMulti + 1];
-  Job j[kMaxMulti];
-  DevMat first[kInlineDescriptions];   // descriptions of the first matrices by value: a launch of one matrix (or of a
-                                       // few) does not wait for a read of device memory before it can start loading
+  const StepEntry* table;     // device table of the n jobs, or null: then j and first below hold them
+  union {
+    struct {
+      uint32_t cost[kMaxMulti + 1];
+      Job j[kMaxMulti];
+      DevMat first[kInlineDescriptions];   // descriptions of the first matrices by value: a launch of one matrix (or of a
+                                           // few) does not wait for a read of device memory before it can start loading
+    } in;
+    uint32_t cost_long[kMaxStep + 1];
+  } u;
 };
 static_assert(sizeof(MatvecArgs) <= 4096, "kernel arguments");
 
@@ -144,6 +160,30 @@ __device__ __forceinline__ DevMat load_description(const DevMat* p) {
   DevMat m;
   __builtin_memcpy(&m, w, sizeof m);
   return m;
+}
+
+// Point i of the launch's cost line (the two forms of the arguments keep it at the same place).
+__device__ __forceinline__ uint32_t cost_at(const MatvecArgs& a, int i) { return a.u.cost_long[i]; }
+
+// Job i of the launch and the description of its matrix: from the kernel arguments, or from the step's device table
+// (scalar loads, like the descriptions the arguments do not hold by value).
+__device__ __forceinline__ void fetch_job(const MatvecArgs& a, int i, Job& job, DevMat& m) {
+  if (a.table) {
+    const StepEntry* e = a.table + i;
+    static_assert(sizeof(StepEntry) % 4 == 0, "whole dwords");
+    uint32_t w[sizeof(StepEntry) / 4];
+#pragma unroll
+    for (size_t k = 0; k < sizeof(StepEntry) / 4; ++k) w[k] = ((const_u32*)e)[k];
+    StepEntry v;
+    __builtin_memcpy(&v, w, sizeof v);
+    m = v.m;
+    job.m = &e->m;
+    job.x = v.x;
+    job.y = v.y;
+  } else {
+    job = a.u.in.j[i];
+    m = i < kInlineDescriptions ? a.u.in.first[i] : load_description(job.m);
+  }
 }
 
 // Byte address inside LDS of a pointer into the workgroup's dynamic shared memory.
@@ -360,14 +400,15 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
   int* slot_band = (int*)(slot_val + 2 * kWaves * 16);               // [2 * kWaves]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   if (lds_address(lds4) != 0) return;   // the code -> word lookup takes the dictionary to start at LDS address 0 (no static LDS here)
-  const uint64_t total = a.cost[a.n];
+  const uint64_t total = cost_at(a, a.n);
   const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
   const uint32_t* staged = nullptr;
   for (int i = 0; i < a.n; ++i) {
-    const uint32_t cb = a.cost[i], ce = a.cost[i + 1];
+    const uint32_t cb = cost_at(a, i), ce = cost_at(a, i + 1);
     if (hi <= cb || lo >= ce) continue;
-    const Job job = a.j[i];
-    const DevMat m = i < kInlineDescriptions ? a.first[i] : load_description(job.m);
+    Job job;
+    DevMat m;
+    fetch_job(a, i, job, m);
     // a band goes to the share that holds its middle
     const uint32_t bc = m.cols;
     const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
@@ -1030,16 +1071,17 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec_ring(MatvecArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   if (lds_address(lds4) != 0) return;   // the code -> entry lookup takes the dictionary to start at LDS address 0
   const uint32_t rings = a.x_off, xtile = a.slot_off;   // LDS addresses (the LDS segment starts at 0)
-  const uint64_t total = a.cost[a.n];
+  const uint64_t total = cost_at(a, a.n);
   const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
   const uint32_t* staged = nullptr;
   const int bn = lane & 15, kg = lane >> 4;   // B operand: batch row and k-group (panel) of this lane
   const uint32_t ring = rings + (uint32_t)wave * (64 * kRingBytes) + (uint32_t)lane * kRingBytes;
   for (int i = 0; i < a.n; ++i) {
-    const uint32_t cb = a.cost[i], ce = a.cost[i + 1];
+    const uint32_t cb = cost_at(a, i), ce = cost_at(a, i + 1);
     if (hi <= cb || lo >= ce) continue;
-    const Job job = a.j[i];
-    const DevMat m = i < kInlineDescriptions ? a.first[i] : load_description(job.m);
+    Job job;
+    DevMat m;
+    fetch_job(a, i, job, m);
     const uint32_t bc = m.cols;
     const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
     const uint32_t band_hi = hi >= ce ? m.n_bands : min(m.n_bands, (hi - cb + bc / 2) / bc);
@@ -1146,15 +1188,16 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_threads = blockDim.x, n_waves = n_threads >> 6;
   if (lds_address(lds4) != 0) return;   // the code -> entry lookup takes the dictionary to start at LDS address 0
-  const uint64_t total = a.cost[a.n];
+  const uint64_t total = cost_at(a, a.n);
   const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
   const uint32_t* staged = nullptr;
   const int bn = lane & 15, kg = lane >> 4;   // B operand: batch row and k-group of this lane
   for (int i = 0; i < a.n; ++i) {
-    const uint32_t cb = a.cost[i], ce = a.cost[i + 1];
+    const uint32_t cb = cost_at(a, i), ce = cost_at(a, i + 1);
     if (hi <= cb || lo >= ce) continue;
-    const Job job = a.j[i];
-    const DevMat m = i < kInlineDescriptions ? a.first[i] : load_description(job.m);
+    Job job;
+    DevMat m;
+    fetch_job(a, i, job, m);
     const uint32_t bc = m.cols;
     const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
     const uint32_t band_hi = hi >= ce ? m.n_bands : min(m.n_bands, (hi - cb + bc / 2) / bc);
@@ -1291,14 +1334,15 @@ __global__ __launch_bounds__(kThreads, 1) void k_decompress(MatvecArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_threads = blockDim.x, n_waves = n_threads >> 6;
   if (lds_address(lds4) != 0) return;   // the code -> entry lookup takes the dictionary to start at LDS address 0
-  const uint64_t total = a.cost[a.n];
+  const uint64_t total = cost_at(a, a.n);
   const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
   const uint32_t* staged = nullptr;
   for (int i = 0; i < a.n; ++i) {
-    const uint32_t cb = a.cost[i], ce = a.cost[i + 1];
+    const uint32_t cb = cost_at(a, i), ce = cost_at(a, i + 1);
     if (hi <= cb || lo >= ce) continue;
-    const Job job = a.j[i];
-    const DevMat m = i < kInlineDescriptions ? a.first[i] : load_description(job.m);
+    Job job;
+    DevMat m;
+    fetch_job(a, i, job, m);
     const uint32_t bc = m.cols;
     const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
     const uint32_t band_hi = hi >= ce ? m.n_bands : min(m.n_bands, (hi - cb + bc / 2) / bc);
@@ -1614,26 +1658,61 @@ namespace {
 
 enum class Op { kMatvec, kDecompress };
 
-// One kernel launch for hs[0..n), n <= kMaxMulti, all on one device, total cost below 2^32.
+// A kernel launch with everything but the stream decided.
+struct PreparedLaunch {
+  MatvecArgs a;
+  const void* kernel;
+  unsigned grid, block;
+  size_t lds;
+  size_t table_first;   // prepared steps: index of the launch's first job in the step's table
+  const char* what;
+};
+
+// Launches recorded for a prepared step instead of being started, and the jobs they will read from device memory.
+struct Recorder {
+  std::vector<PreparedLaunch> launches;
+  std::vector<StepEntry> entries;
+};
+
+int fire(const PreparedLaunch& p, hipStream_t stream) {
+  MatvecArgs a = p.a;
+  void* args[] = {&a};
+  hipError_t e = hipLaunchKernel(p.kernel, dim3(p.grid), dim3(p.block), args, p.lds, stream);
+  if (e == hipSuccess) e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(p.what, e);
+  return TQ_OK;
+}
+
+// One kernel launch for hs[0..n), all on one device, total cost below 2^32; n <= kMaxMulti, or n <= kMaxStep when the
+// launch is recorded for a prepared step (rec: its jobs then go to the step's device table, not into the arguments).
 // kMatvec: xs/ys are the activations and outputs; kDecompress: ys are the int8 output matrices, xs is not used.
 // ring: the batched product with a ring per lane (every matrix of the call has passed ring_eligible).
 int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream, bool ring = false,
-           bool gate_up = false) {
-  MatvecArgs a;
+           bool gate_up = false, Recorder* rec = nullptr) {
+  PreparedLaunch p;
+  MatvecArgs& a = p.a;
+  std::memset(&a, 0, sizeof a);
   a.n = n;
   a.batch = batch;
   a.tile_area = 0;
   a.gate_up = gate_up ? 1u : 0u;
+  p.table_first = rec ? rec->entries.size() : 0;
+  p.what = op == Op::kDecompress ? "tq_decompress launch" : "tq_matvec launch";
+  a.table = rec ? (const StepEntry*)(uintptr_t)8 : nullptr;   // (the address follows when the step's table is in device memory)
   uint32_t dict_words_max = 0, x_dwords_max = 0, seg_max = 0;
   uint64_t cost = 0, bands = 0, band_cost_max = 1;
   bool x_fast = true;
   for (int i = 0; i < n; ++i) {
     const tq_matrix* t = hs[i];
-    a.j[i].m = t->m_dev;
-    if (i < kInlineDescriptions) a.first[i] = t->m;
-    a.j[i].x = xs ? (const uint16_t*)xs[i] : nullptr;
-    a.j[i].y = (float*)ys[i];
-    a.cost[i] = (uint32_t)cost;
+    if (rec) {
+      rec->entries.push_back(StepEntry{t->m, xs ? (const uint16_t*)xs[i] : nullptr, (float*)ys[i]});
+    } else {
+      a.u.in.j[i].m = t->m_dev;
+      if (i < kInlineDescriptions) a.u.in.first[i] = t->m;
+      a.u.in.j[i].x = xs ? (const uint16_t*)xs[i] : nullptr;
+      a.u.in.j[i].y = (float*)ys[i];
+    }
+    a.u.cost_long[i] = (uint32_t)cost;
     cost += (uint64_t)t->m.n_bands * t->m.cols;   // a band costs its 16 x cols weights, counted in units of 16
     bands += t->m.n_bands;
     band_cost_max = std::max<uint64_t>(band_cost_max, t->m.cols);
@@ -1642,23 +1721,22 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     seg_max = std::max(seg_max, t->m.seg_cols);
     x_fast = x_fast && (t->m.packing ? 2 : 1) * t->m.cols % 8 == 0 && xs && (uintptr_t)xs[i] % 16 == 0;
   }
-  a.cost[n] = (uint32_t)cost;
+  a.u.cost_long[n] = (uint32_t)cost;
   if (cost > 0xFFFFFFFFull) {
     set_error("more than 2^36 weights in one launch are not supported");
     return TQ_E_UNSUPPORTED;
   }
   // Every workgroup's share of the cost line is at least one band of the most expensive kind, and there is one
   // workgroup per CU at most.
-  const uint64_t grid = std::max<uint64_t>(1, std::min<uint64_t>({(uint64_t)hs[0]->n_cu, bands, cost / band_cost_max}));
+  p.grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>({(uint64_t)hs[0]->n_cu, bands, cost / band_cost_max}));
+  const bool packed = hs[0]->m.packing != 0;   // (all matrices of a product launch hold their weights the same way: launch_all sees to that)
   if (op == Op::kMatvec && batch == 1) {
-    size_t lds_total;
-    if (!plan_matvec_lds(dict_words_max, x_dwords_max, &a.x_off, &a.slot_off, &lds_total)) {
-      set_error("the matrices of this call together need " + std::to_string(lds_total) + " bytes of LDS (largest dictionary plus longest row)");
+    if (!plan_matvec_lds(dict_words_max, x_dwords_max, &a.x_off, &a.slot_off, &p.lds)) {
+      set_error("the matrices of this call together need " + std::to_string(p.lds) + " bytes of LDS (largest dictionary plus longest row)");
       return TQ_E_UNSUPPORTED;
     }
-    // (all matrices of a product launch hold their weights the same way: launch_all sees to that)
-    if (hs[0]->m.packing) hipLaunchKernelGGL((k_matvec<kDotPiecePacked, kDotWavesPacked, true>), dim3((unsigned)grid), dim3(kDotWavesPacked * 64), lds_total, stream, a);
-    else hipLaunchKernelGGL((k_matvec<kDotPiece, kDotWaves, false>), dim3((unsigned)grid), dim3(kDotWaves * 64), lds_total, stream, a);
+    p.kernel = packed ? (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true> : (const void*)k_matvec<kDotPiece, kDotWaves, false>;
+    p.block = (packed ? kDotWavesPacked : kDotWaves) * 64;
   } else if (ring) {
     // LDS: 16-bit dictionary image | one ring per lane (aligned to its size: the kernel ORs piece offsets into its
     // address) | the activation tile of one quad.
@@ -1669,18 +1747,15 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     const bool more = half && dict16 + (size_t)kRingWavesMore * a.tile_area + ring_x_tile(8) + 128 <= kLdsLimit;   // a smaller dictionary leaves room
     const int waves = more ? kRingWavesMore : half ? kRingWavesHalf : kRingWaves;
     a.slot_off = (uint32_t)(dict16 + (size_t)waves * a.tile_area);
-    const size_t lds = a.slot_off + ring_x_tile(half ? 8 : 16) + 128;   // + the band counter
-    if (lds > kLdsLimit || !x_fast) {
+    p.lds = a.slot_off + ring_x_tile(half ? 8 : 16) + 128;   // + the band counter
+    if (p.lds > kLdsLimit || !x_fast) {
       set_error("internal: ring launch with a dictionary or activations that do not fit it");
       return TQ_E_UNSUPPORTED;
     }
-    const bool packed = hs[0]->m.packing != 0;
-    if (more && packed) hipLaunchKernelGGL((k_matvec_ring<kRingWavesMore, 8, true>), dim3((unsigned)grid), dim3(kRingWavesMore * 64), lds, stream, a);
-    else if (more) hipLaunchKernelGGL((k_matvec_ring<kRingWavesMore, 8, false>), dim3((unsigned)grid), dim3(kRingWavesMore * 64), lds, stream, a);
-    else if (half && packed) hipLaunchKernelGGL((k_matvec_ring<kRingWavesHalf, 8, true>), dim3((unsigned)grid), dim3(kRingWavesHalf * 64), lds, stream, a);
-    else if (half) hipLaunchKernelGGL((k_matvec_ring<kRingWavesHalf, 8, false>), dim3((unsigned)grid), dim3(kRingWavesHalf * 64), lds, stream, a);
-    else if (packed) hipLaunchKernelGGL((k_matvec_ring<kRingWaves, 16, true>), dim3((unsigned)grid), dim3(kRingWaves * 64), lds, stream, a);
-    else hipLaunchKernelGGL((k_matvec_ring<kRingWaves, 16, false>), dim3((unsigned)grid), dim3(kRingWaves * 64), lds, stream, a);
+    if (more) p.kernel = packed ? (const void*)k_matvec_ring<kRingWavesMore, 8, true> : (const void*)k_matvec_ring<kRingWavesMore, 8, false>;
+    else if (half) p.kernel = packed ? (const void*)k_matvec_ring<kRingWavesHalf, 8, true> : (const void*)k_matvec_ring<kRingWavesHalf, 8, false>;
+    else p.kernel = packed ? (const void*)k_matvec_ring<kRingWaves, 16, true> : (const void*)k_matvec_ring<kRingWaves, 16, false>;
+    p.block = (unsigned)waves * 64;
   } else {
     // Tile decode.  LDS: 16-bit dictionary image | one tile (64 strips) per wavefront, which the batched product reuses
     // for its partial sums (per wavefront two slots of 1 KB and their two band numbers).
@@ -1694,17 +1769,17 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     a.x_off = (uint32_t)dict16;
     a.tile_area = (uint32_t)area;
     a.slot_off = 0;
-    const size_t lds = dict16 + waves * area;
-    const dim3 block((unsigned)waves * 64);
-    if (op == Op::kDecompress) hipLaunchKernelGGL(k_decompress, dim3((unsigned)grid), block, lds, stream, a);
-    else if (hs[0]->m.packing && x_fast) hipLaunchKernelGGL((k_matvec_mfma<true, true>), dim3((unsigned)grid), block, lds, stream, a);
-    else if (hs[0]->m.packing) hipLaunchKernelGGL((k_matvec_mfma<false, true>), dim3((unsigned)grid), block, lds, stream, a);
-    else if (x_fast) hipLaunchKernelGGL((k_matvec_mfma<true, false>), dim3((unsigned)grid), block, lds, stream, a);
-    else hipLaunchKernelGGL((k_matvec_mfma<false, false>), dim3((unsigned)grid), block, lds, stream, a);
+    p.lds = dict16 + waves * area;
+    p.block = (unsigned)waves * 64;
+    if (op == Op::kDecompress) p.kernel = (const void*)k_decompress;
+    else if (packed) p.kernel = x_fast ? (const void*)k_matvec_mfma<true, true> : (const void*)k_matvec_mfma<false, true>;
+    else p.kernel = x_fast ? (const void*)k_matvec_mfma<true, false> : (const void*)k_matvec_mfma<false, false>;
   }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return hip_fail(op == Op::kDecompress ? "tq_decompress launch" : "tq_matvec launch", e);
-  return TQ_OK;
+  if (rec) {
+    rec->launches.push_back(p);
+    return TQ_OK;
+  }
+  return fire(p, stream);
 }
 
 // Whether the batched product of this matrix can keep a ring per lane instead of the whole strip.
@@ -1725,7 +1800,8 @@ bool ring_eligible(const tq_matrix* t, const void* x) {
 
 // As few launches as the kernel-argument size and the 32-bit cost line allow.
 int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream, bool ring = false,
-               bool gate_up = false) {
+               bool gate_up = false, Recorder* rec = nullptr) {
+  const int per_launch = rec ? kMaxStep : kMaxMulti;
   if (op == Op::kMatvec) {
     // The product kernels are built once per weight format: matrices of packed 4-bit weights and the others take
     // separate launches.
@@ -1742,7 +1818,7 @@ int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* c
             x2.push_back(xs[i]);
             y2.push_back(ys[i]);
           }
-        if (int rc = launch_all(op, (int)h2.size(), h2.data(), x2.data(), y2.data(), batch, stream, ring, gate_up)) return rc;
+        if (int rc = launch_all(op, (int)h2.size(), h2.data(), x2.data(), y2.data(), batch, stream, ring, gate_up, rec)) return rc;
       }
       return TQ_OK;
     }
@@ -1760,7 +1836,7 @@ int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* c
         ring_bands += hs[i]->m.n_bands;
       }
     if (ring_bands < ring_min_bands_per_cu() * hs[0]->n_cu) n_ring = 0;
-    if (n_ring == n) return launch_all(op, n, hs, xs, ys, batch, stream, true);
+    if (n_ring == n) return launch_all(op, n, hs, xs, ys, batch, stream, true, false, rec);
     if (n_ring > 0) {
       std::vector<tq_handle> h2[2];
       std::vector<const void*> x2[2];
@@ -1771,18 +1847,18 @@ int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* c
         x2[g].push_back(xs[i]);
         y2[g].push_back(ys[i]);
       }
-      if (int rc = launch_all(op, (int)h2[1].size(), h2[1].data(), x2[1].data(), y2[1].data(), batch, stream, true)) return rc;
+      if (int rc = launch_all(op, (int)h2[1].size(), h2[1].data(), x2[1].data(), y2[1].data(), batch, stream, true, false, rec)) return rc;
       n = (int)h2[0].size();
       for (int i = 0; i < n;) {   // the rest, below, with the vectors alive
         int k = 0;
         uint64_t cost = 0;
-        while (i + k < n && k < kMaxMulti) {
+        while (i + k < n && k < per_launch) {
           const uint64_t c = (uint64_t)h2[0][i + k]->m.n_bands * h2[0][i + k]->m.cols;
           if (k > 0 && cost + c > 0xFFFFFFFFull) break;
           cost += c;
           ++k;
         }
-        if (int rc = launch(op, k, h2[0].data() + i, x2[0].data() + i, y2[0].data() + i, batch, stream, false)) return rc;
+        if (int rc = launch(op, k, h2[0].data() + i, x2[0].data() + i, y2[0].data() + i, batch, stream, false, false, rec)) return rc;
         i += k;
       }
       return TQ_OK;
@@ -1791,13 +1867,13 @@ int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* c
   for (int i = 0; i < n;) {
     int k = 0;
     uint64_t cost = 0;
-    while (i + k < n && k < kMaxMulti) {
+    while (i + k < n && k < per_launch) {
       const uint64_t c = (uint64_t)hs[i + k]->m.n_bands * hs[i + k]->m.cols;
       if (k > 0 && cost + c > 0xFFFFFFFFull) break;
       cost += c;
       ++k;
     }
-    if (int rc = launch(op, k, hs + i, xs ? xs + i : nullptr, ys + i, batch, stream, ring, gate_up)) return rc;
+    if (int rc = launch(op, k, hs + i, xs ? xs + i : nullptr, ys + i, batch, stream, ring, gate_up, rec)) return rc;
     i += k;
   }
   return TQ_OK;
@@ -1866,6 +1942,91 @@ extern "C" int tq_matvec_gate_up(tq_handle h, const void* x, void* y, int batch,
     return TQ_E_INVALID_ARG;
   }
   return tq_matvec_gate_up_multi(1, &h, &x, &y, batch, stream);
+}
+
+// A prepared step: the launches tq_matvec_multi (or tq_matvec_gate_up_multi) would make for these matrices and buffers,
+// decided once, with the jobs in a device table so that one launch can serve up to kMaxStep matrices.
+struct tq_step {
+  std::vector<PreparedLaunch> launches;
+  StepEntry* table_dev;
+  size_t n_entries;
+  int n_matrices;
+};
+
+extern "C" int tq_step_create(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, uint32_t flags,
+                              tq_step_handle* out) {
+  if (!out) {
+    set_error("tq_step_create: null output pointer");
+    return TQ_E_INVALID_ARG;
+  }
+  *out = nullptr;
+  if (n < 1 || !hs || !xs || !ys || (flags & ~TQ_STEP_GATE_UP)) {
+    set_error("tq_step_create: null argument, n < 1 or unknown flag");
+    return TQ_E_INVALID_ARG;
+  }
+  if (int rc = check_call("tq_step_create", n, hs, xs, ys, batch)) return rc;
+  const bool gate_up = (flags & TQ_STEP_GATE_UP) != 0;
+  if (gate_up)
+    for (int i = 0; i < n; ++i)
+      if (hs[i]->m.rows % 2) {
+        set_error("tq_step_create: the matrix at index " + std::to_string(i) + " has an odd number of rows");
+        return TQ_E_INVALID_ARG;
+      }
+  try {
+    Recorder rec;
+    if (int rc = launch_all(Op::kMatvec, n, hs, xs, ys, batch, nullptr, false, gate_up, &rec)) return rc;
+    tq_step* s = new tq_step;
+    s->launches = std::move(rec.launches);
+    s->n_entries = rec.entries.size();
+    s->n_matrices = n;
+    s->table_dev = nullptr;
+    hipError_t e = hipMalloc((void**)&s->table_dev, rec.entries.size() * sizeof(StepEntry));
+    if (e == hipSuccess) e = hipMemcpy(s->table_dev, rec.entries.data(), rec.entries.size() * sizeof(StepEntry), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      if (s->table_dev) (void)hipFree(s->table_dev);
+      delete s;
+      if (e == hipErrorOutOfMemory) {
+        set_error("tq_step_create: out of device memory");
+        return TQ_E_OOM;
+      }
+      return hip_fail("tq_step_create", e);
+    }
+    for (PreparedLaunch& p : s->launches) p.a.table = s->table_dev + p.table_first;
+    *out = s;
+    return TQ_OK;
+  } catch (const std::bad_alloc&) {
+    set_error("tq_step_create: out of host memory");
+    return TQ_E_OOM;
+  }
+}
+
+extern "C" int tq_step_launch(tq_step_handle s, void* stream) {
+  if (!s) {
+    set_error("tq_step_launch: null step");
+    return TQ_E_INVALID_ARG;
+  }
+  for (const PreparedLaunch& p : s->launches)
+    if (int rc = fire(p, (hipStream_t)stream)) return rc;
+  return TQ_OK;
+}
+
+extern "C" int tq_step_get_info(tq_step_handle s, tq_step_info* out) {
+  if (!s || !out) {
+    set_error("tq_step_get_info: null argument");
+    return TQ_E_INVALID_ARG;
+  }
+  out->n_matrices = (uint32_t)s->n_matrices;
+  out->n_launches = (uint32_t)s->launches.size();
+  out->table_bytes = (uint64_t)s->n_entries * sizeof(StepEntry);
+  return TQ_OK;
+}
+
+extern "C" int tq_step_destroy(tq_step_handle s) {
+  if (!s) return TQ_OK;
+  hipError_t e = hipFree(s->table_dev);
+  delete s;
+  if (e != hipSuccess) return hip_fail("tq_step_destroy", e);
+  return TQ_OK;
 }
 
 extern "C" int tq_decompress(tq_handle h, void* out, void* stream) {

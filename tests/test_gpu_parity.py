@@ -304,15 +304,23 @@ def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows
                 xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
                 ys.append(torch.full((batch, sp.rows), float("nan"), dtype=torch.float32, device=dev))
                 xf.append(x)
-            tq.tq_matvec_multi(handles, [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch, _stream())
-            torch.cuda.synchronize()
-            for y, rows, Qs, ss, x in zip(ys, picks, q_ref, s_ref, xf):
-                got = y.cpu().numpy()
-                assert np.isfinite(got).all()
-                ref = O.gemv_f64(Qs, ss, x)                           # [batch, sampled rows]
-                scale = np.abs(ref).max(axis=1, keepdims=True)
-                assert (np.abs(got[:, rows] - ref) <= 1e-3 * scale).all()
-                assert (np.abs(got[:, rows] - ref) <= 1e-5 * scale).all()   # what fp32 accumulation of exact products gives
+            step = tq.Step(handles, [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch)   # what bench.py times
+            for through_step in (False, True):
+                for y in ys:
+                    y.fill_(float("nan"))
+                if through_step:
+                    step.launch(_stream())
+                else:
+                    tq.tq_matvec_multi(handles, [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch, _stream())
+                torch.cuda.synchronize()
+                for y, rows, Qs, ss, x in zip(ys, picks, q_ref, s_ref, xf):
+                    got = y.cpu().numpy()
+                    assert np.isfinite(got).all()
+                    ref = O.gemv_f64(Qs, ss, x)                           # [batch, sampled rows]
+                    scale = np.abs(ref).max(axis=1, keepdims=True)
+                    assert (np.abs(got[:, rows] - ref) <= 1e-3 * scale).all()
+                    assert (np.abs(got[:, rows] - ref) <= 1e-5 * scale).all()   # what fp32 accumulation of exact products gives
+            step.close()
     finally:
         for m in mats:
             m.close()
@@ -661,6 +669,106 @@ def test_launches_can_be_captured_in_a_hip_graph_and_replayed(dev):
         del graph
         for m in mats:
             m.close()
+
+
+def _step_case(dev, shapes, batch, max_entries=900, widths=None):
+    """The same matrices through tq_matvec_multi and through a prepared step; both against the oracle."""
+    mats, xs, ys, y2, refs = [], [], [], [], []
+    prev = {}
+    for k, (r, c, seg) in enumerate(shapes):
+        spec = small_case(r, c, seed=600 + k)
+        W = make_weights(spec)
+        width, pack = widths[k % len(widths)] if widths else (8, False)
+        Qo, so = O.quantize_rows(W, bits=width)
+        blob = tq.tq_encode(W, max_entries=max_entries, seg_cols=seg // 2 if pack else seg, dict_from=prev.get(pack) if k % 9 else None,
+                            bits=0 if width == 8 else width, pack=pack)
+        prev[pack] = blob
+        mats.append(tq.Matrix(blob))
+        bits, x = make_activations(spec, batch)
+        xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
+        ys.append(torch.full((batch, r), float("nan"), dtype=torch.float32, device=dev))
+        y2.append(torch.full((batch, r), float("nan"), dtype=torch.float32, device=dev))
+        refs.append(O.gemv_f64(Qo, so, x))
+    hs, xp = [m.handle for m in mats], [x.data_ptr() for x in xs]
+    step = tq.Step(hs, xp, [y.data_ptr() for y in ys], batch)
+    assert step.info["n_matrices"] == len(shapes) and step.info["table_bytes"] % len(shapes) == 0
+    tq.tq_matvec_multi(hs, xp, [y.data_ptr() for y in y2], batch, _stream())
+    for _ in range(2):                       # a step can be launched again and again
+        for y in ys:
+            y.fill_(float("nan"))
+        step.launch(_stream())
+        torch.cuda.synchronize()
+        for y, other, ref in zip(ys, y2, refs):
+            got = y.cpu().numpy()
+            check_outputs(got, ref)
+            assert np.abs(got - other.cpu().numpy()).max() <= 1e-5 * np.abs(ref).max()
+    n_launches = step.info["n_launches"]
+    step.close()
+    for m in mats:
+        m.close()
+    return n_launches
+
+
+def test_prepared_step_serves_more_matrices_per_launch_than_the_kernel_arguments_hold(dev):
+    shapes = [(16 * (1 + k % 5), 256 + 64 * (k % 3), 64) for k in range(150)]
+    assert _step_case(dev, shapes, 1) == 1                      # tq_matvec_multi needs two launches for 150 matrices
+    assert _step_case(dev, shapes, 4) == 1
+
+
+def test_prepared_step_with_ring_whole_strip_and_packed_matrices(dev, ring_for_small_launches):
+    """One step whose matrices go to different kernels: ring (whole units), whole strip (300 columns), packed 4-bit."""
+    shapes = [(192, 768, 64), (64, 768, 64), (64, 768, 192), (40, 300, 32), (512, 768, 192), (192, 2048, 256), (100, 1024, 128)]
+    for batch in (1, 3, 16):
+        n = _step_case(dev, shapes, batch, max_entries=3000, widths=[(8, False), (8, False), (4, True)])
+        assert n >= 2
+
+
+def test_prepared_step_of_gate_up_pairs_in_a_hip_graph(dev):
+    pairs = [(64, 512, 64), (200, 768, 192), (48, 2048, 256)]
+    for batch in (1, 4):
+        mats, refs, xs, ys = [], [], [], []
+        for k, (r, c, seg) in enumerate(pairs):
+            sg, su = small_case(r, c, seed=680 + 2 * k), small_case(r, c, seed=681 + 2 * k)
+            Wg, Wu = make_weights(sg), make_weights(su)
+            mats.append(tq.Matrix(tq.tq_encode_gate_up(Wg, Wu, seg_cols=seg, max_entries=2000)))
+            bits, x = make_activations(sg, batch)
+            xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
+            ys.append(torch.full((batch, r), float("nan"), dtype=torch.float32, device=dev))
+            refs.append(O.gate_up_f64(*O.quantize_rows(Wg), *O.quantize_rows(Wu), x))
+        step = tq.Step([m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch, gate_up=True)
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step.launch(torch.cuda.current_stream().cuda_stream)
+        for _ in range(3):
+            for y in ys:
+                y.fill_(-1.0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for y, ref in zip(ys, refs):
+                check_outputs(y.cpu().numpy(), ref)
+            step.launch(_stream())           # eager work between the replays
+            torch.cuda.synchronize()
+        del graph
+        step.close()
+        for m in mats:
+            m.close()
+
+
+def test_prepared_step_argument_errors(dev):
+    m = tq.Matrix(tq.tq_encode(make_weights(small_case(17, 64, seed=690)), seg_cols=16))
+    x = torch.zeros(64, dtype=torch.int16, device=dev)
+    y = torch.zeros(17, dtype=torch.float32, device=dev)
+    for kw in (dict(batch=0), dict(batch=17), dict(batch=1, flags=2), dict(batch=1, flags=tq.TQ_STEP_GATE_UP)):   # odd rows: no pairs
+        with pytest.raises(tq.TqError):
+            tq.tq_step_create([m.handle], [x.data_ptr()], [y.data_ptr()], **kw)
+    with pytest.raises(tq.TqError):
+        tq.tq_step_create([m.handle], [0], [y.data_ptr()], 1)
+    with pytest.raises(tq.TqError):
+        tq.tq_step_launch(None)
+    tq.tq_step_destroy(None)
+    m.close()
 
 
 def test_argument_errors(dev):
