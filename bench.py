@@ -166,8 +166,8 @@ def main():
     if args.pack and args.bits > 4:
         sys.exit("--pack takes --bits 2..4")
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path is a single-GPU kernel; DESIGN.md says how it "
-              "would shard). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path is a single-GPU kernel; row- or column-parallel "
+              "sharding over several GPUs is a design note, not built). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
