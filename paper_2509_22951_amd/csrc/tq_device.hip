@@ -301,22 +301,29 @@ __device__ __forceinline__ uint32_t advance_by_pair(uint32_t pair, uint32_t xa) 
   return r;
 }
 
+// In two halves, so that the reads of the next chunk can be issued ahead of the dot products of this one (left to
+// itself the compiler finishes a chunk before it requests anything of the next: one LDS round trip per chunk that a
+// wavefront with few neighbours cannot hide).
 template <int kCode0>
-__device__ __forceinline__ void chunk4(uint2 c, uint32_t& xa, float& a0, float& a1) {
-  const uint32_t w0 = lds_read32(word_offset_lo(c.x)), w1 = lds_read32(word_offset_hi(c.x));
-  const uint32_t w2 = lds_read32(word_offset_lo(c.y)), w3 = lds_read32(word_offset_hi(c.y));
-  const uint32_t x0 = lds_read32_off<4 * kCode0>(xa);
+__device__ __forceinline__ void chunk4_read(uint2 c, uint32_t& xa, uint32_t (&w)[4], uint32_t (&x)[8]) {
+  w[0] = lds_read32(word_offset_lo(c.x));
+  w[1] = lds_read32(word_offset_hi(c.x));
+  w[2] = lds_read32(word_offset_lo(c.y));
+  w[3] = lds_read32(word_offset_hi(c.y));
+  x[0] = lds_read32_off<4 * kCode0>(xa);
   xa = advance_by_pair(is_pair_lo(c.x), xa);
-  const uint32_t x1 = lds_read32_off<4 * kCode0 + 4>(xa);
+  x[1] = lds_read32_off<4 * kCode0 + 4>(xa);
   xa = advance_by_pair(is_pair_hi(c.x), xa);
-  const uint32_t x2 = lds_read32_off<4 * kCode0 + 8>(xa);
+  x[2] = lds_read32_off<4 * kCode0 + 8>(xa);
   xa = advance_by_pair(is_pair_lo(c.y), xa);
-  const uint32_t x3 = lds_read32_off<4 * kCode0 + 12>(xa);
+  x[3] = lds_read32_off<4 * kCode0 + 12>(xa);
   xa = advance_by_pair(is_pair_hi(c.y), xa);
-  a0 = dot2(w0, x0, a0);
-  a1 = dot2(w1, x1, a1);
-  a0 = dot2(w2, x2, a0);
-  a1 = dot2(w3, x3, a1);
+}
+__device__ __forceinline__ void chunk4_dot(const uint32_t (&w)[4], const uint32_t (&x)[8], float& a0, float& a1) {
+  a0 = dot2(w[0], x[0], a0);
+  a1 = dot2(w[1], x[1], a1);
+  a0 = dot2(w[2], x[2], a0);
+  a1 = dot2(w[3], x[3], a1);
 }
 
 // The same for a matrix of packed 4-bit weights.  A dictionary word holds the entry's four weights as fp8 (e4m3 holds
@@ -327,25 +334,30 @@ __device__ __forceinline__ float dot2_fp8(uint32_t w, bool high, uint32_t x, flo
   return __builtin_amdgcn_fdot2_f32_bf16(wb, __builtin_bit_cast(bf16x2, x), acc, false);
 }
 template <int kCode0>
-__device__ __forceinline__ void chunk4_packed(uint2 c, uint32_t& xa, float& a0, float& a1) {
-  const uint32_t w0 = lds_read32(word_offset_lo(c.x)), w1 = lds_read32(word_offset_hi(c.x));
-  const uint32_t w2 = lds_read32(word_offset_lo(c.y)), w3 = lds_read32(word_offset_hi(c.y));
-  const uint32_t x0 = lds_read32_off<4 * kCode0>(xa), x0b = lds_read32_off<4 * kCode0 + 4>(xa);
+__device__ __forceinline__ void chunk4_packed_read(uint2 c, uint32_t& xa, uint32_t (&w)[4], uint32_t (&x)[8]) {
+  w[0] = lds_read32(word_offset_lo(c.x));
+  w[1] = lds_read32(word_offset_hi(c.x));
+  w[2] = lds_read32(word_offset_lo(c.y));
+  w[3] = lds_read32(word_offset_hi(c.y));
+  x[0] = lds_read32_off<4 * kCode0>(xa);
+  x[1] = lds_read32_off<4 * kCode0 + 4>(xa);
   xa = advance_by_pair(is_pair_lo(c.x), xa);
-  const uint32_t x1 = lds_read32_off<4 * kCode0 + 4>(xa), x1b = lds_read32_off<4 * kCode0 + 8>(xa);
+  x[2] = lds_read32_off<4 * kCode0 + 4>(xa);
+  x[3] = lds_read32_off<4 * kCode0 + 8>(xa);
   xa = advance_by_pair(is_pair_hi(c.x), xa);
-  const uint32_t x2 = lds_read32_off<4 * kCode0 + 8>(xa), x2b = lds_read32_off<4 * kCode0 + 12>(xa);
+  x[4] = lds_read32_off<4 * kCode0 + 8>(xa);
+  x[5] = lds_read32_off<4 * kCode0 + 12>(xa);
   xa = advance_by_pair(is_pair_lo(c.y), xa);
-  const uint32_t x3 = lds_read32_off<4 * kCode0 + 12>(xa), x3b = lds_read32_off<4 * kCode0 + 16>(xa);
+  x[6] = lds_read32_off<4 * kCode0 + 12>(xa);
+  x[7] = lds_read32_off<4 * kCode0 + 16>(xa);
   xa = advance_by_pair(is_pair_hi(c.y), xa);
-  a0 = dot2_fp8(w0, false, x0, a0);
-  a1 = dot2_fp8(w0, true, x0b, a1);
-  a0 = dot2_fp8(w1, false, x1, a0);
-  a1 = dot2_fp8(w1, true, x1b, a1);
-  a0 = dot2_fp8(w2, false, x2, a0);
-  a1 = dot2_fp8(w2, true, x2b, a1);
-  a0 = dot2_fp8(w3, false, x3, a0);
-  a1 = dot2_fp8(w3, true, x3b, a1);
+}
+__device__ __forceinline__ void chunk4_packed_dot(const uint32_t (&w)[4], const uint32_t (&x)[8], float& a0, float& a1) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    a0 = dot2_fp8(w[k], false, x[2 * k], a0);
+    a1 = dot2_fp8(w[k], true, x[2 * k + 1], a1);
+  }
 }
 
 // LDS image of one activation row for packed weights: dword (panel * x_span + c) = the two activations of byte column
@@ -523,20 +535,38 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
           for (int k = 0; k < kPiece; ++k) cw[k] = load_chunk(m.codes, min(start + k, last), lane);
         };
         auto run_piece = [&](const uint2 (&cw)[kPiece], uint32_t n, bool ends) {
-          auto chunk = [&](auto kk) {
+          uint32_t w[2][4], x[2][8];   // two register sets: one chunk's operands are read while the one before is multiplied
+          auto read = [&](auto kk) {
             constexpr int k = decltype(kk)::value;
-            if constexpr (kPacked) chunk4_packed<4 * k>(cw[k], xa, a0, a1);
-            else chunk4<4 * k>(cw[k], xa, a0, a1);
+            if constexpr (kPacked) chunk4_packed_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);
+            else chunk4_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);
+          };
+          auto dot = [&](auto kk) {
+            constexpr int k = decltype(kk)::value;
+            if constexpr (kPacked) chunk4_packed_dot(w[k & 1], x[k & 1], a0, a1);
+            else chunk4_dot(w[k & 1], x[k & 1], a0, a1);
+          };
+          auto straight = [&](auto nn) {   // a piece of nn chunks as straight-line code
+            constexpr int kN = decltype(nn)::value;
+            read(std::integral_constant<int, 0>{});
+            static_for<kN>([&](auto kk) {
+              constexpr int k = decltype(kk)::value;
+              if constexpr (k + 1 < kN) read(std::integral_constant<int, k + 1>{});
+              dot(kk);
+            });
           };
           if (n == kPiece) {
-            static_for<kPiece>(chunk);
+            straight(std::integral_constant<int, kPiece>{});
           } else if (n == kPiece - 1) {
-            static_for<kPiece - 1>(chunk);
+            straight(std::integral_constant<int, kPiece - 1>{});
           } else if (n == kPiece - 2) {
-            static_for<kPiece - 2>(chunk);
+            straight(std::integral_constant<int, kPiece - 2>{});
           } else {
             static_for<kPiece>([&](auto kk) {
-              if ((uint32_t)decltype(kk)::value < n) chunk(kk);
+              if ((uint32_t)decltype(kk)::value < n) {
+                read(kk);
+                dot(kk);
+              }
             });
           }
           xa += 16 * n;
