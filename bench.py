@@ -268,24 +268,24 @@ def main():
 
     def run(batch, steps, warmup):
         xs, ys = make_io(batch)
-        calls = []
+        calls = []            # one per group; each takes the stream to launch on
         launches[0] = 0
         for g in groups:
-            if len(g) == 1:
+            if len(g) == 1:   # one matrix: its description travels in the kernel arguments
                 m, xp, yp = mats[g[0]], xs[g[0]].data_ptr(), ys[g[0]].data_ptr()
-                calls.append(lambda m=m, xp=xp, yp=yp: m.matvec(xp, yp, batch, stream))
+                calls.append(lambda s, m=m, xp=xp, yp=yp: m.matvec(xp, yp, batch, s))
             elif args.no_prepared_step:
                 mc = tq.MultiCall([mats[i].handle for i in g], [xs[i].data_ptr() for i in g],
                                   [ys[i].data_ptr() for i in g], batch)
-                calls.append(lambda mc=mc: mc.launch(stream))
+                calls.append(lambda s, mc=mc: mc.launch(s))
             else:   # the same products as a prepared step: buffers fixed, jobs in device memory, up to 896 matrices per launch
                 st = tq.Step([mats[i].handle for i in g], [xs[i].data_ptr() for i in g], [ys[i].data_ptr() for i in g], batch)
                 launches[0] += st.info["n_launches"] - (-(-len(g) // 128))
-                calls.append(lambda st=st: st.launch(stream))
+                calls.append(lambda s, st=st: st.launch(s))
 
         def eager_step():
             for c in calls:
-                c()
+                c(stream)
 
         step = eager_step
         if args.graph:
@@ -295,10 +295,8 @@ def main():
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=side):
                 cap = torch.cuda.current_stream().cuda_stream
-                for g in groups:     # the same calls, issued on the capturing stream
-                    tq.tq_matvec_multi([mats[i].handle for i in g], [xs[i].data_ptr() for i in g],
-                                       [ys[i].data_ptr() for i in g], batch, cap)
-                launches[0] = 0
+                for c in calls:      # the same calls, issued on the capturing stream
+                    c(cap)
             step = graph.replay
 
         for _ in range(warmup):
@@ -364,7 +362,7 @@ def main():
     # where the matrices of a group go to different kernels)
     n_launches = sum(-(-len(g) // 128) for g in groups) + launch_delta
     profiled = (args.config == 4 and args.batch == 1 and args.fuse == "sweep" and args.dictionary == "sequence"
-                and args.dictionary_kind == "lzw" and args.bits == 8 and not args.no_prepared_step and not args.graph
+                and args.dictionary_kind == "lzw" and args.bits == 8 and not args.no_prepared_step
                 and not (args.max_entries or args.lmax or args.seg_cols or args.layers))
     gbps = comp_bytes / wall_ms / 1e6
     ach = comp_bytes / ev_ms / 1e6
@@ -389,7 +387,7 @@ def main():
             "bytes_per_weight": round(comp_bytes / n_weights, 4), "weights_per_code": round(n_weights / n_codes, 4),
             "weights_per_real_code": round(n_weights / sum(i["n_real_codes"] for i in infos), 4),
             "dictionary_entries": infos[-1]["n_entries"], "lmax": infos[0]["lmax"], "seg_cols": infos[0]["seg_cols"],
-            "dictionary": args.dictionary, "dictionary_kind": args.dictionary_kind, "bits": args.bits, "packing": "nibbles" if args.pack else "none", "fuse": args.fuse, "prepared_step": not args.no_prepared_step and not args.graph,
+            "dictionary": args.dictionary, "dictionary_kind": args.dictionary_kind, "bits": args.bits, "packing": "nibbles" if args.pack else "none", "fuse": args.fuse, "prepared_step": not args.no_prepared_step,
             "kernel_launches_per_step": n_launches,
             "hip_graph": bool(args.graph),
         },
