@@ -333,8 +333,13 @@ def main():
         out = torch.empty(n_weights, dtype=torch.int8, device=dev)          # the whole model expanded, matrix after matrix
         offs = np.cumsum([0] + [s.rows * s.cols for s in specs])
         handles, ptrs = [m.handle for m in mats], [out.data_ptr() + int(o) for o in offs[:-1]]
+        dstep = None if args.no_prepared_step else tq.Step(handles, None, ptrs, decompress=True)
+
         def expand():
-            tq.tq_decompress_multi(handles, ptrs, stream)
+            if dstep is None:
+                tq.tq_decompress_multi(handles, ptrs, stream)
+            else:
+                dstep.launch(stream)
         for _ in range(5):
             expand()
         torch.cuda.synchronize()
@@ -346,7 +351,8 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         d_ms = e0.elapsed_time(e1) / reps
-        decompress = {"ms_per_model": round(d_ms, 3), "kernel_launches": -(-len(mats) // 128),
+        decompress = {"ms_per_model": round(d_ms, 3),
+                      "kernel_launches": -(-len(mats) // 128) if dstep is None else dstep.info["n_launches"],
                       "GBps_read_plus_write": round((comp_bytes + n_weights) / d_ms / 1e6, 1),
                       "GBps_written": round(n_weights / d_ms / 1e6, 1)}
         del out

@@ -181,7 +181,8 @@ int tq_matvec_gate_up(tq_handle h, const void *x, void *y, int batch, void *stre
 int tq_matvec_gate_up_multi(int n, const tq_handle *hs, const void *const *xs, void *const *ys, int batch, void *stream);
 
 /*
- * A prepared step: tq_matvec_multi (flags 0) or tq_matvec_gate_up_multi (TQ_STEP_GATE_UP) for a fixed set of matrices and
+ * A prepared step: tq_matvec_multi (flags 0), tq_matvec_gate_up_multi (TQ_STEP_GATE_UP) or tq_decompress_multi
+ * (TQ_STEP_DECOMPRESS) for a fixed set of matrices and
  * buffers, with everything but the stream decided once - for a decode loop that runs the same products on the same
  * buffers token after token (the layer-by-layer use of the compressed parameters in the paper's Background "Inference").
  * tq_step_create does what those calls do before they launch (argument checks, which kernel takes which matrix, the
@@ -196,6 +197,8 @@ int tq_matvec_gate_up_multi(int n, const tq_handle *hs, const void *const *xs, v
  * destroyed.
  */
 #define TQ_STEP_GATE_UP 1u
+#define TQ_STEP_DECOMPRESS 2u /* the step stands for tq_decompress_multi: ys are the int8 output matrices, xs may be
+                                 NULL and batch is not used */
 typedef struct tq_step *tq_step_handle;
 typedef struct tq_step_info {
   uint32_t n_matrices, n_launches; /* kernel launches one tq_step_launch makes */

@@ -34,6 +34,7 @@ from .binding import (  # noqa: F401
     tq_matvec_gate_up,
     tq_matvec_gate_up_multi,
     TQ_STEP_GATE_UP,
+    TQ_STEP_DECOMPRESS,
     Step,
     tq_step_create,
     tq_step_launch,

@@ -251,14 +251,17 @@ def tq_matvec_multi(handles, x_ptrs, y_ptrs, batch: int, stream: int = 0) -> Non
 
 
 TQ_STEP_GATE_UP = 1
+TQ_STEP_DECOMPRESS = 2
 
 
 def tq_step_create(handles, x_ptrs, y_ptrs, batch: int, flags: int = 0) -> int:
+    """x_ptrs may be None with TQ_STEP_DECOMPRESS (y_ptrs are then the int8 output matrices)."""
     n = len(handles)
-    assert n == len(x_ptrs) == len(y_ptrs) and n >= 1
+    assert n == len(y_ptrs) and n >= 1 and (x_ptrs is None or len(x_ptrs) == n)
     arr = ctypes.c_void_p * n
     out = ctypes.c_void_p()
-    _check(load().tq_step_create(n, arr(*handles), arr(*x_ptrs), arr(*y_ptrs), batch, flags, ctypes.byref(out)))
+    xs = arr(*x_ptrs) if x_ptrs is not None else None
+    _check(load().tq_step_create(n, arr(*handles), xs, arr(*y_ptrs), batch, flags, ctypes.byref(out)))
     return out.value
 
 
@@ -279,8 +282,9 @@ def tq_step_destroy(step) -> None:
 class Step:
     """Owning wrapper around a prepared step (marshalling only): tq_matvec_multi for fixed matrices and buffers."""
 
-    def __init__(self, handles, x_ptrs, y_ptrs, batch: int, gate_up: bool = False):
-        self.handle = tq_step_create(handles, x_ptrs, y_ptrs, batch, TQ_STEP_GATE_UP if gate_up else 0)
+    def __init__(self, handles, x_ptrs, y_ptrs, batch: int = 1, gate_up: bool = False, decompress: bool = False):
+        flags = (TQ_STEP_GATE_UP if gate_up else 0) | (TQ_STEP_DECOMPRESS if decompress else 0)
+        self.handle = tq_step_create(handles, x_ptrs, y_ptrs, batch, flags)
         self.info = tq_step_get_info(self.handle)
 
     def launch(self, stream: int = 0) -> None:

@@ -1990,12 +1990,25 @@ extern "C" int tq_step_create(int n, const tq_handle* hs, const void* const* xs,
     return TQ_E_INVALID_ARG;
   }
   *out = nullptr;
-  if (n < 1 || !hs || !xs || !ys || (flags & ~TQ_STEP_GATE_UP)) {
-    set_error("tq_step_create: null argument, n < 1 or unknown flag");
+  const bool expand = (flags & TQ_STEP_DECOMPRESS) != 0, gate_up = (flags & TQ_STEP_GATE_UP) != 0;
+  if (n < 1 || !hs || !ys || (!xs && !expand) || (flags & ~(TQ_STEP_GATE_UP | TQ_STEP_DECOMPRESS)) || (expand && gate_up)) {
+    set_error("tq_step_create: null argument, n < 1 or unknown combination of flags");
     return TQ_E_INVALID_ARG;
   }
-  if (int rc = check_call("tq_step_create", n, hs, xs, ys, batch)) return rc;
-  const bool gate_up = (flags & TQ_STEP_GATE_UP) != 0;
+  if (expand) {   // tq_decompress_multi prepared: ys are the int8 matrices, xs and batch are not used
+    for (int i = 0; i < n; ++i) {
+      if (!hs[i] || !ys[i]) {
+        set_error("tq_step_create: null handle or pointer at index " + std::to_string(i));
+        return TQ_E_INVALID_ARG;
+      }
+      if (hs[i]->device != hs[0]->device) {
+        set_error("tq_step_create: all matrices of a step must live on one device");
+        return TQ_E_INVALID_ARG;
+      }
+    }
+  } else if (int rc = check_call("tq_step_create", n, hs, xs, ys, batch)) {
+    return rc;
+  }
   if (gate_up)
     for (int i = 0; i < n; ++i)
       if (hs[i]->m.rows % 2) {
@@ -2004,7 +2017,9 @@ extern "C" int tq_step_create(int n, const tq_handle* hs, const void* const* xs,
       }
   try {
     Recorder rec;
-    if (int rc = launch_all(Op::kMatvec, n, hs, xs, ys, batch, nullptr, false, gate_up, &rec)) return rc;
+    if (int rc = expand ? launch_all(Op::kDecompress, n, hs, nullptr, ys, 1, nullptr, false, false, &rec)
+                        : launch_all(Op::kMatvec, n, hs, xs, ys, batch, nullptr, false, gate_up, &rec))
+      return rc;
     tq_step* s = new tq_step;
     s->launches = std::move(rec.launches);
     s->n_entries = rec.entries.size();

@@ -251,6 +251,20 @@ def test_decompress_multi_is_bit_exact(dev):
     torch.cuda.synchronize()
     for o, w in zip(outs, want):
         assert np.array_equal(o.cpu().numpy(), w)
+    # the same expansion as a prepared step: 150 matrices in one launch instead of two
+    step = tq.Step([m.handle for m in mats], None, [o.data_ptr() for o in outs], decompress=True)
+    assert step.info["n_launches"] == 1 and step.info["n_matrices"] == len(mats)
+    for o in outs:
+        o.fill_(55)
+    step.launch(_stream())
+    torch.cuda.synchronize()
+    for o, w in zip(outs, want):
+        assert np.array_equal(o.cpu().numpy(), w)
+    step.close()
+    with pytest.raises(tq.TqError):
+        tq.tq_step_create([mats[0].handle], None, [outs[0].data_ptr()], 1, tq.TQ_STEP_DECOMPRESS | tq.TQ_STEP_GATE_UP)
+    with pytest.raises(tq.TqError):
+        tq.tq_step_create([mats[0].handle], None, [outs[0].data_ptr()], 1, 0)        # products need activations
     for m in mats:
         m.close()
 
@@ -760,7 +774,8 @@ def test_prepared_step_argument_errors(dev):
     m = tq.Matrix(tq.tq_encode(make_weights(small_case(17, 64, seed=690)), seg_cols=16))
     x = torch.zeros(64, dtype=torch.int16, device=dev)
     y = torch.zeros(17, dtype=torch.float32, device=dev)
-    for kw in (dict(batch=0), dict(batch=17), dict(batch=1, flags=2), dict(batch=1, flags=tq.TQ_STEP_GATE_UP)):   # odd rows: no pairs
+    for kw in (dict(batch=0), dict(batch=17), dict(batch=1, flags=4), dict(batch=1, flags=3),
+               dict(batch=1, flags=tq.TQ_STEP_GATE_UP)):   # unknown flag, two forms at once, odd rows: no pairs
         with pytest.raises(tq.TqError):
             tq.tq_step_create([m.handle], [x.data_ptr()], [y.data_ptr()], **kw)
     with pytest.raises(tq.TqError):
