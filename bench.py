@@ -123,19 +123,26 @@ def gate_up_leg(specs, mats, prev, opts, args, dev, stream):
             "fused_GBps": round(nbytes / t_fused / 1e6, 1)}
 
 
-def listing_leg(specs, dev, stream):
+def listing_leg(specs, mats, dev, stream):
     """The paper's section 4 stream format, literally: table of the most frequent windows of 4 values over the first
-    matrix of the workload, the largest of its first matrices compressed with it, expanded on the device."""
+    matrix of the workload, the largest of its first matrices compressed with it, expanded on the device.
+    The quantized values come from the containers of the workload (tq_decompress); nothing of that is timed."""
     import torch
 
     import paper_2509_22951_amd as tq
-    from inputs import make_weights
-    from oracle import oracle as O                        # its quantizer makes the input bytes; nothing of it is timed
+
+    def quantized_bytes(i):
+        out = torch.empty((specs[i].rows, specs[i].cols), dtype=torch.int8, device=dev)
+        mats[i].decompress(out.data_ptr(), stream)
+        torch.cuda.synchronize()
+        return out.cpu().numpy().view(np.uint8).reshape(-1)
+
     first = specs[0]
-    big = max(specs[:8], key=lambda s: s.rows * s.cols)
-    q_first = O.quantize_rows(make_weights(first))[0].view(np.uint8).reshape(-1)
+    i_big = max(range(min(8, len(specs))), key=lambda i: specs[i].rows * specs[i].cols)
+    big = specs[i_big]
+    q_first = quantized_bytes(0)
     table = tq.tq_listing_build_table([q_first])
-    values = O.quantize_rows(make_weights(big))[0].view(np.uint8).reshape(-1)
+    values = quantized_bytes(i_big)
     words = tq.tq_listing_compress(values, table)
     h = tq.Listing(words, table)
     out = torch.empty(values.size, dtype=torch.uint8, device=dev)
@@ -359,7 +366,7 @@ def main():
 
     listing = None
     if not args.no_listing:
-        listing = listing_leg(specs, dev, stream)
+        listing = listing_leg(specs, mats, dev, stream)
     gate_up = None
     if not args.no_gate_up:
         gate_up = gate_up_leg(specs, mats, prev if args.dictionary == "sequence" else None, opts, args, dev, stream)

@@ -1,7 +1,6 @@
 """CPU oracle for the stream format the paper's section 4 listings define ("listing format").
 
-TEST INFRASTRUCTURE ONLY.  Imported by tests/ and by the ``cpu_baseline``-style leg of ``bench.py``; the product
-package never imports it and the two share no code.
+TEST INFRASTRUCTURE ONLY.  Imported by tests/ only; the product package never imports it and the two share no code.
 
 What the listings of section 4 compute, restated:
 
