@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtq.so")
 SOURCES = ["tq_encode.cpp", "tq_blob.cpp", "tq_device.hip", "tq_listing.hip"]
-HEADERS = ["tq_format.h", os.path.join("..", "..", "include", "tq.h")]
+HEADERS = ["tq_format.h", "tq_kernels_common.h", "tq_kernel_dot.h", "tq_strip_decode.h", "tq_kernel_ring.h", "tq_kernel_strip.h",
+           os.path.join("..", "..", "include", "tq.h")]
 
 
 def hipcc_command(out: str):

@@ -1,0 +1,404 @@
+// Device side of libtq: the batch-1 kernel (dictionary lookup, activation gather, one dot product per code).
+#pragma once
+#include "tq_kernels_common.h"
+
+namespace tq {
+// Staging is split in two so that the loads of the dictionary, of the activations and of the first code chunks are
+// all in flight together before anything waits: issue_* only loads into registers, commit_* writes LDS.
+constexpr int kDictRegs = 16;   // uint4 per thread per round of the tile kernels' dictionary staging
+
+template <int kThreads, int kDictRegs>   // kDictRegs x kThreads x 16 bytes per round (128 KB: the whole dictionary in one)
+__device__ __forceinline__ void issue_dictionary(const DevMat& m, uint32_t base, int tid, uint4 (&v)[kDictRegs]) {
+  const uint4* src = (const uint4*)m.dict_bf16;
+  const uint32_t n4 = m.dict_words / 4;
+#pragma unroll
+  for (int k = 0; k < kDictRegs; ++k) v[k] = global_load(src + min(base + k * kThreads + tid, n4 - 1));
+}
+template <int kThreads, int kDictRegs>
+__device__ __forceinline__ void commit_dictionary(const DevMat& m, uint32_t base, int tid, const uint4 (&v)[kDictRegs], uint32_t* lds_dict) {
+  uint4* dst = (uint4*)lds_dict;
+  const uint32_t n4 = m.dict_words / 4;
+#pragma unroll
+  for (int k = 0; k < kDictRegs; ++k) {
+    const uint32_t i = base + k * kThreads + tid;
+    if (i < n4) dst[i] = v[k];
+  }
+}
+
+// LDS image of one activation row: dword (panel * x_span + c) = (x[panel * seg_cols + c], x[panel * seg_cols + c + 1])
+// as two bf16, zero past the end of the row; the gap dwords between panels and the tail are zero.
+// Thread t of a round handles the column pair (2 j, 2 j + 1), j = first_pair + k * 512 + t: it loads x[2j .. 2j+2].
+template <bool kAligned, int kThreads, int kXRegs>   // kXRegs x kThreads x 2 columns per round (8192)
+__device__ __forceinline__ void issue_activations(const DevMat& m, const uint16_t* __restrict__ x, uint32_t first_pair, int tid,
+                                                  uint32_t (&lo)[kXRegs], uint32_t (&hi)[kXRegs]) {
+#pragma unroll
+  for (int k = 0; k < kXRegs; ++k) {
+    const uint32_t j = first_pair + k * kThreads + tid, col = 2 * j;
+    if (kAligned) {   // x is 4-byte aligned and cols is even
+      lo[k] = col < m.cols ? global_load((const uint32_t*)x + j) : 0u;
+      hi[k] = col + 2 < m.cols ? global_load((const uint32_t*)x + j + 1) : 0u;
+    } else {
+      lo[k] = (col < m.cols ? global_load(x + col) : 0u) | (col + 1 < m.cols ? global_load(x + col + 1) << 16 : 0u);
+      hi[k] = col + 2 < m.cols ? global_load(x + col + 2) : 0u;
+    }
+  }
+}
+template <int kThreads, int kXRegs>
+__device__ __forceinline__ void commit_activations(const DevMat& m, uint32_t first_pair, int tid, const uint32_t (&lo)[kXRegs],
+                                                   const uint32_t (&hi)[kXRegs], uint32_t* lds_x, uint32_t image_cols) {
+  const uint32_t gap = m.x_span - m.seg_cols;
+#pragma unroll
+  for (int k = 0; k < kXRegs; ++k) {
+    const uint32_t col = 2 * (first_pair + k * kThreads + tid);
+    if (col < image_cols) {   // image_cols and seg_cols are even: both dwords of the pair lie in one panel
+      const uint32_t i = col + gap * __umulhi(col, m.seg_magic);
+      lds_x[i] = lo[k];
+      lds_x[i + 1] = lo[k] >> 16 | hi[k] << 16;
+    }
+  }
+}
+template <int kThreads>
+__device__ __forceinline__ void zero_activation_gaps(const DevMat& m, int tid, uint32_t* lds_x, uint32_t n_slots) {
+  const uint32_t gap = m.x_span - m.seg_cols;
+  if (gap)   // gap is 16 dwords
+    for (uint32_t i = tid; i < n_slots * 16; i += kThreads) lds_x[(i >> 4) * m.x_span + m.seg_cols + (i & 15)] = 0u;
+  for (uint32_t i = n_slots * m.x_span + tid; i < m.x_dwords; i += kThreads) lds_x[i] = 0u;
+}
+
+// One chunk = 4 codes per lane.  xa = LDS byte address of the activation pair of the lane's next code, minus 4 bytes
+// per code consumed since the start of the piece; code k of the piece therefore reads at xa + 4 k, and the constant
+// part goes into the instruction's offset field.  A single advances the lane by one column (already counted by the
+// 4 k), a pair by one more.  The dictionary sits at LDS address 0, so a code's word offset is its address.
+// Per chunk and lane: 4 dictionary words, 4 activation pairs, 4 v_dot2_f32_bf16 into two accumulators.
+// xa + 4 * pair as one instruction.  Written out because the compiler otherwise keeps a running count of the pairs and
+// forms every address from it with a second instruction: a shorter dependency chain, but a quarter more vector
+// instructions per code.
+__device__ __forceinline__ uint32_t advance_by_pair(uint32_t pair, uint32_t xa) {
+  uint32_t r;
+  asm("v_lshl_add_u32 %0, %1, 2, %2" : "=v"(r) : "v"(pair), "v"(xa));
+  return r;
+}
+
+// In two halves, so that the reads of the next chunk can be issued ahead of the dot products of this one (left to
+// itself the compiler finishes a chunk before it requests anything of the next: one LDS round trip per chunk that a
+// wavefront with few neighbours cannot hide).
+template <int kCode0>
+__device__ __forceinline__ void chunk4_read(uint2 c, uint32_t& xa, uint32_t (&w)[4], uint32_t (&x)[8]) {
+  w[0] = lds_read32(word_offset_lo(c.x));
+  w[1] = lds_read32(word_offset_hi(c.x));
+  w[2] = lds_read32(word_offset_lo(c.y));
+  w[3] = lds_read32(word_offset_hi(c.y));
+  x[0] = lds_read32_off<4 * kCode0>(xa);
+  xa = advance_by_pair(is_pair_lo(c.x), xa);
+  x[1] = lds_read32_off<4 * kCode0 + 4>(xa);
+  xa = advance_by_pair(is_pair_hi(c.x), xa);
+  x[2] = lds_read32_off<4 * kCode0 + 8>(xa);
+  xa = advance_by_pair(is_pair_lo(c.y), xa);
+  x[3] = lds_read32_off<4 * kCode0 + 12>(xa);
+  xa = advance_by_pair(is_pair_hi(c.y), xa);
+}
+__device__ __forceinline__ void chunk4_dot(const uint32_t (&w)[4], const uint32_t (&x)[8], float& a0, float& a1) {
+  a0 = dot2(w[0], x[0], a0);
+  a1 = dot2(w[1], x[1], a1);
+  a0 = dot2(w[2], x[2], a0);
+  a1 = dot2(w[3], x[3], a1);
+}
+
+// The same for a matrix of packed 4-bit weights.  A dictionary word holds the entry's four weights as fp8 (e4m3 holds
+// -8..7 exactly; two zeros after a single byte), one activation dword holds the two columns of a byte: code k reads the
+// dwords at xa + 4 k and the next one, and two conversions give the bf16 pairs for two dot products.
+__device__ __forceinline__ float dot2_fp8(uint32_t w, bool high, uint32_t x, float acc) {
+  const bf16x2 wb = high ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
+  return __builtin_amdgcn_fdot2_f32_bf16(wb, __builtin_bit_cast(bf16x2, x), acc, false);
+}
+template <int kCode0>
+__device__ __forceinline__ void chunk4_packed_read(uint2 c, uint32_t& xa, uint32_t (&w)[4], uint32_t (&x)[8]) {
+  w[0] = lds_read32(word_offset_lo(c.x));
+  w[1] = lds_read32(word_offset_hi(c.x));
+  w[2] = lds_read32(word_offset_lo(c.y));
+  w[3] = lds_read32(word_offset_hi(c.y));
+  x[0] = lds_read32_off<4 * kCode0>(xa);
+  x[1] = lds_read32_off<4 * kCode0 + 4>(xa);
+  xa = advance_by_pair(is_pair_lo(c.x), xa);
+  x[2] = lds_read32_off<4 * kCode0 + 4>(xa);
+  x[3] = lds_read32_off<4 * kCode0 + 8>(xa);
+  xa = advance_by_pair(is_pair_hi(c.x), xa);
+  x[4] = lds_read32_off<4 * kCode0 + 8>(xa);
+  x[5] = lds_read32_off<4 * kCode0 + 12>(xa);
+  xa = advance_by_pair(is_pair_lo(c.y), xa);
+  x[6] = lds_read32_off<4 * kCode0 + 12>(xa);
+  x[7] = lds_read32_off<4 * kCode0 + 16>(xa);
+  xa = advance_by_pair(is_pair_hi(c.y), xa);
+}
+__device__ __forceinline__ void chunk4_packed_dot(const uint32_t (&w)[4], const uint32_t (&x)[8], float& a0, float& a1) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    a0 = dot2_fp8(w[k], false, x[2 * k], a0);
+    a1 = dot2_fp8(w[k], true, x[2 * k + 1], a1);
+  }
+}
+
+// LDS image of one activation row for packed weights: dword (panel * x_span + c) = the two activations of byte column
+// panel * seg_cols + c, zero past the end of the row.  Thread t of a round handles dword first + k * kThreads + t.
+template <bool kAligned, int kThreads, int kXRegs>
+__device__ __forceinline__ void issue_activations_packed(const DevMat& m, const uint16_t* __restrict__ x, uint32_t first, int tid,
+                                                         uint32_t (&v)[kXRegs]) {
+#pragma unroll
+  for (int k = 0; k < kXRegs; ++k) {
+    const uint32_t j = first + k * kThreads + tid;
+    if (kAligned) v[k] = j < m.cols ? global_load((const uint32_t*)x + j) : 0u;   // x is 4-byte aligned
+    else v[k] = j < m.cols ? global_load(x + 2 * j) | global_load(x + 2 * j + 1) << 16 : 0u;
+  }
+}
+template <int kThreads, int kXRegs>
+__device__ __forceinline__ void commit_activations_packed(const DevMat& m, uint32_t first, int tid, const uint32_t (&v)[kXRegs], uint32_t* lds_x,
+                                                          uint32_t image_cols) {
+  const uint32_t gap = m.x_span - m.seg_cols;
+#pragma unroll
+  for (int k = 0; k < kXRegs; ++k) {
+    const uint32_t j = first + k * kThreads + tid;
+    if (j < image_cols) lds_x[j + gap * __umulhi(j, m.seg_magic)] = v[k];
+  }
+}
+
+// Sum of the four panel lanes of each row: afterwards every lane l holds the sum over lanes l % 16 + {0, 16, 32, 48}.
+__device__ __forceinline__ float sum_over_panels(float v) {
+  v += __shfl_xor(v, 16);
+  v += __shfl_xor(v, 32);
+  return v;
+}
+
+// The gated product of a feed-forward block: silu(gate) * up, silu(g) = g / (1 + exp(-g)).
+__device__ __forceinline__ float silu_times(float gate, float up) { return gate / (1.f + __expf(-gate)) * up; }
+
+// Fused decode + dequantize + matrix-vector product for one activation row and up to kMaxMulti matrices.
+//
+// The launch's work is the line of all bands (16 rows each) of all matrices, each band weighted by its number of
+// weights; workgroup g takes the bands whose middle lies in the g-th equal share of that line, so a workgroup serves a
+// contiguous range of whole bands of one matrix after the other.  Inside a matrix the units of those bands are
+// contiguous in the code stream and are cut into one contiguous run per wavefront.  A wavefront owns every band that
+// lies entirely inside its run (it scales and stores those rows itself); a band it shares with its neighbours goes to
+// one of two partial-sum slots in LDS, and after a workgroup barrier the slots of a band are added in wavefront order,
+// so the result does not depend on timing.
+template <int kPiece, int kWaves, bool kPacked>
+__global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
+  constexpr int kThreads = kWaves * 64, kDictRegs = 128 / kWaves, kXRegs = 64 / kWaves;
+  extern __shared__ uint4 lds4[];
+  uint32_t* lds_dict = (uint32_t*)lds4;
+  uint32_t* lds_x = (uint32_t*)((uint8_t*)lds4 + a.x_off);
+  float* slot_val = (float*)((uint8_t*)lds4 + a.slot_off);           // [2 * kWaves][16]
+  int* slot_band = (int*)(slot_val + 2 * kWaves * 16);               // [2 * kWaves]
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if (lds_address(lds4) != 0) return;   // the code -> word lookup takes the dictionary to start at LDS address 0 (no static LDS here)
+  const uint64_t total = cost_at(a, a.n);
+  const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
+  const uint32_t* staged = nullptr;
+  for (int i = 0; i < a.n; ++i) {
+    const uint32_t cb = cost_at(a, i), ce = cost_at(a, i + 1);
+    if (hi <= cb || lo >= ce) continue;
+    Job job;
+    DevMat m;
+    fetch_job(a, i, job, m);
+    // a band goes to the share that holds its middle
+    const uint32_t bc = m.cols;
+    const uint32_t band_lo = lo <= cb ? 0u : (lo - cb + bc / 2) / bc;
+    const uint32_t band_hi = hi >= ce ? m.n_bands : min(m.n_bands, (hi - cb + bc / 2) / bc);
+    if (band_lo >= band_hi) continue;
+    const bool new_dict = m.dict_bf16 != staged;
+    staged = m.dict_bf16;
+    const uint32_t nq = m.n_quads, n_slots = nq * kUnitPanels, image_cols = n_slots * m.seg_cols;
+    const uint32_t unit_lo = band_lo * nq, n_units = (band_hi - band_lo) * nq;
+    const uint32_t u0 = unit_lo + (uint32_t)((uint64_t)n_units * wave / kWaves);
+    const uint32_t u1 = unit_lo + (uint32_t)((uint64_t)n_units * (wave + 1) / kWaves);
+    // lane's panel inside a unit is lane >> 4; quad q adds 4 q panels
+    const uint32_t xa_lane = lds_address(lds_x) + 4u * m.x_span * (uint32_t)(lane >> 4);
+    const uint32_t xa_quad = 16u * m.x_span;
+    const bool x_aligned = (kPacked || m.cols % 2 == 0) && ((uintptr_t)job.x % 4 == 0);
+    const uint32_t c0 = u0 < u1 ? unit_offset(m, u0) : 0u, n_chunks = u0 < u1 ? unit_offset(m, u1) - c0 : 0u;
+    {   // one activation row: larger batches run the MFMA kernel
+      const uint16_t* xb = job.x;
+      float* yb = job.y;
+      __syncthreads();   // the previous dictionary, activation image and slots are no longer in use
+      {
+        uint4 dv[kDictRegs];
+        uint32_t xlo[kXRegs], xhi[kXRegs];
+        const bool dict_now = new_dict;
+        if (dict_now) issue_dictionary<kThreads, kDictRegs>(m, 0, tid, dv);
+        if constexpr (kPacked) {
+          if (x_aligned) issue_activations_packed<true, kThreads, kXRegs>(m, xb, 0, tid, xlo);
+          else issue_activations_packed<false, kThreads, kXRegs>(m, xb, 0, tid, xlo);
+        } else {
+          if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
+          else issue_activations<false, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
+        }
+        zero_activation_gaps<kThreads>(m, tid, lds_x, n_slots);
+        if (tid < 2 * kWaves) slot_band[tid] = -1;
+        if (dict_now) {
+          commit_dictionary<kThreads, kDictRegs>(m, 0, tid, dv, lds_dict);
+          for (uint32_t base = kDictRegs * kThreads; base < m.dict_words / 4; base += kDictRegs * kThreads) {
+            issue_dictionary<kThreads, kDictRegs>(m, base, tid, dv);
+            commit_dictionary<kThreads, kDictRegs>(m, base, tid, dv, lds_dict);
+          }
+        }
+        if constexpr (kPacked) {
+          commit_activations_packed<kThreads, kXRegs>(m, 0, tid, xlo, lds_x, image_cols);
+          for (uint32_t first = kXRegs * kThreads; first < image_cols; first += kXRegs * kThreads) {
+            if (x_aligned) issue_activations_packed<true, kThreads, kXRegs>(m, xb, first, tid, xlo);
+            else issue_activations_packed<false, kThreads, kXRegs>(m, xb, first, tid, xlo);
+            commit_activations_packed<kThreads, kXRegs>(m, first, tid, xlo, lds_x, image_cols);
+          }
+        } else {
+          commit_activations<kThreads, kXRegs>(m, 0, tid, xlo, xhi, lds_x, image_cols);
+          for (uint32_t first = kXRegs * kThreads; 2 * first < image_cols; first += kXRegs * kThreads) {
+            if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
+            else issue_activations<false, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
+            commit_activations<kThreads, kXRegs>(m, first, tid, xlo, xhi, lds_x, image_cols);
+          }
+        }
+      }
+      __syncthreads();
+      if (u0 < u1) {
+        uint32_t q = u0 % nq, band = u0 / nq;
+        bool whole = q == 0;                             // the current band started inside this wavefront's run
+        float a0 = 0.f, a1 = 0.f;
+        uint32_t xa = xa_lane + q * xa_quad;
+        // the scales of the band in work are requested when the band starts (the array is padded to whole bands)
+        float scale = global_load(m.scales + band * kUnitRows + (lane & 15));
+        auto finish_band = [&](bool complete) {
+          const float v = sum_over_panels(a0 + a1);
+          if (complete) {
+            const uint32_t row = band * kUnitRows + lane;
+            if (a.gate_up) {   // lanes 2r, 2r + 1 hold the gate and the up row of output r
+              const float t = v * scale, other = __shfl_xor(t, 1);
+              if (lane < 16 && !(lane & 1) && row + 1 < m.rows) global_store(yb + row / 2, silu_times(t, other));
+            } else if (lane < 16 && row < m.rows) {
+              global_store(yb + row, v * scale);
+            }
+          } else {
+            const int s = 2 * wave + (whole ? 1 : 0);   // slot 2w: band begun by an earlier wavefront; 2w + 1: band left unfinished
+            if (lane < 16) slot_val[s * 16 + lane] = v;
+            if (lane == 0) slot_band[s] = (int)band;
+          }
+        };
+        // The chunks of the run come in pieces of at most kPiece that never straddle a unit (a unit is cut into equal
+        // pieces); two register sets alternate and every piece issues exactly kPiece loads (those past its end repeat
+        // its last chunk), so the loads of the next piece are in flight while this one is worked on.  A piece of kPiece
+        // or kPiece - 1 chunks (all pieces of a unit of 256-column segments) runs as straight-line code: the LDS reads
+        // of later chunks overlap the dot products of earlier ones.
+        uint32_t wu = u0, wc = c0, w_left = 0, w_base = 0, w_rem = 0;
+        auto next_piece = [&](uint32_t& start, uint32_t& n, bool& ends) {
+          if (w_left == 0) {
+            if (wu == u1) {
+              n = 0;
+              ends = false;
+              start = wc;
+              return;
+            }
+            const uint32_t len = unit_offset(m, wu + 1) - wc;
+            w_left = (len + kPiece - 1) / kPiece;
+            w_base = len / w_left;
+            w_rem = len - w_base * w_left;
+            ++wu;
+          }
+          n = w_base + (w_rem ? 1u : 0u);
+          if (w_rem) --w_rem;
+          start = wc;
+          wc += n;
+          ends = --w_left == 0;
+        };
+        const uint32_t run_last = c0 + n_chunks - 1;
+        auto load_piece = [&](uint2 (&cw)[kPiece], uint32_t start, uint32_t n) {
+          const uint32_t last = min(start + max(n, 1u) - 1, run_last);
+#pragma unroll
+          for (int k = 0; k < kPiece; ++k) cw[k] = load_chunk(m.codes, min(start + k, last), lane);
+        };
+        auto run_piece = [&](const uint2 (&cw)[kPiece], uint32_t n, bool ends) {
+          uint32_t w[2][4], x[2][8];   // two register sets: one chunk's operands are read while the one before is multiplied
+          auto read = [&](auto kk) {
+            constexpr int k = decltype(kk)::value;
+            if constexpr (kPacked) chunk4_packed_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);
+            else chunk4_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);
+          };
+          auto dot = [&](auto kk) {
+            constexpr int k = decltype(kk)::value;
+            if constexpr (kPacked) chunk4_packed_dot(w[k & 1], x[k & 1], a0, a1);
+            else chunk4_dot(w[k & 1], x[k & 1], a0, a1);
+          };
+          auto straight = [&](auto nn) {   // a piece of nn chunks as straight-line code
+            constexpr int kN = decltype(nn)::value;
+            read(std::integral_constant<int, 0>{});
+            static_for<kN>([&](auto kk) {
+              constexpr int k = decltype(kk)::value;
+              if constexpr (k + 1 < kN) read(std::integral_constant<int, k + 1>{});
+              dot(kk);
+            });
+          };
+          if (n == kPiece) {
+            straight(std::integral_constant<int, kPiece>{});
+          } else if (n == kPiece - 1) {
+            straight(std::integral_constant<int, kPiece - 1>{});
+          } else if (n == kPiece - 2) {
+            straight(std::integral_constant<int, kPiece - 2>{});
+          } else {
+            static_for<kPiece>([&](auto kk) {
+              if ((uint32_t)decltype(kk)::value < n) {
+                read(kk);
+                dot(kk);
+              }
+            });
+          }
+          xa += 16 * n;
+          if (ends) {   // every lane restarts at the first column of its next segment
+            if (++q == nq) {
+              const bool more = band * nq + nq < u1;
+              finish_band(whole);
+              q = 0;
+              ++band;
+              if (more) scale = global_load(m.scales + band * kUnitRows + (lane & 15));
+              whole = true;
+              a0 = 0.f;
+              a1 = 0.f;
+            }
+            xa = xa_lane + q * xa_quad;
+          }
+        };
+        uint2 cwa[kPiece], cwb[kPiece];
+        uint32_t sa, na, sb, nb;
+        bool ea, eb;
+        next_piece(sa, na, ea);
+        load_piece(cwa, sa, na);
+        while (na) {
+          next_piece(sb, nb, eb);
+          load_piece(cwb, sb, nb);
+          run_piece(cwa, na, ea);
+          next_piece(sa, na, ea);
+          load_piece(cwa, sa, na);
+          run_piece(cwb, nb, eb);
+        }
+        if (u1 % nq) finish_band(false);   // the run ends inside a band (a band that ends with the run was finished above)
+      }
+      __syncthreads();
+      // Combine the shared bands: the first slot of a band adds the later slots of the same band in slot order.
+      if (tid < 2 * kWaves * 16) {
+        const int s = tid >> 4, r16 = tid & 15;
+        const int bnd = slot_band[s];
+        bool first = bnd >= 0;
+        for (int t = 0; t < s; ++t) first = first && slot_band[t] != bnd;
+        if (first) {
+          float sum = slot_val[s * 16 + r16];
+          for (int t = s + 1; t < 2 * kWaves; ++t)
+            if (slot_band[t] == bnd) sum += slot_val[t * 16 + r16];
+          const uint32_t row = (uint32_t)bnd * kUnitRows + r16;
+          if (a.gate_up) {   // the two threads of a pair of rows are neighbours and take this branch together
+            const float t = sum * global_load(m.scales + min(row, m.rows - 1)), other = __shfl_xor(t, 1);
+            if (!(r16 & 1) && row + 1 < m.rows) global_store(yb + row / 2, silu_times(t, other));
+          } else if (row < m.rows) {
+            global_store(yb + row, sum * global_load(m.scales + row));
+          }
+        }
+      }
+    }
+  }
+}
+
+}  // namespace tq

@@ -1,0 +1,204 @@
+// Device side of libtq: constants, kernel-argument structures and the small device helpers every kernel uses.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+#include <utility>
+
+#include "../../include/tq.h"
+#include "tq_format.h"
+
+namespace tq {
+
+constexpr int kWaves = 8;            // most wavefronts per workgroup of the tile kernels (one workgroup per CU: LDS-bound)
+constexpr int kThreads = kWaves * 64;
+constexpr int kDotWavesPacked = 12;  // the same kernel for packed 4-bit weights: more work per byte read, more wavefronts to
+                                     // hide it (config 4, ms per step: 8 wavefronts 0.379, 12 0.370, 16 0.379)
+constexpr int kDotWavesMax = 12;
+constexpr int kDotPiecePacked = 6;   // its units are half as long (segments of 128 bytes: 17 chunks, three pieces of 5 or 6)
+constexpr int kDotWaves = 8;         // wavefronts per workgroup of the batch-1 kernel (measured on the 3B sweep, TB/s:
+                                     // 6 waves 4.61, 8 waves 5.12, 10 waves 4.64, 12 waves 4.90, 16 waves 4.28)
+constexpr int kDotPiece = 8;         // chunks per piece in the batch-1 kernel: two pieces (16 x 512 bytes) are in flight per
+                                     // wavefront (measured on the 3B sweep, TB/s: 4 chunks 5.30, 6 5.48, 8 5.47, 12 5.41, 18 5.24)
+constexpr uint32_t kLdsLimit = 160 * 1024;
+constexpr int kPiece = 12;           // code chunks fetched together by a wavefront (units of 256-column segments are
+                                     // 33..36 chunks long: three pieces with little repetition)
+constexpr int kMaxMulti = 128;       // matrices one launch can serve (bounded by the 4 KB of kernel arguments)
+constexpr int kInlineDescriptions = 4;
+
+// What the kernels need to know about one matrix.
+struct DevMat {
+  const uint32_t* dict;    // container dictionary words (run bytes + length), dict_words of them, zero filled past the pad entry
+  const uint32_t* dict_bf16;   // the same entries as two bf16 weights each (second one zero for a single byte): the form the
+                               // batch-1 kernel keeps in LDS, made once when the dictionary is uploaded
+  const uint32_t* uoff;    // n_units + 1 unit offsets, in chunks
+  const uint2* codes;      // chunk c, lane l -> codes[c * 64 + l] (4 codes)
+  const float* scales;     // n_bands * 16 row scales
+  uint32_t rows, cols, seg_cols;
+  uint32_t n_bands, n_quads;
+  uint32_t dict_words;     // multiple of 4
+  uint32_t x_span;         // dwords per panel in the LDS image of x: seg_cols plus a gap that spreads the 4 panels of a unit over the banks
+  uint32_t x_dwords;       // size of that image, including the columns lanes can reach while they consume pad codes
+  uint32_t seg_magic;      // floor(2^32 / seg_cols) + 1: col / seg_cols == mulhi(col, seg_magic) for every column index in use
+  uint32_t reserved;       // how the ring kernel may decode the matrix: 0 not at all, 1 in groups of windows, 2 window by window
+  uint32_t packing;        // 1: every byte holds two 4-bit weights (columns 2j and 2j + 1 of a matrix of 2 * cols columns); rows,
+                           // cols and seg_cols describe the byte matrix, and dict_bf16 holds four fp8 (e4m3) weights per entry
+};
+
+struct Job {
+  const DevMat* m;         // device copy of the matrix description
+  const uint16_t* x;       // bf16 [batch][cols]
+  float* y;                // fp32 [batch][rows]
+};
+
+// A job together with its matrix description, as a prepared step keeps them in device memory.
+struct StepEntry {
+  DevMat m;
+  const uint16_t* x;
+  float* y;
+};
+constexpr int kMaxStep = 896;        // matrices one launch can serve when the jobs come from a device table
+
+// The launch's cost line: matrix i covers [cost[i], cost[i + 1]), one band of it costs its number of columns.
+// The jobs travel in the kernel arguments (up to kMaxMulti of them) or, for a prepared step, sit in a table in device
+// memory (up to kMaxStep); the cost line is in the arguments either way, at the same place.
+struct MatvecArgs {
+  int n, batch;
+  uint32_t x_off, slot_off;   // byte offsets in LDS of the activation image (or of the tiles) and of the partial-sum slots
+  uint32_t tile_area;         // bytes of LDS per wavefront in the tile kernels (the same for every matrix of the launch)
+  uint32_t gate_up;           // 1: rows 2r and 2r + 1 are a gate and an up projection; y[b][r] = silu(row 2r) * (row 2r + 1)
+  const StepEntry* table;     // device table of the n jobs, or null: then j and first below hold them
+  union {
+    struct {
+      uint32_t cost[kMaxMulti + 1];
+      Job j[kMaxMulti];
+      DevMat first[kInlineDescriptions];   // descriptions of the first matrices by value: a launch of one matrix (or of a
+                                           // few) does not wait for a read of device memory before it can start loading
+    } in;
+    uint32_t cost_long[kMaxStep + 1];
+  } u;
+};
+static_assert(sizeof(MatvecArgs) <= 4096, "kernel arguments");
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) const uint32_t lds_cu32;
+typedef __attribute__((address_space(3))) const uint16_t lds_cu16;
+typedef __attribute__((address_space(3))) uint8_t lds_u8;
+typedef __attribute__((address_space(4))) const uint32_t const_u32;
+
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+// Unit offsets are wave-uniform and never written while a kernel runs: reading them through the constant address
+// space makes them scalar loads, which do not share a counter with the vector loads of the code stream.
+__device__ __forceinline__ uint32_t unit_offset(const DevMat& m, uint32_t u) { return ((const_u32*)m.uoff)[u]; }
+
+// Loads and stores of device memory through the global address space.  Pointers that come out of a matrix description
+// read from memory are generic to the compiler; a generic access is a flat instruction, which counts on the LDS counter
+// as well as on the vector-memory one and so would make every LDS wait a wait for the code stream too.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// Chunk `chunk` of the code stream, lane's 4 codes: a wave-uniform base in scalar registers plus the lane's offset, so
+// that no vector arithmetic goes into the address.
+__device__ __forceinline__ uint2 load_chunk(const uint2* codes, uint32_t chunk, int lane) {
+  const uint64_t base = (uint64_t)codes + (uint64_t)chunk * (64 * sizeof(uint2));
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)base), hi = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32));
+  const u32x2 v = ((__attribute__((address_space(1))) const u32x2*)((uint64_t)hi << 32 | lo))[(uint32_t)lane];
+  return make_uint2(v.x, v.y);
+}
+
+__device__ __forceinline__ uint2 global_load(const uint2* p) {
+  const u32x2 v = *(__attribute__((address_space(1))) const u32x2*)p;
+  return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ uint4 global_load(const uint4* p) {
+  const u32x4 v = *(__attribute__((address_space(1))) const u32x4*)p;
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint32_t global_load(const uint32_t* p) { return *(__attribute__((address_space(1))) const uint32_t*)p; }
+__device__ __forceinline__ uint32_t global_load(const uint16_t* p) { return *(__attribute__((address_space(1))) const uint16_t*)p; }
+__device__ __forceinline__ float global_load(const float* p) { return *(__attribute__((address_space(1))) const float*)p; }
+__device__ __forceinline__ void global_store(float* p, float v) { *(__attribute__((address_space(1))) float*)p = v; }
+
+// A matrix description from device memory, through scalar loads.
+__device__ __forceinline__ DevMat load_description(const DevMat* p) {
+  static_assert(sizeof(DevMat) % 4 == 0, "whole dwords");
+  uint32_t w[sizeof(DevMat) / 4];
+#pragma unroll
+  for (size_t k = 0; k < sizeof(DevMat) / 4; ++k) w[k] = ((const_u32*)p)[k];
+  DevMat m;
+  __builtin_memcpy(&m, w, sizeof m);
+  return m;
+}
+
+// Point i of the launch's cost line (the two forms of the arguments keep it at the same place).
+__device__ __forceinline__ uint32_t cost_at(const MatvecArgs& a, int i) { return a.u.cost_long[i]; }
+
+// Job i of the launch and the description of its matrix: from the kernel arguments, or from the step's device table
+// (scalar loads, like the descriptions the arguments do not hold by value).
+__device__ __forceinline__ void fetch_job(const MatvecArgs& a, int i, Job& job, DevMat& m) {
+  if (a.table) {
+    const StepEntry* e = a.table + i;
+    static_assert(sizeof(StepEntry) % 4 == 0, "whole dwords");
+    uint32_t w[sizeof(StepEntry) / 4];
+#pragma unroll
+    for (size_t k = 0; k < sizeof(StepEntry) / 4; ++k) w[k] = ((const_u32*)e)[k];
+    StepEntry v;
+    __builtin_memcpy(&v, w, sizeof v);
+    m = v.m;
+    job.m = &e->m;
+    job.x = v.x;
+    job.y = v.y;
+  } else {
+    job = a.u.in.j[i];
+    m = i < kInlineDescriptions ? a.u.in.first[i] : load_description(job.m);
+  }
+}
+
+// Byte address inside LDS of a pointer into the workgroup's dynamic shared memory.
+__device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(size_t)(const lds_u8*)p; }
+
+// Pointer forms on purpose: the compiler tracks the outstanding LDS read and places the wait before the first use.
+__device__ __forceinline__ uint32_t lds_read32(uint32_t addr) { return *(lds_cu32*)(size_t)addr; }
+template <int kOff>
+__device__ __forceinline__ uint32_t lds_read32_off(uint32_t addr) { return *(lds_cu32*)(size_t)(addr + kOff); }
+
+// Byte offset of dictionary word `code` for the code in the low / high half of a packed code pair: one SDWA shift
+// (selects the 16-bit half, zero-extends, multiplies by 4) instead of a mask and a shift.
+__device__ __forceinline__ uint32_t word_offset_lo(uint32_t pair) {
+  uint32_t a;
+  const uint32_t two = 2;
+  asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0" : "=v"(a) : "v"(two), "v"(pair));
+  return a;
+}
+__device__ __forceinline__ uint32_t word_offset_hi(uint32_t pair) {
+  uint32_t a;
+  const uint32_t two = 2;
+  asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1" : "=v"(a) : "v"(two), "v"(pair));
+  return a;
+}
+// min(1, high byte of the low / high code): 1 for a two-weight entry (code >= 256, the pad code included), 0 for a single
+__device__ __forceinline__ uint32_t is_pair_lo(uint32_t pair) {
+  uint32_t a;
+  const uint32_t one = 1;
+  asm("v_min_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(a) : "v"(one), "v"(pair));
+  return a;
+}
+__device__ __forceinline__ uint32_t is_pair_hi(uint32_t pair) {
+  uint32_t a;
+  const uint32_t one = 1;
+  asm("v_min_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(a) : "v"(one), "v"(pair));
+  return a;
+}
+__device__ __forceinline__ float dot2(uint32_t w, uint32_t x, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, x), acc, false);
+}
+
+}  // namespace tq
