@@ -136,7 +136,8 @@ int tq_create_from_encoded(const void *blob, size_t blob_bytes, tq_handle *out);
  * the kernel.  The result is deterministic (fixed summation order).  x values must be finite: a lane that has
  * run out of codes multiplies activations of later columns by zero, so an infinity or NaN anywhere in x can make
  * any output of that batch row non-finite (the plain definition does the same wherever a weight is zero).
- * batch 1 runs the dot-product kernel (activations gathered from an LDS image of x), batch 2..16 an MFMA kernel
+ * batch 1 runs the dot-product kernel (activations gathered from an LDS image of x), and so does batch 2 of matrices
+ * with one weight per byte (two rows in the image); batch 3..16 (and batch 2 of packed matrices) an MFMA kernel
  * (the batch is the N dimension).  Of those there are two.  The ring kernel keeps 128 bytes of every segment in LDS
  * and multiplies while it decodes; it takes matrices whose lane_spread (tq_info) is at most 113 columns, whose rows
  * are a whole number of units (cols a multiple of 4 * seg_cols), with seg_cols a multiple of 32 up to 256 and x

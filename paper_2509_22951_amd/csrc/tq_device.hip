@@ -10,7 +10,8 @@
 //   3. tq_matvec gathers the activation pair (x[col], x[col+1]) from an LDS image of x and issues one
 //      v_dot2_f32_bf16 per code; the per-lane sums of the 4 panels of a row are added at the end of a band of 16
 //      rows, multiplied by the row scale and stored,
-//   4. for batches of 2..16 rows and for tq_decompress the lanes append their run bytes to per-lane storage in LDS
+//      (two activation rows are handled the same way, with both rows in the image and one dot product per row),
+//   4. for batches of 3..16 rows and for tq_decompress the lanes append their run bytes to per-lane storage in LDS
 //      instead - a ring of 128 bytes (k_matvec_ring: multiplied by bf16 MFMA, batch = N, while the decode goes on) or
 //      a strip holding the whole segment (k_matvec_mfma: multiplied when the unit is complete; k_decompress: copied
 //      out row-major).
@@ -133,7 +134,7 @@ hipError_t release_dictionary(DictCopy* d) {
   return e != hipSuccess ? e : e2;
 }
 
-constexpr uint32_t kSlotBytes = 2 * kDotWavesMax * 16 * 4 + 2 * kDotWavesMax * 4;
+constexpr uint32_t kSlotBytes = 2 * kDotWavesMax * 2 * 16 * 4 + 2 * kDotWavesMax * 4;   // (two activation rows at most)
 
 // LDS plan of the product kernel for a set of matrices: dictionary | activation image | partial-sum slots.
 bool plan_matvec_lds(uint32_t dict_words_max, uint32_t x_dwords_max, uint32_t* x_off, uint32_t* slot_off, size_t* total) {
@@ -212,8 +213,9 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
     return TQ_E_UNSUPPORTED;
   }
   // Dynamic LDS above 64 KB has to be allowed per kernel function.
-  e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves, false, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves, false, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_decompress, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
@@ -348,12 +350,14 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
   // workgroup per CU at most.
   p.grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>({(uint64_t)hs[0]->n_cu, bands, cost / band_cost_max}));
   const bool packed = hs[0]->m.packing != 0;   // (all matrices of a product launch hold their weights the same way: launch_all sees to that)
-  if (op == Op::kMatvec && batch == 1) {
+  if (op == Op::kMatvec && (batch == 1 || (batch == 2 && !packed))) {
+    // the dot-product kernel: one activation row, or two rows of one-weight-per-byte matrices
     if (!plan_matvec_lds(dict_words_max, x_dwords_max, &a.x_off, &a.slot_off, &p.lds)) {
       set_error("the matrices of this call together need " + std::to_string(p.lds) + " bytes of LDS (largest dictionary plus longest row)");
       return TQ_E_UNSUPPORTED;
     }
-    p.kernel = packed ? (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true> : (const void*)k_matvec<kDotPiece, kDotWaves, false>;
+    p.kernel = packed ? (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1>
+               : batch == 2 ? (const void*)k_matvec<kDotPiece, kDotWaves, false, 2> : (const void*)k_matvec<kDotPiece, kDotWaves, false, 1>;
     p.block = (packed ? kDotWavesPacked : kDotWaves) * 64;
   } else if (ring) {
     // LDS: 16-bit dictionary image | one ring per lane (aligned to its size: the kernel ORs piece offsets into its
@@ -441,7 +445,8 @@ int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* c
       return TQ_OK;
     }
   }
-  if (op == Op::kMatvec && batch > 1 && !ring && !gate_up) {   // (the ring kernel adds partial sums to y: no place for silu)
+  const bool two_rows_dot = batch == 2 && !hs[0]->m.packing;   // (one packing per call from here on) batch 2 of plain matrices: the dot-product kernel
+  if (op == Op::kMatvec && batch > 1 && !two_rows_dot && !ring && !gate_up) {   // (the ring kernel adds partial sums to y: no place for silu)
     // The matrices that can take the ring kernel go there, the others to the whole-strip kernel; the products are
     // independent, so regrouping them changes nothing but the launches.
     // The ring kernel gives whole bands to wavefronts, a quad at a time: it needs many bands per workgroup to keep its

@@ -161,6 +161,48 @@ __device__ __forceinline__ void commit_activations_packed(const DevMat& m, uint3
   }
 }
 
+// Two activation rows (batch 2).  The image holds one dword per column, (x0[c], x1[c]); a code reads the dwords of its
+// column and of the next one (the reads of chunk4_packed_read), two byte permutes put each row's pair together, and one
+// dot product per row follows: a0 collects row 0, a1 row 1.
+__device__ __forceinline__ void chunk4_two_dot(const uint32_t (&w)[4], const uint32_t (&x)[8], float& a0, float& a1) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    a0 = dot2(w[k], __builtin_amdgcn_perm(x[2 * k + 1], x[2 * k], 0x05040100u), a0);   // (x0[c], x0[c + 1])
+    a1 = dot2(w[k], __builtin_amdgcn_perm(x[2 * k + 1], x[2 * k], 0x07060302u), a1);   // (x1[c], x1[c + 1])
+  }
+}
+// Thread t of a round handles the columns (2 j, 2 j + 1), j = first_pair + k * kThreads + t, of both rows.
+template <bool kAligned, int kThreads, int kXRegs>   // kAligned: both rows start 4-byte aligned and cols is even
+__device__ __forceinline__ void issue_activations_two(const DevMat& m, const uint16_t* __restrict__ x, uint32_t first_pair, int tid,
+                                                      uint32_t (&r0)[kXRegs], uint32_t (&r1)[kXRegs]) {
+  const uint16_t* x1 = x + m.cols;
+#pragma unroll
+  for (int k = 0; k < kXRegs; ++k) {
+    const uint32_t j = first_pair + k * kThreads + tid, col = 2 * j;
+    if (kAligned) {
+      r0[k] = col < m.cols ? global_load((const uint32_t*)x + j) : 0u;
+      r1[k] = col < m.cols ? global_load((const uint32_t*)x1 + j) : 0u;
+    } else {
+      r0[k] = (col < m.cols ? global_load(x + col) : 0u) | (col + 1 < m.cols ? global_load(x + col + 1) << 16 : 0u);
+      r1[k] = (col < m.cols ? global_load(x1 + col) : 0u) | (col + 1 < m.cols ? global_load(x1 + col + 1) << 16 : 0u);
+    }
+  }
+}
+template <int kThreads, int kXRegs>
+__device__ __forceinline__ void commit_activations_two(const DevMat& m, uint32_t first_pair, int tid, const uint32_t (&r0)[kXRegs],
+                                                       const uint32_t (&r1)[kXRegs], uint32_t* lds_x, uint32_t image_cols) {
+  const uint32_t gap = m.x_span - m.seg_cols;
+#pragma unroll
+  for (int k = 0; k < kXRegs; ++k) {
+    const uint32_t col = 2 * (first_pair + k * kThreads + tid);
+    if (col < image_cols) {   // image_cols and seg_cols are even: both columns lie in one panel
+      const uint32_t i = col + gap * __umulhi(col, m.seg_magic);
+      lds_x[i] = (r0[k] & 0xFFFFu) | r1[k] << 16;
+      lds_x[i + 1] = r0[k] >> 16 | (r1[k] & 0xFFFF0000u);
+    }
+  }
+}
+
 // Sum of the four panel lanes of each row: afterwards every lane l holds the sum over lanes l % 16 + {0, 16, 32, 48}.
 __device__ __forceinline__ float sum_over_panels(float v) {
   v += __shfl_xor(v, 16);
@@ -180,14 +222,15 @@ __device__ __forceinline__ float silu_times(float gate, float up) { return gate 
 // lies entirely inside its run (it scales and stores those rows itself); a band it shares with its neighbours goes to
 // one of two partial-sum slots in LDS, and after a workgroup barrier the slots of a band are added in wavefront order,
 // so the result does not depend on timing.
-template <int kPiece, int kWaves, bool kPacked>
+template <int kPiece, int kWaves, bool kPacked, int kB>
 __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
+  static_assert(kB == 1 || (kB == 2 && !kPacked), "one activation row, or two with one weight per byte");
   constexpr int kThreads = kWaves * 64, kDictRegs = 128 / kWaves, kXRegs = 64 / kWaves;
   extern __shared__ uint4 lds4[];
   uint32_t* lds_dict = (uint32_t*)lds4;
   uint32_t* lds_x = (uint32_t*)((uint8_t*)lds4 + a.x_off);
-  float* slot_val = (float*)((uint8_t*)lds4 + a.slot_off);           // [2 * kWaves][16]
-  int* slot_band = (int*)(slot_val + 2 * kWaves * 16);               // [2 * kWaves]
+  float* slot_val = (float*)((uint8_t*)lds4 + a.slot_off);           // [2 * kWaves][kB][16]
+  int* slot_band = (int*)(slot_val + 2 * kWaves * kB * 16);          // [2 * kWaves]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   if (lds_address(lds4) != 0) return;   // the code -> word lookup takes the dictionary to start at LDS address 0 (no static LDS here)
   const uint64_t total = cost_at(a, a.n);
@@ -213,9 +256,9 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
     // lane's panel inside a unit is lane >> 4; quad q adds 4 q panels
     const uint32_t xa_lane = lds_address(lds_x) + 4u * m.x_span * (uint32_t)(lane >> 4);
     const uint32_t xa_quad = 16u * m.x_span;
-    const bool x_aligned = (kPacked || m.cols % 2 == 0) && ((uintptr_t)job.x % 4 == 0);
+    const bool x_aligned = (kPacked || m.cols % 2 == 0) && ((uintptr_t)job.x % 4 == 0);   // (cols even: a second row is aligned like the first)
     const uint32_t c0 = u0 < u1 ? unit_offset(m, u0) : 0u, n_chunks = u0 < u1 ? unit_offset(m, u1) - c0 : 0u;
-    {   // one activation row: larger batches run the MFMA kernel
+    {   // one activation row, or two: larger batches run the MFMA kernels
       const uint16_t* xb = job.x;
       float* yb = job.y;
       __syncthreads();   // the previous dictionary, activation image and slots are no longer in use
@@ -227,6 +270,9 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
         if constexpr (kPacked) {
           if (x_aligned) issue_activations_packed<true, kThreads, kXRegs>(m, xb, 0, tid, xlo);
           else issue_activations_packed<false, kThreads, kXRegs>(m, xb, 0, tid, xlo);
+        } else if constexpr (kB == 2) {
+          if (x_aligned) issue_activations_two<true, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
+          else issue_activations_two<false, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
         } else {
           if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
           else issue_activations<false, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
@@ -247,6 +293,13 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
             else issue_activations_packed<false, kThreads, kXRegs>(m, xb, first, tid, xlo);
             commit_activations_packed<kThreads, kXRegs>(m, first, tid, xlo, lds_x, image_cols);
           }
+        } else if constexpr (kB == 2) {
+          commit_activations_two<kThreads, kXRegs>(m, 0, tid, xlo, xhi, lds_x, image_cols);
+          for (uint32_t first = kXRegs * kThreads; 2 * first < image_cols; first += kXRegs * kThreads) {
+            if (x_aligned) issue_activations_two<true, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
+            else issue_activations_two<false, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
+            commit_activations_two<kThreads, kXRegs>(m, first, tid, xlo, xhi, lds_x, image_cols);
+          }
         } else {
           commit_activations<kThreads, kXRegs>(m, 0, tid, xlo, xhi, lds_x, image_cols);
           for (uint32_t first = kXRegs * kThreads; 2 * first < image_cols; first += kXRegs * kThreads) {
@@ -265,18 +318,30 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
         // the scales of the band in work are requested when the band starts (the array is padded to whole bands)
         float scale = global_load(m.scales + band * kUnitRows + (lane & 15));
         auto finish_band = [&](bool complete) {
-          const float v = sum_over_panels(a0 + a1);
+          // one activation row: a0 and a1 are two chains of the same sum; two rows: one sum each
+          float v[kB];
+          if constexpr (kB == 1) {
+            v[0] = sum_over_panels(a0 + a1);
+          } else {
+            v[0] = sum_over_panels(a0);
+            v[1] = sum_over_panels(a1);
+          }
           if (complete) {
             const uint32_t row = band * kUnitRows + lane;
-            if (a.gate_up) {   // lanes 2r, 2r + 1 hold the gate and the up row of output r
-              const float t = v * scale, other = __shfl_xor(t, 1);
-              if (lane < 16 && !(lane & 1) && row + 1 < m.rows) global_store(yb + row / 2, silu_times(t, other));
-            } else if (lane < 16 && row < m.rows) {
-              global_store(yb + row, v * scale);
+#pragma unroll
+            for (int b = 0; b < kB; ++b) {
+              if (a.gate_up) {   // lanes 2r, 2r + 1 hold the gate and the up row of output r
+                const float t = v[b] * scale, other = __shfl_xor(t, 1);
+                if (lane < 16 && !(lane & 1) && row + 1 < m.rows) global_store(yb + (size_t)b * (m.rows / 2) + row / 2, silu_times(t, other));
+              } else if (lane < 16 && row < m.rows) {
+                global_store(yb + (size_t)b * m.rows + row, v[b] * scale);
+              }
             }
           } else {
             const int s = 2 * wave + (whole ? 1 : 0);   // slot 2w: band begun by an earlier wavefront; 2w + 1: band left unfinished
-            if (lane < 16) slot_val[s * 16 + lane] = v;
+#pragma unroll
+            for (int b = 0; b < kB; ++b)
+              if (lane < 16) slot_val[(s * kB + b) * 16 + lane] = v[b];
             if (lane == 0) slot_band[s] = (int)band;
           }
         };
@@ -316,12 +381,13 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
           uint32_t w[2][4], x[2][8];   // two register sets: one chunk's operands are read while the one before is multiplied
           auto read = [&](auto kk) {
             constexpr int k = decltype(kk)::value;
-            if constexpr (kPacked) chunk4_packed_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);
+            if constexpr (kPacked || kB == 2) chunk4_packed_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);   // this dword and the next
             else chunk4_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);
           };
           auto dot = [&](auto kk) {
             constexpr int k = decltype(kk)::value;
             if constexpr (kPacked) chunk4_packed_dot(w[k & 1], x[k & 1], a0, a1);
+            else if constexpr (kB == 2) chunk4_two_dot(w[k & 1], x[k & 1], a0, a1);
             else chunk4_dot(w[k & 1], x[k & 1], a0, a1);
           };
           auto straight = [&](auto nn) {   // a piece of nn chunks as straight-line code
@@ -379,21 +445,21 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
       }
       __syncthreads();
       // Combine the shared bands: the first slot of a band adds the later slots of the same band in slot order.
-      if (tid < 2 * kWaves * 16) {
-        const int s = tid >> 4, r16 = tid & 15;
+      if (tid < 2 * kWaves * kB * 16) {   // one thread per slot, activation row and row of the band
+        const int s = tid / (16 * kB), b = (tid >> 4) % kB, r16 = tid & 15;
         const int bnd = slot_band[s];
         bool first = bnd >= 0;
         for (int t = 0; t < s; ++t) first = first && slot_band[t] != bnd;
         if (first) {
-          float sum = slot_val[s * 16 + r16];
+          float sum = slot_val[(s * kB + b) * 16 + r16];
           for (int t = s + 1; t < 2 * kWaves; ++t)
-            if (slot_band[t] == bnd) sum += slot_val[t * 16 + r16];
+            if (slot_band[t] == bnd) sum += slot_val[(t * kB + b) * 16 + r16];
           const uint32_t row = (uint32_t)bnd * kUnitRows + r16;
           if (a.gate_up) {   // the two threads of a pair of rows are neighbours and take this branch together
             const float t = sum * global_load(m.scales + min(row, m.rows - 1)), other = __shfl_xor(t, 1);
-            if (!(r16 & 1) && row + 1 < m.rows) global_store(yb + row / 2, silu_times(t, other));
+            if (!(r16 & 1) && row + 1 < m.rows) global_store(yb + (size_t)b * (m.rows / 2) + row / 2, silu_times(t, other));
           } else if (row < m.rows) {
-            global_store(yb + row, sum * global_load(m.scales + row));
+            global_store(yb + (size_t)b * m.rows + row, sum * global_load(m.scales + row));
           }
         }
       }

@@ -358,7 +358,7 @@ def test_batched_product_ring_and_whole_strip_kernels_agree(dev, ring_for_small_
         Qo, so = O.quantize_rows(W)
         m = tq.Matrix(blob)
         try:
-            for batch in (2, 5, 8, 16):
+            for batch in (3, 5, 8, 16):        # (batch 2 of these matrices runs on the dot-product kernel)
                 bits, x = make_activations(spec, batch)
                 ref = O.gemv_f64(Qo, so, x)
                 ring = gpu_matvec(m, bits, dev)
@@ -473,6 +473,43 @@ def test_packed_weights_on_the_ring_kernel(dev, ring_for_small_launches):
         finally:
             m.close()
     assert min(spreads[1:]) <= RING_SPREAD_LIMIT, spreads       # at least these run in groups of four pieces
+
+
+def test_two_activation_rows_on_the_dot_product_kernel(dev):
+    """Batch 2 of one-weight-per-byte matrices: both rows in the LDS image, one dot product per row and code.  Unit
+    vectors in either row land on the right column of the right output row; ragged shapes, an odd number of columns
+    (second row misaligned), shared bands, gate/up pairs."""
+    for rows, cols, seg in [(64, 512, 64), (33, 301, 32), (17, 257, 256), (1027, 2048, 256), (200, 768, 192)]:
+        spec = small_case(rows, cols, seed=940 + rows)
+        W = make_weights(spec)
+        Qo, so = O.quantize_rows(W)
+        m = tq.Matrix(tq.tq_encode(W, seg_cols=seg, max_entries=4000))
+        try:
+            bits, x = make_activations(spec, 2)
+            ref = O.gemv_f64(Qo, so, x)
+            for mis in (False, True):
+                got = gpu_matvec(m, bits, dev, misalign=mis)
+                check_outputs(got, ref)
+                assert (np.abs(got - ref) <= 1e-5 * np.abs(ref).max(axis=1, keepdims=True)).all()
+            one = np.stack([gpu_matvec(m, bits[b:b + 1], dev)[0] for b in range(2)])      # each row alone, batch-1 kernel
+            assert np.abs(gpu_matvec(m, bits, dev) - one).max() <= 1e-5 * np.abs(ref).max()
+            e = np.zeros((2, cols), np.float32)
+            for j0, j1 in ((0, cols - 1), (1, 2), (cols // 2, cols // 2 + 1)):
+                e[:] = 0
+                e[0, j0], e[1, j1] = 1.0, -2.0
+                y = gpu_matvec(m, (e.view(np.uint32) >> 16).astype(np.uint16), dev)
+                assert np.array_equal(y[0], so * Qo[:, j0].astype(np.float32)), (rows, cols, j0)
+                assert np.array_equal(y[1], so * (-2.0 * Qo[:, j1].astype(np.float32))), (rows, cols, j1)
+        finally:
+            m.close()
+    sg, su = small_case(120, 640, seed=946), small_case(120, 640, seed=947)
+    Wg, Wu = make_weights(sg), make_weights(su)
+    m = tq.Matrix(tq.tq_encode_gate_up(Wg, Wu, seg_cols=64))
+    try:
+        bits, x = make_activations(sg, 2)
+        check_outputs(_gpu_gate_up(m, bits, dev, 120), O.gate_up_f64(*O.quantize_rows(Wg), *O.quantize_rows(Wu), x))
+    finally:
+        m.close()
 
 
 def test_packed_weights_take_every_nibble_value(dev):
