@@ -19,6 +19,7 @@ Pins (tests/test_oracle_*.py): quantizer closed forms and invariances; serializa
 reduce to numpy slicing; LZW against a published worked example, closed-form all-equal inputs, a
 brute-force longest-match parser on tiny alphabets, round-trip identity and the zeroth-order entropy
 bound; the frequency dictionary against hand-counted inputs and against a plain counting loop; GEMV against numpy float64 matmul and unit-vector probes.  No function here is unpinned.
+tests/test_oracle_pins_catch_mistakes.py plants mistakes here (wrong rounding, index, sign, order) and expects the pins to fail.
 """
 from __future__ import annotations
 

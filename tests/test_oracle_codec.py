@@ -168,6 +168,14 @@ def test_decode_rejects_inconsistent_stream():
     with pytest.raises(ValueError):
         O.lzw_decode(stream, uoff, wrong, d, d.n_entries)
     assert np.array_equal(O.lzw_decode(stream, uoff, seg_len, d, d.n_entries), S)
+    # Padding only ever ends a lane stream: a real code after a pad code is an error even when the lengths still add up.
+    two = np.array([7, 9], np.uint8)
+    codes, snc, d = O.lzw_encode(two, seg_len=np.array([2], np.uint32), max_entries=256, lmax=2)
+    stream, uoff = O.interleave(codes, snc, d.n_entries)
+    assert list(stream[:4]) == [7, 9, 256, 256] and np.array_equal(O.lzw_decode(stream, uoff, [2], d, 256), two)
+    stream[:4] = [7, 256, 9, 256]
+    with pytest.raises(ValueError):
+        O.lzw_decode(stream, uoff, [2], d, 256)
 
 
 def test_dictionary_carried_over_equals_one_run_over_the_concatenation():
