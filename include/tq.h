@@ -136,9 +136,9 @@ int tq_create_from_encoded(const void *blob, size_t blob_bytes, tq_handle *out);
  * the kernel.  The result is deterministic (fixed summation order).  x values must be finite: a lane that has
  * run out of codes multiplies activations of later columns by zero, so an infinity or NaN anywhere in x can make
  * any output of that batch row non-finite (the plain definition does the same wherever a weight is zero).
- * batch 1 runs the dot-product kernel (activations gathered from an LDS image of x), and so does batch 2 of matrices
- * with one weight per byte (two rows in the image); batch 3..16 (and batch 2 of packed matrices) an MFMA kernel
- * (the batch is the N dimension).  Of those there are two.  The ring kernel keeps 128 bytes of every segment in LDS
+ * batch 1 and batch 2 run the dot-product kernel (activations gathered from an LDS image of x, which holds both rows
+ * at batch 2; packed matrices whose two-row image does not fit the LDS beside the dictionary go on as batch 3 does);
+ * batch 3..16 run an MFMA kernel (the batch is the N dimension).  Of those there are two.  The ring kernel keeps 128 bytes of every segment in LDS
  * and multiplies while it decodes; it takes matrices whose lane_spread (tq_info) is at most 113 columns, whose rows
  * are a whole number of units (cols a multiple of 4 * seg_cols), with seg_cols a multiple of 32 up to 256 and x
  * 16-byte aligned, in calls that bring at least 24 bands of 16 rows per compute unit (the environment variable
@@ -147,8 +147,8 @@ int tq_create_from_encoded(const void *blob, size_t blob_bytes, tq_handle *out);
  * sums of a row's later quads (groups of 4 segments) to y with atomic adds, always in the same order; y must not be
  * read or written by anything else on the device while the call runs (true of any output buffer).
  * Containers of packed 4-bit weights (TQ_PACK_NIBBLES): cols is the number of weights per row, twice the stored bytes;
- * batch 1 runs the dot-product kernel with four weights per dictionary entry, batch 2..16 the same two MFMA kernels
- * (the ring kernel then takes segments of at most 128 bytes).
+ * batch 1 and 2 run the dot-product kernel with four weights per dictionary entry, batch 3..16 the same two MFMA
+ * kernels (the ring kernel then takes segments of at most 128 bytes).
  */
 int tq_matvec(tq_handle h, const void *x, void *y, int batch, void *stream);
 
@@ -174,7 +174,7 @@ int tq_matvec_multi(int n, const tq_handle *hs, const void *const *xs, void *con
  *   y[b][r] = silu(g) * u,  g = scale[2r] * sum_j Q[2r][j] x[b][j],  u = scale[2r+1] * sum_j Q[2r+1][j] x[b][j],
  *   silu(g) = g / (1 + exp(-g)) in fp32.
  * y: device, fp32 [batch][rows / 2].  Works on any handle with an even number of rows; otherwise as tq_matvec /
- * tq_matvec_multi (batch 1: dot-product kernel; batch 2..16: the whole-strip MFMA kernel).
+ * tq_matvec_multi (batch 1 and 2: dot-product kernel; batch 3..16: the whole-strip MFMA kernel).
  */
 int tq_encode_gate_up(const float *w_gate, const float *w_up, uint32_t rows, uint32_t cols, const tq_encode_opts *opts,
                       void **blob, size_t *blob_bytes);

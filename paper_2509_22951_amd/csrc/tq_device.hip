@@ -10,7 +10,8 @@
 //   3. tq_matvec gathers the activation pair (x[col], x[col+1]) from an LDS image of x and issues one
 //      v_dot2_f32_bf16 per code; the per-lane sums of the 4 panels of a row are added at the end of a band of 16
 //      rows, multiplied by the row scale and stored,
-//      (two activation rows are handled the same way, with both rows in the image and one dot product per row),
+//      (two activation rows are handled the same way, with both rows in the image and one dot product per row;
+//      packed 4-bit weights: four weights per entry as fp8, two conversions and two dot products per code and row),
 //   4. for batches of 3..16 rows and for tq_decompress the lanes append their run bytes to per-lane storage in LDS
 //      instead - a ring of 128 bytes (k_matvec_ring: multiplied by bf16 MFMA, batch = N, while the decode goes on) or
 //      a strip holding the whole segment (k_matvec_mfma: multiplied when the unit is complete; k_decompress: copied
@@ -144,6 +145,17 @@ bool plan_matvec_lds(uint32_t dict_words_max, uint32_t x_dwords_max, uint32_t* x
   return *total <= kLdsLimit;
 }
 
+// Which batches the dot-product kernel takes: one activation row always (a matrix whose row does not fit is refused when
+// it is created); two rows of one-weight-per-byte matrices (same image size); two rows of packed matrices when the
+// image, twice as large there, still fits beside the dictionary - otherwise those go to the batched kernels.
+bool dot_kernel_takes(int batch, bool packed, uint32_t dict_words_max, uint32_t x_dwords_max) {
+  if (batch == 1 || (batch == 2 && !packed)) return true;
+  if (batch != 2) return false;
+  uint32_t x_off, slot_off;
+  size_t total;
+  return plan_matvec_lds(dict_words_max, 2 * x_dwords_max, &x_off, &slot_off, &total);
+}
+
 }  // namespace
 
 struct tq_matrix {
@@ -216,6 +228,7 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves, false, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves, false, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_decompress, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
@@ -350,13 +363,13 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
   // workgroup per CU at most.
   p.grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>({(uint64_t)hs[0]->n_cu, bands, cost / band_cost_max}));
   const bool packed = hs[0]->m.packing != 0;   // (all matrices of a product launch hold their weights the same way: launch_all sees to that)
-  if (op == Op::kMatvec && (batch == 1 || (batch == 2 && !packed))) {
-    // the dot-product kernel: one activation row, or two rows of one-weight-per-byte matrices
-    if (!plan_matvec_lds(dict_words_max, x_dwords_max, &a.x_off, &a.slot_off, &p.lds)) {
+  if (op == Op::kMatvec && dot_kernel_takes(batch, packed, dict_words_max, x_dwords_max)) {
+    // the dot-product kernel: one activation row or two
+    if (!plan_matvec_lds(dict_words_max, (packed && batch == 2 ? 2 : 1) * x_dwords_max, &a.x_off, &a.slot_off, &p.lds)) {
       set_error("the matrices of this call together need " + std::to_string(p.lds) + " bytes of LDS (largest dictionary plus longest row)");
       return TQ_E_UNSUPPORTED;
     }
-    p.kernel = packed ? (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1>
+    p.kernel = packed ? (batch == 2 ? (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2> : (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1>)
                : batch == 2 ? (const void*)k_matvec<kDotPiece, kDotWaves, false, 2> : (const void*)k_matvec<kDotPiece, kDotWaves, false, 1>;
     p.block = (packed ? kDotWavesPacked : kDotWaves) * 64;
   } else if (ring) {
@@ -445,7 +458,17 @@ int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* c
       return TQ_OK;
     }
   }
-  const bool two_rows_dot = batch == 2 && !hs[0]->m.packing;   // (one packing per call from here on) batch 2 of plain matrices: the dot-product kernel
+  // (one packing per call from here on)  Batch 2 on the dot-product kernel: decided for the whole call from its largest
+  // dictionary and longest row, so that every launch cut from it decides the same.
+  bool two_rows_dot = false;
+  if (op == Op::kMatvec && batch == 2) {
+    uint32_t dict_words_max = 0, x_dwords_max = 0;
+    for (int i = 0; i < n; ++i) {
+      dict_words_max = std::max(dict_words_max, hs[i]->m.dict_words);
+      x_dwords_max = std::max(x_dwords_max, hs[i]->m.x_dwords);
+    }
+    two_rows_dot = dot_kernel_takes(2, hs[0]->m.packing != 0, dict_words_max, x_dwords_max);
+  }
   if (op == Op::kMatvec && batch > 1 && !two_rows_dot && !ring && !gate_up) {   // (the ring kernel adds partial sums to y: no place for silu)
     // The matrices that can take the ring kernel go there, the others to the whole-strip kernel; the products are
     // independent, so regrouping them changes nothing but the launches.

@@ -57,12 +57,13 @@ __device__ __forceinline__ void commit_activations(const DevMat& m, uint32_t fir
     }
   }
 }
-template <int kThreads>
+template <int kThreads, int kDwords = 1>   // kDwords: dwords per column of the image (2: two rows of packed weights)
 __device__ __forceinline__ void zero_activation_gaps(const DevMat& m, int tid, uint32_t* lds_x, uint32_t n_slots) {
   const uint32_t gap = m.x_span - m.seg_cols;
-  if (gap)   // gap is 16 dwords
-    for (uint32_t i = tid; i < n_slots * 16; i += kThreads) lds_x[(i >> 4) * m.x_span + m.seg_cols + (i & 15)] = 0u;
-  for (uint32_t i = n_slots * m.x_span + tid; i < m.x_dwords; i += kThreads) lds_x[i] = 0u;
+  constexpr uint32_t kGap = 16 * kDwords;
+  if (gap)   // gap is 16 columns
+    for (uint32_t i = tid; i < n_slots * kGap; i += kThreads) lds_x[kDwords * ((i / kGap) * m.x_span + m.seg_cols) + i % kGap] = 0u;
+  for (uint32_t i = kDwords * n_slots * m.x_span + tid; i < kDwords * m.x_dwords; i += kThreads) lds_x[i] = 0u;
 }
 
 // One chunk = 4 codes per lane.  xa = LDS byte address of the activation pair of the lane's next code, minus 4 bytes
@@ -76,6 +77,11 @@ __device__ __forceinline__ void zero_activation_gaps(const DevMat& m, int tid, u
 __device__ __forceinline__ uint32_t advance_by_pair(uint32_t pair, uint32_t xa) {
   uint32_t r;
   asm("v_lshl_add_u32 %0, %1, 2, %2" : "=v"(r) : "v"(pair), "v"(xa));
+  return r;
+}
+__device__ __forceinline__ uint32_t advance_by_wide_pair(uint32_t pair, uint32_t xa) {   // xa + 8 * pair: an image of 8 bytes per column
+  uint32_t r;
+  asm("v_lshl_add_u32 %0, %1, 3, %2" : "=v"(r) : "v"(pair), "v"(xa));
   return r;
 }
 
@@ -161,6 +167,54 @@ __device__ __forceinline__ void commit_activations_packed(const DevMat& m, uint3
   }
 }
 
+// Two activation rows of packed weights.  The image holds two dwords per byte column: the two activations of that byte
+// in row 0, then those in row 1; a code reads the 16 bytes of its byte column and the next one at xa + 8 k, and each
+// half of the dictionary word, converted once, meets the dword of either row: a0 collects row 0, a1 row 1.
+template <int kCode0>
+__device__ __forceinline__ void chunk4_packed_two_read(uint2 c, uint32_t& xa, uint32_t (&w)[4], uint64_t (&x)[8]) {
+  w[0] = lds_read32(word_offset_lo(c.x));
+  w[1] = lds_read32(word_offset_hi(c.x));
+  w[2] = lds_read32(word_offset_lo(c.y));
+  w[3] = lds_read32(word_offset_hi(c.y));
+  x[0] = lds_read64_off<8 * kCode0>(xa);
+  x[1] = lds_read64_off<8 * kCode0 + 8>(xa);
+  xa = advance_by_wide_pair(is_pair_lo(c.x), xa);
+  x[2] = lds_read64_off<8 * kCode0 + 8>(xa);
+  x[3] = lds_read64_off<8 * kCode0 + 16>(xa);
+  xa = advance_by_wide_pair(is_pair_hi(c.x), xa);
+  x[4] = lds_read64_off<8 * kCode0 + 16>(xa);
+  x[5] = lds_read64_off<8 * kCode0 + 24>(xa);
+  xa = advance_by_wide_pair(is_pair_lo(c.y), xa);
+  x[6] = lds_read64_off<8 * kCode0 + 24>(xa);
+  x[7] = lds_read64_off<8 * kCode0 + 32>(xa);
+  xa = advance_by_wide_pair(is_pair_hi(c.y), xa);
+}
+__device__ __forceinline__ void chunk4_packed_two_dot(const uint32_t (&w)[4], const uint64_t (&x)[8], float& a0, float& a1) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const bf16x2 first = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[k], 1.0f, false);   // the weights of the code's first byte
+    const bf16x2 second = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[k], 1.0f, true);   // of its second byte (zeros after a single)
+    a0 = __builtin_amdgcn_fdot2_f32_bf16(first, __builtin_bit_cast(bf16x2, (uint32_t)x[2 * k]), a0, false);
+    a1 = __builtin_amdgcn_fdot2_f32_bf16(first, __builtin_bit_cast(bf16x2, (uint32_t)(x[2 * k] >> 32)), a1, false);
+    a0 = __builtin_amdgcn_fdot2_f32_bf16(second, __builtin_bit_cast(bf16x2, (uint32_t)x[2 * k + 1]), a0, false);
+    a1 = __builtin_amdgcn_fdot2_f32_bf16(second, __builtin_bit_cast(bf16x2, (uint32_t)(x[2 * k + 1] >> 32)), a1, false);
+  }
+}
+template <int kThreads, int kXRegs>
+__device__ __forceinline__ void commit_activations_packed_two(const DevMat& m, uint32_t first, int tid, const uint32_t (&r0)[kXRegs],
+                                                              const uint32_t (&r1)[kXRegs], uint32_t* lds_x, uint32_t image_cols) {
+  const uint32_t gap = m.x_span - m.seg_cols;
+#pragma unroll
+  for (int k = 0; k < kXRegs; ++k) {
+    const uint32_t j = first + k * kThreads + tid;
+    if (j < image_cols) {
+      const uint32_t i = 2 * (j + gap * __umulhi(j, m.seg_magic));
+      lds_x[i] = r0[k];
+      lds_x[i + 1] = r1[k];
+    }
+  }
+}
+
 // Two activation rows (batch 2).  The image holds one dword per column, (x0[c], x1[c]); a code reads the dwords of its
 // column and of the next one (the reads of chunk4_packed_read), two byte permutes put each row's pair together, and one
 // dot product per row follows: a0 collects row 0, a1 row 1.
@@ -224,7 +278,8 @@ __device__ __forceinline__ float silu_times(float gate, float up) { return gate 
 // so the result does not depend on timing.
 template <int kPiece, int kWaves, bool kPacked, int kB>
 __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
-  static_assert(kB == 1 || (kB == 2 && !kPacked), "one activation row, or two with one weight per byte");
+  static_assert(kB == 1 || kB == 2, "one activation row or two");
+  constexpr int kImage = kPacked && kB == 2 ? 2 : 1;   // dwords of the activation image per column
   constexpr int kThreads = kWaves * 64, kDictRegs = 128 / kWaves, kXRegs = 64 / kWaves;
   extern __shared__ uint4 lds4[];
   uint32_t* lds_dict = (uint32_t*)lds4;
@@ -254,8 +309,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
     const uint32_t u0 = unit_lo + (uint32_t)((uint64_t)n_units * wave / kWaves);
     const uint32_t u1 = unit_lo + (uint32_t)((uint64_t)n_units * (wave + 1) / kWaves);
     // lane's panel inside a unit is lane >> 4; quad q adds 4 q panels
-    const uint32_t xa_lane = lds_address(lds_x) + 4u * m.x_span * (uint32_t)(lane >> 4);
-    const uint32_t xa_quad = 16u * m.x_span;
+    const uint32_t xa_lane = lds_address(lds_x) + 4u * kImage * m.x_span * (uint32_t)(lane >> 4);
+    const uint32_t xa_quad = 16u * kImage * m.x_span;
     const bool x_aligned = (kPacked || m.cols % 2 == 0) && ((uintptr_t)job.x % 4 == 0);   // (cols even: a second row is aligned like the first)
     const uint32_t c0 = u0 < u1 ? unit_offset(m, u0) : 0u, n_chunks = u0 < u1 ? unit_offset(m, u1) - c0 : 0u;
     {   // one activation row, or two: larger batches run the MFMA kernels
@@ -270,6 +325,10 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
         if constexpr (kPacked) {
           if (x_aligned) issue_activations_packed<true, kThreads, kXRegs>(m, xb, 0, tid, xlo);
           else issue_activations_packed<false, kThreads, kXRegs>(m, xb, 0, tid, xlo);
+          if constexpr (kB == 2) {   // the second row starts 2 * cols activations later, aligned like the first
+            if (x_aligned) issue_activations_packed<true, kThreads, kXRegs>(m, xb + 2 * m.cols, 0, tid, xhi);
+            else issue_activations_packed<false, kThreads, kXRegs>(m, xb + 2 * m.cols, 0, tid, xhi);
+          }
         } else if constexpr (kB == 2) {
           if (x_aligned) issue_activations_two<true, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
           else issue_activations_two<false, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
@@ -277,7 +336,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
           if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
           else issue_activations<false, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
         }
-        zero_activation_gaps<kThreads>(m, tid, lds_x, n_slots);
+        zero_activation_gaps<kThreads, kImage>(m, tid, lds_x, n_slots);
         if (tid < 2 * kWaves) slot_band[tid] = -1;
         if (dict_now) {
           commit_dictionary<kThreads, kDictRegs>(m, 0, tid, dv, lds_dict);
@@ -286,7 +345,19 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
             commit_dictionary<kThreads, kDictRegs>(m, base, tid, dv, lds_dict);
           }
         }
-        if constexpr (kPacked) {
+        if constexpr (kPacked && kB == 2) {
+          commit_activations_packed_two<kThreads, kXRegs>(m, 0, tid, xlo, xhi, lds_x, image_cols);
+          for (uint32_t first = kXRegs * kThreads; first < image_cols; first += kXRegs * kThreads) {
+            if (x_aligned) {
+              issue_activations_packed<true, kThreads, kXRegs>(m, xb, first, tid, xlo);
+              issue_activations_packed<true, kThreads, kXRegs>(m, xb + 2 * m.cols, first, tid, xhi);
+            } else {
+              issue_activations_packed<false, kThreads, kXRegs>(m, xb, first, tid, xlo);
+              issue_activations_packed<false, kThreads, kXRegs>(m, xb + 2 * m.cols, first, tid, xhi);
+            }
+            commit_activations_packed_two<kThreads, kXRegs>(m, first, tid, xlo, xhi, lds_x, image_cols);
+          }
+        } else if constexpr (kPacked) {
           commit_activations_packed<kThreads, kXRegs>(m, 0, tid, xlo, lds_x, image_cols);
           for (uint32_t first = kXRegs * kThreads; first < image_cols; first += kXRegs * kThreads) {
             if (x_aligned) issue_activations_packed<true, kThreads, kXRegs>(m, xb, first, tid, xlo);
@@ -378,15 +449,18 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
           for (int k = 0; k < kPiece; ++k) cw[k] = load_chunk(m.codes, min(start + k, last), lane);
         };
         auto run_piece = [&](const uint2 (&cw)[kPiece], uint32_t n, bool ends) {
-          uint32_t w[2][4], x[2][8];   // two register sets: one chunk's operands are read while the one before is multiplied
+          uint32_t w[2][4];   // two register sets: one chunk's operands are read while the one before is multiplied
+          std::conditional_t<kImage == 2, uint64_t, uint32_t> x[2][8];
           auto read = [&](auto kk) {
             constexpr int k = decltype(kk)::value;
-            if constexpr (kPacked || kB == 2) chunk4_packed_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);   // this dword and the next
+            if constexpr (kImage == 2) chunk4_packed_two_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);
+            else if constexpr (kPacked || kB == 2) chunk4_packed_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);   // this dword and the next
             else chunk4_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);
           };
           auto dot = [&](auto kk) {
             constexpr int k = decltype(kk)::value;
-            if constexpr (kPacked) chunk4_packed_dot(w[k & 1], x[k & 1], a0, a1);
+            if constexpr (kImage == 2) chunk4_packed_two_dot(w[k & 1], x[k & 1], a0, a1);
+            else if constexpr (kPacked) chunk4_packed_dot(w[k & 1], x[k & 1], a0, a1);
             else if constexpr (kB == 2) chunk4_two_dot(w[k & 1], x[k & 1], a0, a1);
             else chunk4_dot(w[k & 1], x[k & 1], a0, a1);
           };
@@ -413,7 +487,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
               }
             });
           }
-          xa += 16 * n;
+          xa += 16 * kImage * n;
           if (ends) {   // every lane restarts at the first column of its next segment
             if (++q == nq) {
               const bool more = band * nq + nq < u1;

@@ -83,6 +83,7 @@ static_assert(sizeof(MatvecArgs) <= 4096, "kernel arguments");
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) const uint32_t lds_cu32;
+typedef __attribute__((address_space(3))) const uint64_t lds_cq64;
 typedef __attribute__((address_space(3))) const uint16_t lds_cu16;
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
 typedef __attribute__((address_space(4))) const uint32_t const_u32;
@@ -169,6 +170,8 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_
 __device__ __forceinline__ uint32_t lds_read32(uint32_t addr) { return *(lds_cu32*)(size_t)addr; }
 template <int kOff>
 __device__ __forceinline__ uint32_t lds_read32_off(uint32_t addr) { return *(lds_cu32*)(size_t)(addr + kOff); }
+template <int kOff>   // addr + kOff is 8-byte aligned
+__device__ __forceinline__ uint64_t lds_read64_off(uint32_t addr) { return *(lds_cq64*)(size_t)(addr + kOff); }
 
 // Byte offset of dictionary word `code` for the code in the low / high half of a packed code pair: one SDWA shift
 // (selects the 16-bit half, zero-extends, multiplies by 4) instead of a mask and a shift.

@@ -269,7 +269,7 @@ def test_decompress_multi_is_bit_exact(dev):
         m.close()
 
 
-@pytest.mark.parametrize("config,width,pack,batches", [(4, 8, False, (1, 8, 16)), (4, 4, True, (1, 8, 16)),
+@pytest.mark.parametrize("config,width,pack,batches", [(4, 8, False, (1, 8, 16)), (4, 4, True, (1, 2, 8, 16)),
                                                        (5, 8, False, (16,)), (3, 8, False, (1,)), (2, 8, False, (1,))])
 def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows(dev, config, width, pack, batches):
     """Config-4 shapes at full size (one 3B layer plus lm_head 128256 x 3072), encoded as bench.py encodes them (one
@@ -508,6 +508,54 @@ def test_two_activation_rows_on_the_dot_product_kernel(dev):
     try:
         bits, x = make_activations(sg, 2)
         check_outputs(_gpu_gate_up(m, bits, dev, 120), O.gate_up_f64(*O.quantize_rows(Wg), *O.quantize_rows(Wu), x))
+    finally:
+        m.close()
+
+
+def test_two_activation_rows_of_packed_weights(dev):
+    """Batch 2 of packed 4-bit matrices on the dot-product kernel (two dwords per byte column in the LDS image): ragged
+    shapes, misaligned activations, shared bands, unit vectors in either row, every nibble value; a row too long for the
+    doubled image goes to the batched kernels and gives the same result."""
+    for rows, cols, seg in [(64, 512, 64), (33, 302, 32), (17, 258, 128), (1027, 2048, 128), (200, 768, 96), (32, 49152, 128)]:
+        spec = small_case(rows, cols, seed=960 + rows)
+        W = make_weights(spec)
+        Qo, so = O.quantize_rows(W, 4)
+        m = tq.Matrix(tq.tq_encode(W, seg_cols=seg, max_entries=4000, bits=4, pack=True))
+        try:
+            assert np.array_equal(gpu_decompress(m, dev), Qo)
+            bits, x = make_activations(spec, 2)
+            ref = O.gemv_f64(Qo, so, x)
+            for mis in (False, True):
+                got = gpu_matvec(m, bits, dev, misalign=mis)
+                check_outputs(got, ref)
+                assert (np.abs(got - ref) <= 1e-5 * np.abs(ref).max(axis=1, keepdims=True)).all()
+            one = np.stack([gpu_matvec(m, bits[b:b + 1], dev)[0] for b in range(2)])      # each row alone, batch-1 kernel
+            assert np.abs(gpu_matvec(m, bits, dev) - one).max() <= 1e-5 * np.abs(ref).max()
+            e = np.zeros((2, cols), np.float32)
+            for j0, j1 in ((0, cols - 1), (1, 2), (cols // 2, cols // 2 + 1), (3, 0)):
+                e[:] = 0
+                e[0, j0], e[1, j1] = 1.0, -2.0
+                y = gpu_matvec(m, (e.view(np.uint32) >> 16).astype(np.uint16), dev)
+                assert np.array_equal(y[0], so * Qo[:, j0].astype(np.float32)), (rows, cols, j0)
+                assert np.array_equal(y[1], so * (-2.0 * Qo[:, j1].astype(np.float32))), (rows, cols, j1)
+        finally:
+            m.close()
+    rng = np.random.default_rng(13)
+    Q = rng.integers(-8, 8, (48, 512), dtype=np.int8)
+    Q[0, :16] = np.arange(-8, 8)
+    s = (rng.random(48) + 0.5).astype(np.float32)
+    m = tq.Matrix(tq.tq_encode_quantized(Q, s, seg_cols=64, pack=True))
+    try:
+        bits, x = make_activations(small_case(48, 512, seed=972), 2)
+        check_outputs(gpu_matvec(m, bits, dev), O.gemv_f64(Q, s, x), tol=1e-5)
+    finally:
+        m.close()
+    sg, su = small_case(120, 640, seed=948), small_case(120, 640, seed=949)
+    Wg, Wu = make_weights(sg), make_weights(su)
+    m = tq.Matrix(tq.tq_encode_gate_up(Wg, Wu, seg_cols=64, bits=4, pack=True))
+    try:
+        bits, x = make_activations(sg, 2)
+        check_outputs(_gpu_gate_up(m, bits, dev, 120), O.gate_up_f64(*O.quantize_rows(Wg, 4), *O.quantize_rows(Wu, 4), x))
     finally:
         m.close()
 
