@@ -272,6 +272,7 @@ def main():
     groups.append(cur)
 
     launches = [0]   # kernel launches per step relative to tq_matvec_multi's, for the batch run last
+    spread = {}      # batch -> per-step durations (ms) of a second, separately timed pass
 
     def run(batch, steps, warmup):
         xs, ys = make_io(batch)
@@ -318,6 +319,15 @@ def main():
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3 / steps
         ev_ms = e0.elapsed_time(e1) / steps
+        # after the timed region: the same steps once more with an event between every two, for the spread
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(min(steps, 100) + 1)]
+        marks[0].record()
+        for e in marks[1:]:
+            step()
+            e.record()
+        torch.cuda.synchronize()
+        each = sorted(a.elapsed_time(b) for a, b in zip(marks[:-1], marks[1:]))
+        spread[batch] = {"median": round(each[len(each) // 2], 4), "min": round(each[0], 4), "max": round(each[-1], 4), "n": len(each)}
         return wall_ms, ev_ms
 
     setup_s = time.time() - t_setup
@@ -333,7 +343,8 @@ def main():
     if args.also_batch and args.also_batch != args.batch:
         w2, e2 = run(args.also_batch, max(3, args.steps // 2), args.warmup)
         others[str(args.also_batch)] = {"ms_per_step": round(w2, 4), "GBps": round(comp_bytes / w2 / 1e6, 1),
-                                        "tokens_per_s": round(args.also_batch / (w2 * 1e-3), 1)}
+                                        "tokens_per_s": round(args.also_batch / (w2 * 1e-3), 1),
+                                        "step_ms": spread.get(args.also_batch)}
 
     decompress = None
     if not args.no_decompress:
@@ -394,6 +405,7 @@ def main():
         "dtype": f"bf16 activations x {'int8' if args.bits == 8 else str(args.bits) + '-bit'} weights, fp32 accumulate",
         "data": "synthetic",
         "tokens_per_s": round(args.batch / (wall_ms * 1e-3), 1),
+        "step_ms": spread.get(args.batch),   # one event pair per step, in a pass of its own after the timed region
         "config": {
             "workload": f"config {args.config}: {CONFIGS[args.config]['desc']}, batch {args.batch}",
             "matrices": len(specs), "weights": n_weights, "compressed_bytes": comp_bytes,
@@ -403,6 +415,9 @@ def main():
             "dictionary": args.dictionary, "dictionary_kind": args.dictionary_kind, "bits": args.bits, "packing": "nibbles" if args.pack else "none", "fuse": args.fuse, "prepared_step": not args.no_prepared_step,
             "kernel_launches_per_step": n_launches,
             "hip_graph": bool(args.graph),
+            # activations read and outputs written per step: beside the compressed bytes, not part of `value`
+            "x_bytes_per_step": sum(2 * args.batch * s.cols for s in specs),
+            "y_bytes_per_step": sum(4 * args.batch * s.rows for s in specs),
         },
         "roofline": {
             "bound": "hbm", "kernel": "tq::k_matvec",
@@ -438,6 +453,16 @@ def main():
                       f"float64 GEMV, batch {args.batch}; whole sweep extrapolates to {dt * n_weights / sw:.1f} s/token",
             "tokens_per_s_extrapolated": round(args.batch / (dt * n_weights / sw), 4),
         }
+        # the same sample once more, the matrices (independent of each other) spread over the host's threads
+        n_thr = max(1, min(args.threads, len(sample_blobs)))
+        work = [(blob, make_activations(specs[i], args.batch)[1]) for i, blob in sorted(sample_blobs.items())]
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=n_thr) as pool:
+            list(pool.map(lambda bx: O.matvec_from_blob(*bx), work))
+        dt_all = time.perf_counter() - t0
+        model = next((l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name")), "unknown")
+        result["cpu_baseline"]["all_threads"] = {"value": round(sb / dt_all / 1e9, 3), "unit": "GB/s", "threads": n_thr,
+                                                 "seconds": round(dt_all, 2), "os_cpu_count": os.cpu_count(), "cpu": model}
     print(json.dumps(result), flush=True)
     for m in mats:
         m.close()
