@@ -71,6 +71,9 @@ def parse_args():
                     help="launch through tq_matvec_multi (at most 128 matrices per kernel launch) instead of a prepared tq_step")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and replay it (takes the host's launch cost out of plans with many launches)")
+    ap.add_argument("--copies", type=int, default=0,
+                    help="copies of the compressed matrices in device memory that the steps rotate over, so that a workload "
+                         "smaller than the caches is still read from HBM (0 = as many as make 512 MB; 1 = none, cache-resident)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, so a counter profile of this command holds a kernel of "
                          "known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -204,6 +207,8 @@ def main():
     # matrix) or the first layer is through; from then on it is frozen at the size it has reached, so the remaining
     # matrices no longer depend on each other and are encoded in parallel.
     mats = [None] * len(specs)
+    keep_blobs = sum(s.rows * s.cols for s in specs) < 400_000_000 and args.copies != 1   # small workload: further copies are made below
+    blobs = {}
     cap = args.max_entries or tq.TQ_MAX_ENTRIES_DEVICE
     prev, n_chain = None, 0
     while n_chain < min(7, len(specs)):
@@ -213,6 +218,8 @@ def main():
         mats[i] = tq.Matrix(blob)
         if specs[i].name in sample_names:
             sample_blobs[i] = blob
+        if keep_blobs:
+            blobs[i] = blob
         prev = blob
         n_chain += 1
         if args.dictionary != "sequence" or mats[i].info["n_entries"] == cap:
@@ -232,6 +239,8 @@ def main():
             mats[i] = tq.Matrix(blob)                   # validates, uploads, frees nothing on the hot path later
             if specs[i].name in sample_names:
                 sample_blobs[i] = blob
+            if keep_blobs:
+                blobs[i] = blob
     infos = [m.info for m in mats]
     # bytes the kernels must read from HBM: code stream, unit offsets and scales of every matrix, and every distinct
     # dictionary once (matrices encoded as one sequence hold the same dictionary; the library stores one copy)
@@ -242,6 +251,13 @@ def main():
         comp_bytes = stream_bytes + sum(i["dict_bytes"] for i in infos)
     n_weights = sum(s.rows * s.cols for s in specs)
     n_codes = sum(i["n_codes"] for i in infos)
+
+    # Cold-cache protocol: a workload that fits the caches is held in several copies and step k reads copy k mod N.
+    n_copies = args.copies if args.copies > 0 else (-(-512_000_000 // comp_bytes) if keep_blobs else 1)
+    if not keep_blobs:
+        n_copies = 1
+    mat_sets = [mats] + [[tq.Matrix(blobs[i]) for i in range(len(specs))] for _ in range(n_copies - 1)]
+    blobs.clear()
 
     stream = torch.cuda.current_stream().cuda_stream
 
@@ -276,27 +292,31 @@ def main():
 
     def run(batch, steps, warmup):
         xs, ys = make_io(batch)
-        calls = []            # one per group; each takes the stream to launch on
         launches[0] = 0
-        for g in groups:
-            if len(g) == 1:   # one matrix: its description travels in the kernel arguments
-                m, xp, yp = mats[g[0]], xs[g[0]].data_ptr(), ys[g[0]].data_ptr()
-                calls.append(lambda s, m=m, xp=xp, yp=yp: m.matvec(xp, yp, batch, s))
-            elif args.no_prepared_step:
-                mc = tq.MultiCall([mats[i].handle for i in g], [xs[i].data_ptr() for i in g],
-                                  [ys[i].data_ptr() for i in g], batch)
-                calls.append(lambda s, mc=mc: mc.launch(s))
-            else:   # the same products as a prepared step: buffers fixed, jobs in device memory, up to 896 matrices per launch
-                st = tq.Step([mats[i].handle for i in g], [xs[i].data_ptr() for i in g], [ys[i].data_ptr() for i in g], batch)
-                launches[0] += st.info["n_launches"] - (-(-len(g) // 128))
-                calls.append(lambda s, st=st: st.launch(s))
 
-        def eager_step():
-            for c in calls:
-                c(stream)
+        def calls_for(ms, count):
+            calls = []            # one per group; each takes the stream to launch on
+            for g in groups:
+                if len(g) == 1:   # one matrix: its description travels in the kernel arguments
+                    m, xp, yp = ms[g[0]], xs[g[0]].data_ptr(), ys[g[0]].data_ptr()
+                    calls.append(lambda s, m=m, xp=xp, yp=yp: m.matvec(xp, yp, batch, s))
+                elif args.no_prepared_step:
+                    mc = tq.MultiCall([ms[i].handle for i in g], [xs[i].data_ptr() for i in g],
+                                      [ys[i].data_ptr() for i in g], batch)
+                    calls.append(lambda s, mc=mc: mc.launch(s))
+                else:   # the same products as a prepared step: buffers fixed, jobs in device memory, up to 896 matrices per launch
+                    st = tq.Step([ms[i].handle for i in g], [xs[i].data_ptr() for i in g], [ys[i].data_ptr() for i in g], batch)
+                    if count:
+                        launches[0] += st.info["n_launches"] - (-(-len(g) // 128))
+                    calls.append(lambda s, st=st: st.launch(s))
+            return calls
 
-        step = eager_step
-        if args.graph:
+        def stepper(calls):
+            def eager_step():
+                for c in calls:
+                    c(stream)
+            if not args.graph:
+                return eager_step
             eager_step()
             torch.cuda.synchronize()
             side = torch.cuda.Stream()
@@ -305,7 +325,14 @@ def main():
                 cap = torch.cuda.current_stream().cuda_stream
                 for c in calls:      # the same calls, issued on the capturing stream
                     c(cap)
-            step = graph.replay
+            return graph.replay
+
+        steppers = [stepper(calls_for(ms, k == 0)) for k, ms in enumerate(mat_sets)]
+        turn = [0]
+
+        def step():   # copy after copy
+            steppers[turn[0] % len(steppers)]()
+            turn[0] += 1
 
         for _ in range(warmup):
             step()
@@ -415,6 +442,9 @@ def main():
             "dictionary": args.dictionary, "dictionary_kind": args.dictionary_kind, "bits": args.bits, "packing": "nibbles" if args.pack else "none", "fuse": args.fuse, "prepared_step": not args.no_prepared_step,
             "kernel_launches_per_step": n_launches,
             "hip_graph": bool(args.graph),
+            "cache": (f"cold: the steps rotate over {n_copies} copies of the compressed matrices ({n_copies * comp_bytes / 1e6:.0f} MB)" if n_copies > 1
+                      else "cold: one step streams more than the caches hold" if comp_bytes >= 512_000_000
+                      else "cache-resident: the same compressed bytes are read again every step"),
             # activations read and outputs written per step: beside the compressed bytes, not part of `value`
             "x_bytes_per_step": sum(2 * args.batch * s.cols for s in specs),
             "y_bytes_per_step": sum(4 * args.batch * s.rows for s in specs),
@@ -464,8 +494,9 @@ def main():
         result["cpu_baseline"]["all_threads"] = {"value": round(sb / dt_all / 1e9, 3), "unit": "GB/s", "threads": n_thr,
                                                  "seconds": round(dt_all, 2), "os_cpu_count": os.cpu_count(), "cpu": model}
     print(json.dumps(result), flush=True)
-    for m in mats:
-        m.close()
+    for ms in mat_sets:
+        for m in ms:
+            m.close()
 
 
 if __name__ == "__main__":
