@@ -274,3 +274,52 @@ def test_gate_up_container_is_the_row_interleaved_matrix():
     blob = tq.tq_encode_gate_up(Wg, Wu, max_entries=1000, seg_cols=64)
     assert blob == O.build_blob(O.encode_matrix(O.interleave_rows(Wg, Wu), max_entries=1000, seg_cols=64))
     assert tq.tq_validate_blob(blob)["rows"] == 48
+
+
+def test_null_arguments_are_refused_before_any_device_work():
+    """Every entry point checks its pointers first: a null handle, buffer or output is TQ_E_INVALID_ARG with a message,
+    on a machine without a GPU too; destroying nothing is not an error; a malformed container is refused by the host
+    validation that precedes the first device call."""
+    import ctypes
+
+    from paper_2509_22951_amd import binding
+    lib = tq.load()
+    null = ctypes.c_void_p(None)
+    some = ctypes.c_void_p(0x1000)      # never dereferenced: the handle next to it is null
+    arr1 = (ctypes.c_void_p * 1)(None)
+    out = ctypes.c_void_p()
+    info = binding.TqInfo()
+    words = (ctypes.c_uint16 * 1)(1)
+    calls = [
+        ("tq_matvec", lambda: lib.tq_matvec(null, some, some, 1, None)),
+        ("tq_matvec_gate_up", lambda: lib.tq_matvec_gate_up(null, some, some, 1, None)),
+        ("tq_decompress", lambda: lib.tq_decompress(null, some, None)),
+        ("tq_matvec_multi n = 0", lambda: lib.tq_matvec_multi(0, arr1, arr1, arr1, 1, None)),
+        ("tq_matvec_multi null lists", lambda: lib.tq_matvec_multi(1, None, None, None, 1, None)),
+        ("tq_matvec_multi null handle", lambda: lib.tq_matvec_multi(1, arr1, arr1, arr1, 1, None)),
+        ("tq_matvec_gate_up_multi null handle", lambda: lib.tq_matvec_gate_up_multi(1, arr1, arr1, arr1, 1, None)),
+        ("tq_decompress_multi null handle", lambda: lib.tq_decompress_multi(1, arr1, arr1, None)),
+        ("tq_get_info null handle", lambda: lib.tq_get_info(null, ctypes.byref(info))),
+        ("tq_step_create n = 0", lambda: lib.tq_step_create(0, arr1, arr1, arr1, 1, 0, ctypes.byref(out))),
+        ("tq_step_create null handle", lambda: lib.tq_step_create(1, arr1, arr1, arr1, 1, 0, ctypes.byref(out))),
+        ("tq_step_create null output", lambda: lib.tq_step_create(1, arr1, arr1, arr1, 1, 0, None)),
+        ("tq_step_launch null", lambda: lib.tq_step_launch(null, None)),
+        ("tq_step_get_info null", lambda: lib.tq_step_get_info(null, ctypes.byref(binding.TqStepInfo()))),
+        ("tq_create_from_encoded null container", lambda: lib.tq_create_from_encoded(None, 0, ctypes.byref(out))),
+        ("tq_create_from_encoded null output", lambda: lib.tq_create_from_encoded(b"x" * 512, 512, None)),
+        ("tq_listing_create null output", lambda: lib.tq_listing_create(words, 1, None, 0, None)),
+        ("tq_listing_create null words", lambda: lib.tq_listing_create(None, 1, None, 0, ctypes.byref(out))),
+        ("tq_listing_decompress null handle", lambda: lib.tq_listing_decompress(null, some, None)),
+        ("tq_listing_get_info null handle", lambda: lib.tq_listing_get_info(null, ctypes.byref(binding.TqListingInfo()))),
+        ("tq_listing_build_table null outputs", lambda: lib.tq_listing_build_table(None, None, 0, 10, None, None)),
+        ("tq_listing_compress null outputs", lambda: lib.tq_listing_compress(None, 0, None, 0, None, None)),
+    ]
+    for what, call in calls:
+        assert call() == -1, what                                  # TQ_E_INVALID_ARG
+        assert tq.tq_last_error_string(), what
+    assert lib.tq_destroy(null) == 0 and lib.tq_step_destroy(null) == 0 and lib.tq_listing_destroy(null) == 0
+    blob = tq.tq_encode(make_weights(small_case(32, 64, seed=5)), seg_cols=16)
+    for bad in (blob[:-1], blob[:100], b"\0" * len(blob)):
+        out = ctypes.c_void_p(0x55)
+        assert lib.tq_create_from_encoded(bad, len(bad), ctypes.byref(out)) == -2      # TQ_E_BAD_BLOB
+        assert out.value is None                                                       # the output is cleared on failure
