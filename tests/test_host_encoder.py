@@ -323,3 +323,13 @@ def test_null_arguments_are_refused_before_any_device_work():
         out = ctypes.c_void_p(0x55)
         assert lib.tq_create_from_encoded(bad, len(bad), ctypes.byref(out)) == -2      # TQ_E_BAD_BLOB
         assert out.value is None                                                       # the output is cleared on failure
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 exits with a message before it touches a device: the path is a single-GPU kernel."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], stdout=subprocess.PIPE,
+                       stderr=subprocess.PIPE, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and not r.stdout.strip()
