@@ -137,7 +137,8 @@ int tq_create_from_encoded(const void *blob, size_t blob_bytes, tq_handle *out);
  * run out of codes multiplies activations of later columns by zero, so an infinity or NaN anywhere in x can make
  * any output of that batch row non-finite (the plain definition does the same wherever a weight is zero).
  * batch 1 and batch 2 run the dot-product kernel (activations gathered from an LDS image of x, which holds both rows
- * at batch 2; packed matrices whose two-row image does not fit the LDS beside the dictionary go on as batch 3 does);
+ * at batch 2; a matrix whose rows are too long for that image to fit the LDS beside the dictionary - more than 8192
+ * columns with a full dictionary, more with a smaller one - goes on as batch 3 does, slower but to the same result);
  * batch 3..16 run an MFMA kernel (the batch is the N dimension).  Of those there are two.  The ring kernel keeps 128 bytes of every segment in LDS
  * and multiplies while it decodes; it takes matrices whose lane_spread (tq_info) is at most 113 columns, whose rows
  * are a whole number of units (cols a multiple of 4 * seg_cols), with seg_cols a multiple of 32 up to 256 and x

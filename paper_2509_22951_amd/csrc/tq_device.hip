@@ -145,15 +145,14 @@ bool plan_matvec_lds(uint32_t dict_words_max, uint32_t x_dwords_max, uint32_t* x
   return *total <= kLdsLimit;
 }
 
-// Which batches the dot-product kernel takes: one activation row always (a matrix whose row does not fit is refused when
-// it is created); two rows of one-weight-per-byte matrices (same image size); two rows of packed matrices when the
-// image, twice as large there, still fits beside the dictionary - otherwise those go to the batched kernels.
+// Whether the dot-product kernel takes a product: one activation row, two rows of one-weight-per-byte matrices (same
+// image size), or two rows of packed matrices (the image is twice as large there) - and in every case only if the
+// image fits the LDS beside the dictionary.  Everything else goes to the batched kernels.
 bool dot_kernel_takes(int batch, bool packed, uint32_t dict_words_max, uint32_t x_dwords_max) {
-  if (batch == 1 || (batch == 2 && !packed)) return true;
-  if (batch != 2) return false;
+  if (batch > 2) return false;
   uint32_t x_off, slot_off;
   size_t total;
-  return plan_matvec_lds(dict_words_max, 2 * x_dwords_max, &x_off, &slot_off, &total);
+  return plan_matvec_lds(dict_words_max, (batch == 2 && packed ? 2u : 1u) * x_dwords_max, &x_off, &slot_off, &total);
 }
 
 }  // namespace
@@ -200,14 +199,8 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   }
   const uint64_t n_slots = (uint64_t)h.n_quads * kUnitPanels;
   m.x_dwords = (uint32_t)((n_slots - 1) * m.x_span + std::max<uint64_t>(m.x_span, (uint64_t)facts.max_lane_reach + 1));
-  uint32_t x_off, slot_off;
-  size_t lds_total;
-  if (!plan_matvec_lds(m.dict_words, m.x_dwords, &x_off, &slot_off, &lds_total)) {
-    set_error("a dictionary of " + std::to_string(h.n_entries) + " entries and a row of " + std::to_string(h.cols) +
-              " activations (segments of " + std::to_string(h.seg_cols) + " columns) need " + std::to_string(lds_total) +
-              " bytes of LDS; the device has " + std::to_string(kLdsLimit));
-    return TQ_E_UNSUPPORTED;
-  }
+  // (A row whose activation image does not fit the LDS beside the dictionary is not refused: its products run on the
+  // batched kernels, which take their activations from global memory or a tile of one quad, at any batch.)
   // tq_decompress and the batched product: 16-bit dictionary image plus one tile of 64 strips per wavefront.
   if (round_up((uint64_t)m.dict_words * 2, 16) + (size_t)64 * (h.seg_cols + 8) > kLdsLimit) {
     set_error("segments of " + std::to_string(h.seg_cols) + " columns do not fit the LDS tile");
@@ -458,18 +451,34 @@ int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* c
       return TQ_OK;
     }
   }
-  // (one packing per call from here on)  Batch 2 on the dot-product kernel: decided for the whole call from its largest
-  // dictionary and longest row, so that every launch cut from it decides the same.
-  bool two_rows_dot = false;
-  if (op == Op::kMatvec && batch == 2) {
-    uint32_t dict_words_max = 0, x_dwords_max = 0;
-    for (int i = 0; i < n; ++i) {
-      dict_words_max = std::max(dict_words_max, hs[i]->m.dict_words);
-      x_dwords_max = std::max(x_dwords_max, hs[i]->m.x_dwords);
+  // (one packing per call from here on)  The dot-product kernel takes the matrices whose activation image fits the LDS
+  // beside the call's largest dictionary; the decision is taken here for the whole call, so that every launch cut from
+  // it decides the same.  A call with both kinds is split.
+  bool dot_call = false;
+  if (op == Op::kMatvec && batch <= 2) {
+    const bool packed = hs[0]->m.packing != 0;
+    uint32_t dict_words_max = 0;
+    for (int i = 0; i < n; ++i) dict_words_max = std::max(dict_words_max, hs[i]->m.dict_words);
+    int n_dot = 0;
+    for (int i = 0; i < n; ++i) n_dot += dot_kernel_takes(batch, packed, dict_words_max, hs[i]->m.x_dwords) ? 1 : 0;
+    dot_call = n_dot == n;
+    if (n_dot != 0 && n_dot != n) {
+      for (int want = 1; want >= 0; --want) {
+        std::vector<tq_handle> h2;
+        std::vector<const void*> x2;
+        std::vector<void*> y2;
+        for (int i = 0; i < n; ++i)
+          if ((dot_kernel_takes(batch, packed, dict_words_max, hs[i]->m.x_dwords) ? 1 : 0) == want) {
+            h2.push_back(hs[i]);
+            x2.push_back(xs[i]);
+            y2.push_back(ys[i]);
+          }
+        if (int rc = launch_all(op, (int)h2.size(), h2.data(), x2.data(), y2.data(), batch, stream, ring, gate_up, rec)) return rc;
+      }
+      return TQ_OK;
     }
-    two_rows_dot = dot_kernel_takes(2, hs[0]->m.packing != 0, dict_words_max, x_dwords_max);
   }
-  if (op == Op::kMatvec && batch > 1 && !two_rows_dot && !ring && !gate_up) {   // (the ring kernel adds partial sums to y: no place for silu)
+  if (op == Op::kMatvec && !dot_call && !ring && !gate_up) {   // (the ring kernel adds partial sums to y: no place for silu)
     // The matrices that can take the ring kernel go there, the others to the whole-strip kernel; the products are
     // independent, so regrouping them changes nothing but the launches.
     // The ring kernel gives whole bands to wavefronts, a quad at a time: it needs many bands per workgroup to keep its
@@ -556,7 +565,8 @@ extern "C" int tq_matvec(tq_handle h, const void* x, void* y, int batch, void* s
   }
   if (int rc = check_call("tq_matvec", 1, &h, &x, &y, batch)) return rc;
   return launch(Op::kMatvec, 1, &h, &x, &y, batch, (hipStream_t)stream,
-                batch > 1 && ring_eligible(h, x) && h->m.n_bands >= ring_min_bands_per_cu() * h->n_cu);
+                !dot_kernel_takes(batch, h->m.packing != 0, h->m.dict_words, h->m.x_dwords) && ring_eligible(h, x) &&
+                    h->m.n_bands >= ring_min_bands_per_cu() * h->n_cu);
 }
 
 extern "C" int tq_matvec_multi(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {

@@ -560,6 +560,61 @@ def test_two_activation_rows_of_packed_weights(dev):
         m.close()
 
 
+def test_rows_too_long_for_the_activation_image_run_on_the_batched_kernels(dev, monkeypatch):
+    """A row whose LDS image does not fit beside the dictionary is not refused: batch 1 and 2 then run on the kernels that
+    serve the larger batches (whole-strip, or ring when the launch is large enough).  Alone, as a prepared step, mixed
+    with ordinary matrices in one call (the call is split), as a gate/up pair, packed."""
+    cases = [(96, 28672, 256, 12000, 8, False), (64, 65536, 256, 2000, 8, False), (48, 98304, 128, 4000, 4, True)]
+    for rows, cols, seg, me, width, pack in cases:
+        spec = small_case(rows, cols, seed=7000 + rows)
+        W = make_weights(spec)
+        Qo, so = O.quantize_rows(W, width)
+        m = tq.Matrix(tq.tq_encode(W, seg_cols=seg, max_entries=me, bits=0 if width == 8 else width, pack=pack))
+        small = small_case(80, 512, seed=7100 + rows)
+        Ws = make_weights(small)
+        Qs, ss = O.quantize_rows(Ws, width)
+        m_small = tq.Matrix(tq.tq_encode(Ws, seg_cols=64, max_entries=me, bits=0 if width == 8 else width, pack=pack))
+        try:
+            assert np.array_equal(gpu_decompress(m, dev), Qo)
+            for ring_min in ("24", "0"):        # "0": the ring kernel takes the launch whatever its size
+                monkeypatch.setenv("TQ_RING_MIN_BANDS_PER_CU", ring_min)
+                for batch in (1, 2, 8):
+                    bits, x = make_activations(spec, batch)
+                    ref = O.gemv_f64(Qo, so, x)
+                    check_outputs(gpu_matvec(m, bits, dev), ref)
+                    check_outputs(gpu_matvec(m, bits, dev, misalign=True), ref)
+                    bs, xsm = make_activations(small, batch)
+                    xd = [torch.from_numpy(b.view(np.int16).copy()).to(dev) for b in (bs, bits, bs)]
+                    yd = [torch.full((batch, r), float("nan"), dtype=torch.float32, device=dev) for r in (80, rows, 80)]
+                    hs = [m_small.handle, m.handle, m_small.handle]
+                    tq.tq_matvec_multi(hs, [t.data_ptr() for t in xd], [t.data_ptr() for t in yd], batch, _stream())
+                    torch.cuda.synchronize()
+                    for y, r in zip(yd, (O.gemv_f64(Qs, ss, xsm), ref, O.gemv_f64(Qs, ss, xsm))):
+                        check_outputs(y.cpu().numpy(), r)
+                    step = tq.Step(hs, [t.data_ptr() for t in xd], [t.data_ptr() for t in yd], batch)
+                    try:
+                        for y in yd:
+                            y.fill_(float("nan"))
+                        step.launch(_stream())
+                        torch.cuda.synchronize()
+                    finally:
+                        step.close()
+                    for y, r in zip(yd, (O.gemv_f64(Qs, ss, xsm), ref, O.gemv_f64(Qs, ss, xsm))):
+                        check_outputs(y.cpu().numpy(), r)
+        finally:
+            m.close()
+            m_small.close()
+    sg, su = small_case(40, 65536, seed=7201), small_case(40, 65536, seed=7202)
+    Wg, Wu = make_weights(sg), make_weights(su)
+    m = tq.Matrix(tq.tq_encode_gate_up(Wg, Wu, max_entries=2000))
+    try:
+        for batch in (1, 2):
+            bits, x = make_activations(sg, batch)
+            check_outputs(_gpu_gate_up(m, bits, dev, 40), O.gate_up_f64(*O.quantize_rows(Wg), *O.quantize_rows(Wu), x))
+    finally:
+        m.close()
+
+
 def test_packed_weights_take_every_nibble_value(dev):
     """All 16 nibble values, -8 included (the quantizer never makes it, a container may hold it): the batch-1 kernel's fp8
     image and the MFMA kernel's conversion are exact for each."""
