@@ -1,4 +1,5 @@
-// Device side of libtq: the batch-1 kernel (dictionary lookup, activation gather, one dot product per code).
+// Device side of libtq: the dot-product kernel for one or two activation rows (dictionary lookup, activation gather,
+// one dot product per code and row).
 #pragma once
 #include "tq_kernels_common.h"
 
@@ -267,7 +268,8 @@ __device__ __forceinline__ float sum_over_panels(float v) {
 // The gated product of a feed-forward block: silu(gate) * up, silu(g) = g / (1 + exp(-g)).
 __device__ __forceinline__ float silu_times(float gate, float up) { return gate / (1.f + __expf(-gate)) * up; }
 
-// Fused decode + dequantize + matrix-vector product for one activation row and up to kMaxMulti matrices.
+// Fused decode + dequantize + matrix-vector product for one or two activation rows (kB) and up to kMaxMulti matrices
+// (kMaxStep when the jobs come from a prepared step's table).
 //
 // The launch's work is the line of all bands (16 rows each) of all matrices, each band weighted by its number of
 // weights; workgroup g takes the bands whose middle lies in the g-th equal share of that line, so a workgroup serves a

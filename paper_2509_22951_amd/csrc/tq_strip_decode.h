@@ -5,8 +5,9 @@
 
 namespace tq {
 // ---------------------------------------------------------------------------------------------------------------
-// Product for batches of 2..16 activation rows, whole-strip form: decode a unit into an LDS tile, then bf16 MFMA with
-// the batch as N.  (Large launches of well-behaved matrices take the ring form further down instead.)
+// Product for the batches the dot-product kernel does not take (3..16 activation rows; 1 or 2 when a row is too long
+// for that kernel's LDS image), whole-strip form: decode a unit into an LDS tile, then bf16 MFMA with the batch as N.
+// (Large launches of well-behaved matrices take the ring form instead.)
 //
 // A lane's segment is (row l & 15, panel l >> 4) of its unit, which is exactly the A-operand layout of
 // v_mfma_f32_16x16x32_bf16: lane l supplies row l % 16 and the 8 k-values of group l / 16.  Taking those 8 values as
