@@ -233,6 +233,8 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesHalf, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesMore, 8, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesMore, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesQuarter, 4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesQuarter, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
   if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
 
   const uint8_t* src = (const uint8_t*)blob;
@@ -373,14 +375,17 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     a.tile_area = 64 * kRingBytes;
     const bool half = batch <= 8;   // 8 batch rows in the tile: room for two more wavefronts
     const bool more = half && dict16 + (size_t)kRingWavesMore * a.tile_area + ring_x_tile(8) + 128 <= kLdsLimit;   // a smaller dictionary leaves room
-    const int waves = more ? kRingWavesMore : half ? kRingWavesHalf : kRingWaves;
+    // batches up to 4 beside a dictionary too large for that: a tile of 4 rows leaves room for one wavefront more
+    const bool quarter = !more && batch <= 4 && dict16 + (size_t)kRingWavesQuarter * a.tile_area + ring_x_tile(4) + 128 <= kLdsLimit;
+    const int waves = more ? kRingWavesMore : quarter ? kRingWavesQuarter : half ? kRingWavesHalf : kRingWaves;
     a.slot_off = (uint32_t)(dict16 + (size_t)waves * a.tile_area);
-    p.lds = a.slot_off + ring_x_tile(half ? 8 : 16) + 128;   // + the band counter
+    p.lds = a.slot_off + ring_x_tile(quarter ? 4 : half ? 8 : 16) + 128;   // + the band counter
     if (p.lds > kLdsLimit || !x_fast) {
       set_error("internal: ring launch with a dictionary or activations that do not fit it");
       return TQ_E_UNSUPPORTED;
     }
     if (more) p.kernel = packed ? (const void*)k_matvec_ring<kRingWavesMore, 8, true> : (const void*)k_matvec_ring<kRingWavesMore, 8, false>;
+    else if (quarter) p.kernel = packed ? (const void*)k_matvec_ring<kRingWavesQuarter, 4, true> : (const void*)k_matvec_ring<kRingWavesQuarter, 4, false>;
     else if (half) p.kernel = packed ? (const void*)k_matvec_ring<kRingWavesHalf, 8, true> : (const void*)k_matvec_ring<kRingWavesHalf, 8, false>;
     else p.kernel = packed ? (const void*)k_matvec_ring<kRingWaves, 16, true> : (const void*)k_matvec_ring<kRingWaves, 16, false>;
     p.block = (unsigned)waves * 64;

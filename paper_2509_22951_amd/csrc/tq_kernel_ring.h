@@ -35,6 +35,7 @@ constexpr int kRingBytes = 128;
 constexpr int kRingWaves = 8;       // with an activation tile of 16 batch rows
 constexpr int kRingWavesHalf = 10;  // with one of 8 batch rows (batches up to 8): more wavefronts fit next to the smaller tile
 constexpr int kRingWavesMore = 12;  // the same beside a dictionary of at most 24,512 entries
+constexpr int kRingWavesQuarter = 11;   // with a tile of 4 batch rows (batches up to 4) beside a full dictionary
 constexpr int kRingPiece = 12;    // chunks per piece of the code stream (two register sets)
 constexpr int kRingStep = 4;      // chunks between two looks at the lanes' progress
 constexpr int kRingGroup = 4;     // MFMA steps per group
