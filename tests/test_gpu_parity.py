@@ -269,12 +269,12 @@ def test_decompress_multi_is_bit_exact(dev):
         m.close()
 
 
-@pytest.mark.parametrize("config,width,pack,batches", [(4, 8, False, (1, 8, 16)), (4, 4, True, (1, 2, 8, 16)),
+@pytest.mark.parametrize("config,width,pack,batches", [(4, 8, False, (1, 4, 8, 16)), (4, 4, True, (1, 2, 4, 8, 16)),
                                                        (5, 8, False, (16,)), (3, 8, False, (1,)), (2, 8, False, (1,))])
 def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows(dev, config, width, pack, batches):
     """Config-4 shapes at full size (one 3B layer plus lm_head 128256 x 3072), encoded as bench.py encodes them (one
     dictionary over the sequence, default options) and launched as bench.py launches them (all matrices in one
-    tq_matvec_multi / tq_decompress_multi call), batch 1, 8 and 16 (dot-product kernel, ring kernel with 10 and with 8
+    tq_matvec_multi / tq_decompress_multi call), batch 1, 4, 8 and 16 (dot-product kernel, ring kernel with 11, 10 and 8
     wavefronts: the call brings 9,744 bands, enough for the ring kernel).  The oracle computes sampled rows one by one:
     quantization is per row, so the sampled rows of Q and their float64 products need only those rows of W.
     Second case: the same shapes as packed 4-bit weights (bench.py --bits 4 --pack).  Then config 5 (the same shapes with
