@@ -142,8 +142,8 @@ int tq_create_from_encoded(const void *blob, size_t blob_bytes, tq_handle *out);
  * batch 3..16 run an MFMA kernel (the batch is the N dimension).  Of those there are two.  The ring kernel keeps 128 bytes of every segment in LDS
  * and multiplies while it decodes; it takes matrices whose lane_spread (tq_info) is at most 113 columns, whose rows
  * are a whole number of units (cols a multiple of 4 * seg_cols), with seg_cols a multiple of 32 up to 256 and x
- * 16-byte aligned, in calls that bring at least 24 bands of 16 rows per compute unit (the environment variable
- * TQ_RING_MIN_BANDS_PER_CU overrides that number; it is read at every call).  Everything else goes through the
+ * 16-byte aligned, in calls that bring at least 24 bands of 16 rows per compute unit (tq_set_ring_min_bands_per_cu
+ * changes that number).  Everything else goes through the
  * whole-strip kernel, which decodes a unit into an LDS tile before it multiplies it.  The ring kernel adds the partial
  * sums of a row's later quads (groups of 4 segments) to y with atomic adds, always in the same order; y must not be
  * read or written by anything else on the device while the call runs (true of any output buffer).
@@ -152,6 +152,12 @@ int tq_create_from_encoded(const void *blob, size_t blob_bytes, tq_handle *out);
  * kernels (the ring kernel then takes segments of at most 128 bytes).
  */
 int tq_matvec(tq_handle h, const void *x, void *y, int batch, void *stream);
+
+/* Tuning knob of the choice between the two MFMA kernels of tq_matvec (see there): the ring kernel hands whole bands
+ * of 16 rows to its wavefronts and is taken by launches that bring at least this many bands per compute unit
+ * (default 24; 0 = whenever a matrix allows it).  Process-wide, atomic; affects the calls and the prepared steps made
+ * after it returns.  Results stay within the tolerance either way (the two kernels add in different orders). */
+int tq_set_ring_min_bands_per_cu(uint32_t bands_per_cu);
 
 /*
  * tq_matvec for n independent matrices in as few launches as possible (for instance the q, k and v projections of a

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     tq_create_from_encoded,
     tq_matvec,
     tq_matvec_multi,
+    tq_set_ring_min_bands_per_cu,
     MultiCall,
     tq_decompress,
     tq_decompress_multi,

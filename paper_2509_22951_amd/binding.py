@@ -20,6 +20,7 @@ EXPORTS = [
     "tq_encode", "tq_encode_quantized", "tq_free_blob", "tq_validate_blob", "tq_create_from_encoded", "tq_matvec",
     "tq_matvec_multi", "tq_decompress", "tq_decompress_multi", "tq_get_info", "tq_destroy", "tq_last_error_string",
     "tq_encode_gate_up", "tq_matvec_gate_up", "tq_matvec_gate_up_multi",
+    "tq_set_ring_min_bands_per_cu",
     "tq_step_create", "tq_step_launch", "tq_step_get_info", "tq_step_destroy",
     "tq_listing_build_table", "tq_listing_compress", "tq_listing_create", "tq_listing_decompress", "tq_listing_get_info",
     "tq_listing_destroy",
@@ -90,6 +91,8 @@ def load() -> ctypes.CDLL:
     lib.tq_create_from_encoded.argtypes = [vp, sz, ctypes.POINTER(vp)]
     lib.tq_matvec.restype = ci
     lib.tq_matvec.argtypes = [vp, vp, vp, ci, vp]
+    lib.tq_set_ring_min_bands_per_cu.restype = ci
+    lib.tq_set_ring_min_bands_per_cu.argtypes = [u32]
     lib.tq_encode_gate_up.restype = ci
     lib.tq_encode_gate_up.argtypes = [vp, vp, u32, u32, ctypes.POINTER(TqEncodeOpts), ctypes.POINTER(vp), ctypes.POINTER(sz)]
     lib.tq_matvec_gate_up.restype = ci
@@ -219,6 +222,10 @@ def tq_create_from_encoded(blob: bytes) -> int:
 
 def tq_matvec(handle: int, x_ptr: int, y_ptr: int, batch: int, stream: int = 0) -> None:
     _check(load().tq_matvec(handle, x_ptr, y_ptr, batch, stream))
+
+
+def tq_set_ring_min_bands_per_cu(bands_per_cu: int) -> None:
+    _check(load().tq_set_ring_min_bands_per_cu(bands_per_cu))
 
 
 def tq_matvec_gate_up(handle: int, x_ptr: int, y_ptr: int, batch: int, stream: int = 0) -> None:

@@ -2,6 +2,7 @@
 #include <algorithm>
 #include <atomic>
 #include <cstring>
+#include <new>
 #include <string>
 #include <thread>
 #include <vector>
@@ -66,6 +67,8 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* fa
     if (bits % 8 || len < 1 || len > h.lmax) return bad("dictionary entry length");
     if (len < 3 && (w & 0xFFFFFFu) >> (8 * len)) return bad("dictionary entry has bytes past its length");
     if (e < 256 && w != (e | 8u << 24)) return bad("codes 0..255 must be the single bytes");
+    // the kernels take a run's length from its code alone (1 for codes below 256, 2 from there on), never from the entry
+    if (e >= 256 && len != 2) return bad("codes from 256 on must be runs of 2 bytes");
   }
   if (slot[h.n_entries] != 0) return bad("pad entry");
 
@@ -169,8 +172,16 @@ extern "C" const char* tq_last_error_string(void) { return tq::g_err.c_str(); }
 extern "C" int tq_validate_blob(const void* blob, size_t blob_bytes, tq_info* info) {
   tq::Header h;
   tq::BlobFacts facts;
-  unsigned hw = std::thread::hardware_concurrency();
-  int rc = tq::validate_blob(blob, blob_bytes, &h, &facts, hw ? hw : 1);
-  if (rc == TQ_OK && info) tq::fill_info(h, facts, info);
-  return rc;
+  try {   // no C++ exception leaves the library
+    unsigned hw = std::thread::hardware_concurrency();
+    int rc = tq::validate_blob(blob, blob_bytes, &h, &facts, hw ? hw : 1);
+    if (rc == TQ_OK && info) tq::fill_info(h, facts, info);
+    return rc;
+  } catch (const std::bad_alloc&) {
+    tq::set_error("tq_validate_blob: out of host memory");
+    return TQ_E_OOM;
+  } catch (...) {
+    tq::set_error("tq_validate_blob: unexpected internal error (could a thread not be started?)");
+    return TQ_E_HIP;
+  }
 }

@@ -23,6 +23,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
@@ -155,6 +156,60 @@ bool dot_kernel_takes(int batch, bool packed, uint32_t dict_words_max, uint32_t 
   return plan_matvec_lds(dict_words_max, (batch == 2 && packed ? 2u : 1u) * x_dwords_max, &x_off, &slot_off, &total);
 }
 
+// Every kernel of the library that takes its dictionary at LDS address 0.
+const void* const kLdsKernels[] = {
+    (const void*)k_matvec<kDotPiece, kDotWaves, false, 1>,
+    (const void*)k_matvec<kDotPiece, kDotWaves, false, 2>,
+    (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1>,
+    (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2>,
+    (const void*)k_decompress,
+    (const void*)k_matvec_mfma<true, false>,
+    (const void*)k_matvec_mfma<false, false>,
+    (const void*)k_matvec_mfma<true, true>,
+    (const void*)k_matvec_mfma<false, true>,
+    (const void*)k_matvec_ring<kRingWaves, 16, false>,
+    (const void*)k_matvec_ring<kRingWavesHalf, 8, false>,
+    (const void*)k_matvec_ring<kRingWaves, 16, true>,
+    (const void*)k_matvec_ring<kRingWavesHalf, 8, true>,
+    (const void*)k_matvec_ring<kRingWavesMore, 8, false>,
+    (const void*)k_matvec_ring<kRingWavesMore, 8, true>,
+    (const void*)k_matvec_ring<kRingWavesQuarter, 4, false>,
+    (const void*)k_matvec_ring<kRingWavesQuarter, 4, true>,
+};
+
+// Once per matrix creation (cheap): dynamic LDS above 64 KB has to be allowed per kernel function, and the kernels'
+// code -> entry lookup takes the dictionary to start at LDS address 0, which holds exactly when a kernel has no
+// statically allocated LDS ahead of its dynamic segment.  That is checked here, on the host, so that no launch can
+// run with a dictionary somewhere else.
+int prepare_kernels() {
+  for (const void* k : kLdsKernels) {
+    hipFuncAttributes attr;
+    hipError_t e = hipFuncGetAttributes(&attr, k);
+    if (e != hipSuccess) return hip_fail("hipFuncGetAttributes", e);
+    if (attr.sharedSizeBytes != 0) {
+      set_error("internal: a kernel was built with static LDS, so its dictionary would not start at LDS address 0");
+      return TQ_E_UNSUPPORTED;
+    }
+    e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+    if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
+  }
+  return TQ_OK;
+}
+
+// Runs the body of an entry point; no C++ exception leaves the library.
+template <typename F>
+int guarded(const char* who, F&& body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    set_error(std::string(who) + ": out of host memory");
+    return TQ_E_OOM;
+  } catch (...) {
+    set_error(std::string(who) + ": unexpected internal error");
+    return TQ_E_HIP;
+  }
+}
+
 }  // namespace
 
 struct tq_matrix {
@@ -168,7 +223,7 @@ struct tq_matrix {
   int n_cu;
 };
 
-extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_handle* out) {
+static int tq_create_from_encoded_impl(const void* blob, size_t blob_bytes, tq_handle* out) {
   if (!out) {
     set_error("tq_create_from_encoded: null output pointer");
     return TQ_E_INVALID_ARG;
@@ -217,25 +272,7 @@ extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_ha
     set_error("device offers less LDS per workgroup than this library needs (built for gfx950, 160 KB)");
     return TQ_E_UNSUPPORTED;
   }
-  // Dynamic LDS above 64 KB has to be allowed per kernel function.
-  e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves, false, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec<kDotPiece, kDotWaves, false, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_decompress, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_mfma<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWaves, 16, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesHalf, 8, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWaves, 16, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesHalf, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesMore, 8, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesMore, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesQuarter, 4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_matvec_ring<kRingWavesQuarter, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", e);
+  if (int rc = prepare_kernels()) return rc;
 
   const uint8_t* src = (const uint8_t*)blob;
   DictCopy* dict = nullptr;
@@ -416,12 +453,10 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
 }
 
 // Whether the batched product of this matrix can keep a ring per lane instead of the whole strip.
-// Bands per CU a launch needs for the ring kernel; TQ_RING_MIN_BANDS_PER_CU overrides it (tests use 0 to put small
+// Bands per CU a launch needs for the ring kernel; tq_set_ring_min_bands_per_cu changes it (tests use 0 to put small
 // matrices through that kernel).
-uint64_t ring_min_bands_per_cu() {
-  if (const char* e = std::getenv("TQ_RING_MIN_BANDS_PER_CU")) return std::strtoull(e, nullptr, 10);
-  return kRingMinBandsPerCu;
-}
+std::atomic<uint64_t> g_ring_min_bands{kRingMinBandsPerCu};
+uint64_t ring_min_bands_per_cu() { return g_ring_min_bands.load(std::memory_order_relaxed); }
 
 bool ring_eligible(const tq_matrix* t, const void* x) {
   const DevMat& m = t->m;
@@ -563,7 +598,7 @@ int check_call(const char* who, int n, const tq_handle* hs, const void* const* x
 
 }  // namespace
 
-extern "C" int tq_matvec(tq_handle h, const void* x, void* y, int batch, void* stream) {
+static int tq_matvec_impl(tq_handle h, const void* x, void* y, int batch, void* stream) {
   if (!h || !x || !y) {
     set_error("tq_matvec: null argument");
     return TQ_E_INVALID_ARG;
@@ -574,7 +609,7 @@ extern "C" int tq_matvec(tq_handle h, const void* x, void* y, int batch, void* s
                     h->m.n_bands >= ring_min_bands_per_cu() * h->n_cu);
 }
 
-extern "C" int tq_matvec_multi(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {
+static int tq_matvec_multi_impl(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {
   if (n < 1 || !hs || !xs || !ys) {
     set_error("tq_matvec_multi: null argument or n < 1");
     return TQ_E_INVALID_ARG;
@@ -583,7 +618,7 @@ extern "C" int tq_matvec_multi(int n, const tq_handle* hs, const void* const* xs
   return launch_all(Op::kMatvec, n, hs, xs, ys, batch, (hipStream_t)stream);
 }
 
-extern "C" int tq_matvec_gate_up_multi(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {
+static int tq_matvec_gate_up_multi_impl(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {
   if (n < 1 || !hs || !xs || !ys) {
     set_error("tq_matvec_gate_up_multi: null argument or n < 1");
     return TQ_E_INVALID_ARG;
@@ -597,7 +632,7 @@ extern "C" int tq_matvec_gate_up_multi(int n, const tq_handle* hs, const void* c
   return launch_all(Op::kMatvec, n, hs, xs, ys, batch, (hipStream_t)stream, false, true);
 }
 
-extern "C" int tq_matvec_gate_up(tq_handle h, const void* x, void* y, int batch, void* stream) {
+static int tq_matvec_gate_up_impl(tq_handle h, const void* x, void* y, int batch, void* stream) {
   if (!h || !x || !y) {
     set_error("tq_matvec_gate_up: null argument");
     return TQ_E_INVALID_ARG;
@@ -614,7 +649,7 @@ struct tq_step {
   int n_matrices;
 };
 
-extern "C" int tq_step_create(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, uint32_t flags,
+static int tq_step_create_impl(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, uint32_t flags,
                               tq_step_handle* out) {
   if (!out) {
     set_error("tq_step_create: null output pointer");
@@ -676,7 +711,7 @@ extern "C" int tq_step_create(int n, const tq_handle* hs, const void* const* xs,
   }
 }
 
-extern "C" int tq_step_launch(tq_step_handle s, void* stream) {
+static int tq_step_launch_impl(tq_step_handle s, void* stream) {
   if (!s) {
     set_error("tq_step_launch: null step");
     return TQ_E_INVALID_ARG;
@@ -697,7 +732,7 @@ extern "C" int tq_step_get_info(tq_step_handle s, tq_step_info* out) {
   return TQ_OK;
 }
 
-extern "C" int tq_step_destroy(tq_step_handle s) {
+static int tq_step_destroy_impl(tq_step_handle s) {
   if (!s) return TQ_OK;
   hipError_t e = hipFree(s->table_dev);
   delete s;
@@ -705,7 +740,7 @@ extern "C" int tq_step_destroy(tq_step_handle s) {
   return TQ_OK;
 }
 
-extern "C" int tq_decompress(tq_handle h, void* out, void* stream) {
+static int tq_decompress_impl(tq_handle h, void* out, void* stream) {
   if (!h || !out) {
     set_error("tq_decompress: null argument");
     return TQ_E_INVALID_ARG;
@@ -713,7 +748,7 @@ extern "C" int tq_decompress(tq_handle h, void* out, void* stream) {
   return launch(Op::kDecompress, 1, &h, nullptr, &out, 1, (hipStream_t)stream);
 }
 
-extern "C" int tq_decompress_multi(int n, const tq_handle* hs, void* const* outs, void* stream) {
+static int tq_decompress_multi_impl(int n, const tq_handle* hs, void* const* outs, void* stream) {
   if (n < 1 || !hs || !outs) {
     set_error("tq_decompress_multi: null argument or n < 1");
     return TQ_E_INVALID_ARG;
@@ -740,12 +775,62 @@ extern "C" int tq_get_info(tq_handle h, tq_info* out) {
   return TQ_OK;
 }
 
-extern "C" int tq_destroy(tq_handle h) {
+static int tq_destroy_impl(tq_handle h) {
   if (!h) return TQ_OK;
   hipError_t e = hipFree(h->dev_base);
   hipError_t e2 = release_dictionary(h->dict);
   delete h;
   if (e != hipSuccess) return hip_fail("hipFree", e);
   if (e2 != hipSuccess) return hip_fail("hipFree", e2);
+  return TQ_OK;
+}
+
+// The entry points proper: argument checks and work above, behind a wrapper that lets no C++ exception out.
+extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_handle* out) {
+  return guarded("tq_create_from_encoded", [&] { return tq_create_from_encoded_impl(blob, blob_bytes, out); });
+}
+
+extern "C" int tq_matvec(tq_handle h, const void* x, void* y, int batch, void* stream) {
+  return guarded("tq_matvec", [&] { return tq_matvec_impl(h, x, y, batch, stream); });
+}
+
+extern "C" int tq_matvec_multi(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {
+  return guarded("tq_matvec_multi", [&] { return tq_matvec_multi_impl(n, hs, xs, ys, batch, stream); });
+}
+
+extern "C" int tq_matvec_gate_up_multi(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {
+  return guarded("tq_matvec_gate_up_multi", [&] { return tq_matvec_gate_up_multi_impl(n, hs, xs, ys, batch, stream); });
+}
+
+extern "C" int tq_matvec_gate_up(tq_handle h, const void* x, void* y, int batch, void* stream) {
+  return guarded("tq_matvec_gate_up", [&] { return tq_matvec_gate_up_impl(h, x, y, batch, stream); });
+}
+
+extern "C" int tq_step_create(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, uint32_t flags, tq_step_handle* out) {
+  return guarded("tq_step_create", [&] { return tq_step_create_impl(n, hs, xs, ys, batch, flags, out); });
+}
+
+extern "C" int tq_step_launch(tq_step_handle s, void* stream) {
+  return guarded("tq_step_launch", [&] { return tq_step_launch_impl(s, stream); });
+}
+
+extern "C" int tq_decompress(tq_handle h, void* out, void* stream) {
+  return guarded("tq_decompress", [&] { return tq_decompress_impl(h, out, stream); });
+}
+
+extern "C" int tq_decompress_multi(int n, const tq_handle* hs, void* const* outs, void* stream) {
+  return guarded("tq_decompress_multi", [&] { return tq_decompress_multi_impl(n, hs, outs, stream); });
+}
+
+extern "C" int tq_destroy(tq_handle h) {
+  return guarded("tq_destroy", [&] { return tq_destroy_impl(h); });
+}
+
+extern "C" int tq_step_destroy(tq_step_handle s) {
+  return guarded("tq_step_destroy", [&] { return tq_step_destroy_impl(s); });
+}
+
+extern "C" int tq_set_ring_min_bands_per_cu(uint32_t bands_per_cu) {
+  g_ring_min_bands.store(bands_per_cu, std::memory_order_relaxed);
   return TQ_OK;
 }

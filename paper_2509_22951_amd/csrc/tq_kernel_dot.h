@@ -289,7 +289,6 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
   float* slot_val = (float*)((uint8_t*)lds4 + a.slot_off);           // [2 * kWaves][kB][16]
   int* slot_band = (int*)(slot_val + 2 * kWaves * kB * 16);          // [2 * kWaves]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  if (lds_address(lds4) != 0) return;   // the code -> word lookup takes the dictionary to start at LDS address 0 (no static LDS here)
   const uint64_t total = cost_at(a, a.n);
   const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
   const uint32_t* staged = nullptr;

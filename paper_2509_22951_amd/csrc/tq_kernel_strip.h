@@ -11,7 +11,6 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
   uint8_t* tiles = (uint8_t*)lds4 + a.x_off;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_threads = blockDim.x, n_waves = n_threads >> 6;
-  if (lds_address(lds4) != 0) return;   // the code -> entry lookup takes the dictionary to start at LDS address 0
   const uint64_t total = cost_at(a, a.n);
   const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
   const uint32_t* staged = nullptr;
@@ -157,7 +156,6 @@ __global__ __launch_bounds__(kThreads, 1) void k_decompress(MatvecArgs a) {
   uint8_t* tiles = (uint8_t*)lds4 + a.x_off;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_threads = blockDim.x, n_waves = n_threads >> 6;
-  if (lds_address(lds4) != 0) return;   // the code -> entry lookup takes the dictionary to start at LDS address 0
   const uint64_t total = cost_at(a, a.n);
   const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
   const uint32_t* staged = nullptr;

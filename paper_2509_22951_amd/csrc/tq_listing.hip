@@ -252,7 +252,7 @@ extern "C" int tq_listing_compress(const uint8_t* values, uint64_t n_values, con
   return TQ_OK;
 }
 
-extern "C" int tq_listing_create(const uint16_t* words, uint64_t n_words, const uint8_t* table, uint32_t n_table, tq_listing* out) {
+static int listing_create_impl(const uint16_t* words, uint64_t n_words, const uint8_t* table, uint32_t n_table, tq_listing* out) {
   if (!out || (n_words && !words) || (n_table && !table)) {
     set_error("tq_listing_create: null argument");
     return TQ_E_INVALID_ARG;
@@ -303,6 +303,8 @@ extern "C" int tq_listing_create(const uint16_t* words, uint64_t n_words, const 
   }
   while (next_block < n_blocks) base[next_block++] = (uint32_t)tokens;
 
+  std::vector<uint32_t> packed(std::max<uint32_t>(n_table, 1));
+  for (uint32_t c = 0; c < n_table; ++c) packed[c] = pack4(table + (size_t)c * kSeq);
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return hip_fail("hipGetDevice (is a GPU present?)", e);
@@ -319,8 +321,6 @@ extern "C" int tq_listing_create(const uint16_t* words, uint64_t n_words, const 
   h->info.n_tokens = tokens;
   h->info.n_escapes = escapes;
   h->info.n_table = n_table;
-  std::vector<uint32_t> packed(std::max<uint32_t>(n_table, 1));
-  for (uint32_t c = 0; c < n_table; ++c) packed[c] = pack4(table + (size_t)c * kSeq);
   e = hipMalloc((void**)&h->words, std::max<uint64_t>(n_words * 2, 4));
   if (e == hipSuccess) e = hipMalloc((void**)&h->table, packed.size() * 4);
   if (e == hipSuccess) e = hipMalloc((void**)&h->block_base, base.size() * 4);
@@ -340,6 +340,18 @@ extern "C" int tq_listing_create(const uint16_t* words, uint64_t n_words, const 
   }
   *out = h;
   return TQ_OK;
+}
+
+extern "C" int tq_listing_create(const uint16_t* words, uint64_t n_words, const uint8_t* table, uint32_t n_table, tq_listing* out) {
+  try {   // no C++ exception leaves the library
+    return listing_create_impl(words, n_words, table, n_table, out);
+  } catch (const std::bad_alloc&) {
+    set_error("tq_listing_create: out of host memory");
+    return TQ_E_OOM;
+  } catch (...) {
+    set_error("tq_listing_create: unexpected internal error");
+    return TQ_E_HIP;
+  }
 }
 
 extern "C" int tq_listing_decompress(tq_listing h, void* out, void* stream) {

@@ -21,10 +21,22 @@ def dev():
     return torch.device("cuda:0")
 
 
+RING_MIN_BANDS_DEFAULT = 24
+
+
 @pytest.fixture
-def ring_for_small_launches(monkeypatch):
+def ring_for_small_launches(dev):
     """The library keeps the ring kernel for launches with many bands per CU; this lets a small matrix through."""
-    monkeypatch.setenv("TQ_RING_MIN_BANDS_PER_CU", "0")
+    tq.tq_set_ring_min_bands_per_cu(0)
+    yield
+    tq.tq_set_ring_min_bands_per_cu(RING_MIN_BANDS_DEFAULT)
+
+
+@pytest.fixture(autouse=True)
+def _default_ring_threshold_afterwards():
+    """Tests that change the library's ring-kernel threshold leave the default behind."""
+    yield
+    tq.tq_set_ring_min_bands_per_cu(24)
 
 
 def _stream():
@@ -269,32 +281,38 @@ def test_decompress_multi_is_bit_exact(dev):
         m.close()
 
 
-@pytest.mark.parametrize("config,width,pack,batches", [(4, 8, False, (1, 4, 8, 16)), (4, 4, True, (1, 2, 4, 8, 16)),
-                                                       (5, 8, False, (16,)), (3, 8, False, (1,)), (2, 8, False, (1,))])
-def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows(dev, config, width, pack, batches):
+def _oracle_by_row_blocks(fn, n_rows, threads=16, block=4096):
+    """The oracle, as it stands, on blocks of rows spread over host threads (rows are independent: quantization is per
+    row, and so is every output of the product); returns the per-block results in row order."""
+    from concurrent.futures import ThreadPoolExecutor
+    cuts = [(a, min(n_rows, a + block)) for a in range(0, n_rows, block)]
+    with ThreadPoolExecutor(threads) as pool:
+        return list(pool.map(lambda ab: fn(*ab), cuts))
+
+
+@pytest.mark.parametrize("config,width,pack,batches", [(4, 8, False, (1, 8)), (4, 8, False, (4, 16)), (4, 4, True, (1, 2, 4, 8, 16)),
+                                                       (5, 8, False, (1, 16)), (3, 8, False, (1,)), (2, 8, False, (1,))])
+def test_full_size_shapes_in_the_benchmarks_launch_configuration_every_row(dev, config, width, pack, batches):
     """Config-4 shapes at full size (one 3B layer plus lm_head 128256 x 3072), encoded as bench.py encodes them (one
     dictionary over the sequence, default options) and launched as bench.py launches them (all matrices in one
-    tq_matvec_multi / tq_decompress_multi call), batch 1, 4, 8 and 16 (dot-product kernel, ring kernel with 11, 10 and 8
-    wavefronts: the call brings 9,744 bands, enough for the ring kernel).  The oracle computes sampled rows one by one:
-    quantization is per row, so the sampled rows of Q and their float64 products need only those rows of W.
-    Second case: the same shapes as packed 4-bit weights (bench.py --bits 4 --pack).  Then config 5 (the same shapes with
-    Student-t weights, batch 16, and the expansion of every matrix), config 3 (one LLaMA-3.2-1B layer plus its lm_head
+    tq_matvec_multi / tq_decompress_multi call, and as the prepared step), batch 1, 4, 8 and 16 (dot-product kernel,
+    ring kernel with 11, 10 and 8 wavefronts: the call brings 9,744 bands, enough for the ring kernel).  Every row of
+    every matrix is compared: the expansion with the oracle's quantized matrix byte for byte, every output with the
+    oracle's float64 product.  Third case: the same shapes as packed 4-bit weights (bench.py --bits 4 --pack).  Then
+    config 5 (the same shapes with Student-t weights, batch 1 and 16), config 3 (one LLaMA-3.2-1B layer plus its lm_head
     128256 x 2048) and config 2 (the 1B layer alone: a launch too small for the ring kernel)."""
     from inputs import config_matrices
     specs = [s for s in config_matrices(config) if config == 2 or s.name.startswith("L00.") or s.name == "lm_head"]
     assert len(specs) == (7 if config == 2 else 8) and (config == 2 or specs[-1].rows == 128256)
-    rng = np.random.default_rng(77)
-    mats, picks, q_ref, s_ref = [], [], [], []
+    mats, q_ref, s_ref = [], [], []
     prev = None
     for spec in specs:
         W = make_weights(spec)
         prev = tq.tq_encode(W, dict_from=prev, bits=0 if width == 8 else width, pack=pack)
         mats.append(tq.Matrix(prev))
-        rows = np.unique(np.concatenate([[0, 15, 16, spec.rows - 17, spec.rows - 1], rng.integers(0, spec.rows, 59)]))
-        Qs, ss = O.quantize_rows(W[rows], bits=width)
-        picks.append(rows)
-        q_ref.append(Qs)
-        s_ref.append(ss)
+        parts = _oracle_by_row_blocks(lambda a, b: O.quantize_rows(W[a:b], bits=width), spec.rows)
+        q_ref.append(np.concatenate([p[0] for p in parts]))
+        s_ref.append(np.concatenate([p[1] for p in parts]))
         del W
     if pack:
         assert all(m.info["packing"] == 1 and m.info["seg_cols"] == 128 for m in mats)
@@ -305,19 +323,18 @@ def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows
         outs = [torch.full((sp.rows, sp.cols), 77, dtype=torch.int8, device=dev) for sp in specs]
         tq.tq_decompress_multi(handles, [o.data_ptr() for o in outs], _stream())
         torch.cuda.synchronize()
-        for o, rows, Qs in zip(outs, picks, q_ref):
-            assert np.array_equal(o[torch.from_numpy(rows).to(dev)].cpu().numpy(), Qs)
-        assert int((outs[-1] == 77).sum()) < outs[-1].numel() // 100      # nothing left unwritten (77 is an ordinary value too)
+        for o, Qs in zip(outs, q_ref):
+            assert torch.equal(o, torch.from_numpy(Qs).to(dev))          # the whole matrix, bit for bit
         del outs
         if config == 4 and not pack:
             assert all(m.info["lane_spread"] <= 113 for m in mats)   # none of them needs the whole-strip kernel
         for batch in batches:
-            xs, ys, xf = [], [], []
-            for sp in specs:
+            xs, ys, refs = [], [], []
+            for sp, Qs, ss in zip(specs, q_ref, s_ref):
                 bits, x = make_activations(sp, batch)
                 xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
                 ys.append(torch.full((batch, sp.rows), float("nan"), dtype=torch.float32, device=dev))
-                xf.append(x)
+                refs.append(np.concatenate(_oracle_by_row_blocks(lambda a, b: O.gemv_f64(Qs[a:b], ss[a:b], x), sp.rows), axis=1))
             step = tq.Step(handles, [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch)   # what bench.py times
             for through_step in (False, True):
                 for y in ys:
@@ -327,13 +344,12 @@ def test_full_size_shapes_in_the_benchmarks_launch_configuration_on_sampled_rows
                 else:
                     tq.tq_matvec_multi(handles, [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch, _stream())
                 torch.cuda.synchronize()
-                for y, rows, Qs, ss, x in zip(ys, picks, q_ref, s_ref, xf):
+                for y, ref in zip(ys, refs):
                     got = y.cpu().numpy()
-                    assert np.isfinite(got).all()
-                    ref = O.gemv_f64(Qs, ss, x)                           # [batch, sampled rows]
+                    assert got.shape == ref.shape and np.isfinite(got).all()
                     scale = np.abs(ref).max(axis=1, keepdims=True)
-                    assert (np.abs(got[:, rows] - ref) <= 1e-3 * scale).all()
-                    assert (np.abs(got[:, rows] - ref) <= 1e-5 * scale).all()   # what fp32 accumulation of exact products gives
+                    assert (np.abs(got - ref) <= 1e-3 * scale).all()
+                    assert (np.abs(got - ref) <= 1e-5 * scale).all()   # what fp32 accumulation of exact products gives
             step.close()
     finally:
         for m in mats:
@@ -576,8 +592,8 @@ def test_rows_too_long_for_the_activation_image_run_on_the_batched_kernels(dev, 
         m_small = tq.Matrix(tq.tq_encode(Ws, seg_cols=64, max_entries=me, bits=0 if width == 8 else width, pack=pack))
         try:
             assert np.array_equal(gpu_decompress(m, dev), Qo)
-            for ring_min in ("24", "0"):        # "0": the ring kernel takes the launch whatever its size
-                monkeypatch.setenv("TQ_RING_MIN_BANDS_PER_CU", ring_min)
+            for ring_min in (24, 0):        # 0: the ring kernel takes the launch whatever its size
+                tq.tq_set_ring_min_bands_per_cu(ring_min)
                 for batch in (1, 2, 8):
                     bits, x = make_activations(spec, batch)
                     ref = O.gemv_f64(Qo, so, x)

@@ -17,6 +17,13 @@ def dev():
     return torch.device("cuda:0")
 
 
+@pytest.fixture(autouse=True)
+def _default_ring_threshold_afterwards():
+    """Tests that change the library's ring-kernel threshold leave the default behind."""
+    yield
+    tq.tq_set_ring_min_bands_per_cu(24)
+
+
 def _stream():
     return torch.cuda.current_stream().cuda_stream
 
@@ -40,7 +47,7 @@ def test_single_matrices(dev, seed, monkeypatch):
         spec, pack, width, seg = _draw_matrix(rng)
         me = int(rng.choice([256, 300, 1000, 5000, 30719]))
         kind = str(rng.choice(["lzw", "frequency"]))
-        monkeypatch.setenv("TQ_RING_MIN_BANDS_PER_CU", str(int(rng.choice([0, 24]))))
+        tq.tq_set_ring_min_bands_per_cu(int(rng.choice([0, 24])))
         W = make_weights(spec)
         if rng.integers(0, 5) == 0:
             W[rng.integers(0, spec.rows)] = 0           # an all-zero row
@@ -84,7 +91,7 @@ def test_calls_with_several_matrices(dev, seed, monkeypatch):
         n = int(rng.integers(2, 14))
         batch = int(rng.choice([1, 1, 2, 5, 8, 9, 16]))
         gate_up = bool(rng.integers(0, 5) == 0)
-        monkeypatch.setenv("TQ_RING_MIN_BANDS_PER_CU", str(int(rng.choice([0, 0, 24]))))
+        tq.tq_set_ring_min_bands_per_cu(int(rng.choice([0, 0, 24])))
         mats, xs, ys, refs, outs, Qs = [], [], [], [], [], []
         chain, entries = {}, {}
         for _k in range(n):

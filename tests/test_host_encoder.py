@@ -202,6 +202,11 @@ def test_validation_rejects_malformed_containers():
         "pad entry": _mutate(blob, o_d + 4 * p["n_entries"], "<I", 8 << 24),
         "count of real codes": _mutate(blob, 88, "<Q", p["n_real_codes"] + 1),
     }
+    # a one-byte entry at a code from 256 on that no code of the stream uses: every lane stream still adds up, but the
+    # kernels take the run length from the code alone, so such a dictionary must not pass
+    unused = np.setdiff1d(np.arange(256, p["n_entries"]), p["stream"])
+    assert unused.size
+    bad["one-byte entry above 255"] = _mutate(blob, o_d + 4 * int(unused[0]), "<I", (8 << 24) | 0x05)
     # a pad code in the middle of a lane stream (before real codes)
     assert last >= 1
     bad["pad inside a lane stream"] = _mutate(blob, o_c, "<H", p["pad_code"])
