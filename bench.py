@@ -3,12 +3,15 @@
 
 A step = every matrix-vector product of one LLaMA-3.2-3B token step (28 layers x q,k,v,o,gate,up,down + lm_head,
 197 matrices, each with its own seeded activation), weights resident in HBM in compressed form.
-Prints one JSON line: compressed-weight HBM GB/s (value), tokens/s, roofline of the matvec kernel and the CPU
-oracle timed on a sample of the same workload.
+Prints one JSON line: compressed-weight HBM GB/s (value), tokens/s, roofline of the matvec kernel (batch 1), of the
+batched kernel (batch 8), the stress configuration (Student-t weights, batch 16, whole-model expansion), the same sweep
+with one dictionary per matrix, and the CPU oracle timed on a sample of the same workload, against which the timed
+outputs are then checked.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -22,19 +25,36 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM traffic of the matvec launches measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the default workload
-# (config 4, batch 1, default encoder options, whole sweep as one prepared step = one kernel launch), scaled by a plain 1 GiB copy in
-# the same run (profiles/k_matvec_config4_batch1_hbm_traffic.txt): bytes read per algorithmic byte, bytes written per step.
-MEASURED_FETCH_PER_ALGORITHMIC_BYTE = 1.0030
-MEASURED_WRITE_BYTES_PER_STEP = 3_618_000
+# HBM traffic of the default workload's launches measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain
+# 1 GiB copy in the same run; profiles/k_matvec_config4_batch1_hbm_traffic.txt): bytes read per stored byte of the
+# launch, bytes written per step.  The figures belong to the kernel sources whose digest is given; with other sources
+# `traffic` is reported as null rather than as a stale number.
+PROFILED_TRAFFIC = {
+    "csrc_sha16": "",
+    "fetch_per_stored_byte": 1.0030,
+    "write_bytes_per_step": 3_618_000,
+}
+
+
+def csrc_digest() -> str:
+    d = os.path.join(ROOT, "paper_2509_22951_amd", "csrc")
+    h = hashlib.sha256()
+    for f in sorted(os.listdir(d)):
+        if f.endswith((".h", ".hip", ".cpp")):
+            h.update(f.encode())
+            h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=100,
-                    help="untimed steps; a step takes under a millisecond and the GPU needs tens of milliseconds of load to reach its sustained clocks")
+    ap.add_argument("--warmup", type=int, default=100, help="untimed steps right before the timed ones")
+    ap.add_argument("--prewarm-ms", type=float, default=150.0,
+                    help="before the counted warm-up: the same launches repeated, uncounted, for at least this long, so that the "
+                         "GPU has reached its sustained clocks whatever --warmup is (a step takes under a millisecond; the "
+                         "clocks need tens of milliseconds of load)")
     ap.add_argument("--config", type=int, default=4, help="workload: config 4 = LLaMA-3.2-3B decode-step sweep")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--also-batch", type=int, default=8, help="second batch size reported under 'other_batches' (0 = none)")
@@ -53,7 +73,7 @@ def parse_args():
                     help="quantization width (paper section 3 tried 8, 6, 4, 2 and ternary); the headline is 8")
     ap.add_argument("--pack", action="store_true",
                     help="with --bits 2..4: two values per stored byte (a code then stands for up to four weights)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle (then nothing is verified either)")
     ap.add_argument("--cpu-sample-layers", type=int, default=8,
                     help="layers of the sweep the CPU oracle is timed on (8 layers = 56 matrices take about 10 s on one core)")
     ap.add_argument("--no-decompress", action="store_true", help="skip the tq_decompress pass over all matrices")
@@ -61,6 +81,10 @@ def parse_args():
                     help="skip the leg that runs the gate/up pairs of the workload as fused silu(gate) * up products")
     ap.add_argument("--no-listing", action="store_true",
                     help="skip the leg that expands one matrix stored in the paper's own section 4 stream format")
+    ap.add_argument("--no-config5", action="store_true",
+                    help="skip the stress configuration (config 5: Student-t weights, batch 16, whole-model expansion)")
+    ap.add_argument("--no-matrix-dictionary", action="store_true",
+                    help="skip the leg that repeats the sweep with one dictionary per matrix")
     ap.add_argument("--layers", type=int, default=0, help="debug: keep only the first N layers (+ lm_head)")
     ap.add_argument("--fuse", choices=["none", "independent", "layer", "sweep"], default="sweep",
                     help="how the products of a step are grouped into launches.  sweep: the step is a list of independent "
@@ -80,20 +104,265 @@ def parse_args():
     return ap.parse_args()
 
 
-def gate_up_leg(specs, mats, prev, opts, args, dev, stream):
+class Workload:
+    """The matrices of one configuration, encoded and resident in device memory, with the byte counts of their containers."""
+
+    def __init__(self, tq, specs, args, dictionary, opts, keep_names=(), keep_all=False):
+        from inputs import make_weights
+        self.specs = specs
+        self.kept = {}          # index -> container bytes, for the matrices the CPU oracle will decode
+        self.blobs = {}         # every container (small workloads only: further copies are made from them)
+        mats = [None] * len(specs)
+        workers = max(1, min(args.threads, 8))
+        inner = max(1, args.threads // workers)
+        opts = dict(opts)
+        # One LZW dictionary over the sequence: the matrices are encoded one after the other, each starting from the
+        # dictionary the previous one ended with, until the dictionary is full (Gaussian weights fill it inside the first
+        # matrix) or the first layer is through; from then on it is frozen at the size it has reached, so the remaining
+        # matrices no longer depend on each other and are encoded in parallel.
+        cap = args.max_entries or tq.TQ_MAX_ENTRIES_DEVICE
+        prev, n_chain = None, 0
+
+        def keep(i, blob):
+            if specs[i].name in keep_names:
+                self.kept[i] = blob
+            if keep_all:
+                self.blobs[i] = blob
+
+        while n_chain < min(7, len(specs)):
+            i = n_chain
+            blob = tq.tq_encode(make_weights(specs[i]), n_threads=args.threads,
+                                dict_from=prev if dictionary == "sequence" else None, **opts)
+            mats[i] = tq.Matrix(blob)
+            keep(i, blob)
+            prev = blob
+            n_chain += 1
+            if dictionary != "sequence" or mats[i].info["n_entries"] == cap:
+                break
+        if dictionary == "sequence":
+            opts["max_entries"] = mats[n_chain - 1].info["n_entries"]
+        rest = sorted(range(n_chain, len(specs)), key=lambda i: -specs[i].rows * specs[i].cols)
+
+        def encode(i):
+            return i, tq.tq_encode(make_weights(specs[i]), n_threads=inner,
+                                   dict_from=prev if dictionary == "sequence" else None, **opts)
+
+        with ThreadPoolExecutor(workers) as ex:
+            for i, blob in ex.map(encode, rest):
+                mats[i] = tq.Matrix(blob)                   # validates, uploads, frees nothing on the hot path later
+                keep(i, blob)
+        self.mats, self.opts, self.prev, self.dictionary = mats, opts, prev, dictionary
+        self.infos = infos = [m.info for m in mats]
+        # Bytes the kernels must read from HBM: code stream, unit offsets and scales of every matrix, and every distinct
+        # dictionary once (matrices encoded as one sequence hold the same dictionary; the library stores one copy).
+        # The matrices of a chain hold growing dictionaries, all later ones the last of them.
+        dict_bytes = sum(i["dict_bytes"] for i in (infos[:n_chain] if dictionary == "sequence" else infos))
+        self.stored_bytes = sum(i["compressed_bytes"] - i["dict_bytes"] for i in infos) + dict_bytes
+        self.n_codes = sum(i["n_codes"] for i in infos)
+        self.n_real_codes = sum(i["n_real_codes"] for i in infos)
+        # The method's own bytes: the codes of the parse (the padding codes that even out the 64 lane streams of a unit
+        # are this layout's overhead, not the method's), unit offsets, scales, dictionaries.
+        self.algorithmic_bytes = self.stored_bytes - 2 * (self.n_codes - self.n_real_codes)
+        self.n_weights = sum(s.rows * s.cols for s in specs)
+
+    def close(self):
+        for m in self.mats:
+            m.close()
+        self.mats = []
+
+
+def launch_groups(specs, fuse):
+    """Launch plan: consecutive matrices that a transformer layer computes from the same input are independent."""
+    groups, cur = [], []
+    for i, s in enumerate(specs):
+        kind = s.name.split(".")[-1]
+        joins = bool(cur) and (
+            fuse == "sweep" or
+            (fuse == "layer" and s.name.split(".")[0] == specs[cur[-1]].name.split(".")[0]) or
+            (fuse == "independent" and (
+                (kind in ("k_proj", "v_proj") and specs[cur[-1]].name.split(".")[-1] in ("q_proj", "k_proj")) or
+                (kind == "up_proj" and specs[cur[-1]].name.split(".")[-1] == "gate_proj"))))
+        if joins:
+            cur.append(i)
+        else:
+            if cur:
+                groups.append(cur)
+            cur = [i]
+    groups.append(cur)
+    return groups
+
+
+def timed_block(step, steps, warmup, prewarm_ms, torch, spread_steps=100):
+    """prewarm (uncounted, by wall time) -> warmup steps -> `steps` steps timed as one block, by wall clock and by HIP events
+    on the launch stream -> the same steps once more with an event between every two (median / min / max)."""
+    t0 = time.perf_counter()
+    n_pre = 0
+    while (time.perf_counter() - t0) * 1e3 < prewarm_ms:
+        for _ in range(10):
+            step()
+        n_pre += 10
+        torch.cuda.synchronize()
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ev_ms = e0.elapsed_time(e1) / steps
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(min(steps, spread_steps) + 1)]
+    marks[0].record()
+    for e in marks[1:]:
+        step()
+        e.record()
+    torch.cuda.synchronize()
+    each = sorted(a.elapsed_time(b) for a, b in zip(marks[:-1], marks[1:]))
+    spread = {"median": round(each[len(each) // 2], 4), "min": round(each[0], 4), "max": round(each[-1], 4), "n": len(each)}
+    return wall_ms, ev_ms, spread, n_pre
+
+
+def roofline_block(kernel, wl, ev_ms, n_launches, traffic=None, extra_bytes=0, note=None):
+    """achieved = algorithmic bytes per launch / mean launch duration (HIP events on the launch stream around the timed
+    steps, launches back to back).  extra_bytes: algorithmic bytes written (the expansion writes the matrix)."""
+    alg = wl.algorithmic_bytes + extra_bytes
+    ach = alg / ev_ms / 1e6
+    return {
+        "bound": "hbm", "kernel": kernel,
+        "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+        "traffic": traffic,
+        "algorithmic_bytes_per_launch": round(alg / n_launches),
+        "stored_bytes_per_launch": round((wl.stored_bytes + extra_bytes) / n_launches),
+        "padding_frac": round(1 - wl.n_real_codes / wl.n_codes, 4),
+        "frac_on_stored_bytes": round((wl.stored_bytes + extra_bytes) / ev_ms / 1e6 / HBM_PEAK_GBS, 4),
+        "launch_us": round(ev_ms * 1e3 / n_launches, 1),
+        "note": note or "achieved = algorithmic bytes per launch (codes of the parse without the layout's padding codes, unit "
+                        "offsets, scales, each distinct dictionary once) / mean launch duration from HIP events on the launch "
+                        "stream; traffic = HBM bytes per launch from the FETCH_SIZE/WRITE_SIZE counter runs under profiles/ "
+                        "(null off the profiled workload or when the kernel sources have changed since)",
+    }
+
+
+class Runner:
+    """Times the products of a workload at one batch size in the launch plan the arguments ask for."""
+
+    def __init__(self, tq, torch, wl, mat_sets, args, dev, stream):
+        self.tq, self.torch, self.wl, self.mat_sets, self.args, self.dev, self.stream = tq, torch, wl, mat_sets, args, dev, stream
+        self.groups = launch_groups(wl.specs, args.fuse)
+
+    def make_io(self, batch):
+        from inputs import make_activations
+        xs, ys = [], []
+        for s in self.wl.specs:
+            bits, _ = make_activations(s, batch)
+            xs.append(self.torch.from_numpy(bits.view(np.int16).copy()).to(self.dev))
+            ys.append(self.torch.empty((batch, s.rows), dtype=self.torch.float32, device=self.dev))
+        return xs, ys
+
+    def run(self, batch, steps, warmup, prewarm_ms):
+        tq, torch, args, stream = self.tq, self.torch, self.args, self.stream
+        xs, ys = self.make_io(batch)
+        extra = [0]   # kernel launches per step relative to tq_matvec_multi's
+
+        def calls_for(ms, count):
+            calls = []            # one per group; each takes the stream to launch on
+            for g in self.groups:
+                if len(g) == 1:   # one matrix: its description travels in the kernel arguments
+                    m, xp, yp = ms[g[0]], xs[g[0]].data_ptr(), ys[g[0]].data_ptr()
+                    calls.append(lambda s, m=m, xp=xp, yp=yp: m.matvec(xp, yp, batch, s))
+                elif args.no_prepared_step:
+                    mc = tq.MultiCall([ms[i].handle for i in g], [xs[i].data_ptr() for i in g],
+                                      [ys[i].data_ptr() for i in g], batch)
+                    calls.append(lambda s, mc=mc: mc.launch(s))
+                else:   # the same products as a prepared step: buffers fixed, jobs in device memory, up to 896 matrices per launch
+                    st = tq.Step([ms[i].handle for i in g], [xs[i].data_ptr() for i in g], [ys[i].data_ptr() for i in g], batch)
+                    if count:
+                        extra[0] += st.info["n_launches"] - (-(-len(g) // 128))
+                    calls.append(lambda s, st=st: st.launch(s))
+            return calls
+
+        def stepper(calls):
+            def eager_step():
+                for c in calls:
+                    c(stream)
+            if not args.graph:
+                return eager_step
+            eager_step()
+            torch.cuda.synchronize()
+            side = torch.cuda.Stream()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                cap = torch.cuda.current_stream().cuda_stream
+                for c in calls:      # the same calls, issued on the capturing stream
+                    c(cap)
+            return graph.replay
+
+        steppers = [stepper(calls_for(ms, k == 0)) for k, ms in enumerate(self.mat_sets)]
+        turn = [0]
+
+        def step():   # copy after copy
+            steppers[turn[0] % len(steppers)]()
+            turn[0] += 1
+
+        wall_ms, ev_ms, spread, n_pre = timed_block(step, steps, warmup, prewarm_ms, torch)
+        # tq_matvec_multi serves up to 128 matrices per kernel launch; a prepared step may need fewer launches (or more,
+        # where the matrices of a group go to different kernels)
+        n_launches = sum(-(-len(g) // 128) for g in self.groups) + extra[0]
+        return dict(wall_ms=wall_ms, ev_ms=ev_ms, spread=spread, prewarm_steps=n_pre, n_launches=n_launches, xs=xs, ys=ys)
+
+
+def expansion_leg(tq, torch, wl, args, dev, stream, keep_output=False):
+    """tq_decompress of every matrix of the workload into one device buffer, matrix after matrix."""
+    out = torch.empty(wl.n_weights, dtype=torch.int8, device=dev)
+    offs = np.cumsum([0] + [s.rows * s.cols for s in wl.specs])
+    handles, ptrs = [m.handle for m in wl.mats], [out.data_ptr() + int(o) for o in offs[:-1]]
+    dstep = None if args.no_prepared_step else tq.Step(handles, None, ptrs, decompress=True)
+
+    def expand():
+        if dstep is None:
+            tq.tq_decompress_multi(handles, ptrs, stream)
+        else:
+            dstep.launch(stream)
+    for _ in range(5):
+        expand()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 10
+    e0.record()
+    for _ in range(reps):
+        expand()
+    e1.record()
+    torch.cuda.synchronize()
+    d_ms = e0.elapsed_time(e1) / reps
+    n_launches = -(-len(wl.mats) // 128) if dstep is None else dstep.info["n_launches"]
+    res = {"ms_per_model": round(d_ms, 3), "kernel_launches": n_launches,
+           "GBps_read_plus_write": round((wl.algorithmic_bytes + wl.n_weights) / d_ms / 1e6, 1),
+           "GBps_written": round(wl.n_weights / d_ms / 1e6, 1),
+           "roofline": roofline_block("tq::k_decompress", wl, d_ms, n_launches, extra_bytes=wl.n_weights,
+                                      note="read + write: algorithmic bytes read (as for the product) plus one byte written per "
+                                           "weight, per launch / mean launch duration from HIP events on the launch stream")}
+    return res, (out, offs) if keep_output else None
+
+
+def gate_up_leg(wl, args, dev, stream):
     """The gate/up pairs of the workload (up to 8 layers of them) as fused products: one container of interleaved rows
     per pair, silu(gate) * up in the kernel's epilogue, against the same pairs as two separate products each."""
     import torch
 
     import paper_2509_22951_amd as tq
     from inputs import make_activations, make_weights
+    specs, mats = wl.specs, wl.mats
     pairs = [(i, i + 1) for i in range(len(specs) - 1)
              if specs[i].name.endswith("gate_proj") and specs[i + 1].name.endswith("up_proj")][:8]
     if not pairs:
         return None
     batch = args.batch
+    prev = wl.prev if wl.dictionary == "sequence" else None
     fused = [tq.Matrix(tq.tq_encode_gate_up(make_weights(specs[g]), make_weights(specs[u]), n_threads=args.threads,
-                                            dict_from=prev, **opts)) for g, u in pairs]
+                                            dict_from=prev, **wl.opts)) for g, u in pairs]
     xs = [torch.from_numpy(make_activations(specs[g], batch)[0].view(np.int16).copy()).to(dev) for g, _ in pairs]
     ys = [torch.empty((batch, specs[g].rows), dtype=torch.float32, device=dev) for g, _ in pairs]
     y2 = [torch.empty((batch, specs[g].rows), dtype=torch.float32, device=dev) for g, _ in pairs]
@@ -171,6 +440,89 @@ def listing_leg(specs, mats, dev, stream):
             "us": round(us, 1), "GBps_read_plus_write": round(moved / us / 1e3, 1), "exact": ok}
 
 
+def cpu_baseline_and_verification(wl, args, infos, timed_ys, expanded, torch):
+    """The CPU oracle on a bounded sample of the workload (timed: sequential decode + float64 product, one thread, then
+    the same sample over the host's threads), and, with the oracle's results in hand, the check of what the GPU was
+    timed on: every row of the timed outputs of the sample matrices and of the other matrices kept for it (last layer,
+    lm_head) against the oracle's float64 products, and the same matrices of the timed expansion against the oracle's
+    decoded bytes, bit for bit.  For the first layer the oracle also quantizes the generated weights itself, so the
+    whole chain weights -> container -> output is covered there."""
+    from inputs import make_activations, make_weights
+    from oracle import oracle as O
+    specs = wl.specs
+    sample = sorted(i for i in wl.kept if specs[i].name in {s.name for s in specs[:7 * args.cpu_sample_layers]})
+    others = sorted(i for i in wl.kept if i not in sample)
+    t0 = time.perf_counter()
+    sb, refs = 0, {}
+    for i in sample:
+        _, x = make_activations(specs[i], args.batch)
+        refs[i] = O.matvec_from_blob(wl.kept[i], x)                 # oracle: sequential decode, then float64 GEMV
+        sb += infos[i]["compressed_bytes"]
+    dt = time.perf_counter() - t0
+    sw = sum(specs[i].rows * specs[i].cols for i in sample)
+    out = {
+        "value": round(sb / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"first {args.cpu_sample_layers} layers of the sweep ({len(sample)} matrices, {sw} weights, {dt:.2f} s): decode + "
+                  f"float64 GEMV, batch {args.batch}; whole sweep extrapolates to {dt * wl.n_weights / sw:.1f} s/token",
+        "tokens_per_s_extrapolated": round(args.batch / (dt * wl.n_weights / sw), 4),
+    }
+    # the same sample once more, the matrices (independent of each other) spread over the host's threads
+    n_thr = max(1, min(args.threads, len(sample)))
+    work = [(wl.kept[i], make_activations(specs[i], args.batch)[1]) for i in sample]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=n_thr) as pool:
+        list(pool.map(lambda bx: O.matvec_from_blob(*bx), work))
+    dt_all = time.perf_counter() - t0
+    model = next((l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name")), "unknown")
+    out["all_threads"] = {"value": round(sb / dt_all / 1e9, 3), "unit": "GB/s", "threads": n_thr,
+                          "seconds": round(dt_all, 2), "os_cpu_count": os.cpu_count(), "cpu": model}
+
+    # ---- verification of the timed buffers (not timed itself)
+    decoded = {}
+
+    def product_of(i):
+        Q, s = O.decode_blob(wl.kept[i])
+        decoded[i] = Q
+        _, x = make_activations(specs[i], args.batch)
+        rows = specs[i].rows
+        cuts = [(a, min(rows, a + 8192)) for a in range(0, rows, 8192)]
+        with ThreadPoolExecutor(max_workers=max(1, args.threads)) as pool:
+            return np.concatenate(list(pool.map(lambda ab: O.gemv_f64(Q[ab[0]:ab[1]], s[ab[0]:ab[1]], x), cuts)), axis=1)
+
+    for i in others:
+        refs[i] = product_of(i)
+    worst, rows_checked, ok = 0.0, 0, True
+    for i, ref in refs.items():
+        got = timed_ys[i].cpu().numpy().astype(np.float64)
+        scale = np.abs(ref).max(axis=1, keepdims=True)
+        err = float((np.abs(got - ref) / np.maximum(scale, 1e-300)).max()) if np.isfinite(got).all() else float("inf")
+        worst = max(worst, err)
+        ok = ok and err <= 1e-3
+        rows_checked += ref.shape[1]
+    verified = {"outputs": ok, "matrices": len(refs), "rows": rows_checked, "worst_rel_err": float(f"{worst:.3e}"),
+                "tolerance": 1e-3, "against": "oracle decode of the container + float64 product, every row of the timed y buffers of "
+                                              "the sample layers, the last layer and lm_head"}
+    quant_ok = True
+    for i in sorted(refs)[:7]:      # first layer: the oracle quantizes the generated weights itself
+        if i not in decoded:
+            decoded[i] = O.decode_blob(wl.kept[i])[0]
+        Qo, _ = O.quantize_rows(make_weights(specs[i]), args.bits)
+        quant_ok = quant_ok and np.array_equal(Qo, decoded[i])
+    verified["first_layer_containers_hold_the_oracles_quantized_weights"] = bool(quant_ok)
+    if expanded is not None:
+        buf, offs = expanded
+        exact = True
+        for i in sorted(refs):
+            if i not in decoded:
+                decoded[i] = O.decode_blob(wl.kept[i])[0]
+            dev_q = buf[int(offs[i]):int(offs[i + 1])].view(specs[i].rows, specs[i].cols)
+            exact = exact and bool(torch.equal(dev_q, torch.from_numpy(decoded[i]).to(dev_q.device)))
+        verified["expansion_bit_exact"] = exact
+        ok = ok and exact
+    verified["ok"] = bool(ok and quant_ok)
+    return out, verified
+
+
 def main():
     args = parse_args()
     if args.pack and args.bits > 4:
@@ -183,240 +535,81 @@ def main():
     import torch
 
     import paper_2509_22951_amd as tq
-    from inputs import CONFIGS, config_matrices, make_activations, make_weights
+    from inputs import CONFIGS, config_matrices
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(2)
     tq.load()
     dev = torch.device("cuda:0")
-    specs = config_matrices(args.config)
-    if args.layers:
-        specs = [s for s in specs if s.name == "lm_head" or int(s.name[1:3]) < args.layers]
-    t_setup = time.time()
-
-    # ---- encode (host, off the hot path): generate -> quantize -> dictionary-code, a few matrices at a time
-    sample_names = {s.name for s in specs[:7 * args.cpu_sample_layers]}   # the first layers double as the CPU-oracle sample
-    sample_blobs = {}
-    workers = max(1, min(args.threads, 8))
-    inner = max(1, args.threads // workers)
-    opts = dict(max_entries=args.max_entries, lmax=args.lmax, seg_cols=args.seg_cols, dictionary=args.dictionary_kind,
-                bits=0 if args.bits == 8 else args.bits, pack=args.pack)
-    # One LZW dictionary over the sequence: the matrices are encoded one after the other, each starting from the
-    # dictionary the previous one ended with, until the dictionary is full (Gaussian weights fill it inside the first
-    # matrix) or the first layer is through; from then on it is frozen at the size it has reached, so the remaining
-    # matrices no longer depend on each other and are encoded in parallel.
-    mats = [None] * len(specs)
-    keep_blobs = sum(s.rows * s.cols for s in specs) < 400_000_000 and args.copies != 1   # small workload: further copies are made below
-    blobs = {}
-    cap = args.max_entries or tq.TQ_MAX_ENTRIES_DEVICE
-    prev, n_chain = None, 0
-    while n_chain < min(7, len(specs)):
-        i = n_chain
-        blob = tq.tq_encode(make_weights(specs[i]), n_threads=args.threads,
-                            dict_from=prev if args.dictionary == "sequence" else None, **opts)
-        mats[i] = tq.Matrix(blob)
-        if specs[i].name in sample_names:
-            sample_blobs[i] = blob
-        if keep_blobs:
-            blobs[i] = blob
-        prev = blob
-        n_chain += 1
-        if args.dictionary != "sequence" or mats[i].info["n_entries"] == cap:
-            break
-    if args.dictionary == "sequence":
-        opts["max_entries"] = mats[n_chain - 1].info["n_entries"]
-    rest = sorted(range(n_chain, len(specs)), key=lambda i: -specs[i].rows * specs[i].cols)
-
-    def encode(i):
-        s = specs[i]
-        blob = tq.tq_encode(make_weights(s), n_threads=inner,
-                            dict_from=prev if args.dictionary == "sequence" else None, **opts)
-        return i, blob
-
-    with ThreadPoolExecutor(workers) as ex:
-        for i, blob in ex.map(encode, rest):
-            mats[i] = tq.Matrix(blob)                   # validates, uploads, frees nothing on the hot path later
-            if specs[i].name in sample_names:
-                sample_blobs[i] = blob
-            if keep_blobs:
-                blobs[i] = blob
-    infos = [m.info for m in mats]
-    # bytes the kernels must read from HBM: code stream, unit offsets and scales of every matrix, and every distinct
-    # dictionary once (matrices encoded as one sequence hold the same dictionary; the library stores one copy)
-    stream_bytes = sum(i["compressed_bytes"] - i["dict_bytes"] for i in infos)
-    if args.dictionary == "sequence":   # the matrices of the chain hold growing dictionaries, all later ones the last of them
-        comp_bytes = stream_bytes + sum(i["dict_bytes"] for i in infos[:n_chain])
-    else:
-        comp_bytes = stream_bytes + sum(i["dict_bytes"] for i in infos)
-    n_weights = sum(s.rows * s.cols for s in specs)
-    n_codes = sum(i["n_codes"] for i in infos)
-
-    # Cold-cache protocol: a workload that fits the caches is held in several copies and step k reads copy k mod N.
-    n_copies = args.copies if args.copies > 0 else (-(-512_000_000 // comp_bytes) if keep_blobs else 1)
-    if not keep_blobs:
-        n_copies = 1
-    mat_sets = [mats] + [[tq.Matrix(blobs[i]) for i in range(len(specs))] for _ in range(n_copies - 1)]
-    blobs.clear()
-
     stream = torch.cuda.current_stream().cuda_stream
 
-    def make_io(batch):
-        xs, ys = [], []
-        for s in specs:
-            bits, _ = make_activations(s, batch)
-            xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
-            ys.append(torch.empty((batch, s.rows), dtype=torch.float32, device=dev))
-        return xs, ys
+    def specs_of(config):
+        specs = config_matrices(config)
+        if args.layers:
+            specs = [s for s in specs if s.name == "lm_head" or int(s.name[1:3]) < args.layers]
+        return specs
 
-    # launch plan: consecutive matrices that a transformer layer computes from the same input are independent
-    groups, cur = [], []
-    for i, s in enumerate(specs):
-        kind = s.name.split(".")[-1]
-        joins = bool(cur) and (
-            args.fuse == "sweep" or
-            (args.fuse == "layer" and s.name.split(".")[0] == specs[cur[-1]].name.split(".")[0]) or
-            (args.fuse == "independent" and (
-                (kind in ("k_proj", "v_proj") and specs[cur[-1]].name.split(".")[-1] in ("q_proj", "k_proj")) or
-                (kind == "up_proj" and specs[cur[-1]].name.split(".")[-1] == "gate_proj"))))
-        if joins:
-            cur.append(i)
-        else:
-            if cur:
-                groups.append(cur)
-            cur = [i]
-    groups.append(cur)
+    specs = specs_of(args.config)
+    t_setup = time.time()
+    # ---- encode (host, off the hot path): generate -> quantize -> dictionary-code, a few matrices at a time.
+    # Kept for the CPU oracle: the first layers (its timed sample), the last layer and lm_head (verification only).
+    keep_names = set() if args.no_cpu_baseline else ({s.name for s in specs[:7 * args.cpu_sample_layers]} | {s.name for s in specs[-8:]})
+    opts = dict(max_entries=args.max_entries, lmax=args.lmax, seg_cols=args.seg_cols, dictionary=args.dictionary_kind,
+                bits=0 if args.bits == 8 else args.bits, pack=args.pack)
+    small = sum(s.rows * s.cols for s in specs) < 400_000_000 and args.copies != 1   # small workload: further copies are made below
+    wl = Workload(tq, specs, args, args.dictionary, opts, keep_names, keep_all=small)
+    infos = wl.infos
 
-    launches = [0]   # kernel launches per step relative to tq_matvec_multi's, for the batch run last
-    spread = {}      # batch -> per-step durations (ms) of a second, separately timed pass
-
-    def run(batch, steps, warmup):
-        xs, ys = make_io(batch)
-        launches[0] = 0
-
-        def calls_for(ms, count):
-            calls = []            # one per group; each takes the stream to launch on
-            for g in groups:
-                if len(g) == 1:   # one matrix: its description travels in the kernel arguments
-                    m, xp, yp = ms[g[0]], xs[g[0]].data_ptr(), ys[g[0]].data_ptr()
-                    calls.append(lambda s, m=m, xp=xp, yp=yp: m.matvec(xp, yp, batch, s))
-                elif args.no_prepared_step:
-                    mc = tq.MultiCall([ms[i].handle for i in g], [xs[i].data_ptr() for i in g],
-                                      [ys[i].data_ptr() for i in g], batch)
-                    calls.append(lambda s, mc=mc: mc.launch(s))
-                else:   # the same products as a prepared step: buffers fixed, jobs in device memory, up to 896 matrices per launch
-                    st = tq.Step([ms[i].handle for i in g], [xs[i].data_ptr() for i in g], [ys[i].data_ptr() for i in g], batch)
-                    if count:
-                        launches[0] += st.info["n_launches"] - (-(-len(g) // 128))
-                    calls.append(lambda s, st=st: st.launch(s))
-            return calls
-
-        def stepper(calls):
-            def eager_step():
-                for c in calls:
-                    c(stream)
-            if not args.graph:
-                return eager_step
-            eager_step()
-            torch.cuda.synchronize()
-            side = torch.cuda.Stream()
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=side):
-                cap = torch.cuda.current_stream().cuda_stream
-                for c in calls:      # the same calls, issued on the capturing stream
-                    c(cap)
-            return graph.replay
-
-        steppers = [stepper(calls_for(ms, k == 0)) for k, ms in enumerate(mat_sets)]
-        turn = [0]
-
-        def step():   # copy after copy
-            steppers[turn[0] % len(steppers)]()
-            turn[0] += 1
-
-        for _ in range(warmup):
-            step()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record()
-        for _ in range(steps):
-            step()
-        e1.record()
-        torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-        ev_ms = e0.elapsed_time(e1) / steps
-        # after the timed region: the same steps once more with an event between every two, for the spread
-        marks = [torch.cuda.Event(enable_timing=True) for _ in range(min(steps, 100) + 1)]
-        marks[0].record()
-        for e in marks[1:]:
-            step()
-            e.record()
-        torch.cuda.synchronize()
-        each = sorted(a.elapsed_time(b) for a, b in zip(marks[:-1], marks[1:]))
-        spread[batch] = {"median": round(each[len(each) // 2], 4), "min": round(each[0], 4), "max": round(each[-1], 4), "n": len(each)}
-        return wall_ms, ev_ms
-
+    # Cold-cache protocol: a workload that fits the caches is held in several copies and step k reads copy k mod N.
+    n_copies = args.copies if args.copies > 0 else (-(-512_000_000 // wl.stored_bytes) if small else 1)
+    if not small:
+        n_copies = 1
+    mat_sets = [wl.mats] + [[tq.Matrix(wl.blobs[i]) for i in range(len(specs))] for _ in range(n_copies - 1)]
+    wl.blobs.clear()
     setup_s = time.time() - t_setup
+
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)       # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    wall_ms, ev_ms = run(args.batch, args.steps, args.warmup)
-    launch_delta = launches[0]
+
+    runner = Runner(tq, torch, wl, mat_sets, args, dev, stream)
+    main_run = runner.run(args.batch, args.steps, args.warmup, args.prewarm_ms)
+    wall_ms, ev_ms, n_launches = main_run["wall_ms"], main_run["ev_ms"], main_run["n_launches"]
+
+    def kernel_name(batch, packed=False):
+        return "tq::k_matvec" if batch <= 2 else "tq::k_matvec_ring"
+
     others = {}
     if args.also_batch and args.also_batch != args.batch:
-        w2, e2 = run(args.also_batch, max(3, args.steps // 2), args.warmup)
-        others[str(args.also_batch)] = {"ms_per_step": round(w2, 4), "GBps": round(comp_bytes / w2 / 1e6, 1),
-                                        "tokens_per_s": round(args.also_batch / (w2 * 1e-3), 1),
-                                        "step_ms": spread.get(args.also_batch)}
+        r2 = runner.run(args.also_batch, max(3, args.steps // 2), args.warmup, args.prewarm_ms)
+        others[str(args.also_batch)] = {
+            "ms_per_step": round(r2["wall_ms"], 4), "GBps": round(wl.algorithmic_bytes / r2["wall_ms"] / 1e6, 1),
+            "tokens_per_s": round(args.also_batch / (r2["wall_ms"] * 1e-3), 1), "step_ms": r2["spread"],
+            "roofline": roofline_block(kernel_name(args.also_batch), wl, r2["ev_ms"], r2["n_launches"])}
+        del r2
 
-    decompress = None
+    decompress, expanded = None, None
     if not args.no_decompress:
-        out = torch.empty(n_weights, dtype=torch.int8, device=dev)          # the whole model expanded, matrix after matrix
-        offs = np.cumsum([0] + [s.rows * s.cols for s in specs])
-        handles, ptrs = [m.handle for m in mats], [out.data_ptr() + int(o) for o in offs[:-1]]
-        dstep = None if args.no_prepared_step else tq.Step(handles, None, ptrs, decompress=True)
-
-        def expand():
-            if dstep is None:
-                tq.tq_decompress_multi(handles, ptrs, stream)
-            else:
-                dstep.launch(stream)
-        for _ in range(5):
-            expand()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 10
-        e0.record()
-        for _ in range(reps):
-            expand()
-        e1.record()
-        torch.cuda.synchronize()
-        d_ms = e0.elapsed_time(e1) / reps
-        decompress = {"ms_per_model": round(d_ms, 3),
-                      "kernel_launches": -(-len(mats) // 128) if dstep is None else dstep.info["n_launches"],
-                      "GBps_read_plus_write": round((comp_bytes + n_weights) / d_ms / 1e6, 1),
-                      "GBps_written": round(n_weights / d_ms / 1e6, 1)}
-        del out
+        decompress, expanded = expansion_leg(tq, torch, wl, args, dev, stream, keep_output=not args.no_cpu_baseline)
 
     listing = None
     if not args.no_listing:
-        listing = listing_leg(specs, mats, dev, stream)
+        listing = listing_leg(specs, wl.mats, dev, stream)
     gate_up = None
     if not args.no_gate_up:
-        gate_up = gate_up_leg(specs, mats, prev if args.dictionary == "sequence" else None, opts, args, dev, stream)
+        gate_up = gate_up_leg(wl, args, dev, stream)
 
-    # tq_matvec_multi serves up to 128 matrices per kernel launch; a prepared step may need fewer launches (or more,
-    # where the matrices of a group go to different kernels)
-    n_launches = sum(-(-len(g) // 128) for g in groups) + launch_delta
-    profiled = (args.config == 4 and args.batch == 1 and args.fuse == "sweep" and args.dictionary == "sequence"
-                and args.dictionary_kind == "lzw" and args.bits == 8 and not args.no_prepared_step
-                and not (args.max_entries or args.lmax or args.seg_cols or args.layers))
-    gbps = comp_bytes / wall_ms / 1e6
-    ach = comp_bytes / ev_ms / 1e6
+    default_workload = (args.config == 4 and args.batch == 1 and args.fuse == "sweep" and args.dictionary == "sequence"
+                        and args.dictionary_kind == "lzw" and args.bits == 8 and not args.no_prepared_step
+                        and not (args.max_entries or args.lmax or args.seg_cols or args.layers))
+    traffic = None
+    if default_workload and PROFILED_TRAFFIC["csrc_sha16"] == csrc_digest():
+        traffic = round((PROFILED_TRAFFIC["fetch_per_stored_byte"] * wl.stored_bytes + PROFILED_TRAFFIC["write_bytes_per_step"]) / n_launches)
+    gbps = wl.algorithmic_bytes / wall_ms / 1e6
     result = {
         "metric": "compressed-weight HBM GB/s of the fused decode+dequant+GEMV decode-step sweep (% of 8 TB/s peak in "
                   "roofline.frac; tokens/s alongside)",
@@ -432,34 +625,34 @@ def main():
         "dtype": f"bf16 activations x {'int8' if args.bits == 8 else str(args.bits) + '-bit'} weights, fp32 accumulate",
         "data": "synthetic",
         "tokens_per_s": round(args.batch / (wall_ms * 1e-3), 1),
-        "step_ms": spread.get(args.batch),   # one event pair per step, in a pass of its own after the timed region
+        "step_ms": main_run["spread"],   # one event pair per step, in a pass of its own after the timed region
         "config": {
             "workload": f"config {args.config}: {CONFIGS[args.config]['desc']}, batch {args.batch}",
-            "matrices": len(specs), "weights": n_weights, "compressed_bytes": comp_bytes,
-            "bytes_per_weight": round(comp_bytes / n_weights, 4), "weights_per_code": round(n_weights / n_codes, 4),
-            "weights_per_real_code": round(n_weights / sum(i["n_real_codes"] for i in infos), 4),
+            "matrices": len(specs), "weights": wl.n_weights,
+            "value_counts": "algorithmic bytes: the codes of the parse, unit offsets, scales, each distinct dictionary once "
+                            "(the padding codes of the layout are left out; stored_bytes includes them)",
+            "algorithmic_bytes": wl.algorithmic_bytes, "stored_bytes": wl.stored_bytes,
+            "raw_int8_bytes": wl.n_weights, "stored_over_raw_int8": round(wl.stored_bytes / wl.n_weights, 4),
+            "bytes_per_weight": round(wl.algorithmic_bytes / wl.n_weights, 4),
+            "stored_bytes_per_weight": round(wl.stored_bytes / wl.n_weights, 4),
+            "weights_per_code": round(wl.n_weights / wl.n_codes, 4),
+            "weights_per_real_code": round(wl.n_weights / wl.n_real_codes, 4),
+            "padding_frac": round(1 - wl.n_real_codes / wl.n_codes, 4),
+            "GBps_on_stored_bytes": round(wl.stored_bytes / wall_ms / 1e6, 1),
             "dictionary_entries": infos[-1]["n_entries"], "lmax": infos[0]["lmax"], "seg_cols": infos[0]["seg_cols"],
-            "dictionary": args.dictionary, "dictionary_kind": args.dictionary_kind, "bits": args.bits, "packing": "nibbles" if args.pack else "none", "fuse": args.fuse, "prepared_step": not args.no_prepared_step,
+            "dictionary": args.dictionary, "dictionary_kind": args.dictionary_kind, "bits": args.bits,
+            "packing": "nibbles" if args.pack else "none", "fuse": args.fuse, "prepared_step": not args.no_prepared_step,
             "kernel_launches_per_step": n_launches,
             "hip_graph": bool(args.graph),
-            "cache": (f"cold: the steps rotate over {n_copies} copies of the compressed matrices ({n_copies * comp_bytes / 1e6:.0f} MB)" if n_copies > 1
-                      else "cold: one step streams more than the caches hold" if comp_bytes >= 512_000_000
+            "prewarm_ms": args.prewarm_ms, "prewarm_steps": main_run["prewarm_steps"],
+            "cache": (f"cold: the steps rotate over {n_copies} copies of the compressed matrices ({n_copies * wl.stored_bytes / 1e6:.0f} MB)" if n_copies > 1
+                      else "cold: one step streams more than the caches hold" if wl.stored_bytes >= 512_000_000
                       else "cache-resident: the same compressed bytes are read again every step"),
             # activations read and outputs written per step: beside the compressed bytes, not part of `value`
             "x_bytes_per_step": sum(2 * args.batch * s.cols for s in specs),
             "y_bytes_per_step": sum(4 * args.batch * s.rows for s in specs),
         },
-        "roofline": {
-            "bound": "hbm", "kernel": "tq::k_matvec",
-            "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-            "traffic": (round((MEASURED_FETCH_PER_ALGORITHMIC_BYTE * comp_bytes + MEASURED_WRITE_BYTES_PER_STEP) / n_launches)
-                        if profiled else None),
-            "algorithmic_bytes_per_launch": round(comp_bytes / n_launches),
-            "launch_us": round(ev_ms * 1e3 / n_launches, 1),
-            "note": "achieved = algorithmic (compressed) bytes per launch / mean launch duration, from HIP events on the "
-                    "launch stream around the timed steps (launches back to back); traffic = HBM bytes per launch from "
-                    "the FETCH_SIZE/WRITE_SIZE counter runs under profiles/ (null off the profiled workload)",
-        },
+        "roofline": roofline_block(kernel_name(args.batch), wl, ev_ms, n_launches, traffic),
         "other_batches": others,
         "decompress": decompress,
         "gate_up_fused": gate_up,
@@ -471,35 +664,58 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        from oracle import oracle as O
-        t0 = time.perf_counter()
-        sb = 0
-        for i, blob in sorted(sample_blobs.items()):
-            _, x = make_activations(specs[i], args.batch)
-            O.matvec_from_blob(blob, x)                 # oracle: sequential decode, then float64 GEMV
-            sb += infos[i]["compressed_bytes"]
-        dt = time.perf_counter() - t0
-        sw = sum(specs[i].rows * specs[i].cols for i in sample_blobs)
-        result["cpu_baseline"] = {
-            "value": round(sb / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {args.cpu_sample_layers} layers of the sweep ({len(sample_blobs)} matrices, {sw} weights, {dt:.2f} s): decode + "
-                      f"float64 GEMV, batch {args.batch}; whole sweep extrapolates to {dt * n_weights / sw:.1f} s/token",
-            "tokens_per_s_extrapolated": round(args.batch / (dt * n_weights / sw), 4),
-        }
-        # the same sample once more, the matrices (independent of each other) spread over the host's threads
-        n_thr = max(1, min(args.threads, len(sample_blobs)))
-        work = [(blob, make_activations(specs[i], args.batch)[1]) for i, blob in sorted(sample_blobs.items())]
-        t0 = time.perf_counter()
-        with ThreadPoolExecutor(max_workers=n_thr) as pool:
-            list(pool.map(lambda bx: O.matvec_from_blob(*bx), work))
-        dt_all = time.perf_counter() - t0
-        model = next((l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name")), "unknown")
-        result["cpu_baseline"]["all_threads"] = {"value": round(sb / dt_all / 1e9, 3), "unit": "GB/s", "threads": n_thr,
-                                                 "seconds": round(dt_all, 2), "os_cpu_count": os.cpu_count(), "cpu": model}
-    print(json.dumps(result), flush=True)
+        result["cpu_baseline"], result["verified"] = cpu_baseline_and_verification(wl, args, infos, main_run["ys"], expanded, torch)
+    else:
+        result["verified"] = None
+    del expanded, main_run
     for ms in mat_sets:
         for m in ms:
             m.close()
+    wl.mats = []
+    torch.cuda.empty_cache()
+
+    # ---- the same sweep with one dictionary per matrix (what "built greedily from the matrix" says literally)
+    def optional_leg(name, fn):   # a failure in a side leg is reported in the line instead of losing the line
+        try:
+            result[name] = fn()
+        except Exception as e:   # noqa: BLE001
+            result[name] = {"error": f"{type(e).__name__}: {e}"}
+
+    def matrix_dictionary_leg():
+        wm = Workload(tq, specs, args, "matrix", opts)
+        rm = Runner(tq, torch, wm, [wm.mats], args, dev, stream).run(args.batch, args.steps, args.warmup, args.prewarm_ms)
+        out = {
+            "dictionary": "matrix", "ms_per_step": round(rm["wall_ms"], 4), "tokens_per_s": round(args.batch / (rm["wall_ms"] * 1e-3), 1),
+            "GBps": round(wm.algorithmic_bytes / rm["wall_ms"] / 1e6, 1), "bytes_per_weight": round(wm.algorithmic_bytes / wm.n_weights, 4),
+            "step_ms": rm["spread"], "roofline": roofline_block(kernel_name(args.batch), wm, rm["ev_ms"], rm["n_launches"])}
+        del rm
+        wm.close()
+        torch.cuda.empty_cache()
+        return out
+
+    if default_workload and not args.no_matrix_dictionary:
+        optional_leg("dictionary_per_matrix", matrix_dictionary_leg)
+
+    # ---- the stress configuration: config 5 (Student-t weights), batch 16, and the expansion of the whole model
+    def config5_leg():
+        s5 = specs_of(5)
+        w5 = Workload(tq, s5, args, "sequence", opts)
+        r5 = Runner(tq, torch, w5, [w5.mats], args, dev, stream).run(16, max(3, args.steps // 2), args.warmup, args.prewarm_ms)
+        d5, _ = expansion_leg(tq, torch, w5, args, dev, stream)
+        out = {
+            "workload": f"config 5: {CONFIGS[5]['desc']}, batch 16", "ms_per_step": round(r5["wall_ms"], 4),
+            "tokens_per_s": round(16 / (r5["wall_ms"] * 1e-3), 1), "GBps": round(w5.algorithmic_bytes / r5["wall_ms"] / 1e6, 1),
+            "bytes_per_weight": round(w5.algorithmic_bytes / w5.n_weights, 4), "stored_bytes_per_weight": round(w5.stored_bytes / w5.n_weights, 4),
+            "weights_per_real_code": round(w5.n_weights / w5.n_real_codes, 4), "dictionary_entries": w5.infos[-1]["n_entries"],
+            "lmax": w5.infos[0]["lmax"], "step_ms": r5["spread"],
+            "roofline": roofline_block(kernel_name(16), w5, r5["ev_ms"], r5["n_launches"]), "decompress": d5}
+        del r5
+        w5.close()
+        return out
+
+    if default_workload and not args.no_config5:
+        optional_leg("config5", config5_leg)
+    print(json.dumps(result), flush=True)
 
 
 if __name__ == "__main__":
