@@ -219,6 +219,23 @@ int tq_step_get_info(tq_step_handle s, tq_step_info *out);
 int tq_step_destroy(tq_step_handle s);
 
 /*
+ * For callers that cannot allocate device memory where they call the library - code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: tq_matvec_multi for up to TQ_STATIC_MAX_MATRICES matrices with the
+ * job table of a prepared step, so one kernel launch serves them all, but the table lives in a fixed array of
+ * TQ_STATIC_MAX_MATRICES * 104 bytes that is part of the library's device image (each GPU the library runs on holds
+ * it until the process ends) instead of memory a tq_step_create allocates.  The call plans the launches as
+ * tq_step_create does, fills the table through small writer launches on `stream` (ahead of the product launches, on
+ * the same stream; n / 160 of them, rounded up) and launches the products.  It makes no hipMalloc, hipFree or other
+ * allocating HIP call; the planning on the host may use the C++ heap.  n > TQ_STATIC_MAX_MATRICES: TQ_E_UNSUPPORTED.
+ * Arguments, results and asynchrony as for tq_matvec_multi; results are those of a prepared step for the same
+ * matrices and buffers.  All calls on one GPU share the one table, which keeps the entries of the last call: two
+ * calls whose execution overlaps on one GPU (different streams, or a captured graph replayed while another call
+ * runs) race on it and must be ordered by the caller; calls on one stream are ordered by the stream.
+ */
+#define TQ_STATIC_MAX_MATRICES 896
+int tq_matvec_multi_static(int n, const tq_handle *hs, const void *const *xs, void *const *ys, int batch, void *stream);
+
+/*
  * Un-fused form: expand the whole matrix (paper section 4, Listing "Decompressing Model Weights").
  *   out: device, int8 [rows][cols] row-major, fully overwritten, bit-exact quantized weights.
  * Same asynchrony rules as tq_matvec.

@@ -21,6 +21,7 @@ EXPORTS = [
     "tq_matvec_multi", "tq_decompress", "tq_decompress_multi", "tq_get_info", "tq_destroy", "tq_last_error_string",
     "tq_encode_gate_up", "tq_matvec_gate_up", "tq_matvec_gate_up_multi",
     "tq_set_ring_min_bands_per_cu",
+    "tq_matvec_multi_static",
     "tq_step_create", "tq_step_launch", "tq_step_get_info", "tq_step_destroy",
     "tq_listing_build_table", "tq_listing_compress", "tq_listing_create", "tq_listing_decompress", "tq_listing_get_info",
     "tq_listing_destroy",
@@ -101,6 +102,8 @@ def load() -> ctypes.CDLL:
     lib.tq_matvec_gate_up_multi.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
     lib.tq_matvec_multi.restype = ci
     lib.tq_matvec_multi.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
+    lib.tq_matvec_multi_static.restype = ci
+    lib.tq_matvec_multi_static.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
     lib.tq_step_create.restype = ci
     lib.tq_step_create.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, u32, ctypes.POINTER(vp)]
     lib.tq_step_launch.restype = ci
@@ -255,6 +258,16 @@ class MultiCall:
 
 def tq_matvec_multi(handles, x_ptrs, y_ptrs, batch: int, stream: int = 0) -> None:
     MultiCall(handles, x_ptrs, y_ptrs, batch).launch(stream)
+
+
+TQ_STATIC_MAX_MATRICES = 896
+
+
+def tq_matvec_multi_static(handles, x_ptrs, y_ptrs, batch: int, stream: int = 0) -> None:
+    n = len(handles)
+    assert n == len(x_ptrs) == len(y_ptrs) and n >= 1
+    arr = ctypes.c_void_p * n
+    _check(load().tq_matvec_multi_static(n, arr(*handles), arr(*x_ptrs), arr(*y_ptrs), batch, stream))
 
 
 TQ_STEP_GATE_UP = 1

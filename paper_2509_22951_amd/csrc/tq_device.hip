@@ -43,7 +43,43 @@
 
 using namespace tq;
 
+// Job table of tq_matvec_multi_static: device memory that belongs to the library image, so that the call needs no
+// allocation.  Every GPU the library runs on holds its own copy at its own address (looked up once per device, see
+// static_table_of); all calls on a GPU share it.
+constexpr size_t kStaticTableBytes = (size_t)kMaxStep * sizeof(StepEntry);
+static __device__ __align__(256) unsigned char scratch[kStaticTableBytes];
+
 namespace {
+
+// What the table writer needs per job: where the matrix description lives in device memory, and the buffers.
+struct JobRef {
+  const DevMat* m;
+  const uint16_t* x;
+  float* y;
+};
+constexpr int kWriterJobs = 160;   // per launch of the writer (its arguments stay below 4 KB)
+struct TableWrite {
+  StepEntry* table;   // first entry to write
+  int n;
+  JobRef j[kWriterJobs];
+};
+static_assert(sizeof(TableWrite) <= 4096, "kernel arguments");
+
+// Entry t of the table = (description of job t copied from device memory, x, y).  One thread per dword of an entry.
+__global__ __launch_bounds__(64) void k_write_table(TableWrite w) {
+  constexpr int kDescDwords = sizeof(DevMat) / 4;
+  const int t = blockIdx.x, k = threadIdx.x;
+  if (t >= w.n) return;
+  uint32_t* dst = (uint32_t*)(w.table + t);
+  static_assert(offsetof(StepEntry, m) == 0 && sizeof(StepEntry) == sizeof(DevMat) + 16 && sizeof(DevMat) % 8 == 0, "entry layout");
+  if (k < kDescDwords) {
+    dst[k] = ((const uint32_t*)w.j[t].m)[k];
+  } else if (k < kDescDwords + 4) {
+    const uint64_t px = (uint64_t)w.j[t].x, py = (uint64_t)w.j[t].y;
+    const uint32_t tail[4] = {(uint32_t)px, (uint32_t)(px >> 32), (uint32_t)py, (uint32_t)(py >> 32)};
+    dst[k] = tail[k - kDescDwords];
+  }
+}
 
 int hip_fail(const char* what, hipError_t e) {
   set_error(std::string(what) + ": " + hipGetErrorString(e));
@@ -154,6 +190,27 @@ bool dot_kernel_takes(int batch, bool packed, uint32_t dict_words_max, uint32_t 
   uint32_t x_off, slot_off;
   size_t total;
   return plan_matvec_lds(dict_words_max, (batch == 2 && packed ? 2u : 1u) * x_dwords_max, &x_off, &slot_off, &total);
+}
+
+// Address of `scratch` on each device.  In host code the array's name is only a handle for the runtime: the address a
+// kernel can use comes from hipGetSymbolAddress, asked once per device with that device current.
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+StepEntry* g_static_table[kMaxDevices];   // null until looked up
+int static_table_of(int device, StepEntry** out) {   // `device` is the current device
+  if (device < 0 || device >= kMaxDevices) {
+    set_error("device index " + std::to_string(device) + " is beyond what the library keeps a static table for");
+    return TQ_E_UNSUPPORTED;
+  }
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (!g_static_table[device]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return hip_fail("hipGetSymbolAddress(static job table)", e);
+    g_static_table[device] = (StepEntry*)p;
+  }
+  *out = g_static_table[device];
+  return TQ_OK;
 }
 
 // Every kernel of the library that takes its dictionary at LDS address 0.
@@ -273,6 +330,10 @@ static int tq_create_from_encoded_impl(const void* blob, size_t blob_bytes, tq_h
     return TQ_E_UNSUPPORTED;
   }
   if (int rc = prepare_kernels()) return rc;
+  {
+    StepEntry* table = nullptr;   // the static job table of this device, for tq_matvec_multi_static
+    if (int rc = static_table_of(dev, &table)) return rc;
+  }
 
   const uint8_t* src = (const uint8_t*)blob;
   DictCopy* dict = nullptr;
@@ -337,6 +398,7 @@ struct PreparedLaunch {
 struct Recorder {
   std::vector<PreparedLaunch> launches;
   std::vector<StepEntry> entries;
+  std::vector<JobRef> refs;   // the same jobs by the device address of their description (for the table writer)
 };
 
 int fire(const PreparedLaunch& p, hipStream_t stream) {
@@ -371,6 +433,7 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     const tq_matrix* t = hs[i];
     if (rec) {
       rec->entries.push_back(StepEntry{t->m, xs ? (const uint16_t*)xs[i] : nullptr, (float*)ys[i]});
+      rec->refs.push_back(JobRef{t->m_dev, xs ? (const uint16_t*)xs[i] : nullptr, (float*)ys[i]});
     } else {
       a.u.in.j[i].m = t->m_dev;
       if (i < kInlineDescriptions) a.u.in.first[i] = t->m;
@@ -785,6 +848,52 @@ static int tq_destroy_impl(tq_handle h) {
   return TQ_OK;
 }
 
+// tq_matvec_multi with the job table of a prepared step, but in the library's static device array instead of memory
+// allocated for the step: the plan is made as for tq_step_create, small writer launches fill the table on `stream`
+// (the jobs travel in their kernel arguments), and the product launches that follow on the same stream read it.
+static int tq_matvec_multi_static_impl(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {
+  if (n < 1 || !hs || !xs || !ys) {
+    set_error("tq_matvec_multi_static: null argument or n < 1");
+    return TQ_E_INVALID_ARG;
+  }
+  if (n > kMaxStep) {
+    set_error("tq_matvec_multi_static: " + std::to_string(n) + " matrices do not fit the static job table (at most " +
+              std::to_string(kMaxStep) + " per call)");
+    return TQ_E_UNSUPPORTED;
+  }
+  if (int rc = check_call("tq_matvec_multi_static", n, hs, xs, ys, batch)) return rc;
+  StepEntry* table = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    const int dev = hs[0]->device;
+    table = dev >= 0 && dev < kMaxDevices ? g_static_table[dev] : nullptr;   // looked up when the first matrix was created there
+  }
+  if (!table) {
+    set_error("tq_matvec_multi_static: no static table is known for the matrices' device");
+    return TQ_E_HIP;
+  }
+  Recorder rec;
+  if (int rc = launch_all(Op::kMatvec, n, hs, xs, ys, batch, nullptr, false, false, &rec)) return rc;
+  if (rec.refs.size() > (size_t)kMaxStep) {   // (cannot happen: one entry per matrix)
+    set_error("tq_matvec_multi_static: internal: more jobs than matrices");
+    return TQ_E_UNSUPPORTED;
+  }
+  for (size_t first = 0; first < rec.refs.size(); first += kWriterJobs) {
+    TableWrite w;
+    w.table = table + first;
+    w.n = (int)std::min<size_t>(kWriterJobs, rec.refs.size() - first);
+    std::memcpy(w.j, rec.refs.data() + first, (size_t)w.n * sizeof(JobRef));
+    hipLaunchKernelGGL(k_write_table, dim3((unsigned)w.n), dim3(64), 0, (hipStream_t)stream, w);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("tq_matvec_multi_static: table writer launch", e);
+  }
+  for (PreparedLaunch& p : rec.launches) {
+    p.a.table = table + p.table_first;
+    if (int rc = fire(p, (hipStream_t)stream)) return rc;
+  }
+  return TQ_OK;
+}
+
 // The entry points proper: argument checks and work above, behind a wrapper that lets no C++ exception out.
 extern "C" int tq_create_from_encoded(const void* blob, size_t blob_bytes, tq_handle* out) {
   return guarded("tq_create_from_encoded", [&] { return tq_create_from_encoded_impl(blob, blob_bytes, out); });
@@ -828,6 +937,10 @@ extern "C" int tq_destroy(tq_handle h) {
 
 extern "C" int tq_step_destroy(tq_step_handle s) {
   return guarded("tq_step_destroy", [&] { return tq_step_destroy_impl(s); });
+}
+
+extern "C" int tq_matvec_multi_static(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {
+  return guarded("tq_matvec_multi_static", [&] { return tq_matvec_multi_static_impl(n, hs, xs, ys, batch, stream); });
 }
 
 extern "C" int tq_set_ring_min_bands_per_cu(uint32_t bands_per_cu) {
