@@ -49,13 +49,10 @@ static_assert(kRingPiece % kRingStep == 0 && kRingGroup == 4 && kRingStep <= kRi
 // append_chunk for the ring: the complete 8-byte piece goes to its swizzled place; sw8 = 8 * (lane & 15).
 // pos never passes seg_len (pad codes fall off the end), and a piece is complete when pos crosses a multiple of 8.
 __device__ __forceinline__ void append_chunk_ring(uint2 c, uint32_t ring, uint32_t sw8, uint32_t seg_len, uint32_t& pos, uint64_t& carry) {
-  const uint32_t e0 = lds_read16(half_offset_lo(c.x)), e1 = lds_read16(half_offset_hi(c.x));
-  const uint32_t e2 = lds_read16(half_offset_lo(c.y)), e3 = lds_read16(half_offset_hi(c.y));
-  const uint32_t p0 = is_pair_lo(c.x), p1 = is_pair_hi(c.x), p2 = is_pair_lo(c.y), p3 = is_pair_hi(c.y);
-  const uint32_t a01 = e1 << ((p0 << 3) + 8) | e0, n01 = p0 + p1 + 2;   // codes 0, 1: n01 = 2..4 bytes
-  const uint32_t a23 = e3 << ((p2 << 3) + 8) | e2, n23 = p2 + p3 + 2;   // codes 2, 3
-  const uint64_t str = (uint64_t)a23 << (n01 << 3) | a01;               // the 4..8 bytes of the chunk
-  const uint32_t after = min(pos + n01 + n23, seg_len);
+  uint32_t s0, s1, n;
+  chunk_string(c, s0, s1, n);                                           // the 4..8 bytes of the chunk, zero above them
+  const uint64_t str = (uint64_t)s1 << 32 | s0;
+  const uint32_t after = min(pos + n, seg_len);
   const uint32_t sh = (pos & 7u) << 3;
   const uint64_t lo = carry | str << sh, hi = (str >> 1) >> (63 - sh);  // the 16 bytes carry + string; hi is 0 when pos % 8 == 0
   const bool full = (after ^ pos) >= 8;

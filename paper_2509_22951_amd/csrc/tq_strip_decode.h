@@ -66,33 +66,34 @@ __device__ __forceinline__ bf16x8 nib8_to_bf16x8(uint32_t d) {
   return __builtin_bit_cast(bf16x8, make_uint4(r[0], r[1], r[2], r[3]));
 }
 
-// Append the runs of one chunk (4 codes) to the lane's strip.  The 4 entries (1 or 2 bytes each; the length follows
-// from the code) are packed into one string of up to 8 bytes in registers, joined to the bytes the lane has not
-// written yet (`carry`: the pos % 8 bytes after its last complete 8-byte piece), and one aligned 8-byte piece goes to
-// LDS when it is complete: one store per chunk instead of one per byte.  pos = bytes of the segment appended so far.
-// Pad codes (entry 0, counted as 2 bytes by the code test) only follow a complete segment: the clamp against the
-// bytes still missing drops them.
-typedef __attribute__((address_space(3))) uint64_t lds_u64;
-__device__ __forceinline__ void append_chunk(uint2 c, uint32_t strip, uint32_t seg_len, uint32_t& pos, uint64_t& carry) {
+// The runs of one chunk (4 codes) as one string of 4..8 bytes in (s0, s1), n = its length.  The 4 entries (1 or 2 bytes
+// each; the length follows from the code; the byte after a single is zero in the dictionary image) are joined with
+// byte-granular funnel shifts.  Bytes of the string past n are not zero in general.
+__device__ __forceinline__ void chunk_string(uint2 c, uint32_t& s0, uint32_t& s1, uint32_t& n) {
   const uint32_t e0 = lds_read16(half_offset_lo(c.x)), e1 = lds_read16(half_offset_hi(c.x));
   const uint32_t e2 = lds_read16(half_offset_lo(c.y)), e3 = lds_read16(half_offset_hi(c.y));
   const uint32_t p0 = is_pair_lo(c.x), p1 = is_pair_hi(c.x), p2 = is_pair_lo(c.y), p3 = is_pair_hi(c.y);
-  const uint32_t a01 = e1 << ((p0 << 3) + 8) | e0, n01 = p0 + p1 + 2;   // codes 0, 1: n01 = 2..4 bytes
-  const uint32_t a23 = e3 << ((p2 << 3) + 8) | e2, n23 = p2 + p3 + 2;   // codes 2, 3
-  const uint32_t t = (n01 << 3) - 8;                                    // 8, 16, 24: a23 starts 8 + t bits into the string
-  const uint32_t s0 = (a23 << t) << 8 | a01, s1 = a23 >> (24 - t);
-  const uint64_t str = (uint64_t)s1 << 32 | s0;
-  const uint32_t n = min(n01 + n23, seg_len - pos);
-  const uint32_t f = pos & 7u, sh = f << 3;
-  const uint64_t lo = carry | str << sh, hi = (str >> 1) >> (63 - sh);  // the 16 bytes carry + string; hi is 0 for f == 0
-  const bool full = f + n >= 8;
-  if (full) *(lds_u64*)(size_t)(strip + (pos & ~7u)) = lo;
-  carry = full ? hi : lo;
-  pos += n;
+  const uint32_t a01 = e1 << ((p0 << 3) + 8) | e0, q01 = p0 + p1;   // codes 0, 1: 2 + q01 bytes
+  const uint32_t a23 = e3 << ((p2 << 3) + 8) | e2, q23 = p2 + p3;   // codes 2, 3
+  const uint32_t k = 2u - q01;                                      // bytes of a23 that still fit the first dword: 0..2
+  s0 = a01 | __builtin_amdgcn_alignbyte(a23, 0u, k);               // a23 << 8 (4 - k), nothing for k == 0
+  s1 = __builtin_amdgcn_alignbyte(0u, a23, k);                      // a23 >> 8 k
+  n = q01 + q23 + 4u;
 }
-// The bytes after the last complete 8-byte piece (a segment whose length is not a multiple of 8).
-__device__ __forceinline__ void flush_carry(uint32_t strip, uint32_t pos, uint64_t carry) {
-  if (pos & 7u) *(lds_u64*)(size_t)(strip + (pos & ~7u)) = carry;
+
+typedef uint64_t lds_u64_any __attribute__((address_space(3), aligned(1)));
+typedef __attribute__((address_space(3))) uint64_t lds_u64;
+
+// Append the runs of one chunk to the lane's strip: the string goes to LDS as it is, with one 8-byte store at the
+// byte the lane has reached (LDS stores need no alignment on this target); what it writes past its own n bytes is
+// overwritten by the chunks that follow, or falls into the 8 spare bytes every strip has after its segment.
+// wpos = LDS address of the next byte of the segment, limit = address of the segment's end.  Pad codes (entry 0,
+// counted as 2 bytes by the code test) only follow a complete segment: the clamp keeps the lane at its end.
+__device__ __forceinline__ void append_chunk(uint2 c, uint32_t limit, uint32_t& wpos) {
+  uint32_t s0, s1, n;
+  chunk_string(c, s0, s1, n);
+  *(lds_u64_any*)(size_t)wpos = (uint64_t)s1 << 32 | s0;
+  wpos = min(wpos + n, limit);
 }
 
 // Decode the units [u0, u1) of a matrix, one after the other, into the strips of this wavefront's tile and call
@@ -144,31 +145,28 @@ __device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0,
     if (row < m.rows && panel < n_panels) len = min(m.seg_cols, m.cols - panel * m.seg_cols);
     return len;
   };
-  uint32_t pos = 0, seg_len = segment_length();
-  uint64_t carry = 0;
+  uint32_t wpos = my_strip, limit = my_strip + segment_length();   // next byte of the lane's segment in its strip, and its end
   auto decode_piece = [&](const uint2 (&cw)[kPiece], uint32_t n, bool ends) {
     if (ends) before_last_piece(band, quad);
     if (n == kPiece) {   // whole pieces as straight-line code: the dictionary reads of later chunks overlap the packing of earlier ones
 #pragma unroll
-      for (int k = 0; k < kPiece; ++k) append_chunk(cw[k], my_strip, seg_len, pos, carry);
+      for (int k = 0; k < kPiece; ++k) append_chunk(cw[k], limit, wpos);
     } else if (n == kPiece - 1) {
 #pragma unroll
-      for (int k = 0; k < kPiece - 1; ++k) append_chunk(cw[k], my_strip, seg_len, pos, carry);
+      for (int k = 0; k < kPiece - 1; ++k) append_chunk(cw[k], limit, wpos);
     } else {
 #pragma unroll
       for (int k = 0; k < kPiece; ++k)
-        if ((uint32_t)k < n) append_chunk(cw[k], my_strip, seg_len, pos, carry);
+        if ((uint32_t)k < n) append_chunk(cw[k], limit, wpos);
     }
     if (ends) {
-      flush_carry(my_strip, pos, carry);
       on_unit(band, quad);
       if (++quad == nq) {
         quad = 0;
         ++band;
       }
-      pos = 0;
-      carry = 0;
-      seg_len = segment_length();
+      wpos = my_strip;
+      limit = my_strip + segment_length();
     }
   };
   uint2 cwa[kPiece], cwb[kPiece];
