@@ -34,7 +34,7 @@ extern "C" {
 /* Dictionary entries (incl. the 256 single bytes) that fit the 120 KB of LDS the kernels give the dictionary:
  * an entry holds at most 2 weights and takes one 32-bit word there (two bf16 values); one more word is the pad entry. */
 #define TQ_MAX_ENTRIES_DEVICE 30719
-#define TQ_MAX_LMAX 2
+#define TQ_MAX_LMAX 4
 #define TQ_DEFAULT_LMAX 2
 #define TQ_DEFAULT_SEG_COLS 256
 

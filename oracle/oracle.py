@@ -10,6 +10,7 @@ Everything here is the plain definition (or the paper's algorithm step by step) 
 * ``serialize``       the fixed byte order in which a matrix is handed to the codec (format rule, no maths).
 * ``lzw_encode``      LZW as described in the paper's Background, "Compression" (C, see tq_oracle.c).
 * ``frequency_dictionary``  entries picked by frequency, as section 4 picks its table (runs of 2; numpy).
+* ``sort_code_space`` the codes renumbered so that a code's place tells its run length (format rule, a permutation).
 * ``lzw_decode``      table lookup decompression, section 4: reproduces the quantized bytes exactly.
 * ``gemv_f64``        y = diag(s) Q x in float64, the definition the fused kernel must reach.
 * ``build_blob`` / ``parse_blob``  writer and reader of the container format, written from the format
@@ -37,7 +38,10 @@ CHUNK_CODES = 4     # codes per lane and chunk
 CHUNK_WORDS = 64 * CHUNK_CODES
 DEFAULT_SEG_COLS = 256
 LCAP = 16           # must equal TQO_LCAP in tq_oracle.c
-MAGIC = b"TQMOEv2\0"
+MAGIC = b"TQMOEv3\0"
+UNIT_BUDGET = 30716  # dictionary storage the device path offers when runs may be longer than 2 bytes: units of one
+                     # 32-bit word of the product kernel's LDS image, 1 per entry of up to 2 bytes, 2 per longer entry,
+                     # 4 more kept for the padding code's entry and alignment (120 KB in all)
 HEADER_BYTES = 256
 SECTION_ALIGN = 256
 
@@ -64,7 +68,7 @@ def _lib():
         lib = ctypes.CDLL(build_oracle_lib())
         ll, vp, ci = ctypes.c_longlong, ctypes.c_void_p, ctypes.c_int
         lib.tqo_lzw_encode.restype = ll
-        lib.tqo_lzw_encode.argtypes = [vp, ll, vp, ll, ci, ci, ci, vp, vp, vp, vp, ctypes.POINTER(ci)]
+        lib.tqo_lzw_encode.argtypes = [vp, ll, vp, ll, ci, ci, ll, ci, vp, vp, vp, vp, ctypes.POINTER(ci)]
         lib.tqo_lzw_decode.restype = ll
         lib.tqo_lzw_decode.argtypes = [vp, vp, vp, ll, vp, vp, ci, ci, vp]
         lib.tqo_gemv_f64.restype = None
@@ -167,10 +171,13 @@ class Dictionary:
         return bytes(self.ent_bytes[e, : self.ent_len[e]])
 
 
-def lzw_encode(S: np.ndarray, seg_len, max_entries: int = 30719, lmax: int = 2, carry: "Dictionary | None" = None):
+def lzw_encode(S: np.ndarray, seg_len, max_entries: int = 30719, lmax: int = 2, carry: "Dictionary | None" = None,
+               unit_budget: int = 0):
     """LZW over the segments of S (a match never crosses a segment end).  `seg_len` is the array of segment
     lengths, or one integer = equal-length segments (the last may be short).  `carry` = the dictionary a previous
-    call returned: the parse starts with those entries instead of the 256 singles alone.
+    call returned: the parse starts with those entries instead of the 256 singles alone.  `unit_budget` (0 = none):
+    an entry is added only while the dictionary stays within that many units (1 per entry of up to 2 bytes, 2 per
+    longer one).
     Returns (codes uint16 [n_codes], seg_ncodes uint32 [n_segs], Dictionary)."""
     S = np.ascontiguousarray(S, dtype=np.uint8)
     n = int(S.size)
@@ -192,11 +199,26 @@ def lzw_encode(S: np.ndarray, seg_len, max_entries: int = 30719, lmax: int = 2, 
         eb[:n_init] = carry.ent_bytes
         el[:n_init] = carry.ent_len
     ne = ctypes.c_int(0)
-    nc = _lib().tqo_lzw_encode(_ptr(S), n, _ptr(seg_len), n_segs, max_entries, lmax, n_init, _ptr(codes), _ptr(snc),
-                               _ptr(eb), _ptr(el), ctypes.byref(ne))
+    nc = _lib().tqo_lzw_encode(_ptr(S), n, _ptr(seg_len), n_segs, max_entries, lmax, unit_budget, n_init, _ptr(codes),
+                               _ptr(snc), _ptr(eb), _ptr(el), ctypes.byref(ne))
     if nc < 0:
         raise ValueError("tqo_lzw_encode: bad arguments")
     return codes[:nc].copy(), snc[:n_segs].copy(), Dictionary(eb[: ne.value].copy(), el[: ne.value].copy())
+
+
+def sort_code_space(codes: np.ndarray, d: Dictionary):
+    """Renumber the codes so that the entries come in order of run length (all 1-byte entries, then the 2-byte ones,
+    ...), entries of equal length keeping the order LZW created them in: a code's place in the code space then tells its
+    length.  The single bytes keep code == byte.  Returns (renumbered codes, reordered dictionary, class_end) with
+    class_end[k] = number of entries of at most k + 1 bytes, k = 0..3 (runs are at most 4 bytes here).
+    LZW adds a run only after the run it extends, so every entry still follows the entry it extends."""
+    assert int(d.ent_len.max()) <= 4
+    order = np.argsort(d.ent_len, kind="stable")           # order[new] = old
+    new_of_old = np.empty(order.size, np.int64)
+    new_of_old[order] = np.arange(order.size)
+    sorted_len = d.ent_len[order]
+    class_end = np.array([int((sorted_len <= k + 1).sum()) for k in range(4)], np.uint32)
+    return new_of_old[codes].astype(np.uint16), Dictionary(d.ent_bytes[order].copy(), sorted_len.copy()), class_end
 
 
 def interleave(codes: np.ndarray, seg_ncodes: np.ndarray, pad_code: int):
@@ -290,6 +312,7 @@ class Encoded:
     stream: np.ndarray      # uint16, interleaved and padded
     uoff: np.ndarray        # uint32 [n_units + 1], in chunks
     n_real_codes: int
+    class_end: np.ndarray   # uint32 [4]: entries of at most 1, 2, 3, 4 bytes (the code space is sorted by run length)
     packing: int = 0        # 1: Q holds two 4-bit values per byte (pack_nibbles), the weight matrix is rows x 2 cols
 
     @property
@@ -349,7 +372,9 @@ def encode_quantized(Q: np.ndarray, scales: np.ndarray, max_entries: int = 30719
                      seg_cols: int = DEFAULT_SEG_COLS, carry: "Dictionary | None" = None, dictionary: str = "lzw") -> Encoded:
     """dictionary "lzw": LZW growth with freeze (the paper's Background).  "frequency": the dictionary is fixed before
     the parse - the carried one if given, else frequency_dictionary of this matrix - and the parse is the same greedy
-    longest match."""
+    longest match.  Runs are at most lmax <= 4 bytes; beyond 2 the dictionary also has to stay within UNIT_BUDGET."""
+    assert 1 <= lmax <= 4
+    budget = UNIT_BUDGET if lmax > 2 else 0
     rows, cols = Q.shape
     S, seg_len = serialize(Q, seg_cols)
     if dictionary == "frequency":
@@ -358,10 +383,11 @@ def encode_quantized(Q: np.ndarray, scales: np.ndarray, max_entries: int = 30719
         assert d.n_entries == fixed.n_entries
     else:
         assert dictionary == "lzw"
-        codes, snc, d = lzw_encode(S, seg_len, max_entries, lmax, carry)
+        codes, snc, d = lzw_encode(S, seg_len, max_entries, lmax, carry, budget)
+    codes, d, class_end = sort_code_space(codes, d)
     stream, uoff = interleave(codes, snc, d.n_entries)
     return Encoded(rows, cols, seg_cols, lmax, max_entries, Q, np.asarray(scales, np.float32), d, stream, uoff,
-                   int(codes.size))
+                   int(codes.size), class_end)
 
 
 def encode_matrix(W: np.ndarray, max_entries: int = 30719, lmax: int = 2, seg_cols: "int | None" = None,
@@ -381,11 +407,12 @@ def encode_matrix(W: np.ndarray, max_entries: int = 30719, lmax: int = 2, seg_co
 
 
 def dict_slots(d: Dictionary) -> np.ndarray:
-    """Container dictionary words: bytes 0..2 = run (unused bytes zero), byte 3 = run length in bits (8, 16
-    or 24); one extra all-zero word at index n_entries is the pad code's entry (length 0).  Needs lmax <= 3."""
-    assert int(d.ent_len.max()) <= 3
+    """Container dictionary words: the run's bytes, first byte lowest, unused bytes zero (the run's length follows from
+    the code's place in the sorted code space); one extra all-zero word at index n_entries is the pad code's entry.
+    Needs lmax <= 4."""
+    assert int(d.ent_len.max()) <= 4
     eb = d.ent_bytes.astype(np.uint32)
-    w = eb[:, 0] | (eb[:, 1] << 8) | (eb[:, 2] << 16) | ((8 * d.ent_len.astype(np.uint32)) << 24)
+    w = eb[:, 0] | (eb[:, 1] << 8) | (eb[:, 2] << 16) | (eb[:, 3] << 24)
     return np.concatenate([w, np.zeros(1, np.uint32)]).astype(np.uint32)
 
 
@@ -395,8 +422,8 @@ def _align(n: int, a: int = SECTION_ALIGN) -> int:
 
 # magic, version, header_bytes | rows, cols | seg_cols, unit_rows, unit_panels, chunk_codes | n_bands, n_panels,
 # n_quads | n_entries, lmax, max_entries, pad_code, packing | n_units, n_chunks, n_real_codes |
-# (offset, size) of dictionary, unit offsets, codes, scales | total
-_HDR = struct.Struct("<8sII" "II" "IIII" "III" "IIIII" "QQQ" "QQ" "QQ" "QQ" "QQ" "Q")
+# (offset, size) of dictionary, unit offsets, codes, scales | total | class_end[4]
+_HDR = struct.Struct("<8sII" "II" "IIII" "III" "IIIII" "QQQ" "QQ" "QQ" "QQ" "QQ" "Q" "IIII")
 
 
 def build_blob(e: Encoded) -> bytes:
@@ -414,10 +441,11 @@ def build_blob(e: Encoded) -> bytes:
         offs.append(pos)
         pos = _align(pos + len(b))
     total = pos
-    hdr = _HDR.pack(MAGIC, 2, HEADER_BYTES, e.rows, e.cols, e.seg_cols, UNIT_ROWS, UNIT_PANELS, CHUNK_CODES,
+    hdr = _HDR.pack(MAGIC, 3, HEADER_BYTES, e.rows, e.cols, e.seg_cols, UNIT_ROWS, UNIT_PANELS, CHUNK_CODES,
                     n_bands, n_panels, n_quads, e.dictionary.n_entries, e.lmax, e.max_entries, e.pad_code, e.packing,
                     n_units, n_chunks, e.n_real_codes,
-                    offs[0], len(sec[0]), offs[1], len(sec[1]), offs[2], len(sec[2]), offs[3], len(sec[3]), total)
+                    offs[0], len(sec[0]), offs[1], len(sec[1]), offs[2], len(sec[2]), offs[3], len(sec[3]), total,
+                    *[int(c) for c in e.class_end])
     out = bytearray(total)
     out[: len(hdr)] = hdr
     for o, b in zip(offs, sec):
@@ -428,8 +456,8 @@ def build_blob(e: Encoded) -> bytes:
 def parse_blob(blob: bytes) -> dict:
     (magic, version, hbytes, rows, cols, seg_cols, ur, up, cc, n_bands, n_panels, n_quads, n_entries, lmax,
      max_entries, pad_code, packing, n_units, n_chunks, n_real, o_d, b_d, o_u, b_u, o_c, b_c, o_s, b_s,
-     total) = _HDR.unpack_from(blob, 0)
-    assert magic == MAGIC and version == 2 and hbytes == HEADER_BYTES
+     total, ce0, ce1, ce2, ce3) = _HDR.unpack_from(blob, 0)
+    assert magic == MAGIC and version == 3 and hbytes == HEADER_BYTES
     assert (ur, up, cc) == (UNIT_ROWS, UNIT_PANELS, CHUNK_CODES)
     assert (n_bands, n_panels, n_quads) == geometry(rows, cols, seg_cols) and n_units == n_bands * n_quads
     assert total == len(blob) and pad_code == n_entries and packing in (0, 1)
@@ -440,15 +468,18 @@ def parse_blob(blob: bytes) -> dict:
     scales = buf[o_s: o_s + b_s].view(np.float32)
     assert slots.size == n_entries + 1 and uoff.size == n_units + 1 and stream.size == n_chunks * CHUNK_WORDS
     assert scales.size == n_bands * UNIT_ROWS and int(uoff[-1]) == n_chunks
-    assert np.all((slots[:n_entries] >> 24) % 8 == 0)
-    el = ((slots[:n_entries] >> 24) // 8).astype(np.uint8)
+    class_end = np.array([ce0, ce1, ce2, ce3], np.uint32)
+    assert ce0 == 256 and ce0 <= ce1 <= ce2 <= ce3 == n_entries and 1 <= lmax <= 4 and class_end[lmax - 1] == n_entries
+    code = np.arange(n_entries)
+    el = (1 + (code >= ce0) + (code >= ce1) + (code >= ce2)).astype(np.uint8)      # the run length follows from the code
     eb = np.zeros((n_entries, LCAP), np.uint8)
-    for k in range(3):
+    for k in range(4):
         eb[:, k] = (slots[:n_entries] >> (8 * k)) & 0xFF
+    assert not np.any(eb[np.arange(LCAP)[None, :] >= el[:, None]])                   # nothing past an entry's length
     return dict(rows=rows, cols=cols, seg_cols=seg_cols, n_bands=n_bands, n_panels=n_panels, n_quads=n_quads,
                 n_entries=n_entries, lmax=lmax, max_entries=max_entries, pad_code=pad_code, packing=packing, n_units=n_units,
                 n_chunks=n_chunks, n_codes=n_chunks * CHUNK_WORDS, n_real_codes=n_real,
-                dictionary=Dictionary(eb, el), slots=slots, uoff=uoff, stream=stream, scales=scales,
+                dictionary=Dictionary(eb, el), class_end=class_end, slots=slots, uoff=uoff, stream=stream, scales=scales,
                 compressed_bytes=int(b_d + b_u + b_c + b_s), stream_bytes=int(b_c))
 
 

@@ -6,10 +6,13 @@
  *   tqo_lzw_encode  - the LZW scheme of the paper's Background, section "Compression": start from
  *                     the 256 single-byte strings, repeatedly take the longest string already in the
  *                     dictionary, output its code, and add that string plus the following byte as a
- *                     new entry.  Two bounded-resource rules are added (the paper gives none):
+ *                     new entry.  Bounded-resource rules are added (the paper gives none):
  *                     entries stop being added once `max_entries` exist (the dictionary is then
- *                     frozen, never reset), and a match is at most `lmax` bytes and never crosses a
- *                     restart boundary (the input is a sequence of segments of given lengths).
+ *                     frozen, never reset); a match is at most `lmax` bytes and never crosses a
+ *                     restart boundary (the input is a sequence of segments of given lengths); and,
+ *                     when a unit budget is given, an entry is added only while the dictionary's
+ *                     storage stays inside it, an entry of up to 2 bytes costing 1 unit and a longer
+ *                     one 2 (an entry that does not fit is skipped; the parse goes on unchanged).
  *   tqo_lzw_decode  - the decompression step of section 4 ("8-bit Quantization Compression"): each
  *                     codeword is replaced by its table sequence, reproducing the input exactly.
  *                     There is no escape/raw branch because the single bytes are always entries.
@@ -24,6 +27,7 @@
 
 /*
  * in:  S[n] bytes = n_segs segments back to back, segment g has seg_len[g] bytes (may be 0)
+ *      unit_budget: 0 for none, else the most units the dictionary may take (entries of 1..2 bytes: 1 unit each, longer: 2)
  *      n_init: 0 to start from the 256 single bytes, or the number of entries (>= 256) already present in
  *      ent_bytes / ent_len: the dictionary a previous call left behind, so that one LZW dictionary runs over a
  *      sequence of inputs (section 4 of the paper builds its table over all parameters of the model)
@@ -32,8 +36,8 @@
  * returns number of codes, or -1 on bad arguments / allocation failure.
  */
 long long tqo_lzw_encode(const uint8_t *S, long long n, const uint32_t *seg_len, long long n_segs, int max_entries,
-                         int lmax, int n_init, uint16_t *codes, uint32_t *seg_ncodes, uint8_t *ent_bytes,
-                         uint8_t *ent_len, int *n_entries_out) {
+                         int lmax, long long unit_budget, int n_init, uint16_t *codes, uint32_t *seg_ncodes,
+                         uint8_t *ent_bytes, uint8_t *ent_len, int *n_entries_out) {
   if (max_entries < 256 || max_entries > 65536 || lmax < 1 || lmax > TQO_LCAP || n_segs < 0) return -1;
   if (n_init != 0 && (n_init < 256 || n_init > max_entries)) return -1;
   long long total = 0;
@@ -44,6 +48,7 @@ long long tqo_lzw_encode(const uint8_t *S, long long n, const uint32_t *seg_len,
   if (!child) return -1;
   for (size_t i = 0; i < (size_t)max_entries * 256; ++i) child[i] = -1;
   int n_entries = 256;
+  long long units = 256; /* the single bytes */
   for (int b = 0; b < 256; ++b) {
     ent_len[b] = 1;
     ent_bytes[(size_t)b * TQO_LCAP] = (uint8_t)b;
@@ -56,6 +61,7 @@ long long tqo_lzw_encode(const uint8_t *S, long long n, const uint32_t *seg_len,
     if (par < 0 || child[(size_t)par * 256 + ent_bytes[(size_t)e * TQO_LCAP + len - 1]] >= 0) { free(child); return -1; }
     child[(size_t)par * 256 + ent_bytes[(size_t)e * TQO_LCAP + len - 1]] = e;
     n_entries = e + 1;
+    units += len <= 2 ? 1 : 2;
   }
   long long n_codes = 0;
   long long gs = 0;
@@ -74,9 +80,11 @@ long long tqo_lzw_encode(const uint8_t *S, long long n, const uint32_t *seg_len,
       }
       codes[n_codes++] = (uint16_t)e;
       ++emitted;
-      if (n_entries < max_entries && m < lmax && i + m < ge) {
+      int cost = m + 1 <= 2 ? 1 : 2; /* units the new entry (m + 1 bytes) would take */
+      if (n_entries < max_entries && m < lmax && i + m < ge && (unit_budget <= 0 || units + cost <= unit_budget)) {
         /* by construction (entry e, next byte) is not in the dictionary yet */
         int ne = n_entries++;
+        units += cost;
         child[(size_t)e * 256 + S[i + m]] = ne;
         memcpy(ent_bytes + (size_t)ne * TQO_LCAP, ent_bytes + (size_t)e * TQO_LCAP, (size_t)m);
         ent_bytes[(size_t)ne * TQO_LCAP + m] = S[i + m];

@@ -10,7 +10,7 @@ import numpy as np
 
 TQ_MAX_BATCH = 16
 TQ_MAX_ENTRIES_DEVICE = 30719
-TQ_MAX_LMAX = 2
+TQ_MAX_LMAX = 4
 TQ_DEFAULT_SEG_COLS = 256
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

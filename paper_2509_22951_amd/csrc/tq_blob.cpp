@@ -60,15 +60,17 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* fa
   const uint32_t* uoff = (const uint32_t*)(base + h.off_uoff);
   const uint16_t* codes = (const uint16_t*)(base + h.off_codes);
 
-  // Dictionary: codes 0..255 are the single bytes; every entry has length 1..lmax and zero bytes past its length;
-  // the pad entry is all zero (length 0).
+  // Dictionary: codes 0..255 are the single bytes; the code space is sorted by run length (class_end), an entry's word
+  // holds exactly as many bytes as its place says (zero above them); the pad entry is all zero; the entries fit the
+  // device's dictionary storage.  The kernels take a run's length from the code alone, never from the entry.
+  if (h.class_end[0] != 256 || h.class_end[1] < h.class_end[0] || h.class_end[2] < h.class_end[1] || h.class_end[3] < h.class_end[2] ||
+      h.class_end[3] != h.n_entries || h.class_end[h.lmax - 1] != h.n_entries)
+    return bad("code space classes");
+  if (h.lmax > 2 && (uint64_t)h.class_end[1] + 2ull * (h.n_entries - h.class_end[1]) > kUnitBudget) return bad("dictionary exceeds the unit budget");
   for (uint32_t e = 0; e < h.n_entries; ++e) {
-    uint32_t w = slot[e], bits = w >> 24, len = bits / 8;   // the top byte holds the run length in bits
-    if (bits % 8 || len < 1 || len > h.lmax) return bad("dictionary entry length");
-    if (len < 3 && (w & 0xFFFFFFu) >> (8 * len)) return bad("dictionary entry has bytes past its length");
-    if (e < 256 && w != (e | 8u << 24)) return bad("codes 0..255 must be the single bytes");
-    // the kernels take a run's length from its code alone (1 for codes below 256, 2 from there on), never from the entry
-    if (e >= 256 && len != 2) return bad("codes from 256 on must be runs of 2 bytes");
+    const uint32_t w = slot[e], len = run_length(h, e);
+    if (len < 4 && w >> (8 * len)) return bad("dictionary entry has bytes past its length");
+    if (e < 256 && w != e) return bad("codes 0..255 must be the single bytes");
   }
   if (slot[h.n_entries] != 0) return bad("pad entry");
 
@@ -82,6 +84,7 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* fa
   std::atomic<uint32_t> overrun(0), spread(0);
   n_threads = std::max(1u, std::min(n_threads, 16u));
   n_threads = (unsigned)std::min<uint64_t>(n_threads, n_units);
+  const uint32_t pad_advance = h.lmax > 2 ? 4u : 2u;   // columns a pad code moves a lane's activation index in the product kernel
   auto work = [&](uint64_t ub, uint64_t ue) {
     uint64_t real = 0;
     uint32_t over = 0, wide = 0;
@@ -101,7 +104,7 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* fa
           if (c > h.n_entries) { ok = false; break; }
           if (c == h.n_entries) { ++pads; continue; }
           if (pads) { ok = false; break; }   // a real code after a pad
-          sum += slot[c] >> 27;   // bits / 8
+          sum += run_length(h, c);
           if (k % kChunkCodes == kChunkCodes - 1 && sum < want) {   // a whole chunk taken, segment not complete
             reach_lo[k / kChunkCodes] = std::min(reach_lo[k / kChunkCodes], sum);
             reach_hi[k / kChunkCodes] = std::max(reach_hi[k / kChunkCodes], sum);
@@ -109,7 +112,7 @@ int validate_blob(const void* blob, size_t bytes, Header* hdr_out, BlobFacts* fa
         }
         if (sum != want) ok = false;
         real += steps - pads;
-        over = std::max(over, want + 2 * pads);
+        over = std::max(over, want + pad_advance * pads);
       }
       for (size_t k = 0; ok && k < reach_lo.size(); ++k)
         if (reach_hi[k] > reach_lo[k] && reach_lo[k] != UINT32_MAX) wide = std::max(wide, reach_hi[k] - reach_lo[k]);

@@ -96,6 +96,9 @@ struct DictCopy {
   uint32_t* dev_bf16;   // (bf16(b0), bf16(b1)) per entry; a single-byte entry has a zero second weight, the pad entry two.
                         // Packed 4-bit weights: the four nibbles of (b0, b1) as fp8 e4m3, in column order.
   uint32_t packing;
+  uint32_t long_runs, class2, class3;   // containers with runs of 3 and 4 bytes: dev and dev_bf16 are slot images (long_slot)
+  uint32_t image_bytes;                 // long_runs: size of the byte image at dev
+  uint32_t dict_words_bf16;             // dwords of the image at dev_bf16 (a multiple of 4)
   int refs;
 };
 
@@ -119,10 +122,13 @@ uint32_t nibble_to_fp8_bits(uint32_t nibble) {
 std::mutex g_dict_mutex;
 std::vector<DictCopy*> g_dicts;
 
-int acquire_dictionary(int device, const uint32_t* words, uint32_t n_words, uint32_t n_words_pad, uint32_t packing, DictCopy** out) {
+// words: the container's dictionary section (n_words = entries + the pad entry).  hdr tells the code space classes.
+int acquire_dictionary(int device, const uint32_t* words, uint32_t n_words, const Header& hdr, DictCopy** out) {
+  const uint32_t packing = hdr.packing, long_runs = hdr.lmax > 2 ? 1u : 0u, class2 = hdr.class_end[1], class3 = hdr.class_end[2];
   std::lock_guard<std::mutex> lock(g_dict_mutex);
   for (DictCopy* d : g_dicts)
-    if (d->device == device && d->packing == packing && d->words.size() == n_words && std::memcmp(d->words.data(), words, (size_t)n_words * 4) == 0) {
+    if (d->device == device && d->packing == packing && d->long_runs == long_runs && d->class2 == class2 && d->class3 == class3 &&
+        d->words.size() == n_words && std::memcmp(d->words.data(), words, (size_t)n_words * 4) == 0) {
       ++d->refs;
       *out = d;
       return TQ_OK;
@@ -136,27 +142,59 @@ int acquire_dictionary(int device, const uint32_t* words, uint32_t n_words, uint
   d->words.assign(words, words + n_words);
   d->refs = 1;
   d->packing = packing;
+  d->long_runs = long_runs;
+  d->class2 = class2;
+  d->class3 = class3;
+  d->image_bytes = 0;
   d->dev = d->dev_bf16 = nullptr;
-  // bytes past an entry's length are zero in the container, so the conversion needs no length test
-  std::vector<uint32_t> pairs(n_words_pad, 0u);
-  for (uint32_t i = 0; i < n_words; ++i) {
-    if (packing) {
-      for (uint32_t k = 0; k < 4; ++k) pairs[i] |= nibble_to_fp8_bits(words[i] >> (4 * k) & 15u) << (8 * k);
-    } else {
-      pairs[i] = i8_to_bf16_bits(words[i] & 0xFFu) | i8_to_bf16_bits(words[i] >> 8 & 0xFFu) << 16;
+  // bytes past an entry's length are zero in the container, so the conversions need no length test
+  std::vector<uint32_t> first, second;   // what dev and dev_bf16 will hold
+  if (!long_runs) {
+    // dev: the container words (the kernels take the low 16 bits); dev_bf16: one dword per entry
+    const uint32_t n_pad = (uint32_t)round_up(n_words, 4);
+    first.assign(n_pad, 0u);
+    second.assign(n_pad, 0u);
+    for (uint32_t i = 0; i < n_words; ++i) {
+      first[i] = words[i];
+      if (packing) {
+        for (uint32_t k = 0; k < 4; ++k) second[i] |= nibble_to_fp8_bits(words[i] >> (4 * k) & 15u) << (8 * k);
+      } else {
+        second[i] = i8_to_bf16_bits(words[i] & 0xFFu) | i8_to_bf16_bits(words[i] >> 8 & 0xFFu) << 16;
+      }
     }
+  } else {
+    // Slot images: entry e sits at slot e + max(e - even(class2), 0); an entry below class2 takes one slot, the others
+    // (the pad entry among them) two, starting on an even slot.  dev: 2 bytes per slot (the run's bytes as they are);
+    // dev_bf16: one dword per slot (two bf16 weights).
+    const uint32_t even = class2 & ~1u;
+    auto slot_of = [&](uint32_t e) { return e + (e > even ? e - even : 0u); };
+    const uint32_t n_slots = slot_of(n_words - 1) + 2;
+    std::vector<uint16_t> bytes_img(round_up(n_slots, 8), 0);
+    second.assign(round_up(n_slots, 4), 0u);
+    for (uint32_t e = 0; e < n_words; ++e) {
+      const uint32_t s0 = slot_of(e), w = words[e];
+      bytes_img[s0] = (uint16_t)w;
+      second[s0] = i8_to_bf16_bits(w & 0xFFu) | i8_to_bf16_bits(w >> 8 & 0xFFu) << 16;
+      if (e >= class2) {
+        bytes_img[s0 + 1] = (uint16_t)(w >> 16);
+        second[s0 + 1] = i8_to_bf16_bits(w >> 16 & 0xFFu) | i8_to_bf16_bits(w >> 24) << 16;
+      }
+    }
+    first.assign(bytes_img.size() / 2, 0u);
+    std::memcpy(first.data(), bytes_img.data(), bytes_img.size() * 2);
+    d->image_bytes = (uint32_t)(bytes_img.size() * 2);
   }
-  hipError_t e = hipMalloc((void**)&d->dev, (size_t)n_words_pad * 4);
-  if (e == hipSuccess) e = hipMalloc((void**)&d->dev_bf16, (size_t)n_words_pad * 4);
-  if (e == hipSuccess) e = hipMemset(d->dev, 0, (size_t)n_words_pad * 4);
-  if (e == hipSuccess) e = hipMemcpy(d->dev, words, (size_t)n_words * 4, hipMemcpyHostToDevice);
-  if (e == hipSuccess) e = hipMemcpy(d->dev_bf16, pairs.data(), (size_t)n_words_pad * 4, hipMemcpyHostToDevice);
+  hipError_t e = hipMalloc((void**)&d->dev, first.size() * 4);
+  if (e == hipSuccess) e = hipMalloc((void**)&d->dev_bf16, second.size() * 4);
+  if (e == hipSuccess) e = hipMemcpy(d->dev, first.data(), first.size() * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(d->dev_bf16, second.data(), second.size() * 4, hipMemcpyHostToDevice);
   if (e != hipSuccess) {
     if (d->dev) (void)hipFree(d->dev);
     if (d->dev_bf16) (void)hipFree(d->dev_bf16);
     delete d;
     return hip_fail("dictionary upload", e);
   }
+  d->dict_words_bf16 = (uint32_t)second.size();
   g_dicts.push_back(d);
   *out = d;
   return TQ_OK;
@@ -185,8 +223,9 @@ bool plan_matvec_lds(uint32_t dict_words_max, uint32_t x_dwords_max, uint32_t* x
 // Whether the dot-product kernel takes a product: one activation row, two rows of one-weight-per-byte matrices (same
 // image size), or two rows of packed matrices (the image is twice as large there) - and in every case only if the
 // image fits the LDS beside the dictionary.  Everything else goes to the batched kernels.
-bool dot_kernel_takes(int batch, bool packed, uint32_t dict_words_max, uint32_t x_dwords_max) {
+bool dot_kernel_takes(int batch, bool packed, bool long_runs, uint32_t dict_words_max, uint32_t x_dwords_max) {
   if (batch > 2) return false;
+  if (long_runs && (batch != 1 || packed)) return false;   // runs of 3 and 4 bytes: the dot-product kernel has a one-row form only
   uint32_t x_off, slot_off;
   size_t total;
   return plan_matvec_lds(dict_words_max, (batch == 2 && packed ? 2u : 1u) * x_dwords_max, &x_off, &slot_off, &total);
@@ -219,11 +258,17 @@ const void* const kLdsKernels[] = {
     (const void*)k_matvec<kDotPiece, kDotWaves, false, 2>,
     (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1>,
     (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2>,
-    (const void*)k_decompress,
+    (const void*)k_matvec<kDotPiece, kDotWaves, false, 1, true>,
+    (const void*)k_decompress<false>,
+    (const void*)k_decompress<true>,
     (const void*)k_matvec_mfma<true, false>,
     (const void*)k_matvec_mfma<false, false>,
     (const void*)k_matvec_mfma<true, true>,
     (const void*)k_matvec_mfma<false, true>,
+    (const void*)k_matvec_mfma<true, false, true>,
+    (const void*)k_matvec_mfma<false, false, true>,
+    (const void*)k_matvec_mfma<true, true, true>,
+    (const void*)k_matvec_mfma<false, true, true>,
     (const void*)k_matvec_ring<kRingWaves, 16, false>,
     (const void*)k_matvec_ring<kRingWavesHalf, 8, false>,
     (const void*)k_matvec_ring<kRingWaves, 16, true>,
@@ -276,6 +321,7 @@ struct tq_matrix {
   const DevMat* m_dev;   // the same description in device memory, for launches that serve many matrices
   DictCopy* dict;
   void* dev_base;
+  uint32_t lds_dict16;   // bytes of LDS the byte image of the dictionary takes in the strip and ring kernels
   int device;
   int n_cu;
 };
@@ -298,23 +344,30 @@ static int tq_create_from_encoded_impl(const void* blob, size_t blob_bytes, tq_h
   m.seg_cols = h.seg_cols;
   m.n_bands = h.n_bands;
   m.n_quads = h.n_quads;
-  m.dict_words = (uint32_t)round_up(h.n_entries + 1, 4);
+  const bool long_runs = h.lmax > 2;
+  m.dict_words = (uint32_t)round_up(h.n_entries + 1, 4);   // (containers with runs of 3 and 4 bytes: set below, from the slot image)
   // Panels of one unit are seg_cols columns apart; a gap of 16 dwords after every panel keeps their activation reads
   // on different LDS banks when seg_cols is a multiple of 32.
   m.x_span = h.seg_cols + (h.seg_cols % 32 == 0 ? 16u : 0u);
   m.seg_magic = (uint32_t)((1ull << 32) / h.seg_cols) + 1;   // exact quotient while col * seg_cols < 2^32
-  m.reserved = facts.max_lane_spread <= kRingSpread ? 1u : facts.max_lane_spread <= kRingSpreadCareful ? 2u : 0u;
+  m.reserved = long_runs ? 0u : facts.max_lane_spread <= kRingSpread ? 1u : facts.max_lane_spread <= kRingSpreadCareful ? 2u : 0u;
   m.packing = h.packing;
+  m.long_runs = long_runs ? 1u : 0u;
+  m.class2 = h.class_end[1];
+  m.class3 = h.class_end[2];
   if (h.cols > (1u << 20)) {
     set_error("more than 2^20 columns are not supported");
     return TQ_E_UNSUPPORTED;
   }
   const uint64_t n_slots = (uint64_t)h.n_quads * kUnitPanels;
-  m.x_dwords = (uint32_t)((n_slots - 1) * m.x_span + std::max<uint64_t>(m.x_span, (uint64_t)facts.max_lane_reach + 1));
+  // (a code of a long-run container also reads the activation pair two columns further on, against weights that are
+  // zero when its run is shorter: two more dwords behind the furthest column a lane reaches)
+  m.x_dwords = (uint32_t)((n_slots - 1) * m.x_span + std::max<uint64_t>(m.x_span + (long_runs ? 2u : 0u), (uint64_t)facts.max_lane_reach + (long_runs ? 3u : 1u)));
   // (A row whose activation image does not fit the LDS beside the dictionary is not refused: its products run on the
   // batched kernels, which take their activations from global memory or a tile of one quad, at any batch.)
-  // tq_decompress and the batched product: 16-bit dictionary image plus one tile of 64 strips per wavefront.
-  if (round_up((uint64_t)m.dict_words * 2, 16) + (size_t)64 * (h.seg_cols + 8) > kLdsLimit) {
+  // tq_decompress and the batched product: byte image of the dictionary (2 bytes per slot, at most 30,720 slots) plus one
+  // tile of 64 strips per wavefront.
+  if (round_up((uint64_t)(long_runs ? 30720u : m.dict_words) * 2, 16) + (size_t)64 * (h.seg_cols + 8) > kLdsLimit) {
     set_error("segments of " + std::to_string(h.seg_cols) + " columns do not fit the LDS tile");
     return TQ_E_UNSUPPORTED;
   }
@@ -337,7 +390,11 @@ static int tq_create_from_encoded_impl(const void* blob, size_t blob_bytes, tq_h
 
   const uint8_t* src = (const uint8_t*)blob;
   DictCopy* dict = nullptr;
-  if (int rc = acquire_dictionary(dev, (const uint32_t*)(src + h.off_dict), h.n_entries + 1, m.dict_words, h.packing, &dict)) return rc;
+  if (int rc = acquire_dictionary(dev, (const uint32_t*)(src + h.off_dict), h.n_entries + 1, h, &dict)) return rc;
+  if (long_runs) {
+    m.dict_words = dict->dict_words_bf16;
+    m.dict16_bytes = dict->image_bytes;
+  }
 
   const uint64_t sz_uoff = round_up(h.uoff_bytes, kSectionAlign), sz_codes = round_up(h.code_bytes, kSectionAlign),
                  sz_scales = round_up(h.scale_bytes, kSectionAlign);
@@ -374,6 +431,7 @@ static int tq_create_from_encoded_impl(const void* blob, size_t blob_bytes, tq_h
   t->m_dev = (const DevMat*)(base + o_desc);
   t->dict = dict;
   t->dev_base = base;
+  t->lds_dict16 = long_runs ? dict->image_bytes : (uint32_t)round_up((uint64_t)m.dict_words * 2, 16);
   t->device = dev;
   t->n_cu = prop.multiProcessorCount;
   *out = t;
@@ -426,7 +484,7 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
   p.table_first = rec ? rec->entries.size() : 0;
   p.what = op == Op::kDecompress ? "tq_decompress launch" : "tq_matvec launch";
   a.table = rec ? (const StepEntry*)(uintptr_t)8 : nullptr;   // (the address follows when the step's table is in device memory)
-  uint32_t dict_words_max = 0, x_dwords_max = 0, seg_max = 0;
+  uint32_t dict_words_max = 0, x_dwords_max = 0, seg_max = 0, dict16_max = 0;
   uint64_t cost = 0, bands = 0, band_cost_max = 1;
   bool x_fast = true;
   for (int i = 0; i < n; ++i) {
@@ -445,6 +503,7 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     bands += t->m.n_bands;
     band_cost_max = std::max<uint64_t>(band_cost_max, t->m.cols);
     dict_words_max = std::max(dict_words_max, t->m.dict_words);
+    dict16_max = std::max(dict16_max, t->lds_dict16);
     x_dwords_max = std::max(x_dwords_max, t->m.x_dwords);
     seg_max = std::max(seg_max, t->m.seg_cols);
     x_fast = x_fast && (t->m.packing ? 2 : 1) * t->m.cols % 8 == 0 && xs && (uintptr_t)xs[i] % 16 == 0;
@@ -458,13 +517,15 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
   // workgroup per CU at most.
   p.grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>({(uint64_t)hs[0]->n_cu, bands, cost / band_cost_max}));
   const bool packed = hs[0]->m.packing != 0;   // (all matrices of a product launch hold their weights the same way: launch_all sees to that)
-  if (op == Op::kMatvec && dot_kernel_takes(batch, packed, dict_words_max, x_dwords_max)) {
+  const bool long_runs = hs[0]->m.long_runs != 0;   // (likewise)
+  if (op == Op::kMatvec && dot_kernel_takes(batch, packed, long_runs, dict_words_max, x_dwords_max)) {
     // the dot-product kernel: one activation row or two
     if (!plan_matvec_lds(dict_words_max, (packed && batch == 2 ? 2 : 1) * x_dwords_max, &a.x_off, &a.slot_off, &p.lds)) {
       set_error("the matrices of this call together need " + std::to_string(p.lds) + " bytes of LDS (largest dictionary plus longest row)");
       return TQ_E_UNSUPPORTED;
     }
-    p.kernel = packed ? (batch == 2 ? (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2> : (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1>)
+    p.kernel = long_runs ? (const void*)k_matvec<kDotPiece, kDotWaves, false, 1, true>
+               : packed ? (batch == 2 ? (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2> : (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1>)
                : batch == 2 ? (const void*)k_matvec<kDotPiece, kDotWaves, false, 2> : (const void*)k_matvec<kDotPiece, kDotWaves, false, 1>;
     p.block = (packed ? kDotWavesPacked : kDotWaves) * 64;
   } else if (ring) {
@@ -492,7 +553,7 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
   } else {
     // Tile decode.  LDS: 16-bit dictionary image | one tile (64 strips) per wavefront, which the batched product reuses
     // for its partial sums (per wavefront two slots of 1 KB and their two band numbers).
-    const size_t dict16 = round_up((uint64_t)dict_words_max * 2, 16);
+    const size_t dict16 = round_up((uint64_t)dict16_max, 16);
     const size_t area = std::max<size_t>((size_t)64 * (seg_max + 8), 2048 + 8);
     const size_t waves = std::min<size_t>(kWaves, (kLdsLimit - dict16) / area);
     if (waves == 0) {
@@ -504,7 +565,9 @@ int launch(Op op, int n, const tq_handle* hs, const void* const* xs, void* const
     a.slot_off = 0;
     p.lds = dict16 + waves * area;
     p.block = (unsigned)waves * 64;
-    if (op == Op::kDecompress) p.kernel = (const void*)k_decompress;
+    if (op == Op::kDecompress) p.kernel = long_runs ? (const void*)k_decompress<true> : (const void*)k_decompress<false>;
+    else if (long_runs && packed) p.kernel = x_fast ? (const void*)k_matvec_mfma<true, true, true> : (const void*)k_matvec_mfma<false, true, true>;
+    else if (long_runs) p.kernel = x_fast ? (const void*)k_matvec_mfma<true, false, true> : (const void*)k_matvec_mfma<false, false, true>;
     else if (packed) p.kernel = x_fast ? (const void*)k_matvec_mfma<true, true> : (const void*)k_matvec_mfma<false, true>;
     else p.kernel = x_fast ? (const void*)k_matvec_mfma<true, false> : (const void*)k_matvec_mfma<false, false>;
   }
@@ -533,23 +596,25 @@ bool ring_eligible(const tq_matrix* t, const void* x) {
 int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, hipStream_t stream, bool ring = false,
                bool gate_up = false, Recorder* rec = nullptr) {
   const int per_launch = rec ? kMaxStep : kMaxMulti;
-  if (op == Op::kMatvec) {
-    // The product kernels are built once per weight format: matrices of packed 4-bit weights and the others take
-    // separate launches.
-    int n_packed = 0;
-    for (int i = 0; i < n; ++i) n_packed += hs[i]->m.packing ? 1 : 0;
-    if (n_packed != 0 && n_packed != n) {
-      for (uint32_t want = 0; want < 2; ++want) {
+  {
+    // The kernels are built once per weight format: matrices of packed 4-bit weights, matrices with runs of 3 and 4
+    // bytes and the others take separate launches.  (The expansion does not care about packing, only about the runs.)
+    auto kind = [&](const tq_matrix* t) { return (op == Op::kMatvec && t->m.packing ? 1u : 0u) | (t->m.long_runs ? 2u : 0u); };
+    uint32_t seen = 0;
+    for (int i = 0; i < n; ++i) seen |= 1u << kind(hs[i]);
+    if (seen & (seen - 1)) {   // more than one kind
+      for (uint32_t want = 0; want < 4; ++want) {
+        if (!(seen >> want & 1u)) continue;
         std::vector<tq_handle> h2;
         std::vector<const void*> x2;
         std::vector<void*> y2;
         for (int i = 0; i < n; ++i)
-          if ((hs[i]->m.packing ? 1u : 0u) == want) {
+          if (kind(hs[i]) == want) {
             h2.push_back(hs[i]);
-            x2.push_back(xs[i]);
+            x2.push_back(xs ? xs[i] : nullptr);
             y2.push_back(ys[i]);
           }
-        if (int rc = launch_all(op, (int)h2.size(), h2.data(), x2.data(), y2.data(), batch, stream, ring, gate_up, rec)) return rc;
+        if (int rc = launch_all(op, (int)h2.size(), h2.data(), xs ? x2.data() : nullptr, y2.data(), batch, stream, ring, gate_up, rec)) return rc;
       }
       return TQ_OK;
     }
@@ -559,11 +624,11 @@ int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* c
   // it decides the same.  A call with both kinds is split.
   bool dot_call = false;
   if (op == Op::kMatvec && batch <= 2) {
-    const bool packed = hs[0]->m.packing != 0;
+    const bool packed = hs[0]->m.packing != 0, long_runs = hs[0]->m.long_runs != 0;
     uint32_t dict_words_max = 0;
     for (int i = 0; i < n; ++i) dict_words_max = std::max(dict_words_max, hs[i]->m.dict_words);
     int n_dot = 0;
-    for (int i = 0; i < n; ++i) n_dot += dot_kernel_takes(batch, packed, dict_words_max, hs[i]->m.x_dwords) ? 1 : 0;
+    for (int i = 0; i < n; ++i) n_dot += dot_kernel_takes(batch, packed, long_runs, dict_words_max, hs[i]->m.x_dwords) ? 1 : 0;
     dot_call = n_dot == n;
     if (n_dot != 0 && n_dot != n) {
       for (int want = 1; want >= 0; --want) {
@@ -571,7 +636,7 @@ int launch_all(Op op, int n, const tq_handle* hs, const void* const* xs, void* c
         std::vector<const void*> x2;
         std::vector<void*> y2;
         for (int i = 0; i < n; ++i)
-          if ((dot_kernel_takes(batch, packed, dict_words_max, hs[i]->m.x_dwords) ? 1 : 0) == want) {
+          if ((dot_kernel_takes(batch, packed, long_runs, dict_words_max, hs[i]->m.x_dwords) ? 1 : 0) == want) {
             h2.push_back(hs[i]);
             x2.push_back(xs[i]);
             y2.push_back(ys[i]);
@@ -668,7 +733,7 @@ static int tq_matvec_impl(tq_handle h, const void* x, void* y, int batch, void* 
   }
   if (int rc = check_call("tq_matvec", 1, &h, &x, &y, batch)) return rc;
   return launch(Op::kMatvec, 1, &h, &x, &y, batch, (hipStream_t)stream,
-                !dot_kernel_takes(batch, h->m.packing != 0, h->m.dict_words, h->m.x_dwords) && ring_eligible(h, x) &&
+                !dot_kernel_takes(batch, h->m.packing != 0, h->m.long_runs != 0, h->m.dict_words, h->m.x_dwords) && ring_eligible(h, x) &&
                     h->m.n_bands >= ring_min_bands_per_cu() * h->n_cu);
 }
 

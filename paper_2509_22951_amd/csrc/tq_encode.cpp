@@ -42,67 +42,130 @@ void parallel_for(uint64_t n, unsigned n_threads, F&& body) {  // body(begin, en
   for (auto& x : th) x.join();
 }
 
-// Dictionary for runs of at most 2 bytes.  Codes 0..255 are the single bytes; two-byte runs are found through a
-// direct table over the byte pair.
-class PairDict {
+// Dictionary of runs of up to 4 bytes, in the order LZW creates them (the container's code space is that order sorted by
+// run length: final_codes()).  Codes 0..255 are the single bytes; a two-byte run is found through a direct table over
+// the byte pair, a longer one through a hash table over (code of the run it extends, next byte).
+class RunDict {
  public:
-  PairDict(uint32_t max_entries, uint32_t lmax) : max_(max_entries), lmax_(lmax), pair_(65536, kNone) {
-    slot_.reserve(max_entries + 1);
-    for (uint32_t b = 0; b < 256; ++b) slot_.push_back(b | (8u << 24));   // top byte: run length in bits
+  RunDict(uint32_t max_entries, uint32_t lmax, uint32_t unit_budget)
+      : max_(max_entries), lmax_(lmax), budget_(unit_budget), units_(256), pair_(65536, kNone) {
+    bytes_.reserve(max_entries + 1);
+    len_.reserve(max_entries + 1);
+    for (uint32_t b = 0; b < 256; ++b) {
+      bytes_.push_back(b);
+      len_.push_back(1);
+    }
+    if (lmax > 2) {
+      mask_ = 1u << 17;
+      while (mask_ < 4u * max_entries) mask_ <<= 1;
+      key_.assign(mask_, kNone);
+      val_.assign(mask_, 0);
+      --mask_;
+    }
   }
-  // Continue from the dictionary section of another container (its entries 256.. in their order).
-  bool adopt(const uint32_t* slots, uint32_t n) {
+  uint32_t size() const { return (uint32_t)bytes_.size(); }
+  uint32_t length(uint32_t code) const { return len_[code]; }
+  uint32_t word(uint32_t code) const { return bytes_[code]; }
+  // no further entry can be added (count reached, or not even a two-byte run fits the unit budget)
+  bool full() const { return size() >= max_ || lmax_ < 2 || (budget_ && units_ + 1 > budget_); }
+
+  // The run (entry `parent` + byte b) as a new entry; false when it exists, is too long or does not fit.
+  bool add(uint32_t parent, uint32_t b) {
+    const uint32_t len = len_[parent] + 1, cost = len <= 2 ? 1u : 2u;
+    if (len > lmax_ || size() >= max_ || (budget_ && units_ + cost > budget_) || child(parent, b) != kNone) return false;
+    const uint32_t code = size();
+    if (len == 2) {
+      pair_[parent << 8 | b] = code;
+    } else {
+      uint32_t h = hash(parent << 8 | b);
+      while (key_[h] != kNone) h = (h + 1) & mask_;
+      key_[h] = parent << 8 | b;
+      val_[h] = code;
+    }
+    bytes_.push_back(bytes_[parent] | b << (8 * len_[parent]));
+    len_.push_back((uint8_t)len);
+    units_ += cost;
+    return true;
+  }
+  uint32_t child(uint32_t parent, uint32_t b) const {
+    if (parent < 256) return pair_[parent << 8 | b];
+    if (lmax_ <= 2) return kNone;
+    const uint32_t k = parent << 8 | b;
+    for (uint32_t h = hash(k); key_[h] != kNone; h = (h + 1) & mask_)
+      if (key_[h] == k) return val_[h];
+    return kNone;
+  }
+  // Continue from the dictionary section of another container: its entries from 256 on, which come sorted by length,
+  // so each follows the run it extends.  lens[e] = length of entry e.
+  bool adopt(const uint32_t* words, const std::vector<uint8_t>& lens, uint32_t n) {
     for (uint32_t e = 256; e < n; ++e) {
-      const uint32_t w = slots[e];
-      if ((w >> 24) != 16 || full() || lmax_ < 2) return false;
-      uint32_t& p = pair_[(w & 0xFFu) << 8 | (w >> 8 & 0xFFu)];
-      if (p != kNone) return false;
-      p = size();
-      slot_.push_back(w);
+      const uint32_t w = words[e], len = lens[e];
+      if (len < 2 || len > lmax_) return false;
+      uint32_t parent = w & 0xFFu;
+      for (uint32_t k = 1; k + 1 < len && parent != kNone; ++k) parent = child(parent, w >> (8 * k) & 0xFFu);
+      if (parent == kNone || !add(parent, w >> (8 * (len - 1)) & 0xFFu)) return false;
     }
     return true;
   }
-  // A two-byte run chosen from outside (frequency dictionary); false when it exists already or nothing fits.
-  bool add_pair(uint32_t b0, uint32_t b1) {
-    uint32_t& p = pair_[b0 << 8 | b1];
-    if (p != kNone || full() || lmax_ < 2) return false;
-    p = size();
-    slot_.push_back(b0 | b1 << 8 | 16u << 24);
-    return true;
-  }
-  uint32_t size() const { return (uint32_t)slot_.size(); }
-  bool full() const { return size() >= max_; }
-  const std::vector<uint32_t>& slots() const { return slot_; }
 
-  // Greedy parse of S[gs, ge): longest entry at each position, never crossing ge.  While `kGrow` and the
-  // dictionary is not full, the matched run plus the following byte becomes a new entry.
+  // Greedy parse of S[gs, ge): longest entry at each position, never crossing ge.  While `kGrow`, the matched run plus
+  // the following byte becomes a new entry if it fits.  Codes are written in creation order.
   template <bool kGrow>
   void parse(const uint8_t* S, uint64_t gs, uint64_t ge, std::vector<uint16_t>& out) {
     uint64_t i = gs;
-    while (i < ge) {
-      uint32_t code = S[i];
-      uint32_t m = 1;
-      if (lmax_ >= 2 && i + 1 < ge) {
-        const uint32_t pc = pair_[(uint32_t)S[i] << 8 | S[i + 1]];
-        if (pc != kNone) {
-          code = pc;
-          m = 2;
+    if (lmax_ <= 2) {   // the common case: one table lookup per position
+      while (i < ge) {
+        uint32_t code = S[i], m = 1;
+        if (lmax_ == 2 && i + 1 < ge) {
+          const uint32_t pc = pair_[(uint32_t)S[i] << 8 | S[i + 1]];
+          if (pc != kNone) {
+            code = pc;
+            m = 2;
+          }
         }
+        out.push_back((uint16_t)code);
+        if (kGrow && m < lmax_ && i + m < ge) add(code, S[i + 1]);   // m == 1 here: the new entry is a pair
+        i += m;
+      }
+      return;
+    }
+    while (i < ge) {
+      uint32_t code = S[i], m = 1;
+      while (m < lmax_ && i + m < ge) {
+        const uint32_t c = child(code, S[i + m]);
+        if (c == kNone) break;
+        code = c;
+        ++m;
       }
       out.push_back((uint16_t)code);
-      if (kGrow && m < lmax_ && i + m < ge && !full()) {   // m == 1 here: the new entry is a pair
-        const uint32_t nb = S[i + 1];
-        pair_[code << 8 | nb] = size();
-        slot_.push_back(code | nb << 8 | 16u << 24);
-      }
+      if (kGrow && m < lmax_ && i + m < ge) add(code, S[i + m]);
       i += m;
     }
   }
 
+  // The container's numbering: entries in order of run length, equal lengths in order of creation.
+  // final_of[creation code] = container code; class_end[k] = entries of at most k + 1 bytes.
+  void final_codes(std::vector<uint16_t>* final_of, std::vector<uint32_t>* words, uint32_t class_end[4]) const {
+    const uint32_t n = size();
+    uint32_t count[5] = {0, 0, 0, 0, 0};
+    for (uint32_t e = 0; e < n; ++e) ++count[len_[e]];
+    uint32_t next[5] = {0, 0, count[1], count[1] + count[2], count[1] + count[2] + count[3]};
+    for (int k = 0; k < 4; ++k) class_end[k] = next[k + 1] + count[k + 1];
+    final_of->assign(n + 1, 0);
+    words->assign(n, 0);
+    for (uint32_t e = 0; e < n; ++e) {
+      const uint32_t f = next[len_[e]]++;
+      (*final_of)[e] = (uint16_t)f;
+      (*words)[f] = bytes_[e];
+    }
+    (*final_of)[n] = (uint16_t)n;   // the pad code
+  }
+
  private:
-  uint32_t max_, lmax_;
-  std::vector<uint32_t> pair_;
-  std::vector<uint32_t> slot_;
+  uint32_t hash(uint32_t k) const { return (k * 2654435761u) >> 7 & mask_; }
+  uint32_t max_, lmax_, budget_, units_, mask_ = 0;
+  std::vector<uint32_t> pair_, bytes_, key_, val_;
+  std::vector<uint8_t> len_;
 };
 
 int check_opts(const tq_encode_opts* o, uint32_t* max_entries, uint32_t* lmax, uint32_t* seg_cols, unsigned* n_threads) {
@@ -112,7 +175,7 @@ int check_opts(const tq_encode_opts* o, uint32_t* max_entries, uint32_t* lmax, u
   *seg_cols = (o && o->seg_cols) ? o->seg_cols : (o && o->packing == TQ_PACK_NIBBLES) ? TQ_DEFAULT_SEG_COLS / 2 : TQ_DEFAULT_SEG_COLS;
   *n_threads = pick_threads(o ? o->n_threads : 0);
   if (*lmax < 1 || *lmax > TQ_MAX_LMAX) {
-    set_error("tq_encode: lmax must be 0 (default), 1 or 2");
+    set_error("tq_encode: lmax must be 0 (default) or in [1, " + std::to_string(TQ_MAX_LMAX) + "]");
     return TQ_E_INVALID_ARG;
   }
   if (*max_entries < 256 || *max_entries > TQ_MAX_ENTRIES_DEVICE) {
@@ -129,6 +192,10 @@ int check_opts(const tq_encode_opts* o, uint32_t* max_entries, uint32_t* lmax, u
   }
   if (o && o->dictionary != TQ_DICT_LZW && o->dictionary != TQ_DICT_FREQUENCY) {
     set_error("tq_encode: dictionary must be TQ_DICT_LZW or TQ_DICT_FREQUENCY");
+    return TQ_E_INVALID_ARG;
+  }
+  if (o && o->dictionary == TQ_DICT_FREQUENCY && *lmax > 2) {
+    set_error("tq_encode: TQ_DICT_FREQUENCY picks runs of 2 bytes; use lmax 1 or 2 with it");
     return TQ_E_INVALID_ARG;
   }
   if (o && o->bits != 0 && (o->bits < 2 || o->bits > 8)) {
@@ -193,13 +260,16 @@ int encode_quantized_matrix(const std::vector<uint8_t>& Q, const std::vector<flo
   h.packing = opts ? opts->packing : 0;
   const uint64_t n_units = h.n_units;
 
-  PairDict dict(max_entries, lmax);
+  // (runs longer than 2 bytes take two units of the device's dictionary storage each: the unit budget then applies)
+  RunDict dict(max_entries, lmax, lmax > 2 ? kUnitBudget : 0u);
   if (opts && opts->dict_from) {
     // One LZW dictionary over a sequence of matrices: start from the entries the earlier container ended with.
     Header fh;
     if (int rc = validate_blob(opts->dict_from, (size_t)opts->dict_from_bytes, &fh, nullptr, n_threads)) return rc;
+    std::vector<uint8_t> lens(fh.n_entries);
+    for (uint32_t e = 0; e < fh.n_entries; ++e) lens[e] = (uint8_t)run_length(fh, e);
     if (fh.lmax > lmax || fh.n_entries > max_entries ||
-        !dict.adopt((const uint32_t*)((const uint8_t*)opts->dict_from + fh.off_dict), fh.n_entries)) {
+        !dict.adopt((const uint32_t*)((const uint8_t*)opts->dict_from + fh.off_dict), lens, fh.n_entries)) {
       set_error("tq_encode: the dictionary of dict_from does not fit this lmax / max_entries");
       return TQ_E_INVALID_ARG;
     }
@@ -242,7 +312,7 @@ int encode_quantized_matrix(const std::vector<uint8_t>& Q, const std::vector<flo
       if (count[k]) keys.push_back(k);
     std::sort(keys.begin(), keys.end(), [&](uint32_t a, uint32_t b) { return count[a] != count[b] ? count[a] > count[b] : first[a] < first[b]; });
     for (uint32_t k : keys)
-      if (!dict.add_pair(k >> 8, k & 0xFF)) break;
+      if (!dict.add(k >> 8, k & 0xFF)) break;
   }
 
   // Phase 1 (sequential): units in order while the dictionary can still grow.
@@ -253,6 +323,10 @@ int encode_quantized_matrix(const std::vector<uint8_t>& Q, const std::vector<flo
   const uint64_t u_frozen = u;
   const uint32_t n_entries = dict.size();
   const uint16_t pad = (uint16_t)n_entries;
+  // The container's code space is sorted by run length; the parse above and below numbers entries as they were created.
+  std::vector<uint16_t> final_of;
+  std::vector<uint32_t> words;
+  dict.final_codes(&final_of, &words, h.class_end);
 
   // Phase 2 (parallel): the dictionary no longer changes, units are independent.
   {
@@ -312,7 +386,7 @@ int encode_quantized_matrix(const std::vector<uint8_t>& Q, const std::vector<flo
     return TQ_E_OOM;
   }
   std::memcpy(blob, &h, sizeof h);
-  std::memcpy(blob + h.off_dict, dict.slots().data(), (size_t)n_entries * 4);  // pad entry stays zero
+  std::memcpy(blob + h.off_dict, words.data(), (size_t)n_entries * 4);  // pad entry stays zero
   std::memcpy(blob + h.off_uoff, uoff.data(), uoff.size() * 4);
   uint16_t* codes = (uint16_t*)(blob + h.off_codes);
   {
@@ -324,7 +398,7 @@ int encode_quantized_matrix(const std::vector<uint8_t>& Q, const std::vector<flo
         const uint32_t len = (uoff[uu + 1] - uoff[uu]) * kChunkCodes;
         uint16_t* base = codes + (uint64_t)uoff[uu] * kChunkWords;
         for (uint32_t l = 0; l < 64; ++l) {
-          for (uint32_t k = 0; k < len; ++k) base[(uint64_t)(k / kChunkCodes) * kChunkWords + l * kChunkCodes + k % kChunkCodes] = k < c[l] ? src[k] : pad;
+          for (uint32_t k = 0; k < len; ++k) base[(uint64_t)(k / kChunkCodes) * kChunkWords + l * kChunkCodes + k % kChunkCodes] = k < c[l] ? final_of[src[k]] : pad;
           src += c[l];
         }
       }

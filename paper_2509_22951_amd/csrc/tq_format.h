@@ -1,4 +1,4 @@
-// Container layout (version 2) shared by the host encoder, the validator and the device code of libtq.
+// Container layout (version 3) shared by the host encoder, the validator and the device code of libtq.
 // All integers little-endian; every section starts on a 256-byte boundary.
 //
 // The quantized matrix Q (int8, rows x cols, row-major) is cut into *segments*: seg_cols consecutive columns of one
@@ -8,6 +8,12 @@
 // edge are empty.  The LZW parse (paper Background "Compression") visits the segments in (unit, lane) order with one
 // dictionary per matrix; a run never crosses a segment boundary, so every lane's code stream can be decoded
 // independently of the others (per-tile stream offsets).
+//
+// Dictionary: entries 0..255 are the single bytes (code == byte); the code space is sorted by run length - all runs of
+// 2 bytes, then those of 3, then those of 4 (class_end[k] = number of entries of at most k + 1 bytes) - so a code's
+// place tells its length, and entries of equal length keep the order LZW created them in.  An entry's word holds its
+// bytes, first byte lowest, unused bytes zero.  Storage on the device: one unit per entry of up to 2 bytes, two per
+// longer entry (kUnitBudget units when runs may be longer than 2; at most TQ_MAX_ENTRIES_DEVICE entries otherwise).
 //
 // packing 1 (values of at most 4 bits): byte j of a row holds the values of columns 2j (bits 0..3) and 2j + 1 (bits 4..7)
 // in 4-bit two's complement; rows, cols, seg_cols and everything below describe that byte matrix, half as wide as the
@@ -34,8 +40,9 @@ constexpr uint32_t kChunkWords = 64 * kChunkCodes;   // 16-bit codes per chunk
 constexpr uint32_t kMinSegCols = 16, kMaxSegCols = 1024, kDefaultSegCols = 256;
 constexpr uint32_t kSectionAlign = 256;
 constexpr uint32_t kHeaderBytes = 256;
-constexpr uint32_t kVersion = 2;
-constexpr char kMagic[8] = {'T', 'Q', 'M', 'O', 'E', 'v', '2', '\0'};
+constexpr uint32_t kVersion = 3;
+constexpr char kMagic[8] = {'T', 'Q', 'M', 'O', 'E', 'v', '3', '\0'};
+constexpr uint32_t kUnitBudget = 30716;   // units a dictionary with runs of 3 or 4 bytes may take (four more hold its pad entry and alignment)
 
 #pragma pack(push, 1)
 struct Header {
@@ -49,17 +56,23 @@ struct Header {
   uint32_t packing;                       // 0: one value per byte; 1: two 4-bit values per byte (the matrix has 2 * cols columns)
   uint64_t n_units, n_chunks;             // n_bands * n_quads; total chunks of the code section
   uint64_t n_real_codes;                  // codes that are not padding
-  uint64_t off_dict, dict_bytes;          // uint32 slot[n_entries + 1]: run bytes in bits 0..23, run length in BITS (8/16/24) in bits 24..31
+  uint64_t off_dict, dict_bytes;          // uint32 slot[n_entries + 1]: the run's bytes, first byte lowest, unused bytes zero
   uint64_t off_uoff, uoff_bytes;          // uint32 uoff[n_units + 1], in chunks
   uint64_t off_codes, code_bytes;         // uint16 codes[n_chunks * 256]
   uint64_t off_scales, scale_bytes;       // float scale[n_bands * 16]
   uint64_t total_bytes;
-  uint8_t zero[kHeaderBytes - 168];
+  uint32_t class_end[4];                  // entries of at most 1, 2, 3, 4 bytes: 256 <= .. <= n_entries; [lmax - 1] == n_entries
+  uint8_t zero[kHeaderBytes - 184];
 };
 #pragma pack(pop)
 static_assert(sizeof(Header) == kHeaderBytes, "header size");
 
 inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+// Run length of a code by its place in the sorted code space (the pad code, n_entries, counts as the longest class).
+inline uint32_t run_length(const Header& h, uint32_t code) {
+  return 1u + (code >= h.class_end[0]) + (code >= h.class_end[1]) + (code >= h.class_end[2]);
+}
 
 // Length in bytes of the segment lane `lane` of unit (band, quad) owns.
 inline uint32_t segment_len(const Header& h, uint32_t band, uint32_t quad, uint32_t lane) {
@@ -75,6 +88,7 @@ void set_error(const std::string& msg);   // thread-local last-error text
 struct BlobFacts {
   uint32_t max_lane_reach;   // largest (segment length + 2 * pad codes) of any lane stream: how many columns past the start
                              // of its segment a lane's activation index can get when every pad code advances it by two
+                             // (by four in containers whose runs may be longer than 2: what the pad code's place says)
   uint32_t max_lane_spread;  // the 64 lanes of a unit take their chunks in step; after any number of chunks, the lanes whose
                              // segment is not yet complete have reached different columns of it: the largest difference
                              // between two of them, over all units and all chunk counts

@@ -258,6 +258,29 @@ __device__ __forceinline__ void commit_activations_two(const DevMat& m, uint32_t
   }
 }
 
+// Containers with runs of up to 4 bytes (one activation row).  The dictionary image has one dword (two bf16 weights) per
+// slot; an entry of 3 or 4 bytes takes two slots, so a code reads the two dwords at its slot (for a shorter entry the
+// second one belongs to the next entry and is dropped), the activation pairs of its column and of the column two
+// further on, and multiplies both; its run length follows from the code's place in the sorted code space.
+// xa = LDS byte address of the activation pair of the lane's next column.
+struct LongClasses {
+  uint32_t class2, class3;
+};
+__device__ __forceinline__ void code_long_dot(uint32_t code, const LongClasses& cl, uint32_t& xa, float& a0, float& a1) {
+  const uint32_t da = long_slot(code, cl.class2) << 2;
+  const uint32_t w0 = lds_read32(da), w1 = lds_read32_off<4>(da);
+  const uint32_t x0 = lds_read32(xa), x1 = lds_read32_off<8>(xa);
+  a0 = dot2(w0, x0, a0);
+  a1 = dot2(code >= cl.class2 ? w1 : 0u, x1, a1);
+  xa += 4u * long_run_length(code, cl.class2, cl.class3);
+}
+__device__ __forceinline__ void chunk4_long(uint2 c, const LongClasses& cl, uint32_t& xa, float& a0, float& a1) {
+  code_long_dot(c.x & 0xFFFFu, cl, xa, a0, a1);
+  code_long_dot(c.x >> 16, cl, xa, a0, a1);
+  code_long_dot(c.y & 0xFFFFu, cl, xa, a0, a1);
+  code_long_dot(c.y >> 16, cl, xa, a0, a1);
+}
+
 // Sum of the four panel lanes of each row: afterwards every lane l holds the sum over lanes l % 16 + {0, 16, 32, 48}.
 __device__ __forceinline__ float sum_over_panels(float v) {
   v += __shfl_xor(v, 16);
@@ -278,9 +301,10 @@ __device__ __forceinline__ float silu_times(float gate, float up) { return gate 
 // lies entirely inside its run (it scales and stores those rows itself); a band it shares with its neighbours goes to
 // one of two partial-sum slots in LDS, and after a workgroup barrier the slots of a band are added in wavefront order,
 // so the result does not depend on timing.
-template <int kPiece, int kWaves, bool kPacked, int kB>
+template <int kPiece, int kWaves, bool kPacked, int kB, bool kLong = false>
 __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
   static_assert(kB == 1 || kB == 2, "one activation row or two");
+  static_assert(!kLong || (kB == 1 && !kPacked), "runs of 3 and 4 bytes: one activation row of one-weight-per-byte matrices");
   constexpr int kImage = kPacked && kB == 2 ? 2 : 1;   // dwords of the activation image per column
   constexpr int kThreads = kWaves * 64, kDictRegs = 128 / kWaves, kXRegs = 64 / kWaves;
   extern __shared__ uint4 lds4[];
@@ -474,7 +498,12 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
               dot(kk);
             });
           };
-          if (n == kPiece) {
+          if constexpr (kLong) {
+            const LongClasses cl = {m.class2, m.class3};
+            static_for<kPiece>([&](auto kk) {
+              if ((uint32_t)decltype(kk)::value < n) chunk4_long(cw[decltype(kk)::value], cl, xa, a0, a1);
+            });
+          } else if (n == kPiece) {
             straight(std::integral_constant<int, kPiece>{});
           } else if (n == kPiece - 1) {
             straight(std::integral_constant<int, kPiece - 1>{});
@@ -488,7 +517,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
               }
             });
           }
-          xa += 16 * kImage * n;
+          if constexpr (!kLong) xa += 16 * kImage * n;   // (the long form keeps xa at the lane's column itself)
           if (ends) {   // every lane restarts at the first column of its next segment
             if (++q == nq) {
               const bool more = band * nq + nq < u1;

@@ -4,7 +4,15 @@
 #include "tq_strip_decode.h"
 
 namespace tq {
-template <bool kXFast, bool kPacked>
+// Stage a dictionary image that is already laid out the way the kernel reads it (containers with runs of 3 and 4 bytes).
+__device__ __forceinline__ void stage_image(const uint32_t* image, uint32_t bytes, uint16_t* lds_dict, int tid, int n_threads) {
+  const uint4* src = (const uint4*)image;
+  uint4* dst = (uint4*)lds_dict;
+  for (uint32_t i = tid; i < bytes / 16; i += n_threads) dst[i] = global_load(src + i);
+}
+
+// kLong: the matrices of the launch hold runs of up to 4 bytes (append_chunk_long).
+template <bool kXFast, bool kPacked, bool kLong = false>
 __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
   extern __shared__ uint4 lds4[];
   uint16_t* lds_dict = (uint16_t*)lds4;
@@ -30,6 +38,10 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
     const uint32_t u0 = unit_lo + (uint32_t)((uint64_t)n_units * wave / n_waves);
     const uint32_t u1 = unit_lo + (uint32_t)((uint64_t)n_units * (wave + 1) / n_waves);
     __syncthreads();   // the previous matrix's dictionary and partial sums are no longer in use
+    if (kLong && m.dict != staged) {
+      stage_image(m.dict, m.dict16_bytes, lds_dict, tid, n_threads);
+      staged = m.dict;
+    }
     if (m.dict != staged) {
       // 16-bit image of the dictionary: the run bytes of every entry (the length follows from the code)
       const uint4* src = (const uint4*)m.dict;
@@ -91,7 +103,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
       const uint32_t strip = m.seg_cols + 8;   // bytes between the strips of two lanes
       const uint32_t my_strip = lds_address(tiles) + (uint32_t)wave * a.tile_area + (uint32_t)lane * strip;
       uint4 xa[kMfmaGroup];   // activation fragments of the first MFMA group of the unit being decoded
-      decode_run_to_tile(m, u0, u1, lane, my_strip, [&](uint32_t, uint32_t quad) {
+      decode_run_to_tile<kLong>(m, u0, u1, lane, my_strip, [&](uint32_t, uint32_t quad) {
 #pragma unroll
         for (int k = 0; k < kMfmaGroup; ++k)
           xa[k] = load_x_fragment<kXFast>(xrow, x_cols, pk * (quad * kUnitPanels + (uint32_t)kg) * m.seg_cols + 8 * k);
@@ -150,6 +162,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_matvec_mfma(MatvecArgs a) {
 // sequence).  Same work split and same tile decode as the batched product; a finished unit is copied out in 16-byte
 // pieces, consecutive lanes taking consecutive pieces of a row (4 panels x seg_cols contiguous bytes per row).
 // The y pointer of a job is the int8 output matrix here; the activation pointer is not used.
+template <bool kLong = false>
 __global__ __launch_bounds__(kThreads, 1) void k_decompress(MatvecArgs a) {
   extern __shared__ uint4 lds4[];
   uint16_t* lds_dict = (uint16_t*)lds4;
@@ -173,6 +186,12 @@ __global__ __launch_bounds__(kThreads, 1) void k_decompress(MatvecArgs a) {
     const uint32_t unit_lo = band_lo * nq, n_units = (band_hi - band_lo) * nq;
     const uint32_t u0 = unit_lo + (uint32_t)((uint64_t)n_units * wave / n_waves);
     const uint32_t u1 = unit_lo + (uint32_t)((uint64_t)n_units * (wave + 1) / n_waves);
+    if (kLong && m.dict != staged) {
+      __syncthreads();   // nobody reads the previous dictionary any more
+      stage_image(m.dict, m.dict16_bytes, lds_dict, tid, n_threads);
+      staged = m.dict;
+      __syncthreads();
+    }
     if (m.dict != staged) {
       __syncthreads();   // nobody reads the previous dictionary any more
       const uint4* src = (const uint4*)m.dict;
@@ -196,7 +215,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_decompress(MatvecArgs a) {
     int8_t* out = (int8_t*)job.y;
     const bool aligned = ((m.packing ? 2 * m.cols : m.cols) % 16 == 0) && ((uintptr_t)out % 16 == 0);
     const uint32_t ppp = m.seg_cols / 16;   // 16-byte pieces per segment
-    decode_run_to_tile(m, u0, u1, lane, tile_lds + (uint32_t)lane * strip, [](uint32_t, uint32_t) {}, [&](uint32_t band, uint32_t quad) {
+    decode_run_to_tile<kLong>(m, u0, u1, lane, tile_lds + (uint32_t)lane * strip, [](uint32_t, uint32_t) {}, [&](uint32_t band, uint32_t quad) {
       for (uint32_t pc = lane; pc < 64 * ppp; pc += 64) {
         const uint32_t seg = pc / ppp, part = pc - seg * ppp;            // segment (row seg / 4, panel seg % 4) of the unit
         const uint32_t row = band * kUnitRows + (seg >> 2), col = (quad * kUnitPanels + (seg & 3)) * m.seg_cols + part * 16;

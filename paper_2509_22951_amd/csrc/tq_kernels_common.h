@@ -44,7 +44,23 @@ struct DevMat {
   uint32_t reserved;       // how the ring kernel may decode the matrix: 0 not at all, 1 in groups of windows, 2 window by window
   uint32_t packing;        // 1: every byte holds two 4-bit weights (columns 2j and 2j + 1 of a matrix of 2 * cols columns); rows,
                            // cols and seg_cols describe the byte matrix, and dict_bf16 holds four fp8 (e4m3) weights per entry
+  uint32_t long_runs;      // 1: runs of 3 and 4 bytes exist (lmax > 2): the code space classes below apply, and dict / dict_bf16
+                           // point to images with two slots for every entry from `class2` on (see long_slot)
+  uint32_t class2, class3; // codes from class2 on are runs of at least 3 bytes, from class3 on of 4 (sorted code space)
+  uint32_t dict16_bytes;   // long_runs: size of the byte image at `dict` (a multiple of 16)
 };
+static_assert(sizeof(DevMat) % 8 == 0, "copied as whole dwords, kept 8-byte aligned in tables");
+
+// Containers with runs of up to 4 bytes keep a dictionary image with one slot for an entry of up to 2 bytes and two
+// slots for a longer one, the long ones starting on an even slot: slot index of a code.
+__device__ __forceinline__ uint32_t long_slot(uint32_t code, uint32_t class2) {
+  const uint32_t even = class2 & ~1u;
+  return code + (code > even ? code - even : 0u);   // codes below class2 never exceed `even` by more than 0: class2 - 1 <= even
+}
+// Run length of a code by its place in the sorted code space (the pad code, past the last entry, counts as 4).
+__device__ __forceinline__ uint32_t long_run_length(uint32_t code, uint32_t class2, uint32_t class3) {
+  return 1u + (code >= 256u ? 1u : 0u) + (code >= class2 ? 1u : 0u) + (code >= class3 ? 1u : 0u);
+}
 
 struct Job {
   const DevMat* m;         // device copy of the matrix description

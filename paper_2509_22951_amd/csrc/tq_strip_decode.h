@@ -96,6 +96,25 @@ __device__ __forceinline__ void append_chunk(uint2 c, uint32_t limit, uint32_t& 
   wpos = min(wpos + n, limit);
 }
 
+// The same for containers with runs of up to 4 bytes.  The byte image of the dictionary has one 2-byte slot per entry
+// of up to 2 bytes and two slots (4 bytes, 4-byte aligned) per longer entry; a code reads the aligned dword its slot lies
+// in, moves its bytes down, and stores them as one dword at the byte the lane has reached (bytes past the run's length
+// are overwritten by the next code or fall into the strip's spare bytes).  One store per code: this form is the general
+// one, not the fast one.
+typedef uint32_t lds_u32_any __attribute__((address_space(3), aligned(1)));
+__device__ __forceinline__ void append_code_long(uint32_t code, uint32_t class2, uint32_t class3, uint32_t limit, uint32_t& wpos) {
+  const uint32_t ba = long_slot(code, class2) << 1;                    // byte address of the entry in the image
+  const uint32_t e = lds_read32(ba & ~3u) >> ((ba & 2u) << 3);
+  *(lds_u32_any*)(size_t)wpos = e;
+  wpos = min(wpos + long_run_length(code, class2, class3), limit);
+}
+__device__ __forceinline__ void append_chunk_long(uint2 c, uint32_t class2, uint32_t class3, uint32_t limit, uint32_t& wpos) {
+  append_code_long(c.x & 0xFFFFu, class2, class3, limit, wpos);
+  append_code_long(c.x >> 16, class2, class3, limit, wpos);
+  append_code_long(c.y & 0xFFFFu, class2, class3, limit, wpos);
+  append_code_long(c.y >> 16, class2, class3, limit, wpos);
+}
+
 // Decode the units [u0, u1) of a matrix, one after the other, into the strips of this wavefront's tile and call
 // on_unit(band, quad) each time the tile holds a complete unit; before_last_piece(band, quad) is called ahead of the
 // unit's last piece of chunks, a few thousand clocks earlier (the place to request what on_unit will need).  The code chunks of the run are contiguous in memory.
@@ -104,7 +123,7 @@ __device__ __forceinline__ void append_chunk(uint2 c, uint32_t limit, uint32_t& 
 // Every piece issues exactly kPiece loads (those past its end repeat its last chunk): a fixed number of loads in flight
 // is what lets the compiler wait for the current piece only and not for the one just requested.
 
-template <typename BeforeLast, typename OnUnit>
+template <bool kLong = false, typename BeforeLast, typename OnUnit>
 __device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0, uint32_t u1, int lane, uint32_t my_strip,
                                                    BeforeLast&& before_last_piece, OnUnit&& on_unit) {
   if (u0 >= u1) return;
@@ -148,7 +167,11 @@ __device__ __forceinline__ void decode_run_to_tile(const DevMat& m, uint32_t u0,
   uint32_t wpos = my_strip, limit = my_strip + segment_length();   // next byte of the lane's segment in its strip, and its end
   auto decode_piece = [&](const uint2 (&cw)[kPiece], uint32_t n, bool ends) {
     if (ends) before_last_piece(band, quad);
-    if (n == kPiece) {   // whole pieces as straight-line code: the dictionary reads of later chunks overlap the packing of earlier ones
+    if constexpr (kLong) {
+#pragma unroll
+      for (int k = 0; k < kPiece; ++k)
+        if ((uint32_t)k < n) append_chunk_long(cw[k], m.class2, m.class3, limit, wpos);
+    } else if (n == kPiece) {   // whole pieces as straight-line code: the dictionary reads of later chunks overlap the packing of earlier ones
 #pragma unroll
       for (int k = 0; k < kPiece; ++k) append_chunk(cw[k], limit, wpos);
     } else if (n == kPiece - 1) {

@@ -169,6 +169,28 @@ def _plant(name: str):
         _edited_c_library(O, "(double)Q[r * K + j] * (double)x[b * K + j]", "(double)(uint8_t)Q[r * K + j] * (double)x[b * K + j]")
     elif name == "gemv_activations_read_transposed":
         _edited_c_library(O, "(double)Q[r * K + j] * (double)x[b * K + j]", "(double)Q[r * K + j] * (double)x[j * B + b]")
+    elif name == "lzw_unit_budget_ignored":
+        _edited_c_library(O, "(unit_budget <= 0 || units + cost <= unit_budget)) {", "1) {")
+    elif name == "lzw_long_entries_cost_one_unit":
+        _edited_c_library(O, "int cost = m + 1 <= 2 ? 1 : 2;", "int cost = 1;")
+    elif name in ("sorted_codes_not_renumbered", "sorted_order_not_stable"):
+        def sort_code_space(codes, d):
+            kind = "stable" if name == "sorted_codes_not_renumbered" else None
+            key = d.ent_len if kind else d.ent_len.astype(np.int64) * 100000 - np.arange(d.ent_len.size)   # equal lengths reversed
+            order = np.argsort(key, kind="stable")
+            new_of_old = np.empty(order.size, np.int64)
+            new_of_old[order] = np.arange(order.size)
+            sorted_len = d.ent_len[order]
+            class_end = np.array([int((sorted_len <= k + 1).sum()) for k in range(4)], np.uint32)
+            out = codes if name == "sorted_codes_not_renumbered" else new_of_old[codes].astype(np.uint16)
+            return out, O.Dictionary(d.ent_bytes[order].copy(), sorted_len.copy()), class_end
+        O.sort_code_space = sort_code_space
+    elif name == "dictionary_words_high_byte_first":
+        def dict_slots(d):
+            eb = d.ent_bytes.astype(np.uint32)
+            w = eb[:, 3] | (eb[:, 2] << 8) | (eb[:, 1] << 16) | (eb[:, 0] << 24)
+            return np.concatenate([w, np.zeros(1, np.uint32)]).astype(np.uint32)
+        O.dict_slots = dict_slots
     elif name == "lzw_carried_dictionary_ignored":
         _edited_c_library(O, "for (int e = 256; e < n_init; ++e) {", "for (int e = 256; e < n_init && e < 256; ++e) {")
     elif name == "gemv_output_transposed":

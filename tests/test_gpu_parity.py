@@ -110,6 +110,104 @@ def test_decompress_bit_exact_and_matvec(dev, rows, cols, max_entries, lmax, seg
         m.close()
 
 
+LONG_RUN_CASES = [
+    # rows, cols, lmax, seg_cols, width, pack, what the weights are
+    (64, 512, 3, 64, 8, False, "student"),
+    (200, 1024, 4, 128, 8, False, "sparse"),          # 90 % zeros: runs of 4 zeros carry most of the matrix
+    (33, 300, 4, 32, 8, False, "sparse"),             # ragged rows and columns
+    (512, 2048, 4, 256, 4, False, "normal"),          # 4-bit levels one per byte: 15 distinct bytes
+    (100, 768, 3, 64, 6, False, "normal"),
+    (48, 1024, 4, 128, 4, True, "normal"),            # packed nibbles and long runs: the batched kernels at every batch
+    (1040, 768, 4, 192, 8, False, "zero rows"),
+    (17, 257, 4, 256, 8, False, "sparse"),            # one-column last panel
+]
+
+
+@pytest.mark.parametrize("rows,cols,lmax,seg_cols,width,pack,what", LONG_RUN_CASES)
+def test_runs_of_three_and_four_bytes(dev, rows, cols, lmax, seg_cols, width, pack, what):
+    """Containers whose dictionary holds runs of up to 4 bytes (sorted code space, two LDS slots per long entry):
+    expansion bit-exact, products within the tolerance at batch 1 (the dot-product kernel's long form), 2, 3, 8 and 16
+    (whole-strip kernels), aligned and misaligned activations, alone and as a prepared step."""
+    spec = small_case(rows, cols, seed=rows * 11 + cols, dist="student_t4" if what == "student" else "normal")
+    W = make_weights(spec)
+    rng = np.random.default_rng(rows)
+    if what == "sparse":
+        W *= rng.random(W.shape) < 0.1
+    if what == "zero rows":
+        W[5] = 0
+        W[rows - 1] = 0
+        W[100:140] = 0
+    Qo, so = O.quantize_rows(W, width)
+    blob = tq.tq_encode(W, lmax=lmax, seg_cols=seg_cols, bits=0 if width == 8 else width, pack=pack)
+    assert blob == O.build_blob(O.encode_matrix(W, lmax=lmax, seg_cols=seg_cols, bits=width, pack=pack))
+    m = tq.Matrix(blob)
+    try:
+        assert m.info["lmax"] == lmax
+        assert np.array_equal(gpu_decompress(m, dev), Qo)
+        for batch in (1, 2, 3, 8, 16):
+            bits, x = make_activations(spec, batch)
+            ref = O.gemv_f64(Qo, so, x)
+            assert check_outputs(gpu_matvec(m, bits, dev), ref) < 1e-5
+            assert check_outputs(gpu_matvec(m, bits, dev, misalign=True), ref) < 1e-5
+            xd = torch.from_numpy(bits.view(np.int16).copy()).to(dev)
+            y = torch.full((batch, rows), float("nan"), dtype=torch.float32, device=dev)
+            step = tq.Step([m.handle], [xd.data_ptr()], [y.data_ptr()], batch)
+            step.launch(_stream())
+            torch.cuda.synchronize()
+            step.close()
+            assert check_outputs(y.cpu().numpy(), ref) < 1e-5
+        # unit vectors: every output is one weight times its scale, exactly; checks the column position of every run
+        for j in (0, 1, 2, 3, cols // 2, cols - 2, cols - 1):
+            xb = np.zeros((1, cols), np.float32)
+            xb[0, j] = 1.0
+            from inputs.synth import f32_to_bf16_bits
+            y1 = gpu_matvec(m, f32_to_bf16_bits(xb), dev)
+            assert np.array_equal(y1[0], (Qo[:, j].astype(np.float32) * so).astype(np.float32)), j
+    finally:
+        m.close()
+
+
+def test_one_call_with_long_run_and_ordinary_matrices(dev):
+    """A call that mixes containers with runs of up to 4 bytes, ordinary ones and packed ones is split by kind;
+    every product and every expansion still comes out right, directly and as prepared steps."""
+    shapes = [(64, 512, 4, False), (48, 256, 2, False), (80, 768, 3, False), (32, 512, 2, True), (96, 512, 4, True)]
+    mats, xs, refs, Qs = [], [], [], []
+    batch = 1
+    for k, (rows, cols, lmax, pack) in enumerate(shapes):
+        spec = small_case(rows, cols, seed=400 + k)
+        W = make_weights(spec) * (np.random.default_rng(k).random((rows, cols)) < 0.3)
+        width = 4 if pack else 8
+        mats.append(tq.Matrix(tq.tq_encode(W, lmax=lmax, seg_cols=64, bits=0 if width == 8 else width, pack=pack)))
+        Q, s = O.quantize_rows(W, width)
+        bits, x = make_activations(spec, batch)
+        xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
+        refs.append(O.gemv_f64(Q, s, x))
+        Qs.append(Q)
+    hs = [m.handle for m in mats]
+    try:
+        for use_step in (False, True):
+            ys = [torch.full((batch, r), float("nan"), dtype=torch.float32, device=dev) for r, _, _, _ in shapes]
+            outs = [torch.full((r, c), 77, dtype=torch.int8, device=dev) for r, c, _, _ in shapes]
+            if use_step:
+                st = tq.Step(hs, [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch)
+                sd = tq.Step(hs, None, [o.data_ptr() for o in outs], decompress=True)
+                st.launch(_stream())
+                sd.launch(_stream())
+                torch.cuda.synchronize()
+                st.close()
+                sd.close()
+            else:
+                tq.tq_matvec_multi(hs, [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], batch, _stream())
+                tq.tq_decompress_multi(hs, [o.data_ptr() for o in outs], _stream())
+                torch.cuda.synchronize()
+            for y, ref, o, Q in zip(ys, refs, outs, Qs):
+                check_outputs(y.cpu().numpy(), ref)
+                assert np.array_equal(o.cpu().numpy(), Q)
+    finally:
+        for m in mats:
+            m.close()
+
+
 def test_oracle_made_container_decodes_on_gpu(dev):
     spec = small_case(96, 768, seed=5)
     W = make_weights(spec)

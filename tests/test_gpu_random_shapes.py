@@ -47,13 +47,16 @@ def test_single_matrices(dev, seed, monkeypatch):
         spec, pack, width, seg = _draw_matrix(rng)
         me = int(rng.choice([256, 300, 1000, 5000, 30719]))
         kind = str(rng.choice(["lzw", "frequency"]))
+        lmax = 2 if kind == "frequency" else int(rng.choice([2, 2, 3, 4]))     # runs of up to 3 and 4 bytes now and then
         tq.tq_set_ring_min_bands_per_cu(int(rng.choice([0, 24])))
         W = make_weights(spec)
         if rng.integers(0, 5) == 0:
             W[rng.integers(0, spec.rows)] = 0           # an all-zero row
-        case = dict(rows=spec.rows, cols=spec.cols, seg=seg, entries=me, width=width, pack=pack, dist=spec.dist, kind=kind)
-        blob = tq.tq_encode(W, max_entries=me, seg_cols=seg, bits=0 if width == 8 else width, pack=pack, dictionary=kind)
-        assert blob == O.build_blob(O.encode_matrix(W, max_entries=me, seg_cols=seg, bits=width, pack=pack, dictionary=kind)), case
+        if lmax > 2 and rng.integers(0, 2):
+            W *= rng.random(W.shape) < 0.2              # mostly zeros: the long runs get used
+        case = dict(rows=spec.rows, cols=spec.cols, seg=seg, entries=me, width=width, pack=pack, dist=spec.dist, kind=kind, lmax=lmax)
+        blob = tq.tq_encode(W, max_entries=me, lmax=lmax, seg_cols=seg, bits=0 if width == 8 else width, pack=pack, dictionary=kind)
+        assert blob == O.build_blob(O.encode_matrix(W, max_entries=me, lmax=lmax, seg_cols=seg, bits=width, pack=pack, dictionary=kind)), case
         Q, s = O.quantize_rows(W, bits=width)
         m = tq.Matrix(blob)
         try:

@@ -34,6 +34,10 @@ def test_library_exports_every_declared_symbol():
     ((512, 2048), 30719, 2, 256, "student_t4"),
     ((48, 256), 300, 1, 256, "normal"),
     ((100, 3000), 30719, 2, 1024, "normal"),
+    ((200, 1024), 30719, 3, 128, "student_t4"),      # runs of up to 3 and 4 bytes: sorted code space, unit budget
+    ((512, 2048), 30719, 4, 256, "student_t4"),
+    ((64, 512), 700, 4, 64, "normal"),
+    ((33, 300), 30719, 4, 32, "student_t4"),
 ])
 def test_encoder_container_is_byte_identical_to_the_oracles(shape, max_entries, lmax, seg_cols, dist):
     W = make_weights(small_case(shape[0], shape[1], seed=7, dist=dist))
@@ -48,6 +52,28 @@ def test_encoder_container_is_byte_identical_to_the_oracles(shape, max_entries, 
     Q, s = O.decode_blob(blob)
     Qo, so = O.quantize_rows(W)
     assert np.array_equal(Q, Qo) and np.array_equal(s, so)
+
+
+def test_longer_runs_on_low_entropy_matrices_and_over_a_sequence():
+    """Runs of up to 4 bytes where they pay: 4-bit levels one per byte and a matrix that is mostly zeros (the unit budget
+    binds there: every 4-byte run takes two units), containers identical to the oracle's, also when a second matrix
+    goes on from the first one's dictionary; both store well under 0.7 bytes per weight."""
+    rng = np.random.default_rng(3)
+    W4 = make_weights(small_case(512, 2048, seed=8))
+    Ws = make_weights(small_case(512, 2048, seed=9)) * (rng.random((512, 2048)) < 0.1)      # 90 % zeros
+    for W, bits in ((W4, 4), (Ws, 8)):
+        blob = tq.tq_encode(W, lmax=4, bits=0 if bits == 8 else bits)
+        enc = O.encode_matrix(W, lmax=4, bits=bits)
+        assert blob == O.build_blob(enc)
+        info = tq.tq_validate_blob(blob)
+        assert info["lmax"] == 4 and info["compressed_bytes"] < 0.7 * W.size
+        assert np.array_equal(O.decode_blob(blob)[0], O.quantize_rows(W, bits)[0])
+        W2 = np.roll(W, 7, axis=1)
+        blob2 = tq.tq_encode(W2, lmax=4, bits=0 if bits == 8 else bits, dict_from=blob)
+        enc2 = O.encode_matrix(W2, lmax=4, bits=bits, carry=enc.dictionary)
+        assert blob2 == O.build_blob(enc2)
+        p = O.parse_blob(blob2)
+        assert int(p["class_end"][1]) + 2 * (p["n_entries"] - int(p["class_end"][1])) <= O.UNIT_BUDGET
 
 
 def test_defaults_are_the_documented_ones():
@@ -165,7 +191,7 @@ def test_four_bit_values_all_pair_up():
 
 def test_encode_argument_errors():
     W = np.zeros((4, 4), np.float32)
-    for kw in (dict(max_entries=100), dict(max_entries=tq.TQ_MAX_ENTRIES_DEVICE + 1), dict(lmax=3),
+    for kw in (dict(max_entries=100), dict(max_entries=tq.TQ_MAX_ENTRIES_DEVICE + 1), dict(lmax=5), dict(lmax=3, dictionary="frequency"),
                dict(seg_cols=24), dict(seg_cols=2048), dict(bits=1), dict(bits=9)):
         with pytest.raises(tq.TqError) as ei:
             tq.tq_encode(W, **kw)
@@ -195,18 +221,16 @@ def test_validation_rejects_malformed_containers():
         "segment length": _mutate(blob, o_c, "<H", 256 if p["stream"][0] < 256 else 0),
         "offset not monotone": _mutate(blob, o_u + 4, "<I", 0xFFFFFFF0),
         "offset shifted": _mutate(blob, o_u + 4, "<I", int(p["uoff"][1]) + 1),
-        "entry length": _mutate(blob, o_d + 4 * 300, "<I", (24 << 24) | 0x010203),
-        "entry length not whole bytes": _mutate(blob, o_d + 4 * 300, "<I", (12 << 24) | 0x0102),
-        "entry bytes past its length": _mutate(blob, o_d + 4 * 7, "<I", (8 << 24) | 0x0107),
-        "single byte entry": _mutate(blob, o_d + 4 * 7, "<I", (8 << 24) | 8),
-        "pad entry": _mutate(blob, o_d + 4 * p["n_entries"], "<I", 8 << 24),
+        "entry longer than its place in the code space says": _mutate(blob, o_d + 4 * 300, "<I", 0x010203),
+        "entry bytes past its length": _mutate(blob, o_d + 4 * 7, "<I", 0x0107),
+        "single byte entry": _mutate(blob, o_d + 4 * 7, "<I", 8),
+        "pad entry": _mutate(blob, o_d + 4 * p["n_entries"], "<I", 5),
+        "classes not monotone": _mutate(blob, 168 + 8, "<I", 255),
+        "classes beyond the entries": _mutate(blob, 168 + 4, "<I", p["n_entries"] + 1),
+        "classes say longer runs than lmax": _mutate(blob, 168 + 4, "<I", p["n_entries"] - 1),
+        "singles class": _mutate(blob, 168, "<I", 255),
         "count of real codes": _mutate(blob, 88, "<Q", p["n_real_codes"] + 1),
     }
-    # a one-byte entry at a code from 256 on that no code of the stream uses: every lane stream still adds up, but the
-    # kernels take the run length from the code alone, so such a dictionary must not pass
-    unused = np.setdiff1d(np.arange(256, p["n_entries"]), p["stream"])
-    assert unused.size
-    bad["one-byte entry above 255"] = _mutate(blob, o_d + 4 * int(unused[0]), "<I", (8 << 24) | 0x05)
     # a pad code in the middle of a lane stream (before real codes)
     assert last >= 1
     bad["pad inside a lane stream"] = _mutate(blob, o_c, "<H", p["pad_code"])

@@ -10,10 +10,15 @@ from oracle import oracle as O
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
-def brute_force_lzw(S: bytes, group_bytes: int, max_entries: int, lmax: int, entries=None):
+def brute_force_lzw(S: bytes, group_bytes: int, max_entries: int, lmax: int, entries=None, unit_budget: int = 0):
     """Independent restatement used only as a pin: the dictionary is a plain Python list of byte strings and
-    the longest match is found by trying every entry at every position (no trie, no incremental walk)."""
+    the longest match is found by trying every entry at every position (no trie, no incremental walk).
+    unit_budget (0 = none): an entry is added only if the dictionary then takes at most that many units, entries of up
+    to 2 bytes counting 1 and longer ones 2."""
     entries = [bytes([b]) for b in range(256)] if entries is None else list(entries)
+
+    def units(es):
+        return sum(1 if len(e) <= 2 else 2 for e in es)
     codes, per_group = [], []
     for gs in range(0, len(S), group_bytes):
         ge = min(gs + group_bytes, len(S))
@@ -28,7 +33,8 @@ def brute_force_lzw(S: bytes, group_bytes: int, max_entries: int, lmax: int, ent
             codes.append(best)
             cnt += 1
             if len(entries) < max_entries and m < lmax and i + m < ge:
-                entries.append(S[i:i + m + 1])
+                if not unit_budget or units(entries + [S[i:i + m + 1]]) <= unit_budget:
+                    entries.append(S[i:i + m + 1])
             i += m
         per_group.append(cnt)
     return codes, per_group, entries
@@ -278,3 +284,66 @@ def test_frequency_dictionary_round_trip_and_gain_over_lzw():
     S, seg_len = O.serialize(Q)
     assert np.array_equal(O.lzw_decode(f.stream, f.uoff, seg_len, f.dictionary, f.pad_code), S)
     assert f.dictionary.n_entries == 30719 and f.n_real_codes < l.n_real_codes       # the better-chosen pairs cover more
+
+
+def test_unit_budget_closed_form_on_equal_bytes():
+    """20 zero bytes, runs of up to 4: LZW wants to add 00 (1 unit), 000 (2 units), 0000 (2 units) on top of the 256
+    units of the single bytes.  Budget 261 or none: all three, runs 1 2 3 4 4 4 2.  Budget 259: 0000 does not fit, runs
+    1 2 3 3 3 3 3 2.  Budget 258: 000 does not fit either (and is offered again at every later match of 00, in vain):
+    runs 1 2 2 ... 2 1.  Budget 256: nothing but the single bytes."""
+    S = np.zeros(20, np.uint8)
+    for budget, want_entries, want_runs in ((0, 259, [1, 2, 3, 4, 4, 4, 2]), (261, 259, [1, 2, 3, 4, 4, 4, 2]),
+                                            (260, 258, [1, 2, 3, 3, 3, 3, 3, 2]), (259, 258, [1, 2, 3, 3, 3, 3, 3, 2]),
+                                            (258, 257, [1] + [2] * 9 + [1]), (256, 256, [1] * 20)):
+        codes, _, d = O.lzw_encode(S, seg_len=64, max_entries=65536, lmax=4, unit_budget=budget)
+        assert d.n_entries == want_entries, budget
+        assert [int(d.ent_len[c]) for c in codes] == want_runs, budget
+
+
+def test_unit_budget_against_the_brute_force_parser():
+    rng = np.random.default_rng(77)
+    for _ in range(12):
+        n = int(rng.integers(50, 400))
+        S = rng.integers(0, int(rng.choice([2, 3, 5])), n).astype(np.uint8)
+        group = int(rng.choice([7, 16, 64, 1000]))
+        lmax = int(rng.choice([3, 4]))
+        budget = 256 + int(rng.integers(0, 40))
+        max_entries = int(rng.choice([262, 280, 65536]))
+        codes, gnc, d = O.lzw_encode(S, seg_len=group, max_entries=max_entries, lmax=lmax, unit_budget=budget)
+        bc, bg, be = brute_force_lzw(S.tobytes(), group, max_entries, lmax, unit_budget=budget)
+        assert list(codes) == bc and list(gnc) == bg
+        assert [d.entry(e) for e in range(d.n_entries)] == be
+        assert sum(1 if len(e) <= 2 else 2 for e in be) <= budget
+
+
+def test_sorted_code_space_hand_example():
+    """"aaabaabab", runs of up to 4, one segment, by hand: a | aa | b | aab | a | b with the entries created in the order
+    256 aa, 257 aab, 258 ba, 259 aaba, 260 ab.  Sorted by length, equal lengths in order of creation: 256 aa, 257 ba,
+    258 ab, 259 aab, 260 aaba, so the stream 97 256 98 257 97 98 becomes 97 256 98 259 97 98."""
+    S = np.frombuffer(b"aaabaabab", np.uint8)
+    codes, _, d = O.lzw_encode(S, seg_len=64, max_entries=65536, lmax=4)
+    assert list(codes) == [97, 256, 98, 257, 97, 98]
+    assert [d.entry(e) for e in range(256, d.n_entries)] == [b"aa", b"aab", b"ba", b"aaba", b"ab"]
+    codes2, d2, class_end = O.sort_code_space(codes, d)
+    assert list(codes2) == [97, 256, 98, 259, 97, 98]
+    assert [d2.entry(e) for e in range(256, d2.n_entries)] == [b"aa", b"ba", b"ab", b"aab", b"aaba"]
+    assert list(class_end) == [256, 259, 260, 261]
+    assert all(d2.entry(b) == bytes([b]) for b in range(256))
+
+
+def test_sorted_code_space_is_a_relabelling():
+    """The renumbered stream with the reordered dictionary spells the same bytes; lengths never decrease along the code
+    space; every entry of two or more bytes still follows the entry it extends (what lets a later matrix go on from it)."""
+    rng = np.random.default_rng(5)
+    S = rng.integers(0, 4, 3000).astype(np.uint8)
+    seg_len = np.full(30, 100, np.uint32)
+    codes, snc, d = O.lzw_encode(S, seg_len=seg_len, max_entries=700, lmax=4, unit_budget=900)
+    codes2, d2, class_end = O.sort_code_space(codes, d)
+    assert b"".join(d.entry(c) for c in codes) == b"".join(d2.entry(c) for c in codes2) == S.tobytes()
+    assert np.all(np.diff(d2.ent_len.astype(int)) >= 0) and class_end[3] == d2.n_entries and class_end[0] == 256
+    where = {d2.entry(e): e for e in range(d2.n_entries)}
+    assert all(where[d2.entry(e)[:-1]] < e for e in range(256, d2.n_entries))
+    again = O.lzw_encode(S, seg_len=seg_len, max_entries=700, lmax=4, carry=d2, unit_budget=900)   # a carried, sorted dictionary
+    assert again[2].n_entries >= d2.n_entries
+    stream, uoff = O.interleave(codes2, snc, d2.n_entries)
+    assert np.array_equal(O.lzw_decode(stream, uoff, seg_len, d2, d2.n_entries), S)

@@ -81,8 +81,9 @@ def test_container_round_trip(shape, max_entries, seg_cols):
     p = O.parse_blob(blob)
     assert (p["rows"], p["cols"]) == shape and p["n_entries"] == enc.dictionary.n_entries
     assert p["n_codes"] == enc.stream.size and p["pad_code"] == enc.dictionary.n_entries and p["seg_cols"] == seg_cols
-    assert p["slots"][-1] == 0                                    # the pad entry has length 0
-    assert np.array_equal(p["slots"][:256], np.arange(256, dtype=np.uint32) | (8 << 24))   # singles: code == byte, 8 bits long
+    assert p["slots"][-1] == 0                                    # the pad entry is empty
+    assert np.array_equal(p["slots"][:256], np.arange(256, dtype=np.uint32))               # singles: code == byte
+    assert list(p["class_end"]) == [256] + [p["n_entries"]] * 3                           # no run longer than 2 here
     Q, s = O.decode_blob(blob)
     assert np.array_equal(Q, enc.Q) and np.array_equal(s, enc.scales)
     Qq, sq = O.quantize_rows(W)
@@ -91,6 +92,30 @@ def test_container_round_trip(shape, max_entries, seg_cols):
     y = O.matvec_from_blob(blob, x)
     ref = (x.astype(np.float64) @ Qq.astype(np.float64).T) * sq.astype(np.float64)[None, :]
     np.testing.assert_allclose(y, ref, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("lmax", [3, 4])
+def test_container_with_longer_runs(lmax):
+    """Runs of up to 4 bytes: the container word of an entry holds its bytes, first byte lowest; the length is told by
+    the code's place (class_end); the round trip through writer, reader and decoder is exact; the dictionary stays
+    within the unit budget."""
+    spec = small_case(96, 640, seed=9, dist="student_t4")
+    W = make_weights(spec)
+    W[:, 100:300] = 0                                   # a stretch of equal values, so that long runs do get used
+    enc = O.encode_matrix(W, lmax=lmax, seg_cols=128)
+    assert int(enc.dictionary.ent_len.max()) == lmax
+    p = O.parse_blob(O.build_blob(enc))
+    assert list(p["class_end"]) == list(enc.class_end) and p["class_end"][lmax - 1] == p["n_entries"]
+    assert np.array_equal(p["dictionary"].ent_len, enc.dictionary.ent_len)
+    assert np.array_equal(p["dictionary"].ent_bytes, enc.dictionary.ent_bytes)
+    e = int(p["class_end"][1])                          # the first 3-byte entry, written out by hand
+    b = enc.dictionary.entry(e)
+    assert len(b) == 3 and int(p["slots"][e]) == b[0] | b[1] << 8 | b[2] << 16
+    n12, n34 = int(p["class_end"][1]), p["n_entries"] - int(p["class_end"][1])
+    assert n12 + 2 * n34 <= O.UNIT_BUDGET
+    Q, s = O.decode_blob(O.build_blob(enc))
+    assert np.array_equal(Q, O.quantize_rows(W)[0]) and np.array_equal(s, enc.scales)
+    assert enc.n_real_codes < O.encode_matrix(W, lmax=2, seg_cols=128).n_real_codes      # the longer runs do pay here
 
 
 def test_measured_ratio_config1_like():

@@ -36,6 +36,11 @@ MISTAKES = [
     ("lzw_new_entry_repeats_first_byte", CODEC),
     ("lzw_restarts_when_full", CODEC),
     ("lzw_carried_dictionary_ignored", CODEC),
+    ("lzw_unit_budget_ignored", CODEC),
+    ("lzw_long_entries_cost_one_unit", CODEC),
+    ("sorted_codes_not_renumbered", CODEC),
+    ("sorted_order_not_stable", CODEC),
+    ("dictionary_words_high_byte_first", GEMV),
     ("decode_ignores_codes_after_padding", CODEC),
     ("gemv_scale_dropped", GEMV),
     ("gemv_weights_read_transposed", GEMV),
