@@ -86,11 +86,13 @@ def parse_args():
     ap.add_argument("--no-matrix-dictionary", action="store_true",
                     help="skip the leg that repeats the sweep with one dictionary per matrix")
     ap.add_argument("--layers", type=int, default=0, help="debug: keep only the first N layers (+ lm_head)")
-    ap.add_argument("--fuse", choices=["none", "independent", "layer", "sweep"], default="sweep",
+    ap.add_argument("--fuse", choices=["none", "independent", "staged", "layer", "sweep"], default="sweep",
                     help="how the products of a step are grouped into launches.  sweep: the step is a list of independent "
                          "products (each has its own activation vector), so all of them go to tq_matvec_multi at once; "
                          "layer: one tq_matvec_multi per transformer layer; independent: only products that a real layer "
-                         "computes from the same input (q,k,v and gate,up) share a launch; none: one tq_matvec per matrix")
+                         "computes from the same input (q,k,v and gate,up) share a launch; staged: the same grouping as one "
+                         "staged step (tq_step_create_staged: one kernel launch, device-side hand-over between the groups); "
+                         "none: one tq_matvec per matrix")
     ap.add_argument("--no-prepared-step", action="store_true",
                     help="launch through tq_matvec_multi (at most 128 matrices per kernel launch) instead of a prepared tq_step")
     ap.add_argument("--graph", action="store_true",
@@ -251,7 +253,7 @@ class Runner:
 
     def __init__(self, tq, torch, wl, mat_sets, args, dev, stream):
         self.tq, self.torch, self.wl, self.mat_sets, self.args, self.dev, self.stream = tq, torch, wl, mat_sets, args, dev, stream
-        self.groups = launch_groups(wl.specs, args.fuse)
+        self.groups = launch_groups(wl.specs, "independent" if args.fuse == "staged" else args.fuse)
 
     def make_io(self, batch):
         from inputs import make_activations
@@ -269,6 +271,13 @@ class Runner:
 
         def calls_for(ms, count):
             calls = []            # one per group; each takes the stream to launch on
+            if args.fuse == "staged":   # every group a stage of one staged step
+                order = [i for g in self.groups for i in g]
+                st = tq.Step([ms[i].handle for i in order], [xs[i].data_ptr() for i in order], [ys[i].data_ptr() for i in order], batch,
+                             stages=[k for k, g in enumerate(self.groups) for _ in g])
+                if count:
+                    extra[0] += st.info["n_launches"] - len(self.groups)
+                return [lambda s, st=st: st.launch(s)]
             for g in self.groups:
                 if len(g) == 1:   # one matrix: its description travels in the kernel arguments
                     m, xp, yp = ms[g[0]], xs[g[0]].data_ptr(), ys[g[0]].data_ptr()

@@ -209,11 +209,41 @@ int tq_matvec_gate_up_multi(int n, const tq_handle *hs, const void *const *xs, v
                                  NULL and batch is not used */
 typedef struct tq_step *tq_step_handle;
 typedef struct tq_step_info {
-  uint32_t n_matrices, n_launches; /* kernel launches one tq_step_launch makes */
+  uint32_t n_matrices, n_launches; /* kernel launches one tq_step_launch makes (a staged step that runs as one kernel: 1,
+                                      not counting the small launch that clears its stage counters) */
   uint64_t table_bytes;            /* device memory the step holds */
+  uint32_t n_stages;               /* staged steps: number of stages, else 0 */
+  uint32_t persistent;             /* 1: all stages run in one kernel launch with device-side hand-over between them */
+  uint32_t fault;                  /* 1: a launch of the staged step gave up waiting at a hand-over (see tq_step_create_staged) */
+  uint32_t reserved;
 } tq_step_info;
 int tq_step_create(int n, const tq_handle *hs, const void *const *xs, void *const *ys, int batch, uint32_t flags,
                    tq_step_handle *out);
+/*
+ * A staged step: the products of a decode step that DEPEND on each other, prepared once and run in order - the paper's
+ * layer-by-layer use of the compressed parameters (Background "Inference"; section 5: the model's linear layers are
+ * replaced by compressed counterparts): within a transformer layer q, k and v can run side by side, the output
+ * projection needs their result, gate and up need the output projection's, down needs theirs, and the next layer needs
+ * down's.  stage[i] (host array, n entries, starting at 0, never decreasing, never skipping) says which stage product i
+ * belongs to; the products of one stage are independent of each other; no product of stage s + 1 reads its x before
+ * every y of stage s has been stored and made visible (so whatever produces that x from those y on the same stream
+ * order - or the caller's own kernels between two steps - finds them).  The activations x and outputs y are the
+ * caller's, as in tq_step_create; this call only orders the products.
+ * When every matrix takes the dot-product kernel (batch 1 or 2; ordinary or packed weights; rows that fit its LDS image;
+ * no runs longer than 2 bytes) the whole step is one kernel launch: one workgroup per compute unit walks the stages, the
+ * dictionary stays in LDS across them, and between two stages the workgroups hand over through a counter in device
+ * memory (release / acquire at device scope).  That needs all workgroups resident together, which holds when nothing
+ * else occupies the GPU's compute units while the step runs; a wait is bounded (tq_step_set_spin_limit; about two
+ * seconds by default): a workgroup that gives up sets a fault flag, every other wait of that launch ends at once, the
+ * results must not be used, tq_step_get_info reports fault = 1 and later launches return TQ_E_HIP.
+ * Otherwise (larger batches, long runs, mixed kinds) each stage gets the launches tq_matvec_multi would make, in order
+ * on the stream.  Results equal tq_matvec_multi's for the same products up to the order of fp32 additions.
+ * flags: none defined yet, pass 0.  Launch with tq_step_launch, release with tq_step_destroy.
+ */
+int tq_step_create_staged(int n, const tq_handle *hs, const void *const *xs, void *const *ys, const int *stage, int batch,
+                          uint32_t flags, tq_step_handle *out);
+/* Polls of a stage counter (a microsecond or two each) after which a workgroup of a staged step gives up waiting. */
+int tq_step_set_spin_limit(tq_step_handle s, uint32_t polls);
 int tq_step_launch(tq_step_handle s, void *stream);
 int tq_step_get_info(tq_step_handle s, tq_step_info *out);
 int tq_step_destroy(tq_step_handle s);

@@ -21,7 +21,7 @@ EXPORTS = [
     "tq_matvec_multi", "tq_decompress", "tq_decompress_multi", "tq_get_info", "tq_destroy", "tq_last_error_string",
     "tq_encode_gate_up", "tq_matvec_gate_up", "tq_matvec_gate_up_multi",
     "tq_set_ring_min_bands_per_cu",
-    "tq_matvec_multi_static",
+    "tq_matvec_multi_static", "tq_step_create_staged", "tq_step_set_spin_limit",
     "tq_step_create", "tq_step_launch", "tq_step_get_info", "tq_step_destroy",
     "tq_listing_build_table", "tq_listing_compress", "tq_listing_create", "tq_listing_decompress", "tq_listing_get_info",
     "tq_listing_destroy",
@@ -42,7 +42,8 @@ class TqEncodeOpts(ctypes.Structure):
 
 
 class TqStepInfo(ctypes.Structure):
-    _fields_ = [("n_matrices", ctypes.c_uint32), ("n_launches", ctypes.c_uint32), ("table_bytes", ctypes.c_uint64)]
+    _fields_ = [("n_matrices", ctypes.c_uint32), ("n_launches", ctypes.c_uint32), ("table_bytes", ctypes.c_uint64),
+                ("n_stages", ctypes.c_uint32), ("persistent", ctypes.c_uint32), ("fault", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 class TqInfo(ctypes.Structure):
@@ -106,6 +107,11 @@ def load() -> ctypes.CDLL:
     lib.tq_matvec_multi_static.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
     lib.tq_step_create.restype = ci
     lib.tq_step_create.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, u32, ctypes.POINTER(vp)]
+    lib.tq_step_create_staged.restype = ci
+    lib.tq_step_create_staged.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ci), ci, u32,
+                                          ctypes.POINTER(vp)]
+    lib.tq_step_set_spin_limit.restype = ci
+    lib.tq_step_set_spin_limit.argtypes = [vp, u32]
     lib.tq_step_launch.restype = ci
     lib.tq_step_launch.argtypes = [vp, vp]
     lib.tq_step_get_info.restype = ci
@@ -285,6 +291,21 @@ def tq_step_create(handles, x_ptrs, y_ptrs, batch: int, flags: int = 0) -> int:
     return out.value
 
 
+def tq_step_create_staged(handles, x_ptrs, y_ptrs, stages, batch: int, flags: int = 0) -> int:
+    """stages[i]: the stage product i belongs to (from 0, never decreasing, never skipping)."""
+    n = len(handles)
+    assert n == len(x_ptrs) == len(y_ptrs) == len(stages) and n >= 1
+    arr = ctypes.c_void_p * n
+    out = ctypes.c_void_p()
+    _check(load().tq_step_create_staged(n, arr(*handles), arr(*x_ptrs), arr(*y_ptrs), (ctypes.c_int * n)(*stages), batch, flags,
+                                        ctypes.byref(out)))
+    return out.value
+
+
+def tq_step_set_spin_limit(step: int, polls: int) -> None:
+    _check(load().tq_step_set_spin_limit(step, polls))
+
+
 def tq_step_launch(step: int, stream: int = 0) -> None:
     _check(load().tq_step_launch(step, stream))
 
@@ -302,9 +323,12 @@ def tq_step_destroy(step) -> None:
 class Step:
     """Owning wrapper around a prepared step (marshalling only): tq_matvec_multi for fixed matrices and buffers."""
 
-    def __init__(self, handles, x_ptrs, y_ptrs, batch: int = 1, gate_up: bool = False, decompress: bool = False):
+    def __init__(self, handles, x_ptrs, y_ptrs, batch: int = 1, gate_up: bool = False, decompress: bool = False, stages=None):
         flags = (TQ_STEP_GATE_UP if gate_up else 0) | (TQ_STEP_DECOMPRESS if decompress else 0)
-        self.handle = tq_step_create(handles, x_ptrs, y_ptrs, batch, flags)
+        if stages is not None:      # products that depend on each other: tq_step_create_staged
+            self.handle = tq_step_create_staged(handles, x_ptrs, y_ptrs, stages, batch, flags)
+        else:
+            self.handle = tq_step_create(handles, x_ptrs, y_ptrs, batch, flags)
         self.info = tq_step_get_info(self.handle)
 
     def launch(self, stream: int = 0) -> None:

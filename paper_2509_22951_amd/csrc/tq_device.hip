@@ -65,6 +65,12 @@ struct TableWrite {
 };
 static_assert(sizeof(TableWrite) <= 4096, "kernel arguments");
 
+// The stage counters of a staged step start every launch at zero (a fill kernel, not a memset node: the launch may be
+// captured in a HIP graph).
+__global__ __launch_bounds__(256) void k_zero_words(uint32_t* p, uint32_t n) {
+  for (uint32_t i = threadIdx.x; i < n; i += 256) p[i] = 0u;
+}
+
 // Entry t of the table = (description of job t copied from device memory, x, y).  One thread per dword of an entry.
 __global__ __launch_bounds__(64) void k_write_table(TableWrite w) {
   constexpr int kDescDwords = sizeof(DevMat) / 4;
@@ -259,6 +265,10 @@ const void* const kLdsKernels[] = {
     (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1>,
     (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2>,
     (const void*)k_matvec<kDotPiece, kDotWaves, false, 1, true>,
+    (const void*)k_matvec<kDotPiece, kDotWaves, false, 1, false, true>,
+    (const void*)k_matvec<kDotPiece, kDotWaves, false, 2, false, true>,
+    (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1, false, true>,
+    (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2, false, true>,
     (const void*)k_decompress<false>,
     (const void*)k_decompress<true>,
     (const void*)k_matvec_mfma<true, false>,
@@ -775,7 +785,14 @@ struct tq_step {
   StepEntry* table_dev;
   size_t n_entries;
   int n_matrices;
+  // staged steps that run as one launch (all stages in one persistent kernel):
+  uint32_t n_stages = 0;
+  bool persistent = false;
+  uint32_t* stage_dev = nullptr;    // stage_first[n_stages + 1] | sync[n_stages + 1]
+  uint32_t* fault_host = nullptr;   // pinned host word the kernel sets when a hand-over wait gave up
 };
+
+constexpr uint32_t kDefaultSpinLimit = 1u << 20;   // polls of a stage counter (a microsecond or two each) before a workgroup gives up
 
 static int tq_step_create_impl(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, uint32_t flags,
                               tq_step_handle* out) {
@@ -839,10 +856,140 @@ static int tq_step_create_impl(int n, const tq_handle* hs, const void* const* xs
   }
 }
 
+// A staged step: products that depend on each other in one prepared step.  When every matrix takes the dot-product
+// kernel (batch 1 or 2, ordinary or packed weights, rows that fit its activation image) the whole step is ONE launch of
+// that kernel's staged form, one workgroup per compute unit, with a grid-wide hand-over between stages; otherwise
+// every stage gets the launches tq_matvec_multi would make for it, in stage order on the stream.
+static int tq_step_create_staged_impl(int n, const tq_handle* hs, const void* const* xs, void* const* ys, const int* stage, int batch,
+                                      uint32_t flags, tq_step_handle* out) {
+  if (!out) {
+    set_error("tq_step_create_staged: null output pointer");
+    return TQ_E_INVALID_ARG;
+  }
+  *out = nullptr;
+  if (n < 1 || !hs || !xs || !ys || !stage || flags != 0) {
+    set_error("tq_step_create_staged: null argument, n < 1 or flags (none are defined for staged steps)");
+    return TQ_E_INVALID_ARG;
+  }
+  if (int rc = check_call("tq_step_create_staged", n, hs, xs, ys, batch)) return rc;
+  if (stage[0] != 0) {
+    set_error("tq_step_create_staged: stages are numbered from 0");
+    return TQ_E_INVALID_ARG;
+  }
+  for (int i = 1; i < n; ++i)
+    if (stage[i] != stage[i - 1] && stage[i] != stage[i - 1] + 1) {
+      set_error("tq_step_create_staged: stage numbers must not decrease and must not skip (index " + std::to_string(i) + ")");
+      return TQ_E_INVALID_ARG;
+    }
+  const uint32_t n_stages = (uint32_t)stage[n - 1] + 1;
+  std::vector<uint32_t> first(n_stages + 1, (uint32_t)n);
+  for (int i = n - 1; i >= 0; --i) first[stage[i]] = (uint32_t)i;
+
+  const bool packed = hs[0]->m.packing != 0;
+  uint32_t dict_words_max = 0, x_dwords_max = 0;
+  uint64_t cost = 0;
+  bool one_kind = n <= kMaxStep;
+  for (int i = 0; i < n; ++i) {
+    one_kind = one_kind && (hs[i]->m.packing != 0) == packed && !hs[i]->m.long_runs;
+    dict_words_max = std::max(dict_words_max, hs[i]->m.dict_words);
+    x_dwords_max = std::max(x_dwords_max, hs[i]->m.x_dwords);
+    cost += (uint64_t)hs[i]->m.n_bands * hs[i]->m.cols;
+  }
+  const bool persistent = one_kind && cost <= 0xFFFFFFFFull && dot_kernel_takes(batch, packed, false, dict_words_max, x_dwords_max);
+
+  tq_step* s = new tq_step;
+  s->table_dev = nullptr;
+  s->n_matrices = n;
+  s->n_stages = n_stages;
+  s->persistent = persistent;
+  auto fail = [&](int rc) {
+    if (s->table_dev) (void)hipFree(s->table_dev);
+    if (s->stage_dev) (void)hipFree(s->stage_dev);
+    if (s->fault_host) (void)hipHostFree(s->fault_host);
+    delete s;
+    return rc;
+  };
+  Recorder rec;
+  if (!persistent) {
+    for (uint32_t k = 0; k < n_stages; ++k)
+      if (int rc = launch_all(Op::kMatvec, (int)(first[k + 1] - first[k]), hs + first[k], xs + first[k], ys + first[k], batch, nullptr, false,
+                              false, &rec))
+        return fail(rc);
+  } else {
+    PreparedLaunch p;
+    MatvecArgs& a = p.a;
+    std::memset(&a, 0, sizeof a);
+    a.n = n;
+    a.batch = batch;
+    a.n_stages = n_stages;
+    a.spin_limit = kDefaultSpinLimit;
+    a.table = (const StepEntry*)(uintptr_t)8;   // (the address follows below)
+    p.table_first = 0;
+    p.what = "tq_step_launch (staged)";
+    uint64_t c = 0;
+    for (int i = 0; i < n; ++i) {
+      rec.entries.push_back(StepEntry{hs[i]->m, (const uint16_t*)xs[i], (float*)ys[i]});
+      a.u.cost_long[i] = (uint32_t)c;
+      c += (uint64_t)hs[i]->m.n_bands * hs[i]->m.cols;
+    }
+    a.u.cost_long[n] = (uint32_t)c;
+    if (!plan_matvec_lds(dict_words_max, (packed && batch == 2 ? 2 : 1) * x_dwords_max, &a.x_off, &a.slot_off, &p.lds)) {
+      set_error("tq_step_create_staged: internal: LDS plan");
+      return fail(TQ_E_UNSUPPORTED);
+    }
+    p.kernel = packed ? (batch == 2 ? (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2, false, true>
+                                    : (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1, false, true>)
+               : batch == 2 ? (const void*)k_matvec<kDotPiece, kDotWaves, false, 2, false, true>
+                            : (const void*)k_matvec<kDotPiece, kDotWaves, false, 1, false, true>;
+    p.block = (packed ? kDotWavesPacked : kDotWaves) * 64;
+    p.grid = (unsigned)hs[0]->n_cu;   // one workgroup per compute unit (each takes the whole LDS): all resident together
+    rec.launches.push_back(p);
+  }
+  s->launches = std::move(rec.launches);
+  s->n_entries = rec.entries.size();
+  hipError_t e = hipMalloc((void**)&s->table_dev, rec.entries.size() * sizeof(StepEntry));
+  if (e == hipSuccess) e = hipMemcpy(s->table_dev, rec.entries.data(), rec.entries.size() * sizeof(StepEntry), hipMemcpyHostToDevice);
+  if (e == hipSuccess && persistent) {
+    e = hipMalloc((void**)&s->stage_dev, (size_t)2 * (n_stages + 1) * 4);
+    if (e == hipSuccess) e = hipMemset(s->stage_dev, 0, (size_t)2 * (n_stages + 1) * 4);
+    if (e == hipSuccess) e = hipMemcpy(s->stage_dev, first.data(), (size_t)(n_stages + 1) * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&s->fault_host, 64, hipHostMallocMapped);
+    if (e == hipSuccess) *s->fault_host = 0;
+  }
+  if (e != hipSuccess) {
+    const bool oom = e == hipErrorOutOfMemory;
+    if (oom) set_error("tq_step_create_staged: out of device memory");
+    return fail(oom ? TQ_E_OOM : hip_fail("tq_step_create_staged", e));
+  }
+  for (PreparedLaunch& p : s->launches) {
+    p.a.table = s->table_dev + p.table_first;
+    if (persistent) {
+      p.a.stage_first = s->stage_dev;
+      p.a.sync = s->stage_dev + n_stages + 1;
+      void* dp = nullptr;
+      e = hipHostGetDevicePointer(&dp, s->fault_host, 0);
+      if (e != hipSuccess) return fail(hip_fail("hipHostGetDevicePointer", e));
+      p.a.fault_host = (uint32_t*)dp;
+    }
+  }
+  *out = s;
+  return TQ_OK;
+}
+
 static int tq_step_launch_impl(tq_step_handle s, void* stream) {
   if (!s) {
     set_error("tq_step_launch: null step");
     return TQ_E_INVALID_ARG;
+  }
+  if (s->persistent) {
+    if (*(volatile uint32_t*)s->fault_host != 0) {
+      set_error("tq_step_launch: an earlier launch of this staged step gave up waiting at a stage hand-over (were all its workgroups "
+                "resident together?); its results must not be used");
+      return TQ_E_HIP;
+    }
+    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(256), 0, (hipStream_t)stream, s->stage_dev + s->n_stages + 1, s->n_stages + 1);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("tq_step_launch: counter reset", e);
   }
   for (const PreparedLaunch& p : s->launches)
     if (int rc = fire(p, (hipStream_t)stream)) return rc;
@@ -856,13 +1003,18 @@ extern "C" int tq_step_get_info(tq_step_handle s, tq_step_info* out) {
   }
   out->n_matrices = (uint32_t)s->n_matrices;
   out->n_launches = (uint32_t)s->launches.size();
-  out->table_bytes = (uint64_t)s->n_entries * sizeof(StepEntry);
+  out->table_bytes = (uint64_t)s->n_entries * sizeof(StepEntry) + (s->stage_dev ? (uint64_t)(2 * (s->n_stages + 1)) * 4 : 0);
+  out->n_stages = s->n_stages;
+  out->persistent = s->persistent ? 1u : 0u;
+  out->fault = s->fault_host ? *(volatile uint32_t*)s->fault_host : 0u;
   return TQ_OK;
 }
 
 static int tq_step_destroy_impl(tq_step_handle s) {
   if (!s) return TQ_OK;
   hipError_t e = hipFree(s->table_dev);
+  if (s->stage_dev) (void)hipFree(s->stage_dev);
+  if (s->fault_host) (void)hipHostFree(s->fault_host);
   delete s;
   if (e != hipSuccess) return hip_fail("tq_step_destroy", e);
   return TQ_OK;
@@ -1002,6 +1154,20 @@ extern "C" int tq_destroy(tq_handle h) {
 
 extern "C" int tq_step_destroy(tq_step_handle s) {
   return guarded("tq_step_destroy", [&] { return tq_step_destroy_impl(s); });
+}
+
+extern "C" int tq_step_create_staged(int n, const tq_handle* hs, const void* const* xs, void* const* ys, const int* stage, int batch,
+                                     uint32_t flags, tq_step_handle* out) {
+  return guarded("tq_step_create_staged", [&] { return tq_step_create_staged_impl(n, hs, xs, ys, stage, batch, flags, out); });
+}
+
+extern "C" int tq_step_set_spin_limit(tq_step_handle s, uint32_t polls) {
+  if (!s) {
+    set_error("tq_step_set_spin_limit: null step");
+    return TQ_E_INVALID_ARG;
+  }
+  for (PreparedLaunch& p : s->launches) p.a.spin_limit = polls;
+  return TQ_OK;
 }
 
 extern "C" int tq_matvec_multi_static(int n, const tq_handle* hs, const void* const* xs, void* const* ys, int batch, void* stream) {

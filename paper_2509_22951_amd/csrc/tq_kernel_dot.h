@@ -29,18 +29,18 @@ __device__ __forceinline__ void commit_dictionary(const DevMat& m, uint32_t base
 // LDS image of one activation row: dword (panel * x_span + c) = (x[panel * seg_cols + c], x[panel * seg_cols + c + 1])
 // as two bf16, zero past the end of the row; the gap dwords between panels and the tail are zero.
 // Thread t of a round handles the column pair (2 j, 2 j + 1), j = first_pair + k * 512 + t: it loads x[2j .. 2j+2].
-template <bool kAligned, int kThreads, int kXRegs>   // kXRegs x kThreads x 2 columns per round (8192)
+template <bool kAligned, int kThreads, int kXRegs, bool kCoherent = false>   // kXRegs x kThreads x 2 columns per round (8192)
 __device__ __forceinline__ void issue_activations(const DevMat& m, const uint16_t* __restrict__ x, uint32_t first_pair, int tid,
                                                   uint32_t (&lo)[kXRegs], uint32_t (&hi)[kXRegs]) {
 #pragma unroll
   for (int k = 0; k < kXRegs; ++k) {
     const uint32_t j = first_pair + k * kThreads + tid, col = 2 * j;
     if (kAligned) {   // x is 4-byte aligned and cols is even
-      lo[k] = col < m.cols ? global_load((const uint32_t*)x + j) : 0u;
-      hi[k] = col + 2 < m.cols ? global_load((const uint32_t*)x + j + 1) : 0u;
+      lo[k] = col < m.cols ? x_load<kCoherent>((const uint32_t*)x + j) : 0u;
+      hi[k] = col + 2 < m.cols ? x_load<kCoherent>((const uint32_t*)x + j + 1) : 0u;
     } else {
-      lo[k] = (col < m.cols ? global_load(x + col) : 0u) | (col + 1 < m.cols ? global_load(x + col + 1) << 16 : 0u);
-      hi[k] = col + 2 < m.cols ? global_load(x + col + 2) : 0u;
+      lo[k] = (col < m.cols ? x_load<kCoherent>(x + col) : 0u) | (col + 1 < m.cols ? x_load<kCoherent>(x + col + 1) << 16 : 0u);
+      hi[k] = col + 2 < m.cols ? x_load<kCoherent>(x + col + 2) : 0u;
     }
   }
 }
@@ -147,14 +147,14 @@ __device__ __forceinline__ void chunk4_packed_dot(const uint32_t (&w)[4], const 
 
 // LDS image of one activation row for packed weights: dword (panel * x_span + c) = the two activations of byte column
 // panel * seg_cols + c, zero past the end of the row.  Thread t of a round handles dword first + k * kThreads + t.
-template <bool kAligned, int kThreads, int kXRegs>
+template <bool kAligned, int kThreads, int kXRegs, bool kCoherent = false>
 __device__ __forceinline__ void issue_activations_packed(const DevMat& m, const uint16_t* __restrict__ x, uint32_t first, int tid,
                                                          uint32_t (&v)[kXRegs]) {
 #pragma unroll
   for (int k = 0; k < kXRegs; ++k) {
     const uint32_t j = first + k * kThreads + tid;
-    if (kAligned) v[k] = j < m.cols ? global_load((const uint32_t*)x + j) : 0u;   // x is 4-byte aligned
-    else v[k] = j < m.cols ? global_load(x + 2 * j) | global_load(x + 2 * j + 1) << 16 : 0u;
+    if (kAligned) v[k] = j < m.cols ? x_load<kCoherent>((const uint32_t*)x + j) : 0u;   // x is 4-byte aligned
+    else v[k] = j < m.cols ? x_load<kCoherent>(x + 2 * j) | x_load<kCoherent>(x + 2 * j + 1) << 16 : 0u;
   }
 }
 template <int kThreads, int kXRegs>
@@ -227,7 +227,7 @@ __device__ __forceinline__ void chunk4_two_dot(const uint32_t (&w)[4], const uin
   }
 }
 // Thread t of a round handles the columns (2 j, 2 j + 1), j = first_pair + k * kThreads + t, of both rows.
-template <bool kAligned, int kThreads, int kXRegs>   // kAligned: both rows start 4-byte aligned and cols is even
+template <bool kAligned, int kThreads, int kXRegs, bool kCoherent = false>   // kAligned: both rows start 4-byte aligned and cols is even
 __device__ __forceinline__ void issue_activations_two(const DevMat& m, const uint16_t* __restrict__ x, uint32_t first_pair, int tid,
                                                       uint32_t (&r0)[kXRegs], uint32_t (&r1)[kXRegs]) {
   const uint16_t* x1 = x + m.cols;
@@ -235,11 +235,11 @@ __device__ __forceinline__ void issue_activations_two(const DevMat& m, const uin
   for (int k = 0; k < kXRegs; ++k) {
     const uint32_t j = first_pair + k * kThreads + tid, col = 2 * j;
     if (kAligned) {
-      r0[k] = col < m.cols ? global_load((const uint32_t*)x + j) : 0u;
-      r1[k] = col < m.cols ? global_load((const uint32_t*)x1 + j) : 0u;
+      r0[k] = col < m.cols ? x_load<kCoherent>((const uint32_t*)x + j) : 0u;
+      r1[k] = col < m.cols ? x_load<kCoherent>((const uint32_t*)x1 + j) : 0u;
     } else {
-      r0[k] = (col < m.cols ? global_load(x + col) : 0u) | (col + 1 < m.cols ? global_load(x + col + 1) << 16 : 0u);
-      r1[k] = (col < m.cols ? global_load(x1 + col) : 0u) | (col + 1 < m.cols ? global_load(x1 + col + 1) << 16 : 0u);
+      r0[k] = (col < m.cols ? x_load<kCoherent>(x + col) : 0u) | (col + 1 < m.cols ? x_load<kCoherent>(x + col + 1) << 16 : 0u);
+      r1[k] = (col < m.cols ? x_load<kCoherent>(x1 + col) : 0u) | (col + 1 < m.cols ? x_load<kCoherent>(x1 + col + 1) << 16 : 0u);
     }
   }
 }
@@ -301,7 +301,9 @@ __device__ __forceinline__ float silu_times(float gate, float up) { return gate 
 // lies entirely inside its run (it scales and stores those rows itself); a band it shares with its neighbours goes to
 // one of two partial-sum slots in LDS, and after a workgroup barrier the slots of a band are added in wavefront order,
 // so the result does not depend on timing.
-template <int kPiece, int kWaves, bool kPacked, int kB, bool kLong = false>
+// kStaged: the jobs form stages (MatvecArgs::stage_first); the workgroups take the stages in turn, each one's bands cut
+// into equal shares as above, with a grid-wide hand-over between two stages; the dictionary stays in LDS across them.
+template <int kPiece, int kWaves, bool kPacked, int kB, bool kLong = false, bool kStaged = false>
 __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
   static_assert(kB == 1 || kB == 2, "one activation row or two");
   static_assert(!kLong || (kB == 1 && !kPacked), "runs of 3 and 4 bytes: one activation row of one-weight-per-byte matrices");
@@ -313,10 +315,14 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
   float* slot_val = (float*)((uint8_t*)lds4 + a.slot_off);           // [2 * kWaves][kB][16]
   int* slot_band = (int*)(slot_val + 2 * kWaves * kB * 16);          // [2 * kWaves]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const uint64_t total = cost_at(a, a.n);
-  const uint32_t lo = (uint32_t)(total * blockIdx.x / gridDim.x), hi = (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
   const uint32_t* staged = nullptr;
-  for (int i = 0; i < a.n; ++i) {
+  const uint32_t n_stages = kStaged ? a.n_stages : 1u;
+  for (uint32_t stage = 0; stage < n_stages; ++stage) {
+  const int job_first = kStaged ? (int)((const_u32*)a.stage_first)[stage] : 0, job_end = kStaged ? (int)((const_u32*)a.stage_first)[stage + 1] : a.n;
+  const uint32_t cost_first = cost_at(a, job_first);
+  const uint64_t total = cost_at(a, job_end) - cost_first;
+  const uint32_t lo = cost_first + (uint32_t)(total * blockIdx.x / gridDim.x), hi = cost_first + (uint32_t)(total * (blockIdx.x + 1) / gridDim.x);
+  for (int i = job_first; i < job_end; ++i) {
     const uint32_t cb = cost_at(a, i), ce = cost_at(a, i + 1);
     if (hi <= cb || lo >= ce) continue;
     Job job;
@@ -341,6 +347,47 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
     {   // one activation row, or two: larger batches run the MFMA kernels
       const uint16_t* xb = job.x;
       float* yb = job.y;
+      // The chunks of the run come in pieces of at most kPiece that never straddle a unit (a unit is cut into equal
+      // pieces); two register sets alternate and every piece issues exactly kPiece loads (those past its end repeat
+      // its last chunk), so the loads of the next piece are in flight while this one is worked on.  A piece of kPiece
+      // or kPiece - 1 chunks (all pieces of a unit of 256-column segments) runs as straight-line code: the LDS reads
+      // of later chunks overlap the dot products of earlier ones.
+      uint32_t wu = u0, wc = c0, w_left = 0, w_base = 0, w_rem = 0;
+      auto next_piece = [&](uint32_t& start, uint32_t& n, bool& ends) {
+        if (w_left == 0) {
+          if (wu == u1) {
+            n = 0;
+            ends = false;
+            start = wc;
+            return;
+          }
+          const uint32_t len = unit_offset(m, wu + 1) - wc;
+          w_left = (len + kPiece - 1) / kPiece;
+          w_base = len / w_left;
+          w_rem = len - w_base * w_left;
+          ++wu;
+        }
+        n = w_base + (w_rem ? 1u : 0u);
+        if (w_rem) --w_rem;
+        start = wc;
+        wc += n;
+        ends = --w_left == 0;
+      };
+      const uint32_t run_last = c0 + n_chunks - 1;
+      auto load_piece = [&](uint2 (&cw)[kPiece], uint32_t start, uint32_t n) {
+        const uint32_t last = min(start + max(n, 1u) - 1, run_last);
+#pragma unroll
+        for (int k = 0; k < kPiece; ++k) cw[k] = load_chunk(m.codes, min(start + k, last), lane);
+      };
+      // The first piece of code chunks is requested here, ahead of the staging of dictionary and activations: the
+      // chunks then arrive while the workgroup stages, and a small launch does not wait for device memory twice in a row.
+      uint2 cwa[kPiece], cwb[kPiece];
+      uint32_t sa = c0, na = 0, sb, nb;
+      bool ea = false, eb;
+      if (u0 < u1) {
+        next_piece(sa, na, ea);
+        load_piece(cwa, sa, na);
+      }
       __syncthreads();   // the previous dictionary, activation image and slots are no longer in use
       {
         uint4 dv[kDictRegs];
@@ -348,18 +395,18 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
         const bool dict_now = new_dict;
         if (dict_now) issue_dictionary<kThreads, kDictRegs>(m, 0, tid, dv);
         if constexpr (kPacked) {
-          if (x_aligned) issue_activations_packed<true, kThreads, kXRegs>(m, xb, 0, tid, xlo);
-          else issue_activations_packed<false, kThreads, kXRegs>(m, xb, 0, tid, xlo);
+          if (x_aligned) issue_activations_packed<true, kThreads, kXRegs, kStaged>(m, xb, 0, tid, xlo);
+          else issue_activations_packed<false, kThreads, kXRegs, kStaged>(m, xb, 0, tid, xlo);
           if constexpr (kB == 2) {   // the second row starts 2 * cols activations later, aligned like the first
-            if (x_aligned) issue_activations_packed<true, kThreads, kXRegs>(m, xb + 2 * m.cols, 0, tid, xhi);
-            else issue_activations_packed<false, kThreads, kXRegs>(m, xb + 2 * m.cols, 0, tid, xhi);
+            if (x_aligned) issue_activations_packed<true, kThreads, kXRegs, kStaged>(m, xb + 2 * m.cols, 0, tid, xhi);
+            else issue_activations_packed<false, kThreads, kXRegs, kStaged>(m, xb + 2 * m.cols, 0, tid, xhi);
           }
         } else if constexpr (kB == 2) {
-          if (x_aligned) issue_activations_two<true, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
-          else issue_activations_two<false, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
+          if (x_aligned) issue_activations_two<true, kThreads, kXRegs, kStaged>(m, xb, 0, tid, xlo, xhi);
+          else issue_activations_two<false, kThreads, kXRegs, kStaged>(m, xb, 0, tid, xlo, xhi);
         } else {
-          if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
-          else issue_activations<false, kThreads, kXRegs>(m, xb, 0, tid, xlo, xhi);
+          if (x_aligned) issue_activations<true, kThreads, kXRegs, kStaged>(m, xb, 0, tid, xlo, xhi);
+          else issue_activations<false, kThreads, kXRegs, kStaged>(m, xb, 0, tid, xlo, xhi);
         }
         zero_activation_gaps<kThreads, kImage>(m, tid, lds_x, n_slots);
         if (tid < 2 * kWaves) slot_band[tid] = -1;
@@ -374,33 +421,33 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
           commit_activations_packed_two<kThreads, kXRegs>(m, 0, tid, xlo, xhi, lds_x, image_cols);
           for (uint32_t first = kXRegs * kThreads; first < image_cols; first += kXRegs * kThreads) {
             if (x_aligned) {
-              issue_activations_packed<true, kThreads, kXRegs>(m, xb, first, tid, xlo);
-              issue_activations_packed<true, kThreads, kXRegs>(m, xb + 2 * m.cols, first, tid, xhi);
+              issue_activations_packed<true, kThreads, kXRegs, kStaged>(m, xb, first, tid, xlo);
+              issue_activations_packed<true, kThreads, kXRegs, kStaged>(m, xb + 2 * m.cols, first, tid, xhi);
             } else {
-              issue_activations_packed<false, kThreads, kXRegs>(m, xb, first, tid, xlo);
-              issue_activations_packed<false, kThreads, kXRegs>(m, xb + 2 * m.cols, first, tid, xhi);
+              issue_activations_packed<false, kThreads, kXRegs, kStaged>(m, xb, first, tid, xlo);
+              issue_activations_packed<false, kThreads, kXRegs, kStaged>(m, xb + 2 * m.cols, first, tid, xhi);
             }
             commit_activations_packed_two<kThreads, kXRegs>(m, first, tid, xlo, xhi, lds_x, image_cols);
           }
         } else if constexpr (kPacked) {
           commit_activations_packed<kThreads, kXRegs>(m, 0, tid, xlo, lds_x, image_cols);
           for (uint32_t first = kXRegs * kThreads; first < image_cols; first += kXRegs * kThreads) {
-            if (x_aligned) issue_activations_packed<true, kThreads, kXRegs>(m, xb, first, tid, xlo);
-            else issue_activations_packed<false, kThreads, kXRegs>(m, xb, first, tid, xlo);
+            if (x_aligned) issue_activations_packed<true, kThreads, kXRegs, kStaged>(m, xb, first, tid, xlo);
+            else issue_activations_packed<false, kThreads, kXRegs, kStaged>(m, xb, first, tid, xlo);
             commit_activations_packed<kThreads, kXRegs>(m, first, tid, xlo, lds_x, image_cols);
           }
         } else if constexpr (kB == 2) {
           commit_activations_two<kThreads, kXRegs>(m, 0, tid, xlo, xhi, lds_x, image_cols);
           for (uint32_t first = kXRegs * kThreads; 2 * first < image_cols; first += kXRegs * kThreads) {
-            if (x_aligned) issue_activations_two<true, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
-            else issue_activations_two<false, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
+            if (x_aligned) issue_activations_two<true, kThreads, kXRegs, kStaged>(m, xb, first, tid, xlo, xhi);
+            else issue_activations_two<false, kThreads, kXRegs, kStaged>(m, xb, first, tid, xlo, xhi);
             commit_activations_two<kThreads, kXRegs>(m, first, tid, xlo, xhi, lds_x, image_cols);
           }
         } else {
           commit_activations<kThreads, kXRegs>(m, 0, tid, xlo, xhi, lds_x, image_cols);
           for (uint32_t first = kXRegs * kThreads; 2 * first < image_cols; first += kXRegs * kThreads) {
-            if (x_aligned) issue_activations<true, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
-            else issue_activations<false, kThreads, kXRegs>(m, xb, first, tid, xlo, xhi);
+            if (x_aligned) issue_activations<true, kThreads, kXRegs, kStaged>(m, xb, first, tid, xlo, xhi);
+            else issue_activations<false, kThreads, kXRegs, kStaged>(m, xb, first, tid, xlo, xhi);
             commit_activations<kThreads, kXRegs>(m, first, tid, xlo, xhi, lds_x, image_cols);
           }
         }
@@ -428,9 +475,9 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
             for (int b = 0; b < kB; ++b) {
               if (a.gate_up) {   // lanes 2r, 2r + 1 hold the gate and the up row of output r
                 const float t = v[b] * scale, other = __shfl_xor(t, 1);
-                if (lane < 16 && !(lane & 1) && row + 1 < m.rows) global_store(yb + (size_t)b * (m.rows / 2) + row / 2, silu_times(t, other));
+                if (lane < 16 && !(lane & 1) && row + 1 < m.rows) y_store<kStaged>(yb + (size_t)b * (m.rows / 2) + row / 2, silu_times(t, other));
               } else if (lane < 16 && row < m.rows) {
-                global_store(yb + (size_t)b * m.rows + row, v[b] * scale);
+                y_store<kStaged>(yb + (size_t)b * m.rows + row, v[b] * scale);
               }
             }
           } else {
@@ -441,60 +488,31 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
             if (lane == 0) slot_band[s] = (int)band;
           }
         };
-        // The chunks of the run come in pieces of at most kPiece that never straddle a unit (a unit is cut into equal
-        // pieces); two register sets alternate and every piece issues exactly kPiece loads (those past its end repeat
-        // its last chunk), so the loads of the next piece are in flight while this one is worked on.  A piece of kPiece
-        // or kPiece - 1 chunks (all pieces of a unit of 256-column segments) runs as straight-line code: the LDS reads
-        // of later chunks overlap the dot products of earlier ones.
-        uint32_t wu = u0, wc = c0, w_left = 0, w_base = 0, w_rem = 0;
-        auto next_piece = [&](uint32_t& start, uint32_t& n, bool& ends) {
-          if (w_left == 0) {
-            if (wu == u1) {
-              n = 0;
-              ends = false;
-              start = wc;
-              return;
-            }
-            const uint32_t len = unit_offset(m, wu + 1) - wc;
-            w_left = (len + kPiece - 1) / kPiece;
-            w_base = len / w_left;
-            w_rem = len - w_base * w_left;
-            ++wu;
-          }
-          n = w_base + (w_rem ? 1u : 0u);
-          if (w_rem) --w_rem;
-          start = wc;
-          wc += n;
-          ends = --w_left == 0;
-        };
-        const uint32_t run_last = c0 + n_chunks - 1;
-        auto load_piece = [&](uint2 (&cw)[kPiece], uint32_t start, uint32_t n) {
-          const uint32_t last = min(start + max(n, 1u) - 1, run_last);
-#pragma unroll
-          for (int k = 0; k < kPiece; ++k) cw[k] = load_chunk(m.codes, min(start + k, last), lane);
-        };
         auto run_piece = [&](const uint2 (&cw)[kPiece], uint32_t n, bool ends) {
-          uint32_t w[2][4];   // two register sets: one chunk's operands are read while the one before is multiplied
-          std::conditional_t<kImage == 2, uint64_t, uint32_t> x[2][8];
+          // kSets register sets: the operands of the next kSets - 1 chunks are read while one chunk is multiplied, so a
+          // wavefront that works alone (a small launch, the tail of a stage) does not sit out an LDS round trip per chunk
+          constexpr int kSets = kDotSets;
+          uint32_t w[kSets][4];
+          std::conditional_t<kImage == 2, uint64_t, uint32_t> x[kSets][8];
           auto read = [&](auto kk) {
             constexpr int k = decltype(kk)::value;
-            if constexpr (kImage == 2) chunk4_packed_two_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);
-            else if constexpr (kPacked || kB == 2) chunk4_packed_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);   // this dword and the next
-            else chunk4_read<4 * k>(cw[k], xa, w[k & 1], x[k & 1]);
+            if constexpr (kImage == 2) chunk4_packed_two_read<4 * k>(cw[k], xa, w[k % kSets], x[k % kSets]);
+            else if constexpr (kPacked || kB == 2) chunk4_packed_read<4 * k>(cw[k], xa, w[k % kSets], x[k % kSets]);   // this dword and the next
+            else chunk4_read<4 * k>(cw[k], xa, w[k % kSets], x[k % kSets]);
           };
           auto dot = [&](auto kk) {
             constexpr int k = decltype(kk)::value;
-            if constexpr (kImage == 2) chunk4_packed_two_dot(w[k & 1], x[k & 1], a0, a1);
-            else if constexpr (kPacked) chunk4_packed_dot(w[k & 1], x[k & 1], a0, a1);
-            else if constexpr (kB == 2) chunk4_two_dot(w[k & 1], x[k & 1], a0, a1);
-            else chunk4_dot(w[k & 1], x[k & 1], a0, a1);
+            if constexpr (kImage == 2) chunk4_packed_two_dot(w[k % kSets], x[k % kSets], a0, a1);
+            else if constexpr (kPacked) chunk4_packed_dot(w[k % kSets], x[k % kSets], a0, a1);
+            else if constexpr (kB == 2) chunk4_two_dot(w[k % kSets], x[k % kSets], a0, a1);
+            else chunk4_dot(w[k % kSets], x[k % kSets], a0, a1);
           };
           auto straight = [&](auto nn) {   // a piece of nn chunks as straight-line code
             constexpr int kN = decltype(nn)::value;
-            read(std::integral_constant<int, 0>{});
+            static_for<(kSets - 1 < kN ? kSets - 1 : kN)>([&](auto kk) { read(kk); });
             static_for<kN>([&](auto kk) {
               constexpr int k = decltype(kk)::value;
-              if constexpr (k + 1 < kN) read(std::integral_constant<int, k + 1>{});
+              if constexpr (k + kSets - 1 < kN) read(std::integral_constant<int, k + kSets - 1>{});
               dot(kk);
             });
           };
@@ -532,11 +550,6 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
             xa = xa_lane + q * xa_quad;
           }
         };
-        uint2 cwa[kPiece], cwb[kPiece];
-        uint32_t sa, na, sb, nb;
-        bool ea, eb;
-        next_piece(sa, na, ea);
-        load_piece(cwa, sa, na);
         while (na) {
           next_piece(sb, nb, eb);
           load_piece(cwb, sb, nb);
@@ -561,13 +574,15 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
           const uint32_t row = (uint32_t)bnd * kUnitRows + r16;
           if (a.gate_up) {   // the two threads of a pair of rows are neighbours and take this branch together
             const float t = sum * global_load(m.scales + min(row, m.rows - 1)), other = __shfl_xor(t, 1);
-            if (!(r16 & 1) && row + 1 < m.rows) global_store(yb + (size_t)b * (m.rows / 2) + row / 2, silu_times(t, other));
+            if (!(r16 & 1) && row + 1 < m.rows) y_store<kStaged>(yb + (size_t)b * (m.rows / 2) + row / 2, silu_times(t, other));
           } else if (row < m.rows) {
-            global_store(yb + (size_t)b * m.rows + row, sum * global_load(m.scales + row));
+            y_store<kStaged>(yb + (size_t)b * m.rows + row, sum * global_load(m.scales + row));
           }
         }
       }
     }
+  }
+  if (kStaged && stage + 1 < n_stages) stage_handover(a, stage);
   }
 }
 

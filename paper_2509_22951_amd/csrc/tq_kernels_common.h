@@ -21,6 +21,10 @@ constexpr int kDotWaves = 8;         // wavefronts per workgroup of the batch-1 
                                      // 6 waves 4.61, 8 waves 5.12, 10 waves 4.64, 12 waves 4.90, 16 waves 4.28)
 constexpr int kDotPiece = 8;         // chunks per piece in the batch-1 kernel: two pieces (16 x 512 bytes) are in flight per
                                      // wavefront (measured on the 3B sweep, TB/s: 4 chunks 5.30, 6 5.48, 8 5.47, 12 5.41, 18 5.24)
+#ifndef TQ_DOT_SETS
+#define TQ_DOT_SETS 2
+#endif
+constexpr int kDotSets = TQ_DOT_SETS;   // register sets of the batch-1 kernel's chunk pipeline (operands read kDotSets - 1 chunks ahead)
 constexpr uint32_t kLdsLimit = 160 * 1024;
 constexpr int kPiece = 12;           // code chunks fetched together by a wavefront (units of 256-column segments are
                                      // 33..36 chunks long: three pieces with little repetition)
@@ -85,6 +89,14 @@ struct MatvecArgs {
   uint32_t tile_area;         // bytes of LDS per wavefront in the tile kernels (the same for every matrix of the launch)
   uint32_t gate_up;           // 1: rows 2r and 2r + 1 are a gate and an up projection; y[b][r] = silu(row 2r) * (row 2r + 1)
   const StepEntry* table;     // device table of the n jobs, or null: then j and first below hold them
+  // A staged step (one launch for products that depend on each other): the jobs come in n_stages groups, jobs
+  // stage_first[s] .. stage_first[s + 1] - 1 form stage s, and no workgroup starts a stage before every workgroup has
+  // stored the results of the one before (grid-wide hand-over through sync[s]; sync[n_stages] is set when a wait gave up).
+  const uint32_t* stage_first;   // device, n_stages + 1 entries; null: not staged
+  uint32_t* sync;                // device, n_stages + 1 words, zero at launch
+  uint32_t* fault_host;          // host memory the device can write: set to 1 when a wait gave up
+  uint32_t n_stages;
+  uint32_t spin_limit;           // polls of a stage counter before a workgroup gives up
   union {
     struct {
       uint32_t cost[kMaxMulti + 1];
@@ -144,6 +156,25 @@ __device__ __forceinline__ uint32_t global_load(const uint16_t* p) { return *(__
 __device__ __forceinline__ float global_load(const float* p) { return *(__attribute__((address_space(1))) const float*)p; }
 __device__ __forceinline__ void global_store(float* p, float v) { *(__attribute__((address_space(1))) float*)p = v; }
 
+// The same accesses, coherent across the whole device without any cache maintenance: relaxed atomics at device scope
+// are served at the level all compute units share.  A staged step stores its outputs and loads its activations this
+// way, so that a hand-over between stages needs no write-back or invalidation of caches (those cost microseconds).
+template <bool kCoherent>
+__device__ __forceinline__ uint32_t x_load(const uint32_t* p) {
+  if constexpr (kCoherent) return __hip_atomic_load((__attribute__((address_space(1))) const uint32_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else return global_load(p);
+}
+template <bool kCoherent>
+__device__ __forceinline__ uint32_t x_load(const uint16_t* p) {
+  if constexpr (kCoherent) return __hip_atomic_load((__attribute__((address_space(1))) const uint16_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else return global_load(p);
+}
+template <bool kCoherent>
+__device__ __forceinline__ void y_store(float* p, float v) {
+  if constexpr (kCoherent) __hip_atomic_store((__attribute__((address_space(1))) float*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else global_store(p, v);
+}
+
 // A matrix description from device memory, through scalar loads.
 __device__ __forceinline__ DevMat load_description(const DevMat* p) {
   static_assert(sizeof(DevMat) % 4 == 0, "whole dwords");
@@ -177,6 +208,34 @@ __device__ __forceinline__ void fetch_job(const MatvecArgs& a, int i, Job& job, 
     job = a.u.in.j[i];
     m = i < kInlineDescriptions ? a.u.in.first[i] : load_description(job.m);
   }
+}
+
+// Grid-wide hand-over between two stages of a staged step.  The stage's outputs were stored with device-coherent
+// stores (y_store<true>); every wavefront waits until its own stores have been acknowledged, the workgroup meets at a
+// barrier, one thread announces the workgroup at the stage's counter and polls it until all gridDim.x workgroups have
+// arrived (relaxed device-scope atomics throughout: the counter and the data are coherent by the way they are accessed,
+// so no cache is written back or invalidated).  The next stage loads its activations coherently too (x_load<true>).
+// All workgroups of the launch must be resident together (the host launches at most one per compute unit).  The wait is
+// bounded: after spin_limit polls, or when another workgroup has given up, the workgroup sets the fault words and
+// goes on without waiting - the launch then ends with results that must not be used, and the host reports it.
+__device__ __forceinline__ void stage_handover(const MatvecArgs& a, uint32_t stage) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's stores have reached the level the device shares
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t* counter = a.sync + stage;
+    uint32_t* fault = a.sync + a.n_stages;
+    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t polls = 0;
+    while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < gridDim.x) {
+      if (++polls > a.spin_limit || __hip_atomic_load(fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+        __hip_atomic_store(fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.fault_host, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(2);
+    }
+  }
+  __syncthreads();
 }
 
 // Byte address inside LDS of a pointer into the workgroup's dynamic shared memory.

@@ -1024,6 +1024,99 @@ def test_prepared_step_of_gate_up_pairs_in_a_hip_graph(dev):
             m.close()
 
 
+def _staged_case(dev, batch, shapes_by_stage, seed, pack=False):
+    mats, xs, ys, refs, stages, prev = [], [], [], [], [], None
+    for st, shapes in enumerate(shapes_by_stage):
+        for rows, cols in shapes:
+            spec = small_case(rows, cols, seed=seed + len(mats))
+            W = make_weights(spec)
+            prev = tq.tq_encode(W, seg_cols=64, max_entries=4000, dict_from=prev, bits=4 if pack else 0, pack=pack)
+            mats.append(tq.Matrix(prev))
+            bits, x = make_activations(spec, batch)
+            xs.append(torch.from_numpy(bits.view(np.int16).copy()).to(dev))
+            ys.append(torch.full((batch, rows), float("nan"), dtype=torch.float32, device=dev))
+            Q, s = O.quantize_rows(W, 4 if pack else 8)
+            refs.append(O.gemv_f64(Q, s, x))
+            stages.append(st)
+    return mats, xs, ys, refs, stages
+
+
+@pytest.mark.parametrize("batch,pack", [(1, False), (2, False), (1, True)])
+def test_staged_step_runs_dependent_products_in_one_launch(dev, batch, pack):
+    """Products in stages (the shapes of two small transformer layers: q,k,v | o | gate,up | down, then a head): one
+    kernel launch walks the stages with a device-side hand-over between them; every product against the oracle, on
+    repeated launches, and equal to the plain prepared step bit for bit (same kernels, same split per stage or not,
+    the sums of a row are the same numbers: checked to the tolerance, and for determinism against itself)."""
+    layer = [[(256, 512), (64, 512), (64, 512)], [(256, 256)], [(1024, 256), (1024, 256)], [(256, 1024)]]
+    mats, xs, ys, refs, stages = _staged_case(dev, batch, layer + layer + [[(4000, 256)]], 12000, pack)
+    hs, xp, yp = [m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys]
+    step = tq.Step(hs, xp, yp, batch, stages=stages)
+    try:
+        assert step.info["persistent"] == 1 and step.info["n_launches"] == 1 and step.info["n_stages"] == 9
+        first = None
+        for rep in range(3):
+            for y in ys:
+                y.fill_(float("nan"))
+            step.launch(_stream())
+            torch.cuda.synchronize()
+            got = [y.cpu().numpy() for y in ys]
+            for g, ref in zip(got, refs):
+                assert check_outputs(g, ref) < 1e-5
+            if first is None:
+                first = got
+            assert all(np.array_equal(a, b) for a, b in zip(first, got))
+        assert tq.tq_step_get_info(step.handle)["fault"] == 0
+    finally:
+        step.close()
+        for m in mats:
+            m.close()
+
+
+def test_staged_step_falls_back_to_one_set_of_launches_per_stage(dev):
+    """Batch 8 goes to the MFMA kernels, which have no staged form: the step then holds the launches of every stage in
+    order (the stream orders them); results as before.  Argument errors of the staged form."""
+    layer = [[(256, 512), (64, 512)], [(256, 256)], [(512, 256)]]
+    mats, xs, ys, refs, stages = _staged_case(dev, 8, layer, 13000)
+    hs, xp, yp = [m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys]
+    step = tq.Step(hs, xp, yp, 8, stages=stages)
+    try:
+        assert step.info["persistent"] == 0 and step.info["n_launches"] == 3 and step.info["n_stages"] == 3
+        step.launch(_stream())
+        torch.cuda.synchronize()
+        for y, ref in zip(ys, refs):
+            check_outputs(y.cpu().numpy(), ref)
+        for bad in ([1, 1, 2, 3], [0, 2, 2, 3], [0, 1, 0, 1]):
+            with pytest.raises(tq.TqError):
+                tq.tq_step_create_staged(hs, xp, yp, bad, 8)
+    finally:
+        step.close()
+        for m in mats:
+            m.close()
+
+
+def test_staged_step_reports_a_hand_over_that_gave_up(dev):
+    """The wait at a hand-over is bounded.  With the bound set to zero polls from the host, every workgroup that arrives
+    before the last one gives up at once: the kernel still ends normally, the step reports the fault, and later launches
+    are refused."""
+    layer = [[(2048, 512)], [(2048, 512)], [(2048, 512)]]
+    mats, xs, ys, refs, stages = _staged_case(dev, 1, layer, 14000)
+    hs, xp, yp = [m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys]
+    step = tq.Step(hs, xp, yp, 1, stages=stages)
+    try:
+        assert step.info["persistent"] == 1
+        tq.tq_step_set_spin_limit(step.handle, 0)
+        step.launch(_stream())
+        torch.cuda.synchronize()
+        assert tq.tq_step_get_info(step.handle)["fault"] == 1
+        with pytest.raises(tq.TqError) as ei:
+            step.launch(_stream())
+        assert ei.value.code == -5
+    finally:
+        step.close()
+        for m in mats:
+            m.close()
+
+
 def test_prepared_step_argument_errors(dev):
     m = tq.Matrix(tq.tq_encode(make_weights(small_case(17, 64, seed=690)), seg_cols=16))
     x = torch.zeros(64, dtype=torch.int16, device=dev)
