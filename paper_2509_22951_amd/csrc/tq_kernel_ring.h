@@ -56,7 +56,9 @@ __device__ __forceinline__ void append_chunk_ring(uint2 c, uint32_t ring, uint32
   const uint32_t sh = (pos & 7u) << 3;
   const uint64_t lo = carry | str << sh, hi = (str >> 1) >> (63 - sh);  // the 16 bytes carry + string; hi is 0 when pos % 8 == 0
   const bool full = (after ^ pos) >= 8;
-  if (full) *(lds_u64*)(size_t)(ring | ((pos ^ sw8) & 0x78u)) = lo;
+  // stored whether the piece is complete or not (an incomplete one holds zeros above its bytes and is stored again,
+  // complete, by a later chunk; nobody reads a piece before every lane has passed it): no branch in the chunk's code
+  *(lds_u64*)(size_t)(ring | ((pos ^ sw8) & 0x78u)) = lo;
   carry = full ? hi : lo;
   pos = after;
 }
