@@ -30,9 +30,11 @@ HBM_PEAK_GBS = 8000.0
 # launch, bytes written per step.  The figures belong to the kernel sources whose digest is given; with other sources
 # `traffic` is reported as null rather than as a stale number.
 PROFILED_TRAFFIC = {
-    "csrc_sha16": "",
-    "fetch_per_stored_byte": 1.0030,
-    "write_bytes_per_step": 3_618_000,
+    "csrc_sha16": "c92b14d0734bd4e0",
+    # kernel: (bytes read per stored byte of the launch, bytes written per step: a number, or "weights" = one per weight)
+    "tq::k_matvec": (1.0030, 3_620_000),                 # batch 1
+    "tq::k_matvec_ring": (1.0115, 316_580_000),          # batch 8: y is 28.9 MB; partial sums go out once per quad
+    "tq::k_decompress": (1.0000, "weights"),
 }
 
 
@@ -592,18 +594,32 @@ def main():
     def kernel_name(batch, packed=False):
         return "tq::k_matvec" if batch <= 2 else "tq::k_matvec_ring"
 
+    default_workload = (args.config == 4 and args.batch == 1 and args.fuse == "sweep" and args.dictionary == "sequence"
+                        and args.dictionary_kind == "lzw" and args.bits == 8 and not args.pack and not args.no_prepared_step
+                        and not (args.max_entries or args.lmax or args.seg_cols or args.layers or args.copies))
+    digest_matches = PROFILED_TRAFFIC["csrc_sha16"] == csrc_digest()
+
+    def profiled_traffic(kernel, n_launches, batch=1):
+        """HBM bytes per launch as the counter runs under profiles/ measured them, for the workload they were taken on."""
+        if not (default_workload and digest_matches) or (kernel == "tq::k_matvec_ring" and batch != 8):
+            return None
+        per_stored, written = PROFILED_TRAFFIC[kernel]
+        return round((per_stored * wl.stored_bytes + (wl.n_weights if written == "weights" else written)) / n_launches)
+
     others = {}
     if args.also_batch and args.also_batch != args.batch:
         r2 = runner.run(args.also_batch, max(3, args.steps // 2), args.warmup, args.prewarm_ms)
         others[str(args.also_batch)] = {
             "ms_per_step": round(r2["wall_ms"], 4), "GBps": round(wl.algorithmic_bytes / r2["wall_ms"] / 1e6, 1),
             "tokens_per_s": round(args.also_batch / (r2["wall_ms"] * 1e-3), 1), "step_ms": r2["spread"],
-            "roofline": roofline_block(kernel_name(args.also_batch), wl, r2["ev_ms"], r2["n_launches"])}
+            "roofline": roofline_block(kernel_name(args.also_batch), wl, r2["ev_ms"], r2["n_launches"],
+                                       profiled_traffic(kernel_name(args.also_batch), r2["n_launches"], args.also_batch))}
         del r2
 
     decompress, expanded = None, None
     if not args.no_decompress:
         decompress, expanded = expansion_leg(tq, torch, wl, args, dev, stream, keep_output=not args.no_cpu_baseline)
+        decompress["roofline"]["traffic"] = profiled_traffic("tq::k_decompress", decompress["kernel_launches"])
 
     listing = None
     if not args.no_listing:
@@ -612,12 +628,7 @@ def main():
     if not args.no_gate_up:
         gate_up = gate_up_leg(wl, args, dev, stream)
 
-    default_workload = (args.config == 4 and args.batch == 1 and args.fuse == "sweep" and args.dictionary == "sequence"
-                        and args.dictionary_kind == "lzw" and args.bits == 8 and not args.no_prepared_step
-                        and not (args.max_entries or args.lmax or args.seg_cols or args.layers))
-    traffic = None
-    if default_workload and PROFILED_TRAFFIC["csrc_sha16"] == csrc_digest():
-        traffic = round((PROFILED_TRAFFIC["fetch_per_stored_byte"] * wl.stored_bytes + PROFILED_TRAFFIC["write_bytes_per_step"]) / n_launches)
+    traffic = profiled_traffic("tq::k_matvec", n_launches)
     gbps = wl.algorithmic_bytes / wall_ms / 1e6
     result = {
         "metric": "compressed-weight HBM GB/s of the fused decode+dequant+GEMV decode-step sweep (% of 8 TB/s peak in "

@@ -265,8 +265,8 @@ const void* const kLdsKernels[] = {
     (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1>,
     (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2>,
     (const void*)k_matvec<kDotPiece, kDotWaves, false, 1, true>,
-    (const void*)k_matvec<kDotPiece, kDotWaves, false, 1, false, true>,
-    (const void*)k_matvec<kDotPiece, kDotWaves, false, 2, false, true>,
+    (const void*)k_matvec<kDotPiece, kDotWavesStaged, false, 1, false, true>,
+    (const void*)k_matvec<kDotPiece, kDotWavesStaged, false, 2, false, true>,
     (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1, false, true>,
     (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2, false, true>,
     (const void*)k_decompress<false>,
@@ -939,9 +939,9 @@ static int tq_step_create_staged_impl(int n, const tq_handle* hs, const void* co
     }
     p.kernel = packed ? (batch == 2 ? (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 2, false, true>
                                     : (const void*)k_matvec<kDotPiecePacked, kDotWavesPacked, true, 1, false, true>)
-               : batch == 2 ? (const void*)k_matvec<kDotPiece, kDotWaves, false, 2, false, true>
-                            : (const void*)k_matvec<kDotPiece, kDotWaves, false, 1, false, true>;
-    p.block = (packed ? kDotWavesPacked : kDotWaves) * 64;
+               : batch == 2 ? (const void*)k_matvec<kDotPiece, kDotWavesStaged, false, 2, false, true>
+                            : (const void*)k_matvec<kDotPiece, kDotWavesStaged, false, 1, false, true>;
+    p.block = (packed ? kDotWavesPacked : kDotWavesStaged) * 64;
     p.grid = (unsigned)hs[0]->n_cu;   // one workgroup per compute unit (each takes the whole LDS): all resident together
     rec.launches.push_back(p);
   }

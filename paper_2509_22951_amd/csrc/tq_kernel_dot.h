@@ -317,6 +317,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t* staged = nullptr;
   const uint32_t n_stages = kStaged ? a.n_stages : 1u;
+  constexpr uint32_t kNoStage = 0xFFFFFFFFu;
+  uint32_t wait_for = kNoStage;   // staged: the stage whose outputs this workgroup has yet to wait for
   for (uint32_t stage = 0; stage < n_stages; ++stage) {
   const int job_first = kStaged ? (int)((const_u32*)a.stage_first)[stage] : 0, job_end = kStaged ? (int)((const_u32*)a.stage_first)[stage + 1] : a.n;
   const uint32_t cost_first = cost_at(a, job_first);
@@ -388,7 +390,14 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
         next_piece(sa, na, ea);
         load_piece(cwa, sa, na);
       }
-      __syncthreads();   // the previous dictionary, activation image and slots are no longer in use
+      // the previous dictionary, activation image and slots are no longer in use; staged: nor is anyone still writing
+      // the activations (the wait ends with the same barrier)
+      if (kStaged && wait_for != kNoStage) {
+        stage_wait(a, wait_for);
+        wait_for = kNoStage;
+      } else {
+        __syncthreads();
+      }
       {
         uint4 dv[kDictRegs];
         uint32_t xlo[kXRegs], xhi[kXRegs];
@@ -582,7 +591,10 @@ __global__ __launch_bounds__(kWaves * 64, 1) void k_matvec(MatvecArgs a) {
       }
     }
   }
-  if (kStaged && stage + 1 < n_stages) stage_handover(a, stage);
+  if (kStaged && stage + 1 < n_stages) {
+    stage_arrive(a, stage);
+    wait_for = stage;
+  }
   }
 }
 

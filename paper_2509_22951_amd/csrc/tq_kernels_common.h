@@ -15,7 +15,12 @@ constexpr int kWaves = 8;            // most wavefronts per workgroup of the til
 constexpr int kThreads = kWaves * 64;
 constexpr int kDotWavesPacked = 12;  // the same kernel for packed 4-bit weights: more work per byte read, more wavefronts to
                                      // hide it (config 4, ms per step: 8 wavefronts 0.379, 12 0.370, 16 0.379)
-constexpr int kDotWavesMax = 12;
+#ifndef TQ_STAGED_WAVES
+#define TQ_STAGED_WAVES 8
+#endif
+constexpr int kDotWavesStaged = TQ_STAGED_WAVES;   // the staged form of the batch-1 and batch-2 kernel (the 113 dependent stages
+                                                   // of the 3B sweep, ms per step: 8 wavefronts 1.59, 12 1.87, 16 1.88)
+constexpr int kDotWavesMax = kDotWavesStaged > 12 ? kDotWavesStaged : 12;
 constexpr int kDotPiecePacked = 6;   // its units are half as long (segments of 128 bytes: 17 chunks, three pieces of 5 or 6)
 constexpr int kDotWaves = 8;         // wavefronts per workgroup of the batch-1 kernel (measured on the 3B sweep, TB/s:
                                      // 6 waves 4.61, 8 waves 5.12, 10 waves 4.64, 12 waves 4.90, 16 waves 4.28)
@@ -218,13 +223,20 @@ __device__ __forceinline__ void fetch_job(const MatvecArgs& a, int i, Job& job, 
 // All workgroups of the launch must be resident together (the host launches at most one per compute unit).  The wait is
 // bounded: after spin_limit polls, or when another workgroup has given up, the workgroup sets the fault words and
 // goes on without waiting - the launch then ends with results that must not be used, and the host reports it.
-__device__ __forceinline__ void stage_handover(const MatvecArgs& a, uint32_t stage) {
+// The hand-over comes in two halves so that a workgroup can fetch what its next stage needs and what no other workgroup
+// writes (matrix descriptions, unit offsets, the first code chunks) between the two, while the others still finish.
+// stage_arrive: this workgroup's outputs of `stage` are out.  stage_wait: every workgroup's are; it ends with a
+// workgroup barrier.  A workgroup that has no share of a stage goes on to the next arrive without waiting: it reads
+// and writes nothing there, and whatever it does later comes after a wait on a later stage.
+__device__ __forceinline__ void stage_arrive(const MatvecArgs& a, uint32_t stage) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's stores have reached the level the device shares
   __syncthreads();
+  if (threadIdx.x == 0) __hip_atomic_fetch_add(a.sync + stage, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void stage_wait(const MatvecArgs& a, uint32_t stage) {
   if (threadIdx.x == 0) {
     uint32_t* counter = a.sync + stage;
     uint32_t* fault = a.sync + a.n_stages;
-    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     uint32_t polls = 0;
     while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < gridDim.x) {
       if (++polls > a.spin_limit || __hip_atomic_load(fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
