@@ -78,20 +78,31 @@ def compress(values: np.ndarray, table: np.ndarray) -> np.ndarray:
 
 
 def decompress(words: np.ndarray, table: np.ndarray) -> np.ndarray:
-    """Section 4, third listing, for one parameter.  Returns the uint8 values."""
-    w = np.ascontiguousarray(words, dtype=np.uint16)
+    """Section 4, "Decompressing Model Weights", for one parameter.  Returns the uint8 values.
+
+    Written as a whole-array computation rather than a reader that walks the words: a raw value is at most 0xFF and a
+    codeword at most 0xFFFE (the reading above), so every word equal to the marker IS a marker, wherever it stands.
+    The (up to) 4 words after a marker are raw values; every other word is a codeword and yields its table entry."""
+    w = np.ascontiguousarray(words, dtype=np.uint16).astype(np.int64)
     t = np.ascontiguousarray(table, dtype=np.uint8).reshape(-1, SEQ)
-    out = []
-    i = 0
-    while i < w.size:
-        c = int(w[i])
-        i += 1
-        if c == MARKER:
-            raw = w[i: i + SEQ]
-            assert np.all(raw <= 0xFF), "a raw value does not fit a byte"
-            out.extend(int(x) for x in raw)
-            i += SEQ
-        else:
-            assert 1 <= c <= t.shape[0], f"codeword {c} is not in the table"
-            out.extend(int(x) for x in t[c - 1])
-    return np.array(out, dtype=np.uint8)
+    n = w.size
+    pos = np.arange(n)
+    markers = pos[w == MARKER]
+    # how far behind the nearest earlier marker each word stands (0 = the marker itself; n = no marker before it)
+    last = np.full(n, -1, np.int64)
+    last[markers] = markers
+    last = np.maximum.accumulate(last)
+    behind = np.where(last >= 0, pos - last, n)
+    assert markers.size < 2 or np.all(np.diff(markers) > SEQ), "a marker inside the raw values of another"
+    raw = (behind >= 1) & (behind <= SEQ)
+    code = ~raw & (w != MARKER)
+    assert np.all(w[raw] <= 0xFF), "a raw value does not fit a byte"
+    assert np.all((w[code] >= 1) & (w[code] <= t.shape[0])), "a codeword is not in the table"
+    # values each word contributes, then their place in the output
+    yields = np.where(raw, 1, np.where(code, SEQ, 0))
+    start = np.cumsum(yields) - yields
+    out = np.zeros(int(yields.sum()), np.uint8)
+    out[start[raw]] = w[raw]
+    if code.any():
+        out[(start[code][:, None] + np.arange(SEQ)[None, :]).reshape(-1)] = t[w[code] - 1].reshape(-1)
+    return out

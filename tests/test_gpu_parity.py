@@ -1072,6 +1072,39 @@ def test_staged_step_runs_dependent_products_in_one_launch(dev, batch, pack):
             m.close()
 
 
+def test_staged_step_in_a_hip_graph(dev):
+    """The staged launch (a fill kernel for the stage counters, then the persistent kernel) captured into a graph and
+    replayed, with eager launches of the same step between the replays: every replay against the oracle."""
+    layer = [[(256, 512), (64, 512), (64, 512)], [(256, 256)], [(1024, 256), (1024, 256)], [(256, 1024)]]
+    mats, xs, ys, refs, stages = _staged_case(dev, 1, layer + layer, 15000)
+    hs, xp, yp = [m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys]
+    step = tq.Step(hs, xp, yp, 1, stages=stages)
+    try:
+        assert step.info["persistent"] == 1
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step.launch(torch.cuda.current_stream().cuda_stream)
+        for _ in range(4):
+            for y in ys:
+                y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for y, ref in zip(ys, refs):
+                assert check_outputs(y.cpu().numpy(), ref) < 1e-5
+            step.launch(_stream())           # eager work between the replays
+            torch.cuda.synchronize()
+            for y, ref in zip(ys, refs):
+                assert check_outputs(y.cpu().numpy(), ref) < 1e-5
+        assert tq.tq_step_get_info(step.handle)["fault"] == 0
+        del graph
+    finally:
+        step.close()
+        for m in mats:
+            m.close()
+
+
 def test_staged_step_falls_back_to_one_set_of_launches_per_stage(dev):
     """Batch 8 goes to the MFMA kernels, which have no staged form: the step then holds the launches of every stage in
     order (the stream orders them); results as before.  Argument errors of the staged form."""
