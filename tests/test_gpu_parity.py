@@ -1130,8 +1130,9 @@ def test_staged_step_falls_back_to_one_set_of_launches_per_stage(dev):
 def test_staged_step_reports_a_hand_over_that_gave_up(dev):
     """The wait at a hand-over is bounded.  With the bound set to zero polls from the host, every workgroup that arrives
     before the last one gives up at once: the kernel still ends normally, the step reports the fault, and later launches
-    are refused."""
-    layer = [[(2048, 512)], [(2048, 512)], [(2048, 512)]]
+    are refused.  The first stage is one band of a long row: one workgroup works on it for microseconds while all others
+    have nothing to do there and reach the wait for it at once."""
+    layer = [[(16, 16384)], [(2048, 512)], [(2048, 512)]]
     mats, xs, ys, refs, stages = _staged_case(dev, 1, layer, 14000)
     hs, xp, yp = [m.handle for m in mats], [x.data_ptr() for x in xs], [y.data_ptr() for y in ys]
     step = tq.Step(hs, xp, yp, 1, stages=stages)
