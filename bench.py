@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0
 # launch, bytes written per step.  The figures belong to the kernel sources whose digest is given; with other sources
 # `traffic` is reported as null rather than as a stale number.
 PROFILED_TRAFFIC = {
-    "csrc_sha16": "c92b14d0734bd4e0",
+    "csrc_sha16": "cd3cf3bfc8810c9d",
     # kernel: (bytes read per stored byte of the launch, bytes written per step: a number, or "weights" = one per weight)
     "tq::k_matvec": (1.0030, 3_620_000),                 # batch 1
     "tq::k_matvec_ring": (1.0115, 316_580_000),          # batch 8: y is 28.9 MB; partial sums go out once per quad
