@@ -85,6 +85,8 @@ def parse_args():
                     help="skip the leg that expands one matrix stored in the paper's own section 4 stream format")
     ap.add_argument("--no-config5", action="store_true",
                     help="skip the stress configuration (config 5: Student-t weights, batch 16, whole-model expansion)")
+    ap.add_argument("--no-dependent-stages", action="store_true",
+                    help="skip the side leg that runs the default sweep in dependent stages (one persistent launch, and one launch per stage)")
     ap.add_argument("--no-matrix-dictionary", action="store_true",
                     help="skip the leg that repeats the sweep with one dictionary per matrix")
     ap.add_argument("--layers", type=int, default=0, help="debug: keep only the first N layers (+ lm_head)")
@@ -683,6 +685,33 @@ def main():
                          "question compressed against 0.20-0.33 s uncompressed; it reports no throughput of this path",
     }
 
+    # ---- the same sweep with a real layer's dependencies respected: q,k,v | o | gate,up | down per layer, then lm_head
+    def dependent_stages_leg():
+        import copy
+        out = {"plan": "the products that a layer can run side by side form a stage; a stage starts when the one before it has "
+                       "stored its outputs"}
+        for fuse, key in (("staged", "one_persistent_launch"), ("independent", "one_launch_per_stage")):
+            a2 = copy.copy(args)
+            a2.fuse, a2.graph = fuse, False
+            r = Runner(tq, torch, wl, mat_sets[:1], a2, dev, stream)
+            rr = r.run(args.batch, max(3, args.steps // 2), max(2, args.warmup // 2), min(args.prewarm_ms, 50.0))
+            out["stages"] = len(r.groups)
+            out[key] = {"ms_per_step": round(rr["wall_ms"], 4), "tokens_per_s": round(args.batch / (rr["wall_ms"] * 1e-3), 1),
+                        "GBps": round(wl.algorithmic_bytes / rr["wall_ms"] / 1e6, 1),
+                        "frac": round(wl.algorithmic_bytes / rr["wall_ms"] / 1e6 / HBM_PEAK_GBS, 4),
+                        "kernel_launches_per_step": rr["n_launches"], "step_ms": rr["spread"]}
+            del rr, r
+        return out
+
+    def optional_leg(name, fn):   # a failure in a side leg is reported in the line instead of losing the line
+        try:
+            result[name] = fn()
+        except Exception as e:   # noqa: BLE001
+            result[name] = {"error": f"{type(e).__name__}: {e}"}
+
+    if default_workload and not args.no_dependent_stages:
+        optional_leg("dependent_stages", dependent_stages_leg)
+
     if not args.no_cpu_baseline:
         result["cpu_baseline"], result["verified"] = cpu_baseline_and_verification(wl, args, infos, main_run["ys"], expanded, torch)
     else:
@@ -695,12 +724,6 @@ def main():
     torch.cuda.empty_cache()
 
     # ---- the same sweep with one dictionary per matrix (what "built greedily from the matrix" says literally)
-    def optional_leg(name, fn):   # a failure in a side leg is reported in the line instead of losing the line
-        try:
-            result[name] = fn()
-        except Exception as e:   # noqa: BLE001
-            result[name] = {"error": f"{type(e).__name__}: {e}"}
-
     def matrix_dictionary_leg():
         wm = Workload(tq, specs, args, "matrix", opts)
         rm = Runner(tq, torch, wm, [wm.mats], args, dev, stream).run(args.batch, args.steps, args.warmup, args.prewarm_ms)
