@@ -252,7 +252,7 @@ int tq_step_destroy(tq_step_handle s);
  * For callers that cannot allocate device memory where they call the library - code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc: tq_matvec_multi for up to TQ_STATIC_MAX_MATRICES matrices with the
  * job table of a prepared step, so one kernel launch serves them all, but the table lives in a fixed array of
- * TQ_STATIC_MAX_MATRICES * 104 bytes that is part of the library's device image (each GPU the library runs on holds
+ * TQ_STATIC_MAX_MATRICES * 120 bytes that is part of the library's device image (each GPU the library runs on holds
  * it until the process ends) instead of memory a tq_step_create allocates.  The call plans the launches as
  * tq_step_create does, fills the table through small writer launches on `stream` (ahead of the product launches, on
  * the same stream; n / 160 of them, rounded up) and launches the products.  It makes no hipMalloc, hipFree or other
