@@ -362,3 +362,26 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], stdout=subprocess.PIPE,
                        stderr=subprocess.PIPE, text=True, timeout=120)
     assert r.returncode != 0 and "one GPU" in r.stderr and not r.stdout.strip()
+
+
+def test_bench_launch_plans_group_what_a_layer_can_run_side_by_side():
+    """The launch plans of bench.py on the 3B sweep (28 layers of q, k, v, o, gate, up, down, then lm_head): one group, one
+    per layer, one per set of products with a common input (q,k,v | o | gate,up | down: the stages of the staged step),
+    one per matrix; every plan keeps the order of the sweep and covers every matrix once."""
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    from inputs import config_matrices
+    specs = config_matrices(4)
+    assert len(specs) == 197
+    sizes = {fuse: [len(g) for g in bench.launch_groups(specs, fuse)] for fuse in ("sweep", "layer", "independent", "none")}
+    assert sizes["sweep"] == [197]
+    assert sizes["layer"] == [7] * 28 + [1]
+    assert sizes["independent"] == [3, 1, 2, 1] * 28 + [1] and len(sizes["independent"]) == 113
+    assert sizes["none"] == [1] * 197
+    for fuse in sizes:
+        flat = [i for g in bench.launch_groups(specs, fuse) for i in g]
+        assert flat == list(range(197))
+    first = bench.launch_groups(specs, "independent")[:4]
+    assert [[specs[i].name.split(".")[-1] for i in g] for g in first] == [["q_proj", "k_proj", "v_proj"], ["o_proj"], ["gate_proj", "up_proj"], ["down_proj"]]
