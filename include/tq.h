@@ -232,7 +232,7 @@ int tq_step_create(int n, const tq_handle *hs, const void *const *xs, void *cons
  * When every matrix takes the dot-product kernel (batch 1 or 2; ordinary or packed weights; rows that fit its LDS image;
  * no runs longer than 2 bytes) the whole step is one kernel launch: one workgroup per compute unit walks the stages, the
  * dictionary stays in LDS across them, and between two stages the workgroups hand over through a counter in device
- * memory (release / acquire at device scope).  That needs all workgroups resident together, which holds when nothing
+ * memory (outputs and activations of such a step are stored and loaded device-coherently).  That needs all workgroups resident together, which holds when nothing
  * else occupies the GPU's compute units while the step runs; a wait is bounded (tq_step_set_spin_limit; about two
  * seconds by default): a workgroup that gives up sets a fault flag, every other wait of that launch ends at once, the
  * results must not be used, tq_step_get_info reports fault = 1 and later launches return TQ_E_HIP.
